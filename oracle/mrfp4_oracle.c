@@ -1,0 +1,336 @@
+/*
+ * CPU oracle for the micro-rotated FP4 linear-layer path:  Y = Q(X H_b) * Q(W H_b)^T.
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE.  It is the slow, plain reference that the HIP kernels are checked
+ * against.  It shares no code, table or constant with the HIP library and must never be linked or
+ * called by the product path.  Only tests, the smoke check and the benchmark's CPU-baseline leg use it.
+ *
+ * What each function follows (paper = arXiv 2509.23202):
+ *   orc_hadamard        Sylvester construction of the +-1 Hadamard matrix; the rotation is U = H/sqrt(b)
+ *                       (Appendix "Outliers Analysis", proof of Lemma 1; Section 4.1 "Ingredient 3":
+ *                       block-diagonal H_k with k x k blocks, k a power of two).
+ *   orc_rotate          X H_b with H_b block-diagonal along the reduction (K) axis (Section 4.1,
+ *                       Ingredient 3; Section 4.2 item 1).
+ *   orc_quantize_mxfp4  MFP format (G=32, E=E2M1, S=E8M0) of Section 2, abs-max scale and round-to-
+ *                       nearest of Section 3 (Definition "Scales"), with the scale rounded to a power of
+ *                       two by the OCP Microscaling rule  2^(floor(log2 amax) - 2).
+ *   orc_quantize_nvfp4  MFP format (G=16, E=E2M1, S=E4M3) plus a per-tensor scale, Section 2 and
+ *                       Section 4.1 "Ingredient 1":  Xhat = s_T * s_G * Q(X / (s_T * s_G)).
+ *   orc_dequantize      the decoding side of the same two definitions.
+ *   orc_matmul          Y = Ahat * What^T as a plain triple loop in fp64, plus S = |Ahat| * |What|^T.
+ *
+ * Parity pins (see tests/test_oracle_*.py): every function here is pinned; nothing is "parity unpinned"
+ * except the paper's plotted error statistics, which the tests check in direction only.
+ *
+ * Precision: rotation accumulates in fp64 and rounds once to fp32.  Scale arithmetic for NVFP4 is IEEE
+ * binary32, one rounding per written operation (compile with -ffp-contract=off, no fast-math).
+ * Element and scale rounding are done by nearest-neighbour search over the decoded grid, ties to the
+ * code with an even mantissa bit.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---------------------------------------------------------------- utilities */
+
+static float bf16_bits_to_float(uint16_t h)
+{
+    uint32_t u = ((uint32_t)h) << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+int orc_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void orc_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* ---------------------------------------------------------------- Hadamard */
+
+/* Sylvester: H_1 = [1];  H_2n = [[H_n, H_n], [H_n, -H_n]].  H is b*b int8, row-major.
+ * Returns 0 on success, -1 if b is not a power of two in [1, 1024]. */
+int orc_hadamard(int b, int8_t *H)
+{
+    if (b < 1 || b > 1024 || (b & (b - 1)) != 0) return -1;
+    H[0] = 1;
+    for (int n = 1; n < b; n *= 2) {
+        /* grow the n*n matrix stored with row stride b into 2n*2n */
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j) {
+                int8_t h = H[i * b + j];
+                H[i * b + (j + n)] = h;
+                H[(i + n) * b + j] = h;
+                H[(i + n) * b + (j + n)] = (int8_t)(-h);
+            }
+    }
+    return 0;
+}
+
+/* y[m, j0+c] = (1/sqrt(b)) * sum_r x[m, j0+r] * H[r][c]   for every block j0 = 0, b, 2b, ...
+ * x: bf16 bit patterns [M,K] row-major;  y: fp32 [M,K].  fp64 accumulation, ONE rounding to fp32.
+ * b == 1 is the identity.  Returns -1 if K % b != 0 or b is invalid. */
+int orc_rotate(const uint16_t *x, int64_t M, int64_t K, int b, float *y)
+{
+    if (b < 1 || b > 1024 || (b & (b - 1)) != 0 || K % b != 0) return -1;
+    int8_t *H = (int8_t *)malloc((size_t)b * (size_t)b);
+    if (!H) return -2;
+    orc_hadamard(b, H);
+    const double inv_sqrt_b = 1.0 / sqrt((double)b);
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t j0 = 0; j0 < K; j0 += b) {
+            for (int c = 0; c < b; ++c) {
+                double acc = 0.0;
+                for (int r = 0; r < b; ++r)
+                    acc += (double)bf16_bits_to_float(x[m * K + j0 + r]) * (double)H[r * b + c];
+                y[m * K + j0 + c] = (float)(acc * inv_sqrt_b);
+            }
+        }
+    }
+    free(H);
+    return 0;
+}
+
+/* Same rotation applied to an fp64 matrix and kept in fp64 (used by invariance tests only). */
+int orc_rotate_f64(const double *x, int64_t M, int64_t K, int b, double *y)
+{
+    if (b < 1 || b > 1024 || (b & (b - 1)) != 0 || K % b != 0) return -1;
+    int8_t *H = (int8_t *)malloc((size_t)b * (size_t)b);
+    if (!H) return -2;
+    orc_hadamard(b, H);
+    const double inv_sqrt_b = 1.0 / sqrt((double)b);
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t j0 = 0; j0 < K; j0 += b)
+            for (int c = 0; c < b; ++c) {
+                double acc = 0.0;
+                for (int r = 0; r < b; ++r) acc += x[m * K + j0 + r] * (double)H[r * b + c];
+                y[m * K + j0 + c] = acc * inv_sqrt_b;
+            }
+    free(H);
+    return 0;
+}
+
+/* ---------------------------------------------------------------- E2M1 elements */
+
+/* Positive E2M1 values in code order (Section 2: 1 sign, 2 exponent, 1 mantissa bit). */
+static const double E2M1_GRID[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
+
+double orc_e2m1_decode(uint8_t code)
+{
+    double v = E2M1_GRID[code & 7];
+    return (code & 8) ? -v : v;
+}
+
+/* Nearest grid point to v; exact ties go to the code whose mantissa bit (bit 0) is 0;
+ * anything beyond the largest value saturates to it.  Sign bit copied from v (so -0.0 and small
+ * negatives give 0x8). */
+uint8_t orc_e2m1_encode(double v)
+{
+    uint8_t sign = signbit(v) ? 8 : 0;
+    double a = fabs(v);
+    if (a >= E2M1_GRID[7]) return (uint8_t)(sign | 7); /* saturation, also keeps huge inputs out of the search */
+    int best = 0;
+    double best_d = fabs(a - E2M1_GRID[0]);
+    for (int c = 1; c < 8; ++c) {
+        double d = fabs(a - E2M1_GRID[c]);
+        if (d < best_d || (d == best_d && (c & 1) == 0)) {
+            best = c;
+            best_d = d;
+        }
+    }
+    return (uint8_t)(sign | best);
+}
+
+/* ---------------------------------------------------------------- E8M0 scales */
+
+/* byte e <-> 2^(e-127), e in [0,254]; 255 is NaN and never produced. */
+double orc_e8m0_decode(uint8_t e) { return ldexp(1.0, (int)e - 127); }
+
+/* OCP MX rule for a group whose largest magnitude is amax, element format E2M1 (emax = 2):
+ * shared exponent = floor(log2(amax)) - 2, clamped to the E8M0 range.  amax == 0 gives byte 0. */
+uint8_t orc_e8m0_from_amax(double amax)
+{
+    if (!(amax > 0.0)) return 0;
+    int ex;
+    (void)frexp(amax, &ex); /* amax = f * 2^ex with f in [0.5,1)  =>  floor(log2 amax) = ex-1 */
+    int E = (ex - 1) - 2;
+    int byte = E + 127;
+    if (byte < 0) byte = 0;
+    if (byte > 254) byte = 254;
+    return (uint8_t)byte;
+}
+
+/* ---------------------------------------------------------------- E4M3 scales */
+
+/* "fn" flavour: bias 7, no infinities, 0x7F is NaN, largest finite 0x7E = 448; subnormals m * 2^-9. */
+double orc_e4m3_decode(uint8_t c)
+{
+    int e = (c >> 3) & 15, m = c & 7;
+    double v = (e == 0) ? ldexp((double)m, -9) : ldexp(1.0 + (double)m / 8.0, e - 7);
+    return (c & 0x80) ? -v : v;
+}
+
+/* Non-negative input only (a scale).  Nearest of the 127 finite codes 0x00..0x7E, ties to the even
+ * code, saturating at 448. */
+uint8_t orc_e4m3_encode(double t)
+{
+    if (!(t > 0.0)) return 0;
+    if (t >= 448.0) return 0x7E; /* saturation */
+    int best = 0;
+    double best_d = t;
+    for (int c = 1; c <= 0x7E; ++c) {
+        double d = fabs(t - orc_e4m3_decode((uint8_t)c));
+        if (d < best_d || (d == best_d && (c & 1) == 0)) {
+            best = c;
+            best_d = d;
+        }
+    }
+    return (uint8_t)best;
+}
+
+/* ---------------------------------------------------------------- quantizers */
+
+/* MXFP4.  y: fp32 [M,K] (already rotated);  codes: [M,K/2], element k=2j in bits 3:0 of byte j and
+ * k=2j+1 in bits 7:4;  scales: [M,K/32] E8M0 bytes.  Returns -1 if K % 32 != 0. */
+int orc_quantize_mxfp4(const float *y, int64_t M, int64_t K, uint8_t *codes, uint8_t *scales)
+{
+    const int G = 32;
+    if (K % G != 0) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t g = 0; g < K / G; ++g) {
+            const float *v = y + m * K + g * G;
+            double amax = 0.0;
+            for (int i = 0; i < G; ++i) {
+                double a = fabs((double)v[i]);
+                if (a > amax) amax = a;
+            }
+            uint8_t sb = orc_e8m0_from_amax(amax);
+            scales[m * (K / G) + g] = sb;
+            double inv = ldexp(1.0, 127 - (int)sb); /* exact power of two */
+            for (int i = 0; i < G; i += 2) {
+                uint8_t lo = orc_e2m1_encode((double)v[i] * inv);
+                uint8_t hi = orc_e2m1_encode((double)v[i + 1] * inv);
+                codes[(m * K + g * G + i) / 2] = (uint8_t)(lo | (hi << 4));
+            }
+        }
+    }
+    return 0;
+}
+
+/* NVFP4 with abs-max scales.  All scale arithmetic is binary32 with one rounding per operation, in
+ * exactly this order:
+ *     s_T = amax_T / 2688                       (2688 = 6 * 448: largest element times largest scale)
+ *     t   = amax_g / (6 * s_T);  c = E4M3(t);  s_G = decode(c)
+ *     d   = s_T * s_G;  r = 1 / d;  code_i = E2M1(y_i * r)          (d == 0: all codes 0)
+ * y: fp32 [M,K];  codes [M,K/2];  scales [M,K/16] E4M3 bytes;  *s_T_out the tensor scale.
+ * If s_T_in is non-NULL its value is used instead of the abs-max one (static tensor scale). */
+int orc_quantize_nvfp4(const float *y, int64_t M, int64_t K, const float *s_T_in, uint8_t *codes,
+                       uint8_t *scales, float *s_T_out)
+{
+    const int G = 16;
+    if (K % G != 0) return -1;
+    float s_T;
+    if (s_T_in) {
+        s_T = *s_T_in;
+    } else {
+        float amax_T = 0.0f;
+        for (int64_t i = 0; i < M * K; ++i) {
+            float a = fabsf(y[i]);
+            if (a > amax_T) amax_T = a;
+        }
+        s_T = amax_T / 2688.0f;
+    }
+    *s_T_out = s_T;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t g = 0; g < K / G; ++g) {
+            const float *v = y + m * K + g * G;
+            float amax = 0.0f;
+            for (int i = 0; i < G; ++i) {
+                float a = fabsf(v[i]);
+                if (a > amax) amax = a;
+            }
+            uint8_t c = 0;
+            if (s_T > 0.0f) {
+                volatile float six_sT = 6.0f * s_T;
+                volatile float t = amax / six_sT;
+                c = orc_e4m3_encode((double)t);
+            }
+            scales[m * (K / G) + g] = c;
+            volatile float s_G = (float)orc_e4m3_decode(c);
+            volatile float d = s_T * s_G;
+            if (d == 0.0f) {
+                for (int i = 0; i < G; i += 2) codes[(m * K + g * G + i) / 2] = 0;
+                continue;
+            }
+            volatile float r = 1.0f / d;
+            for (int i = 0; i < G; i += 2) {
+                volatile float a0 = v[i] * r;
+                volatile float a1 = v[i + 1] * r;
+                uint8_t lo = orc_e2m1_encode((double)a0);
+                uint8_t hi = orc_e2m1_encode((double)a1);
+                codes[(m * K + g * G + i) / 2] = (uint8_t)(lo | (hi << 4));
+            }
+        }
+    }
+    return 0;
+}
+
+/* fmt 0 = MXFP4 (G=32, E8M0), fmt 1 = NVFP4 (G=16, E4M3, times s_T).  out: fp64 [M,K], exact. */
+int orc_dequantize(const uint8_t *codes, const uint8_t *scales, double s_T, int fmt, int64_t M,
+                   int64_t K, double *out)
+{
+    const int G = (fmt == 0) ? 32 : 16;
+    if (fmt != 0 && fmt != 1) return -1;
+    if (K % G != 0) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            uint8_t byte = codes[(m * K + k) / 2];
+            uint8_t code = (k & 1) ? (uint8_t)(byte >> 4) : (uint8_t)(byte & 15);
+            uint8_t sb = scales[m * (K / G) + k / G];
+            double s = (fmt == 0) ? orc_e8m0_decode(sb) : orc_e4m3_decode(sb) * s_T;
+            out[m * K + k] = orc_e2m1_decode(code) * s;
+        }
+    return 0;
+}
+
+/* ---------------------------------------------------------------- contraction */
+
+/* Y[m,n] = sum_k A[m,k] * W[n,k];  S[m,n] = sum_k |A[m,k]| * |W[n,k]|   (S may be NULL).
+ * A: [M,K], W: [N,K], both fp64 row-major.  Plain loops, k innermost, ascending. */
+void orc_matmul(const double *A, const double *W, int64_t M, int64_t N, int64_t K, double *Y, double *S)
+{
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0, accs = 0.0;
+            const double *a = A + m * K, *w = W + n * K;
+            for (int64_t k = 0; k < K; ++k) {
+                double p = a[k] * w[k];
+                acc += p;
+                accs += fabs(p);
+            }
+            Y[m * N + n] = acc;
+            if (S) S[m * N + n] = accs;
+        }
+}

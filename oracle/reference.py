@@ -1,0 +1,203 @@
+"""NumPy front end of the plain-C oracle (``mrfp4_oracle.c``).  TEST INFRASTRUCTURE ONLY.
+
+The arithmetic lives in the C file, written from the paper (arXiv 2509.23202, Sections 2, 3, 4.1,
+4.2 and the proof of Lemma 1) and the OCP Microscaling rules; this module only compiles it with gcc,
+loads it with ctypes and marshals NumPy arrays.  It shares nothing with the HIP library.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "mrfp4_oracle.c"
+_LIB = _HERE / "libmrfp4_oracle.so"
+
+MXFP4 = 0
+NVFP4 = 1
+GROUP = {MXFP4: 32, NVFP4: 16}
+
+
+def build(force: bool = False) -> Path:
+    """Compile the C oracle (gcc, -O2, no contraction, no fast-math, OpenMP)."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB.with_suffix(".so.tmp%d" % os.getpid())
+        cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared",
+               "-fPIC", "-Wall", "-Wextra", "-o", str(tmp), str(_SRC), "-lm"]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(str(_LIB))
+        i64, p, i32, dbl, u8 = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_double, ctypes.c_uint8
+        L.orc_max_threads.restype = i32
+        L.orc_set_threads.argtypes = [i32]
+        L.orc_hadamard.argtypes = [i32, p]
+        L.orc_hadamard.restype = i32
+        L.orc_rotate.argtypes = [p, i64, i64, i32, p]
+        L.orc_rotate.restype = i32
+        L.orc_rotate_f64.argtypes = [p, i64, i64, i32, p]
+        L.orc_rotate_f64.restype = i32
+        L.orc_e2m1_decode.argtypes = [u8]
+        L.orc_e2m1_decode.restype = dbl
+        L.orc_e2m1_encode.argtypes = [dbl]
+        L.orc_e2m1_encode.restype = u8
+        L.orc_e8m0_decode.argtypes = [u8]
+        L.orc_e8m0_decode.restype = dbl
+        L.orc_e8m0_from_amax.argtypes = [dbl]
+        L.orc_e8m0_from_amax.restype = u8
+        L.orc_e4m3_decode.argtypes = [u8]
+        L.orc_e4m3_decode.restype = dbl
+        L.orc_e4m3_encode.argtypes = [dbl]
+        L.orc_e4m3_encode.restype = u8
+        L.orc_quantize_mxfp4.argtypes = [p, i64, i64, p, p]
+        L.orc_quantize_mxfp4.restype = i32
+        L.orc_quantize_nvfp4.argtypes = [p, i64, i64, p, p, p, p]
+        L.orc_quantize_nvfp4.restype = i32
+        L.orc_dequantize.argtypes = [p, p, dbl, i32, i64, i64, p]
+        L.orc_dequantize.restype = i32
+        L.orc_matmul.argtypes = [p, p, i64, i64, i64, p, p]
+        L.orc_matmul.restype = None
+        _lib = L
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def max_threads() -> int:
+    return int(_load().orc_max_threads())
+
+
+def set_threads(n: int) -> None:
+    _load().orc_set_threads(int(n))
+
+
+# ---------------------------------------------------------------- scalar codecs
+def e2m1_decode(code: int) -> float:
+    return float(_load().orc_e2m1_decode(int(code) & 0xFF))
+
+
+def e2m1_encode(v: float) -> int:
+    return int(_load().orc_e2m1_encode(float(v)))
+
+
+def e8m0_decode(byte: int) -> float:
+    return float(_load().orc_e8m0_decode(int(byte)))
+
+
+def e8m0_from_amax(amax: float) -> int:
+    return int(_load().orc_e8m0_from_amax(float(amax)))
+
+
+def e4m3_decode(byte: int) -> float:
+    return float(_load().orc_e4m3_decode(int(byte)))
+
+
+def e4m3_encode(t: float) -> int:
+    return int(_load().orc_e4m3_encode(float(t)))
+
+
+# ---------------------------------------------------------------- arrays
+def hadamard(b: int) -> np.ndarray:
+    H = np.zeros((b, b), dtype=np.int8)
+    if _load().orc_hadamard(int(b), _ptr(H)) != 0:
+        raise ValueError(f"hadamard: b={b} is not a power of two in [1,1024]")
+    return H
+
+
+def rotate(x_bf16_bits: np.ndarray, b: int) -> np.ndarray:
+    """x: uint16 bf16 bit patterns [M,K] -> fp32 [M,K] = x @ blockdiag(H_b/sqrt(b))."""
+    x = np.ascontiguousarray(x_bf16_bits, dtype=np.uint16)
+    M, K = x.shape
+    y = np.empty((M, K), dtype=np.float32)
+    if _load().orc_rotate(_ptr(x), M, K, int(b), _ptr(y)) != 0:
+        raise ValueError(f"rotate: bad b={b} for K={K}")
+    return y
+
+
+def rotate_f64(x: np.ndarray, b: int) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    M, K = x.shape
+    y = np.empty((M, K), dtype=np.float64)
+    if _load().orc_rotate_f64(_ptr(x), M, K, int(b), _ptr(y)) != 0:
+        raise ValueError(f"rotate_f64: bad b={b} for K={K}")
+    return y
+
+
+def quantize(y_f32: np.ndarray, fmt: int, tensor_scale: float | None = None):
+    """fp32 [M,K] -> (codes u8 [M,K/2], scales u8 [M,K/G], s_T float32 scalar or None)."""
+    y = np.ascontiguousarray(y_f32, dtype=np.float32)
+    M, K = y.shape
+    G = GROUP[fmt]
+    if K % G:
+        raise ValueError(f"quantize: K={K} not a multiple of {G}")
+    codes = np.empty((M, K // 2), dtype=np.uint8)
+    scales = np.empty((M, K // G), dtype=np.uint8)
+    if fmt == MXFP4:
+        rc = _load().orc_quantize_mxfp4(_ptr(y), M, K, _ptr(codes), _ptr(scales))
+        s_T = None
+    else:
+        s_out = np.zeros(1, dtype=np.float32)
+        s_in = None
+        if tensor_scale is not None:
+            s_in_arr = np.array([tensor_scale], dtype=np.float32)
+            s_in = _ptr(s_in_arr)
+        rc = _load().orc_quantize_nvfp4(_ptr(y), M, K, s_in, _ptr(codes), _ptr(scales), _ptr(s_out))
+        s_T = np.float32(s_out[0])
+    if rc != 0:
+        raise ValueError("quantize failed")
+    return codes, scales, s_T
+
+
+def dequantize(codes: np.ndarray, scales: np.ndarray, fmt: int, s_T=None) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.uint8)
+    M, K2 = codes.shape
+    K = 2 * K2
+    out = np.empty((M, K), dtype=np.float64)
+    st = 1.0 if s_T is None else float(s_T)
+    if _load().orc_dequantize(_ptr(codes), _ptr(scales), st, int(fmt), M, K, _ptr(out)) != 0:
+        raise ValueError("dequantize failed")
+    return out
+
+
+def matmul(A: np.ndarray, W: np.ndarray, want_abs: bool = True):
+    """Y = A @ W.T and S = |A| @ |W|.T by plain fp64 loops."""
+    A = np.ascontiguousarray(A, dtype=np.float64)
+    W = np.ascontiguousarray(W, dtype=np.float64)
+    M, K = A.shape
+    N, K2 = W.shape
+    assert K == K2
+    Y = np.empty((M, N), dtype=np.float64)
+    S = np.empty((M, N), dtype=np.float64) if want_abs else None
+    _load().orc_matmul(_ptr(A), _ptr(W), M, N, K, _ptr(Y), _ptr(S) if want_abs else None)
+    return Y, S
+
+
+def rotate_quantize(x_bf16_bits: np.ndarray, b: int, fmt: int, tensor_scale=None):
+    """The whole activation/weight encoding: rotate along K, then quantize."""
+    y = rotate(x_bf16_bits, b)
+    return quantize(y, fmt, tensor_scale) + (y,)
+
+
+def linear(x_bits: np.ndarray, w_bits: np.ndarray, b: int, fmt: int):
+    """Y = Q(X H_b) Q(W H_b)^T in fp64 plus the tolerance denominator S."""
+    ac, asc, aT, _ = rotate_quantize(x_bits, b, fmt)
+    wc, wsc, wT, _ = rotate_quantize(w_bits, b, fmt)
+    A = dequantize(ac, asc, fmt, aT)
+    W = dequantize(wc, wsc, fmt, wT)
+    return matmul(A, W)

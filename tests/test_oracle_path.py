@@ -1,0 +1,352 @@
+"""Pins for the oracle's rotation, MXFP4 / NVFP4 quantizers, dequantizer and fp64 contraction.
+
+Independent references used here: a NumPy FWHT butterfly (different algorithm from the oracle's dense
+product), exact constructions whose encoding is known in advance, property checks recomputed with
+NumPy/torch library casts, brute force over the decoded grid, and the paper's qualitative claims.
+"""
+from pathlib import Path
+
+import numpy as np
+import pytest
+
+from paper_2509_23202_amd import inputs
+
+MX, NV = 0, 1
+GRID = np.array([0, .5, 1, 1.5, 2, 3, 4, 6], dtype=np.float64)
+
+
+def bits(a):
+    return inputs.f32_to_bf16_bits(np.asarray(a, dtype=np.float32))
+
+
+def unpack(codes):
+    lo = codes & 15
+    hi = codes >> 4
+    return np.stack([lo, hi], axis=-1).reshape(codes.shape[0], -1)
+
+
+def decode_codes(c):
+    return np.where(c & 8, -1.0, 1.0) * GRID[c & 7]
+
+
+def fwht_rows(x, b):
+    """Textbook in-place butterfly on blocks of b along the last axis (natural / Sylvester order)."""
+    y = np.array(x, dtype=np.float64)
+    M, K = y.shape
+    y = y.reshape(M, K // b, b)
+    h = 1
+    while h < b:
+        y = y.reshape(M, K // b, b // (2 * h), 2, h)
+        a = y[..., 0, :] + y[..., 1, :]
+        d = y[..., 0, :] - y[..., 1, :]
+        y = np.stack([a, d], axis=-2).reshape(M, K // b, b)
+        h *= 2
+    return (y / np.sqrt(b)).reshape(M, K)
+
+
+# ---------------------------------------------------------------- rotation
+@pytest.mark.parametrize("b", [1, 16, 32, 64, 128])
+def test_rotation_matches_butterfly_and_preserves_norm(oracle, b):
+    rng = np.random.default_rng(b)
+    xb = bits(rng.standard_normal((5, 384)) * np.exp(rng.uniform(-3, 3, (5, 384))))
+    x = inputs.bf16_bits_to_f32(xb).astype(np.float64)
+    y = oracle.rotate(xb, b)
+    assert y.dtype == np.float32
+    want = fwht_rows(x, b)
+    assert np.array_equal(y, want.astype(np.float32)) or np.max(np.abs(y - want) / (np.abs(want) + 1e-30)) < 2.0 ** -22
+    # one rounding to fp32: error at most half an ulp of the exact value
+    assert np.all(np.abs(y.astype(np.float64) - want) <= np.spacing(np.abs(want).astype(np.float32)) * 0.5 + 1e-300)
+    assert np.allclose(np.linalg.norm(y.astype(np.float64), axis=1), np.linalg.norm(x, axis=1), rtol=1e-6)
+    if b == 1:
+        assert np.array_equal(y, x.astype(np.float32))
+
+
+@pytest.mark.parametrize("b", [16, 32, 128])
+def test_rotation_of_unit_vectors_gives_hadamard_rows(oracle, b):
+    H = oracle.hadamard(b).astype(np.float64)
+    K = 2 * b
+    for i in (0, 1, b - 1, b, b + 5):
+        e = np.zeros((1, K), dtype=np.float32)
+        e[0, i] = 1.0
+        y = oracle.rotate(bits(e), b)[0].astype(np.float64)
+        want = np.zeros(K)
+        blk = i // b
+        want[blk * b:(blk + 1) * b] = H[i % b] / np.sqrt(b)
+        assert np.array_equal(y, want.astype(np.float32).astype(np.float64))   # block-diagonal: other block untouched
+
+
+def test_rotation_rejects_bad_block(oracle):
+    with pytest.raises(ValueError):
+        oracle.rotate(np.zeros((1, 48), dtype=np.uint16), 32)
+    with pytest.raises(ValueError):
+        oracle.rotate(np.zeros((1, 48), dtype=np.uint16), 24)
+
+
+def test_rotating_both_operands_leaves_product_unchanged(oracle):
+    """(X U)(W U)^T = X W^T for orthogonal block-diagonal U: pins that both operands use the same matrix,
+    along the same axis (Section 4.1, Ingredient 3)."""
+    rng = np.random.default_rng(3)
+    X = rng.standard_normal((7, 256))
+    W = rng.standard_normal((9, 256))
+    for b in (16, 32, 64, 128):
+        Xr, Wr = oracle.rotate_f64(X, b), oracle.rotate_f64(W, b)
+        Y, _ = oracle.matmul(Xr, Wr)
+        assert np.allclose(Y, X @ W.T, rtol=0, atol=1e-11)
+        assert np.allclose(Xr, fwht_rows(X, b), atol=1e-13)
+
+
+# ---------------------------------------------------------------- contraction
+def test_matmul_against_library_and_abs_sum(oracle):
+    rng = np.random.default_rng(5)
+    A = rng.standard_normal((13, 160))
+    W = rng.standard_normal((11, 160))
+    Y, S = oracle.matmul(A, W)
+    assert np.allclose(Y, A @ W.T, rtol=0, atol=1e-12)
+    assert np.allclose(S, np.abs(A) @ np.abs(W).T, rtol=1e-13)
+    assert np.all(S >= np.abs(Y) - 1e-12)
+    # not symmetric in its operands' roles: W is [N,K], result is [M,N]
+    assert Y.shape == (13, 11)
+
+
+def test_matmul_exact_on_integers_and_selector_weights(oracle):
+    rng = np.random.default_rng(6)
+    A = rng.integers(-12, 13, (6, 64)).astype(np.float64) / 2
+    W = rng.integers(-12, 13, (5, 64)).astype(np.float64) / 2
+    Y, _ = oracle.matmul(A, W)
+    want = (2 * A).astype(np.int64) @ (2 * W).astype(np.int64).T
+    assert np.array_equal(Y * 4, want.astype(np.float64))
+    sel = np.zeros((4, 64))
+    for n, k in enumerate((3, 17, 40, 63)):
+        sel[n, k] = 1.0
+    Y, _ = oracle.matmul(A, sel)
+    assert np.array_equal(Y, A[:, [3, 17, 40, 63]])
+
+
+# ---------------------------------------------------------------- MXFP4
+def test_mxfp4_on_grid_vectors_round_trip(oracle):
+    """Rows of the form grid * 2^e whose largest element is 4 or 6 (times 2^e) are recovered exactly,
+    with scale byte e+127; a different e per group pins the group/scale indexing and the nibble order."""
+    rng = np.random.default_rng(1)
+    M, K, G = 6, 256, 32
+    codes = rng.integers(0, 16, (M, K))
+    exps = rng.integers(-20, 21, (M, K // G))
+    top = rng.choice([6, 7], (M, K // G))
+    pos = rng.integers(0, G, (M, K // G))
+    for m in range(M):
+        for g in range(K // G):
+            codes[m, g * G + pos[m, g]] = top[m, g] | (8 * rng.integers(0, 2))
+    y = (decode_codes(codes).reshape(M, K // G, G) * (2.0 ** exps)[..., None]).reshape(M, K).astype(np.float32)
+    c, s, sT = oracle.quantize(y, MX)
+    assert sT is None
+    assert c.shape == (M, K // 2) and s.shape == (M, K // G)
+    assert np.array_equal(s, (exps + 127).astype(np.uint8))
+    got = unpack(c)
+    same = (got == codes) | ((got & 7) == 0) & ((codes & 7) == 0) & (np.signbit(y) == ((got & 8) != 0))
+    assert same.all()
+    assert np.array_equal(oracle.dequantize(c, s, MX), y.astype(np.float64))
+    assert c[0, 0] == (got[0, 0] | (got[0, 1] << 4))                      # element 2j in the low nibble
+    bits_per_elem = 8 * (c.nbytes + s.nbytes) / (M * K)
+    assert bits_per_elem == 4.25                                          # Section 2: 4.25 bits per element
+
+
+def test_mxfp4_properties_on_random_data(oracle):
+    """scale = the power of two with amax/scale in [4,8); every code is the nearest grid point of
+    y/scale (recomputed with NumPy); values in (6,8)*scale saturate to 6."""
+    rng = np.random.default_rng(2)
+    y = (rng.laplace(0, 1, (16, 512)) * np.exp(rng.uniform(-8, 8, (16, 1)))).astype(np.float32)
+    y[3, 64:96] = 0.0                                                     # an all-zero group
+    y[4, 0] = 0.0
+    c, s, _ = oracle.quantize(y, MX)
+    G = 32
+    yg = y.astype(np.float64).reshape(16, -1, G)
+    amax = np.abs(yg).max(-1)
+    sc = 2.0 ** (s.astype(np.int64) - 127)
+    nz = amax > 0
+    r = amax[nz] / sc[nz]
+    assert np.all((r >= 4) & (r < 8))
+    assert np.all(s[~nz] == 0)
+    u = np.abs(yg) / sc[..., None]
+    dist = np.abs(u[..., None] - GRID)                                    # brute force over the grid
+    near = dist.argmin(-1)
+    tie = np.isclose(np.sort(dist, -1)[..., 0], np.sort(dist, -1)[..., 1], rtol=0, atol=0)
+    got = unpack(c).reshape(16, -1, G)
+    assert np.array_equal((got & 7)[~tie], near[~tie])
+    assert np.array_equal((got & 8) != 0, np.signbit(yg))
+    sat = u > 6
+    assert sat.any() and np.all((got & 7)[sat] == 7)
+    assert np.all(got[3, 2] == 0)
+
+
+def test_mxfp4_ties_are_even_with_power_of_two_scale(oracle):
+    # group max 4 -> scale 1; the seven midpoints appear verbatim
+    y = np.zeros((1, 32), dtype=np.float32)
+    y[0, :8] = [4.0, 0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0]
+    y[0, 8:15] = [-0.25, -0.75, -1.25, -1.75, -2.5, -3.5, -5.0]
+    c, s, _ = oracle.quantize(y, MX)
+    assert s[0, 0] == 127
+    got = decode_codes(unpack(c))[0]
+    assert list(got[:8]) == [4.0, 0.0, 1.0, 1.0, 2.0, 2.0, 4.0, 4.0]
+    assert list(got[8:15]) == [-0.0, -1.0, -1.0, -2.0, -2.0, -4.0, -4.0]
+    assert unpack(c)[0, 8] == 8                                           # -0.25 -> "-0"
+
+
+# ---------------------------------------------------------------- NVFP4
+def _nv_reference(y, sT=None):
+    """Independent NumPy/torch recomputation of the NVFP4 recipe in float32 (library E4M3 cast)."""
+    import torch
+    y = np.asarray(y, dtype=np.float32)
+    M, K = y.shape
+    if sT is None:
+        sT = np.float32(np.abs(y).max()) / np.float32(2688.0)
+    sT = np.float32(sT)
+    yg = y.reshape(M, K // 16, 16)
+    amax = np.abs(yg).max(-1).astype(np.float32)
+    t = amax / (np.float32(6.0) * sT)
+    t = np.minimum(t, np.float32(448.0))
+    sc_code = torch.from_numpy(t).to(torch.float8_e4m3fn)
+    sG = sc_code.to(torch.float32).numpy()
+    d = (sT * sG).astype(np.float32)
+    r = (np.float32(1.0) / d).astype(np.float32)
+    u = (yg * r[..., None]).astype(np.float32)
+    return sT, sc_code.view(torch.uint8).numpy(), u.reshape(M, K)
+
+
+def test_nvfp4_matches_independent_float32_recipe(oracle):
+    rng = np.random.default_rng(4)
+    y = (rng.standard_t(3, (12, 256)) / np.sqrt(3)).astype(np.float32)
+    c, s, sT = oracle.quantize(y, NV)
+    sT_ref, s_ref, u = _nv_reference(y)
+    assert sT == sT_ref and sT.dtype == np.float32
+    assert np.array_equal(s, s_ref)
+    assert np.all(s < 0x80)                                               # sign bit of the scale never used
+    a = np.abs(u.astype(np.float64))
+    dist = np.abs(a[..., None] - GRID)
+    srt = np.sort(dist, -1)
+    tie = srt[..., 0] == srt[..., 1]
+    got = unpack(c)
+    assert np.array_equal((got & 7)[~tie], dist.argmin(-1)[~tie])
+    assert np.array_equal((got & 8) != 0, np.signbit(y))
+    assert 8 * (c.nbytes + s.nbytes) / y.size == 4.5                      # Section 2: 4.5 bits per element
+
+
+def test_nvfp4_top_element_is_preserved(oracle):
+    """The tensor's abs-max element lands on scale code 448 and element code +-6, so it is reproduced
+    up to the rounding of s_T (top-value preservation, Section 3 discussion)."""
+    rng = np.random.default_rng(8)
+    y = rng.standard_normal((8, 128)).astype(np.float32)
+    y[5, 77] = -9.5
+    c, s, sT = oracle.quantize(y, NV)
+    assert s[5, 77 // 16] == 0x7E
+    assert unpack(c)[5, 77] == 15
+    deq = oracle.dequantize(c, s, NV, sT)
+    assert abs(deq[5, 77] - (-9.5)) <= 9.5 * 2.0 ** -22
+
+
+def test_nvfp4_on_grid_construction_round_trips(oracle):
+    rng = np.random.default_rng(9)
+    M, K, G = 4, 128, 16
+    sT = np.float32(2.0 ** -7)
+    sc_codes = rng.integers(0x20, 0x7F, (M, K // G)).astype(np.uint8)     # normal E4M3 scales
+    codes = rng.integers(0, 16, (M, K))
+    for m in range(M):
+        for g in range(K // G):
+            codes[m, g * G + rng.integers(0, G)] = 7                      # group max is 6 * scale
+    sG = np.array([[oracle.e4m3_decode(int(v)) for v in row] for row in sc_codes])
+    sc_codes[0, 0] = 0x7E
+    sG[0, 0] = 448.0                                                      # tensor max = 6*448*sT -> s_T recovered
+    y = (decode_codes(codes).reshape(M, K // G, G) * sG[..., None] * float(sT)).reshape(M, K)
+    assert np.array_equal(y, y.astype(np.float32).astype(np.float64))
+    c, s, sT_got = oracle.quantize(y.astype(np.float32), NV)
+    assert sT_got == sT
+    assert np.array_equal(s, sc_codes)
+    got = unpack(c)
+    assert np.array_equal(got & 7, codes & 7)
+    assert np.array_equal(oracle.dequantize(c, s, NV, sT_got), y)
+
+
+def test_nvfp4_zero_tensor_and_static_scale(oracle):
+    y = np.zeros((2, 32), dtype=np.float32)
+    c, s, sT = oracle.quantize(y, NV)
+    assert sT == 0 and not s.any() and not c.any()
+    rng = np.random.default_rng(10)
+    y = rng.standard_normal((3, 64)).astype(np.float32)
+    c, s, sT = oracle.quantize(y, NV, tensor_scale=2.0 ** -9)
+    sT_ref, s_ref, _ = _nv_reference(y, 2.0 ** -9)
+    assert sT == np.float32(2.0 ** -9) and np.array_equal(s, s_ref)
+
+
+def test_quantizers_reject_ragged_K(oracle):
+    with pytest.raises(ValueError):
+        oracle.quantize(np.zeros((1, 48), dtype=np.float32), MX)
+    with pytest.raises(ValueError):
+        oracle.quantize(np.zeros((1, 24), dtype=np.float32), NV)
+
+
+# ---------------------------------------------------------------- qualitative claims of the paper
+def _rel_mse(oracle, xb, b, fmt):
+    y = oracle.rotate(xb, b)
+    c, s, sT = oracle.quantize(y, fmt)
+    d = oracle.dequantize(c, s, fmt, sT)
+    yy = y.astype(np.float64)
+    return float(((d - yy) ** 2).sum() / (yy ** 2).sum())
+
+
+def test_hadamard_helps_mxfp4_and_hurts_nvfp4_on_laplace(oracle):
+    """Direction only (the plotted numbers are not in the text): Sections 1 and 3.3 state that rotations
+    lower MXFP4's relative error on heavy-tailed data and raise NVFP4's at G=16."""
+    rng = np.random.default_rng(12)
+    xb = bits(rng.laplace(0, 1 / np.sqrt(2), (256, 1024)))
+    mx_plain, mx_rot = _rel_mse(oracle, xb, 1, MX), _rel_mse(oracle, xb, 32, MX)
+    nv_plain, nv_rot = _rel_mse(oracle, xb, 1, NV), _rel_mse(oracle, xb, 16, NV)
+    assert mx_rot < mx_plain
+    assert nv_rot > nv_plain
+    assert nv_plain < mx_plain                                            # NVFP4 has the lower RTN error
+
+
+def test_rotation_spreads_error_evenly_lemma1(oracle):
+    """Lemma 1: with the Hadamard rotation the error on the original top coordinate equals the mean
+    error; without it abs-max scaling keeps the top element (unquantized scale, here NVFP4's near-exact one)."""
+    rng = np.random.default_rng(13)
+    G = 32
+    x = rng.standard_normal((4000, G))
+    xb = bits(x)
+    xf = inputs.bf16_bits_to_f32(xb).astype(np.float64)
+    y = oracle.rotate(xb, G)
+    c, s, _ = oracle.quantize(y, MX)
+    eps_y = oracle.dequantize(c, s, MX) - y.astype(np.float64)
+    eps_x = oracle.rotate_f64(eps_y, G)                                   # U symmetric: U^T eps = eps U
+    assert np.allclose((eps_x ** 2).sum(1), (eps_y ** 2).sum(1), rtol=1e-9)   # ||eps_x|| = ||eps_y||
+    top = np.abs(xf).argmax(1)
+    mse_top = (eps_x[np.arange(len(top)), top] ** 2).mean()
+    mse = (eps_x ** 2).mean()
+    assert abs(mse_top / mse - 1.0) < 0.3       # idealised statement; saturation correlates error and data a little
+    # no rotation, NVFP4: the top element of each tensor is reproduced (almost) exactly
+    y0 = oracle.rotate(xb[:1, :16], 1)
+    c0, s0, sT0 = oracle.quantize(y0, NV)
+    d0 = oracle.dequantize(c0, s0, NV, sT0)
+    j = np.abs(y0[0]).argmax()
+    assert abs(d0[0, j] - y0[0, j]) <= abs(y0[0, j]) * 2.0 ** -22
+
+
+# ---------------------------------------------------------------- whole path
+def test_linear_close_to_unquantized_product(oracle):
+    r = inputs.RECIPES[1]
+    xb, wb = r.x(8, 512), r.w(24, 512)
+    X = inputs.bf16_bits_to_f32(xb).astype(np.float64)
+    W = inputs.bf16_bits_to_f32(wb).astype(np.float64)
+    exact = X @ W.T
+    for fmt, b in ((MX, 32), (NV, 16), (MX, 128), (MX, 1)):
+        Y, S = oracle.linear(xb, wb, b, fmt)
+        rel = np.linalg.norm(Y - exact) / np.linalg.norm(exact)
+        assert rel < 0.25, (fmt, b, rel)
+        assert np.all(np.abs(Y) <= S + 1e-12)
+
+
+def test_oracle_is_not_imported_by_the_product():
+    """The oracle is test infrastructure: no file of the package may mention it."""
+    root = Path(__file__).resolve().parent.parent / "paper_2509_23202_amd"
+    for p in root.rglob("*"):
+        if p.suffix in {".py", ".hip", ".h", ".hpp", ".cpp", ".c"}:
+            txt = p.read_text()
+            assert "oracle" not in txt.lower() or p.name == "inputs.py" and "import" not in [
+                ln for ln in txt.splitlines() if "oracle" in ln.lower()][0], p
