@@ -1,0 +1,125 @@
+/*
+ * fp4mr — micro-rotated FP4 linear-layer hot path for AMD MI355X (gfx950).
+ *
+ * C ABI of libfp4mr.so.  The library computes, for a linear layer with activations X [M,K] and weights
+ * W [N,K] (both bf16, row-major),
+ *
+ *        Y = Q(X H_b) * Q(W H_b)^T            (arXiv 2509.23202, Section 4.1 "Ingredient 3", Section 4.2)
+ *
+ * where H_b is the block-diagonal normalised Hadamard rotation with b x b Sylvester blocks along K and Q
+ * is round-to-nearest microscaling FP4 quantization with abs-max group scales (Section 2; Section 3,
+ * definition "Scales"):
+ *     MXFP4: groups of 32, E2M1 elements, E8M0 scale 2^(floor(log2 amax) - 2)     (OCP MX rule)
+ *     NVFP4: groups of 16, E2M1 elements, E4M3 group scale s_G and one fp32 tensor scale s_T,
+ *            Xhat = s_T * s_G * Q(X / (s_T * s_G))                                (Section 4.1 "Ingredient 1")
+ *            with s_T = amax_T / 2688, s_G = E4M3(amax_g / (6 s_T)), all in binary32.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers unless a parameter says "host".  The caller owns every
+ *     buffer, including the workspace; the library allocates, frees and retains nothing.
+ *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *     Outputs are valid once the caller has synchronised with the stream.
+ *   - Every argument is validated on the host before anything is launched; on a non-zero status nothing
+ *     was written.  No exception or abort crosses this boundary.
+ *   - Data pointers must be 16-byte aligned.
+ *   - Behaviour for NaN / Inf inputs is unspecified.
+ *
+ * Canonical layouts
+ *   codes  [rows, K/2] bytes, row-major: byte j of a row holds element k=2j in bits 3:0 and k=2j+1 in
+ *          bits 7:4.  A code is  s e1 e0 m : magnitudes 0..7 -> {0, 0.5, 1, 1.5, 2, 3, 4, 6}, bit 3 = sign.
+ *   scales [rows, K/G] bytes, row-major.  MXFP4: byte e means 2^(e-127), 0xFF is never produced.
+ *          NVFP4: E4M3 ("fn": bias 7, max 448, no infinities), sign bit always 0.
+ * GEMM layout (FP4MR_LAYOUT_GEMM): an opaque tiled order produced by the two quantize calls and consumed
+ *   by fp4_gemm; sizes come from fp4_packed_bytes (rows are padded to a multiple of 16, K to 128/512).
+ *   Padding bytes are never read into a stored result and need not be initialised.
+ */
+#ifndef FP4MR_H
+#define FP4MR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { FP4MR_MXFP4 = 0, FP4MR_NVFP4 = 1 } fp4mr_fmt_t;
+
+typedef enum {
+    FP4MR_OK = 0,
+    FP4MR_ERR_NULL = 1,       /* a required pointer is NULL */
+    FP4MR_ERR_SHAPE = 2,      /* M, N or K <= 0, or K not a multiple of what the format/layout needs */
+    FP4MR_ERR_HAD_BLOCK = 3,  /* had_block not in {1, 16, 32, 64, 128} */
+    FP4MR_ERR_FMT = 4,        /* fmt is neither FP4MR_MXFP4 nor FP4MR_NVFP4, or unknown flag bits */
+    FP4MR_ERR_ALIGN = 5,      /* a data pointer is not 16-byte aligned */
+    FP4MR_ERR_WORKSPACE = 6,  /* workspace is NULL or smaller than fp4_workspace_bytes() says */
+    FP4MR_ERR_DEVICE = 7      /* the HIP runtime reported an error at launch */
+} fp4mr_status_t;
+
+/* flags (bit field) */
+enum {
+    FP4MR_LAYOUT_CANONICAL = 0u,
+    FP4MR_LAYOUT_GEMM = 1u << 0,          /* quantize calls: write codes and scales in GEMM layout           */
+    FP4MR_INPUT_F32 = 1u << 1,            /* quantize calls: input is fp32 [rows,K]; requires had_block == 1  */
+    FP4MR_STATIC_TENSOR_SCALE = 1u << 2,  /* NVFP4 quantize: *tensor_scale already holds s_T; do not derive it */
+    FP4MR_A_LAYOUT_GEMM = 1u << 3,        /* fp4_gemm: A codes/scales are in GEMM layout (else canonical)     */
+    FP4MR_W_LAYOUT_GEMM = 1u << 4,        /* fp4_gemm: W codes/scales are in GEMM layout (else canonical)     */
+    FP4MR_OUT_F32 = 1u << 5               /* fp4_gemm: write the fp32 accumulator instead of bf16             */
+};
+
+/* operation selector for fp4_workspace_bytes */
+enum { FP4MR_OP_ROTATE_QUANTIZE = 0, FP4MR_OP_QUANTIZE_WEIGHTS = 1, FP4MR_OP_GEMM = 2 };
+
+/*
+ * Online rotation + quantization of activations: codes, scales = Q(X H_b)   (Section 4.2 item 1: rotation
+ * with quantization and scale calculation fused behind it; replaces the separate scale re-layout step of
+ * Section 4.2 item 2 by writing GEMM layout directly when FP4MR_LAYOUT_GEMM is set).
+ *   x            [M,K] bf16 (fp32 with FP4MR_INPUT_F32), row-major
+ *   had_block    b in {1,16,32,64,128}; 1 = no rotation.  K must be a multiple of lcm(b, G) (and of 128 for
+ *                GEMM layout).
+ *   codes_out    canonical: M*K/2 bytes;  scales_out: M*K/G bytes (see fp4_packed_bytes for GEMM layout)
+ *   tensor_scale NVFP4 only (NULL for MXFP4): one device float; written with s_T, or read if
+ *                FP4MR_STATIC_TENSOR_SCALE is set.
+ *   workspace    device scratch of at least fp4_workspace_bytes(FP4MR_OP_ROTATE_QUANTIZE, ...) bytes
+ *                (0 for MXFP4: may be NULL).
+ */
+fp4mr_status_t fp4_rotate_quantize(const void* x, int64_t M, int64_t K, int had_block, fp4mr_fmt_t fmt,
+                                   void* codes_out, void* scales_out, float* tensor_scale,
+                                   void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
+
+/*
+ * Offline weight preparation: codes, scales = Q(W H_b) by round-to-nearest (Section 4.2 item 1: "W H_k is
+ * pre-fused in the weights"; RTN + HT row of Section 5's method list).  Same arguments as
+ * fp4_rotate_quantize with rows = N.  GPTQ-style calibration is not part of this library.
+ */
+fp4mr_status_t fp4_quantize_weights(const void* w, int64_t N, int64_t K, int had_block, fp4mr_fmt_t fmt,
+                                    void* codes_out, void* scales_out, float* tensor_scale,
+                                    void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
+
+/*
+ * W4A4 product of two quantized operands: out[m,n] = sum_k Ahat[m,k] * What[n,k]  (Section 4.2 item 2),
+ * fp32 accumulation, bf16 round-to-nearest-even output (fp32 with FP4MR_OUT_F32).  K % 128 == 0.
+ *   a_codes/a_scales  [M,K] operand, w_codes/w_scales [N,K] operand, layouts per flags
+ *   a_tensor_scale, w_tensor_scale   NVFP4: device floats s_T of each operand; MXFP4: NULL
+ *   out          [M,N] row-major
+ */
+fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* a_tensor_scale,
+                        const void* w_codes, const void* w_scales, const float* w_tensor_scale,
+                        int64_t M, int64_t N, int64_t K, fp4mr_fmt_t fmt, void* out,
+                        void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
+
+/* Bytes of device scratch the given operation needs (0 = none).  rows = M for the quantize ops. */
+size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t fmt, uint32_t flags);
+
+/* Buffer sizes for an operand of `rows` x K in the layout selected by flags & FP4MR_LAYOUT_GEMM.
+ * Returns FP4MR_OK and fills both outputs (host pointers). */
+fp4mr_status_t fp4_packed_bytes(int64_t rows, int64_t K, fp4mr_fmt_t fmt, uint32_t flags,
+                                size_t* codes_bytes, size_t* scales_bytes);
+
+const char* fp4_status_string(fp4mr_status_t status);
+int fp4_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FP4MR_H */

@@ -1,0 +1,133 @@
+"""Thin ctypes binding of libfp4mr.so: argument marshalling only.
+
+PyTorch supplies device memory (``torch.empty(..., device="cuda")``) and the current HIP stream; every step of
+the path runs inside the library's HIP kernels.  There is no CPU fallback: importing this module raises if the
+library has not been built (``python -m paper_2509_23202_amd.build``).
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+import torch
+
+_LIB_PATH = Path(__file__).resolve().parent / "libfp4mr.so"
+if not _LIB_PATH.exists():
+    raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2509_23202_amd.build` "
+                      "(there is no fallback path)")
+lib = ctypes.CDLL(str(_LIB_PATH))
+
+MXFP4, NVFP4 = 0, 1
+GROUP = {MXFP4: 32, NVFP4: 16}
+
+LAYOUT_GEMM = 1 << 0
+INPUT_F32 = 1 << 1
+STATIC_TENSOR_SCALE = 1 << 2
+A_LAYOUT_GEMM = 1 << 3
+W_LAYOUT_GEMM = 1 << 4
+OUT_F32 = 1 << 5
+OP_ROTATE_QUANTIZE, OP_QUANTIZE_WEIGHTS, OP_GEMM = 0, 1, 2
+
+_p, _i64, _i32, _u32, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32, ctypes.c_size_t
+_quant_sig = [_p, _i64, _i64, _i32, _i32, _p, _p, _p, _p, _sz, _u32, _p]
+lib.fp4_rotate_quantize.argtypes = _quant_sig
+lib.fp4_rotate_quantize.restype = _i32
+lib.fp4_quantize_weights.argtypes = _quant_sig
+lib.fp4_quantize_weights.restype = _i32
+lib.fp4_gemm.argtypes = [_p, _p, _p, _p, _p, _p, _i64, _i64, _i64, _i32, _p, _p, _sz, _u32, _p]
+lib.fp4_gemm.restype = _i32
+lib.fp4_workspace_bytes.argtypes = [_i32, _i64, _i64, _i64, _i32, _u32]
+lib.fp4_workspace_bytes.restype = _sz
+lib.fp4_packed_bytes.argtypes = [_i64, _i64, _i32, _u32, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]
+lib.fp4_packed_bytes.restype = _i32
+lib.fp4_status_string.argtypes = [_i32]
+lib.fp4_status_string.restype = ctypes.c_char_p
+lib.fp4_version.restype = _i32
+
+
+class Fp4mrError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"fp4mr status {status}: {lib.fp4_status_string(status).decode()}")
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise Fp4mrError(status)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def packed_bytes(rows: int, K: int, fmt: int, flags: int = 0):
+    c, s = _sz(), _sz()
+    _check(lib.fp4_packed_bytes(rows, K, fmt, flags, ctypes.byref(c), ctypes.byref(s)))
+    return c.value, s.value
+
+
+def workspace_bytes(op: int, M: int, N: int, K: int, fmt: int, flags: int = 0) -> int:
+    return int(lib.fp4_workspace_bytes(op, M, N, K, fmt, flags))
+
+
+def _quantize(fn, op, x, had_block, fmt, flags, tensor_scale, codes, scales, workspace):
+    assert x.is_cuda and x.dim() == 2 and x.is_contiguous()
+    rows, K = x.shape
+    if x.dtype == torch.float32:
+        flags |= INPUT_F32
+    elif x.dtype != torch.bfloat16:
+        raise TypeError("x must be bfloat16 (or float32 with had_block=1)")
+    if codes is None or scales is None:
+        cb, sb = packed_bytes(rows, K, fmt, flags & LAYOUT_GEMM)
+        codes = torch.empty(cb, dtype=torch.uint8, device=x.device)
+        scales = torch.empty(sb, dtype=torch.uint8, device=x.device)
+    ts = None
+    if fmt == NVFP4:
+        if tensor_scale is not None:
+            flags |= STATIC_TENSOR_SCALE
+            ts = tensor_scale
+        else:
+            ts = torch.empty(1, dtype=torch.float32, device=x.device)
+    need = workspace_bytes(op, rows, 0, K, fmt, flags)
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    wsz = 0 if workspace is None else workspace.numel()
+    _check(fn(x.data_ptr(), rows, K, had_block, fmt, codes.data_ptr(), scales.data_ptr(), _ptr(ts), _ptr(workspace), wsz,
+              flags, _stream()))
+    return codes, scales, ts
+
+
+def fp4_rotate_quantize(x, had_block: int, fmt: int, *, flags: int = 0, tensor_scale=None, codes=None, scales=None,
+                        workspace=None):
+    """codes, scales, tensor_scale = Q(X H_b).  x: [M,K] bf16 cuda tensor (fp32 allowed with had_block=1).
+    With flags=LAYOUT_GEMM the outputs are in the opaque GEMM layout; else canonical flat byte tensors
+    (codes [M*K/2], scales [M*K/G])."""
+    return _quantize(lib.fp4_rotate_quantize, OP_ROTATE_QUANTIZE, x, had_block, fmt, flags, tensor_scale, codes, scales, workspace)
+
+
+def fp4_quantize_weights(w, had_block: int, fmt: int, *, flags: int = 0, tensor_scale=None, codes=None, scales=None,
+                         workspace=None):
+    """Offline RTN weight preparation, codes, scales, tensor_scale = Q(W H_b).  w: [N,K] bf16 cuda tensor."""
+    return _quantize(lib.fp4_quantize_weights, OP_QUANTIZE_WEIGHTS, w, had_block, fmt, flags, tensor_scale, codes, scales, workspace)
+
+
+def fp4_gemm(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M: int, N: int, K: int, fmt: int, *,
+             flags: int = 0, out=None, workspace=None):
+    """out[M,N] = Ahat @ What^T (bf16, or fp32 with OUT_F32).  Operand layouts per A_LAYOUT_GEMM / W_LAYOUT_GEMM."""
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32 if flags & OUT_F32 else torch.bfloat16, device=a_codes.device)
+    need = workspace_bytes(OP_GEMM, M, N, K, fmt, flags)
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=a_codes.device)
+    wsz = 0 if workspace is None else workspace.numel()
+    _check(lib.fp4_gemm(a_codes.data_ptr(), a_scales.data_ptr(), _ptr(a_tensor_scale), w_codes.data_ptr(), w_scales.data_ptr(),
+                        _ptr(w_tensor_scale), M, N, K, fmt, out.data_ptr(), _ptr(workspace), wsz, flags, _stream()))
+    return out
+
+
+def version() -> int:
+    return int(lib.fp4_version())

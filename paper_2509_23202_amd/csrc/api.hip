@@ -1,0 +1,179 @@
+// C ABI of libfp4mr.so: argument validation on the host, then dispatch to the kernel launchers.
+// Nothing here allocates, frees or keeps device memory.
+#include "../../include/fp4mr.h"
+
+#include <cstdlib>
+#include <cstring>
+
+#include "internal.hpp"
+#include "layout.hpp"
+
+using namespace fp4mr;
+
+namespace {
+
+constexpr uint32_t kQuantFlags = FP4MR_LAYOUT_GEMM | FP4MR_INPUT_F32 | FP4MR_STATIC_TENSOR_SCALE;
+constexpr uint32_t kGemmFlags = FP4MR_A_LAYOUT_GEMM | FP4MR_W_LAYOUT_GEMM | FP4MR_OUT_F32;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+bool env_flag(const char* name)
+{
+    const char* v = std::getenv(name);
+    return v && *v && std::strcmp(v, "0") != 0;
+}
+
+int env_int(const char* name, int dflt)
+{
+    const char* v = std::getenv(name);
+    return (v && *v) ? std::atoi(v) : dflt;
+}
+
+int group_of(fp4mr_fmt_t fmt) { return fmt == FP4MR_MXFP4 ? 32 : 16; }
+
+size_t quant_workspace(fp4mr_fmt_t fmt, uint32_t flags)
+{
+    return (fmt == FP4MR_NVFP4 && !(flags & FP4MR_STATIC_TENSOR_SCALE)) ? 256 : 0;
+}
+
+size_t repack_bytes(int64_t rows, int64_t K, fp4mr_fmt_t fmt)
+{
+    return align256((size_t)gemm_codes_bytes(rows, K)) + align256((size_t)gemm_scales_bytes(rows, K, (int)fmt));
+}
+
+fp4mr_status_t quantize_common(const void* x, int64_t rows, int64_t K, int had_block, fp4mr_fmt_t fmt, void* codes,
+                               void* scales, float* tensor_scale, void* workspace, size_t workspace_bytes,
+                               uint32_t flags, void* stream)
+{
+    if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return FP4MR_ERR_FMT;
+    if (flags & ~kQuantFlags) return FP4MR_ERR_FMT;
+    if (!x || !codes || !scales) return FP4MR_ERR_NULL;
+    if (fmt == FP4MR_NVFP4 && !tensor_scale) return FP4MR_ERR_NULL;
+    if (had_block != 1 && had_block != 16 && had_block != 32 && had_block != 64 && had_block != 128) return FP4MR_ERR_HAD_BLOCK;
+    if ((flags & FP4MR_INPUT_F32) && had_block != 1) return FP4MR_ERR_HAD_BLOCK;
+    if (rows <= 0 || K <= 0) return FP4MR_ERR_SHAPE;
+    const int G = group_of(fmt);
+    const int lcm = had_block > G ? had_block : G;  // both are powers of two
+    if (K % lcm != 0) return FP4MR_ERR_SHAPE;
+    if ((flags & FP4MR_LAYOUT_GEMM) && K % 128 != 0) return FP4MR_ERR_SHAPE;
+    if (rows > ((int64_t)1 << 40) / K) return FP4MR_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(codes) || !aligned16(scales)) return FP4MR_ERR_ALIGN;
+    const size_t need = quant_workspace(fmt, flags);
+    if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return FP4MR_ERR_WORKSPACE;
+
+    const hipError_t e = launch_rotate_quantize(x, rows, K, had_block, (int)fmt, (flags & FP4MR_INPUT_F32) != 0,
+                                                (flags & FP4MR_LAYOUT_GEMM) ? 1 : 0, (flags & FP4MR_STATIC_TENSOR_SCALE) != 0,
+                                                codes, scales, tensor_scale, workspace, !env_flag("FP4MR_SW_CODEC"),
+                                                static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
+}
+
+}  // namespace
+
+extern "C" {
+
+fp4mr_status_t fp4_rotate_quantize(const void* x, int64_t M, int64_t K, int had_block, fp4mr_fmt_t fmt, void* codes_out,
+                                   void* scales_out, float* tensor_scale, void* workspace, size_t workspace_bytes,
+                                   uint32_t flags, void* stream)
+{
+    return quantize_common(x, M, K, had_block, fmt, codes_out, scales_out, tensor_scale, workspace, workspace_bytes, flags, stream);
+}
+
+fp4mr_status_t fp4_quantize_weights(const void* w, int64_t N, int64_t K, int had_block, fp4mr_fmt_t fmt, void* codes_out,
+                                    void* scales_out, float* tensor_scale, void* workspace, size_t workspace_bytes,
+                                    uint32_t flags, void* stream)
+{
+    return quantize_common(w, N, K, had_block, fmt, codes_out, scales_out, tensor_scale, workspace, workspace_bytes, flags, stream);
+}
+
+fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* a_tensor_scale, const void* w_codes,
+                        const void* w_scales, const float* w_tensor_scale, int64_t M, int64_t N, int64_t K,
+                        fp4mr_fmt_t fmt, void* out, void* workspace, size_t workspace_bytes, uint32_t flags, void* stream)
+{
+    if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return FP4MR_ERR_FMT;
+    if (flags & ~kGemmFlags) return FP4MR_ERR_FMT;
+    if (!a_codes || !a_scales || !w_codes || !w_scales || !out) return FP4MR_ERR_NULL;
+    if (fmt == FP4MR_NVFP4 && (!a_tensor_scale || !w_tensor_scale)) return FP4MR_ERR_NULL;
+    if (M <= 0 || N <= 0 || K <= 0 || K % 128 != 0) return FP4MR_ERR_SHAPE;
+    if (M > (1 << 24) || N > (1 << 24) || K > (1 << 24)) return FP4MR_ERR_SHAPE;
+    if (!aligned16(a_codes) || !aligned16(a_scales) || !aligned16(w_codes) || !aligned16(w_scales) || !aligned16(out)) return FP4MR_ERR_ALIGN;
+    const size_t need = fp4_workspace_bytes(FP4MR_OP_GEMM, M, N, K, fmt, flags);
+    if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return FP4MR_ERR_WORKSPACE;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    hipError_t e;
+    if (!(flags & FP4MR_A_LAYOUT_GEMM)) {
+        void* c = ws;
+        void* s = ws + align256((size_t)gemm_codes_bytes(M, K));
+        if ((e = launch_repack_to_gemm(a_codes, a_scales, M, K, (int)fmt, c, s, st)) != hipSuccess) return FP4MR_ERR_DEVICE;
+        a_codes = c;
+        a_scales = s;
+        ws += repack_bytes(M, K, fmt);
+    }
+    if (!(flags & FP4MR_W_LAYOUT_GEMM)) {
+        void* c = ws;
+        void* s = ws + align256((size_t)gemm_codes_bytes(N, K));
+        if ((e = launch_repack_to_gemm(w_codes, w_scales, N, K, (int)fmt, c, s, st)) != hipSuccess) return FP4MR_ERR_DEVICE;
+        w_codes = c;
+        w_scales = s;
+    }
+    const bool out_f32 = (flags & FP4MR_OUT_F32) != 0;
+    if (fmt == FP4MR_MXFP4)
+        e = launch_gemm_mxfp4(a_codes, a_scales, w_codes, w_scales, M, N, K, out, out_f32, env_int("FP4MR_GEMM_VARIANT", 0), st);
+    else
+        e = launch_gemm_nvfp4(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M, N, K, out, out_f32,
+                              env_int("FP4MR_GEMM_VARIANT", 0), st);
+    return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
+}
+
+size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t fmt, uint32_t flags)
+{
+    if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return 0;
+    if (op == FP4MR_OP_ROTATE_QUANTIZE || op == FP4MR_OP_QUANTIZE_WEIGHTS) return quant_workspace(fmt, flags);
+    if (op == FP4MR_OP_GEMM) {
+        if (M <= 0 || N <= 0 || K <= 0 || K % 128 != 0) return 0;
+        size_t n = 0;
+        if (!(flags & FP4MR_A_LAYOUT_GEMM)) n += repack_bytes(M, K, fmt);
+        if (!(flags & FP4MR_W_LAYOUT_GEMM)) n += repack_bytes(N, K, fmt);
+        return n;
+    }
+    return 0;
+}
+
+fp4mr_status_t fp4_packed_bytes(int64_t rows, int64_t K, fp4mr_fmt_t fmt, uint32_t flags, size_t* codes_bytes, size_t* scales_bytes)
+{
+    if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return FP4MR_ERR_FMT;
+    if (!codes_bytes || !scales_bytes) return FP4MR_ERR_NULL;
+    const int G = group_of(fmt);
+    if (rows <= 0 || K <= 0 || K % G != 0) return FP4MR_ERR_SHAPE;
+    if (flags & FP4MR_LAYOUT_GEMM) {
+        if (K % 128 != 0) return FP4MR_ERR_SHAPE;
+        *codes_bytes = (size_t)gemm_codes_bytes(rows, K);
+        *scales_bytes = (size_t)gemm_scales_bytes(rows, K, (int)fmt);
+    } else {
+        *codes_bytes = (size_t)(rows * K / 2);
+        *scales_bytes = (size_t)(rows * K / G);
+    }
+    return FP4MR_OK;
+}
+
+const char* fp4_status_string(fp4mr_status_t s)
+{
+    switch (s) {
+        case FP4MR_OK: return "ok";
+        case FP4MR_ERR_NULL: return "a required pointer is NULL";
+        case FP4MR_ERR_SHAPE: return "bad shape: sizes must be positive and K a multiple of the group, the Hadamard block and (GEMM layout) 128";
+        case FP4MR_ERR_HAD_BLOCK: return "had_block must be 1, 16, 32, 64 or 128 (1 with fp32 input)";
+        case FP4MR_ERR_FMT: return "unknown format or flag bits";
+        case FP4MR_ERR_ALIGN: return "pointers must be 16-byte aligned";
+        case FP4MR_ERR_WORKSPACE: return "workspace missing, misaligned or smaller than fp4_workspace_bytes()";
+        case FP4MR_ERR_DEVICE: return "HIP runtime error at launch";
+    }
+    return "unknown status";
+}
+
+int fp4_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,317 @@
+// MXFP4 W4A4 GEMM on the CDNA4 block-scaled FP4 MFMA (arXiv 2509.23202, Section 4.2 item 2: the FP4 matmul
+// Q(W H) Q(X H)^T with hardware-applied group scales).
+//
+//   out[m,n] = sum_k  2^(sa[m,k/32]-127) * 2^(sw[n,k/32]-127) * a[m,k] * w[n,k]
+//
+// v_mfma_scale_f32_16x16x128_f8f6f4 multiplies a 16x128 by a 128x16 FP4 tile; every lane supplies 32 consecutive
+// K-elements of one row (16 bytes) and one E8M0 byte that scales exactly those 32 elements -- the MXFP4 group.
+// Both operands arrive in "GEMM layout": 1 KB fragments already in lane order (layout.hpp), so a fragment moves
+// global -> LDS with one 16-byte direct-to-LDS load per lane and LDS -> registers with one conflict-free
+// ds_read_b128 per lane; no re-layout pass runs between the quantizer and the GEMM.
+//
+// Roles are swapped on purpose: the W fragment is the MFMA's A operand (rows = n) and the X fragment its B
+// operand (columns = m).  A lane then owns four consecutive n of one m, i.e. one 8-byte bf16x4 store.
+//
+// Block tile BM x BN, K-step 128, STAGES-deep LDS ring fed by direct-to-LDS loads (tracked with vmcnt), one
+// barrier per K-step.  Scales take the same route (4-byte direct-to-LDS loads, two-deep ring), one dword per lane per
+// fragment row-block per 4 K-steps.
+#include "device_util.hpp"
+#include "internal.hpp"
+#include "layout.hpp"
+
+#include <type_traits>
+
+namespace fp4mr {
+namespace {
+
+struct GemmArgs {
+    const uint8_t* a_codes;
+    const uint8_t* a_scales;
+    const uint8_t* w_codes;
+    const uint8_t* w_scales;
+    void* out;
+    int64_t M, N, K;
+    int tiles_m, tiles_n;
+};
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);  // expcnt / lgkmcnt: no wait
+}
+
+// Barrier without the memory fence of __syncthreads(): a fence would make the compiler drain every outstanding
+// load (vmcnt(0)) and with it the whole prefetch ring.  The data hazards are handled explicitly instead: the
+// wait_vmcnt above it covers this wave's direct-to-LDS copies, the barrier publishes them to the other waves.
+__device__ __forceinline__ void block_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void global_void;
+
+__device__ __forceinline__ void load_frag_to_lds(const uint8_t* gsrc_lane, char* lds_frag_base)
+{
+    // 16 bytes per lane, written to lds_frag_base + 16 * lane
+    __builtin_amdgcn_global_load_lds((global_void*)gsrc_lane, (lds_void*)lds_frag_base, 16, 0, 0);
+}
+
+template <int OPSEL>
+__device__ __forceinline__ v4f mfma_fp4(const v4i& a, const v4i& b, const v4f& c, uint32_t sa, uint32_t sb)
+{
+    const v8i a8 = {a[0], a[1], a[2], a[3], 0, 0, 0, 0};
+    const v8i b8 = {b[0], b[1], b[2], b[3], 0, 0, 0, 0};
+    // cbsz = blgp = 4: both operands E2M1.  op_sel picks byte OPSEL of each scale register.
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, c, 4, 4, OPSEL, (int)sa, OPSEL, (int)sb);
+}
+
+__device__ __forceinline__ void remap_block(int bid, int nblocks, int tiles_m, int tiles_n, int& tm, int& tn)
+{
+    // Workgroups are dealt round-robin to the 8 XCDs.  Give every XCD one contiguous range of logical tile
+    // ids, and order logical ids in bands of GM tile-rows, so the tiles that share an L2 share operands.
+    const int per = nblocks >> 3, rem = nblocks & 7;
+    const int xcd = bid & 7, idx = bid >> 3;
+    const int L = (xcd < rem) ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
+    constexpr int GM = 4;
+    const int band = GM * tiles_n;
+    const int gidx = L / band;
+    const int first_m = gidx * GM;
+    const int gsz = min(tiles_m - first_m, GM);
+    const int in_band = L - gidx * band;
+    tm = first_m + in_band % gsz;
+    tn = in_band / gsz;
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES, bool OUT_F32>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(GemmArgs g)
+{
+    constexpr int NWM = BM / WM, NWN = BN / WN, NW = NWM * NWN;
+    constexpr int FX = BM / 16, FW = BN / 16, F = FX + FW;  // fragments per stage
+    constexpr int LPW = (F + NW - 1) / NW;                  // fragment loads per wave per stage
+    constexpr int TM = WM / 16, TN = WN / 16;               // MFMA tiles per wave
+    constexpr int STAGE_BYTES = F * 1024;
+    static_assert(STAGES >= 2 && STAGES <= 5, "scale prefetch distance assumes at most 5 stages");
+
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int wm = wave % NWM, wn = wave / NWM;
+
+    int tm, tn;
+    remap_block(blockIdx.x, g.tiles_m * g.tiles_n, g.tiles_m, g.tiles_n, tm, tn);
+
+    const int64_t KC = g.K >> 7;            // K-steps
+    const int64_t KS = (g.K + 511) >> 9;    // scale super-steps
+    const int KT = (int)KC;
+    const int64_t rbx_max = (g.M + 15) / 16 - 1, rbw_max = (g.N + 15) / 16 - 1;
+
+    // global source of each fragment this wave copies (row-block clamped to the operand; clamped duplicates only
+    // feed output rows/columns that are never stored)
+    const uint8_t* gsrc[LPW];
+    int lds_off[LPW];
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+        // every wave issues exactly LPW loads per stage so that the vmcnt bookkeeping is uniform; when F is not
+        // a multiple of NW the spare slots re-copy the last fragment (same bytes to the same place)
+        const int f = min(wave + i * NW, F - 1);
+        if (f < FX) {
+            int64_t rb = (int64_t)tm * FX + f;
+            rb = rb > rbx_max ? rbx_max : rb;
+            gsrc[i] = g.a_codes + rb * KC * 1024 + lane * 16;
+        } else {
+            int64_t rb = (int64_t)tn * FW + (f - FX);
+            rb = rb > rbw_max ? rbw_max : rb;
+            gsrc[i] = g.w_codes + rb * KC * 1024 + lane * 16;
+        }
+        lds_off[i] = f * 1024;
+    }
+    // Scales: every (row-block, 4 K-steps) owns 256 bytes = one dword per lane.  They travel global -> LDS with
+    // 4-byte direct-to-LDS loads into a two-deep ring (so no VGPR is ever the target of an in-flight load inside
+    // the main loop) and are read back once per 4 K-steps.
+    constexpr int NS = (F + NW - 1) / NW;                   // scale-block loads per wave per batch
+    constexpr int SCALE_BYTES = F * 256;
+    char* const scale_ring = smem + STAGES * STAGE_BYTES;
+    const uint8_t* ssrc[NS];
+    int slds_off[NS];
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        const int f = min(wave + i * NW, F - 1);
+        if (f < FX) {
+            int64_t rb = (int64_t)tm * FX + f;
+            rb = rb > rbx_max ? rbx_max : rb;
+            ssrc[i] = g.a_scales + rb * KS * 256 + lane * 4;
+        } else {
+            int64_t rb = (int64_t)tn * FW + (f - FX);
+            rb = rb > rbw_max ? rbw_max : rb;
+            ssrc[i] = g.w_scales + rb * KS * 256 + lane * 4;
+        }
+        slds_off[i] = f * 256;
+    }
+
+    v4f acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    uint32_t sx[TM], sw[TN];
+
+    auto issue_scales = [&](int64_t ss) {
+        char* base = scale_ring + (ss & 1) * SCALE_BYTES;
+        ss = ss < KS ? ss : KS - 1;  // the batch past the end re-reads the last one: keeps the load count uniform
+#pragma unroll
+        for (int i = 0; i < NS; ++i)
+            __builtin_amdgcn_global_load_lds((global_void*)(ssrc[i] + ss * 256), (lds_void*)(base + slds_off[i]), 4, 0, 0);
+    };
+    auto read_scales = [&](int64_t ss) {
+        const char* base = scale_ring + (ss & 1) * SCALE_BYTES;
+#pragma unroll
+        for (int j = 0; j < TM; ++j) sx[j] = *(reinterpret_cast<const uint32_t*>(base + (wm * TM + j) * 256) + lane);
+#pragma unroll
+        for (int i = 0; i < TN; ++i) sw[i] = *(reinterpret_cast<const uint32_t*>(base + (FX + wn * TN + i) * 256) + lane);
+    };
+    auto issue_frags = [&](int kt) {
+        char* base = smem + (kt % STAGES) * STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) load_frag_to_lds(gsrc[i] + (int64_t)kt * 1024, base + lds_off[i]);
+    };
+
+    // prologue: scales of super-step 0, then the first STAGES-1 stages
+    issue_scales(0);
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+        if (s < KT) issue_frags(s);
+
+    auto compute = [&](int kt, auto opsel_tag) {
+        constexpr int OPSEL = decltype(opsel_tag)::value;
+        const char* base = smem + (kt % STAGES) * STAGE_BYTES;
+        v4i xf[TM];
+#pragma unroll
+        for (int j = 0; j < TM; ++j) xf[j] = *(reinterpret_cast<const v4i*>(base + (wm * TM + j) * 1024) + lane);
+#pragma unroll
+        for (int i = 0; i < TN; ++i) {
+            const v4i wf = *(reinterpret_cast<const v4i*>(base + (FX + wn * TN + i) * 1024) + lane);
+#pragma unroll
+            for (int j = 0; j < TM; ++j) acc[i][j] = mfma_fp4<OPSEL>(wf, xf[j], acc[i][j], sw[i], sx[j]);
+        }
+    };
+
+    // Number of loads allowed to be still in flight when stage kt must have landed: the STAGES-2 later stages,
+    // plus one scale batch when it was issued after stage kt's loads (j = kt % 4; batches go out at j == 0,
+    // ahead of that iteration's fragment loads).
+    auto step = [&](int kt, auto jtag) {
+        constexpr int J = decltype(jtag)::value;
+        constexpr bool batch_after = (STAGES >= 3) && ((J >= 1 && J <= STAGES - 2));
+        constexpr int ALLOWED = (STAGES - 2) * LPW + (batch_after ? NS : 0);
+        if (kt + STAGES - 2 < KT) wait_vmcnt<ALLOWED>(); else wait_vmcnt<0>();
+        block_barrier();
+        if constexpr (J == 0) {
+            read_scales(kt >> 2);
+            issue_scales((kt >> 2) + 1);
+        }
+        if (kt + STAGES - 1 < KT) issue_frags(kt + STAGES - 1);
+        compute(kt, jtag);
+    };
+
+    for (int kt0 = 0; kt0 < KT; kt0 += 4) {
+        step(kt0, std::integral_constant<int, 0>{});
+        if (kt0 + 1 < KT) step(kt0 + 1, std::integral_constant<int, 1>{});
+        if (kt0 + 2 < KT) step(kt0 + 2, std::integral_constant<int, 2>{});
+        if (kt0 + 3 < KT) step(kt0 + 3, std::integral_constant<int, 3>{});
+    }
+    wait_vmcnt<0>();  // the clamped last scale batch
+
+    // epilogue: lane owns out[m][n..n+3], m = m0 + 16*j + lane%16, n = n0 + 16*i + 4*(lane/16)
+    const int64_t m_base = (int64_t)tm * BM + wm * WM + (lane & 15);
+    const int64_t n_base = (int64_t)tn * BN + wn * WN + (lane >> 4) * 4;
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+        const int64_t m = m_base + 16 * j;
+        if (m >= g.M) continue;
+#pragma unroll
+        for (int i = 0; i < TN; ++i) {
+            const int64_t n = n_base + 16 * i;
+            if (n >= g.N) continue;
+            const v4f v = acc[i][j];
+            if constexpr (OUT_F32) {
+                float* o = static_cast<float*>(g.out) + m * g.N + n;
+                if (n + 3 < g.N && (g.N & 3) == 0) {
+                    *reinterpret_cast<float4*>(o) = make_float4(v[0], v[1], v[2], v[3]);
+                } else {
+                    for (int e = 0; e < 4; ++e)
+                        if (n + e < g.N) o[e] = v[e];
+                }
+            } else {
+                __bf16* o = static_cast<__bf16*>(g.out) + m * g.N + n;
+                typedef __bf16 v4bf __attribute__((ext_vector_type(4)));
+                if (n + 3 < g.N && (g.N & 3) == 0) {
+                    v4bf p = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3]};
+                    *reinterpret_cast<v4bf*>(o) = p;
+                } else {
+                    for (int e = 0; e < 4; ++e)
+                        if (n + e < g.N) o[e] = (__bf16)v[e];
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES>
+hipError_t launch_variant(const GemmArgs& g0, bool out_f32, hipStream_t st)
+{
+    GemmArgs g = g0;
+    g.tiles_m = (int)((g.M + BM - 1) / BM);
+    g.tiles_n = (int)((g.N + BN - 1) / BN);
+    constexpr int threads = (BM / WM) * (BN / WN) * 64;
+    constexpr size_t lds = (size_t)STAGES * (BM + BN) / 16 * 1024 + 2 * (size_t)(BM + BN) / 16 * 256;
+    const dim3 grid((unsigned)(g.tiles_m * g.tiles_n));
+    hipError_t e;
+    if (out_f32) {
+        auto k = gemm_mx_kernel<BM, BN, WM, WN, STAGES, true>;
+        if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess) return e;
+        hipLaunchKernelGGL(k, grid, dim3(threads), lds, st, g);
+    } else {
+        auto k = gemm_mx_kernel<BM, BN, WM, WN, STAGES, false>;
+        if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess) return e;
+        hipLaunchKernelGGL(k, grid, dim3(threads), lds, st, g);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// variant: 0 = pick by shape; 1.. = force a tile configuration (used by the benchmark's sweep)
+hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const void* w_codes, const void* w_scales,
+                             int64_t M, int64_t N, int64_t K, void* out, bool out_f32, int variant, hipStream_t st)
+{
+    GemmArgs g{};
+    g.a_codes = static_cast<const uint8_t*>(a_codes);
+    g.a_scales = static_cast<const uint8_t*>(a_scales);
+    g.w_codes = static_cast<const uint8_t*>(w_codes);
+    g.w_scales = static_cast<const uint8_t*>(w_scales);
+    g.out = out;
+    g.M = M;
+    g.N = N;
+    g.K = K;
+    if (variant == 0) {
+        if (M <= 16) variant = 4;
+        else if (M <= 64) variant = 3;
+        else if (M <= 1024 || N < 2048) variant = 2;
+        else variant = 1;
+    }
+    switch (variant) {
+        case 1: return launch_variant<256, 256, 128, 128, 4>(g, out_f32, st);
+        case 2: return launch_variant<128, 128, 64, 64, 4>(g, out_f32, st);
+        case 3: return launch_variant<64, 256, 64, 64, 4>(g, out_f32, st);
+        case 4: return launch_variant<16, 256, 16, 64, 4>(g, out_f32, st);
+        case 5: return launch_variant<256, 256, 128, 64, 3>(g, out_f32, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace fp4mr

@@ -1,0 +1,27 @@
+// Host-side launchers behind the C ABI (one per kernel family).  All pointers are device pointers that the
+// C-ABI layer has already validated.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace fp4mr {
+
+hipError_t launch_rotate_quantize(const void* x, int64_t rows, int64_t K, int b, int fmt, bool in_f32,
+                                  int layout_gemm, bool static_scale, void* codes, void* scales,
+                                  float* tensor_scale, void* workspace, bool hw_codec, hipStream_t st);
+
+// canonical -> GEMM layout copy of one quantized operand (codes and scales)
+hipError_t launch_repack_to_gemm(const void* codes, const void* scales, int64_t rows, int64_t K, int fmt,
+                                 void* codes_gemm, void* scales_gemm, hipStream_t st);
+
+// both operands in GEMM layout
+hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const void* w_codes, const void* w_scales,
+                             int64_t M, int64_t N, int64_t K, void* out, bool out_f32, int variant, hipStream_t st);
+
+hipError_t launch_gemm_nvfp4(const void* a_codes, const void* a_scales, const float* a_ts, const void* w_codes,
+                             const void* w_scales, const float* w_ts, int64_t M, int64_t N, int64_t K, void* out,
+                             bool out_f32, int variant, hipStream_t st);
+
+}  // namespace fp4mr

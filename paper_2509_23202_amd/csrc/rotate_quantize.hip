@@ -1,0 +1,458 @@
+// Fused block-Hadamard rotation + FP4 microscaling quantization (arXiv 2509.23202, Section 4.2 item 1:
+// online rotation X H_k with k in {16,32,64,128}, quantization and scale computation fused behind it).
+//
+// Design for gfx950.  The rotation is a small dense contraction y = x H_b over blocks of b elements; it runs
+// on the bf16 MFMA (v_mfma_f32_16x16x32_bf16) with the +-1 Hadamard matrix held in registers as the A operand
+// and 16 independent b-element vectors of the input as the B operand, loaded straight from global memory
+// with one 16-byte load per lane (lane l: vector l%16, elements 8*(l/16)..+8 of a 32-element K-step).  The
+// products are exact (+-x), accumulation is fp32.  Rows of the A operand are permuted so that every lane ends
+// up with b'/4 CONSECUTIVE outputs of its vector, i.e. whole dwords of packed codes.  What remains for the
+// vector ALU is |max|, two multiplies and the hardware FP4 pack per element, which keeps the kernel bound by
+// HBM and not by VALU issue (a butterfly in registers costs about 10 VALU operations per element).
+//
+//   b' = max(b, 32).  b = 16 uses b' = 32 with the block-diagonal matrix diag(H_16, H_16).
+//   lane (g = l%16, q = l/16) of a "supertile" owns outputs [q*b'/4, (q+1)*b'/4) of vector g.
+//
+// Normalisation 1/sqrt(b) is applied in fp32 after the contraction as y = fma(h, c_hi, h*c_lo) with
+// c_hi + c_lo = 1/sqrt(b) to ~48 bits, so y is (almost always) the correctly rounded product.
+#include "device_util.hpp"
+#include "internal.hpp"
+#include "layout.hpp"
+
+namespace fp4mr {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWavesPerBlock = kThreads / kWave;
+
+struct RqArgs {
+    const void* x;
+    uint8_t* codes;
+    uint8_t* scales;
+    float* tensor_scale;   // NVFP4: s_T (written by the quantize pass unless static)
+    uint32_t* amax_bits;   // NVFP4 dynamic: bit pattern of max |y| over the tensor (workspace)
+    int64_t rows, K;
+    int64_t n_items;
+    int b;                 // Hadamard block (1 = none)
+    float c_hi, c_lo;      // 1/sqrt(b) split in two floats
+    int static_scale;
+};
+
+template <int LAYOUT>
+__device__ __forceinline__ int64_t codes_offset_gemm(int64_t row, int64_t k, int64_t KC)
+{
+    return ((row >> 4) * KC + (k >> 7)) * 1024 + ((((k & 127) >> 5) * 16 + (row & 15)) << 4) + ((k & 31) >> 1);
+}
+
+__device__ __forceinline__ int64_t mx_scale_offset_gemm(int64_t row, int64_t kg, int64_t KS)
+{
+    return ((((row >> 4) * KS + (kg >> 4)) * 64 + ((kg & 3) * 16 + (row & 15))) << 2) + ((kg >> 2) & 3);
+}
+
+__device__ __forceinline__ int64_t nv_scale_offset_gemm(int64_t row, int64_t g16, int64_t KC)
+{
+    return ((((row >> 4) * KC + (g16 >> 3)) * 64 + (((g16 & 7) >> 1) * 16 + (row & 15))) << 1) + (g16 & 1);
+}
+
+// ------------------------------------------------------------------------------------------------------
+// Quantize NO consecutive fp32 values held by one lane (NO in {8,16,32}) whose group of G elements spans LG
+// lanes (lanes differ in bits 4/5 of the lane id for the MFMA kernel, bits 0/1 for the direct kernel).
+// XOR_LO is the lane-id distance of the first partner.
+template <int G, int NO, int XOR_LO, bool HW>
+struct GroupQuant {
+    static constexpr int LG = (G > NO) ? G / NO : 1;   // lanes per group
+    static constexpr int NG = (NO > G) ? NO / G : 1;   // groups per lane
+    static constexpr int VG = NO / NG;                 // values per lane per group
+    static constexpr int ND = NO / 8;                  // dwords of codes per lane
+
+    // MXFP4: returns scale bytes in sc[NG], codes in out[ND]
+    __device__ static __forceinline__ void mx(const float (&y)[NO], uint32_t (&out)[ND], uint32_t (&sc)[NG])
+    {
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) {
+            float amax = 0.0f;
+#pragma unroll
+            for (int i = 0; i < VG; ++i) amax = fabs_max(amax, y[gi * VG + i]);
+            if constexpr (LG >= 2) amax = fmaxf(amax, __shfl_xor(amax, XOR_LO));
+            if constexpr (LG >= 4) amax = fmaxf(amax, __shfl_xor(amax, XOR_LO * 2));
+            // OCP MX: shared exponent = floor(log2 amax) - 2 -> biased byte = exponent field - 2, clamped at 0
+            const int ef = (int)((__float_as_uint(amax) >> 23) & 0xffu);
+            const uint32_t byte = (uint32_t)max(ef - 2, 0);
+            sc[gi] = byte;
+            const float inv = __uint_as_float((254u - byte) << 23);  // 2^(127 - byte), always a normal number
+#pragma unroll
+            for (int d = 0; d < VG / 8; ++d) {
+                float t[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) t[i] = y[gi * VG + d * 8 + i] * inv;
+                out[gi * (VG / 8) + d] = e2m1_pack8<HW>(t);
+            }
+        }
+    }
+
+    // NVFP4 with tensor scale s_T
+    __device__ static __forceinline__ void nv(const float (&y)[NO], float s_T, uint32_t (&out)[ND], uint32_t (&sc)[NG])
+    {
+        const float six_sT = 6.0f * s_T;
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) {
+            float amax = 0.0f;
+#pragma unroll
+            for (int i = 0; i < VG; ++i) amax = fabs_max(amax, y[gi * VG + i]);
+            if constexpr (LG >= 2) amax = fmaxf(amax, __shfl_xor(amax, XOR_LO));
+            if constexpr (LG >= 4) amax = fmaxf(amax, __shfl_xor(amax, XOR_LO * 2));
+            uint32_t c = 0;
+            if (s_T > 0.0f) c = e4m3_encode<HW>(__fdiv_rn(amax, six_sT));
+            sc[gi] = c;
+            const float d = s_T * e4m3_decode<HW>(c);
+            const float r = (d == 0.0f) ? 0.0f : __fdiv_rn(1.0f, d);
+#pragma unroll
+            for (int dd = 0; dd < VG / 8; ++dd) {
+                float t[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) t[i] = y[gi * VG + dd * 8 + i] * r;
+                uint32_t p = e2m1_pack8<HW>(t);
+                out[gi * (VG / 8) + dd] = (d == 0.0f) ? 0u : p;
+            }
+        }
+    }
+};
+
+template <int ND>
+__device__ __forceinline__ void store_codes(uint8_t* p, const uint32_t (&w)[ND])
+{
+    if constexpr (ND == 1) {
+        *reinterpret_cast<uint32_t*>(p) = w[0];
+    } else if constexpr (ND == 2) {
+        *reinterpret_cast<uint2*>(p) = make_uint2(w[0], w[1]);
+    } else {
+        *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------
+// MFMA rotation kernel.  BP = b' in {32,64,128}; G = 32 (MXFP4) or 16 (NVFP4); LAYOUT 0 canonical / 1 GEMM;
+// PASS 0 = quantize, 1 = tensor abs-max only (NVFP4 pre-pass).
+//
+// Work item = FR * (128/BP) supertiles = FR * 2048 elements.
+//   canonical: supertiles are consecutive runs of 16 vectors in flat (row-major) order;
+//   GEMM:      an item is FR fragments (16 rows x 128 K); supertile u covers K-offset u*BP of all 16 rows.
+template <int BP, int G, int LAYOUT, int PASS, bool HW, int FR>
+__global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
+{
+    constexpr int S = BP / 32;           // K-steps of the contraction
+    constexpr int T = BP / 16;           // output tiles
+    constexpr int NO = BP / 4;           // outputs per lane
+    constexpr int NST = FR * (128 / BP); // supertiles per item
+    using GQ = GroupQuant<G, NO, 16, HW>;
+
+    const int lane = threadIdx.x & 63;
+    const int g = lane & 15, q = lane >> 4;
+    const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    const int64_t n_waves = (int64_t)gridDim.x * kWavesPerBlock;
+
+    // Hadamard operand: A[i][k] = H[32s + k][c(t,i)],  c(t,i) = (i/4)*NO + 4t + i%4,  lane holds i = g, k = 8q..8q+7.
+    v8bf hop[T][S];
+    {
+        const int bm = a.b - 1;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int c = (g >> 2) * NO + 4 * t + (g & 3);
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                typedef unsigned short v8us __attribute__((ext_vector_type(8)));
+                v8us bits;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int r = 32 * s + 8 * q + e;
+                    const bool same = (r & ~bm) == (c & ~bm);
+                    const unsigned sgn = __popc((unsigned)(r & c & bm)) & 1u;
+                    bits[e] = same ? (unsigned short)(0x3f80u | (sgn << 15)) : (unsigned short)0;
+                }
+                hop[t][s] = __builtin_bit_cast(v8bf, bits);
+            }
+        }
+    }
+
+    const int64_t NV = a.rows * a.K / BP;  // vectors in the tensor
+    const int64_t KC = a.K >> 7;
+    const int64_t KS = (a.K + 511) >> 9;
+    const uint16_t* __restrict__ x = static_cast<const uint16_t*>(a.x);
+
+    float s_T = 0.0f;
+    if constexpr (G == 16 && PASS == 0) {
+        s_T = a.static_scale ? *a.tensor_scale : __fdiv_rn(__uint_as_float(*a.amax_bits), 2688.0f);
+        if (!a.static_scale && blockIdx.x == 0 && threadIdx.x == 0) *a.tensor_scale = s_T;
+    }
+    float hmax = 0.0f;
+
+    for (int64_t item = wave; item < a.n_items; item += n_waves) {
+        int64_t ebase[NST];
+        int64_t row[NST], k0[NST];
+        bool valid[NST];
+        v4i xin[NST][S];
+#pragma unroll
+        for (int u = 0; u < NST; ++u) {
+            if constexpr (LAYOUT == 0) {
+                const int64_t v = (item * NST + u) * 16 + g;
+                valid[u] = v < NV;
+                ebase[u] = v * BP;
+                row[u] = 0;
+                k0[u] = 0;
+            } else {
+                const int64_t f = item * FR + u / (128 / BP);
+                const int64_t rb = f / KC, kc = f - rb * KC;
+                row[u] = rb * 16 + g;
+                k0[u] = kc * 128 + (u % (128 / BP)) * BP;
+                valid[u] = row[u] < a.rows && rb * 16 < round_up(a.rows, 16);
+                ebase[u] = row[u] * a.K + k0[u];
+            }
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                v4i z = {0, 0, 0, 0};
+                xin[u][s] = valid[u] ? *reinterpret_cast<const v4i*>(x + ebase[u] + 32 * s + 8 * q) : z;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < NST; ++u) {
+            v4f acc[T];
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                acc[t] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < S; ++s)
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hop[t][s], __builtin_bit_cast(v8bf, xin[u][s]), acc[t], 0, 0, 0);
+            }
+            if constexpr (PASS == 1) {
+#pragma unroll
+                for (int t = 0; t < T; ++t)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) hmax = fabs_max(hmax, acc[t][v]);
+                continue;
+            }
+            float y[NO];
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float h = acc[t][v];
+                    y[4 * t + v] = __fmaf_rn(h, a.c_hi, h * a.c_lo);
+                }
+            uint32_t out[GQ::ND], sc[GQ::NG];
+            if constexpr (G == 32) GQ::mx(y, out, sc); else GQ::nv(y, s_T, out, sc);
+
+            if constexpr (LAYOUT == 0) {
+                if (valid[u]) {
+                    const int64_t e0 = ebase[u] + q * NO;
+                    store_codes<GQ::ND>(a.codes + (e0 >> 1), out);
+                    if ((q % GQ::LG) == 0) {
+#pragma unroll
+                        for (int gi = 0; gi < GQ::NG; ++gi) a.scales[e0 / G + gi] = (uint8_t)sc[gi];
+                    }
+                }
+            } else {
+                // padded rows are written too (zeros come out of zero inputs), the buffers include the padding
+                const int64_t kk = k0[u] + q * NO;
+                store_codes<GQ::ND>(a.codes + codes_offset_gemm<1>(row[u], kk, KC), out);
+                if ((q % GQ::LG) == 0) {
+#pragma unroll
+                    for (int gi = 0; gi < GQ::NG; ++gi) {
+                        if constexpr (G == 32) a.scales[mx_scale_offset_gemm(row[u], (kk >> 5) + gi, KS)] = (uint8_t)sc[gi];
+                        else a.scales[nv_scale_offset_gemm(row[u], (kk >> 4) + gi, KC)] = (uint8_t)sc[gi];
+                    }
+                }
+            }
+        }
+    }
+    if constexpr (PASS == 1) {
+        // wave max -> one atomic per wave.  max is order-independent, so the result is deterministic.
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) hmax = fmaxf(hmax, __shfl_xor(hmax, m));
+        if (lane == 0) {
+            const float ymax = __fmaf_rn(hmax, a.c_hi, hmax * a.c_lo);  // monotone: max|y| = y(max|h|)
+            atomicMax(a.amax_bits, __float_as_uint(ymax));
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------
+// No-rotation kernel (had_block = 1), bf16 or fp32 input.  Lane handles 8 consecutive elements; a group of G
+// spans G/8 adjacent lanes.  Work item = 2048 elements (256 lane-pieces, 4 per lane).
+//   canonical: flat;   GEMM: item = fragment, piece p = j*64+lane: row = p/16, K-offset 8*(p%16).
+template <typename TIN, int G, int LAYOUT, int PASS, bool HW>
+__global__ __launch_bounds__(kThreads) void q_direct_kernel(RqArgs a)
+{
+    using GQ = GroupQuant<G, 8, 1, HW>;
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    const int64_t n_waves = (int64_t)gridDim.x * kWavesPerBlock;
+    const int64_t total = a.rows * a.K;
+    const int64_t KC = a.K >> 7;
+    const int64_t KS = (a.K + 511) >> 9;
+    const TIN* __restrict__ x = static_cast<const TIN*>(a.x);
+
+    float s_T = 0.0f;
+    if constexpr (G == 16 && PASS == 0) {
+        s_T = a.static_scale ? *a.tensor_scale : __fdiv_rn(__uint_as_float(*a.amax_bits), 2688.0f);
+        if (!a.static_scale && blockIdx.x == 0 && threadIdx.x == 0) *a.tensor_scale = s_T;
+    }
+    float hmax = 0.0f;
+
+    for (int64_t item = wave; item < a.n_items; item += n_waves) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int p = j * 64 + lane;
+            int64_t e0, row = 0, kk = 0;
+            bool valid;
+            if constexpr (LAYOUT == 0) {
+                e0 = item * 2048 + (int64_t)p * 8;
+                valid = e0 < total;
+            } else {
+                const int64_t rb = item / KC, kc = item - rb * KC;
+                row = rb * 16 + (p >> 4);
+                kk = kc * 128 + (p & 15) * 8;
+                valid = row < a.rows;
+                e0 = row * a.K + kk;
+            }
+            float y[8];
+            if (valid) {
+                if constexpr (sizeof(TIN) == 2) {
+                    const uint4 w = *reinterpret_cast<const uint4*>(x + e0);
+                    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        y[2 * i] = __uint_as_float(ww[i] << 16);
+                        y[2 * i + 1] = __uint_as_float(ww[i] & 0xffff0000u);
+                    }
+                } else {
+                    const float4 f0 = *reinterpret_cast<const float4*>(x + e0);
+                    const float4 f1 = *reinterpret_cast<const float4*>(x + e0 + 4);
+                    y[0] = f0.x; y[1] = f0.y; y[2] = f0.z; y[3] = f0.w;
+                    y[4] = f1.x; y[5] = f1.y; y[6] = f1.z; y[7] = f1.w;
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) y[i] = 0.0f;
+            }
+            if constexpr (PASS == 1) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) hmax = fabs_max(hmax, y[i]);
+                continue;
+            }
+            uint32_t out[1], sc[1];
+            if constexpr (G == 32) GQ::mx(y, out, sc); else GQ::nv(y, s_T, out, sc);
+            if constexpr (LAYOUT == 0) {
+                if (valid) {
+                    *reinterpret_cast<uint32_t*>(a.codes + (e0 >> 1)) = out[0];
+                    if ((lane % GQ::LG) == 0) a.scales[e0 / G] = (uint8_t)sc[0];
+                }
+            } else {
+                *reinterpret_cast<uint32_t*>(a.codes + codes_offset_gemm<1>(row, kk, KC)) = out[0];
+                if ((lane % GQ::LG) == 0) {
+                    if constexpr (G == 32) a.scales[mx_scale_offset_gemm(row, kk >> 5, KS)] = (uint8_t)sc[0];
+                    else a.scales[nv_scale_offset_gemm(row, kk >> 4, KC)] = (uint8_t)sc[0];
+                }
+            }
+        }
+    }
+    if constexpr (PASS == 1) {
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) hmax = fmaxf(hmax, __shfl_xor(hmax, m));
+        if (lane == 0) atomicMax(a.amax_bits, __float_as_uint(hmax));
+    }
+}
+
+__global__ void fill_u32_kernel(uint32_t* p, uint32_t v) { *p = v; }
+
+// ------------------------------------------------------------------------------------------------------
+template <int BP, int G, int LAYOUT, int PASS, bool HW>
+hipError_t launch_mfma(const RqArgs& a0, int grid_cap, hipStream_t st)
+{
+    constexpr int FR = (BP == 128) ? 2 : 1;
+    RqArgs a = a0;
+    if (LAYOUT == 0) {
+        const int64_t nv = a.rows * a.K / BP;
+        const int64_t nst = (nv + 15) / 16;
+        a.n_items = (nst + FR * (128 / BP) - 1) / (FR * (128 / BP));
+    } else {
+        const int64_t nf = round_up(a.rows, 16) / 16 * (a.K / 128);
+        a.n_items = (nf + FR - 1) / FR;
+        // FR > 1 in GEMM layout may run one fragment past the end; keep FR = 1 there (see dispatch below)
+    }
+    int64_t blocks = (a.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks > grid_cap) blocks = grid_cap;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL((rq_mfma_kernel<BP, G, LAYOUT, PASS, HW, (LAYOUT == 0 ? FR : 1)>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
+    return hipGetLastError();
+}
+
+template <typename TIN, int G, int LAYOUT, int PASS, bool HW>
+hipError_t launch_direct(const RqArgs& a0, int grid_cap, hipStream_t st)
+{
+    RqArgs a = a0;
+    if (LAYOUT == 0) a.n_items = (a.rows * a.K + 2047) / 2048;
+    else a.n_items = round_up(a.rows, 16) / 16 * (a.K / 128);
+    int64_t blocks = (a.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks > grid_cap) blocks = grid_cap;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL((q_direct_kernel<TIN, G, LAYOUT, PASS, HW>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
+    return hipGetLastError();
+}
+
+template <int G, int LAYOUT, int PASS, bool HW>
+hipError_t dispatch_block(const RqArgs& a, bool in_f32, int grid_cap, hipStream_t st)
+{
+    if (a.b == 1) {
+        if (in_f32) return launch_direct<float, G, LAYOUT, PASS, HW>(a, grid_cap, st);
+        return launch_direct<uint16_t, G, LAYOUT, PASS, HW>(a, grid_cap, st);
+    }
+    if (a.b <= 32) return launch_mfma<32, G, LAYOUT, PASS, HW>(a, grid_cap, st);
+    if (a.b == 64) return launch_mfma<64, G, LAYOUT, PASS, HW>(a, grid_cap, st);
+    return launch_mfma<128, G, LAYOUT, PASS, HW>(a, grid_cap, st);
+}
+
+template <int G, bool HW>
+hipError_t dispatch_layout_pass(const RqArgs& a, bool in_f32, int layout, int pass, int grid_cap, hipStream_t st)
+{
+    if (pass == 1) return dispatch_block<G, 0, 1, HW>(a, in_f32, grid_cap, st);  // layout irrelevant for the abs-max pass
+    if (layout == 0) return dispatch_block<G, 0, 0, HW>(a, in_f32, grid_cap, st);
+    return dispatch_block<G, 1, 0, HW>(a, in_f32, grid_cap, st);
+}
+
+}  // namespace
+
+hipError_t launch_rotate_quantize(const void* x, int64_t rows, int64_t K, int b, int fmt, bool in_f32,
+                                  int layout_gemm, bool static_scale, void* codes, void* scales,
+                                  float* tensor_scale, void* workspace, bool hw_codec, hipStream_t st)
+{
+    RqArgs a{};
+    a.x = x;
+    a.codes = static_cast<uint8_t*>(codes);
+    a.scales = static_cast<uint8_t*>(scales);
+    a.tensor_scale = tensor_scale;
+    a.amax_bits = static_cast<uint32_t*>(workspace);
+    a.rows = rows;
+    a.K = K;
+    a.b = b;
+    const double c = 1.0 / sqrt((double)b);
+    a.c_hi = (float)c;
+    a.c_lo = (float)(c - (double)a.c_hi);
+    a.static_scale = static_scale ? 1 : 0;
+    const int grid_cap = 256 * 8;  // 256 CUs, up to 8 blocks of 4 waves each
+
+    hipError_t e;
+    if (fmt == 1 && !static_scale) {
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(1), 0, st, a.amax_bits, 0u);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        e = hw_codec ? dispatch_layout_pass<16, true>(a, in_f32, 0, 1, grid_cap, st)
+                     : dispatch_layout_pass<16, false>(a, in_f32, 0, 1, grid_cap, st);
+        if (e != hipSuccess) return e;
+    }
+    if (fmt == 0)
+        return hw_codec ? dispatch_layout_pass<32, true>(a, in_f32, layout_gemm, 0, grid_cap, st)
+                        : dispatch_layout_pass<32, false>(a, in_f32, layout_gemm, 0, grid_cap, st);
+    return hw_codec ? dispatch_layout_pass<16, true>(a, in_f32, layout_gemm, 0, grid_cap, st)
+                    : dispatch_layout_pass<16, false>(a, in_f32, layout_gemm, 0, grid_cap, st);
+}
+
+}  // namespace fp4mr

@@ -1,0 +1,92 @@
+"""The C-ABI library loads, exports every symbol the header declares, and validates its arguments on the host
+before anything is launched (so these checks need no GPU: every call below is rejected before a launch)."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+ROOT = Path(__file__).resolve().parent.parent
+LIB = ROOT / "paper_2509_23202_amd" / "libfp4mr.so"
+HEADER = ROOT / "include" / "fp4mr.h"
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not LIB.exists():
+        from paper_2509_23202_amd import build
+        build.build(verbose=False)
+    return ctypes.CDLL(str(LIB))
+
+
+def declared_functions():
+    txt = re.sub(r"/\*.*?\*/", "", HEADER.read_text(), flags=re.S)
+    return sorted(set(re.findall(r"\b(fp4_[a-z0-9_]+)\s*\(", txt)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"fp4_rotate_quantize", "fp4_quantize_weights", "fp4_gemm", "fp4_workspace_bytes", "fp4_packed_bytes",
+            "fp4_status_string", "fp4_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    lib.fp4_version.restype = ctypes.c_int
+    assert lib.fp4_version() >= 100
+
+
+def test_binding_imports_and_matches_header():
+    from paper_2509_23202_amd import binding
+    for n in ("fp4_rotate_quantize", "fp4_quantize_weights", "fp4_gemm"):
+        assert callable(getattr(binding, n))
+    hdr = HEADER.read_text()
+    for name in ("LAYOUT_GEMM", "INPUT_F32", "STATIC_TENSOR_SCALE", "A_LAYOUT_GEMM", "W_LAYOUT_GEMM", "OUT_F32"):
+        m = re.search(rf"FP4MR_{name}\s*=\s*1u\s*<<\s*(\d+)", hdr)
+        assert m and getattr(binding, name) == 1 << int(m.group(1)), name
+
+
+def test_sizes(lib):
+    from paper_2509_23202_amd import binding as b
+    assert b.packed_bytes(64, 4096, b.MXFP4) == (64 * 4096 // 2, 64 * 4096 // 32)        # 4.25 bits / element
+    assert b.packed_bytes(64, 4096, b.NVFP4) == (64 * 4096 // 2, 64 * 4096 // 16)        # 4.5 bits / element
+    c, s = b.packed_bytes(1, 4096, b.MXFP4, b.LAYOUT_GEMM)                               # rows padded to 16
+    assert c == 16 * 4096 // 2 and s == 16 * 4096 // 32
+    c, s = b.packed_bytes(17, 640, b.MXFP4, b.LAYOUT_GEMM)                               # K/128 = 5: scales padded to 1024
+    assert c == 32 * 640 // 2 and s == 2 * 2 * 256
+    assert b.workspace_bytes(b.OP_ROTATE_QUANTIZE, 64, 0, 4096, b.MXFP4) == 0
+    assert b.workspace_bytes(b.OP_ROTATE_QUANTIZE, 64, 0, 4096, b.NVFP4) > 0
+    assert b.workspace_bytes(b.OP_ROTATE_QUANTIZE, 64, 0, 4096, b.NVFP4, b.STATIC_TENSOR_SCALE) == 0
+    assert b.workspace_bytes(b.OP_GEMM, 64, 64, 4096, b.MXFP4, b.A_LAYOUT_GEMM | b.W_LAYOUT_GEMM) == 0
+    assert b.workspace_bytes(b.OP_GEMM, 64, 64, 4096, b.MXFP4) > 0
+
+
+def test_argument_validation_happens_before_any_launch(lib):
+    from paper_2509_23202_amd import binding as b
+    L = b.lib
+    fake = 0x10000            # non-NULL, 16-byte aligned, never dereferenced: every call below fails validation
+    q = lambda **kw: L.fp4_rotate_quantize(kw.get("x", fake), kw.get("M", 4), kw.get("K", 128), kw.get("b", 32), kw.get("fmt", 0),
+                                           kw.get("codes", fake), kw.get("scales", fake), kw.get("ts", None), kw.get("ws", None),
+                                           kw.get("wsz", 0), kw.get("flags", 0), None)
+    assert q(x=None) == 1                       # NULL
+    assert q(codes=None) == 1
+    assert q(M=0) == 2 and q(K=0) == 2 and q(K=48) == 2          # shape
+    assert q(b=64, K=96) == 2                   # K % had_block
+    assert q(K=160, flags=b.LAYOUT_GEMM) == 2   # GEMM layout wants K % 128
+    assert q(b=8) == 3 and q(b=256) == 3 and q(b=0) == 3         # had_block
+    assert q(b=32, flags=b.INPUT_F32) == 3      # fp32 input only without rotation
+    assert q(fmt=2) == 4 and q(flags=1 << 9) == 4                # fmt / flags
+    assert q(x=fake + 4) == 5 and q(codes=fake + 8) == 5         # alignment
+    assert q(fmt=1) == 1                        # NVFP4 needs the tensor-scale pointer
+    assert q(fmt=1, ts=fake) == 6               # ... and a workspace
+    assert q(fmt=1, ts=fake, ws=fake, wsz=8) == 6
+    g = lambda **kw: L.fp4_gemm(kw.get("a", fake), fake, kw.get("ats", None), fake, fake, None, kw.get("M", 16), kw.get("N", 16),
+                                kw.get("K", 128), kw.get("fmt", 0), kw.get("out", fake), kw.get("ws", None), kw.get("wsz", 0),
+                                kw.get("flags", b.A_LAYOUT_GEMM | b.W_LAYOUT_GEMM), None)
+    assert g(a=None) == 1 and g(out=None) == 1
+    assert g(K=64) == 2 and g(M=0) == 2 and g(N=-1) == 2
+    assert g(fmt=3) == 4 and g(flags=1 << 12) == 4
+    assert g(out=fake + 2) == 5
+    assert g(fmt=1) == 1                        # NVFP4 needs both tensor scales
+    assert g(flags=0) == 6                      # canonical operands need the repack workspace
+    assert L.fp4_status_string(2).decode().startswith("bad shape")
+    for s in range(8):
+        assert L.fp4_status_string(s)

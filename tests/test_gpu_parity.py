@@ -1,0 +1,316 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Bars (from the benchmark spec):
+  * quantizer fed the oracle's fp32 rotated values: codes, scales and tensor scale BIT-EXACT;
+  * end to end (library's own rotation): <= 1e-4 of codes differ, each by <= 1 grid step;
+  * GEMM: |gpu - oracle| <= 1e-3 * sum_k |a*w| per element (plus half a bf16 ulp of the value for bf16 output;
+    the fp32-output runs check the bare bound).
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2509_23202_amd import inputs
+from tests.gpu_util import MX, NV, compare_codes, gemm_layout_to_canonical, to_dev, to_dev_bf16, unpack
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def fp4():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2509_23202_amd import binding
+    return binding
+
+
+def np_(t):
+    return t.detach().cpu().numpy()
+
+
+def rand_bits(rng, shape, spread=3.0):
+    x = rng.standard_normal(shape) * np.exp(rng.uniform(-spread, spread, shape))
+    return inputs.f32_to_bf16_bits(x.astype(np.float32))
+
+
+# ---------------------------------------------------------------- quantizer, mode (i): bit-exact
+@pytest.mark.parametrize("sw_codec", [False, True])
+@pytest.mark.parametrize("fmt", [MX, NV])
+@pytest.mark.parametrize("b", [1, 16, 32, 64, 128])
+def test_quantizer_bit_exact_on_oracle_rotation(fp4, oracle, fmt, b, sw_codec, monkeypatch):
+    import torch
+    if sw_codec:
+        monkeypatch.setenv("FP4MR_SW_CODEC", "1")
+    else:
+        monkeypatch.delenv("FP4MR_SW_CODEC", raising=False)
+    rng = np.random.default_rng(100 * b + fmt)
+    M, K = 67, 1536                       # 100k elements: many work items, ragged last item
+    xb = rand_bits(rng, (M, K))
+    y = oracle.rotate(xb, b)
+    # plant exact midpoints, zeros and a saturating value so that ties and edge codes are exercised
+    y[0, :8] = [4.0, 0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0]
+    y[1, 32:64] = 0.0
+    y[2, 5] = -0.0
+    ref_c, ref_s, ref_T = oracle.quantize(y, fmt)
+    say(f"quantizer mode-i fmt={fmt} b={b} sw={sw_codec} M={M} K={K}")
+    c, s, T = fp4.fp4_rotate_quantize(to_dev(y), 1, fmt)
+    torch.cuda.synchronize()
+    assert np.array_equal(np_(s).reshape(M, -1), ref_s)
+    assert np.array_equal(np_(c).reshape(M, -1), ref_c)
+    if fmt == NV:
+        assert np_(T)[0] == ref_T
+
+
+@pytest.mark.parametrize("fmt", [MX, NV])
+def test_quantizer_bit_exact_bf16_no_rotation(fp4, oracle, fmt):
+    """had_block = 1 on bf16 input is exact end to end (no irrational factor): bit-exact."""
+    import torch
+    rng = np.random.default_rng(7 + fmt)
+    M, K = 33, 4096 + 512
+    xb = rand_bits(rng, (M, K), 2.0)
+    xb[3, 100:164] = 0
+    ref_c, ref_s, ref_T, _ = oracle.rotate_quantize(xb, 1, fmt)
+    say(f"quantizer b=1 bf16 fmt={fmt}")
+    c, s, T = fp4.fp4_rotate_quantize(to_dev_bf16(xb), 1, fmt)
+    torch.cuda.synchronize()
+    assert np.array_equal(np_(s).reshape(M, -1), ref_s)
+    assert np.array_equal(np_(c).reshape(M, -1), ref_c)
+    if fmt == NV:
+        assert np_(T)[0] == ref_T
+
+
+# ---------------------------------------------------------------- quantizer, mode (ii): end to end
+@pytest.mark.parametrize("fmt", [MX, NV])
+@pytest.mark.parametrize("b", [16, 32, 64, 128])
+def test_rotate_quantize_end_to_end(fp4, oracle, fmt, b):
+    import torch
+    r = inputs.RECIPES[1 if fmt == MX else 4]
+    M, K = 77, 2048 + 512
+    xb = r.x(M, K, salt=b)
+    ref_c, ref_s, ref_T, y = oracle.rotate_quantize(xb, b, fmt)
+    say(f"rotate_quantize e2e fmt={fmt} b={b}")
+    c, s, T = fp4.fp4_rotate_quantize(to_dev_bf16(xb), b, fmt)
+    torch.cuda.synchronize()
+    if fmt == NV:
+        assert abs(float(np_(T)[0]) - float(ref_T)) <= 2 * np.spacing(np.float32(ref_T))
+        if np_(T)[0] != ref_T:
+            pytest.skip("tensor scale differs by an ulp: codes are compared in the static-scale test")
+    frac, flips = compare_codes(np_(c).reshape(M, -1), np_(s).reshape(M, -1), ref_c, ref_s, y, fmt)
+    say(f"   differing codes: {frac:.2e}, scale flips: {flips}")
+
+
+@pytest.mark.parametrize("b", [16, 64])
+def test_rotate_quantize_nvfp4_static_tensor_scale(fp4, oracle, b):
+    import torch
+    r = inputs.RECIPES[4]
+    M, K = 40, 1024
+    xb = r.x(M, K, salt=3)
+    sT = np.float32(2.0 ** -8)
+    y = oracle.rotate(xb, b)
+    ref_c, ref_s, ref_T = oracle.quantize(y, NV, tensor_scale=float(sT))
+    say(f"nvfp4 static scale b={b}")
+    ts = torch.tensor([sT], dtype=torch.float32, device="cuda")
+    c, s, T = fp4.fp4_rotate_quantize(to_dev_bf16(xb), b, NV, tensor_scale=ts)
+    torch.cuda.synchronize()
+    assert np_(T)[0] == sT
+    compare_codes(np_(c).reshape(M, -1), np_(s).reshape(M, -1), ref_c, ref_s, y, NV)
+
+
+@pytest.mark.parametrize("fmt", [MX, NV])
+@pytest.mark.parametrize("b", [1, 16, 32, 64, 128])
+def test_gemm_layout_is_a_permutation_of_canonical(fp4, fmt, b):
+    """Same kernel, two output orders: un-shuffling the GEMM layout on the host gives the canonical bytes."""
+    import torch
+    r = inputs.RECIPES[1]
+    M, K = 45, 1024 + 128                 # ragged row block (45 = 2*16 + 13), K/128 = 9 (not a multiple of 4)
+    x = to_dev_bf16(r.x(M, K, salt=50 + b))
+    say(f"gemm layout vs canonical fmt={fmt} b={b}")
+    c0, s0, T0 = fp4.fp4_rotate_quantize(x, b, fmt)
+    c1, s1, T1 = fp4.fp4_rotate_quantize(x, b, fmt, flags=fp4.LAYOUT_GEMM)
+    torch.cuda.synchronize()
+    cc, ss = gemm_layout_to_canonical(np_(c1), np_(s1), M, K, fmt)
+    assert np.array_equal(cc, np_(c0).reshape(M, -1))
+    assert np.array_equal(ss, np_(s0).reshape(M, -1))
+    if fmt == NV:
+        assert np_(T0)[0] == np_(T1)[0]
+
+
+def test_quantize_weights_matches_rotate_quantize(fp4):
+    import torch
+    w = to_dev_bf16(inputs.RECIPES[1].w(96, 512))
+    a = fp4.fp4_quantize_weights(w, 32, MX)
+    b = fp4.fp4_rotate_quantize(w, 32, MX)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+# ---------------------------------------------------------------- GEMM
+def _gemm_case(fp4, oracle, fmt, M, N, K, seed, out_f32, layout_gemm):
+    """Operands are the ORACLE's codes and scales; the product is checked against the oracle's fp64 product."""
+    import torch
+    rng = np.random.default_rng(seed)
+    r = inputs.RECIPES[1 if fmt == MX else 4]
+    b = 32 if fmt == MX else 16
+    xb, wb = r.x(M, K, salt=seed), r.w(N, K, salt=seed)
+    ac, asc, aT, _ = oracle.rotate_quantize(xb, b, fmt)
+    wc, wsc, wT, _ = oracle.rotate_quantize(wb, b, fmt)
+    Y, S = oracle.matmul(oracle.dequantize(ac, asc, fmt, aT), oracle.dequantize(wc, wsc, fmt, wT))
+    say(f"gemm fmt={fmt} M={M} N={N} K={K} out_f32={out_f32} layout_gemm={layout_gemm}")
+    flags = fp4.OUT_F32 if out_f32 else 0
+    d = lambda a: to_dev(a.reshape(-1))
+    ts = lambda v: None if v is None else torch.tensor([v], dtype=torch.float32, device="cuda")
+    if layout_gemm:
+        # let the library's quantizer produce GEMM-layout operands from the oracle's fp32 rotated values: they
+        # are bit-identical to the oracle's codes (mode-i test), so the reference product is unchanged
+        ya, yw = oracle.rotate(xb, b), oracle.rotate(wb, b)
+        qa = fp4.fp4_rotate_quantize(to_dev(ya), 1, fmt, flags=fp4.LAYOUT_GEMM)
+        qw = fp4.fp4_quantize_weights(to_dev(yw), 1, fmt, flags=fp4.LAYOUT_GEMM)
+        out = fp4.fp4_gemm(qa[0], qa[1], qa[2], qw[0], qw[1], qw[2], M, N, K, fmt,
+                           flags=flags | fp4.A_LAYOUT_GEMM | fp4.W_LAYOUT_GEMM)
+    else:
+        out = fp4.fp4_gemm(d(ac), d(asc), ts(aT), d(wc), d(wsc), ts(wT), M, N, K, fmt, flags=flags)
+    torch.cuda.synchronize()
+    got = np_(out.float()).astype(np.float64)
+    tol = 1e-3 * S
+    if not out_f32:
+        tol = tol + np.abs(Y) * 2.0 ** -8          # bf16 output rounding (half an ulp <= 2^-9 |y|), generous
+    err = np.abs(got - Y)
+    worst = float((err / (1e-3 * S + 1e-300)).max())
+    say(f"   max err / (1e-3 S) = {worst:.3e}")
+    assert np.all(err <= tol), f"worst ratio {worst}"
+    return worst
+
+
+@pytest.mark.parametrize("fmt", [MX, NV])
+@pytest.mark.parametrize("M,N,K", [(64, 256, 512), (150, 328, 1152), (1, 4096, 4096), (16, 512, 2048), (300, 136, 128)])
+def test_gemm_against_oracle_fp32_out(fp4, oracle, fmt, M, N, K):
+    _gemm_case(fp4, oracle, fmt, M, N, K, seed=M + N + K, out_f32=True, layout_gemm=False)
+
+
+@pytest.mark.parametrize("fmt", [MX, NV])
+def test_gemm_gemm_layout_operands_bf16_out(fp4, oracle, fmt):
+    _gemm_case(fp4, oracle, fmt, 200, 520, 1024 + 384, seed=5, out_f32=False, layout_gemm=True)
+
+
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5])
+def test_gemm_mxfp4_every_tile_variant(fp4, oracle, variant, monkeypatch):
+    monkeypatch.setenv("FP4MR_GEMM_VARIANT", str(variant))
+    _gemm_case(fp4, oracle, MX, 272, 528, 1280, seed=variant, out_f32=True, layout_gemm=True)
+
+
+def test_gemm_mxfp4_exact_on_small_integers(fp4, oracle):
+    """With scale bytes chosen freely and on-grid codes, 4*a*w are small integers: the fp32 accumulator must be
+    EXACT (any summation order), and distinct scales per K-group pin the scale-to-group wiring."""
+    import torch
+    rng = np.random.default_rng(99)
+    M, N, K = 48, 80, 1024
+    ac = rng.integers(0, 256, (M, K // 2), dtype=np.uint8)
+    wc = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)
+    asc = rng.integers(126, 129, (M, K // 32)).astype(np.uint8)
+    wsc = rng.integers(126, 130, (N, K // 32)).astype(np.uint8)
+    Y, S = oracle.matmul(oracle.dequantize(ac, asc, MX), oracle.dequantize(wc, wsc, MX))
+    assert np.abs(S).max() * 16 < 2.0 ** 24      # every term is a multiple of 2^-4: all partial sums are exact in fp32
+    say("gemm exact integers")
+    out = fp4.fp4_gemm(to_dev(ac.reshape(-1)), to_dev(asc.reshape(-1)), None, to_dev(wc.reshape(-1)), to_dev(wsc.reshape(-1)),
+                       None, M, N, K, MX, flags=fp4.OUT_F32)
+    torch.cuda.synchronize()
+    assert np.array_equal(np_(out).astype(np.float64), Y)
+
+
+def test_gemm_selector_weights_return_decoded_activations(fp4, oracle):
+    """W rows with a single 1.0 pick single columns of the decoded A: pins row/column roles and K order."""
+    import torch
+    rng = np.random.default_rng(5)
+    M, N, K = 32, 64, 256
+    ac = rng.integers(0, 256, (M, K // 2), dtype=np.uint8)
+    asc = rng.integers(124, 130, (M, K // 32)).astype(np.uint8)
+    wc = np.zeros((N, K // 2), dtype=np.uint8)
+    picks = rng.integers(0, K, N)
+    for n, k in enumerate(picks):
+        wc[n, k // 2] = 2 << (4 * (k & 1))         # code 2 = 1.0
+    wsc = np.full((N, K // 32), 127, dtype=np.uint8)
+    A = oracle.dequantize(ac, asc, MX)
+    say("gemm selector")
+    out = fp4.fp4_gemm(to_dev(ac.reshape(-1)), to_dev(asc.reshape(-1)), None, to_dev(wc.reshape(-1)), to_dev(wsc.reshape(-1)),
+                       None, M, N, K, MX, flags=fp4.OUT_F32)
+    torch.cuda.synchronize()
+    assert np.array_equal(np_(out).astype(np.float64), A[:, picks])
+
+
+# ---------------------------------------------------------------- whole path
+@pytest.mark.parametrize("fmt,b", [(MX, 32), (NV, 16), (MX, 128), (MX, 64), (MX, 16)])
+def test_linear_layer_whole_path(fp4, oracle, fmt, b):
+    """bf16 X, W -> rotate+quantize (GEMM layout) -> FP4 GEMM -> bf16, all on the GPU, against the oracle run on
+    the same bits.  The library's own codes are checked against the oracle's by the end-to-end rule; the product
+    is checked against the oracle's product of the LIBRARY's codes (so one differing code cannot hide in the
+    GEMM tolerance, nor break it)."""
+    import torch
+    r = inputs.RECIPES[1 if fmt == MX else 4]
+    M, N, K = 64, 384, 4096
+    xb, wb = r.x(M, K), r.w(N, K)
+    say(f"whole path fmt={fmt} b={b}")
+    qa = fp4.fp4_rotate_quantize(to_dev_bf16(xb), b, fmt, flags=fp4.LAYOUT_GEMM)
+    qw = fp4.fp4_quantize_weights(to_dev_bf16(wb), b, fmt, flags=fp4.LAYOUT_GEMM)
+    out = fp4.fp4_gemm(qa[0], qa[1], qa[2], qw[0], qw[1], qw[2], M, N, K, fmt, flags=fp4.A_LAYOUT_GEMM | fp4.W_LAYOUT_GEMM)
+    torch.cuda.synchronize()
+    ac, asc = gemm_layout_to_canonical(np_(qa[0]), np_(qa[1]), M, K, fmt)
+    wc, wsc = gemm_layout_to_canonical(np_(qw[0]), np_(qw[1]), N, K, fmt)
+    rac, rasc, raT, ya = oracle.rotate_quantize(xb, b, fmt)
+    rwc, rwsc, rwT, yw = oracle.rotate_quantize(wb, b, fmt)
+    aT = None if fmt == MX else np_(qa[2])[0]
+    wT = None if fmt == MX else np_(qw[2])[0]
+    if fmt == NV:
+        assert abs(float(aT) - float(raT)) <= 2 * np.spacing(raT) and abs(float(wT) - float(rwT)) <= 2 * np.spacing(rwT)
+    if fmt == MX or (aT == raT and wT == rwT):
+        compare_codes(ac, asc, rac, rasc, ya, fmt)
+        compare_codes(wc, wsc, rwc, rwsc, yw, fmt)
+    Y, S = oracle.matmul(oracle.dequantize(ac, asc, fmt, aT), oracle.dequantize(wc, wsc, fmt, wT))
+    got = np_(out.float()).astype(np.float64)
+    assert np.all(np.abs(got - Y) <= 1e-3 * S + np.abs(Y) * 2.0 ** -8)
+    # and the oracle's own end result is within the same bound of the GPU's (codes differ in <= 1e-4 of places)
+    Y0, S0 = oracle.linear(xb, wb, b, fmt)
+    assert np.mean(np.abs(got - Y0) <= 1e-3 * S0 + np.abs(Y0) * 2.0 ** -8) > 0.999
+
+
+# ---------------------------------------------------------------- edge cases
+def test_zero_input_and_extreme_magnitudes(fp4, oracle):
+    import torch
+    M, K = 16, 256
+    x = np.zeros((M, K), dtype=np.float32)
+    x[1] = 3.0e38
+    x[2] = 1e-40
+    x[3, ::2] = -1e-38
+    x[4, 7] = 2.0 ** -126
+    for fmt in (MX,):
+        ref_c, ref_s, _ = oracle.quantize(x, fmt)
+        say(f"extremes fmt={fmt}")
+        c, s, _ = fp4.fp4_rotate_quantize(to_dev(x), 1, fmt)
+        torch.cuda.synchronize()
+        assert np.array_equal(np_(s).reshape(M, -1), ref_s)
+        assert np.array_equal(np_(c).reshape(M, -1), ref_c)
+    z = np.zeros((M, K), dtype=np.float32)
+    c, s, T = fp4.fp4_rotate_quantize(to_dev(z), 1, NV)
+    torch.cuda.synchronize()
+    assert np_(T)[0] == 0 and not np_(c).any() and not np_(s).any()
+
+
+def test_results_are_deterministic(fp4):
+    import torch
+    r = inputs.RECIPES[1]
+    x = to_dev_bf16(r.x(128, 1024))
+    w = to_dev_bf16(r.w(256, 1024))
+    outs = []
+    for _ in range(2):
+        qa = fp4.fp4_rotate_quantize(x, 32, MX, flags=fp4.LAYOUT_GEMM)
+        qw = fp4.fp4_quantize_weights(w, 32, MX, flags=fp4.LAYOUT_GEMM)
+        outs.append(fp4.fp4_gemm(qa[0], qa[1], None, qw[0], qw[1], None, 128, 256, 1024, MX,
+                                 flags=fp4.A_LAYOUT_GEMM | fp4.W_LAYOUT_GEMM).clone())
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
