@@ -11,7 +11,8 @@
 // regime gets the full bandwidth saving; the large-M regime is bounded by the fp16 MFMA rate, not the FP4 one.
 //
 // Data movement is the same as in the MXFP4 kernel: 1 KB code fragments and 128-byte scale blocks (two E4M3
-// bytes per lane) go global -> LDS with direct-to-LDS loads into a ring, one barrier per K-step of 128.
+// bytes per lane, copied by half a wave as dwords) go global -> LDS with direct-to-LDS loads into a ring, one
+// barrier per K-step of 128.
 // The contraction index inside a fragment is permuted (lane q, dword s, element e <-> k = 32q + 8s + e for both
 // operands alike), which a dot product does not see.
 #include "device_util.hpp"
@@ -120,7 +121,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_nv_kernel(NvG
             sbase = g.w_scales;
         }
         gsrc[i] = cbase + rb * KC * 1024 + lane * 16;
-        ssrc[i] = sbase + rb * KC * 128 + lane * 2;
+        ssrc[i] = sbase + rb * KC * 128 + (lane & 31) * 4;
         foff[i] = f;
     }
 
@@ -135,7 +136,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_nv_kernel(NvG
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             __builtin_amdgcn_global_load_lds((global_void*)(gsrc[i] + (int64_t)kt * 1024), (lds_void*)(base + foff[i] * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((global_void*)(ssrc[i] + (int64_t)kt * 128), (lds_void*)(base + SCALE_OFF + foff[i] * 128), 2, 0, 0);
+            // direct-to-LDS loads place lane l's data at 4*l whatever the access size is below a dword, so the
+            // 128-byte scale block is copied as 32 lanes x 4 bytes (the upper half-wave is masked off)
+            if (lane < 32)
+                __builtin_amdgcn_global_load_lds((global_void*)(ssrc[i] + (int64_t)kt * 128), (lds_void*)(base + SCALE_OFF + foff[i] * 128), 4, 0, 0);
         }
     };
 

@@ -368,7 +368,9 @@ __global__ void fill_u32_kernel(uint32_t* p, uint32_t v) { *p = v; }
 template <int BP, int G, int LAYOUT, int PASS, bool HW>
 hipError_t launch_mfma(const RqArgs& a0, int grid_cap, hipStream_t st)
 {
-    constexpr int FR = (BP == 128) ? 2 : 1;
+    // two fragments' worth of loads in flight per wave for the widest block (canonical order only: there an
+    // item may run past the end and is masked per vector; GEMM-order items are whole fragments)
+    constexpr int FR = (BP == 128 && LAYOUT == 0) ? 2 : 1;
     RqArgs a = a0;
     if (LAYOUT == 0) {
         const int64_t nv = a.rows * a.K / BP;
@@ -376,13 +378,12 @@ hipError_t launch_mfma(const RqArgs& a0, int grid_cap, hipStream_t st)
         a.n_items = (nst + FR * (128 / BP) - 1) / (FR * (128 / BP));
     } else {
         const int64_t nf = round_up(a.rows, 16) / 16 * (a.K / 128);
-        a.n_items = (nf + FR - 1) / FR;
-        // FR > 1 in GEMM layout may run one fragment past the end; keep FR = 1 there (see dispatch below)
+        a.n_items = nf;
     }
     int64_t blocks = (a.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > grid_cap) blocks = grid_cap;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL((rq_mfma_kernel<BP, G, LAYOUT, PASS, HW, (LAYOUT == 0 ? FR : 1)>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((rq_mfma_kernel<BP, G, LAYOUT, PASS, HW, FR>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
     return hipGetLastError();
 }
 
