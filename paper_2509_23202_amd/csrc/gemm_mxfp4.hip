@@ -7,7 +7,8 @@
 // K-elements of one row (16 bytes) and one E8M0 byte that scales exactly those 32 elements -- the MXFP4 group.
 // Both operands arrive in "GEMM layout": 1 KB fragments already in lane order (layout.hpp), so a fragment moves
 // global -> LDS with one 16-byte direct-to-LDS load per lane and LDS -> registers with one conflict-free
-// ds_read_b128 per lane; no re-layout pass runs between the quantizer and the GEMM.
+// ds_read_b128 per lane; no re-layout pass runs between the quantizer and the GEMM.  (Direct-to-LDS loads write
+// lane l's bytes at LDS base + 16*l, which is exactly the fragment order.)
 //
 // Roles are swapped on purpose: the W fragment is the MFMA's A operand (rows = n) and the X fragment its B
 // operand (columns = m).  A lane then owns four consecutive n of one m, i.e. one 8-byte bf16x4 store.
@@ -51,14 +52,13 @@ __device__ __forceinline__ void block_barrier()
     asm volatile("" ::: "memory");
 }
 
+__device__ __forceinline__ void wait_lgkmcnt0()
+{
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0); vmcnt / expcnt: no wait
+}
+
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_void;
-
-__device__ __forceinline__ void load_frag_to_lds(const uint8_t* gsrc_lane, char* lds_frag_base)
-{
-    // 16 bytes per lane, written to lds_frag_base + 16 * lane
-    __builtin_amdgcn_global_load_lds((global_void*)gsrc_lane, (lds_void*)lds_frag_base, 16, 0, 0);
-}
 
 template <int OPSEL>
 __device__ __forceinline__ v4f mfma_fp4(const v4i& a, const v4i& b, const v4f& c, uint32_t sa, uint32_t sb)
@@ -94,13 +94,16 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     constexpr int LPW = (F + NW - 1) / NW;                  // fragment loads per wave per stage
     constexpr int TM = WM / 16, TN = WN / 16;               // MFMA tiles per wave
     constexpr int STAGE_BYTES = F * 1024;
-    static_assert(STAGES >= 2 && STAGES <= 5, "scale prefetch distance assumes at most 5 stages");
+    static_assert(STAGES >= 3 && STAGES <= 5, "ring bookkeeping is written for 3 to 5 stages");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    // the wave index is uniform across the wavefront: telling the compiler keeps every fragment base address,
+    // LDS offset and tile coordinate in scalar registers (the vector file is needed for accumulators and fragments)
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int wm = wave % NWM, wn = wave / NWM;
+    const uint32_t lane16 = (uint32_t)lane * 16u, lane4 = (uint32_t)lane * 4u;
 
     int tm, tn;
     remap_block(blockIdx.x, g.tiles_m * g.tiles_n, g.tiles_m, g.tiles_n, tm, tn);
@@ -108,50 +111,28 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     const int64_t KC = g.K >> 7;            // K-steps
     const int64_t KS = (g.K + 511) >> 9;    // scale super-steps
     const int KT = (int)KC;
-    const int64_t rbx_max = (g.M + 15) / 16 - 1, rbw_max = (g.N + 15) / 16 - 1;
 
-    // global source of each fragment this wave copies (row-block clamped to the operand; clamped duplicates only
-    // feed output rows/columns that are never stored)
-    const uint8_t* gsrc[LPW];
-    int lds_off[LPW];
-#pragma unroll
-    for (int i = 0; i < LPW; ++i) {
-        // every wave issues exactly LPW loads per stage so that the vmcnt bookkeeping is uniform; when F is not
-        // a multiple of NW the spare slots re-copy the last fragment (same bytes to the same place)
-        const int f = min(wave + i * NW, F - 1);
-        if (f < FX) {
-            int64_t rb = (int64_t)tm * FX + f;
-            rb = rb > rbx_max ? rbx_max : rb;
-            gsrc[i] = g.a_codes + rb * KC * 1024 + lane * 16;
-        } else {
-            int64_t rb = (int64_t)tn * FW + (f - FX);
-            rb = rb > rbw_max ? rbw_max : rb;
-            gsrc[i] = g.w_codes + rb * KC * 1024 + lane * 16;
-        }
-        lds_off[i] = f * 1024;
-    }
+    // Operands are addressed through buffer resources: one VGPR (16 * lane) is the only per-lane address, every
+    // fragment's position is a scalar offset, and reads past the end of an operand (row-blocks beyond M or N in
+    // the last tile) return zero instead of needing a clamp.
+    const int64_t a_rb0 = (int64_t)tm * FX, w_rb0 = (int64_t)tn * FW;
+    const int64_t a_rbs = (g.M + 15) / 16, w_rbs = (g.N + 15) / 16;
+    auto make_rsrc = [](const uint8_t* base, int64_t bytes) {
+        const uint32_t n = bytes <= 0 ? 0u : (bytes > 0xffffffffll ? 0xffffffffu : (uint32_t)bytes);
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, (int)n, 0x00020000);
+    };
+    const __amdgpu_buffer_rsrc_t rs_ac = make_rsrc(g.a_codes + a_rb0 * KC * 1024, (a_rbs - a_rb0) * KC * 1024);
+    const __amdgpu_buffer_rsrc_t rs_wc = make_rsrc(g.w_codes + w_rb0 * KC * 1024, (w_rbs - w_rb0) * KC * 1024);
+    const __amdgpu_buffer_rsrc_t rs_as = make_rsrc(g.a_scales + a_rb0 * KS * 256, (a_rbs - a_rb0) * KS * 256);
+    const __amdgpu_buffer_rsrc_t rs_ws = make_rsrc(g.w_scales + w_rb0 * KS * 256, (w_rbs - w_rb0) * KS * 256);
+
     // Scales: every (row-block, 4 K-steps) owns 256 bytes = one dword per lane.  They travel global -> LDS with
     // 4-byte direct-to-LDS loads into a two-deep ring (so no VGPR is ever the target of an in-flight load inside
     // the main loop) and are read back once per 4 K-steps.
-    constexpr int NS = (F + NW - 1) / NW;                   // scale-block loads per wave per batch
+    constexpr int NS = LPW;                                 // scale-block loads per wave per batch
     constexpr int SCALE_BYTES = F * 256;
     char* const scale_ring = smem + STAGES * STAGE_BYTES;
-    const uint8_t* ssrc[NS];
-    int slds_off[NS];
-#pragma unroll
-    for (int i = 0; i < NS; ++i) {
-        const int f = min(wave + i * NW, F - 1);
-        if (f < FX) {
-            int64_t rb = (int64_t)tm * FX + f;
-            rb = rb > rbx_max ? rbx_max : rb;
-            ssrc[i] = g.a_scales + rb * KS * 256 + lane * 4;
-        } else {
-            int64_t rb = (int64_t)tn * FW + (f - FX);
-            rb = rb > rbw_max ? rbw_max : rb;
-            ssrc[i] = g.w_scales + rb * KS * 256 + lane * 4;
-        }
-        slds_off[i] = f * 256;
-    }
+    const int kc_bytes = (int)KC * 1024, ks_bytes = (int)KS * 256;
 
     v4f acc[TN][TM];
 #pragma unroll
@@ -160,62 +141,92 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
         for (int j = 0; j < TM; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
 
     uint32_t sx[TM], sw[TN];
-
-    auto issue_scales = [&](int64_t ss) {
+    // Software pipeline of the LDS reads: the X fragments of step kt+1 are read into the other half of xf[2][.]
+    // while step kt computes, and the W fragments run through a 4-deep register ring two groups of TM MFMAs ahead
+    // of their use -- so no MFMA waits on LDS latency, at a cost of 2*TM*4 + 16 fragment registers.
+    v4i xf[2][TM], wring[4];
+    static_assert(TN % 4 == 0, "the W-fragment ring index must be static");
+    auto issue_scales = [&](int ss) {
         char* base = scale_ring + (ss & 1) * SCALE_BYTES;
-        ss = ss < KS ? ss : KS - 1;  // the batch past the end re-reads the last one: keeps the load count uniform
+        ss = ss < (int)KS ? ss : (int)KS - 1;  // the batch past the end re-reads the last one
 #pragma unroll
-        for (int i = 0; i < NS; ++i)
-            __builtin_amdgcn_global_load_lds((global_void*)(ssrc[i] + ss * 256), (lds_void*)(base + slds_off[i]), 4, 0, 0);
+        for (int i = 0; i < NS; ++i) {
+            const int f = min(wave + i * NW, F - 1);
+            if (f < FX) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_as, (lds_void*)(base + f * 256), 4, lane4, f * ks_bytes + ss * 256, 0, 0);
+            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_ws, (lds_void*)(base + f * 256), 4, lane4, (f - FX) * ks_bytes + ss * 256, 0, 0);
+        }
     };
-    auto read_scales = [&](int64_t ss) {
+    auto read_scales = [&](int64_t ss, uint32_t (&dx)[TM], uint32_t (&dw)[TN]) {
         const char* base = scale_ring + (ss & 1) * SCALE_BYTES;
 #pragma unroll
-        for (int j = 0; j < TM; ++j) sx[j] = *(reinterpret_cast<const uint32_t*>(base + (wm * TM + j) * 256) + lane);
+        for (int j = 0; j < TM; ++j) dx[j] = *(reinterpret_cast<const uint32_t*>(base + (wm * TM + j) * 256) + lane);
 #pragma unroll
-        for (int i = 0; i < TN; ++i) sw[i] = *(reinterpret_cast<const uint32_t*>(base + (FX + wn * TN + i) * 256) + lane);
+        for (int i = 0; i < TN; ++i) dw[i] = *(reinterpret_cast<const uint32_t*>(base + (FX + wn * TN + i) * 256) + lane);
     };
     auto issue_frags = [&](int kt) {
         char* base = smem + (kt % STAGES) * STAGE_BYTES;
 #pragma unroll
-        for (int i = 0; i < LPW; ++i) load_frag_to_lds(gsrc[i] + (int64_t)kt * 1024, base + lds_off[i]);
+        for (int i = 0; i < LPW; ++i) {
+            const int f = min(wave + i * NW, F - 1);
+            if (f < FX) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_ac, (lds_void*)(base + f * 1024), 16, lane16, f * kc_bytes + kt * 1024, 0, 0);
+            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_wc, (lds_void*)(base + f * 1024), 16, lane16, (f - FX) * kc_bytes + kt * 1024, 0, 0);
+        }
+    };
+    auto read_x = [&](int kt, auto ptag, int j) {
+        constexpr int P = decltype(ptag)::value;
+        xf[P][j] = *(reinterpret_cast<const v4i*>(smem + (kt % STAGES) * STAGE_BYTES + (wm * TM + j) * 1024) + lane);
+    };
+    auto read_w = [&](int kt, int i) {  // into ring slot i % 4 (i is a compile-time constant after unrolling)
+        wring[i & 3] = *(reinterpret_cast<const v4i*>(smem + (kt % STAGES) * STAGE_BYTES + (FX + wn * TN + i) * 1024) + lane);
     };
 
-    // prologue: scales of super-step 0, then the first STAGES-1 stages
+    // prologue: scales of super-step 0, then STAGES-1 stages; scales, X fragments and the first two W fragments of
+    // step 0 into registers
     issue_scales(0);
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s)
         if (s < KT) issue_frags(s);
+    if (STAGES - 2 < KT) wait_vmcnt<(STAGES - 2) * LPW>(); else wait_vmcnt<0>();
+    block_barrier();
+    read_scales(0, sx, sw);
+#pragma unroll
+    for (int j = 0; j < TM; ++j) read_x(0, std::integral_constant<int, 0>{}, j);
+    read_w(0, 0);
+    read_w(0, 1);
 
-    auto compute = [&](int kt, auto opsel_tag) {
-        constexpr int OPSEL = decltype(opsel_tag)::value;
-        const char* base = smem + (kt % STAGES) * STAGE_BYTES;
-        v4i xf[TM];
-#pragma unroll
-        for (int j = 0; j < TM; ++j) xf[j] = *(reinterpret_cast<const v4i*>(base + (wm * TM + j) * 1024) + lane);
-#pragma unroll
-        for (int i = 0; i < TN; ++i) {
-            const v4i wf = *(reinterpret_cast<const v4i*>(base + (FX + wn * TN + i) * 1024) + lane);
-#pragma unroll
-            for (int j = 0; j < TM; ++j) acc[i][j] = mfma_fp4<OPSEL>(wf, xf[j], acc[i][j], sw[i], sx[j]);
-        }
-    };
-
-    // Number of loads allowed to be still in flight when stage kt must have landed: the STAGES-2 later stages,
-    // plus one scale batch when it was issued after stage kt's loads (j = kt % 4; batches go out at j == 0,
-    // ahead of that iteration's fragment loads).
+    // One K-step.  J = kt % 4 selects the scale byte (op_sel) and the X register half (J & 1).
+    //   top:    stage kt+1 must have landed (this wave's copies: vmcnt; everybody's: barrier).  The same barrier
+    //           says that every wave is done reading stage kt-1, whose LDS buffer is refilled with stage kt+STAGES-1.
+    //   vmcnt:  allowed in flight = the STAGES-3 stages after kt+1, plus one scale batch when it was issued after
+    //           stage kt+1's loads (batches go out at J == 0, ahead of that step's fragment loads).
+    constexpr int XPG = (TM + TN - 1) / TN;  // X-fragment reads folded in front of each group of TM MFMAs
+    // The LDS reads for "the next step" are unconditional: in the very last step they fetch stale bytes of the ring
+    // that nothing consumes, which keeps the step body free of branches (and of a second copy of the code).
     auto step = [&](int kt, auto jtag) {
         constexpr int J = decltype(jtag)::value;
-        constexpr bool batch_after = (STAGES >= 3) && ((J >= 1 && J <= STAGES - 2));
-        constexpr int ALLOWED = (STAGES - 2) * LPW + (batch_after ? NS : 0);
+        constexpr int P = J & 1;
+        constexpr bool batch_after = (J >= 1 && J <= STAGES - 3);
+        constexpr int ALLOWED = (STAGES - 3) * LPW + (batch_after ? NS : 0);
         if (kt + STAGES - 2 < KT) wait_vmcnt<ALLOWED>(); else wait_vmcnt<0>();
+        wait_lgkmcnt0();
         block_barrier();
-        if constexpr (J == 0) {
-            read_scales(kt >> 2);
-            issue_scales((kt >> 2) + 1);
-        }
+        if constexpr (J == 0) issue_scales((kt >> 2) + 1);
         if (kt + STAGES - 1 < KT) issue_frags(kt + STAGES - 1);
-        compute(kt, jtag);
+#pragma unroll
+        for (int i = 0; i < TN; ++i) {
+            // W fragment two groups ahead (wraps into the next step), X fragments of the next step
+            if (i + 2 < TN) read_w(kt, i + 2);
+            else read_w(kt + 1, i + 2 - TN);
+#pragma unroll
+            for (int j = i * XPG; j < (i + 1) * XPG && j < TM; ++j) read_x(kt + 1, std::integral_constant<int, 1 - P>{}, j);
+#pragma unroll
+            for (int j = 0; j < TM; ++j) acc[i][j] = mfma_fp4<J>(wring[i & 3], xf[P][j], acc[i][j], sw[i], sx[j]);
+            // keep the instruction scheduler from hoisting the later groups' LDS reads up here: that would rebuild a
+            // full second copy of the W fragments in registers
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // scales of the next four steps (their batch landed before this step's barrier)
+        if constexpr (J == 3) read_scales((kt >> 2) + 1, sx, sw);
     };
 
     for (int kt0 = 0; kt0 < KT; kt0 += 4) {
@@ -309,7 +320,7 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
         case 2: return launch_variant<128, 128, 64, 64, 4>(g, out_f32, st);
         case 3: return launch_variant<64, 256, 64, 64, 4>(g, out_f32, st);
         case 4: return launch_variant<16, 256, 16, 64, 4>(g, out_f32, st);
-        case 5: return launch_variant<256, 256, 128, 64, 3>(g, out_f32, st);
+        case 5: return launch_variant<256, 128, 128, 64, 4>(g, out_f32, st);
         default: return hipErrorInvalidValue;
     }
 }
