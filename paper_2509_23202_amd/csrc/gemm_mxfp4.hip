@@ -112,19 +112,21 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     const int64_t KS = (g.K + 511) >> 9;    // scale super-steps
     const int KT = (int)KC;
 
-    // Operands are addressed through buffer resources: one VGPR (16 * lane) is the only per-lane address, every
-    // fragment's position is a scalar offset, and reads past the end of an operand (row-blocks beyond M or N in
-    // the last tile) return zero instead of needing a clamp.
-    const int64_t a_rb0 = (int64_t)tm * FX, w_rb0 = (int64_t)tn * FW;
-    const int64_t a_rbs = (g.M + 15) / 16, w_rbs = (g.N + 15) / 16;
+    // Operands are addressed through buffer resources: one VGPR (16 * lane) is the only per-lane address and every
+    // fragment's position is a scalar offset.  Row-blocks past the end of an operand (last tile) are clamped to its
+    // last row-block: the duplicates only feed output rows / columns that are never stored.
+    const int a_rbs = (int)((g.M + 15) / 16), w_rbs = (int)((g.N + 15) / 16);
     auto make_rsrc = [](const uint8_t* base, int64_t bytes) {
-        const uint32_t n = bytes <= 0 ? 0u : (bytes > 0xffffffffll ? 0xffffffffu : (uint32_t)bytes);
+        const uint32_t n = bytes > 0xffffffffll ? 0xffffffffu : (uint32_t)bytes;
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, (int)n, 0x00020000);
     };
-    const __amdgpu_buffer_rsrc_t rs_ac = make_rsrc(g.a_codes + a_rb0 * KC * 1024, (a_rbs - a_rb0) * KC * 1024);
-    const __amdgpu_buffer_rsrc_t rs_wc = make_rsrc(g.w_codes + w_rb0 * KC * 1024, (w_rbs - w_rb0) * KC * 1024);
-    const __amdgpu_buffer_rsrc_t rs_as = make_rsrc(g.a_scales + a_rb0 * KS * 256, (a_rbs - a_rb0) * KS * 256);
-    const __amdgpu_buffer_rsrc_t rs_ws = make_rsrc(g.w_scales + w_rb0 * KS * 256, (w_rbs - w_rb0) * KS * 256);
+    // bases at the tile's first row-block keep every scalar offset far below 2^31
+    const int a_rb0 = min(tm * FX, a_rbs - 1), w_rb0 = min(tn * FW, w_rbs - 1);
+    const __amdgpu_buffer_rsrc_t rs_ac = make_rsrc(g.a_codes + (int64_t)a_rb0 * KC * 1024, (int64_t)(a_rbs - a_rb0) * KC * 1024);
+    const __amdgpu_buffer_rsrc_t rs_wc = make_rsrc(g.w_codes + (int64_t)w_rb0 * KC * 1024, (int64_t)(w_rbs - w_rb0) * KC * 1024);
+    const __amdgpu_buffer_rsrc_t rs_as = make_rsrc(g.a_scales + (int64_t)a_rb0 * KS * 256, (int64_t)(a_rbs - a_rb0) * KS * 256);
+    const __amdgpu_buffer_rsrc_t rs_ws = make_rsrc(g.w_scales + (int64_t)w_rb0 * KS * 256, (int64_t)(w_rbs - w_rb0) * KS * 256);
+    const int a_rb_last = a_rbs - 1 - a_rb0, w_rb_last = w_rbs - 1 - w_rb0;  // largest valid row-block relative to the base
 
     // Scales: every (row-block, 4 K-steps) owns 256 bytes = one dword per lane.  They travel global -> LDS with
     // 4-byte direct-to-LDS loads into a two-deep ring (so no VGPR is ever the target of an in-flight load inside
@@ -146,15 +148,24 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     // of their use -- so no MFMA waits on LDS latency, at a cost of 2*TM*4 + 16 fragment registers.
     v4i xf[2][TM], wring[4];
     static_assert(TN % 4 == 0, "the W-fragment ring index must be static");
-    auto issue_scales = [&](int ss) {
+    // every wave issues exactly LPW fragment loads per stage and NS scale loads per batch so that the vmcnt
+    // bookkeeping is uniform; when F is not a multiple of NW the spare slots re-copy the last fragment (same bytes
+    // to the same place)
+    auto issue_scale_one = [&](int ss, int i) {
         char* base = scale_ring + (ss & 1) * SCALE_BYTES;
         ss = ss < (int)KS ? ss : (int)KS - 1;  // the batch past the end re-reads the last one
+        const int f = min(wave + i * NW, F - 1);
+        if (f < FX) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_as, (lds_void*)(base + f * 256), 4, lane4, min(f, a_rb_last) * ks_bytes + ss * 256, 0, 0);
+        else __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_ws, (lds_void*)(base + f * 256), 4, lane4, min(f - FX, w_rb_last) * ks_bytes + ss * 256, 0, 0);
+    };
+    auto issue_frag_one = [&](int kt, char* base, int i) {
+        const int f = min(wave + i * NW, F - 1);
+        if (f < FX) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_ac, (lds_void*)(base + f * 1024), 16, lane16, min(f, a_rb_last) * kc_bytes + kt * 1024, 0, 0);
+        else __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_wc, (lds_void*)(base + f * 1024), 16, lane16, (min(f - FX, w_rb_last)) * kc_bytes + kt * 1024, 0, 0);
+    };
+    auto issue_scales = [&](int ss) {
 #pragma unroll
-        for (int i = 0; i < NS; ++i) {
-            const int f = min(wave + i * NW, F - 1);
-            if (f < FX) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_as, (lds_void*)(base + f * 256), 4, lane4, f * ks_bytes + ss * 256, 0, 0);
-            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_ws, (lds_void*)(base + f * 256), 4, lane4, (f - FX) * ks_bytes + ss * 256, 0, 0);
-        }
+        for (int i = 0; i < NS; ++i) issue_scale_one(ss, i);
     };
     auto read_scales = [&](int64_t ss, uint32_t (&dx)[TM], uint32_t (&dw)[TN]) {
         const char* base = scale_ring + (ss & 1) * SCALE_BYTES;
@@ -162,15 +173,6 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
         for (int j = 0; j < TM; ++j) dx[j] = *(reinterpret_cast<const uint32_t*>(base + (wm * TM + j) * 256) + lane);
 #pragma unroll
         for (int i = 0; i < TN; ++i) dw[i] = *(reinterpret_cast<const uint32_t*>(base + (FX + wn * TN + i) * 256) + lane);
-    };
-    auto issue_frags = [&](int kt) {
-        char* base = smem + (kt % STAGES) * STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < LPW; ++i) {
-            const int f = min(wave + i * NW, F - 1);
-            if (f < FX) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_ac, (lds_void*)(base + f * 1024), 16, lane16, f * kc_bytes + kt * 1024, 0, 0);
-            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_wc, (lds_void*)(base + f * 1024), 16, lane16, (f - FX) * kc_bytes + kt * 1024, 0, 0);
-        }
     };
     auto read_x = [&](int kt, auto ptag, int j) {
         constexpr int P = decltype(ptag)::value;
@@ -184,9 +186,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     // step 0 into registers
     issue_scales(0);
 #pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
-        if (s < KT) issue_frags(s);
-    if (STAGES - 2 < KT) wait_vmcnt<(STAGES - 2) * LPW>(); else wait_vmcnt<0>();
+    for (int s = 0; s < STAGES - 1; ++s) {
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) issue_frag_one(min(s, KT - 1), smem + s * STAGE_BYTES, i);
+    }
+    wait_vmcnt<(STAGES - 2) * LPW>();
     block_barrier();
     read_scales(0, sx, sw);
 #pragma unroll
@@ -202,16 +206,24 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     constexpr int XPG = (TM + TN - 1) / TN;  // X-fragment reads folded in front of each group of TM MFMAs
     // The LDS reads for "the next step" are unconditional: in the very last step they fetch stale bytes of the ring
     // that nothing consumes, which keeps the step body free of branches (and of a second copy of the code).
-    auto step = [&](int kt, auto jtag) {
+    auto step = [&](int kt, auto jtag, auto wtag) {
         constexpr int J = decltype(jtag)::value;
+        constexpr int SKEW = (2 * decltype(wtag)::value) % TM;  // MFMA index inside a group after which this wave issues its loads
         constexpr int P = J & 1;
         constexpr bool batch_after = (J >= 1 && J <= STAGES - 3);
         constexpr int ALLOWED = (STAGES - 3) * LPW + (batch_after ? NS : 0);
-        if (kt + STAGES - 2 < KT) wait_vmcnt<ALLOWED>(); else wait_vmcnt<0>();
+        wait_vmcnt<ALLOWED>();
         wait_lgkmcnt0();
         block_barrier();
-        if constexpr (J == 0) issue_scales((kt >> 2) + 1);
-        if (kt + STAGES - 1 < KT) issue_frags(kt + STAGES - 1);
+        // The global -> LDS loads of stage kt+STAGES-1 (and, at J == 0, of the next scale batch) are spread over the
+        // groups of MFMAs: a wave issues in order, and a burst of vector-memory instructions at the top of the step
+        // would hold its MFMAs back while the CU's single address unit works through all four waves' bursts.
+        // Past the last stage the loads re-copy stage KT-1 into a ring slot nobody reads any more: the step body stays
+        // free of branches (which would let the compiler pull the MFMAs away from the loads they are meant to cover)
+        // and the vmcnt bookkeeping needs no special case for the tail.
+        const int kt_load = min(kt + STAGES - 1, KT - 1);
+        char* const load_base = smem + ((kt + STAGES - 1) % STAGES) * STAGE_BYTES;
+        constexpr int DPG = (LPW + TN - 1) / TN;  // loads per group
 #pragma unroll
         for (int i = 0; i < TN; ++i) {
             // W fragment two groups ahead (wraps into the next step), X fragments of the next step
@@ -220,7 +232,21 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
 #pragma unroll
             for (int j = i * XPG; j < (i + 1) * XPG && j < TM; ++j) read_x(kt + 1, std::integral_constant<int, 1 - P>{}, j);
 #pragma unroll
-            for (int j = 0; j < TM; ++j) acc[i][j] = mfma_fp4<J>(wring[i & 3], xf[P][j], acc[i][j], sw[i], sx[j]);
+            for (int j = 0; j < TM; ++j) {
+                acc[i][j] = mfma_fp4<J>(wring[i & 3], xf[P][j], acc[i][j], sw[i], sx[j]);
+                if (j == SKEW) {
+                    // the four waves of a workgroup run in lockstep (one barrier per step); issuing their loads at
+                    // different points of the group keeps them from queueing up behind each other at the CU's one
+                    // address unit while their MFMA pipes run dry
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int d = i * DPG; d < (i + 1) * DPG && d < LPW; ++d) {
+                        if constexpr (J == 0) issue_scale_one((kt >> 2) + 1, d);
+                        issue_frag_one(kt_load, load_base, d);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
             // keep the instruction scheduler from hoisting the later groups' LDS reads up here: that would rebuild a
             // full second copy of the W fragments in registers
             __builtin_amdgcn_sched_barrier(0);
@@ -229,15 +255,54 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
         if constexpr (J == 3) read_scales((kt >> 2) + 1, sx, sw);
     };
 
-    for (int kt0 = 0; kt0 < KT; kt0 += 4) {
-        step(kt0, std::integral_constant<int, 0>{});
-        if (kt0 + 1 < KT) step(kt0 + 1, std::integral_constant<int, 1>{});
-        if (kt0 + 2 < KT) step(kt0 + 2, std::integral_constant<int, 2>{});
-        if (kt0 + 3 < KT) step(kt0 + 3, std::integral_constant<int, 3>{});
+    auto main_loop = [&](auto wtag) {
+        for (int kt0 = 0; kt0 < KT; kt0 += 4) {
+            step(kt0, std::integral_constant<int, 0>{}, wtag);
+            if (kt0 + 1 < KT) step(kt0 + 1, std::integral_constant<int, 1>{}, wtag);
+            if (kt0 + 2 < KT) step(kt0 + 2, std::integral_constant<int, 2>{}, wtag);
+            if (kt0 + 3 < KT) step(kt0 + 3, std::integral_constant<int, 3>{}, wtag);
+        }
+    };
+    switch (wave & 3) {
+        case 0: main_loop(std::integral_constant<int, 0>{}); break;
+        case 1: main_loop(std::integral_constant<int, 1>{}); break;
+        case 2: main_loop(std::integral_constant<int, 2>{}); break;
+        default: main_loop(std::integral_constant<int, 3>{}); break;
     }
     wait_vmcnt<0>();  // the clamped last scale batch
 
-    // epilogue: lane owns out[m][n..n+3], m = m0 + 16*j + lane%16, n = n0 + 16*i + 4*(lane/16)
+    // Epilogue.  A lane owns out[m][n..n+3] with m = m0 + 16*j + lane%16, n = n0 + 16*i + 4*(lane/16): stored directly
+    // that is 16 rows x 32 bytes per instruction.  For bf16 output the wave tile is first transposed through LDS
+    // (free once the main loop is over) so that every store instruction writes 16 bytes per lane in whole rows.
+    constexpr int ROWB = WN * 2 + 16;  // padded row pitch: the 8-byte writes of 32 lanes then hit distinct banks
+    if constexpr (!OUT_F32 && NW * WM * ROWB <= STAGES * STAGE_BYTES + 2 * SCALE_BYTES) {
+        if ((g.N & 7) == 0) {
+            wait_lgkmcnt0();
+            block_barrier();  // every wave is done with the operand ring (and the last scale batch has landed)
+            char* const mine = smem + wave * (WM * ROWB);
+            typedef __bf16 v4bf __attribute__((ext_vector_type(4)));
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+#pragma unroll
+                for (int i = 0; i < TN; ++i) {
+                    const v4f v = acc[i][j];
+                    const v4bf p = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3]};
+                    *reinterpret_cast<v4bf*>(mine + (16 * j + (lane & 15)) * ROWB + (16 * i + 4 * (lane >> 4)) * 2) = p;
+                }
+            constexpr int CPR = WN / 8;  // 16-byte chunks per row
+            const int64_t m0 = (int64_t)tm * BM + wm * WM, n0 = (int64_t)tn * BN + wn * WN;
+#pragma unroll
+            for (int it = 0; it < WM * CPR / 64; ++it) {
+                const int c = it * 64 + lane;
+                const int row = c / CPR, ch = c % CPR;
+                const uint4 v = *reinterpret_cast<const uint4*>(mine + row * ROWB + ch * 16);
+                const int64_t m = m0 + row, n = n0 + ch * 8;
+                if (m < g.M && n < g.N) *reinterpret_cast<uint4*>(static_cast<__bf16*>(g.out) + m * g.N + n) = v;
+            }
+            return;
+        }
+    }
+    // direct stores (fp32 output, or N not a multiple of 8)
     const int64_t m_base = (int64_t)tm * BM + wm * WM + (lane & 15);
     const int64_t n_base = (int64_t)tn * BN + wn * WN + (lane >> 4) * 4;
 #pragma unroll
@@ -313,7 +378,7 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
         if (M <= 16) variant = 4;
         else if (M <= 64) variant = 3;
         else if (M <= 1024 || N < 2048) variant = 2;
-        else variant = 1;
+        else variant = 7;
     }
     switch (variant) {
         case 1: return launch_variant<256, 256, 128, 128, 4>(g, out_f32, st);
@@ -321,6 +386,8 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
         case 3: return launch_variant<64, 256, 64, 64, 4>(g, out_f32, st);
         case 4: return launch_variant<16, 256, 16, 64, 4>(g, out_f32, st);
         case 5: return launch_variant<256, 128, 128, 64, 4>(g, out_f32, st);
+        case 6: return launch_variant<256, 256, 128, 64, 4>(g, out_f32, st);
+        case 7: return launch_variant<256, 256, 64, 128, 4>(g, out_f32, st);
         default: return hipErrorInvalidValue;
     }
 }
