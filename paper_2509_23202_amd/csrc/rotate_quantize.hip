@@ -19,6 +19,8 @@
 #include "internal.hpp"
 #include "layout.hpp"
 
+#include <type_traits>
+
 namespace fp4mr {
 namespace {
 
@@ -122,11 +124,13 @@ template <int ND>
 __device__ __forceinline__ void store_codes(uint8_t* p, const uint32_t (&w)[ND])
 {
     if constexpr (ND == 1) {
-        *reinterpret_cast<uint32_t*>(p) = w[0];
+        __builtin_nontemporal_store(w[0], reinterpret_cast<uint32_t*>(p));
     } else if constexpr (ND == 2) {
-        *reinterpret_cast<uint2*>(p) = make_uint2(w[0], w[1]);
+        const v2i v = {(int)w[0], (int)w[1]};
+        __builtin_nontemporal_store(v, reinterpret_cast<v2i*>(p));
     } else {
-        *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+        const v4i v = {(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+        __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(p));
     }
 }
 
@@ -210,7 +214,12 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
 #pragma unroll
             for (int s = 0; s < S; ++s) {
                 v4i z = {0, 0, 0, 0};
-                xin[u][s] = valid[u] ? *reinterpret_cast<const v4i*>(x + ebase[u] + 32 * s + 8 * q) : z;
+                if constexpr (LAYOUT == 0 && S == 1) {
+                    // streamed once, whole cache lines per instruction: keep it out of the caches
+                    xin[u][s] = valid[u] ? __builtin_nontemporal_load(reinterpret_cast<const v4i*>(x + ebase[u] + 32 * s + 8 * q)) : z;
+                } else {
+                    xin[u][s] = valid[u] ? *reinterpret_cast<const v4i*>(x + ebase[u] + 32 * s + 8 * q) : z;
+                }
             }
         }
 #pragma unroll
@@ -271,6 +280,160 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
         if (lane == 0) {
             const float ymax = __fmaf_rn(hmax, a.c_hi, hmax * a.c_lo);  // monotone: max|y| = y(max|h|)
             atomicMax(a.amax_bits, __float_as_uint(ymax));
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------
+// GEMM-layout writer for b' in {32, 64} (the hot path in front of the GEMM).  Same arithmetic as rq_mfma_kernel,
+// different data movement, shaped for HBM:
+//   * a work item is 16 rows x 512 K = four fragments of one row-block; the 16 vectors of a supertile are taken as
+//     (16/VPR rows) x (VPR = 128/b' consecutive vectors), so one load instruction reads 256 contiguous bytes per row;
+//   * packed codes are staged through 1 KB of LDS per wave and leave as ONE 16-byte-per-lane store per fragment
+//     (1 KB contiguous, the fragment itself);
+//   * scale bytes are staged likewise and leave as whole dwords (MXFP4: the four fragments of the item complete
+//     each lane's dword; NVFP4: 128 bytes per fragment).
+// Input loads and all stores are non-temporal: every byte is touched exactly once.
+template <int BP, int G, bool HW>
+__global__ __launch_bounds__(kThreads) void rq_frag_kernel(RqArgs a)
+{
+    constexpr int S = BP / 32, T = BP / 16, NO = BP / 4;
+    constexpr int VPR = 128 / BP;        // vectors per row per fragment
+    constexpr int RPS = 16 / VPR;        // rows per supertile
+    constexpr int NSTF = VPR;            // supertiles per fragment
+    using GQ = GroupQuant<G, NO, 16, HW>;
+
+    __shared__ __attribute__((aligned(16))) uint32_t stage_codes[kWavesPerBlock][256];
+    __shared__ __attribute__((aligned(16))) uint8_t stage_scales[kWavesPerBlock][256];
+
+    const int lane = threadIdx.x & 63;
+    const int wib = threadIdx.x >> 6;
+    const int g = lane & 15, q = lane >> 4;
+    const int r_in = g / VPR, vb = g % VPR;
+    const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + wib;
+    const int64_t n_waves = (int64_t)gridDim.x * kWavesPerBlock;
+
+    v8bf hop[T][S];
+    {
+        const int bm = a.b - 1;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int c = (g >> 2) * NO + 4 * t + (g & 3);
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                typedef unsigned short v8us __attribute__((ext_vector_type(8)));
+                v8us bits;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int r = 32 * s + 8 * q + e;
+                    const bool same = (r & ~bm) == (c & ~bm);
+                    const unsigned sgn = __popc((unsigned)(r & c & bm)) & 1u;
+                    bits[e] = same ? (unsigned short)(0x3f80u | (sgn << 15)) : (unsigned short)0;
+                }
+                hop[t][s] = __builtin_bit_cast(v8bf, bits);
+            }
+        }
+    }
+
+    const int KC = (int)(a.K >> 7), KS = (int)((a.K + 511) >> 9);
+    const uint16_t* __restrict__ x = static_cast<const uint16_t*>(a.x);
+    float s_T = 0.0f;
+    if constexpr (G == 16) {
+        s_T = a.static_scale ? *a.tensor_scale : __fdiv_rn(__uint_as_float(*a.amax_bits), 2688.0f);
+        if (!a.static_scale && blockIdx.x == 0 && threadIdx.x == 0) *a.tensor_scale = s_T;
+    }
+
+    uint32_t* const sc_codes = stage_codes[wib];
+    uint8_t* const sc_scales = stage_scales[wib];
+
+    for (int64_t item = wave; item < a.n_items; item += n_waves) {
+        const int64_t rb = item / KS;
+        const int ks = (int)(item - rb * KS);
+        const int nfrag = min(4, KC - 4 * ks);
+        v4i xin[2][NSTF][S];
+        auto load_frag = [&](int f, auto ptag) {
+            constexpr int P = decltype(ptag)::value;
+            const int64_t kbase = (int64_t)(4 * ks + f) * 128 + vb * BP + 8 * q;
+#pragma unroll
+            for (int u = 0; u < NSTF; ++u) {
+                const int64_t row = rb * 16 + u * RPS + r_in;
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    v4i z = {0, 0, 0, 0};
+                    const v4i* p = reinterpret_cast<const v4i*>(x + row * a.K + kbase + 32 * s);
+                    if constexpr (S == 1) xin[P][u][s] = (row < a.rows) ? __builtin_nontemporal_load(p) : z;
+                    else xin[P][u][s] = (row < a.rows) ? *p : z;
+                }
+            }
+        };
+        auto compute_frag = [&](int f, auto ptag) {
+            constexpr int P = decltype(ptag)::value;
+            const int kc = 4 * ks + f;
+#pragma unroll
+            for (int u = 0; u < NSTF; ++u) {
+                v4f acc[T];
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    acc[t] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int s = 0; s < S; ++s)
+                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hop[t][s], __builtin_bit_cast(v8bf, xin[P][u][s]), acc[t], 0, 0, 0);
+                }
+                float y[NO];
+#pragma unroll
+                for (int t = 0; t < T; ++t)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float h = acc[t][v];
+                        y[4 * t + v] = __fmaf_rn(h, a.c_hi, h * a.c_lo);
+                    }
+                uint32_t out[GQ::ND], sc[GQ::NG];
+                if constexpr (G == 32) GQ::mx(y, out, sc); else GQ::nv(y, s_T, out, sc);
+                // position inside the fragment: element offset e0 of row rr
+                const int rr = u * RPS + r_in;
+                const int e0 = vb * BP + q * NO;
+                const int d = (((e0 >> 5) * 16 + rr) << 2) + ((e0 & 31) >> 3);
+                if constexpr (GQ::ND == 1) sc_codes[d] = out[0];
+                else *reinterpret_cast<uint2*>(sc_codes + d) = make_uint2(out[0], out[1]);
+                if ((q % GQ::LG) == 0) {
+                    if constexpr (G == 32) {
+                        sc_scales[(((e0 >> 5) * 16 + rr) << 2) + f] = (uint8_t)sc[0];
+                    } else {
+#pragma unroll
+                        for (int gi = 0; gi < GQ::NG; ++gi) {
+                            const int g16 = (e0 >> 4) + gi;
+                            sc_scales[(((g16 >> 1) * 16 + rr) << 1) + (g16 & 1)] = (uint8_t)sc[gi];
+                        }
+                    }
+                }
+            }
+            // the fragment leaves in one piece
+            const v4i frag = *reinterpret_cast<const v4i*>(sc_codes + lane * 4);
+            __builtin_nontemporal_store(frag, reinterpret_cast<v4i*>(a.codes + ((rb * KC + kc) * 1024 + lane * 16)));
+            if constexpr (G == 16) {
+                if (lane < 32) {
+                    const uint32_t w = *reinterpret_cast<const uint32_t*>(sc_scales + lane * 4);
+                    __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(a.scales + ((rb * KC + kc) * 128 + lane * 4)));
+                }
+            }
+        };
+
+        load_frag(0, std::integral_constant<int, 0>{});
+        if (nfrag > 1) load_frag(1, std::integral_constant<int, 1>{});
+        compute_frag(0, std::integral_constant<int, 0>{});
+        if (nfrag > 1) {
+            if (nfrag > 2) load_frag(2, std::integral_constant<int, 0>{});
+            compute_frag(1, std::integral_constant<int, 1>{});
+            if (nfrag > 2) {
+                if (nfrag > 3) load_frag(3, std::integral_constant<int, 1>{});
+                compute_frag(2, std::integral_constant<int, 0>{});
+                if (nfrag > 3) compute_frag(3, std::integral_constant<int, 1>{});
+            }
+        }
+        if constexpr (G == 32) {
+            // bytes of fragments past the end of K (K/128 not a multiple of 4) are padding: never read
+            const uint32_t w = *reinterpret_cast<const uint32_t*>(sc_scales + lane * 4);
+            __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(a.scales + ((rb * KS + ks) * 256 + lane * 4)));
         }
     }
 }
@@ -365,9 +528,22 @@ __global__ __launch_bounds__(kThreads) void q_direct_kernel(RqArgs a)
 __global__ void fill_u32_kernel(uint32_t* p, uint32_t v) { *p = v; }
 
 // ------------------------------------------------------------------------------------------------------
+template <int BP, int G, bool HW>
+hipError_t launch_frag(const RqArgs& a0, int grid_cap, hipStream_t st)
+{
+    RqArgs a = a0;
+    a.n_items = round_up(a.rows, 16) / 16 * ((a.K + 511) / 512);
+    int64_t blocks = (a.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks > grid_cap) blocks = grid_cap;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL((rq_frag_kernel<BP, G, HW>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
+    return hipGetLastError();
+}
+
 template <int BP, int G, int LAYOUT, int PASS, bool HW>
 hipError_t launch_mfma(const RqArgs& a0, int grid_cap, hipStream_t st)
 {
+    if constexpr (LAYOUT == 1 && PASS == 0 && BP <= 64) return launch_frag<BP, G, HW>(a0, grid_cap, st);
     // two fragments' worth of loads in flight per wave for the widest block (canonical order only: there an
     // item may run past the end and is masked per vector; GEMM-order items are whole fragments)
     constexpr int FR = (BP == 128 && LAYOUT == 0) ? 2 : 1;
