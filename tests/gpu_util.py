@@ -30,11 +30,11 @@ def grid_steps(ca: np.ndarray, cb: np.ndarray) -> np.ndarray:
     return np.abs(pos(ca) - pos(cb))
 
 
-def gemm_layout_to_canonical(codes_g: np.ndarray, scales_g: np.ndarray, rows: int, K: int, fmt: int):
-    """Undo the GEMM layout as documented in include/fp4mr.h / csrc/layout.hpp.  Returns canonical
-    codes [rows,K/2] and scales [rows,K/G]."""
+def gemm_layout_to_canonical(codes_g: np.ndarray, scales_g: np.ndarray, rows, K: int, fmt: int):
+    """Undo the GEMM layout as documented in include/fp4mr.h / csrc/layout.hpp.  `rows` is a row count (all rows)
+    or an array of row indices (a sample).  Returns canonical codes [len(rows),K/2] and scales [len(rows),K/G]."""
     KC = K // 128
-    r = np.arange(rows)[:, None]
+    r = (np.arange(rows) if np.isscalar(rows) else np.asarray(rows, dtype=np.int64))[:, None]
     kb = np.arange(K // 2)[None, :]          # byte index along the row; element k = 2*kb
     k = 2 * kb
     off = ((r // 16) * KC + k // 128) * 1024 + (((k % 128) // 32) * 16 + r % 16) * 16 + (k % 32) // 2

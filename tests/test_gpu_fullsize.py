@@ -1,0 +1,126 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times (GEMM-layout operands, default
+tile selection), on samples the oracle can compute row by row: MXFP4 rows are quantized independently, so a sample
+of rows of X and W is re-encoded by the oracle and the corresponding sub-block of Y recomputed in fp64.
+NVFP4 needs the tensor abs-max: the oracle rotates the whole tensor for it (cheap) and encodes the sampled rows."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2509_23202_amd import inputs
+from tests.gpu_util import MX, NV, compare_codes, gemm_layout_to_canonical, to_dev_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def fp4():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2509_23202_amd import binding
+    return binding
+
+
+def np_(t):
+    return t.detach().cpu().numpy()
+
+
+def sample_rows(n, count, rng):
+    """first / last rows, tile boundaries and random ones"""
+    fixed = [0, 1, 15, 16, 255, 256, n - 257, n - 17, n - 16, n - 1]
+    fixed = [v for v in fixed if 0 <= v < n]
+    extra = rng.choice(n, size=max(0, count - len(fixed)), replace=False) if n > count else np.arange(n)
+    return np.unique(np.concatenate([np.array(fixed, dtype=np.int64), extra.astype(np.int64)]))[:max(count, len(fixed))]
+
+
+def oracle_rows(oracle, bits_rows, b, fmt, tensor_scale=None):
+    y = oracle.rotate(bits_rows, b)
+    c, s, T = oracle.quantize(y, fmt, tensor_scale)
+    return c, s, T, y
+
+
+def check_layer(fp4, oracle, recipe, M, K, N, fmt, b, n_m=40, n_n=56, salt=0):
+    import torch
+    rng = np.random.default_rng(K + N + M)
+    xb, wb = recipe.x(M, K, salt=salt), recipe.w(N, K, salt=salt)
+    say(f"full-size layer fmt={fmt} b={b} M={M} K={K} N={N}")
+    qa = fp4.fp4_rotate_quantize(to_dev_bf16(xb), b, fmt, flags=fp4.LAYOUT_GEMM)
+    qw = fp4.fp4_quantize_weights(to_dev_bf16(wb), b, fmt, flags=fp4.LAYOUT_GEMM)
+    out = fp4.fp4_gemm(qa[0], qa[1], qa[2], qw[0], qw[1], qw[2], M, N, K, fmt, flags=fp4.A_LAYOUT_GEMM | fp4.W_LAYOUT_GEMM)
+    torch.cuda.synchronize()
+    mi, ni = sample_rows(M, n_m, rng), sample_rows(N, n_n, rng)
+    ac, asc = gemm_layout_to_canonical(np_(qa[0]), np_(qa[1]), mi, K, fmt)
+    wc, wsc = gemm_layout_to_canonical(np_(qw[0]), np_(qw[1]), ni, K, fmt)
+    aT = wT = None
+    if fmt == NV:
+        # tensor scales from the oracle's own rotation of the whole tensors
+        aT_ref = np.float32(np.abs(oracle.rotate(xb, b)).max()) / np.float32(2688.0)
+        wT_ref = np.float32(np.abs(oracle.rotate(wb, b)).max()) / np.float32(2688.0)
+        aT, wT = np_(qa[2])[0], np_(qw[2])[0]
+        assert abs(float(aT) - float(aT_ref)) <= 2 * np.spacing(aT_ref)
+        assert abs(float(wT) - float(wT_ref)) <= 2 * np.spacing(wT_ref)
+        rac, rasc, _, ya = oracle_rows(oracle, xb[mi], b, fmt, float(aT))
+        rwc, rwsc, _, yw = oracle_rows(oracle, wb[ni], b, fmt, float(wT))
+    else:
+        rac, rasc, _, ya = oracle_rows(oracle, xb[mi], b, fmt)
+        rwc, rwsc, _, yw = oracle_rows(oracle, wb[ni], b, fmt)
+    fa, _ = compare_codes(ac, asc, rac, rasc, ya, fmt)
+    fw, _ = compare_codes(wc, wsc, rwc, rwsc, yw, fmt)
+    Y, S = oracle.matmul(oracle.dequantize(ac, asc, fmt, aT), oracle.dequantize(wc, wsc, fmt, wT))
+    got = np_(out[torch.from_numpy(mi).cuda()][:, torch.from_numpy(ni).cuda()].float()).astype(np.float64)
+    err = np.abs(got - Y)
+    tol = 1e-3 * S + np.abs(Y) * 2.0 ** -8
+    say(f"   code mismatch X {fa:.1e} W {fw:.1e}; max err/(1e-3 S) = {float((err / (1e-3 * S)).max()):.3f}")
+    assert np.all(err <= tol)
+
+
+@pytest.mark.parametrize("layer", [1, 3, 0])
+def test_prefill_layers_mxfp4(fp4, oracle, layer):
+    L = inputs.LLAMA3_8B_LAYERS[layer]
+    check_layer(fp4, oracle, inputs.RECIPES[3], 4096, L.K, L.N, MX, 32, salt=layer)
+
+
+@pytest.mark.parametrize("M", [1, 16])
+@pytest.mark.parametrize("layer", [0, 2, 3])
+def test_decode_layers_mxfp4(fp4, oracle, layer, M):
+    L = inputs.LLAMA3_8B_LAYERS[layer]
+    check_layer(fp4, oracle, inputs.RECIPES[2], M, L.K, L.N, MX, 32, n_m=M, salt=layer)
+
+
+def test_config1_whole_output(fp4, oracle):
+    """configs[0]: M=64, K=N=4096, every output element."""
+    check_layer(fp4, oracle, inputs.RECIPES[1], 64, 4096, 4096, MX, 32, n_m=64, n_n=4096)
+
+
+@pytest.mark.parametrize("M", [16, 4096])
+def test_nvfp4_70b_qkv_layer(fp4, oracle, M):
+    L = inputs.LLAMA3_70B_LAYERS[0]
+    check_layer(fp4, oracle, inputs.RECIPES[4], M, L.K, L.N, NV, 16, n_m=min(M, 32), n_n=48)
+
+
+@pytest.mark.parametrize("b", [16, 32, 64, 128])
+def test_block_sweep_2048_8192(fp4, oracle, b):
+    check_layer(fp4, oracle, inputs.RECIPES[5], 2048, 8192, 8192, MX, b, n_m=24, n_n=32, salt=b)
+
+
+def test_standalone_rotate_quantize_16384_8192(fp4, oracle):
+    import torch
+    r = inputs.RECIPES[6]
+    M, K = 16384, 8192
+    xb = r.x(M, K)
+    say("standalone rotate+quantize 16384 x 8192 (Laplace, outlier channels)")
+    for flags in (fp4.LAYOUT_GEMM, 0):
+        c, s, _ = fp4.fp4_rotate_quantize(to_dev_bf16(xb), 32, MX, flags=flags)
+        torch.cuda.synchronize()
+        mi = sample_rows(M, 64, np.random.default_rng(1))
+        if flags:
+            gc, gs = gemm_layout_to_canonical(np_(c), np_(s), mi, K, MX)
+        else:
+            gc, gs = np_(c).reshape(M, -1)[mi], np_(s).reshape(M, -1)[mi]
+        rc, rs, _, y = oracle_rows(oracle, xb[mi], 32, MX)
+        compare_codes(gc, gs, rc, rs, y, MX)
