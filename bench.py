@@ -26,6 +26,11 @@ PEAK_FP4_TFLOPS = 10100.0     # MI355X dense FP4/FP6 MFMA
 PEAK_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 RQ_BYTES_PER_ELEM_MX = 2.0 + 0.5 + 1.0 / 32.0   # bf16 in, 4-bit code out, one scale byte per 32
+# HBM-side bytes per launch from hardware counters (FETCH_SIZE, WRITE_SIZE; two rocprofv3 --pmc runs of this script,
+# each scaled by the reading for a plain 1 GiB device copy: x2.000 and x1.000).  Summary and commands:
+# profiles/hbm_traffic__llama3_8b_prefill_m4096_and_rq_16384x8192__pmc.txt
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 264.5e6    # mean over the four GEMMs of a step: 176.4 MB fetched + 88.1 MB written
+RQ_TRAFFIC_BYTES_PER_LAUNCH = 338.7e6      # [16384, 8192]: 267.6 MB fetched + 71.0 MB written (algorithmic: 339.7 MB)
 
 
 def parse():
@@ -36,6 +41,8 @@ def parse():
     ap.add_argument("--tokens", type=int, default=4096, help="M of the prefill workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the bf16 baseline and the standalone rotate+quantize figure")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference point for HBM-traffic counters under a profiler)")
     return ap.parse_args()
 
 
@@ -136,7 +143,7 @@ def main():
         e1.record()
         cal.append((e0, e1))
     torch.cuda.synchronize()
-    TINY_KERNEL_MS = 0.002  # the calibration launch itself (one wave, one fragment)
+    TINY_KERNEL_MS = 0.0035  # the calibration launch itself (one wave, one fragment; 3.4-4.1 us in a kernel trace)
     bracket_ms = max(0.0, float(np.median([a.elapsed_time(b_) for a, b_ in cal])) - TINY_KERNEL_MS)
     ev = []
     t0 = time.perf_counter()
@@ -170,7 +177,8 @@ def main():
     achieved = flops_step / (gemm_ms_total * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "gemm_mx_kernel (v_mfma_scale_f32_16x16x128_f8f6f4, E2M1 x E2M1)",
                 "achieved": round(achieved, 1), "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP4_TFLOPS, 4),
-                "avg_launch_us": round(avg_gemm_ms * 1e3, 2), "launches_per_step": n_launch, "traffic": None,
+                "avg_launch_us": round(avg_gemm_ms * 1e3, 2), "launches_per_step": n_launch,
+                "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH if M == 4096 else None,
                 "timing": "HIP events around one launch per step inside the timed region, minus the event-bracket overhead "
                           f"({bracket_ms * 1e3:.1f} us, calibrated on a 2 KB launch)"}
 
@@ -227,8 +235,15 @@ def main():
         result["roofline_rotate_quantize"] = {"bound": "hbm", "kernel": "rq_frag_kernel<32, MXFP4> (GEMM layout)",
                                               "workload": "X bf16 [16384, 8192], Laplace(0,1), 1% outlier channels x100, block 32",
                                               "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
-                                              "avg_launch_us": round(ms * 1e3, 2), "traffic": None}
+                                              "avg_launch_us": round(ms * 1e3, 2), "traffic": RQ_TRAFFIC_BYTES_PER_LAUNCH}
         del xs
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(recipe, layers[2], min(M, 4096), 16384)
