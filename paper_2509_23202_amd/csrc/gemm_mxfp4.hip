@@ -86,7 +86,7 @@ __device__ __forceinline__ void remap_block(int bid, int nblocks, int tiles_m, i
     tn = in_band / gsz;
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, bool OUT_F32>
+template <int BM, int BN, int WM, int WN, int STAGES, bool OUT_F32, int RD = 2>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(GemmArgs g)
 {
     constexpr int NWM = BM / WM, NWN = BN / WN, NW = NWM * NWN;
@@ -146,8 +146,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     // Software pipeline of the LDS reads: the X fragments of step kt+1 are read into the other half of xf[2][.]
     // while step kt computes, and the W fragments run through a 4-deep register ring two groups of TM MFMAs ahead
     // of their use -- so no MFMA waits on LDS latency, at a cost of 2*TM*4 + 16 fragment registers.
-    v4i xf[2][TM], wring[4];
-    static_assert(TN % 4 == 0, "the W-fragment ring index must be static");
+    constexpr int RING = (RD <= 3) ? 4 : 8;  // W-fragment register ring; RD = how many MFMA groups ahead it is filled
+    v4i xf[2][TM], wring[RING];
+    static_assert(TN % RING == 0 && RD < RING && RD <= TN, "the W-fragment ring index must be static");
     // every wave issues exactly LPW fragment loads per stage and NS scale loads per batch so that the vmcnt
     // bookkeeping is uniform; when F is not a multiple of NW the spare slots re-copy the last fragment (same bytes
     // to the same place)
@@ -179,7 +180,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
         xf[P][j] = *(reinterpret_cast<const v4i*>(smem + (kt % STAGES) * STAGE_BYTES + (wm * TM + j) * 1024) + lane);
     };
     auto read_w = [&](int kt, int i) {  // into ring slot i % 4 (i is a compile-time constant after unrolling)
-        wring[i & 3] = *(reinterpret_cast<const v4i*>(smem + (kt % STAGES) * STAGE_BYTES + (FX + wn * TN + i) * 1024) + lane);
+        wring[i & (RING - 1)] = *(reinterpret_cast<const v4i*>(smem + (kt % STAGES) * STAGE_BYTES + (FX + wn * TN + i) * 1024) + lane);
     };
 
     // prologue: scales of super-step 0, then STAGES-1 stages; scales, X fragments and the first two W fragments of
@@ -195,8 +196,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     read_scales(0, sx, sw);
 #pragma unroll
     for (int j = 0; j < TM; ++j) read_x(0, std::integral_constant<int, 0>{}, j);
-    read_w(0, 0);
-    read_w(0, 1);
+#pragma unroll
+    for (int i = 0; i < RD; ++i) read_w(0, i);
 
     // One K-step.  J = kt % 4 selects the scale byte (op_sel) and the X register half (J & 1).
     //   top:    stage kt+1 must have landed (this wave's copies: vmcnt; everybody's: barrier).  The same barrier
@@ -227,13 +228,13 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
 #pragma unroll
         for (int i = 0; i < TN; ++i) {
             // W fragment two groups ahead (wraps into the next step), X fragments of the next step
-            if (i + 2 < TN) read_w(kt, i + 2);
-            else read_w(kt + 1, i + 2 - TN);
+            if (i + RD < TN) read_w(kt, i + RD);
+            else read_w(kt + 1, i + RD - TN);
 #pragma unroll
             for (int j = i * XPG; j < (i + 1) * XPG && j < TM; ++j) read_x(kt + 1, std::integral_constant<int, 1 - P>{}, j);
 #pragma unroll
             for (int j = 0; j < TM; ++j) {
-                acc[i][j] = mfma_fp4<J>(wring[i & 3], xf[P][j], acc[i][j], sw[i], sx[j]);
+                acc[i][j] = mfma_fp4<J>(wring[i & (RING - 1)], xf[P][j], acc[i][j], sw[i], sx[j]);
                 if (j == SKEW) {
                     // the four waves of a workgroup run in lockstep (one barrier per step); issuing their loads at
                     // different points of the group keeps them from queueing up behind each other at the CU's one
@@ -295,9 +296,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
             for (int it = 0; it < WM * CPR / 64; ++it) {
                 const int c = it * 64 + lane;
                 const int row = c / CPR, ch = c % CPR;
-                const uint4 v = *reinterpret_cast<const uint4*>(mine + row * ROWB + ch * 16);
+                const v4i v = *reinterpret_cast<const v4i*>(mine + row * ROWB + ch * 16);
                 const int64_t m = m0 + row, n = n0 + ch * 8;
-                if (m < g.M && n < g.N) *reinterpret_cast<uint4*>(static_cast<__bf16*>(g.out) + m * g.N + n) = v;
+                if (m < g.M && n < g.N) __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(static_cast<__bf16*>(g.out) + m * g.N + n));
             }
             return;
         }
@@ -337,7 +338,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     }
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES>
+template <int BM, int BN, int WM, int WN, int STAGES, int RD = 2>
 hipError_t launch_variant(const GemmArgs& g0, bool out_f32, hipStream_t st)
 {
     GemmArgs g = g0;
@@ -348,11 +349,11 @@ hipError_t launch_variant(const GemmArgs& g0, bool out_f32, hipStream_t st)
     const dim3 grid((unsigned)(g.tiles_m * g.tiles_n));
     hipError_t e;
     if (out_f32) {
-        auto k = gemm_mx_kernel<BM, BN, WM, WN, STAGES, true>;
+        auto k = gemm_mx_kernel<BM, BN, WM, WN, STAGES, true, RD>;
         if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, dim3(threads), lds, st, g);
     } else {
-        auto k = gemm_mx_kernel<BM, BN, WM, WN, STAGES, false>;
+        auto k = gemm_mx_kernel<BM, BN, WM, WN, STAGES, false, RD>;
         if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, dim3(threads), lds, st, g);
     }
@@ -378,7 +379,7 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
         if (M <= 16) variant = 4;
         else if (M <= 64) variant = 3;
         else if (M <= 1024 || N < 2048) variant = 2;
-        else variant = 7;
+        else variant = 10;
     }
     switch (variant) {
         case 1: return launch_variant<256, 256, 128, 128, 4>(g, out_f32, st);
@@ -388,6 +389,9 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
         case 5: return launch_variant<256, 128, 128, 64, 4>(g, out_f32, st);
         case 6: return launch_variant<256, 256, 128, 64, 4>(g, out_f32, st);
         case 7: return launch_variant<256, 256, 64, 128, 4>(g, out_f32, st);
+        case 8: return launch_variant<256, 256, 128, 128, 4, 4>(g, out_f32, st);
+        case 9: return launch_variant<256, 256, 128, 128, 4, 6>(g, out_f32, st);
+        case 10: return launch_variant<256, 256, 64, 128, 4, 3>(g, out_f32, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -199,7 +199,7 @@ def test_gemm_gemm_layout_operands_bf16_out(fp4, oracle, fmt):
     _gemm_case(fp4, oracle, fmt, 200, 520, 1024 + 384, seed=5, out_f32=False, layout_gemm=True)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
 def test_gemm_mxfp4_every_tile_variant(fp4, oracle, variant, monkeypatch):
     monkeypatch.setenv("FP4MR_GEMM_VARIANT", str(variant))
     _gemm_case(fp4, oracle, MX, 272, 528, 1280, seed=variant, out_f32=True, layout_gemm=True)
