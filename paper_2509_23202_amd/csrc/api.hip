@@ -120,11 +120,13 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
         w_scales = s;
     }
     const bool out_f32 = (flags & FP4MR_OUT_F32) != 0;
-    if (fmt == FP4MR_MXFP4)
-        e = launch_gemm_mxfp4(a_codes, a_scales, w_codes, w_scales, M, N, K, out, out_f32, env_int("FP4MR_GEMM_VARIANT", 0), st);
+    const int variant = env_int("FP4MR_GEMM_VARIANT", 0);
+    if (M <= 64 && variant == 0)
+        e = launch_gemm_skinny(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M, N, K, (int)fmt, out, out_f32, st);
+    else if (fmt == FP4MR_MXFP4)
+        e = launch_gemm_mxfp4(a_codes, a_scales, w_codes, w_scales, M, N, K, out, out_f32, variant, st);
     else
-        e = launch_gemm_nvfp4(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M, N, K, out, out_f32,
-                              env_int("FP4MR_GEMM_VARIANT", 0), st);
+        e = launch_gemm_nvfp4(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M, N, K, out, out_f32, variant, st);
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
 }
 

@@ -18,6 +18,7 @@
 #include "device_util.hpp"
 #include "internal.hpp"
 #include "layout.hpp"
+#include "nv_dequant.hpp"
 
 namespace fp4mr {
 namespace {
@@ -50,35 +51,6 @@ __device__ __forceinline__ void block_barrier()
 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_void;
-
-// 8 codes (one dword) times one scale -> 8 fp16
-__device__ __forceinline__ v8h dequant8(uint32_t codes, v2h scale2)
-{
-    // byte i of the dword: low nibble -> .x, high nibble -> .y
-    const v2h p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 1.0f, 0) * scale2;
-    const v2h p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 1.0f, 1) * scale2;
-    const v2h p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 1.0f, 2) * scale2;
-    const v2h p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 1.0f, 3) * scale2;
-    const v8h r = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
-    return r;
-}
-
-struct Frag16 {
-    v8h s[4];
-};
-
-__device__ __forceinline__ Frag16 dequant_frag(const v4i& codes, uint32_t scale_bytes)
-{
-    const _Float16 s0 = (_Float16)e4m3_decode<true>(scale_bytes & 0xffu);
-    const _Float16 s1 = (_Float16)e4m3_decode<true>((scale_bytes >> 8) & 0xffu);
-    const v2h a = {s0, s0}, b = {s1, s1};
-    Frag16 f;
-    f.s[0] = dequant8((uint32_t)codes[0], a);
-    f.s[1] = dequant8((uint32_t)codes[1], a);
-    f.s[2] = dequant8((uint32_t)codes[2], b);
-    f.s[3] = dequant8((uint32_t)codes[3], b);
-    return f;
-}
 
 template <int BM, int BN, int WM, int WN, int STAGES, bool OUT_F32>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_nv_kernel(NvGemmArgs g)
@@ -153,20 +125,20 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_nv_kernel(NvG
         if (kt + STAGES - 1 < KT) issue(kt + STAGES - 1);
 
         const char* base = smem + (kt % STAGES) * STAGE_BYTES;
-        Frag16 xf[TM];
+        NvFrag16 xf[TM];
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
             const int f = wm * TM + j;
             const v4i c = *(reinterpret_cast<const v4i*>(base + f * 1024) + lane);
             const uint32_t sc = *(reinterpret_cast<const uint16_t*>(base + SCALE_OFF + f * 128) + lane);
-            xf[j] = dequant_frag(c, sc);
+            xf[j] = nv_dequant_frag(c, sc);
         }
 #pragma unroll
         for (int i = 0; i < TN; ++i) {
             const int f = FX + wn * TN + i;
             const v4i c = *(reinterpret_cast<const v4i*>(base + f * 1024) + lane);
             const uint32_t sc = *(reinterpret_cast<const uint16_t*>(base + SCALE_OFF + f * 128) + lane);
-            const Frag16 wf = dequant_frag(c, sc);
+            const NvFrag16 wf = nv_dequant_frag(c, sc);
 #pragma unroll
             for (int j = 0; j < TM; ++j)
 #pragma unroll

@@ -24,4 +24,9 @@ hipError_t launch_gemm_nvfp4(const void* a_codes, const void* a_scales, const fl
                              const void* w_scales, const float* w_ts, int64_t M, int64_t N, int64_t K, void* out,
                              bool out_f32, int variant, hipStream_t st);
 
+// few-token (M <= 64) weight-streaming GEMM, both formats, operands in GEMM layout
+hipError_t launch_gemm_skinny(const void* a_codes, const void* a_scales, const float* a_ts, const void* w_codes,
+                              const void* w_scales, const float* w_ts, int64_t M, int64_t N, int64_t K, int fmt, void* out,
+                              bool out_f32, hipStream_t st);
+
 }  // namespace fp4mr

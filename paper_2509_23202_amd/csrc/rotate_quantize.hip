@@ -543,7 +543,11 @@ hipError_t launch_frag(const RqArgs& a0, int grid_cap, hipStream_t st)
 template <int BP, int G, int LAYOUT, int PASS, bool HW>
 hipError_t launch_mfma(const RqArgs& a0, int grid_cap, hipStream_t st)
 {
-    if constexpr (LAYOUT == 1 && PASS == 0 && BP <= 64) return launch_frag<BP, G, HW>(a0, grid_cap, st);
+    if constexpr (LAYOUT == 1 && PASS == 0 && BP <= 64) {
+        // The fragment-shaped kernel walks 16 rows x 512 K per wave, which is what HBM likes for big tensors; a
+        // few-token call has too few of those items to fill the GPU, so it keeps the one-fragment-per-wave kernel.
+        if (round_up(a0.rows, 16) / 16 * ((a0.K + 511) / 512) >= 1024) return launch_frag<BP, G, HW>(a0, grid_cap, st);
+    }
     // two fragments' worth of loads in flight per wave for the widest block (canonical order only: there an
     // item may run past the end and is masked per vector; GEMM-order items are whole fragments)
     constexpr int FR = (BP == 128 && LAYOUT == 0) ? 2 : 1;
