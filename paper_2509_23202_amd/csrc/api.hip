@@ -34,7 +34,8 @@ int group_of(fp4mr_fmt_t fmt) { return fmt == FP4MR_MXFP4 ? 32 : 16; }
 
 size_t quant_workspace(fp4mr_fmt_t fmt, uint32_t flags)
 {
-    return (fmt == FP4MR_NVFP4 && !(flags & FP4MR_STATIC_TENSOR_SCALE)) ? 256 : 0;
+    // 256 bytes for the tensor abs-max plus one 4-byte partial per wave of the abs-max pass (1024 blocks x 4 waves)
+    return (fmt == FP4MR_NVFP4 && !(flags & FP4MR_STATIC_TENSOR_SCALE)) ? 256 + 4096 * 4 : 0;
 }
 
 size_t repack_bytes(int64_t rows, int64_t K, fp4mr_fmt_t fmt)

@@ -26,6 +26,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWavesPerBlock = kThreads / kWave;
+constexpr int kAmaxPassBlocks = 1024;  // grid cap of the NVFP4 abs-max pass (4096 partials)
 
 struct RqArgs {
     const void* x;
@@ -33,6 +34,7 @@ struct RqArgs {
     uint8_t* scales;
     float* tensor_scale;   // NVFP4: s_T (written by the quantize pass unless static)
     uint32_t* amax_bits;   // NVFP4 dynamic: bit pattern of max |y| over the tensor (workspace)
+    uint32_t* amax_partial;  // NVFP4 dynamic: one partial maximum per wave of the abs-max pass (workspace)
     int64_t rows, K;
     int64_t n_items;
     int b;                 // Hadamard block (1 = none)
@@ -274,12 +276,12 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
         }
     }
     if constexpr (PASS == 1) {
-        // wave max -> one atomic per wave.  max is order-independent, so the result is deterministic.
+        // wave max -> one slot per wave (no atomics: thousands of waves finish together and would queue on one address)
 #pragma unroll
         for (int m = 1; m < 64; m <<= 1) hmax = fmaxf(hmax, __shfl_xor(hmax, m));
         if (lane == 0) {
             const float ymax = __fmaf_rn(hmax, a.c_hi, hmax * a.c_lo);  // monotone: max|y| = y(max|h|)
-            atomicMax(a.amax_bits, __float_as_uint(ymax));
+            a.amax_partial[wave] = __float_as_uint(ymax);  // one slot per wave, reduced by amax_finalize_kernel
         }
     }
 }
@@ -521,32 +523,47 @@ __global__ __launch_bounds__(kThreads) void q_direct_kernel(RqArgs a)
     if constexpr (PASS == 1) {
 #pragma unroll
         for (int m = 1; m < 64; m <<= 1) hmax = fmaxf(hmax, __shfl_xor(hmax, m));
-        if (lane == 0) atomicMax(a.amax_bits, __float_as_uint(hmax));
+        if (lane == 0) a.amax_partial[wave] = __float_as_uint(hmax);
     }
 }
 
-__global__ void fill_u32_kernel(uint32_t* p, uint32_t v) { *p = v; }
+// max over the per-wave partials of the abs-max pass (non-negative floats order like their bit patterns)
+__global__ __launch_bounds__(1024) void amax_finalize_kernel(const uint32_t* partial, int n, uint32_t* out)
+{
+    __shared__ uint32_t red[16];
+    uint32_t m = 0;
+    for (int i = threadIdx.x; i < n; i += 1024) m = max(m, partial[i]);
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) m = max(m, (uint32_t)__shfl_xor((int)m, d));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 16; ++w) m = max(m, red[w]);
+        *out = m;
+    }
+}
 
 // ------------------------------------------------------------------------------------------------------
 template <int BP, int G, bool HW>
-hipError_t launch_frag(const RqArgs& a0, int grid_cap, hipStream_t st)
+hipError_t launch_frag(const RqArgs& a0, int grid_cap, hipStream_t st, int* blocks_out)
 {
     RqArgs a = a0;
     a.n_items = round_up(a.rows, 16) / 16 * ((a.K + 511) / 512);
     int64_t blocks = (a.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > grid_cap) blocks = grid_cap;
     if (blocks < 1) blocks = 1;
+    if (blocks_out) *blocks_out = (int)blocks;
     hipLaunchKernelGGL((rq_frag_kernel<BP, G, HW>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
     return hipGetLastError();
 }
 
 template <int BP, int G, int LAYOUT, int PASS, bool HW>
-hipError_t launch_mfma(const RqArgs& a0, int grid_cap, hipStream_t st)
+hipError_t launch_mfma(const RqArgs& a0, int grid_cap, hipStream_t st, int* blocks_out)
 {
     if constexpr (LAYOUT == 1 && PASS == 0 && BP <= 64) {
         // The fragment-shaped kernel walks 16 rows x 512 K per wave, which is what HBM likes for big tensors; a
         // few-token call has too few of those items to fill the GPU, so it keeps the one-fragment-per-wave kernel.
-        if (round_up(a0.rows, 16) / 16 * ((a0.K + 511) / 512) >= 1024) return launch_frag<BP, G, HW>(a0, grid_cap, st);
+        if (round_up(a0.rows, 16) / 16 * ((a0.K + 511) / 512) >= 1024) return launch_frag<BP, G, HW>(a0, grid_cap, st, blocks_out);
     }
     // two fragments' worth of loads in flight per wave for the widest block (canonical order only: there an
     // item may run past the end and is masked per vector; GEMM-order items are whole fragments)
@@ -563,12 +580,13 @@ hipError_t launch_mfma(const RqArgs& a0, int grid_cap, hipStream_t st)
     int64_t blocks = (a.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > grid_cap) blocks = grid_cap;
     if (blocks < 1) blocks = 1;
+    if (blocks_out) *blocks_out = (int)blocks;
     hipLaunchKernelGGL((rq_mfma_kernel<BP, G, LAYOUT, PASS, HW, FR>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
     return hipGetLastError();
 }
 
 template <typename TIN, int G, int LAYOUT, int PASS, bool HW>
-hipError_t launch_direct(const RqArgs& a0, int grid_cap, hipStream_t st)
+hipError_t launch_direct(const RqArgs& a0, int grid_cap, hipStream_t st, int* blocks_out)
 {
     RqArgs a = a0;
     if (LAYOUT == 0) a.n_items = (a.rows * a.K + 2047) / 2048;
@@ -576,28 +594,29 @@ hipError_t launch_direct(const RqArgs& a0, int grid_cap, hipStream_t st)
     int64_t blocks = (a.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > grid_cap) blocks = grid_cap;
     if (blocks < 1) blocks = 1;
+    if (blocks_out) *blocks_out = (int)blocks;
     hipLaunchKernelGGL((q_direct_kernel<TIN, G, LAYOUT, PASS, HW>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
     return hipGetLastError();
 }
 
 template <int G, int LAYOUT, int PASS, bool HW>
-hipError_t dispatch_block(const RqArgs& a, bool in_f32, int grid_cap, hipStream_t st)
+hipError_t dispatch_block(const RqArgs& a, bool in_f32, int grid_cap, hipStream_t st, int* blocks_out)
 {
     if (a.b == 1) {
-        if (in_f32) return launch_direct<float, G, LAYOUT, PASS, HW>(a, grid_cap, st);
-        return launch_direct<uint16_t, G, LAYOUT, PASS, HW>(a, grid_cap, st);
+        if (in_f32) return launch_direct<float, G, LAYOUT, PASS, HW>(a, grid_cap, st, blocks_out);
+        return launch_direct<uint16_t, G, LAYOUT, PASS, HW>(a, grid_cap, st, blocks_out);
     }
-    if (a.b <= 32) return launch_mfma<32, G, LAYOUT, PASS, HW>(a, grid_cap, st);
-    if (a.b == 64) return launch_mfma<64, G, LAYOUT, PASS, HW>(a, grid_cap, st);
-    return launch_mfma<128, G, LAYOUT, PASS, HW>(a, grid_cap, st);
+    if (a.b <= 32) return launch_mfma<32, G, LAYOUT, PASS, HW>(a, grid_cap, st, blocks_out);
+    if (a.b == 64) return launch_mfma<64, G, LAYOUT, PASS, HW>(a, grid_cap, st, blocks_out);
+    return launch_mfma<128, G, LAYOUT, PASS, HW>(a, grid_cap, st, blocks_out);
 }
 
 template <int G, bool HW>
-hipError_t dispatch_layout_pass(const RqArgs& a, bool in_f32, int layout, int pass, int grid_cap, hipStream_t st)
+hipError_t dispatch_layout_pass(const RqArgs& a, bool in_f32, int layout, int pass, int grid_cap, hipStream_t st, int* blocks_out = nullptr)
 {
-    if (pass == 1) return dispatch_block<G, 0, 1, HW>(a, in_f32, grid_cap, st);  // layout irrelevant for the abs-max pass
-    if (layout == 0) return dispatch_block<G, 0, 0, HW>(a, in_f32, grid_cap, st);
-    return dispatch_block<G, 1, 0, HW>(a, in_f32, grid_cap, st);
+    if (pass == 1) return dispatch_block<G, 0, 1, HW>(a, in_f32, grid_cap, st, blocks_out);  // layout irrelevant for the abs-max pass
+    if (layout == 0) return dispatch_block<G, 0, 0, HW>(a, in_f32, grid_cap, st, blocks_out);
+    return dispatch_block<G, 1, 0, HW>(a, in_f32, grid_cap, st, blocks_out);
 }
 
 }  // namespace
@@ -623,11 +642,16 @@ hipError_t launch_rotate_quantize(const void* x, int64_t rows, int64_t K, int b,
 
     hipError_t e;
     if (fmt == 1 && !static_scale) {
-        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(1), 0, st, a.amax_bits, 0u);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-        e = hw_codec ? dispatch_layout_pass<16, true>(a, in_f32, 0, 1, grid_cap, st)
-                     : dispatch_layout_pass<16, false>(a, in_f32, 0, 1, grid_cap, st);
+        // dynamic tensor scale: abs-max pass (one partial per wave) -> finalize -> quantize pass
+        a.amax_partial = a.amax_bits + 64;
+        const int pass_cap = kAmaxPassBlocks;
+        int pass_blocks = 0;
+        e = hw_codec ? dispatch_layout_pass<16, true>(a, in_f32, 0, 1, pass_cap, st, &pass_blocks)
+                     : dispatch_layout_pass<16, false>(a, in_f32, 0, 1, pass_cap, st, &pass_blocks);
         if (e != hipSuccess) return e;
+        // blocks that had no item still wrote their (zero) partial: every wave of the grid stores one
+        hipLaunchKernelGGL(amax_finalize_kernel, dim3(1), dim3(1024), 0, st, a.amax_partial, pass_blocks * kWavesPerBlock, a.amax_bits);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (fmt == 0)
         return hw_codec ? dispatch_layout_pass<32, true>(a, in_f32, layout_gemm, 0, grid_cap, st)
