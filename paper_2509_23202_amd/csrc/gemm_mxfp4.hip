@@ -20,6 +20,8 @@
 #include "internal.hpp"
 #include "layout.hpp"
 
+#include <algorithm>
+#include <cstdlib>
 #include <type_traits>
 
 namespace fp4mr {
@@ -86,7 +88,7 @@ __device__ __forceinline__ void remap_block(int bid, int nblocks, int tiles_m, i
     tn = in_band / gsz;
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, bool OUT_F32, int RD = 2>
+template <int BM, int BN, int WM, int WN, int STAGES, bool OUT_F32, int RD = 2, bool PERSIST = false>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(GemmArgs g)
 {
     constexpr int NWM = BM / WM, NWN = BN / WN, NW = NWM * NWN;
@@ -105,8 +107,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     const int wm = wave % NWM, wn = wave / NWM;
     const uint32_t lane16 = (uint32_t)lane * 16u, lane4 = (uint32_t)lane * 4u;
 
-    int tm, tn;
-    remap_block(blockIdx.x, g.tiles_m * g.tiles_n, g.tiles_m, g.tiles_n, tm, tn);
+    // PERSIST: the grid is one workgroup per compute unit and a workgroup walks the tiles blockIdx.x,
+    // blockIdx.x + gridDim.x, ...; otherwise the grid has one workgroup per tile and the loop below runs once.
+    const int ntiles = g.tiles_m * g.tiles_n;
+    int tile = blockIdx.x;
 
     const int64_t KC = g.K >> 7;            // K-steps
     const int64_t KS = (g.K + 511) >> 9;    // scale super-steps
@@ -121,12 +125,20 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, (int)n, 0x00020000);
     };
     // bases at the tile's first row-block keep every scalar offset far below 2^31
-    const int a_rb0 = min(tm * FX, a_rbs - 1), w_rb0 = min(tn * FW, w_rbs - 1);
-    const __amdgpu_buffer_rsrc_t rs_ac = make_rsrc(g.a_codes + (int64_t)a_rb0 * KC * 1024, (int64_t)(a_rbs - a_rb0) * KC * 1024);
-    const __amdgpu_buffer_rsrc_t rs_wc = make_rsrc(g.w_codes + (int64_t)w_rb0 * KC * 1024, (int64_t)(w_rbs - w_rb0) * KC * 1024);
-    const __amdgpu_buffer_rsrc_t rs_as = make_rsrc(g.a_scales + (int64_t)a_rb0 * KS * 256, (int64_t)(a_rbs - a_rb0) * KS * 256);
-    const __amdgpu_buffer_rsrc_t rs_ws = make_rsrc(g.w_scales + (int64_t)w_rb0 * KS * 256, (int64_t)(w_rbs - w_rb0) * KS * 256);
-    const int a_rb_last = a_rbs - 1 - a_rb0, w_rb_last = w_rbs - 1 - w_rb0;  // largest valid row-block relative to the base
+    int tm, tn;                  // tile whose operands the loads below address
+    __amdgpu_buffer_rsrc_t rs_ac, rs_wc, rs_as, rs_ws;
+    int a_rb_last, w_rb_last;    // largest valid row-block relative to the base
+    auto set_tile = [&](int t) {
+        remap_block(t, ntiles, g.tiles_m, g.tiles_n, tm, tn);
+        const int a_rb0 = min(tm * FX, a_rbs - 1), w_rb0 = min(tn * FW, w_rbs - 1);
+        rs_ac = make_rsrc(g.a_codes + (int64_t)a_rb0 * KC * 1024, (int64_t)(a_rbs - a_rb0) * KC * 1024);
+        rs_wc = make_rsrc(g.w_codes + (int64_t)w_rb0 * KC * 1024, (int64_t)(w_rbs - w_rb0) * KC * 1024);
+        rs_as = make_rsrc(g.a_scales + (int64_t)a_rb0 * KS * 256, (int64_t)(a_rbs - a_rb0) * KS * 256);
+        rs_ws = make_rsrc(g.w_scales + (int64_t)w_rb0 * KS * 256, (int64_t)(w_rbs - w_rb0) * KS * 256);
+        a_rb_last = a_rbs - 1 - a_rb0;
+        w_rb_last = w_rbs - 1 - w_rb0;
+    };
+    set_tile(tile);
 
     // Scales: every (row-block, 4 K-steps) owns 256 bytes = one dword per lane.  They travel global -> LDS with
     // 4-byte direct-to-LDS loads into a two-deep ring (so no VGPR is ever the target of an in-flight load inside
@@ -137,11 +149,6 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     const int kc_bytes = (int)KC * 1024, ks_bytes = (int)KS * 256;
 
     v4f acc[TN][TM];
-#pragma unroll
-    for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
-
     uint32_t sx[TM], sw[TN];
     // Software pipeline of the LDS reads: the X fragments of step kt+1 are read into the other half of xf[2][.]
     // while step kt computes, and the W fragments run through a 4-deep register ring two groups of TM MFMAs ahead
@@ -152,16 +159,19 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     // every wave issues exactly LPW fragment loads per stage and NS scale loads per batch so that the vmcnt
     // bookkeeping is uniform; when F is not a multiple of NW the spare slots re-copy the last fragment (same bytes
     // to the same place)
+    // which operand load slot i of this wave belongs to: known at compile time (i is a constant after unrolling)
+    // whenever the X fragments divide evenly among the waves, which keeps the step body free of branches
+    auto is_x = [&](int f, int i) { return (FX % NW == 0) ? (i < FX / NW) : (f < FX); };
     auto issue_scale_one = [&](int ss, int i) {
         char* base = scale_ring + (ss & 1) * SCALE_BYTES;
         ss = ss < (int)KS ? ss : (int)KS - 1;  // the batch past the end re-reads the last one
         const int f = min(wave + i * NW, F - 1);
-        if (f < FX) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_as, (lds_void*)(base + f * 256), 4, lane4, min(f, a_rb_last) * ks_bytes + ss * 256, 0, 0);
+        if (is_x(f, i)) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_as, (lds_void*)(base + f * 256), 4, lane4, min(f, a_rb_last) * ks_bytes + ss * 256, 0, 0);
         else __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_ws, (lds_void*)(base + f * 256), 4, lane4, min(f - FX, w_rb_last) * ks_bytes + ss * 256, 0, 0);
     };
     auto issue_frag_one = [&](int kt, char* base, int i) {
         const int f = min(wave + i * NW, F - 1);
-        if (f < FX) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_ac, (lds_void*)(base + f * 1024), 16, lane16, min(f, a_rb_last) * kc_bytes + kt * 1024, 0, 0);
+        if (is_x(f, i)) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_ac, (lds_void*)(base + f * 1024), 16, lane16, min(f, a_rb_last) * kc_bytes + kt * 1024, 0, 0);
         else __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_wc, (lds_void*)(base + f * 1024), 16, lane16, (min(f - FX, w_rb_last)) * kc_bytes + kt * 1024, 0, 0);
     };
     auto issue_scales = [&](int ss) {
@@ -183,21 +193,17 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
         wring[i & (RING - 1)] = *(reinterpret_cast<const v4i*>(smem + (kt % STAGES) * STAGE_BYTES + (FX + wn * TN + i) * 1024) + lane);
     };
 
-    // prologue: scales of super-step 0, then STAGES-1 stages; scales, X fragments and the first two W fragments of
-    // step 0 into registers
-    issue_scales(0);
+    // prologue of a tile: scales of super-step 0 and STAGES-1 stages on their way into ring slots 0 .. STAGES-2
+    auto issue_prologue = [&]() {
+        issue_scales(0);
 #pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s) {
+        for (int s = 0; s < STAGES - 1; ++s) {
 #pragma unroll
-        for (int i = 0; i < LPW; ++i) issue_frag_one(min(s, KT - 1), smem + s * STAGE_BYTES, i);
-    }
+            for (int i = 0; i < LPW; ++i) issue_frag_one(min(s, KT - 1), smem + s * STAGE_BYTES, i);
+        }
+    };
+    issue_prologue();
     wait_vmcnt<(STAGES - 2) * LPW>();
-    block_barrier();
-    read_scales(0, sx, sw);
-#pragma unroll
-    for (int j = 0; j < TM; ++j) read_x(0, std::integral_constant<int, 0>{}, j);
-#pragma unroll
-    for (int i = 0; i < RD; ++i) read_w(0, i);
 
     // One K-step.  J = kt % 4 selects the scale byte (op_sel) and the X register half (J & 1).
     //   top:    stage kt+1 must have landed (this wave's copies: vmcnt; everybody's: barrier).  The same barrier
@@ -264,81 +270,135 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
             if (kt0 + 3 < KT) step(kt0 + 3, std::integral_constant<int, 3>{}, wtag);
         }
     };
-    switch (wave & 3) {
-        case 0: main_loop(std::integral_constant<int, 0>{}); break;
-        case 1: main_loop(std::integral_constant<int, 1>{}); break;
-        case 2: main_loop(std::integral_constant<int, 2>{}); break;
-        default: main_loop(std::integral_constant<int, 3>{}); break;
-    }
-    wait_vmcnt<0>();  // the clamped last scale batch
 
-    // Epilogue.  A lane owns out[m][n..n+3] with m = m0 + 16*j + lane%16, n = n0 + 16*i + 4*(lane/16): stored directly
-    // that is 16 rows x 32 bytes per instruction.  For bf16 output the wave tile is first transposed through LDS
-    // (free once the main loop is over) so that every store instruction writes 16 bytes per lane in whole rows.
-    constexpr int ROWB = WN * 2 + 16;  // padded row pitch: the 8-byte writes of 32 lanes then hit distinct banks
-    if constexpr (!OUT_F32 && NW * WM * ROWB <= STAGES * STAGE_BYTES + 2 * SCALE_BYTES) {
-        if ((g.N & 7) == 0) {
-            wait_lgkmcnt0();
-            block_barrier();  // every wave is done with the operand ring (and the last scale batch has landed)
-            char* const mine = smem + wave * (WM * ROWB);
-            typedef __bf16 v4bf __attribute__((ext_vector_type(4)));
+    // The epilogue transposes 16 output rows of the wave tile at a time through a staging area in the last ring
+    // slot; the other slots are free for the next tile's prologue loads while the stores drain.
+    constexpr int CPR = WN / 8;                  // 16-byte chunks per staged row
+    constexpr int STAGING = 16 * WN * 2;         // bytes per wave
+    constexpr bool STAGED = !OUT_F32 && NW * STAGING <= STAGE_BYTES && (CPR == 8 || CPR == 16);
+
+    for (;;) {
+        // stage 0 and the first scale batch have landed (this wave's copies: the vmcnt wait before this point)
+        block_barrier();
+        read_scales(0, sx, sw);
 #pragma unroll
-            for (int j = 0; j < TM; ++j)
+        for (int j = 0; j < TM; ++j) read_x(0, std::integral_constant<int, 0>{}, j);
+#pragma unroll
+        for (int i = 0; i < RD; ++i) read_w(0, i);
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
+
+        switch (wave & 3) {
+            case 0: main_loop(std::integral_constant<int, 0>{}); break;
+            case 1: main_loop(std::integral_constant<int, 1>{}); break;
+            case 2: main_loop(std::integral_constant<int, 2>{}); break;
+            default: main_loop(std::integral_constant<int, 3>{}); break;
+        }
+        wait_vmcnt<0>();  // the clamped loads of the last steps
+        wait_lgkmcnt0();
+        block_barrier();  // every wave is done with the operand ring, and nothing is in flight into it
+
+        const int64_t m0 = (int64_t)tm * BM + wm * WM, n0 = (int64_t)tn * BN + wn * WN;  // this wave's output tile
+        const int next = tile + (int)gridDim.x;
+        const bool more = PERSIST && next < ntiles;
+        if (more) {
+            // the next tile's first stages travel while this tile's results are converted and stored
+            set_tile(next);
+            issue_prologue();
+        }
+
+        // A lane owns out[m][n..n+3] with m = m0 + 16*j + lane%16, n = n0 + 16*i + 4*(lane/16): stored directly that
+        // is 16 rows x 32 bytes per instruction.  For bf16 output the rows go through LDS first so that every store
+        // instruction writes 16 bytes per lane in whole rows.  A staged row is WN*2 bytes with its 16-byte chunks
+        // XOR-swizzled by the row number: the 8-byte writes of a half-wave and the 16-byte reads of a quarter-wave
+        // then both spread over all banks.
+        // the lane-dependent address arithmetic of the epilogue is tied to a value defined here, so that the compiler
+        // cannot hoist it above the tile loop and carry it (in registers the main loop needs) through every K-step
+        int el = lane;
+        asm volatile("" : "+v"(el));
+        if (STAGED && (g.N & 7) == 0) {
+            char* const mine = smem + (STAGES - 1) * STAGE_BYTES + wave * STAGING;
+            typedef __bf16 v4bf __attribute__((ext_vector_type(4)));
+            const int wr = el & 15, wq = el >> 4;
+#pragma unroll
+            for (int j = 0; j < TM; ++j) {
 #pragma unroll
                 for (int i = 0; i < TN; ++i) {
                     const v4f v = acc[i][j];
                     const v4bf p = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3]};
-                    *reinterpret_cast<v4bf*>(mine + (16 * j + (lane & 15)) * ROWB + (16 * i + 4 * (lane >> 4)) * 2) = p;
+                    const int ch = (2 * i + (wq >> 1)) ^ (wr & (CPR - 1));
+                    *reinterpret_cast<v4bf*>(mine + wr * (WN * 2) + ch * 16 + (wq & 1) * 8) = p;
                 }
-            constexpr int CPR = WN / 8;  // 16-byte chunks per row
-            const int64_t m0 = (int64_t)tm * BM + wm * WM, n0 = (int64_t)tn * BN + wn * WN;
 #pragma unroll
-            for (int it = 0; it < WM * CPR / 64; ++it) {
-                const int c = it * 64 + lane;
-                const int row = c / CPR, ch = c % CPR;
-                const v4i v = *reinterpret_cast<const v4i*>(mine + row * ROWB + ch * 16);
-                const int64_t m = m0 + row, n = n0 + ch * 8;
-                if (m < g.M && n < g.N) __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(static_cast<__bf16*>(g.out) + m * g.N + n));
-            }
-            return;
-        }
-    }
-    // direct stores (fp32 output, or N not a multiple of 8)
-    const int64_t m_base = (int64_t)tm * BM + wm * WM + (lane & 15);
-    const int64_t n_base = (int64_t)tn * BN + wn * WN + (lane >> 4) * 4;
-#pragma unroll
-    for (int j = 0; j < TM; ++j) {
-        const int64_t m = m_base + 16 * j;
-        if (m >= g.M) continue;
-#pragma unroll
-        for (int i = 0; i < TN; ++i) {
-            const int64_t n = n_base + 16 * i;
-            if (n >= g.N) continue;
-            const v4f v = acc[i][j];
-            if constexpr (OUT_F32) {
-                float* o = static_cast<float*>(g.out) + m * g.N + n;
-                if (n + 3 < g.N && (g.N & 3) == 0) {
-                    *reinterpret_cast<float4*>(o) = make_float4(v[0], v[1], v[2], v[3]);
-                } else {
-                    for (int e = 0; e < 4; ++e)
-                        if (n + e < g.N) o[e] = v[e];
-                }
-            } else {
-                __bf16* o = static_cast<__bf16*>(g.out) + m * g.N + n;
-                typedef __bf16 v4bf __attribute__((ext_vector_type(4)));
-                if (n + 3 < g.N && (g.N & 3) == 0) {
-                    v4bf p = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3]};
-                    *reinterpret_cast<v4bf*>(o) = p;
-                } else {
-                    for (int e = 0; e < 4; ++e)
-                        if (n + e < g.N) o[e] = (__bf16)v[e];
+                for (int it = 0; it < 16 * CPR / 64; ++it) {
+                    const int c = it * 64 + el;
+                    const int row = c / CPR, ch = c % CPR;
+                    const v4i v = *reinterpret_cast<const v4i*>(mine + row * (WN * 2) + ((ch ^ (row & (CPR - 1))) * 16));
+                    const int64_t m = m0 + 16 * j + row, n = n0 + ch * 8;
+                    if (m < g.M && n < g.N) __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(static_cast<__bf16*>(g.out) + m * g.N + n));
                 }
             }
+        } else {
+            // direct stores (fp32 output, or N not a multiple of 8)
+            const int64_t m_base = m0 + (el & 15);
+            const int64_t n_base = n0 + (el >> 4) * 4;
+#pragma unroll
+            for (int j = 0; j < TM; ++j) {
+                const int64_t m = m_base + 16 * j;
+                if (m >= g.M) continue;
+#pragma unroll
+                for (int i = 0; i < TN; ++i) {
+                    const int64_t n = n_base + 16 * i;
+                    if (n >= g.N) continue;
+                    const v4f v = acc[i][j];
+                    if constexpr (OUT_F32) {
+                        float* o = static_cast<float*>(g.out) + m * g.N + n;
+                        if (n + 3 < g.N && (g.N & 3) == 0) {
+                            *reinterpret_cast<float4*>(o) = make_float4(v[0], v[1], v[2], v[3]);
+                        } else {
+                            for (int e = 0; e < 4; ++e)
+                                if (n + e < g.N) o[e] = v[e];
+                        }
+                    } else {
+                        __bf16* o = static_cast<__bf16*>(g.out) + m * g.N + n;
+                        typedef __bf16 v4bf __attribute__((ext_vector_type(4)));
+                        if (n + 3 < g.N && (g.N & 3) == 0) {
+                            v4bf p = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3]};
+                            *reinterpret_cast<v4bf*>(o) = p;
+                        } else {
+                            for (int e = 0; e < 4; ++e)
+                                if (n + e < g.N) o[e] = (__bf16)v[e];
+                        }
+                    }
+                }
+            }
         }
+        if (!more) break;
+        tile = next;
+        // Loads and stores retire out of order with respect to each other, so a partial vmcnt cannot single out the
+        // prologue loads among the stores issued after them: wait for everything.  By now all STAGES-1 prefetched
+        // stages have landed and the next main loop starts with a full ring.
+        wait_vmcnt<0>();
     }
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, int RD = 2>
+// compute units of the current device (the persistent variants launch one workgroup per unit)
+int compute_units()
+{
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES, int RD = 2, bool PERSIST = false>
 hipError_t launch_variant(const GemmArgs& g0, bool out_f32, hipStream_t st)
 {
     GemmArgs g = g0;
@@ -346,14 +406,22 @@ hipError_t launch_variant(const GemmArgs& g0, bool out_f32, hipStream_t st)
     g.tiles_n = (int)((g.N + BN - 1) / BN);
     constexpr int threads = (BM / WM) * (BN / WN) * 64;
     constexpr size_t lds = (size_t)STAGES * (BM + BN) / 16 * 1024 + 2 * (size_t)(BM + BN) / 16 * 256;
-    const dim3 grid((unsigned)(g.tiles_m * g.tiles_n));
+    const int ntiles = g.tiles_m * g.tiles_n;
+    int nwg = ntiles;
+    if (PERSIST) {
+        nwg = std::min(ntiles, compute_units());
+        // FP4MR_GEMM_GRID caps the persistent grid (a testing aid: a small grid walks many tiles per workgroup)
+        const char* cap = std::getenv("FP4MR_GEMM_GRID");
+        if (cap && *cap && std::atoi(cap) > 0) nwg = std::min(nwg, std::atoi(cap));
+    }
+    const dim3 grid((unsigned)nwg);
     hipError_t e;
     if (out_f32) {
-        auto k = gemm_mx_kernel<BM, BN, WM, WN, STAGES, true, RD>;
+        auto k = gemm_mx_kernel<BM, BN, WM, WN, STAGES, true, RD, PERSIST>;
         if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, dim3(threads), lds, st, g);
     } else {
-        auto k = gemm_mx_kernel<BM, BN, WM, WN, STAGES, false, RD>;
+        auto k = gemm_mx_kernel<BM, BN, WM, WN, STAGES, false, RD, PERSIST>;
         if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, dim3(threads), lds, st, g);
     }
@@ -392,6 +460,7 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
         case 8: return launch_variant<256, 256, 128, 128, 4, 4>(g, out_f32, st);
         case 9: return launch_variant<256, 256, 128, 128, 4, 6>(g, out_f32, st);
         case 10: return launch_variant<256, 256, 64, 128, 4, 3>(g, out_f32, st);
+        case 11: return launch_variant<256, 256, 64, 128, 4, 3, true>(g, out_f32, st);
         default: return hipErrorInvalidValue;
     }
 }

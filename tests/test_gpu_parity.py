@@ -199,10 +199,20 @@ def test_gemm_gemm_layout_operands_bf16_out(fp4, oracle, fmt):
     _gemm_case(fp4, oracle, fmt, 200, 520, 1024 + 384, seed=5, out_f32=False, layout_gemm=True)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11])
 def test_gemm_mxfp4_every_tile_variant(fp4, oracle, variant, monkeypatch):
     monkeypatch.setenv("FP4MR_GEMM_VARIANT", str(variant))
     _gemm_case(fp4, oracle, MX, 272, 528, 1280, seed=variant, out_f32=True, layout_gemm=True)
+
+
+@pytest.mark.parametrize("grid", [1, 2, 4])
+@pytest.mark.parametrize("out_f32", [False, True])
+def test_gemm_mxfp4_persistent_workgroups_walk_several_tiles(fp4, oracle, grid, out_f32, monkeypatch):
+    """Six 256x256 tiles on 1, 2 or 4 workgroups: every workgroup computes a sequence of tiles (uneven for 4), with
+    the next tile's first stages loaded while the previous tile's results are stored."""
+    monkeypatch.setenv("FP4MR_GEMM_VARIANT", "11")
+    monkeypatch.setenv("FP4MR_GEMM_GRID", str(grid))
+    _gemm_case(fp4, oracle, MX, 272, 528, 1280, seed=40 + grid, out_f32=out_f32, layout_gemm=True)
 
 
 def test_gemm_mxfp4_exact_on_small_integers(fp4, oracle):
