@@ -26,9 +26,15 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+# The rotation kernels consume every MFMA result in the vector ALU right away: letting the MFMAs write ordinary
+# vector registers saves one v_accvgpr_read per value (the GEMM kernels keep their accumulators where the
+# compiler puts them).
+EXTRA_FLAGS = {"rotate_quantize.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
+
 def _compile(src: str) -> Path:
     obj = BUILD / (src + ".o")
-    cmd = [HIPCC, *FLAGS, "-I", str(HERE.parent / "include"), "-c", str(CSRC / src), "-o", str(obj)]
+    cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), "-I", str(HERE.parent / "include"), "-c", str(CSRC / src), "-o", str(obj)]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

@@ -60,6 +60,29 @@ __device__ __forceinline__ uint32_t e2m1_pack8(const float (&t)[8])
     }
 }
 
+// Eight values divided by the E8M0 scale 2^(byte - 127) -> one dword of codes.  The hardware convert takes the scale
+// as the exponent field of a binary32 operand, so the division is free (checked against multiply-then-convert over
+// every scale byte, subnormal inputs included); the software codec multiplies by the exact reciprocal.
+template <bool HW>
+__device__ __forceinline__ uint32_t e2m1_pack8_e8m0(const float (&y)[8], uint32_t byte)
+{
+    if constexpr (HW) {
+        const float sc = __uint_as_float(byte << 23);
+        uint32_t p = 0;
+        p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, y[0], y[1], sc, 0);
+        p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, y[2], y[3], sc, 1);
+        p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, y[4], y[5], sc, 2);
+        p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, y[6], y[7], sc, 3);
+        return p;
+    } else {
+        const float inv = __uint_as_float((254u - byte) << 23);  // 2^(127 - byte), a normal number for byte <= 253
+        float t[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t[i] = y[i] * inv;
+        return e2m1_pack8<false>(t);
+    }
+}
+
 // ---------------------------------------------------------------- E4M3 scale codec (non-negative input)
 // Software encoder: round-to-nearest-even onto the e4m3fn grid (bias 7, subnormal step 2^-9), saturating
 // at 448.
