@@ -236,6 +236,31 @@ def main():
                                               "workload": "X bf16 [16384, 8192], Laplace(0,1), 1% outlier channels x100, block 32",
                                               "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
                                               "avg_launch_us": round(ms * 1e3, 2), "traffic": RQ_TRAFFIC_BYTES_PER_LAUNCH}
+
+        # ---- the same tensor through a caller-supplied dense rotation (orthonormal DCT-II block rounded to bf16)
+        def time_rq(fn):
+            for j in range(3):
+                fn(xs[j])
+            torch.cuda.synchronize()
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0.record()
+            for it in range(n_rq):
+                fn(xs[it % 3])
+            a1.record()
+            torch.cuda.synchronize()
+            t = a0.elapsed_time(a1) / n_rq
+            return {"avg_launch_us": round(t * 1e3, 2), "achieved_gbs": round(Mr * Kr * RQ_BYTES_PER_ELEM_MX / (t * 1e-3) / 1e9, 1)}
+
+        dense = {}
+        for bd in (32, 128):
+            n_ = np.arange(bd)[:, None]
+            k_ = np.arange(bd)[None, :]
+            R = np.cos(np.pi * (2 * n_ + 1) * k_ / (2 * bd)) * np.sqrt(2.0 / bd)
+            R[:, 0] = 1.0 / np.sqrt(bd)
+            Rd = to_dev_bf16(inputs.f32_to_bf16_bits(R.astype(np.float32)))
+            dense[f"dct{bd}"] = time_rq(lambda x_: fp4.fp4_rotate_quantize_dense(x_, Rd, fp4.MXFP4, flags=GL, codes=oc, scales=osc))
+            dense[f"hadamard{bd}"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, bd, fp4.MXFP4, flags=GL, codes=oc, scales=osc))
+        result["rotate_quantize_other_rotations"] = dense
         del xs
 
     if args.copy_calibration:

@@ -88,6 +88,21 @@ fp4mr_status_t fp4_rotate_quantize(const void* x, int64_t M, int64_t K, int had_
                                    void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
 
 /*
+ * The same with a caller-supplied rotation instead of the Hadamard: codes, scales = Q(X R) with R block-diagonal,
+ * every diagonal block equal to rot (Section 4.2 item 1: for k < 256 a dense k x k transform stays memory-bound,
+ * so any rotation -- DCT, DST, learned -- costs what the Hadamard costs; appendix tables on other transforms).
+ *   block        k in {16,32,64,128}
+ *   rot_bf16     device pointer, [block, block] bf16 row-major, 16-byte aligned; y[m, j*k + c] = sum_r x[m, j*k + r] *
+ *                rot[r][c], accumulated in fp32.  The matrix carries its own normalisation.  Not retained after the
+ *                call returns to the stream (the kernels read it; the caller keeps it alive until they finish).
+ * Everything else as fp4_rotate_quantize (FP4MR_INPUT_F32 is not accepted).  Weights are prepared with the same
+ * call (rows = N): the GEMM needs both operands rotated by the same matrix.
+ */
+fp4mr_status_t fp4_rotate_quantize_dense(const void* x, int64_t M, int64_t K, int block, const void* rot_bf16,
+                                         fp4mr_fmt_t fmt, void* codes_out, void* scales_out, float* tensor_scale,
+                                         void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
+
+/*
  * Offline weight preparation: codes, scales = Q(W H_b) by round-to-nearest (Section 4.2 item 1: "W H_k is
  * pre-fused in the weights"; RTN + HT row of Section 5's method list).  Same arguments as
  * fp4_rotate_quantize with rows = N.  GPTQ-style calibration is not part of this library.

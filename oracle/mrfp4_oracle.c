@@ -11,6 +11,9 @@
  *                       block-diagonal H_k with k x k blocks, k a power of two).
  *   orc_rotate          X H_b with H_b block-diagonal along the reduction (K) axis (Section 4.1,
  *                       Ingredient 3; Section 4.2 item 1).
+ *   orc_rotate_dense    X R with R block-diagonal and an arbitrary k x k block given by the caller (Section 4.2
+ *                       item 1: any rotation, not just Hadamards, loaded at run time; appendix tables on DCT,
+ *                       DST and other transforms).
  *   orc_quantize_mxfp4  MFP format (G=32, E=E2M1, S=E8M0) of Section 2, abs-max scale and round-to-
  *                       nearest of Section 3 (Definition "Scales"), with the scale rounded to a power of
  *                       two by the OCP Microscaling rule  2^(floor(log2 amax) - 2).
@@ -106,6 +109,26 @@ int orc_rotate(const uint16_t *x, int64_t M, int64_t K, int b, float *y)
         }
     }
     free(H);
+    return 0;
+}
+
+/* y = x . blockdiag(R, R, ...) along K with a caller-supplied block R [b,b] (bf16 bit patterns, row-major):
+ * y[m, j0 + c] = sum_r x[m, j0 + r] * R[r][c].  fp64 accumulation (every product of two bf16 values is exact in
+ * fp64), ONE rounding to fp32.  No normalisation is applied: R carries its own. */
+int orc_rotate_dense(const uint16_t *x, int64_t M, int64_t K, int b, const uint16_t *R, float *y)
+{
+    if (b < 1 || b > 1024 || K % b != 0) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t j0 = 0; j0 < K; j0 += b) {
+            for (int c = 0; c < b; ++c) {
+                double acc = 0.0;
+                for (int r = 0; r < b; ++r)
+                    acc += (double)bf16_bits_to_float(x[m * K + j0 + r]) * (double)bf16_bits_to_float(R[r * b + c]);
+                y[m * K + j0 + c] = (float)acc;
+            }
+        }
+    }
     return 0;
 }
 

@@ -48,6 +48,8 @@ def _load():
         L.orc_hadamard.restype = i32
         L.orc_rotate.argtypes = [p, i64, i64, i32, p]
         L.orc_rotate.restype = i32
+        L.orc_rotate_dense.argtypes = [p, i64, i64, i32, p, p]
+        L.orc_rotate_dense.restype = i32
         L.orc_rotate_f64.argtypes = [p, i64, i64, i32, p]
         L.orc_rotate_f64.restype = i32
         L.orc_e2m1_decode.argtypes = [u8]
@@ -126,6 +128,20 @@ def rotate(x_bf16_bits: np.ndarray, b: int) -> np.ndarray:
     y = np.empty((M, K), dtype=np.float32)
     if _load().orc_rotate(_ptr(x), M, K, int(b), _ptr(y)) != 0:
         raise ValueError(f"rotate: bad b={b} for K={K}")
+    return y
+
+
+def rotate_dense(x_bf16_bits: np.ndarray, rot_bf16_bits: np.ndarray) -> np.ndarray:
+    """x: uint16 bf16 bit patterns [M,K], rot: uint16 bf16 bit patterns [b,b] -> fp32 [M,K] = x @ blockdiag(rot)."""
+    x = np.ascontiguousarray(x_bf16_bits, dtype=np.uint16)
+    R = np.ascontiguousarray(rot_bf16_bits, dtype=np.uint16)
+    M, K = x.shape
+    b = R.shape[0]
+    if R.shape != (b, b):
+        raise ValueError("rot must be square")
+    y = np.empty((M, K), dtype=np.float32)
+    if _load().orc_rotate_dense(_ptr(x), M, K, int(b), _ptr(R), _ptr(y)) != 0:
+        raise ValueError(f"rotate_dense: bad b={b} for K={K}")
     return y
 
 

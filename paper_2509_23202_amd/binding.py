@@ -34,6 +34,8 @@ lib.fp4_rotate_quantize.argtypes = _quant_sig
 lib.fp4_rotate_quantize.restype = _i32
 lib.fp4_quantize_weights.argtypes = _quant_sig
 lib.fp4_quantize_weights.restype = _i32
+lib.fp4_rotate_quantize_dense.argtypes = [_p, _i64, _i64, _i32, _p, _i32, _p, _p, _p, _p, _sz, _u32, _p]
+lib.fp4_rotate_quantize_dense.restype = _i32
 lib.fp4_gemm.argtypes = [_p, _p, _p, _p, _p, _p, _i64, _i64, _i64, _i32, _p, _p, _sz, _u32, _p]
 lib.fp4_gemm.restype = _i32
 lib.fp4_workspace_bytes.argtypes = [_i32, _i64, _i64, _i64, _i32, _u32]
@@ -74,7 +76,7 @@ def workspace_bytes(op: int, M: int, N: int, K: int, fmt: int, flags: int = 0) -
     return int(lib.fp4_workspace_bytes(op, M, N, K, fmt, flags))
 
 
-def _quantize(fn, op, x, had_block, fmt, flags, tensor_scale, codes, scales, workspace):
+def _quantize(fn, op, x, had_block, fmt, flags, tensor_scale, codes, scales, workspace, rot=None):
     assert x.is_cuda and x.dim() == 2 and x.is_contiguous()
     rows, K = x.shape
     if x.dtype == torch.float32:
@@ -96,8 +98,12 @@ def _quantize(fn, op, x, had_block, fmt, flags, tensor_scale, codes, scales, wor
     if need and workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
     wsz = 0 if workspace is None else workspace.numel()
-    _check(fn(x.data_ptr(), rows, K, had_block, fmt, codes.data_ptr(), scales.data_ptr(), _ptr(ts), _ptr(workspace), wsz,
-              flags, _stream()))
+    if rot is None:
+        _check(fn(x.data_ptr(), rows, K, had_block, fmt, codes.data_ptr(), scales.data_ptr(), _ptr(ts), _ptr(workspace), wsz,
+                  flags, _stream()))
+    else:
+        _check(fn(x.data_ptr(), rows, K, had_block, rot.data_ptr(), fmt, codes.data_ptr(), scales.data_ptr(), _ptr(ts),
+                  _ptr(workspace), wsz, flags, _stream()))
     return codes, scales, ts
 
 
@@ -107,6 +113,14 @@ def fp4_rotate_quantize(x, had_block: int, fmt: int, *, flags: int = 0, tensor_s
     With flags=LAYOUT_GEMM the outputs are in the opaque GEMM layout; else canonical flat byte tensors
     (codes [M*K/2], scales [M*K/G])."""
     return _quantize(lib.fp4_rotate_quantize, OP_ROTATE_QUANTIZE, x, had_block, fmt, flags, tensor_scale, codes, scales, workspace)
+
+
+def fp4_rotate_quantize_dense(x, rot, fmt: int, *, flags: int = 0, tensor_scale=None, codes=None, scales=None, workspace=None):
+    """codes, scales, tensor_scale = Q(X R), R block-diagonal with the bf16 [k,k] cuda tensor `rot` on the diagonal
+    (k in {16,32,64,128}); for weights pass W as x."""
+    assert rot.is_cuda and rot.dtype == torch.bfloat16 and rot.dim() == 2 and rot.shape[0] == rot.shape[1] and rot.is_contiguous()
+    return _quantize(lib.fp4_rotate_quantize_dense, OP_ROTATE_QUANTIZE, x, int(rot.shape[0]), fmt, flags, tensor_scale, codes,
+                     scales, workspace, rot=rot)
 
 
 def fp4_quantize_weights(w, had_block: int, fmt: int, *, flags: int = 0, tensor_scale=None, codes=None, scales=None,

@@ -43,8 +43,8 @@ size_t repack_bytes(int64_t rows, int64_t K, fp4mr_fmt_t fmt)
     return align256((size_t)gemm_codes_bytes(rows, K)) + align256((size_t)gemm_scales_bytes(rows, K, (int)fmt));
 }
 
-fp4mr_status_t quantize_common(const void* x, int64_t rows, int64_t K, int had_block, fp4mr_fmt_t fmt, void* codes,
-                               void* scales, float* tensor_scale, void* workspace, size_t workspace_bytes,
+fp4mr_status_t quantize_common(const void* x, int64_t rows, int64_t K, int had_block, const void* rot, fp4mr_fmt_t fmt,
+                               void* codes, void* scales, float* tensor_scale, void* workspace, size_t workspace_bytes,
                                uint32_t flags, void* stream)
 {
     if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return FP4MR_ERR_FMT;
@@ -53,6 +53,7 @@ fp4mr_status_t quantize_common(const void* x, int64_t rows, int64_t K, int had_b
     if (fmt == FP4MR_NVFP4 && !tensor_scale) return FP4MR_ERR_NULL;
     if (had_block != 1 && had_block != 16 && had_block != 32 && had_block != 64 && had_block != 128) return FP4MR_ERR_HAD_BLOCK;
     if ((flags & FP4MR_INPUT_F32) && had_block != 1) return FP4MR_ERR_HAD_BLOCK;
+    if (rot && (had_block == 1 || !aligned16(rot))) return had_block == 1 ? FP4MR_ERR_HAD_BLOCK : FP4MR_ERR_ALIGN;
     if (rows <= 0 || K <= 0) return FP4MR_ERR_SHAPE;
     const int G = group_of(fmt);
     const int lcm = had_block > G ? had_block : G;  // both are powers of two
@@ -63,7 +64,7 @@ fp4mr_status_t quantize_common(const void* x, int64_t rows, int64_t K, int had_b
     const size_t need = quant_workspace(fmt, flags);
     if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return FP4MR_ERR_WORKSPACE;
 
-    const hipError_t e = launch_rotate_quantize(x, rows, K, had_block, (int)fmt, (flags & FP4MR_INPUT_F32) != 0,
+    const hipError_t e = launch_rotate_quantize(x, rows, K, had_block, rot, (int)fmt, (flags & FP4MR_INPUT_F32) != 0,
                                                 (flags & FP4MR_LAYOUT_GEMM) ? 1 : 0, (flags & FP4MR_STATIC_TENSOR_SCALE) != 0,
                                                 codes, scales, tensor_scale, workspace, !env_flag("FP4MR_SW_CODEC"),
                                                 static_cast<hipStream_t>(stream));
@@ -78,14 +79,22 @@ fp4mr_status_t fp4_rotate_quantize(const void* x, int64_t M, int64_t K, int had_
                                    void* scales_out, float* tensor_scale, void* workspace, size_t workspace_bytes,
                                    uint32_t flags, void* stream)
 {
-    return quantize_common(x, M, K, had_block, fmt, codes_out, scales_out, tensor_scale, workspace, workspace_bytes, flags, stream);
+    return quantize_common(x, M, K, had_block, nullptr, fmt, codes_out, scales_out, tensor_scale, workspace, workspace_bytes, flags, stream);
+}
+
+fp4mr_status_t fp4_rotate_quantize_dense(const void* x, int64_t M, int64_t K, int block, const void* rot_bf16, fp4mr_fmt_t fmt,
+                                         void* codes_out, void* scales_out, float* tensor_scale, void* workspace,
+                                         size_t workspace_bytes, uint32_t flags, void* stream)
+{
+    if (!rot_bf16) return FP4MR_ERR_NULL;
+    return quantize_common(x, M, K, block, rot_bf16, fmt, codes_out, scales_out, tensor_scale, workspace, workspace_bytes, flags, stream);
 }
 
 fp4mr_status_t fp4_quantize_weights(const void* w, int64_t N, int64_t K, int had_block, fp4mr_fmt_t fmt, void* codes_out,
                                     void* scales_out, float* tensor_scale, void* workspace, size_t workspace_bytes,
                                     uint32_t flags, void* stream)
 {
-    return quantize_common(w, N, K, had_block, fmt, codes_out, scales_out, tensor_scale, workspace, workspace_bytes, flags, stream);
+    return quantize_common(w, N, K, had_block, nullptr, fmt, codes_out, scales_out, tensor_scale, workspace, workspace_bytes, flags, stream);
 }
 
 fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* a_tensor_scale, const void* w_codes,

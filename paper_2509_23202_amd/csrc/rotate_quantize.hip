@@ -37,8 +37,9 @@ struct RqArgs {
     uint32_t* amax_partial;  // NVFP4 dynamic: one partial maximum per wave of the abs-max pass (workspace)
     int64_t rows, K;
     int64_t n_items;
-    int b;                 // Hadamard block (1 = none)
-    float c_hi, c_lo;      // 1/sqrt(b) split in two floats
+    int b;                 // rotation block (1 = none)
+    const uint16_t* rot;   // dense rotation: bf16 [b, b] row-major, y = x . rot (null: normalised Hadamard)
+    float c_hi, c_lo;      // 1/sqrt(b) split in two floats (1 and 0 for a dense rotation)
     int static_scale;
 };
 
@@ -172,6 +173,66 @@ __device__ __forceinline__ void build_hadamard_operand(v8bf (&hop)[BP / 16][BP /
     }
 }
 
+// The same operand for a caller-supplied rotation (arXiv 2509.23202, Section 4.2 item 1: below k = 256 a dense
+// k x k transform stays memory-bound, so any rotation costs what the Hadamard costs): A[i][k] = R[32s + k][c(t,i)]
+// taken from the bf16 matrix R [b, b] in global memory, block-diagonal when b < BP.
+template <int BP>
+__device__ __forceinline__ void build_dense_operand(v8bf (&hop)[BP / 16][BP / 32], int g, int q, int b, const uint16_t* __restrict__ rot)
+{
+    constexpr int S = BP / 32, T = BP / 16, NO = BP / 4;
+    const unsigned bm = (unsigned)b - 1u;
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const unsigned c = (unsigned)((g >> 2) * NO + 4 * t + (g & 3));
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const unsigned r_hi = (unsigned)(32 * s + 8 * q);
+            const bool same = (r_hi & ~bm) == (c & ~bm);
+            typedef unsigned short v8us __attribute__((ext_vector_type(8)));
+            v8us bits;
+#pragma unroll
+            for (unsigned e = 0; e < 8; ++e) bits[e] = same ? rot[((r_hi + e) & bm) * (unsigned)b + (c & bm)] : (unsigned short)0;
+            hop[t][s] = __builtin_bit_cast(v8bf, bits);
+        }
+    }
+}
+
+// Hadamard blocks of 64 and 128 on the 32-wide operand.  Sylvester's matrix is a Kronecker product,
+// H_64 = H_2 (x) H_32 and H_128 = H_4 (x) H_32: after the MFMA has applied H_32 to every 32-element vector, the
+// 2 (4) vectors of one block sit in the lanes g, g^1 (g, g^1, g^2, g^3) of a quad -- the 16 vectors of an MFMA group
+// are consecutive along K and blocks are aligned -- and one (two) butterfly levels across those lanes finish the
+// transform: lane bit clear -> self + partner, set -> partner - self.  The 128 x 128 operand (128 registers) and
+// its MFMAs are never needed.
+template <int CTRL>
+__device__ __forceinline__ float quad_partner(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+template <int T>
+__device__ __forceinline__ void kronecker_levels(v4f (&acc)[T], int g, int levels)
+{
+    float h[4 * T], p[4 * T];
+#pragma unroll
+    for (int i = 0; i < 4 * T; ++i) h[i] = acc[i >> 2][i & 3];
+    if (levels >= 1) {
+        const float sg = (g & 1) ? -1.0f : 1.0f;
+#pragma unroll
+        for (int i = 0; i < 4 * T; ++i) p[i] = quad_partner<0xB1>(h[i]);  // quad_perm [1,0,3,2]: lane ^ 1
+#pragma unroll
+        for (int i = 0; i < 4 * T; ++i) h[i] = __fmaf_rn(h[i], sg, p[i]);
+    }
+    if (levels >= 2) {
+        const float sg = (g & 2) ? -1.0f : 1.0f;
+#pragma unroll
+        for (int i = 0; i < 4 * T; ++i) p[i] = quad_partner<0x4E>(h[i]);  // quad_perm [2,3,0,1]: lane ^ 2
+#pragma unroll
+        for (int i = 0; i < 4 * T; ++i) h[i] = __fmaf_rn(h[i], sg, p[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < 4 * T; ++i) acc[i >> 2][i & 3] = h[i];
+}
+
 // ------------------------------------------------------------------------------------------------------
 // MFMA rotation kernel.  BP = b' in {32,64,128}; G = 32 (MXFP4) or 16 (NVFP4); LAYOUT 0 canonical / 1 GEMM;
 // PASS 0 = quantize, 1 = tensor abs-max only (NVFP4 pre-pass).
@@ -194,7 +255,10 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
     const int64_t n_waves = (int64_t)gridDim.x * kWavesPerBlock;
 
     v8bf hop[T][S];
-    build_hadamard_operand<BP>(hop, g, q, a.b);
+    if (a.rot) build_dense_operand<BP>(hop, g, q, a.b, a.rot);
+    else build_hadamard_operand<BP>(hop, g, q, a.b < BP ? a.b : BP);
+    // Hadamard blocks wider than the operand: finished by butterfly levels across the lanes of a quad
+    const int kron = (!a.rot && a.b > BP) ? (a.b == 2 * BP ? 1 : 2) : 0;
 
     const int64_t NV = a.rows * a.K / BP;  // vectors in the tensor
     const int64_t KC = a.K >> 7;
@@ -250,6 +314,7 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
                 for (int s = 0; s < S; ++s)
                     acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hop[t][s], __builtin_bit_cast(v8bf, xin[u][s]), acc[t], 0, 0, 0);
             }
+            if constexpr (LAYOUT == 0) kronecker_levels<T>(acc, g, kron);  // the launcher sends wider blocks here only in canonical order
             if constexpr (PASS == 1) {
 #pragma unroll
                 for (int t = 0; t < T; ++t)
@@ -362,7 +427,10 @@ __global__ __launch_bounds__(kThreads) void rq_frag_kernel(RqArgs a)
     }
 
     v8bf hop[T][S];
-    build_hadamard_operand<BP>(hop, g, q, a.b);
+    if (a.rot) build_dense_operand<BP>(hop, g, q, a.b, a.rot);
+    else build_hadamard_operand<BP>(hop, g, q, a.b < BP ? a.b : BP);
+    // Hadamard blocks wider than the operand: finished by butterfly levels across the lanes of a quad
+    const int kron = (!a.rot && a.b > BP) ? (a.b == 2 * BP ? 1 : 2) : 0;
 
     float s_T = 0.0f;
     if constexpr (G == 16) {
@@ -385,6 +453,7 @@ __global__ __launch_bounds__(kThreads) void rq_frag_kernel(RqArgs a)
                 for (int s = 0; s < S; ++s)
                     acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hop[t][s], __builtin_bit_cast(v8bf, xin[u][kk][s]), acc[t], 0, 0, 0);
             }
+            kronecker_levels<T>(acc, g, kron);
             float y[NO];
 #pragma unroll
             for (int t = 0; t < T; ++t)
@@ -564,13 +633,20 @@ hipError_t launch_frag(const RqArgs& a0, int grid_cap, hipStream_t st, int* bloc
     return hipGetLastError();
 }
 
+// The fragment-shaped kernel is for big calls with the built-in Hadamard (a few-token call has too few of its items
+// to fill the GPU; a dense rotation gathers its operand per wave and wants several items per wave).
+inline bool frag_kernel_eligible(const RqArgs& a)
+{
+    return round_up(a.rows, 16) / 16 * ((a.K + 511) / 512) >= 1024 && !a.rot;
+}
+
 template <int BP, int G, int LAYOUT, int PASS, bool HW>
 hipError_t launch_mfma(const RqArgs& a0, int grid_cap, hipStream_t st, int* blocks_out)
 {
     if constexpr (LAYOUT == 1 && PASS == 0 && BP <= 64) {
         // The fragment-shaped kernel walks 16 rows x 512 K per wave, which is what HBM likes for big tensors; a
         // few-token call has too few of those items to fill the GPU, so it keeps the one-fragment-per-wave kernel.
-        if (round_up(a0.rows, 16) / 16 * ((a0.K + 511) / 512) >= 1024) return launch_frag<BP, G, HW>(a0, grid_cap, st, blocks_out);
+        if (frag_kernel_eligible(a0)) return launch_frag<BP, G, HW>(a0, grid_cap, st, blocks_out);
     }
     // two fragments' worth of loads in flight per wave for the widest block (canonical order only: there an
     // item may run past the end and is masked per vector; GEMM-order items are whole fragments)
@@ -614,6 +690,10 @@ hipError_t dispatch_block(const RqArgs& a, bool in_f32, int grid_cap, hipStream_
         return launch_direct<uint16_t, G, LAYOUT, PASS, HW>(a, grid_cap, st, blocks_out);
     }
     if (a.b <= 32) return launch_mfma<32, G, LAYOUT, PASS, HW>(a, grid_cap, st, blocks_out);
+    // Hadamard blocks of 64 and 128 run on the 32-wide kernels plus butterfly levels across lanes wherever the
+    // vectors of an MFMA group are consecutive along K: canonical order, and the big-call GEMM-order kernel.
+    const bool k_consecutive = LAYOUT == 0 || frag_kernel_eligible(a);
+    if (!a.rot && k_consecutive) return launch_mfma<32, G, LAYOUT, PASS, HW>(a, grid_cap, st, blocks_out);
     if (a.b == 64) return launch_mfma<64, G, LAYOUT, PASS, HW>(a, grid_cap, st, blocks_out);
     return launch_mfma<128, G, LAYOUT, PASS, HW>(a, grid_cap, st, blocks_out);
 }
@@ -628,7 +708,7 @@ hipError_t dispatch_layout_pass(const RqArgs& a, bool in_f32, int layout, int pa
 
 }  // namespace
 
-hipError_t launch_rotate_quantize(const void* x, int64_t rows, int64_t K, int b, int fmt, bool in_f32,
+hipError_t launch_rotate_quantize(const void* x, int64_t rows, int64_t K, int b, const void* rot, int fmt, bool in_f32,
                                   int layout_gemm, bool static_scale, void* codes, void* scales,
                                   float* tensor_scale, void* workspace, bool hw_codec, hipStream_t st)
 {
@@ -641,13 +721,16 @@ hipError_t launch_rotate_quantize(const void* x, int64_t rows, int64_t K, int b,
     a.rows = rows;
     a.K = K;
     a.b = b;
-    const double c = 1.0 / sqrt((double)b);
+    a.rot = static_cast<const uint16_t*>(rot);
+    const double c = rot ? 1.0 : 1.0 / sqrt((double)b);  // a dense rotation carries its own normalisation
     a.c_hi = (float)c;
     a.c_lo = (float)(c - (double)a.c_hi);
     a.static_scale = static_scale ? 1 : 0;
     // One work item per wave: the hardware's workgroup dispatcher balances the load better than a grid-stride loop
     // over resident waves does (measured on [16384, 8192]: 53 us against 59 us), and the per-wave set-up is cheap.
-    const int grid_cap = 1 << 20;
+    // A dense rotation gathers its operand from memory (up to 256 two-byte loads per lane for b = 128): there the
+    // grid is capped at 8 workgroups per compute unit and each wave walks several items.
+    const int grid_cap = rot ? 256 * 8 : 1 << 20;
 
     hipError_t e;
     if (fmt == 1 && !static_scale) {

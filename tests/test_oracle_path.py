@@ -82,6 +82,64 @@ def test_rotation_rejects_bad_block(oracle):
         oracle.rotate(np.zeros((1, 48), dtype=np.uint16), 24)
 
 
+def dct_matrix(b):
+    """Orthonormal DCT-II matrix (textbook closed form), as the columns of a right-multiplied rotation."""
+    n = np.arange(b)[:, None]
+    k = np.arange(b)[None, :]
+    R = np.cos(np.pi * (2 * n + 1) * k / (2 * b)) * np.sqrt(2.0 / b)
+    R[:, 0] = 1.0 / np.sqrt(b)
+    return R
+
+
+@pytest.mark.parametrize("b", [16, 64])
+def test_dense_rotation_with_the_hadamard_matrix_is_the_hadamard_rotation(oracle, b):
+    """For b = 16 and 64 the normalised Hadamard matrix is exact in bf16 (entries +-1/4, +-1/8): the dense path
+    (arbitrary matrix, Section 4.2 item 1) must then reproduce the Hadamard path bit for bit."""
+    rng = np.random.default_rng(b)
+    xb = bits(rng.standard_normal((6, 4 * b)) * np.exp(rng.uniform(-3, 3, (6, 4 * b))))
+    R = oracle.hadamard(b).astype(np.float64) / np.sqrt(b)
+    Rb = bits(R)
+    assert np.array_equal(inputs.bf16_bits_to_f32(Rb).astype(np.float64), R)
+    assert np.array_equal(oracle.rotate_dense(xb, Rb), oracle.rotate(xb, b))
+
+
+@pytest.mark.parametrize("b", [16, 32, 128])
+def test_dense_rotation_identity_permutation_and_library_product(oracle, b):
+    rng = np.random.default_rng(100 + b)
+    xb = bits(rng.standard_normal((5, 3 * b)))
+    x = inputs.bf16_bits_to_f32(xb).astype(np.float64)
+    # identity: y = x exactly
+    assert np.array_equal(oracle.rotate_dense(xb, bits(np.eye(b))), x.astype(np.float32))
+    # a permutation matrix moves columns inside each block: y[:, j0 + c] = x[:, j0 + perm[c]]  (R[perm[c], c] = 1)
+    perm = rng.permutation(b)
+    P = np.zeros((b, b))
+    P[perm, np.arange(b)] = 1.0
+    y = oracle.rotate_dense(xb, bits(P))
+    want = x.reshape(5, 3, b)[:, :, perm].reshape(5, 3 * b)
+    assert np.array_equal(y, want.astype(np.float32))
+    # an asymmetric matrix against the library product: pins the orientation (x . R, not x . R^T) and the
+    # block-diagonal structure; error at most half an fp32 ulp of the exact value (one rounding)
+    Rb = bits(dct_matrix(b) + 0.05 * rng.standard_normal((b, b)))
+    R = inputs.bf16_bits_to_f32(Rb).astype(np.float64)
+    y = oracle.rotate_dense(xb, Rb).astype(np.float64)
+    want = np.einsum("mjr,rc->mjc", x.reshape(5, 3, b), R).reshape(5, 3 * b)
+    assert np.all(np.abs(y - want) <= 0.5 * np.spacing(np.abs(want).astype(np.float32)) * (1 + 1e-9) + 1e-300)
+    assert not np.allclose(y, np.einsum("mjr,cr->mjc", x.reshape(5, 3, b), R).reshape(5, 3 * b), atol=1e-3)
+
+
+def test_dense_rotation_with_dct_preserves_norm_and_product(oracle):
+    """An orthonormal DCT block (rounded to bf16) nearly preserves row norms, and rotating both operands with it
+    leaves the product nearly unchanged: what makes any orthogonal block usable in front of the GEMM."""
+    rng = np.random.default_rng(17)
+    b = 32
+    Rb = bits(dct_matrix(b))
+    xb, wb = bits(rng.standard_normal((6, 4 * b))), bits(rng.standard_normal((7, 4 * b)))
+    x, w = (inputs.bf16_bits_to_f32(t).astype(np.float64) for t in (xb, wb))
+    yx, yw = oracle.rotate_dense(xb, Rb).astype(np.float64), oracle.rotate_dense(wb, Rb).astype(np.float64)
+    assert np.allclose(np.linalg.norm(yx, axis=1), np.linalg.norm(x, axis=1), rtol=5e-3)
+    assert np.allclose(yx @ yw.T, x @ w.T, atol=0.2)       # bf16 rounding of the matrix: ~2^-9 relative per entry
+
+
 def test_rotating_both_operands_leaves_product_unchanged(oracle):
     """(X U)(W U)^T = X W^T for orthogonal block-diagonal U: pins that both operands use the same matrix,
     along the same axis (Section 4.1, Ingredient 3)."""
