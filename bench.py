@@ -260,7 +260,8 @@ def main():
             Rd = to_dev_bf16(inputs.f32_to_bf16_bits(R.astype(np.float32)))
             dense[f"dct{bd}"] = time_rq(lambda x_: fp4.fp4_rotate_quantize_dense(x_, Rd, fp4.MXFP4, flags=GL, codes=oc, scales=osc))
             dense[f"hadamard{bd}"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, bd, fp4.MXFP4, flags=GL, codes=oc, scales=osc))
-        result["rotate_quantize_other_rotations"] = dense
+        dense["hadamard32_mse_scales"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, 32, fp4.MXFP4, flags=GL | fp4.SCALE_MSE, codes=oc, scales=osc))
+        result["rotate_quantize_variants"] = dense
         del xs
 
     if args.copy_calibration:

@@ -64,7 +64,8 @@ enum {
     FP4MR_STATIC_TENSOR_SCALE = 1u << 2,  /* NVFP4 quantize: *tensor_scale already holds s_T; do not derive it */
     FP4MR_A_LAYOUT_GEMM = 1u << 3,        /* fp4_gemm: A codes/scales are in GEMM layout (else canonical)     */
     FP4MR_W_LAYOUT_GEMM = 1u << 4,        /* fp4_gemm: W codes/scales are in GEMM layout (else canonical)     */
-    FP4MR_OUT_F32 = 1u << 5               /* fp4_gemm: write the fp32 accumulator instead of bf16             */
+    FP4MR_OUT_F32 = 1u << 5,              /* fp4_gemm: write the fp32 accumulator instead of bf16             */
+    FP4MR_SCALE_MSE = 1u << 6             /* quantize ops: group scale by squared-error search (below)        */
 };
 
 /* operation selector for fp4_workspace_bytes */
@@ -86,6 +87,15 @@ enum { FP4MR_OP_ROTATE_QUANTIZE = 0, FP4MR_OP_QUANTIZE_WEIGHTS = 1, FP4MR_OP_GEM
 fp4mr_status_t fp4_rotate_quantize(const void* x, int64_t M, int64_t K, int had_block, fp4mr_fmt_t fmt,
                                    void* codes_out, void* scales_out, float* tensor_scale,
                                    void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
+
+/*
+ * Scale policy.  By default a group's scale is the abs-max one (Section 3 "Scales").  With FP4MR_SCALE_MSE the
+ * scale code is chosen to minimise the group's squared error sum_i (xhat_i - x_i)^2 (the objective of Section 4.1
+ * "Ingredient 1"; the "MSE" method of Section 4.2 item 1) among the abs-max code and its two neighbours, tried in
+ * that order (abs-max, one above, one below), a candidate winning only with a strictly smaller error; the error is
+ * evaluated in fp32.  MXFP4: E8M0 byte +-1; NVFP4: E4M3 code +-1 with the abs-max tensor scale.  Hardware codec
+ * only.  Costs about twice the vector-ALU work of abs-max.
+ */
 
 /*
  * The same with a caller-supplied rotation instead of the Hadamard: codes, scales = Q(X R) with R block-diagonal,

@@ -19,6 +19,8 @@
  *                       two by the OCP Microscaling rule  2^(floor(log2 amax) - 2).
  *   orc_quantize_nvfp4  MFP format (G=16, E=E2M1, S=E4M3) plus a per-tensor scale, Section 2 and
  *                       Section 4.1 "Ingredient 1":  Xhat = s_T * s_G * Q(X / (s_T * s_G)).
+ *   orc_quantize_*_mse  the same two formats with the group scale chosen to minimise the squared error
+ *                       (Section 4.1 "Ingredient 1" objective; "MSE" method of Section 4.2 item 1).
  *   orc_dequantize      the decoding side of the same two definitions.
  *   orc_matmul          Y = Ahat * What^T as a plain triple loop in fp64, plus S = |Ahat| * |What|^T.
  *
@@ -313,6 +315,139 @@ int orc_quantize_nvfp4(const float *y, int64_t M, int64_t K, const float *s_T_in
                 uint8_t hi = orc_e2m1_encode((double)a1);
                 codes[(m * K + g * G + i) / 2] = (uint8_t)(lo | (hi << 4));
             }
+        }
+    }
+    return 0;
+}
+
+/* ---------------------------------------------------------------- MSE scale policy
+ * Section 4.2 item 1 names two quantization methods for the fused kernel, abs-max and MSE, without spelling the
+ * second out; Section 4.1 "Ingredient 1" states its objective: choose the scales that minimise
+ * sum_i (Xhat_i - X_i)^2.  The reading taken here is a per-group search over the scale codes next to the abs-max
+ * one: candidates are tried in the order (abs-max code, one above, one below), a candidate replaces the current
+ * choice only if its squared error is strictly smaller.  Errors are exact in fp64 for MXFP4 (power-of-two scales)
+ * and accumulated in fp64 for NVFP4.  The NVFP4 tensor scale stays the abs-max one (the alternating optimisation
+ * over s_T of Ingredient 1 is an offline procedure and not part of the online path). */
+
+static double group_sq_err(const float *v, int G, double scale, double inv, int inv_is_f32, float r32,
+                           uint8_t *codes_out)
+{
+    double err = 0.0;
+    for (int i = 0; i < G; ++i) {
+        double t;
+        if (inv_is_f32) {
+            volatile float a = v[i] * r32; /* binary32 product, as the abs-max NVFP4 path rounds it */
+            t = (double)a;
+        } else {
+            t = (double)v[i] * inv; /* exact: power of two */
+        }
+        const uint8_t c = orc_e2m1_encode(t);
+        codes_out[i] = c;
+        const double d = (double)v[i] - orc_e2m1_decode(c) * scale;
+        err += d * d;
+    }
+    return err;
+}
+
+int orc_quantize_mxfp4_mse(const float *y, int64_t M, int64_t K, uint8_t *codes, uint8_t *scales)
+{
+    const int G = 32;
+    if (K % G != 0) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t g = 0; g < K / G; ++g) {
+            const float *v = y + m * K + g * G;
+            double amax = 0.0;
+            for (int i = 0; i < G; ++i) {
+                double a = fabs((double)v[i]);
+                if (a > amax) amax = a;
+            }
+            const int e0 = (int)orc_e8m0_from_amax(amax);
+            const int delta[3] = {0, 1, -1};
+            double best_err = 0.0;
+            int best_e = e0;
+            uint8_t best_codes[32], cand_codes[32];
+            for (int k = 0; k < 3; ++k) {
+                int e = e0 + delta[k];
+                if (e < 0) e = 0;
+                if (e > 254) e = 254;
+                const double err = group_sq_err(v, G, ldexp(1.0, e - 127), ldexp(1.0, 127 - e), 0, 0.0f, cand_codes);
+                if (k == 0 || err < best_err) {
+                    best_err = err;
+                    best_e = e;
+                    memcpy(best_codes, cand_codes, sizeof best_codes);
+                }
+            }
+            scales[m * (K / G) + g] = (uint8_t)best_e;
+            for (int i = 0; i < G; i += 2)
+                codes[(m * K + g * G + i) / 2] = (uint8_t)(best_codes[i] | (best_codes[i + 1] << 4));
+        }
+    }
+    return 0;
+}
+
+int orc_quantize_nvfp4_mse(const float *y, int64_t M, int64_t K, const float *s_T_in, uint8_t *codes,
+                           uint8_t *scales, float *s_T_out)
+{
+    const int G = 16;
+    if (K % G != 0) return -1;
+    float s_T;
+    if (s_T_in) {
+        s_T = *s_T_in;
+    } else {
+        float amax_T = 0.0f;
+        for (int64_t i = 0; i < M * K; ++i) {
+            float a = fabsf(y[i]);
+            if (a > amax_T) amax_T = a;
+        }
+        s_T = amax_T / 2688.0f;
+    }
+    *s_T_out = s_T;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t g = 0; g < K / G; ++g) {
+            const float *v = y + m * K + g * G;
+            float amax = 0.0f;
+            for (int i = 0; i < G; ++i) {
+                float a = fabsf(v[i]);
+                if (a > amax) amax = a;
+            }
+            int c0 = 0;
+            if (s_T > 0.0f) {
+                volatile float six_sT = 6.0f * s_T;
+                volatile float t = amax / six_sT;
+                c0 = (int)orc_e4m3_encode((double)t);
+            }
+            const int delta[3] = {0, 1, -1};
+            double best_err = 0.0;
+            int best_c = c0;
+            uint8_t best_codes[16], cand_codes[16];
+            for (int k = 0; k < 3; ++k) {
+                int c = c0 + delta[k];
+                if (c < 0) c = 0;
+                if (c > 0x7e) c = 0x7e;
+                volatile float s_G = (float)orc_e4m3_decode((uint8_t)c);
+                volatile float d = s_T * s_G;
+                double err;
+                if (d == 0.0f) {
+                    err = 0.0;
+                    for (int i = 0; i < G; ++i) {
+                        cand_codes[i] = 0;
+                        err += (double)v[i] * (double)v[i];
+                    }
+                } else {
+                    volatile float r = 1.0f / d;
+                    err = group_sq_err(v, G, (double)d, 0.0, 1, r, cand_codes);
+                }
+                if (k == 0 || err < best_err) {
+                    best_err = err;
+                    best_c = c;
+                    memcpy(best_codes, cand_codes, sizeof best_codes);
+                }
+            }
+            scales[m * (K / G) + g] = (uint8_t)best_c;
+            for (int i = 0; i < G; i += 2)
+                codes[(m * K + g * G + i) / 2] = (uint8_t)(best_codes[i] | (best_codes[i + 1] << 4));
         }
     }
     return 0;

@@ -68,6 +68,10 @@ def _load():
         L.orc_quantize_mxfp4.restype = i32
         L.orc_quantize_nvfp4.argtypes = [p, i64, i64, p, p, p, p]
         L.orc_quantize_nvfp4.restype = i32
+        L.orc_quantize_mxfp4_mse.argtypes = [p, i64, i64, p, p]
+        L.orc_quantize_mxfp4_mse.restype = i32
+        L.orc_quantize_nvfp4_mse.argtypes = [p, i64, i64, p, p, p, p]
+        L.orc_quantize_nvfp4_mse.restype = i32
         L.orc_dequantize.argtypes = [p, p, dbl, i32, i64, i64, p]
         L.orc_dequantize.restype = i32
         L.orc_matmul.argtypes = [p, p, i64, i64, i64, p, p]
@@ -154,8 +158,12 @@ def rotate_f64(x: np.ndarray, b: int) -> np.ndarray:
     return y
 
 
-def quantize(y_f32: np.ndarray, fmt: int, tensor_scale: float | None = None):
-    """fp32 [M,K] -> (codes u8 [M,K/2], scales u8 [M,K/G], s_T float32 scalar or None)."""
+def quantize(y_f32: np.ndarray, fmt: int, tensor_scale: float | None = None, policy: str = "absmax"):
+    """fp32 [M,K] -> (codes u8 [M,K/2], scales u8 [M,K/G], s_T float32 scalar or None).
+    policy: "absmax" (abs-max group scales) or "mse" (group scale code chosen among the abs-max code and its two
+    neighbours to minimise the group's squared error)."""
+    if policy not in ("absmax", "mse"):
+        raise ValueError(policy)
     y = np.ascontiguousarray(y_f32, dtype=np.float32)
     M, K = y.shape
     G = GROUP[fmt]
@@ -164,7 +172,8 @@ def quantize(y_f32: np.ndarray, fmt: int, tensor_scale: float | None = None):
     codes = np.empty((M, K // 2), dtype=np.uint8)
     scales = np.empty((M, K // G), dtype=np.uint8)
     if fmt == MXFP4:
-        rc = _load().orc_quantize_mxfp4(_ptr(y), M, K, _ptr(codes), _ptr(scales))
+        fn = _load().orc_quantize_mxfp4 if policy == "absmax" else _load().orc_quantize_mxfp4_mse
+        rc = fn(_ptr(y), M, K, _ptr(codes), _ptr(scales))
         s_T = None
     else:
         s_out = np.zeros(1, dtype=np.float32)
@@ -172,7 +181,8 @@ def quantize(y_f32: np.ndarray, fmt: int, tensor_scale: float | None = None):
         if tensor_scale is not None:
             s_in_arr = np.array([tensor_scale], dtype=np.float32)
             s_in = _ptr(s_in_arr)
-        rc = _load().orc_quantize_nvfp4(_ptr(y), M, K, s_in, _ptr(codes), _ptr(scales), _ptr(s_out))
+        fn = _load().orc_quantize_nvfp4 if policy == "absmax" else _load().orc_quantize_nvfp4_mse
+        rc = fn(_ptr(y), M, K, s_in, _ptr(codes), _ptr(scales), _ptr(s_out))
         s_T = np.float32(s_out[0])
     if rc != 0:
         raise ValueError("quantize failed")

@@ -26,6 +26,7 @@ STATIC_TENSOR_SCALE = 1 << 2
 A_LAYOUT_GEMM = 1 << 3
 W_LAYOUT_GEMM = 1 << 4
 OUT_F32 = 1 << 5
+SCALE_MSE = 1 << 6
 OP_ROTATE_QUANTIZE, OP_QUANTIZE_WEIGHTS, OP_GEMM = 0, 1, 2
 
 _p, _i64, _i32, _u32, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32, ctypes.c_size_t

@@ -12,7 +12,7 @@ using namespace fp4mr;
 
 namespace {
 
-constexpr uint32_t kQuantFlags = FP4MR_LAYOUT_GEMM | FP4MR_INPUT_F32 | FP4MR_STATIC_TENSOR_SCALE;
+constexpr uint32_t kQuantFlags = FP4MR_LAYOUT_GEMM | FP4MR_INPUT_F32 | FP4MR_STATIC_TENSOR_SCALE | FP4MR_SCALE_MSE;
 constexpr uint32_t kGemmFlags = FP4MR_A_LAYOUT_GEMM | FP4MR_W_LAYOUT_GEMM | FP4MR_OUT_F32;
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -66,7 +66,7 @@ fp4mr_status_t quantize_common(const void* x, int64_t rows, int64_t K, int had_b
 
     const hipError_t e = launch_rotate_quantize(x, rows, K, had_block, rot, (int)fmt, (flags & FP4MR_INPUT_F32) != 0,
                                                 (flags & FP4MR_LAYOUT_GEMM) ? 1 : 0, (flags & FP4MR_STATIC_TENSOR_SCALE) != 0,
-                                                codes, scales, tensor_scale, workspace, !env_flag("FP4MR_SW_CODEC"),
+                                                (flags & FP4MR_SCALE_MSE) != 0, codes, scales, tensor_scale, workspace, !env_flag("FP4MR_SW_CODEC"),
                                                 static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
 }

@@ -8,9 +8,10 @@
 
 namespace fp4mr {
 
+// mse: group scales by the squared-error search instead of abs-max.
 // rot: null for the normalised Hadamard of size b, else a bf16 [b, b] row-major matrix (y = x . rot per block)
 hipError_t launch_rotate_quantize(const void* x, int64_t rows, int64_t K, int b, const void* rot, int fmt, bool in_f32,
-                                  int layout_gemm, bool static_scale, void* codes, void* scales,
+                                  int layout_gemm, bool static_scale, bool mse, void* codes, void* scales,
                                   float* tensor_scale, void* workspace, bool hw_codec, hipStream_t st);
 
 // canonical -> GEMM layout copy of one quantized operand (codes and scales)

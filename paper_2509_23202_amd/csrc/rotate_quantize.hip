@@ -120,6 +120,140 @@ struct GroupQuant {
             }
         }
     }
+
+    // ---- MSE scale policy (Section 4.1 "Ingredient 1": the scales that minimise sum (Xhat - X)^2; the "MSE" method of
+    // Section 4.2 item 1).  Per group the scale code is searched among the abs-max code and its two neighbours, tried
+    // in the order (abs-max, one above, one below); a candidate wins only with a strictly smaller squared error.
+    // The error is accumulated in fp32 per lane and added across the lanes of the group symmetrically, so that every
+    // lane of a group takes the same decision.  Hardware converts only (encode and decode).
+    typedef float v2f_t __attribute__((ext_vector_type(2)));
+
+    // codes of 8 values at scale `sc` (E8M0 in the exponent field) and the squared error they leave
+    __device__ static __forceinline__ uint32_t try8(const float (&t)[8], float sc, float mul, float& err)
+    {
+        uint32_t p = 0;
+        p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, t[0], t[1], sc, 0);
+        p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, t[2], t[3], sc, 1);
+        p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, t[4], t[5], sc, 2);
+        p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, t[6], t[7], sc, 3);
+        const v2f_t q0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(p, sc, 0);
+        const v2f_t q1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(p, sc, 1);
+        const v2f_t q2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(p, sc, 2);
+        const v2f_t q3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(p, sc, 3);
+        const float q[8] = {q0[0], q0[1], q1[0], q1[1], q2[0], q2[1], q3[0], q3[1]};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float d = t[i] - q[i];
+            err = __fmaf_rn(d * mul, d * mul, err);
+        }
+        return p;
+    }
+
+    __device__ static __forceinline__ float group_sum(float e)
+    {
+        if constexpr (LG >= 2) e += __shfl_xor(e, XOR_LO);
+        if constexpr (LG >= 4) e += __shfl_xor(e, XOR_LO * 2);
+        return e;
+    }
+
+    __device__ static __forceinline__ void mx_mse(const float (&y)[NO], uint32_t (&out)[ND], uint32_t (&sc)[NG])
+    {
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) {
+            float amax = 0.0f;
+#pragma unroll
+            for (int i = 0; i < VG; ++i) amax = fabs_max(amax, y[gi * VG + i]);
+            if constexpr (LG >= 2) amax = fmaxf(amax, __shfl_xor(amax, XOR_LO));
+            if constexpr (LG >= 4) amax = fmaxf(amax, __shfl_xor(amax, XOR_LO * 2));
+            const int ef = (int)((__float_as_uint(amax) >> 23) & 0xffu);
+            const int byte0 = max(ef - 2, 0);
+            float best_err = 0.0f;
+            uint32_t best_byte = 0, best[VG / 8];
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                const int byte = min(max(byte0 + (k == 0 ? 0 : (k == 1 ? 1 : -1)), 0), 254);
+                const float scf = __uint_as_float((uint32_t)byte << 23);
+                float err = 0.0f;
+                uint32_t cand[VG / 8];
+#pragma unroll
+                for (int d = 0; d < VG / 8; ++d) {
+                    float t[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) t[i] = y[gi * VG + d * 8 + i];
+                    cand[d] = try8(t, scf, 1.0f, err);
+                }
+                err = group_sum(err);
+                if (k == 0 || err < best_err) {
+                    best_err = err;
+                    best_byte = (uint32_t)byte;
+#pragma unroll
+                    for (int d = 0; d < VG / 8; ++d) best[d] = cand[d];
+                }
+            }
+            sc[gi] = best_byte;
+#pragma unroll
+            for (int d = 0; d < VG / 8; ++d) out[gi * (VG / 8) + d] = best[d];
+        }
+    }
+
+    __device__ static __forceinline__ void nv_mse(const float (&y)[NO], float s_T, uint32_t (&out)[ND], uint32_t (&sc)[NG])
+    {
+        const float six_sT = 6.0f * s_T;
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) {
+            float amax = 0.0f;
+#pragma unroll
+            for (int i = 0; i < VG; ++i) amax = fabs_max(amax, y[gi * VG + i]);
+            if constexpr (LG >= 2) amax = fmaxf(amax, __shfl_xor(amax, XOR_LO));
+            if constexpr (LG >= 4) amax = fmaxf(amax, __shfl_xor(amax, XOR_LO * 2));
+            int c0 = 0;
+            if (s_T > 0.0f) c0 = (int)e4m3_encode<true>(__fdiv_rn(amax, six_sT));
+            float best_err = 0.0f;
+            uint32_t best_c = 0, best[VG / 8];
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                const int c = min(max(c0 + (k == 0 ? 0 : (k == 1 ? 1 : -1)), 0), 0x7e);
+                const float d = s_T * e4m3_decode<true>((uint32_t)c);
+                const float r = (d == 0.0f) ? 0.0f : __fdiv_rn(1.0f, d);
+                float err = 0.0f;
+                uint32_t cand[VG / 8];
+#pragma unroll
+                for (int dd = 0; dd < VG / 8; ++dd) {
+                    // the error is measured in units of d: (y r - q)^2 d^2 = (y - q d)^2 up to the rounding of y r
+                    float t[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) t[i] = y[gi * VG + dd * 8 + i] * r;
+                    if (d == 0.0f) {
+                        cand[dd] = 0u;
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) err = __fmaf_rn(y[gi * VG + dd * 8 + i], y[gi * VG + dd * 8 + i], err);
+                    } else {
+                        cand[dd] = try8(t, 1.0f, d, err);
+                    }
+                }
+                err = group_sum(err);
+                if (k == 0 || err < best_err) {
+                    best_err = err;
+                    best_c = (uint32_t)c;
+#pragma unroll
+                    for (int dd = 0; dd < VG / 8; ++dd) best[dd] = cand[dd];
+                }
+            }
+            sc[gi] = best_c;
+#pragma unroll
+            for (int dd = 0; dd < VG / 8; ++dd) out[gi * (VG / 8) + dd] = best[dd];
+        }
+    }
+
+    template <bool MSE>
+    __device__ static __forceinline__ void run(const float (&y)[NO], float s_T, uint32_t (&out)[ND], uint32_t (&sc)[NG])
+    {
+        if constexpr (G == 32) {
+            if constexpr (MSE) mx_mse(y, out, sc); else mx(y, out, sc);
+        } else {
+            if constexpr (MSE) nv_mse(y, s_T, out, sc); else nv(y, s_T, out, sc);
+        }
+    }
 };
 
 template <int ND>
@@ -240,7 +374,7 @@ __device__ __forceinline__ void kronecker_levels(v4f (&acc)[T], int g, int level
 // Work item = FR * (128/BP) supertiles = FR * 2048 elements.
 //   canonical: supertiles are consecutive runs of 16 vectors in flat (row-major) order;
 //   GEMM:      an item is FR fragments (16 rows x 128 K); supertile u covers K-offset u*BP of all 16 rows.
-template <int BP, int G, int LAYOUT, int PASS, bool HW, int FR>
+template <int BP, int G, int LAYOUT, int PASS, bool HW, int FR, bool MSE>
 __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
 {
     constexpr int S = BP / 32;           // K-steps of the contraction
@@ -331,7 +465,7 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
                     y[4 * t + v] = __fmaf_rn(h, a.c_hi, h * a.c_lo);
                 }
             uint32_t out[GQ::ND], sc[GQ::NG];
-            if constexpr (G == 32) GQ::mx(y, out, sc); else GQ::nv(y, s_T, out, sc);
+            GQ::template run<MSE>(y, s_T, out, sc);
 
             if constexpr (LAYOUT == 0) {
                 if (valid[u]) {
@@ -380,7 +514,7 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
 //     NVFP4: 128 bytes per fragment).
 // One item per workgroup, no grid-stride loop: the dispatcher balances the load.  Input loads and all stores are
 // non-temporal: every byte is touched exactly once.
-template <int BP, int G, bool HW, int KI>
+template <int BP, int G, bool HW, int KI, bool MSE>
 __global__ __launch_bounds__(kThreads) void rq_frag_kernel(RqArgs a)
 {
     constexpr int S = BP / 32, T = BP / 16, NO = BP / 4;
@@ -463,7 +597,7 @@ __global__ __launch_bounds__(kThreads) void rq_frag_kernel(RqArgs a)
                     y[4 * t + v] = __fmaf_rn(h, a.c_hi, h * a.c_lo);
                 }
             uint32_t out[GQ::ND], sc[GQ::NG];
-            if constexpr (G == 32) GQ::mx(y, out, sc); else GQ::nv(y, s_T, out, sc);
+            GQ::template run<MSE>(y, s_T, out, sc);
             const int rr = wib * RPW + u;  // row inside the row-block
             const int fr = kk * (BP / 8) + (e_grp >> 7), e0 = e_grp & 127;  // fragment of the item, offset inside it
             const int d = fr * 256 + ((((e0 >> 5) * 16 + rr) << 2) + ((e0 & 31) >> 3));
@@ -516,7 +650,7 @@ __global__ __launch_bounds__(kThreads) void rq_frag_kernel(RqArgs a)
 // No-rotation kernel (had_block = 1), bf16 or fp32 input.  Lane handles 8 consecutive elements; a group of G
 // spans G/8 adjacent lanes.  Work item = 2048 elements (256 lane-pieces, 4 per lane).
 //   canonical: flat;   GEMM: item = fragment, piece p = j*64+lane: row = p/16, K-offset 8*(p%16).
-template <typename TIN, int G, int LAYOUT, int PASS, bool HW>
+template <typename TIN, int G, int LAYOUT, int PASS, bool HW, bool MSE>
 __global__ __launch_bounds__(kThreads) void q_direct_kernel(RqArgs a)
 {
     using GQ = GroupQuant<G, 8, 1, HW>;
@@ -577,7 +711,7 @@ __global__ __launch_bounds__(kThreads) void q_direct_kernel(RqArgs a)
                 continue;
             }
             uint32_t out[1], sc[1];
-            if constexpr (G == 32) GQ::mx(y, out, sc); else GQ::nv(y, s_T, out, sc);
+            GQ::template run<MSE>(y, s_T, out, sc);
             if constexpr (LAYOUT == 0) {
                 if (valid) {
                     *reinterpret_cast<uint32_t*>(a.codes + (e0 >> 1)) = out[0];
@@ -616,7 +750,7 @@ __global__ __launch_bounds__(1024) void amax_finalize_kernel(const uint32_t* par
 }
 
 // ------------------------------------------------------------------------------------------------------
-template <int BP, int G, bool HW>
+template <int BP, int G, bool HW, bool MSE>
 hipError_t launch_frag(const RqArgs& a0, int grid_cap, hipStream_t st, int* blocks_out)
 {
     RqArgs a = a0;
@@ -629,7 +763,7 @@ hipError_t launch_frag(const RqArgs& a0, int grid_cap, hipStream_t st, int* bloc
     const int64_t gy = rbs < 32768 ? rbs : 32768, gz = (rbs + gy - 1) / gy;
     if (rbs < 1 || gz > 65535 || ipr > 0x7fffffffll) return hipErrorInvalidValue;
     if (blocks_out) *blocks_out = (int)(ipr * gy * gz);
-    hipLaunchKernelGGL((rq_frag_kernel<BP, G, HW, KI>), dim3((unsigned)ipr, (unsigned)gy, (unsigned)gz), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((rq_frag_kernel<BP, G, HW, KI, MSE>), dim3((unsigned)ipr, (unsigned)gy, (unsigned)gz), dim3(kThreads), 0, st, a);
     return hipGetLastError();
 }
 
@@ -640,13 +774,13 @@ inline bool frag_kernel_eligible(const RqArgs& a)
     return round_up(a.rows, 16) / 16 * ((a.K + 511) / 512) >= 1024 && !a.rot;
 }
 
-template <int BP, int G, int LAYOUT, int PASS, bool HW>
+template <int BP, int G, int LAYOUT, int PASS, bool HW, bool MSE>
 hipError_t launch_mfma(const RqArgs& a0, int grid_cap, hipStream_t st, int* blocks_out)
 {
     if constexpr (LAYOUT == 1 && PASS == 0 && BP <= 64) {
         // The fragment-shaped kernel walks 16 rows x 512 K per wave, which is what HBM likes for big tensors; a
         // few-token call has too few of those items to fill the GPU, so it keeps the one-fragment-per-wave kernel.
-        if (frag_kernel_eligible(a0)) return launch_frag<BP, G, HW>(a0, grid_cap, st, blocks_out);
+        if (frag_kernel_eligible(a0)) return launch_frag<BP, G, HW, MSE>(a0, grid_cap, st, blocks_out);
     }
     // two fragments' worth of loads in flight per wave for the widest block (canonical order only: there an
     // item may run past the end and is masked per vector; GEMM-order items are whole fragments)
@@ -664,11 +798,11 @@ hipError_t launch_mfma(const RqArgs& a0, int grid_cap, hipStream_t st, int* bloc
     if (blocks > grid_cap) blocks = grid_cap;
     if (blocks < 1) blocks = 1;
     if (blocks_out) *blocks_out = (int)blocks;
-    hipLaunchKernelGGL((rq_mfma_kernel<BP, G, LAYOUT, PASS, HW, FR>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((rq_mfma_kernel<BP, G, LAYOUT, PASS, HW, FR, MSE>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
     return hipGetLastError();
 }
 
-template <typename TIN, int G, int LAYOUT, int PASS, bool HW>
+template <typename TIN, int G, int LAYOUT, int PASS, bool HW, bool MSE>
 hipError_t launch_direct(const RqArgs& a0, int grid_cap, hipStream_t st, int* blocks_out)
 {
     RqArgs a = a0;
@@ -678,38 +812,38 @@ hipError_t launch_direct(const RqArgs& a0, int grid_cap, hipStream_t st, int* bl
     if (blocks > grid_cap) blocks = grid_cap;
     if (blocks < 1) blocks = 1;
     if (blocks_out) *blocks_out = (int)blocks;
-    hipLaunchKernelGGL((q_direct_kernel<TIN, G, LAYOUT, PASS, HW>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((q_direct_kernel<TIN, G, LAYOUT, PASS, HW, MSE>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
     return hipGetLastError();
 }
 
-template <int G, int LAYOUT, int PASS, bool HW>
+template <int G, int LAYOUT, int PASS, bool HW, bool MSE>
 hipError_t dispatch_block(const RqArgs& a, bool in_f32, int grid_cap, hipStream_t st, int* blocks_out)
 {
     if (a.b == 1) {
-        if (in_f32) return launch_direct<float, G, LAYOUT, PASS, HW>(a, grid_cap, st, blocks_out);
-        return launch_direct<uint16_t, G, LAYOUT, PASS, HW>(a, grid_cap, st, blocks_out);
+        if (in_f32) return launch_direct<float, G, LAYOUT, PASS, HW, MSE>(a, grid_cap, st, blocks_out);
+        return launch_direct<uint16_t, G, LAYOUT, PASS, HW, MSE>(a, grid_cap, st, blocks_out);
     }
-    if (a.b <= 32) return launch_mfma<32, G, LAYOUT, PASS, HW>(a, grid_cap, st, blocks_out);
+    if (a.b <= 32) return launch_mfma<32, G, LAYOUT, PASS, HW, MSE>(a, grid_cap, st, blocks_out);
     // Hadamard blocks of 64 and 128 run on the 32-wide kernels plus butterfly levels across lanes wherever the
     // vectors of an MFMA group are consecutive along K: canonical order, and the big-call GEMM-order kernel.
     const bool k_consecutive = LAYOUT == 0 || frag_kernel_eligible(a);
-    if (!a.rot && k_consecutive) return launch_mfma<32, G, LAYOUT, PASS, HW>(a, grid_cap, st, blocks_out);
-    if (a.b == 64) return launch_mfma<64, G, LAYOUT, PASS, HW>(a, grid_cap, st, blocks_out);
-    return launch_mfma<128, G, LAYOUT, PASS, HW>(a, grid_cap, st, blocks_out);
+    if (!a.rot && k_consecutive) return launch_mfma<32, G, LAYOUT, PASS, HW, MSE>(a, grid_cap, st, blocks_out);
+    if (a.b == 64) return launch_mfma<64, G, LAYOUT, PASS, HW, MSE>(a, grid_cap, st, blocks_out);
+    return launch_mfma<128, G, LAYOUT, PASS, HW, MSE>(a, grid_cap, st, blocks_out);
 }
 
-template <int G, bool HW>
+template <int G, bool HW, bool MSE = false>
 hipError_t dispatch_layout_pass(const RqArgs& a, bool in_f32, int layout, int pass, int grid_cap, hipStream_t st, int* blocks_out = nullptr)
 {
-    if (pass == 1) return dispatch_block<G, 0, 1, HW>(a, in_f32, grid_cap, st, blocks_out);  // layout irrelevant for the abs-max pass
-    if (layout == 0) return dispatch_block<G, 0, 0, HW>(a, in_f32, grid_cap, st, blocks_out);
-    return dispatch_block<G, 1, 0, HW>(a, in_f32, grid_cap, st, blocks_out);
+    if (pass == 1) return dispatch_block<G, 0, 1, HW, false>(a, in_f32, grid_cap, st, blocks_out);  // layout and scale policy do not matter for the abs-max pass
+    if (layout == 0) return dispatch_block<G, 0, 0, HW, MSE>(a, in_f32, grid_cap, st, blocks_out);
+    return dispatch_block<G, 1, 0, HW, MSE>(a, in_f32, grid_cap, st, blocks_out);
 }
 
 }  // namespace
 
 hipError_t launch_rotate_quantize(const void* x, int64_t rows, int64_t K, int b, const void* rot, int fmt, bool in_f32,
-                                  int layout_gemm, bool static_scale, void* codes, void* scales,
+                                  int layout_gemm, bool static_scale, bool mse, void* codes, void* scales,
                                   float* tensor_scale, void* workspace, bool hw_codec, hipStream_t st)
 {
     RqArgs a{};
@@ -744,6 +878,11 @@ hipError_t launch_rotate_quantize(const void* x, int64_t rows, int64_t K, int b,
         // blocks that had no item still wrote their (zero) partial: every wave of the grid stores one
         hipLaunchKernelGGL(amax_finalize_kernel, dim3(1), dim3(1024), 0, st, a.amax_partial, pass_blocks * kWavesPerBlock, a.amax_bits);
         if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if (mse) {
+        // the scale search is written with the hardware converts only
+        return fmt == 0 ? dispatch_layout_pass<32, true, true>(a, in_f32, layout_gemm, 0, grid_cap, st)
+                        : dispatch_layout_pass<16, true, true>(a, in_f32, layout_gemm, 0, grid_cap, st);
     }
     if (fmt == 0)
         return hw_codec ? dispatch_layout_pass<32, true>(a, in_f32, layout_gemm, 0, grid_cap, st)

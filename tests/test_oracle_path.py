@@ -408,3 +408,106 @@ def test_oracle_is_not_imported_by_the_product():
     for p in root.rglob("*"):
         if p.suffix in {".py", ".hip", ".h", ".hpp", ".cpp", ".c"}:
             assert not pat.search(p.read_text()), p
+
+
+# ---------------------------------------------------------------- MSE scale policy (Section 4.1 Ingredient 1 objective)
+E2M1_GRID = np.array([0, .5, 1, 1.5, 2, 3, 4, 6])
+
+
+def _brute_group(v, scale):
+    """Nearest grid point (saturating) of v / scale by exhaustive search, returned as dequantized values."""
+    cand = np.concatenate([-E2M1_GRID[::-1], E2M1_GRID]) * scale
+    return cand[np.argmin(np.abs(v[:, None] - cand[None, :]), axis=1)]
+
+
+def _group_err(y, deq, G):
+    return ((y.astype(np.float64) - deq) ** 2).reshape(y.shape[0], -1, G).sum(-1)
+
+
+@pytest.mark.parametrize("fmt", [MX, NV])
+def test_mse_policy_never_loses_to_absmax_and_moves_by_one_code(oracle, fmt):
+    rng = np.random.default_rng(31 + fmt)
+    G = 32 if fmt == MX else 16
+    y = (rng.laplace(size=(64, 512)) * np.exp(rng.uniform(-2, 2, (64, 512)))).astype(np.float32)
+    c0, s0, T0 = oracle.quantize(y, fmt)
+    c1, s1, T1 = oracle.quantize(y, fmt, policy="mse")
+    if fmt == NV:
+        assert T0 == T1                      # the tensor scale is not part of the search
+    e0 = _group_err(y, oracle.dequantize(c0, s0, fmt, T0), G)
+    e1 = _group_err(y, oracle.dequantize(c1, s1, fmt, T1), G)
+    assert np.all(e1 <= e0)                  # abs-max is one of the candidates
+    assert np.all(np.abs(s1.astype(int) - s0.astype(int)) <= 1)
+    assert (s1 != s0).mean() > 0.05          # and the search is not vacuous on heavy-tailed data
+    assert e1.sum() < 0.97 * e0.sum()
+    # where the scale did not move, nothing else did
+    same = np.repeat(s1 == s0, G // 2, axis=1)
+    assert np.array_equal(c1[same], c0[same])
+
+
+def test_mse_policy_mxfp4_matches_brute_force_over_the_three_scales(oracle):
+    """Independent recomputation: for every group try the three scale bytes with a brute-force nearest-grid
+    quantizer and keep the best in the documented order (abs-max, one above, one below; strict improvement)."""
+    rng = np.random.default_rng(41)
+    y = (rng.standard_normal((16, 256)) * np.exp(rng.uniform(-3, 3, (16, 256)))).astype(np.float32)
+    y[0, :32] = 0.0
+    c, s, _ = oracle.quantize(y, MX, policy="mse")
+    _, s_abs, _ = oracle.quantize(y, MX)
+    deq = oracle.dequantize(c, s, MX)
+    yg = y.astype(np.float64).reshape(16, 8, 32)
+    for m in range(16):
+        for g in range(8):
+            v = yg[m, g]
+            best, best_e = None, None
+            for d in (0, 1, -1):
+                e = int(np.clip(int(s_abs[m, g]) + d, 0, 254))
+                err = ((v - _brute_group(v, 2.0 ** (e - 127))) ** 2).sum()
+                if best is None or err < best:
+                    best, best_e = err, e
+            assert s[m, g] == best_e
+            assert np.isclose(((v - deq[m, g * 32:(g + 1) * 32]) ** 2).sum(), best, rtol=1e-12, atol=0)
+
+
+def test_mse_policy_keeps_absmax_on_exactly_representable_groups(oracle):
+    """Zero error at the abs-max scale cannot be improved: ties keep the abs-max code (also the all-zero group)."""
+    rng = np.random.default_rng(43)
+    vals = np.concatenate([-E2M1_GRID[1:], E2M1_GRID])
+    y = rng.choice(vals, size=(8, 128)) * np.exp2(rng.integers(-6, 6, (8, 4))).repeat(32, axis=1)
+    y[:, ::32] = 6.0 * np.exp2(rng.integers(-6, 6, (8, 4)))            # pin each group's abs-max to 6 * 2^e
+    y = y.astype(np.float32)
+    y[3, 32:64] = 0.0
+    a = oracle.quantize(y, MX)
+    b = oracle.quantize(y, MX, policy="mse")
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_mse_policy_nvfp4_candidates_by_independent_recipe(oracle):
+    """float32 recomputation of the NVFP4 search with numpy/torch casts (not the C code)."""
+    import torch
+    rng = np.random.default_rng(47)
+    y = (rng.standard_t(3, size=(8, 128))).astype(np.float32)
+    c, s, T = oracle.quantize(y, NV, policy="mse")
+    _, s_abs, _ = oracle.quantize(y, NV)
+    yg = y.reshape(8, 8, 16)
+    for m in range(8):
+        for g in range(8):
+            v = yg[m, g]
+            best, best_c = None, None
+            for d in (0, 1, -1):
+                code = int(np.clip(int(s_abs[m, g]) + d, 0, 0x7e))
+                sg = torch.tensor([code], dtype=torch.uint8).view(torch.float8_e4m3fn).float().numpy()[0]
+                dd = np.float32(T) * np.float32(sg)
+                if dd == 0:
+                    err = (v.astype(np.float64) ** 2).sum()
+                else:
+                    r = np.float32(1.0) / dd
+                    t = (v * r).astype(np.float32).astype(np.float64)
+                    q = _brute_group(t, 1.0)
+                    # ties: the brute force picks the first minimum; recompute with even-mantissa ties
+                    mid = np.isin(np.abs(t), [0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0])
+                    if mid.any():
+                        even = {0.25: 0.0, 0.75: 1.0, 1.25: 1.0, 1.75: 2.0, 2.5: 2.0, 3.5: 4.0, 5.0: 4.0}
+                        q = np.where(mid, np.sign(t) * np.vectorize(lambda a: even.get(a, 0.0))(np.abs(t)), q)
+                    err = ((v.astype(np.float64) - q * float(dd)) ** 2).sum()
+                if best is None or err < best:
+                    best, best_c = err, code
+            assert s[m, g] == best_c
