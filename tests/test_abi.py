@@ -26,8 +26,8 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert {"fp4_rotate_quantize", "fp4_quantize_weights", "fp4_gemm", "fp4_workspace_bytes", "fp4_packed_bytes",
-            "fp4_status_string", "fp4_version"} <= set(names)
+    assert {"fp4_rotate_quantize", "fp4_rotate_quantize_dense", "fp4_quantize_weights", "fp4_gemm", "fp4_workspace_bytes",
+            "fp4_packed_bytes", "fp4_status_string", "fp4_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
     lib.fp4_version.restype = ctypes.c_int
@@ -36,10 +36,10 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_binding_imports_and_matches_header():
     from paper_2509_23202_amd import binding
-    for n in ("fp4_rotate_quantize", "fp4_quantize_weights", "fp4_gemm"):
+    for n in ("fp4_rotate_quantize", "fp4_rotate_quantize_dense", "fp4_quantize_weights", "fp4_gemm"):
         assert callable(getattr(binding, n))
     hdr = HEADER.read_text()
-    for name in ("LAYOUT_GEMM", "INPUT_F32", "STATIC_TENSOR_SCALE", "A_LAYOUT_GEMM", "W_LAYOUT_GEMM", "OUT_F32"):
+    for name in ("LAYOUT_GEMM", "INPUT_F32", "STATIC_TENSOR_SCALE", "A_LAYOUT_GEMM", "W_LAYOUT_GEMM", "OUT_F32", "SCALE_MSE"):
         m = re.search(rf"FP4MR_{name}\s*=\s*1u\s*<<\s*(\d+)", hdr)
         assert m and getattr(binding, name) == 1 << int(m.group(1)), name
 
