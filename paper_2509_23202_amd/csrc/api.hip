@@ -131,7 +131,11 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
     }
     const bool out_f32 = (flags & FP4MR_OUT_F32) != 0;
     const int variant = env_int("FP4MR_GEMM_VARIANT", 0);
-    if (M <= 64 && variant == 0)
+    // Few tokens: the weight-streaming kernel, except MXFP4 with more than one 16-token block and a very wide layer,
+    // where its per-token-block re-reads of the activations from L2 cost more than the 64 x 256 tile kernel does
+    // (M = 64, N = 28672, K = 4096: 29.6 us against 13.7 us).
+    const bool wide_mx = fmt == FP4MR_MXFP4 && M > 16 && N >= 16384;
+    if (M <= 64 && variant == 0 && !wide_mx)
         e = launch_gemm_skinny(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M, N, K, (int)fmt, out, out_f32, st);
     else if (fmt == FP4MR_MXFP4)
         e = launch_gemm_mxfp4(a_codes, a_scales, w_codes, w_scales, M, N, K, out, out_f32, variant, st);

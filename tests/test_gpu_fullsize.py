@@ -92,6 +92,13 @@ def test_decode_layers_mxfp4(fp4, oracle, layer, M):
     check_layer(fp4, oracle, inputs.RECIPES[2], M, L.K, L.N, MX, 32, n_m=M, salt=layer)
 
 
+@pytest.mark.parametrize("M", [17, 64])
+def test_few_tokens_wide_layer_mxfp4(fp4, oracle, M):
+    """More than one 16-token block on the widest layer (gate_up, N = 28672): the 64 x 256 tile kernel's territory."""
+    L = inputs.LLAMA3_8B_LAYERS[2]
+    check_layer(fp4, oracle, inputs.RECIPES[2], M, L.K, L.N, MX, 32, n_m=M, salt=40 + M)
+
+
 def test_config1_whole_output(fp4, oracle):
     """configs[0]: M=64, K=N=4096, every output element."""
     check_layer(fp4, oracle, inputs.RECIPES[1], 64, 4096, 4096, MX, 32, n_m=64, n_n=4096)
