@@ -10,8 +10,15 @@
 // vector ALU is |max|, two multiplies and the hardware FP4 pack per element, which keeps the kernel bound by
 // HBM and not by VALU issue (a butterfly in registers costs about 10 VALU operations per element).
 //
-//   b' = max(b, 32).  b = 16 uses b' = 32 with the block-diagonal matrix diag(H_16, H_16).
+//   b' = operand width.  b = 16 uses b' = 32 with the block-diagonal matrix diag(H_16, H_16); Hadamard blocks of 64
+//   and 128 also use b' = 32 and finish with butterfly levels across lanes (kronecker_levels) wherever the 16 vectors
+//   of an MFMA group are consecutive along K; b' = 64 / 128 operands remain for caller-supplied dense rotations
+//   and for small GEMM-order calls.
 //   lane (g = l%16, q = l/16) of a "supertile" owns outputs [q*b'/4, (q+1)*b'/4) of vector g.
+//
+// Throughput is bound by the bytes in flight per compute unit: kernels keep registers low (many resident waves), ask
+// for all of a wave's input before doing anything else and, for the built-in Hadamard, run one work item per wave /
+// workgroup and leave load balancing to the hardware dispatcher.
 //
 // Normalisation 1/sqrt(b) is applied in fp32 after the contraction as y = fma(h, c_hi, h*c_lo) with
 // c_hi + c_lo = 1/sqrt(b) to ~48 bits, so y is (almost always) the correctly rounded product.
@@ -35,6 +42,7 @@ struct RqArgs {
     float* tensor_scale;   // NVFP4: s_T (written by the quantize pass unless static)
     uint32_t* amax_bits;   // NVFP4 dynamic: bit pattern of max |y| over the tensor (workspace)
     uint32_t* amax_partial;  // NVFP4 dynamic: one partial maximum per wave of the abs-max pass (workspace)
+    int n_partials;          // > 0: the quantize pass reduces that many partials itself (small calls: no finalize launch)
     int64_t rows, K;
     int64_t n_items;
     int b;                 // rotation block (1 = none)
@@ -42,6 +50,24 @@ struct RqArgs {
     float c_hi, c_lo;      // 1/sqrt(b) split in two floats (1 and 0 for a dense rotation)
     int static_scale;
 };
+
+// NVFP4 tensor scale as the quantize pass sees it: caller-supplied, or abs-max / 2688 with the abs-max taken from the
+// finalized word or -- small calls -- reduced here from the abs-max pass's per-wave partials (every wave computes the
+// same maximum: order-independent).  Non-negative floats order like their bit patterns.
+__device__ __forceinline__ float load_tensor_scale(const RqArgs& a, int lane)
+{
+    if (a.static_scale) return *a.tensor_scale;
+    uint32_t m;
+    if (a.n_partials > 0) {
+        m = 0;
+        for (int i = lane; i < a.n_partials; i += 64) m = max(m, a.amax_partial[i]);
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) m = max(m, (uint32_t)__shfl_xor((int)m, d));
+    } else {
+        m = *a.amax_bits;
+    }
+    return __fdiv_rn(__uint_as_float(m), 2688.0f);
+}
 
 template <int LAYOUT>
 __device__ __forceinline__ int64_t codes_offset_gemm(int64_t row, int64_t k, int64_t KC)
@@ -401,7 +427,7 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
 
     float s_T = 0.0f;
     if constexpr (G == 16 && PASS == 0) {
-        s_T = a.static_scale ? *a.tensor_scale : __fdiv_rn(__uint_as_float(*a.amax_bits), 2688.0f);
+        s_T = load_tensor_scale(a, (int)(threadIdx.x & 63));
         if (!a.static_scale && blockIdx.x == 0 && threadIdx.x == 0) *a.tensor_scale = s_T;
     }
     float hmax = 0.0f;
@@ -568,7 +594,7 @@ __global__ __launch_bounds__(kThreads) void rq_frag_kernel(RqArgs a)
 
     float s_T = 0.0f;
     if constexpr (G == 16) {
-        s_T = a.static_scale ? *a.tensor_scale : __fdiv_rn(__uint_as_float(*a.amax_bits), 2688.0f);
+        s_T = load_tensor_scale(a, (int)(threadIdx.x & 63));
         if (!a.static_scale && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) *a.tensor_scale = s_T;
     }
 
@@ -664,7 +690,7 @@ __global__ __launch_bounds__(kThreads) void q_direct_kernel(RqArgs a)
 
     float s_T = 0.0f;
     if constexpr (G == 16 && PASS == 0) {
-        s_T = a.static_scale ? *a.tensor_scale : __fdiv_rn(__uint_as_float(*a.amax_bits), 2688.0f);
+        s_T = load_tensor_scale(a, (int)(threadIdx.x & 63));
         if (!a.static_scale && blockIdx.x == 0 && threadIdx.x == 0) *a.tensor_scale = s_T;
     }
     float hmax = 0.0f;
@@ -876,8 +902,13 @@ hipError_t launch_rotate_quantize(const void* x, int64_t rows, int64_t K, int b,
                      : dispatch_layout_pass<16, false>(a, in_f32, 0, 1, pass_cap, st, &pass_blocks);
         if (e != hipSuccess) return e;
         // blocks that had no item still wrote their (zero) partial: every wave of the grid stores one
-        hipLaunchKernelGGL(amax_finalize_kernel, dim3(1), dim3(1024), 0, st, a.amax_partial, pass_blocks * kWavesPerBlock, a.amax_bits);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+        const int n_partials = pass_blocks * kWavesPerBlock;
+        if (n_partials <= 256) {
+            a.n_partials = n_partials;  // few-token calls: one launch less, the quantize pass reduces the partials itself
+        } else {
+            hipLaunchKernelGGL(amax_finalize_kernel, dim3(1), dim3(1024), 0, st, a.amax_partial, n_partials, a.amax_bits);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+        }
     }
     if (mse) {
         // the scale search is written with the hardware converts only
