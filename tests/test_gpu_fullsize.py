@@ -131,3 +131,29 @@ def test_standalone_rotate_quantize_16384_8192(fp4, oracle):
             gc, gs = np_(c).reshape(M, -1)[mi], np_(s).reshape(M, -1)[mi]
         rc, rs, _, y = oracle_rows(oracle, xb[mi], 32, MX)
         compare_codes(gc, gs, rc, rs, y, MX)
+
+
+@pytest.mark.parametrize("fmt", [MX, NV])
+def test_rotate_quantize_more_than_32768_row_blocks_and_short_k(fp4, oracle, fmt):
+    """540000 tokens x K = 384: the fragment-order kernel's grid needs a second slice of row-blocks (33750 > 32768)
+    and a work item (1024 K-elements) reaches past the end of K; ragged last row-block (540000 = 33750 * 16 exactly,
+    so one more case with 540007 rows)."""
+    import torch
+    rng = np.random.default_rng(9)
+    K = 384
+    for M in (540000, 540007):
+        x = (rng.standard_normal((M, K), dtype=np.float32) * np.exp(rng.uniform(-2, 2, (M, 1))).astype(np.float32))
+        xb = inputs.f32_to_bf16_bits(x)
+        del x
+        say(f"tall tensor fmt={fmt} M={M} K={K}")
+        c, s, T = fp4.fp4_rotate_quantize(to_dev_bf16(xb), 32, fmt, flags=fp4.LAYOUT_GEMM)
+        torch.cuda.synchronize()
+        mi = np.unique(np.concatenate([sample_rows(M, 48, rng), np.array([32768 * 16 - 1, 32768 * 16, 32768 * 16 + 17, M - 2])]))
+        gc, gs = gemm_layout_to_canonical(np_(c), np_(s), mi, K, fmt)
+        Tg = None if fmt == MX else float(np_(T)[0])
+        if fmt == NV:
+            T_ref = np.float32(np.abs(oracle.rotate(xb, 32)).max()) / np.float32(2688.0)
+            assert abs(Tg - float(T_ref)) <= 2 * np.spacing(T_ref)
+        rc, rs, _, y = oracle_rows(oracle, xb[mi], 32, fmt, Tg)
+        compare_codes(gc, gs, rc, rs, y, fmt)
+        del c, s
