@@ -264,6 +264,56 @@ def main():
         result["rotate_quantize_variants"] = dense
         del xs
 
+        # ---- the decode configuration (BASELINE configs[1]: M in {1, 16}, same four layers): weight streaming, so the
+        # figure of merit is time and GB/s of W, not TFLOP/s.  A few-microsecond kernel cannot be timed through
+        # Python-issued launches (the host needs ~8 us per call), so 20 calls are captured into a HIP graph on a side
+        # stream and the graph is replayed; every replayed result is compared with the eager one (the library records
+        # kernels only, no memsets).
+        def graph_us(fn, out_t, n=20, reps=5):
+            st = torch.cuda.Stream()
+            with torch.cuda.stream(st):
+                for _ in range(3):
+                    fn()
+                st.synchronize()
+                eager = out_t.clone()
+                gr = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gr, stream=st):
+                    for _ in range(n):
+                        fn()
+            torch.cuda.synchronize()
+            gr.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out_t, eager), "graph replay differs from the eager result"
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0.record()
+            for _ in range(reps):
+                gr.replay()
+            a1.record()
+            torch.cuda.synchronize()
+            assert torch.equal(out_t, eager), "graph replay differs from the eager result"
+            return a0.elapsed_time(a1) / (reps * n) * 1e3
+
+        decode = {}
+        for Md in (1, 16):
+            per = {}
+            for s_ in state:
+                L = s_["L"]
+                xd = s_["x"][:Md].contiguous()
+                cbd, sbd = fp4.packed_bytes(Md, L.K, fp4.MXFP4, GL)
+                acd = torch.zeros(cbd, dtype=torch.uint8, device="cuda")
+                ascd = torch.zeros(sbd, dtype=torch.uint8, device="cuda")
+                outd = torch.empty((Md, L.N), dtype=torch.bfloat16, device="cuda")
+                outb = torch.empty((Md, L.N), dtype=torch.bfloat16, device="cuda")
+                wt = s_["w"].t()
+                t_rq = graph_us(lambda: fp4.fp4_rotate_quantize(xd, b, fp4.MXFP4, flags=GL, codes=acd, scales=ascd), acd)
+                t_g = graph_us(lambda: fp4.fp4_gemm(acd, ascd, None, s_["wc"], s_["ws"], None, Md, L.N, L.K, fp4.MXFP4, flags=gflags, out=outd), outd)
+                t_b = graph_us(lambda: torch.matmul(xd, wt, out=outb), outb)
+                wbytes = L.N * L.K * (0.5 + 1.0 / 32)
+                per[L.name] = {"rq_us": round(t_rq, 2), "gemm_us": round(t_g, 2), "w_gbs": round(wbytes / t_g / 1e3, 1),
+                               "bf16_gemm_us": round(t_b, 2), "speedup_vs_bf16": round(t_b / (t_rq + t_g), 2)}
+            decode[f"M={Md}"] = per
+        result["decode_configs1"] = decode
+
     if args.copy_calibration:
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").fill_(1.0)
         dst = torch.empty_like(src)
