@@ -21,6 +21,7 @@
 #include "layout.hpp"
 
 #include <algorithm>
+#include <cmath>
 #include <cstdlib>
 #include <type_traits>
 
@@ -446,8 +447,23 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
     if (variant == 0) {
         if (M <= 16) variant = 4;
         else if (M <= 64) variant = 3;
-        else if (M <= 1024 || N < 2048) variant = 2;
-        else variant = 10;
+        else {
+            // Pick the tile by a small cost model: rounds of workgroups over the chip times (fixed cost per tile + K-steps
+            // times the measured step time of that tile).  256x256 and 256x128 hold one workgroup per compute unit,
+            // 128x128 two (and runs faster still when a compute unit has a single one).
+            const int cus = compute_units();
+            const double kt = (double)(K >> 7);
+            auto tiles = [&](int bm, int bn) { return (double)((M + bm - 1) / bm) * (double)((N + bn - 1) / bn); };
+            auto rounds = [](double t, double slots) { return t <= slots ? 1.0 : ceil(t / slots); };
+            const double t10 = rounds(tiles(256, 256), cus) * (9.5 + kt * 0.74);
+            const double t5 = rounds(tiles(256, 128), cus) * (9.0 + kt * 0.37);
+            const double n2 = tiles(128, 128);
+            const double t2 = rounds(n2, 2.0 * cus) * (8.0 + kt * (n2 <= cus ? 0.15 : 0.40));
+            variant = 10;
+            double best = t10;
+            if (t5 < best * 0.97) { variant = 5; best = t5; }
+            if (t2 < best * 0.97) { variant = 2; best = t2; }
+        }
     }
     switch (variant) {
         case 1: return launch_variant<256, 256, 128, 128, 4>(g, out_f32, st);
