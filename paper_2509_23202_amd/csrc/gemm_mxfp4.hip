@@ -211,6 +211,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     //           says that every wave is done reading stage kt-1, whose LDS buffer is refilled with stage kt+STAGES-1.
     //   vmcnt:  allowed in flight = the STAGES-3 stages after kt+1, plus one scale batch when it was issued after
     //           stage kt+1's loads (batches go out at J == 0, ahead of that step's fragment loads).
+    constexpr int NST = TM * (16 * (WN / 8) / 64);  // store instructions a wave issues for one interior output tile
+    static_assert((STAGES - 2) * LPW + NST < 64 && (STAGES - 3) * LPW + NS + NST < 64, "vmcnt is a 6-bit counter");
+    bool pend = false;  // persistent workgroups: the previous tile's stores may be outstanding at the top of this tile
     constexpr int XPG = (TM + TN - 1) / TN;  // X-fragment reads folded in front of each group of TM MFMAs
     // The LDS reads for "the next step" are unconditional: in the very last step they fetch stale bytes of the ring
     // that nothing consumes, which keeps the step body free of branches (and of a second copy of the code).
@@ -220,7 +223,14 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
         constexpr int P = J & 1;
         constexpr bool batch_after = (J >= 1 && J <= STAGES - 3);
         constexpr int ALLOWED = (STAGES - 3) * LPW + (batch_after ? NS : 0);
-        wait_vmcnt<ALLOWED>();
+        if constexpr (PERSIST && J < 2) {
+            // first two steps of a follow-on tile: the previous tile's NST output stores were issued after this tile's
+            // prefetched stages and may still be in flight (vector memory operations complete in issue order, so the
+            // stages in front of them can be waited for without waiting for the stores)
+            if (pend && kt < 2) wait_vmcnt<ALLOWED + NST>(); else wait_vmcnt<ALLOWED>();
+        } else {
+            wait_vmcnt<ALLOWED>();
+        }
         wait_lgkmcnt0();
         block_barrier();
         // The global -> LDS loads of stage kt+STAGES-1 (and, at J == 0, of the next scale batch) are spread over the
@@ -302,8 +312,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
         block_barrier();  // every wave is done with the operand ring, and nothing is in flight into it
 
         const int64_t m0 = (int64_t)tm * BM + wm * WM, n0 = (int64_t)tn * BN + wn * WN;  // this wave's output tile
+        const bool interior = (int64_t)(tm + 1) * BM <= g.M && (int64_t)(tn + 1) * BN <= g.N;  // no lane is masked off
         const int next = tile + (int)gridDim.x;
         const bool more = PERSIST && next < ntiles;
+        pend = false;
         if (more) {
             // the next tile's first stages travel while this tile's results are converted and stored
             set_tile(next);
@@ -338,9 +350,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
                     const int row = c / CPR, ch = c % CPR;
                     const v4i v = *reinterpret_cast<const v4i*>(mine + row * (WN * 2) + ((ch ^ (row & (CPR - 1))) * 16));
                     const int64_t m = m0 + 16 * j + row, n = n0 + ch * 8;
-                    if (m < g.M && n < g.N) __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(static_cast<__bf16*>(g.out) + m * g.N + n));
+                    // an interior tile issues exactly NST stores per wave (what the follow-on tile's vmcnt allowance counts)
+                    if (interior || (m < g.M && n < g.N)) __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(static_cast<__bf16*>(g.out) + m * g.N + n));
                 }
             }
+            pend = more && interior;
         } else {
             // direct stores (fp32 output, or N not a multiple of 8)
             const int64_t m_base = m0 + (el & 15);
@@ -378,10 +392,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
         }
         if (!more) break;
         tile = next;
-        // Loads and stores retire out of order with respect to each other, so a partial vmcnt cannot single out the
-        // prologue loads among the stores issued after them: wait for everything.  By now all STAGES-1 prefetched
-        // stages have landed and the next main loop starts with a full ring.
-        wait_vmcnt<0>();
+        // Stage 0 and the scale batch of the next tile were issued before this tile's stores: after an interior tile
+        // (exact store count) wait for them only and let the stores drain under the first K-steps; otherwise wait for
+        // everything.
+        if (pend) wait_vmcnt<(STAGES - 2) * LPW + NST>(); else wait_vmcnt<0>();
     }
 }
 
@@ -463,6 +477,9 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
             double best = t10;
             if (t5 < best * 0.97) { variant = 5; best = t5; }
             if (t2 < best * 0.97) { variant = 2; best = t2; }
+            // more 256x256 tiles than compute units: persistent workgroups, which prefetch the next tile's first stages
+            // and let the output stores drain under its first K-steps (1.5-6% on such shapes, never slower)
+            if (variant == 10 && tiles(256, 256) > cus) variant = 11;
         }
     }
     switch (variant) {
@@ -477,6 +494,7 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
         case 9: return launch_variant<256, 256, 128, 128, 4, 6>(g, out_f32, st);
         case 10: return launch_variant<256, 256, 64, 128, 4, 3>(g, out_f32, st);
         case 11: return launch_variant<256, 256, 64, 128, 4, 3, true>(g, out_f32, st);
+        case 12: return launch_variant<256, 128, 128, 64, 4, 2, true>(g, out_f32, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -199,7 +199,7 @@ def test_gemm_gemm_layout_operands_bf16_out(fp4, oracle, fmt):
     _gemm_case(fp4, oracle, fmt, 200, 520, 1024 + 384, seed=5, out_f32=False, layout_gemm=True)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12])
 def test_gemm_mxfp4_every_tile_variant(fp4, oracle, variant, monkeypatch):
     monkeypatch.setenv("FP4MR_GEMM_VARIANT", str(variant))
     _gemm_case(fp4, oracle, MX, 272, 528, 1280, seed=variant, out_f32=True, layout_gemm=True)
@@ -213,6 +213,17 @@ def test_gemm_mxfp4_persistent_workgroups_walk_several_tiles(fp4, oracle, grid, 
     monkeypatch.setenv("FP4MR_GEMM_VARIANT", "11")
     monkeypatch.setenv("FP4MR_GEMM_GRID", str(grid))
     _gemm_case(fp4, oracle, MX, 272, 528, 1280, seed=40 + grid, out_f32=out_f32, layout_gemm=True)
+
+
+@pytest.mark.parametrize("variant", [11, 12])
+@pytest.mark.parametrize("K", [128, 256, 384, 1152])
+@pytest.mark.parametrize("grid", [1, 2])
+def test_gemm_mxfp4_persistent_interior_tiles_overlap_their_stores(fp4, oracle, grid, K, variant, monkeypatch):
+    """All tiles interior (M, N multiples of the tile): every follow-on tile starts its main loop while the previous
+    tile's stores are still draining; K = 128 ... 384 are the cases with fewer K-steps than the drain window."""
+    monkeypatch.setenv("FP4MR_GEMM_VARIANT", str(variant))
+    monkeypatch.setenv("FP4MR_GEMM_GRID", str(grid))
+    _gemm_case(fp4, oracle, MX, 512, 768, K, seed=60 + grid + K, out_f32=False, layout_gemm=True)
 
 
 def test_gemm_mxfp4_exact_on_small_integers(fp4, oracle):
