@@ -308,9 +308,15 @@ def main():
                 t_rq = graph_us(lambda: fp4.fp4_rotate_quantize(xd, b, fp4.MXFP4, flags=GL, codes=acd, scales=ascd), acd)
                 t_g = graph_us(lambda: fp4.fp4_gemm(acd, ascd, None, s_["wc"], s_["ws"], None, Md, L.N, L.K, fp4.MXFP4, flags=gflags, out=outd), outd)
                 t_b = graph_us(lambda: torch.matmul(xd, wt, out=outb), outb)
+                # one launch: rotation and quantization inside the GEMM (bit-identical result)
+                outf = torch.empty((Md, L.N), dtype=torch.bfloat16, device="cuda")
+                t_f = graph_us(lambda: fp4.fp4_fused_linear(xd, b, s_["wc"], s_["ws"], L.N, fp4.MXFP4, out=outf), outf)
+                assert torch.equal(outf, outd), "one-launch path differs from the two-launch path"
                 wbytes = L.N * L.K * (0.5 + 1.0 / 32)
                 per[L.name] = {"rq_us": round(t_rq, 2), "gemm_us": round(t_g, 2), "w_gbs": round(wbytes / t_g / 1e3, 1),
-                               "bf16_gemm_us": round(t_b, 2), "speedup_vs_bf16": round(t_b / (t_rq + t_g), 2)}
+                               "fused_us": round(t_f, 2), "fused_w_gbs": round(wbytes / t_f / 1e3, 1),
+                               "bf16_gemm_us": round(t_b, 2), "speedup_vs_bf16": round(t_b / (t_rq + t_g), 2),
+                               "fused_speedup_vs_bf16": round(t_b / t_f, 2)}
             decode[f"M={Md}"] = per
         result["decode_configs1"] = decode
 

@@ -133,6 +133,20 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
                         int64_t M, int64_t N, int64_t K, fp4mr_fmt_t fmt, void* out,
                         void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
 
+/*
+ * Few tokens in one launch: out = Q(X H_b) Q(W H_b)^T with the activations rotated and quantized inside the GEMM
+ * (Section 4.2 items 1 and 2 fused; the paper's appendix on inference regimes: at small batch its separate kernels give
+ * little).  Result bit-identical to fp4_rotate_quantize followed by fp4_gemm for had_block <= 32.
+ *   x            [M,K] bf16 row-major, 1 <= M <= 16, K % 128 == 0
+ *   had_block    b in {16,32,64,128}
+ *   w_codes, w_scales   [N,K] operand in GEMM layout (flags must contain FP4MR_W_LAYOUT_GEMM)
+ *   fmt          FP4MR_MXFP4 only (NVFP4's tensor scale needs a pass over all of X first: FP4MR_ERR_FMT)
+ *   out          [M,N] bf16 (fp32 with FP4MR_OUT_F32)
+ * No workspace.
+ */
+fp4mr_status_t fp4_fused_linear(const void* x, int64_t M, int64_t K, int had_block, const void* w_codes, const void* w_scales,
+                                int64_t N, fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream);
+
 /* Bytes of device scratch the given operation needs (0 = none).  rows = M for the quantize ops. */
 size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t fmt, uint32_t flags);
 

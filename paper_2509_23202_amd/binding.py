@@ -37,6 +37,8 @@ lib.fp4_quantize_weights.argtypes = _quant_sig
 lib.fp4_quantize_weights.restype = _i32
 lib.fp4_rotate_quantize_dense.argtypes = [_p, _i64, _i64, _i32, _p, _i32, _p, _p, _p, _p, _sz, _u32, _p]
 lib.fp4_rotate_quantize_dense.restype = _i32
+lib.fp4_fused_linear.argtypes = [_p, _i64, _i64, _i32, _p, _p, _i64, _i32, _p, _u32, _p]
+lib.fp4_fused_linear.restype = _i32
 lib.fp4_gemm.argtypes = [_p, _p, _p, _p, _p, _p, _i64, _i64, _i64, _i32, _p, _p, _sz, _u32, _p]
 lib.fp4_gemm.restype = _i32
 lib.fp4_workspace_bytes.argtypes = [_i32, _i64, _i64, _i64, _i32, _u32]
@@ -141,6 +143,17 @@ def fp4_gemm(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scal
     wsz = 0 if workspace is None else workspace.numel()
     _check(lib.fp4_gemm(a_codes.data_ptr(), a_scales.data_ptr(), _ptr(a_tensor_scale), w_codes.data_ptr(), w_scales.data_ptr(),
                         _ptr(w_tensor_scale), M, N, K, fmt, out.data_ptr(), _ptr(workspace), wsz, flags, _stream()))
+    return out
+
+
+def fp4_fused_linear(x, had_block: int, w_codes, w_scales, N: int, fmt: int = MXFP4, *, flags: int = 0, out=None):
+    """out[M,N] = Q(X H_b) @ Q(W H_b)^T in one launch for M <= 16 tokens (MXFP4, W in GEMM layout)."""
+    assert x.is_cuda and x.dim() == 2 and x.is_contiguous() and x.dtype == torch.bfloat16
+    M, K = x.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32 if flags & OUT_F32 else torch.bfloat16, device=x.device)
+    _check(lib.fp4_fused_linear(x.data_ptr(), M, K, had_block, w_codes.data_ptr(), w_scales.data_ptr(), N, fmt, out.data_ptr(),
+                                flags | W_LAYOUT_GEMM, _stream()))
     return out
 
 

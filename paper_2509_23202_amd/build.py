@@ -17,7 +17,7 @@ HERE = Path(__file__).resolve().parent
 CSRC = HERE / "csrc"
 BUILD = HERE / "_build"
 LIB = HERE / "libfp4mr.so"
-SOURCES = ["api.hip", "rotate_quantize.hip", "gemm_mxfp4.hip", "gemm_nvfp4.hip", "gemm_skinny.hip", "repack.hip"]
+SOURCES = ["api.hip", "rotate_quantize.hip", "gemm_mxfp4.hip", "gemm_nvfp4.hip", "gemm_skinny.hip", "gemm_fused_decode.hip", "repack.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # Packed-fp32 instruction selection is switched off for all device code (a device-only target feature; the host
@@ -29,7 +29,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 # The rotation kernels consume every MFMA result in the vector ALU right away: letting the MFMAs write ordinary
 # vector registers saves one v_accvgpr_read per value (the GEMM kernels keep their accumulators where the
 # compiler puts them).
-EXTRA_FLAGS = {"rotate_quantize.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+EXTRA_FLAGS = {"rotate_quantize.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+               "gemm_fused_decode.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _compile(src: str) -> Path:
