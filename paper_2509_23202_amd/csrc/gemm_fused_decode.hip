@@ -66,16 +66,6 @@ __global__ __launch_bounds__(kFusedWaves * 64) void gemm_fused_decode_kernel(Fus
     v4f acc = {0.f, 0.f, 0.f, 0.f};
 
     for (int kc0 = k_begin; kc0 < k_end; kc0 += U) {
-        // W fragments and scales of the chunk (the tail repeats the last fragment; its products are skipped below)
-        v4i wf[U];
-        uint32_t swv[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int kc = min(kc0 + u, k_end - 1);
-            wf[u] = __builtin_nontemporal_load(wfrag + (int64_t)kc * 64);
-            const uint32_t d = *(reinterpret_cast<const uint32_t*>(a.w_scales) + ((int64_t)rb * KS + (kc >> 2)) * 64 + lane);
-            swv[u] = d >> (8 * (kc & 3));
-        }
         // activations of the chunk: vector g of the chunk starts at element (kc0 * 4 + g) * 32; it exists if its fragment
         // is inside this wave's share of K
         const bool v_ok = kc0 + (g >> 2) < k_end;
@@ -111,6 +101,18 @@ __global__ __launch_bounds__(kFusedWaves * 64) void gemm_fused_decode_kernel(Fus
                 sc_codes[pos * 4 + q] = out[0];
                 if (q == 0) sc_scales[pos] = sc[0];
             }
+        }
+        // W fragments and scales of the chunk, asked for only now: holding them across the quantization above would cost the
+        // registers that let eight waves per SIMD stay resident, and resident waves are what keeps HBM busy here
+        // (the tail repeats the last fragment; its products are skipped below)
+        v4i wf[U];
+        uint32_t swv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int kc = min(kc0 + u, k_end - 1);
+            wf[u] = __builtin_nontemporal_load(wfrag + (int64_t)kc * 64);
+            const uint32_t d = *(reinterpret_cast<const uint32_t*>(a.w_scales) + ((int64_t)rb * KS + (kc >> 2)) * 64 + lane);
+            swv[u] = d >> (8 * (kc & 3));
         }
         // the chunk's activation fragments in B-operand order (same wave wrote them: LDS operations of a wave are in order)
 #pragma unroll
