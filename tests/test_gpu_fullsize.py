@@ -157,3 +157,9 @@ def test_rotate_quantize_more_than_32768_row_blocks_and_short_k(fp4, oracle, fmt
         rc, rs, _, y = oracle_rows(oracle, xb[mi], 32, fmt, Tg)
         compare_codes(gc, gs, rc, rs, y, fmt)
         del c, s
+
+
+def test_persistent_gemm_with_edge_tiles_at_scale(fp4, oracle):
+    """425 tiles of 256 x 256 on 256 workgroups, the last tile row and column ragged (M = 4113, N = 6152): interior
+    tiles (stores draining under the next tile) and edge tiles (full wait) alternate inside one workgroup."""
+    check_layer(fp4, oracle, inputs.RECIPES[3], 4113, 512, 6152, MX, 32, n_m=48, n_n=64, salt=77)
