@@ -312,9 +312,12 @@ def main():
                 outf = torch.empty((Md, L.N), dtype=torch.bfloat16, device="cuda")
                 t_f = graph_us(lambda: fp4.fp4_fused_linear(xd, b, s_["wc"], s_["ws"], L.N, fp4.MXFP4, out=outf), outf)
                 assert torch.equal(outf, outd), "one-launch path differs from the two-launch path"
+                # weight-only variant: rotated activations stay bf16
+                outw = torch.empty((Md, L.N), dtype=torch.bfloat16, device="cuda")
+                t_w = graph_us(lambda: fp4.fp4_w4a16_linear(xd, b, s_["wc"], s_["ws"], L.N, fp4.MXFP4, out=outw), outw)
                 wbytes = L.N * L.K * (0.5 + 1.0 / 32)
                 per[L.name] = {"rq_us": round(t_rq, 2), "gemm_us": round(t_g, 2), "w_gbs": round(wbytes / t_g / 1e3, 1),
-                               "fused_us": round(t_f, 2), "fused_w_gbs": round(wbytes / t_f / 1e3, 1),
+                               "fused_us": round(t_f, 2), "fused_w_gbs": round(wbytes / t_f / 1e3, 1), "w4a16_us": round(t_w, 2),
                                "bf16_gemm_us": round(t_b, 2), "speedup_vs_bf16": round(t_b / (t_rq + t_g), 2),
                                "fused_speedup_vs_bf16": round(t_b / t_f, 2)}
             decode[f"M={Md}"] = per

@@ -147,6 +147,15 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
 fp4mr_status_t fp4_fused_linear(const void* x, int64_t M, int64_t K, int had_block, const void* w_codes, const void* w_scales,
                                 int64_t N, fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream);
 
+/*
+ * Weight-only variant of the same (W4A16): out = bf16(X H_b) Q(W H_b)^T.  The rotated activations are rounded to bf16
+ * (round-to-nearest-even) instead of quantized; the weights' E2M1 codes are decoded with their E8M0 scales and the
+ * product accumulates in fp32 (appendix on inference regimes: where the layer is memory-bound, weight-only
+ * quantization loses no speed and keeps the activations' accuracy).  Arguments as fp4_fused_linear.
+ */
+fp4mr_status_t fp4_w4a16_linear(const void* x, int64_t M, int64_t K, int had_block, const void* w_codes, const void* w_scales,
+                                int64_t N, fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream);
+
 /* Bytes of device scratch the given operation needs (0 = none).  rows = M for the quantize ops. */
 size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t fmt, uint32_t flags);
 

@@ -201,6 +201,22 @@ def dequantize(codes: np.ndarray, scales: np.ndarray, fmt: int, s_T=None) -> np.
     return out
 
 
+def round_to_bf16(y_f32: np.ndarray) -> np.ndarray:
+    """fp32 -> nearest bf16 (ties to even), returned as fp64 values.  Plain integer arithmetic on the bit patterns."""
+    u = np.ascontiguousarray(y_f32, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    r = ((u + np.uint64(0x7fff) + lsb) >> np.uint64(16)) << np.uint64(16)
+    return r.astype(np.uint32).view(np.float32).astype(np.float64).reshape(np.shape(y_f32))
+
+
+def linear_w4a16(x_bf16_bits: np.ndarray, w_bf16_bits: np.ndarray, b: int, fmt: int = MXFP4):
+    """Weight-only micro-rotated layer (the paper's appendix on inference regimes): Y = bf16(X H_b) . Q(W H_b)^T with
+    the rotated activations rounded to bf16 and only the weights quantized.  Returns (Y, S) like matmul."""
+    ya = round_to_bf16(rotate(x_bf16_bits, b))
+    wc, ws, wT = quantize(rotate(w_bf16_bits, b), fmt)
+    return matmul(ya, dequantize(wc, ws, fmt, wT))
+
+
 def matmul(A: np.ndarray, W: np.ndarray, want_abs: bool = True):
     """Y = A @ W.T and S = |A| @ |W|.T by plain fp64 loops."""
     A = np.ascontiguousarray(A, dtype=np.float64)

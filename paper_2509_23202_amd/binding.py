@@ -39,6 +39,8 @@ lib.fp4_rotate_quantize_dense.argtypes = [_p, _i64, _i64, _i32, _p, _i32, _p, _p
 lib.fp4_rotate_quantize_dense.restype = _i32
 lib.fp4_fused_linear.argtypes = [_p, _i64, _i64, _i32, _p, _p, _i64, _i32, _p, _u32, _p]
 lib.fp4_fused_linear.restype = _i32
+lib.fp4_w4a16_linear.argtypes = lib.fp4_fused_linear.argtypes
+lib.fp4_w4a16_linear.restype = _i32
 lib.fp4_gemm.argtypes = [_p, _p, _p, _p, _p, _p, _i64, _i64, _i64, _i32, _p, _p, _sz, _u32, _p]
 lib.fp4_gemm.restype = _i32
 lib.fp4_workspace_bytes.argtypes = [_i32, _i64, _i64, _i64, _i32, _u32]
@@ -153,6 +155,17 @@ def fp4_fused_linear(x, had_block: int, w_codes, w_scales, N: int, fmt: int = MX
     if out is None:
         out = torch.empty((M, N), dtype=torch.float32 if flags & OUT_F32 else torch.bfloat16, device=x.device)
     _check(lib.fp4_fused_linear(x.data_ptr(), M, K, had_block, w_codes.data_ptr(), w_scales.data_ptr(), N, fmt, out.data_ptr(),
+                                flags | W_LAYOUT_GEMM, _stream()))
+    return out
+
+
+def fp4_w4a16_linear(x, had_block: int, w_codes, w_scales, N: int, fmt: int = MXFP4, *, flags: int = 0, out=None):
+    """out[M,N] = bf16(X H_b) @ Q(W H_b)^T: weight-only variant of fp4_fused_linear (M <= 16, MXFP4, W in GEMM layout)."""
+    assert x.is_cuda and x.dim() == 2 and x.is_contiguous() and x.dtype == torch.bfloat16
+    M, K = x.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32 if flags & OUT_F32 else torch.bfloat16, device=x.device)
+    _check(lib.fp4_w4a16_linear(x.data_ptr(), M, K, had_block, w_codes.data_ptr(), w_scales.data_ptr(), N, fmt, out.data_ptr(),
                                 flags | W_LAYOUT_GEMM, _stream()))
     return out
 

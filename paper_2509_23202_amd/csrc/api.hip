@@ -144,8 +144,9 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
 }
 
-fp4mr_status_t fp4_fused_linear(const void* x, int64_t M, int64_t K, int had_block, const void* w_codes, const void* w_scales,
-                                int64_t N, fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream)
+namespace {
+fp4mr_status_t few_token_linear(const void* x, int64_t M, int64_t K, int had_block, const void* w_codes, const void* w_scales,
+                                int64_t N, fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream, bool weight_only)
 {
     if (fmt != FP4MR_MXFP4) return FP4MR_ERR_FMT;  // NVFP4 needs the tensor abs-max first: not a one-pass operation
     if (flags & ~(uint32_t)(FP4MR_OUT_F32 | FP4MR_W_LAYOUT_GEMM)) return FP4MR_ERR_FMT;
@@ -155,8 +156,21 @@ fp4mr_status_t fp4_fused_linear(const void* x, int64_t M, int64_t K, int had_blo
     if (M <= 0 || M > 16 || N <= 0 || K <= 0 || K % 128 != 0 || N > (1 << 24) || K > (1 << 24)) return FP4MR_ERR_SHAPE;
     if (!aligned16(x) || !aligned16(w_codes) || !aligned16(w_scales) || !aligned16(out)) return FP4MR_ERR_ALIGN;
     const hipError_t e = launch_fused_decode(x, M, K, had_block, w_codes, w_scales, N, out, (flags & FP4MR_OUT_F32) != 0,
-                                             static_cast<hipStream_t>(stream));
+                                             weight_only, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
+}
+}  // namespace
+
+fp4mr_status_t fp4_fused_linear(const void* x, int64_t M, int64_t K, int had_block, const void* w_codes, const void* w_scales,
+                                int64_t N, fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream)
+{
+    return few_token_linear(x, M, K, had_block, w_codes, w_scales, N, fmt, out, flags, stream, false);
+}
+
+fp4mr_status_t fp4_w4a16_linear(const void* x, int64_t M, int64_t K, int had_block, const void* w_codes, const void* w_scales,
+                                int64_t N, fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream)
+{
+    return few_token_linear(x, M, K, had_block, w_codes, w_scales, N, fmt, out, flags, stream, true);
 }
 
 size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t fmt, uint32_t flags)

@@ -146,10 +146,135 @@ __global__ __launch_bounds__(kFusedWaves * 64) void gemm_fused_decode_kernel(Fus
     }
 }
 
+
+// ------------------------------------------------------------------------------------------------------
+// Weight-only variant (W4A16) for a handful of tokens: out = bf16(X H_b) Q(W H_b)^T.  The paper's appendix on
+// inference regimes recommends weight-only quantization where the layer is memory-bound: activation quantization
+// buys no speed there and costs accuracy.  Same streaming of W, same rotation MFMA group per token and chunk; the
+// rotated activations are rounded to bf16 instead of quantized, the E2M1 codes of W are decoded with their E8M0
+// scale straight to bf16 (exact: two significant bits, bf16 has the exponent range of the scale) and the product runs
+// on the bf16 MFMA, four K = 32 instructions per fragment.  The contraction index inside a fragment is permuted the
+// same way for both operands (instruction j takes elements 32*kb + 8*j .. +8 of K-block kb), which a dot product
+// does not see.
+typedef __bf16 v2bf_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ v8bf decode8_bf16(uint32_t codes, float scale)
+{
+    const v2bf_t p0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 0);
+    const v2bf_t p1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 1);
+    const v2bf_t p2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 2);
+    const v2bf_t p3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 3);
+    const v8bf r = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+    return r;
+}
+
+template <bool OUT_F32, int MP>
+__global__ __launch_bounds__(kFusedWaves * 64) void gemm_w4a16_decode_kernel(FusedArgs a)
+{
+    constexpr int U = 4;    // fragments per chunk = 16 vectors of 32
+    constexpr int TOK = 4;  // tokens whose loads are in flight together
+
+    // staging: rotated activations in bf16, entry (vector v of the chunk, token m, part q) = 8 values = 16 bytes
+    __shared__ __attribute__((aligned(16))) uint32_t st_y[kFusedWaves][16 * MP * 16];
+    __shared__ float partial[kFusedWaves][256];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int g = lane & 15, q = lane >> 4;
+    const int rb = blockIdx.x;
+    const int KC = a.K >> 7, KS = (a.K + 511) >> 9;
+    const int per = (KC + kFusedWaves - 1) / kFusedWaves;
+    const int k_begin = min(wave * per, KC), k_end = min(k_begin + per, KC);
+
+    v8bf hop[2][1];
+    build_hadamard_operand<32>(hop, g, q, a.b < 32 ? a.b : 32);
+    const int kron = a.b > 32 ? (a.b == 64 ? 1 : 2) : 0;
+
+    uint32_t* const sy = st_y[wave];
+    for (int i = lane; i < 16 * MP * 16; i += 64) sy[i] = 0u;  // rows that belong to no token stay zero
+
+    const v4i* wfrag = reinterpret_cast<const v4i*>(a.w_codes + (int64_t)rb * KC * 1024) + lane;
+    v4f acc = {0.f, 0.f, 0.f, 0.f};
+
+    for (int kc0 = k_begin; kc0 < k_end; kc0 += U) {
+        const bool v_ok = kc0 + (g >> 2) < k_end;
+        const int64_t k_lane = (int64_t)kc0 * 128 + g * 32 + 8 * q;
+        for (int m0 = 0; m0 < a.M; m0 += TOK) {
+            v4i xin[TOK];
+#pragma unroll
+            for (int t = 0; t < TOK; ++t) {
+                const v4i z = {0, 0, 0, 0};
+                const int m = m0 + t;
+                xin[t] = (m < a.M && v_ok) ? *reinterpret_cast<const v4i*>(a.x + (int64_t)m * a.K + k_lane) : z;
+            }
+#pragma unroll
+            for (int t = 0; t < TOK; ++t) {
+                const int m = m0 + t;
+                if (m >= a.M) break;  // uniform
+                v4f h[2];
+#pragma unroll
+                for (int tt = 0; tt < 2; ++tt) {
+                    h[tt] = v4f{0.f, 0.f, 0.f, 0.f};
+                    h[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hop[tt][0], __builtin_bit_cast(v8bf, xin[t]), h[tt], 0, 0, 0);
+                }
+                kronecker_levels<2>(h, g, kron);
+                v8bf yb;
+#pragma unroll
+                for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) yb[4 * tt + v] = (__bf16)__fmaf_rn(h[tt][v], a.c_hi, h[tt][v] * a.c_lo);
+                // lane (g, q) holds elements 8q .. 8q+7 of vector g, token m
+                *reinterpret_cast<v8bf*>(sy + ((g * MP + m) * 4 + q) * 4) = yb;
+            }
+        }
+        // W fragments and scales of the chunk, asked for only now (registers: see the quantizing kernel above)
+        v4i wf[U];
+        uint32_t swv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int kc = min(kc0 + u, k_end - 1);
+            wf[u] = __builtin_nontemporal_load(wfrag + (int64_t)kc * 64);
+            const uint32_t d = *(reinterpret_cast<const uint32_t*>(a.w_scales) + ((int64_t)rb * KS + (kc >> 2)) * 64 + lane);
+            swv[u] = (d >> (8 * (kc & 3))) & 0xffu;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (kc0 + u < k_end) {
+                const float wscale = __uint_as_float(swv[u] << 23);  // E8M0 byte as the exponent field of a binary32
+                const int row = lane & 15, kb = lane >> 4;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    // lane (row n, kb) of W holds elements 32 kb .. +32 of its row: dword j = elements 32 kb + 8 j .. +8
+                    const v8bf w8 = decode8_bf16((uint32_t)wf[u][j], wscale);
+                    const v8bf z = {(__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f};
+                    // lane (token row, kb) of X: the same elements 32 kb + 8 j .. +8 = part j of vector 4u + kb
+                    const v8bf x8 = row < MP ? *reinterpret_cast<const v8bf*>(sy + (((u * 4 + kb) * MP + row) * 4 + j) * 4) : z;
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w8, x8, acc, 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    *reinterpret_cast<v4f*>(&partial[wave][lane * 4]) = acc;
+    __syncthreads();
+    for (int e = threadIdx.x; e < 256; e += kFusedWaves * 64) {
+        const int l = e >> 2, v = e & 3;
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kFusedWaves; ++w) s += partial[w][e];
+        const int m = l & 15;
+        const int n = rb * 16 + (l >> 4) * 4 + v;
+        if (m < a.M && n < a.N) {
+            if constexpr (OUT_F32) static_cast<float*>(a.out)[(int64_t)m * a.N + n] = s;
+            else static_cast<__bf16*>(a.out)[(int64_t)m * a.N + n] = (__bf16)s;
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_fused_decode(const void* x, int64_t M, int64_t K, int b, const void* w_codes, const void* w_scales,
-                               int64_t N, void* out, bool out_f32, hipStream_t st)
+                               int64_t N, void* out, bool out_f32, bool weight_only, hipStream_t st)
 {
     FusedArgs a{};
     a.x = static_cast<const uint16_t*>(x);
@@ -164,7 +289,15 @@ hipError_t launch_fused_decode(const void* x, int64_t M, int64_t K, int b, const
     a.c_hi = (float)c;
     a.c_lo = (float)(c - (double)a.c_hi);
     const dim3 grid((unsigned)((N + 15) / 16)), block(kFusedWaves * 64);
-    if (M <= 4) {
+    if (weight_only) {
+        if (M <= 4) {
+            if (out_f32) hipLaunchKernelGGL((gemm_w4a16_decode_kernel<true, 4>), grid, block, 0, st, a);
+            else hipLaunchKernelGGL((gemm_w4a16_decode_kernel<false, 4>), grid, block, 0, st, a);
+        } else {
+            if (out_f32) hipLaunchKernelGGL((gemm_w4a16_decode_kernel<true, 16>), grid, block, 0, st, a);
+            else hipLaunchKernelGGL((gemm_w4a16_decode_kernel<false, 16>), grid, block, 0, st, a);
+        }
+    } else if (M <= 4) {
         if (out_f32) hipLaunchKernelGGL((gemm_fused_decode_kernel<true, 4>), grid, block, 0, st, a);
         else hipLaunchKernelGGL((gemm_fused_decode_kernel<false, 4>), grid, block, 0, st, a);
     } else {

@@ -31,8 +31,9 @@ hipError_t launch_gemm_skinny(const void* a_codes, const void* a_scales, const f
                               const void* w_scales, const float* w_ts, int64_t M, int64_t N, int64_t K, int fmt, void* out,
                               bool out_f32, hipStream_t st);
 
-// M <= 16, MXFP4: rotation + quantization of the activations inside the weight-streaming GEMM (W in GEMM layout)
+// M <= 16, MXFP4: rotation + quantization of the activations inside the weight-streaming GEMM (W in GEMM layout);
+// weight_only: the rotated activations stay bf16 (W4A16)
 hipError_t launch_fused_decode(const void* x, int64_t M, int64_t K, int b, const void* w_codes, const void* w_scales,
-                               int64_t N, void* out, bool out_f32, hipStream_t st);
+                               int64_t N, void* out, bool out_f32, bool weight_only, hipStream_t st);
 
 }  // namespace fp4mr

@@ -26,7 +26,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert {"fp4_rotate_quantize", "fp4_rotate_quantize_dense", "fp4_fused_linear", "fp4_quantize_weights", "fp4_gemm", "fp4_workspace_bytes",
+    assert {"fp4_rotate_quantize", "fp4_rotate_quantize_dense", "fp4_fused_linear", "fp4_w4a16_linear", "fp4_quantize_weights", "fp4_gemm", "fp4_workspace_bytes",
             "fp4_packed_bytes", "fp4_status_string", "fp4_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n

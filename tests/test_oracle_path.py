@@ -511,3 +511,37 @@ def test_mse_policy_nvfp4_candidates_by_independent_recipe(oracle):
                 if best is None or err < best:
                     best, best_c = err, code
             assert s[m, g] == best_c
+
+
+# ---------------------------------------------------------------- weight-only (W4A16) reference
+def test_round_to_bf16_against_torch_cast(oracle):
+    import torch
+    rng = np.random.default_rng(71)
+    v = (rng.standard_normal(20000) * np.exp(rng.uniform(-20, 20, 20000))).astype(np.float32)
+    v[:6] = [0.0, -0.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 3.0e38, -1.1754944e-38]   # ties both ways, large, tiny
+    want = torch.from_numpy(v).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(oracle.round_to_bf16(v), want)
+
+
+def test_w4a16_reference_is_the_product_of_its_definition(oracle):
+    """Y = bf16(X H) . Q(W H)^T: with weights already on the grid the weight side is exact, so the reference must equal
+    the library product of the bf16-rounded rotated activations and the weights themselves."""
+    rng = np.random.default_rng(73)
+    b, M, N, K = 32, 3, 5, 256
+    xb = bits(rng.standard_normal((M, K)))
+    # weights whose rotation lands exactly on the grid: W = (grid values * 2^-3) H (H symmetric, H H = b I)
+    grid = np.concatenate([-E2M1_GRID[1:], E2M1_GRID])
+    Wr = rng.choice(grid, size=(N, K)) * 0.125
+    Wr[:, ::32] = 6 * 0.125                                            # every group's abs-max is 6 * 2^-3
+    W = oracle.rotate_f64(Wr, b)                                       # H is an involution up to normalisation: (Wr U) U = Wr
+    wb = bits(W)
+    assert np.allclose(oracle.rotate(wb, b), Wr, atol=0.02)            # bf16 rounding of W perturbs this slightly
+    Y, S = oracle.linear_w4a16(xb, wb, b)
+    ya = oracle.round_to_bf16(oracle.rotate(xb, b))
+    wc, ws, _ = oracle.quantize(oracle.rotate(wb, b), MX)
+    assert np.allclose(Y, ya @ oracle.dequantize(wc, ws, MX).T, rtol=1e-12, atol=1e-12)
+    # and it is closer to the unquantized product than the W4A4 path on the same data (activations keep 8 bits)
+    x = inputs.bf16_bits_to_f32(xb).astype(np.float64)
+    w = inputs.bf16_bits_to_f32(wb).astype(np.float64)
+    Y44, _ = oracle.linear(xb, wb, b, MX)
+    assert np.abs(Y - x @ w.T).mean() < np.abs(Y44 - x @ w.T).mean()
