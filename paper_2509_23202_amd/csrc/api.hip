@@ -71,6 +71,23 @@ fp4mr_status_t quantize_common(const void* x, int64_t rows, int64_t K, int had_b
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
 }
 
+
+// shared by fp4_fused_linear (activations quantized) and fp4_w4a16_linear (activations kept in bf16)
+fp4mr_status_t few_token_linear(const void* x, int64_t M, int64_t K, int had_block, const void* w_codes, const void* w_scales,
+                                int64_t N, fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream, bool weight_only)
+{
+    if (fmt != FP4MR_MXFP4) return FP4MR_ERR_FMT;  // NVFP4 needs the tensor abs-max first: not a one-pass operation
+    if (flags & ~(uint32_t)(FP4MR_OUT_F32 | FP4MR_W_LAYOUT_GEMM)) return FP4MR_ERR_FMT;
+    if (!(flags & FP4MR_W_LAYOUT_GEMM)) return FP4MR_ERR_FMT;
+    if (!x || !w_codes || !w_scales || !out) return FP4MR_ERR_NULL;
+    if (had_block != 16 && had_block != 32 && had_block != 64 && had_block != 128) return FP4MR_ERR_HAD_BLOCK;
+    if (M <= 0 || M > 16 || N <= 0 || K <= 0 || K % 128 != 0 || N > (1 << 24) || K > (1 << 24)) return FP4MR_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(w_codes) || !aligned16(w_scales) || !aligned16(out)) return FP4MR_ERR_ALIGN;
+    const hipError_t e = launch_fused_decode(x, M, K, had_block, w_codes, w_scales, N, out, (flags & FP4MR_OUT_F32) != 0,
+                                             weight_only, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
+}
+
 }  // namespace
 
 extern "C" {
@@ -143,23 +160,6 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
         e = launch_gemm_nvfp4(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M, N, K, out, out_f32, variant, st);
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
 }
-
-namespace {
-fp4mr_status_t few_token_linear(const void* x, int64_t M, int64_t K, int had_block, const void* w_codes, const void* w_scales,
-                                int64_t N, fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream, bool weight_only)
-{
-    if (fmt != FP4MR_MXFP4) return FP4MR_ERR_FMT;  // NVFP4 needs the tensor abs-max first: not a one-pass operation
-    if (flags & ~(uint32_t)(FP4MR_OUT_F32 | FP4MR_W_LAYOUT_GEMM)) return FP4MR_ERR_FMT;
-    if (!(flags & FP4MR_W_LAYOUT_GEMM)) return FP4MR_ERR_FMT;
-    if (!x || !w_codes || !w_scales || !out) return FP4MR_ERR_NULL;
-    if (had_block != 16 && had_block != 32 && had_block != 64 && had_block != 128) return FP4MR_ERR_HAD_BLOCK;
-    if (M <= 0 || M > 16 || N <= 0 || K <= 0 || K % 128 != 0 || N > (1 << 24) || K > (1 << 24)) return FP4MR_ERR_SHAPE;
-    if (!aligned16(x) || !aligned16(w_codes) || !aligned16(w_scales) || !aligned16(out)) return FP4MR_ERR_ALIGN;
-    const hipError_t e = launch_fused_decode(x, M, K, had_block, w_codes, w_scales, N, out, (flags & FP4MR_OUT_F32) != 0,
-                                             weight_only, static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
-}
-}  // namespace
 
 fp4mr_status_t fp4_fused_linear(const void* x, int64_t M, int64_t K, int had_block, const void* w_codes, const void* w_scales,
                                 int64_t N, fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream)
