@@ -192,136 +192,150 @@ def main():
               "pct_of_fp4_peak": round(100.0 * value / PEAK_FP4_TFLOPS, 2), "layers": layers_out, "roofline": roofline}
 
     if not args.no_extras:
-        # ---- bf16 GEMM baseline on the same shapes (library GEMM through torch.matmul), unquantized X and W
-        base_ms = 0.0
-        for s in state:
-            wt = s["w"].t()
-            for _ in range(3):
-                torch.matmul(s["x"], wt)
+        # Each section below is a side measurement: a failure in one is recorded and must not cost the headline line.
+        extras_errors = {}
+        try:
+            # ---- bf16 GEMM baseline on the same shapes (library GEMM through torch.matmul), unquantized X and W
+            base_ms = 0.0
+            for s in state:
+                wt = s["w"].t()
+                for _ in range(3):
+                    torch.matmul(s["x"], wt)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(10):
+                    torch.matmul(s["x"], wt)
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / 10
+                layers_out[s["L"].name]["bf16_gemm_us"] = round(ms * 1e3, 2)
+                layers_out[s["L"].name]["speedup_vs_bf16"] = round(ms / (layers_out[s["L"].name]["rq_us"] * 1e-3 + layers_out[s["L"].name]["gemm_us"] * 1e-3), 3)
+                base_ms += ms
+            result["bf16_gemm_tflops"] = round(flops_step / (base_ms * 1e-3) / 1e12, 1)
+            result["speedup_vs_bf16_gemm"] = round(base_ms / ms_per_step, 3)
+        except Exception as exc:  # noqa: BLE001 - reported in the JSON line
+            extras_errors["bf16_gemm"] = repr(exc)
+
+        try:
+            # ---- standalone rotate+quantize on [16384, 8192] Laplace inputs with outlier channels (HBM roofline).
+            # Three distinct input buffers are cycled so that no call finds its input in the 256 MB last-level cache.
+            r6 = inputs.RECIPES[6]
+            Mr, Kr = 16384, 8192
+            xs = [to_dev_bf16(r6.x(Mr, Kr, salt=j)) for j in range(3)]
+            cb, sb = fp4.packed_bytes(Mr, Kr, fp4.MXFP4, GL)
+            oc = torch.empty(cb, dtype=torch.uint8, device="cuda")
+            osc = torch.empty(sb, dtype=torch.uint8, device="cuda")
+            for j in range(3):
+                fp4.fp4_rotate_quantize(xs[j], 32, fp4.MXFP4, flags=GL, codes=oc, scales=osc)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            n_rq = 30
             e0.record()
-            for _ in range(10):
-                torch.matmul(s["x"], wt)
+            for it in range(n_rq):
+                fp4.fp4_rotate_quantize(xs[it % 3], 32, fp4.MXFP4, flags=GL, codes=oc, scales=osc)
             e1.record()
             torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / 10
-            layers_out[s["L"].name]["bf16_gemm_us"] = round(ms * 1e3, 2)
-            layers_out[s["L"].name]["speedup_vs_bf16"] = round(ms / (layers_out[s["L"].name]["rq_us"] * 1e-3 + layers_out[s["L"].name]["gemm_us"] * 1e-3), 3)
-            base_ms += ms
-        result["bf16_gemm_tflops"] = round(flops_step / (base_ms * 1e-3) / 1e12, 1)
-        result["speedup_vs_bf16_gemm"] = round(base_ms / ms_per_step, 3)
+            ms = e0.elapsed_time(e1) / n_rq
+            gbs = Mr * Kr * RQ_BYTES_PER_ELEM_MX / (ms * 1e-3) / 1e9
+            result["roofline_rotate_quantize"] = {"bound": "hbm", "kernel": "rq_frag_kernel<32, MXFP4> (GEMM layout)",
+                                                  "workload": "X bf16 [16384, 8192], Laplace(0,1), 1% outlier channels x100, block 32",
+                                                  "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
+                                                  "avg_launch_us": round(ms * 1e3, 2), "traffic": RQ_TRAFFIC_BYTES_PER_LAUNCH}
 
-        # ---- standalone rotate+quantize on [16384, 8192] Laplace inputs with outlier channels (HBM roofline).
-        # Three distinct input buffers are cycled so that no call finds its input in the 256 MB last-level cache.
-        r6 = inputs.RECIPES[6]
-        Mr, Kr = 16384, 8192
-        xs = [to_dev_bf16(r6.x(Mr, Kr, salt=j)) for j in range(3)]
-        cb, sb = fp4.packed_bytes(Mr, Kr, fp4.MXFP4, GL)
-        oc = torch.empty(cb, dtype=torch.uint8, device="cuda")
-        osc = torch.empty(sb, dtype=torch.uint8, device="cuda")
-        for j in range(3):
-            fp4.fp4_rotate_quantize(xs[j], 32, fp4.MXFP4, flags=GL, codes=oc, scales=osc)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        n_rq = 30
-        e0.record()
-        for it in range(n_rq):
-            fp4.fp4_rotate_quantize(xs[it % 3], 32, fp4.MXFP4, flags=GL, codes=oc, scales=osc)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / n_rq
-        gbs = Mr * Kr * RQ_BYTES_PER_ELEM_MX / (ms * 1e-3) / 1e9
-        result["roofline_rotate_quantize"] = {"bound": "hbm", "kernel": "rq_frag_kernel<32, MXFP4> (GEMM layout)",
-                                              "workload": "X bf16 [16384, 8192], Laplace(0,1), 1% outlier channels x100, block 32",
-                                              "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
-                                              "avg_launch_us": round(ms * 1e3, 2), "traffic": RQ_TRAFFIC_BYTES_PER_LAUNCH}
+            # ---- the same tensor through a caller-supplied dense rotation (orthonormal DCT-II block rounded to bf16)
+            def time_rq(fn):
+                for j in range(3):
+                    fn(xs[j])
+                torch.cuda.synchronize()
+                a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a0.record()
+                for it in range(n_rq):
+                    fn(xs[it % 3])
+                a1.record()
+                torch.cuda.synchronize()
+                t = a0.elapsed_time(a1) / n_rq
+                return {"avg_launch_us": round(t * 1e3, 2), "achieved_gbs": round(Mr * Kr * RQ_BYTES_PER_ELEM_MX / (t * 1e-3) / 1e9, 1)}
 
-        # ---- the same tensor through a caller-supplied dense rotation (orthonormal DCT-II block rounded to bf16)
-        def time_rq(fn):
-            for j in range(3):
-                fn(xs[j])
-            torch.cuda.synchronize()
-            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a0.record()
-            for it in range(n_rq):
-                fn(xs[it % 3])
-            a1.record()
-            torch.cuda.synchronize()
-            t = a0.elapsed_time(a1) / n_rq
-            return {"avg_launch_us": round(t * 1e3, 2), "achieved_gbs": round(Mr * Kr * RQ_BYTES_PER_ELEM_MX / (t * 1e-3) / 1e9, 1)}
+            dense = {}
+            for bd in (32, 128):
+                n_ = np.arange(bd)[:, None]
+                k_ = np.arange(bd)[None, :]
+                R = np.cos(np.pi * (2 * n_ + 1) * k_ / (2 * bd)) * np.sqrt(2.0 / bd)
+                R[:, 0] = 1.0 / np.sqrt(bd)
+                Rd = to_dev_bf16(inputs.f32_to_bf16_bits(R.astype(np.float32)))
+                dense[f"dct{bd}"] = time_rq(lambda x_: fp4.fp4_rotate_quantize_dense(x_, Rd, fp4.MXFP4, flags=GL, codes=oc, scales=osc))
+                dense[f"hadamard{bd}"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, bd, fp4.MXFP4, flags=GL, codes=oc, scales=osc))
+            dense["hadamard32_mse_scales"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, 32, fp4.MXFP4, flags=GL | fp4.SCALE_MSE, codes=oc, scales=osc))
+            result["rotate_quantize_variants"] = dense
+            del xs
+        except Exception as exc:  # noqa: BLE001 - reported in the JSON line
+            extras_errors["rotate_quantize"] = repr(exc)
 
-        dense = {}
-        for bd in (32, 128):
-            n_ = np.arange(bd)[:, None]
-            k_ = np.arange(bd)[None, :]
-            R = np.cos(np.pi * (2 * n_ + 1) * k_ / (2 * bd)) * np.sqrt(2.0 / bd)
-            R[:, 0] = 1.0 / np.sqrt(bd)
-            Rd = to_dev_bf16(inputs.f32_to_bf16_bits(R.astype(np.float32)))
-            dense[f"dct{bd}"] = time_rq(lambda x_: fp4.fp4_rotate_quantize_dense(x_, Rd, fp4.MXFP4, flags=GL, codes=oc, scales=osc))
-            dense[f"hadamard{bd}"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, bd, fp4.MXFP4, flags=GL, codes=oc, scales=osc))
-        dense["hadamard32_mse_scales"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, 32, fp4.MXFP4, flags=GL | fp4.SCALE_MSE, codes=oc, scales=osc))
-        result["rotate_quantize_variants"] = dense
-        del xs
-
-        # ---- the decode configuration (BASELINE configs[1]: M in {1, 16}, same four layers): weight streaming, so the
-        # figure of merit is time and GB/s of W, not TFLOP/s.  A few-microsecond kernel cannot be timed through
-        # Python-issued launches (the host needs ~8 us per call), so 20 calls are captured into a HIP graph on a side
-        # stream and the graph is replayed; every replayed result is compared with the eager one (the library records
-        # kernels only, no memsets).
-        def graph_us(fn, out_t, n=20, reps=5):
-            st = torch.cuda.Stream()
-            with torch.cuda.stream(st):
-                for _ in range(3):
-                    fn()
-                st.synchronize()
-                eager = out_t.clone()
-                gr = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(gr, stream=st):
-                    for _ in range(n):
+        try:
+            # ---- the decode configuration (BASELINE configs[1]: M in {1, 16}, same four layers): weight streaming, so the
+            # figure of merit is time and GB/s of W, not TFLOP/s.  A few-microsecond kernel cannot be timed through
+            # Python-issued launches (the host needs ~8 us per call), so 20 calls are captured into a HIP graph on a side
+            # stream and the graph is replayed; every replayed result is compared with the eager one (the library records
+            # kernels only, no memsets).
+            def graph_us(fn, out_t, n=20, reps=5):
+                st = torch.cuda.Stream()
+                with torch.cuda.stream(st):
+                    for _ in range(3):
                         fn()
-            torch.cuda.synchronize()
-            gr.replay()
-            torch.cuda.synchronize()
-            assert torch.equal(out_t, eager), "graph replay differs from the eager result"
-            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a0.record()
-            for _ in range(reps):
+                    st.synchronize()
+                    eager = out_t.clone()
+                    gr = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(gr, stream=st):
+                        for _ in range(n):
+                            fn()
+                torch.cuda.synchronize()
                 gr.replay()
-            a1.record()
-            torch.cuda.synchronize()
-            assert torch.equal(out_t, eager), "graph replay differs from the eager result"
-            return a0.elapsed_time(a1) / (reps * n) * 1e3
+                torch.cuda.synchronize()
+                assert torch.equal(out_t, eager), "graph replay differs from the eager result"
+                a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a0.record()
+                for _ in range(reps):
+                    gr.replay()
+                a1.record()
+                torch.cuda.synchronize()
+                assert torch.equal(out_t, eager), "graph replay differs from the eager result"
+                return a0.elapsed_time(a1) / (reps * n) * 1e3
 
-        decode = {}
-        for Md in (1, 16):
-            per = {}
-            for s_ in state:
-                L = s_["L"]
-                xd = s_["x"][:Md].contiguous()
-                cbd, sbd = fp4.packed_bytes(Md, L.K, fp4.MXFP4, GL)
-                acd = torch.zeros(cbd, dtype=torch.uint8, device="cuda")
-                ascd = torch.zeros(sbd, dtype=torch.uint8, device="cuda")
-                outd = torch.empty((Md, L.N), dtype=torch.bfloat16, device="cuda")
-                outb = torch.empty((Md, L.N), dtype=torch.bfloat16, device="cuda")
-                wt = s_["w"].t()
-                t_rq = graph_us(lambda: fp4.fp4_rotate_quantize(xd, b, fp4.MXFP4, flags=GL, codes=acd, scales=ascd), acd)
-                t_g = graph_us(lambda: fp4.fp4_gemm(acd, ascd, None, s_["wc"], s_["ws"], None, Md, L.N, L.K, fp4.MXFP4, flags=gflags, out=outd), outd)
-                t_b = graph_us(lambda: torch.matmul(xd, wt, out=outb), outb)
-                # one launch: rotation and quantization inside the GEMM (bit-identical result)
-                outf = torch.empty((Md, L.N), dtype=torch.bfloat16, device="cuda")
-                t_f = graph_us(lambda: fp4.fp4_fused_linear(xd, b, s_["wc"], s_["ws"], L.N, fp4.MXFP4, out=outf), outf)
-                assert torch.equal(outf, outd), "one-launch path differs from the two-launch path"
-                # weight-only variant: rotated activations stay bf16
-                outw = torch.empty((Md, L.N), dtype=torch.bfloat16, device="cuda")
-                t_w = graph_us(lambda: fp4.fp4_w4a16_linear(xd, b, s_["wc"], s_["ws"], L.N, fp4.MXFP4, out=outw), outw)
-                wbytes = L.N * L.K * (0.5 + 1.0 / 32)
-                per[L.name] = {"rq_us": round(t_rq, 2), "gemm_us": round(t_g, 2), "w_gbs": round(wbytes / t_g / 1e3, 1),
-                               "fused_us": round(t_f, 2), "fused_w_gbs": round(wbytes / t_f / 1e3, 1), "w4a16_us": round(t_w, 2),
-                               "bf16_gemm_us": round(t_b, 2), "speedup_vs_bf16": round(t_b / (t_rq + t_g), 2),
-                               "fused_speedup_vs_bf16": round(t_b / t_f, 2)}
-            decode[f"M={Md}"] = per
-        result["decode_configs1"] = decode
+            decode = {}
+            for Md in (1, 16):
+                per = {}
+                for s_ in state:
+                    L = s_["L"]
+                    xd = s_["x"][:Md].contiguous()
+                    cbd, sbd = fp4.packed_bytes(Md, L.K, fp4.MXFP4, GL)
+                    acd = torch.zeros(cbd, dtype=torch.uint8, device="cuda")
+                    ascd = torch.zeros(sbd, dtype=torch.uint8, device="cuda")
+                    outd = torch.empty((Md, L.N), dtype=torch.bfloat16, device="cuda")
+                    outb = torch.empty((Md, L.N), dtype=torch.bfloat16, device="cuda")
+                    wt = s_["w"].t()
+                    t_rq = graph_us(lambda: fp4.fp4_rotate_quantize(xd, b, fp4.MXFP4, flags=GL, codes=acd, scales=ascd), acd)
+                    t_g = graph_us(lambda: fp4.fp4_gemm(acd, ascd, None, s_["wc"], s_["ws"], None, Md, L.N, L.K, fp4.MXFP4, flags=gflags, out=outd), outd)
+                    t_b = graph_us(lambda: torch.matmul(xd, wt, out=outb), outb)
+                    # one launch: rotation and quantization inside the GEMM (bit-identical result)
+                    outf = torch.empty((Md, L.N), dtype=torch.bfloat16, device="cuda")
+                    t_f = graph_us(lambda: fp4.fp4_fused_linear(xd, b, s_["wc"], s_["ws"], L.N, fp4.MXFP4, out=outf), outf)
+                    assert torch.equal(outf, outd), "one-launch path differs from the two-launch path"
+                    # weight-only variant: rotated activations stay bf16
+                    outw = torch.empty((Md, L.N), dtype=torch.bfloat16, device="cuda")
+                    t_w = graph_us(lambda: fp4.fp4_w4a16_linear(xd, b, s_["wc"], s_["ws"], L.N, fp4.MXFP4, out=outw), outw)
+                    wbytes = L.N * L.K * (0.5 + 1.0 / 32)
+                    per[L.name] = {"rq_us": round(t_rq, 2), "gemm_us": round(t_g, 2), "w_gbs": round(wbytes / t_g / 1e3, 1),
+                                   "fused_us": round(t_f, 2), "fused_w_gbs": round(wbytes / t_f / 1e3, 1), "w4a16_us": round(t_w, 2),
+                                   "bf16_gemm_us": round(t_b, 2), "speedup_vs_bf16": round(t_b / (t_rq + t_g), 2),
+                                   "fused_speedup_vs_bf16": round(t_b / t_f, 2)}
+                decode[f"M={Md}"] = per
+            result["decode_configs1"] = decode
+        except Exception as exc:  # noqa: BLE001 - reported in the JSON line
+            extras_errors["decode"] = repr(exc)
+
+        if extras_errors:
+            result["extras_errors"] = extras_errors
 
     if args.copy_calibration:
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").fill_(1.0)

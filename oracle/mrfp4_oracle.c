@@ -21,7 +21,10 @@
  *                       Section 4.1 "Ingredient 1":  Xhat = s_T * s_G * Q(X / (s_T * s_G)).
  *   orc_quantize_*_mse  the same two formats with the group scale chosen to minimise the squared error
  *                       (Section 4.1 "Ingredient 1" objective; "MSE" method of Section 4.2 item 1).
- *   orc_dequantize      the decoding side of the same two definitions.
+ *   orc_quantize_mxfp4_round43  MXFP4 with the scale rounded in the log domain and re-scaled by 4/3,
+ *                       s = (4/3) * 2^clamp(round(log2 s)) (Appendix "MXFP scale fitting", first equation;
+ *                       Appendix "Scale quantization analysis").
+ *   orc_dequantize      the decoding side of the same definitions.
  *   orc_matmul          Y = Ahat * What^T as a plain triple loop in fp64, plus S = |Ahat| * |What|^T.
  *
  * Parity pins (see tests/test_oracle_*.py): every function here is pinned; nothing is "parity unpinned"
@@ -453,7 +456,53 @@ int orc_quantize_nvfp4_mse(const float *y, int64_t M, int64_t K, const float *s_
     return 0;
 }
 
-/* fmt 0 = MXFP4 (G=32, E8M0), fmt 1 = NVFP4 (G=16, E4M3, times s_T).  out: fp64 [M,K], exact. */
+/* ---------------------------------------------------------------- rounded, 4/3-rescaled E8M0 scale
+ * Appendix "MXFP scale fitting", first equation (and Appendix "Scale quantization analysis"): the scale of a group
+ * is quantized as  (4/3) * 2^clamp(round(log2 s)).  Readings taken here: s is the ideal abs-max scale amax / 6 (the
+ * largest element lands on the largest grid value, Section 3 "Scales"); round is to the nearest integer (log2 s is
+ * never a half-integer for a binary floating-point s); the exponent is clamped to what an E8M0 byte can hold,
+ * [-127, 127] (the equation's -128 has no byte).  The byte stores the exponent only; the constant 4/3 belongs to
+ * the whole tensor and is applied where the tensor is decoded (orc_dequantize's s_T).  Elements are rounded to the
+ * nearest E2M1 value of  v / ((4/3) 2^k) = 0.75 v 2^-k, which is exact in fp64 for an fp32 v.
+ * amax == 0 gives byte 0. */
+uint8_t orc_e8m0_round43_from_amax(double amax)
+{
+    if (!(amax > 0.0)) return 0;
+    const double l = log2(amax / 6.0);
+    int k = (int)floor(l + 0.5);
+    if (k < -127) k = -127;
+    if (k > 127) k = 127;
+    return (uint8_t)(k + 127);
+}
+
+int orc_quantize_mxfp4_round43(const float *y, int64_t M, int64_t K, uint8_t *codes, uint8_t *scales)
+{
+    const int G = 32;
+    if (K % G != 0) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t g = 0; g < K / G; ++g) {
+            const float *v = y + m * K + g * G;
+            double amax = 0.0;
+            for (int i = 0; i < G; ++i) {
+                double a = fabs((double)v[i]);
+                if (a > amax) amax = a;
+            }
+            const uint8_t sb = orc_e8m0_round43_from_amax(amax);
+            scales[m * (K / G) + g] = sb;
+            const double inv = ldexp(0.75, 127 - (int)sb); /* 1 / ((4/3) 2^k) */
+            for (int i = 0; i < G; i += 2) {
+                uint8_t lo = orc_e2m1_encode((double)v[i] * inv);
+                uint8_t hi = orc_e2m1_encode((double)v[i + 1] * inv);
+                codes[(m * K + g * G + i) / 2] = (uint8_t)(lo | (hi << 4));
+            }
+        }
+    }
+    return 0;
+}
+
+/* fmt 0 = MXFP4 (G=32, E8M0), fmt 1 = NVFP4 (G=16, E4M3); both times the tensor-level factor s_T (1 for plain
+ * MXFP4, 4/3 for the re-scaled E8M0 rule, the tensor scale for NVFP4).  out: fp64 [M,K]. */
 int orc_dequantize(const uint8_t *codes, const uint8_t *scales, double s_T, int fmt, int64_t M,
                    int64_t K, double *out)
 {
@@ -466,7 +515,7 @@ int orc_dequantize(const uint8_t *codes, const uint8_t *scales, double s_T, int 
             uint8_t byte = codes[(m * K + k) / 2];
             uint8_t code = (k & 1) ? (uint8_t)(byte >> 4) : (uint8_t)(byte & 15);
             uint8_t sb = scales[m * (K / G) + k / G];
-            double s = (fmt == 0) ? orc_e8m0_decode(sb) : orc_e4m3_decode(sb) * s_T;
+            double s = ((fmt == 0) ? orc_e8m0_decode(sb) : orc_e4m3_decode(sb)) * s_T;
             out[m * K + k] = orc_e2m1_decode(code) * s;
         }
     return 0;

@@ -72,6 +72,10 @@ def _load():
         L.orc_quantize_mxfp4_mse.restype = i32
         L.orc_quantize_nvfp4_mse.argtypes = [p, i64, i64, p, p, p, p]
         L.orc_quantize_nvfp4_mse.restype = i32
+        L.orc_quantize_mxfp4_round43.argtypes = [p, i64, i64, p, p]
+        L.orc_quantize_mxfp4_round43.restype = i32
+        L.orc_e8m0_round43_from_amax.argtypes = [ctypes.c_double]
+        L.orc_e8m0_round43_from_amax.restype = ctypes.c_uint8
         L.orc_dequantize.argtypes = [p, p, dbl, i32, i64, i64, p]
         L.orc_dequantize.restype = i32
         L.orc_matmul.argtypes = [p, p, i64, i64, i64, p, p]
@@ -107,6 +111,10 @@ def e8m0_decode(byte: int) -> float:
 
 def e8m0_from_amax(amax: float) -> int:
     return int(_load().orc_e8m0_from_amax(float(amax)))
+
+
+def e8m0_round43_from_amax(amax: float) -> int:
+    return int(_load().orc_e8m0_round43_from_amax(float(amax)))
 
 
 def e4m3_decode(byte: int) -> float:
@@ -160,9 +168,10 @@ def rotate_f64(x: np.ndarray, b: int) -> np.ndarray:
 
 def quantize(y_f32: np.ndarray, fmt: int, tensor_scale: float | None = None, policy: str = "absmax"):
     """fp32 [M,K] -> (codes u8 [M,K/2], scales u8 [M,K/G], s_T float32 scalar or None).
-    policy: "absmax" (abs-max group scales) or "mse" (group scale code chosen among the abs-max code and its two
-    neighbours to minimise the group's squared error)."""
-    if policy not in ("absmax", "mse"):
+    policy: "absmax" (abs-max group scales), "mse" (group scale code chosen among the abs-max code and its two
+    neighbours to minimise the group's squared error) or, MXFP4 only, "round43" (exponent round(log2(amax/6)), scale
+    (4/3) 2^k; the returned s_T is then the tensor-level factor 4/3 in binary32)."""
+    if policy not in ("absmax", "mse", "round43") or (policy == "round43" and fmt != MXFP4):
         raise ValueError(policy)
     y = np.ascontiguousarray(y_f32, dtype=np.float32)
     M, K = y.shape
@@ -172,9 +181,10 @@ def quantize(y_f32: np.ndarray, fmt: int, tensor_scale: float | None = None, pol
     codes = np.empty((M, K // 2), dtype=np.uint8)
     scales = np.empty((M, K // G), dtype=np.uint8)
     if fmt == MXFP4:
-        fn = _load().orc_quantize_mxfp4 if policy == "absmax" else _load().orc_quantize_mxfp4_mse
+        fn = {"absmax": _load().orc_quantize_mxfp4, "mse": _load().orc_quantize_mxfp4_mse,
+              "round43": _load().orc_quantize_mxfp4_round43}[policy]
         rc = fn(_ptr(y), M, K, _ptr(codes), _ptr(scales))
-        s_T = None
+        s_T = np.float32(4.0 / 3.0) if policy == "round43" else None
     else:
         s_out = np.zeros(1, dtype=np.float32)
         s_in = None

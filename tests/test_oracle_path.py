@@ -545,3 +545,97 @@ def test_w4a16_reference_is_the_product_of_its_definition(oracle):
     w = inputs.bf16_bits_to_f32(wb).astype(np.float64)
     Y44, _ = oracle.linear(xb, wb, b, MX)
     assert np.abs(Y - x @ w.T).mean() < np.abs(Y44 - x @ w.T).mean()
+
+
+# ---------------------------------------------------------------- rounded, 4/3-rescaled E8M0 scale (appendix on MXFP
+# scale fitting, first equation): exponent k = round(log2(amax / 6)), scale (4/3) 2^k
+
+def _round43_exponent_exact(amax_f32):
+    """k = round(log2(amax/6)) decided in exact integer arithmetic: 2^(2k-1) <= (amax/6)^2 < 2^(2k+1)."""
+    from fractions import Fraction
+    q = Fraction(float(amax_f32)) ** 2 / 36
+    k = 0
+    while q >= Fraction(2) ** (2 * k + 1):
+        k += 1
+    while q < Fraction(2) ** (2 * k - 1):
+        k -= 1
+    return k
+
+
+def test_round43_exponent_rule_against_exact_arithmetic(oracle):
+    rng = np.random.default_rng(7)
+    vals = list(np.exp(rng.uniform(-20, 20, 300)).astype(np.float32))
+    # the binary32 neighbours of every decision boundary 6 * 2^(k + 1/2)
+    for k in range(-12, 13):
+        t = np.float32(6.0 * 2.0 ** (k + 0.5))
+        vals += [np.nextafter(t, np.float32(0)), t, np.nextafter(t, np.float32(np.inf))]
+    # and of the powers of two in between
+    vals += [np.float32(6.0 * 2.0 ** k) for k in range(-5, 6)]
+    for a in vals:
+        assert oracle.e8m0_round43_from_amax(float(a)) == _round43_exponent_exact(a) + 127, float(a)
+    assert oracle.e8m0_round43_from_amax(0.0) == 0
+    assert oracle.e8m0_round43_from_amax(1e-45) == 0          # clamped at the smallest exponent a byte holds
+    assert oracle.e8m0_round43_from_amax(3.0e38) == 125 + 127  # log2(3e38 / 6) = 125.2
+
+
+def test_round43_worked_example(oracle):
+    """amax = 8: s = 8/6, log2 s = 0.415 -> k = 0, scale 4/3; v / (4/3) = 6, 4.5, 3, 1.5, 0.75, 0.375 land on
+    6, 4 (4.5 is nearer to 4 than to 6), 3, 1.5, 1.0 (0.75 ties between 0.5 and 1.0: even code) and 0.5 (0.375 is
+    nearer to 0.5 than to 0)."""
+    y = np.zeros((1, 32), dtype=np.float32)
+    y[0, :7] = [8.0, 6.0, 4.0, 2.0, 1.0, 0.5, -8.0]
+    c, s, t = oracle.quantize(y, MX, policy="round43")
+    assert s[0, 0] == 127 and t == np.float32(4.0 / 3.0)
+    got = decode_codes(unpack(c))[0, :7]
+    assert np.array_equal(got, [6.0, 4.0, 3.0, 1.5, 1.0, 0.5, -6.0])
+    # amax = 6 * 2^j exactly: s = 2^j, the byte is j + 127 and the top element decodes to 4.5 -> 4 (times 4/3 2^j)
+    for j in (-3, 0, 5):
+        y = np.zeros((1, 32), dtype=np.float32)
+        y[0, 3] = 6.0 * 2.0 ** j
+        c, s, _ = oracle.quantize(y, MX, policy="round43")
+        assert s[0, 0] == j + 127 and decode_codes(unpack(c))[0, 3] == 4.0
+
+
+def test_round43_codes_are_the_nearest_points_of_the_rescaled_grid(oracle):
+    """Brute force in rational arithmetic, independent of how the oracle forms v / scale: every element's code is the
+    grid point c that minimises |v - c (4/3) 2^k| (ties cannot occur except where 0.75 v 2^-k is a grid midpoint,
+    which the even-code rule decides), and the dequantized tensor is codes * 2^k * s_T."""
+    from fractions import Fraction
+    rng = np.random.default_rng(8)
+    y = (rng.standard_normal((4, 64)) * np.exp(rng.uniform(-2, 2, (4, 64)))).astype(np.float32)
+    c, s, t = oracle.quantize(y, MX, policy="round43")
+    codes = unpack(c)
+    grid = [Fraction(x) for x in (0, 0.5, 1, 1.5, 2, 3, 4, 6)]
+    for m in range(4):
+        for g in range(2):
+            k = int(s[m, g]) - 127
+            assert k == _round43_exponent_exact(np.abs(y[m, g * 32:(g + 1) * 32]).max())
+            scale = Fraction(4, 3) * Fraction(2) ** k
+            for i in range(32):
+                v = Fraction(float(y[m, g * 32 + i]))
+                d = [abs(abs(v) - q * scale) for q in grid]
+                best = min(d)
+                winners = [j for j in range(8) if d[j] == best]
+                code = int(codes[m, g * 32 + i])
+                assert (code & 7) in winners
+                if len(winners) > 1:
+                    assert (code & 1) == 0
+                assert bool(code & 8) == (y[m, g * 32 + i] < 0)
+    deq = oracle.dequantize(c, s, MX, t)
+    want = decode_codes(codes) * np.repeat(2.0 ** (s.astype(np.float64) - 127), 32, axis=1) * float(t)
+    assert np.array_equal(deq, want)
+
+
+def test_round43_scale_stays_within_the_rounding_band(oracle):
+    """By construction amax / ((4/3) 2^k) lies in [6 * 0.75 / sqrt 2, 6 * 0.75 * sqrt 2) = [3.18, 6.36): the top
+    element never falls below grid value 3 and overshoots 6 by at most 6%."""
+    rng = np.random.default_rng(9)
+    y = (rng.laplace(size=(32, 512)) * np.exp(rng.uniform(-4, 4, (32, 1)))).astype(np.float32)
+    c, s, t = oracle.quantize(y, MX, policy="round43")
+    amax = np.abs(y.astype(np.float64)).reshape(32, 16, 32).max(axis=2)
+    ratio = amax / (4.0 / 3.0 * 2.0 ** (s.astype(np.float64) - 127))
+    assert ratio.min() >= 4.5 / np.sqrt(2) * (1 - 1e-12) and ratio.max() < 4.5 * np.sqrt(2)
+    top = np.abs(decode_codes(unpack(c))).reshape(32, 16, 32).max(axis=2)
+    assert set(np.unique(top)) <= {3.0, 4.0, 6.0}
+    with pytest.raises(ValueError):
+        oracle.quantize(y, NV, policy="round43")
