@@ -267,6 +267,7 @@ def main():
                 dense[f"dct{bd}"] = time_rq(lambda x_: fp4.fp4_rotate_quantize_dense(x_, Rd, fp4.MXFP4, flags=GL, codes=oc, scales=osc))
                 dense[f"hadamard{bd}"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, bd, fp4.MXFP4, flags=GL, codes=oc, scales=osc))
             dense["hadamard32_mse_scales"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, 32, fp4.MXFP4, flags=GL | fp4.SCALE_MSE, codes=oc, scales=osc))
+            dense["hadamard32_round43_scales"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, 32, fp4.MXFP4, flags=GL | fp4.SCALE_ROUND43, codes=oc, scales=osc))
             result["rotate_quantize_variants"] = dense
             del xs
         except Exception as exc:  # noqa: BLE001 - reported in the JSON line

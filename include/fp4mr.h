@@ -65,7 +65,10 @@ enum {
     FP4MR_A_LAYOUT_GEMM = 1u << 3,        /* fp4_gemm: A codes/scales are in GEMM layout (else canonical)     */
     FP4MR_W_LAYOUT_GEMM = 1u << 4,        /* fp4_gemm: W codes/scales are in GEMM layout (else canonical)     */
     FP4MR_OUT_F32 = 1u << 5,              /* fp4_gemm: write the fp32 accumulator instead of bf16             */
-    FP4MR_SCALE_MSE = 1u << 6             /* quantize ops: group scale by squared-error search (below)        */
+    FP4MR_SCALE_MSE = 1u << 6,            /* quantize ops: group scale by squared-error search (below)        */
+    FP4MR_SCALE_ROUND43 = 1u << 7,        /* MXFP4 quantize ops: rounded exponent, scale (4/3) 2^k (below)    */
+    FP4MR_A_SCALE43 = 1u << 8,            /* MXFP4 products: the A operand was quantized with SCALE_ROUND43   */
+    FP4MR_W_SCALE43 = 1u << 9             /* MXFP4 products: the W operand was quantized with SCALE_ROUND43   */
 };
 
 /* operation selector for fp4_workspace_bytes */
@@ -95,6 +98,12 @@ fp4mr_status_t fp4_rotate_quantize(const void* x, int64_t M, int64_t K, int had_
  * that order (abs-max, one above, one below), a candidate winning only with a strictly smaller error; the error is
  * evaluated in fp32.  MXFP4: E8M0 byte +-1; NVFP4: E4M3 code +-1 with the abs-max tensor scale.  Hardware codec
  * only.  Costs about twice the vector-ALU work of abs-max.
+ *
+ * With FP4MR_SCALE_ROUND43 (MXFP4 only; not together with FP4MR_SCALE_MSE: FP4MR_ERR_FMT) the scale follows the
+ * first equation of the appendix on MXFP scale fitting: s = (4/3) 2^k with k = clamp(round(log2(amax / 6)), -127, 127).
+ * The scale byte stores k + 127; elements are E2M1(x / s), correctly rounded.  The factor 4/3 is not representable in
+ * E8M0: it is a constant of the whole tensor, and the products take it as a flag -- FP4MR_A_SCALE43 / FP4MR_W_SCALE43
+ * multiply the result by 4/3 for each operand so quantized (in fp32, before the output is rounded).
  */
 
 /*
@@ -127,6 +136,7 @@ fp4mr_status_t fp4_quantize_weights(const void* w, int64_t N, int64_t K, int had
  *   a_codes/a_scales  [M,K] operand, w_codes/w_scales [N,K] operand, layouts per flags
  *   a_tensor_scale, w_tensor_scale   NVFP4: device floats s_T of each operand; MXFP4: NULL
  *   out          [M,N] row-major
+ *   flags        layouts, FP4MR_OUT_F32, and for MXFP4 FP4MR_A_SCALE43 / FP4MR_W_SCALE43 (FP4MR_ERR_FMT with NVFP4)
  */
 fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* a_tensor_scale,
                         const void* w_codes, const void* w_scales, const float* w_tensor_scale,
@@ -142,6 +152,8 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
  *   w_codes, w_scales   [N,K] operand in GEMM layout (flags must contain FP4MR_W_LAYOUT_GEMM)
  *   fmt          FP4MR_MXFP4 only (NVFP4's tensor scale needs a pass over all of X first: FP4MR_ERR_FMT)
  *   out          [M,N] bf16 (fp32 with FP4MR_OUT_F32)
+ *   flags        FP4MR_W_LAYOUT_GEMM (required), FP4MR_OUT_F32, FP4MR_W_SCALE43 (weights quantized with
+ *                FP4MR_SCALE_ROUND43; the activations are always quantized with the abs-max rule here)
  * No workspace.
  */
 fp4mr_status_t fp4_fused_linear(const void* x, int64_t M, int64_t K, int had_block, const void* w_codes, const void* w_scales,

@@ -27,6 +27,9 @@ A_LAYOUT_GEMM = 1 << 3
 W_LAYOUT_GEMM = 1 << 4
 OUT_F32 = 1 << 5
 SCALE_MSE = 1 << 6
+SCALE_ROUND43 = 1 << 7
+A_SCALE43 = 1 << 8
+W_SCALE43 = 1 << 9
 OP_ROTATE_QUANTIZE, OP_QUANTIZE_WEIGHTS, OP_GEMM = 0, 1, 2
 
 _p, _i64, _i32, _u32, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32, ctypes.c_size_t

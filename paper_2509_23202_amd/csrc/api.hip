@@ -12,8 +12,17 @@ using namespace fp4mr;
 
 namespace {
 
-constexpr uint32_t kQuantFlags = FP4MR_LAYOUT_GEMM | FP4MR_INPUT_F32 | FP4MR_STATIC_TENSOR_SCALE | FP4MR_SCALE_MSE;
-constexpr uint32_t kGemmFlags = FP4MR_A_LAYOUT_GEMM | FP4MR_W_LAYOUT_GEMM | FP4MR_OUT_F32;
+constexpr uint32_t kQuantFlags = FP4MR_LAYOUT_GEMM | FP4MR_INPUT_F32 | FP4MR_STATIC_TENSOR_SCALE | FP4MR_SCALE_MSE | FP4MR_SCALE_ROUND43;
+constexpr uint32_t kGemmFlags = FP4MR_A_LAYOUT_GEMM | FP4MR_W_LAYOUT_GEMM | FP4MR_OUT_F32 | FP4MR_A_SCALE43 | FP4MR_W_SCALE43;
+
+// result factor for operands whose scales carry the tensor-level 4/3 (FP4MR_SCALE_ROUND43)
+float scale43_factor(uint32_t flags)
+{
+    float f = 1.0f;
+    if (flags & FP4MR_A_SCALE43) f *= 4.0f / 3.0f;
+    if (flags & FP4MR_W_SCALE43) f *= 4.0f / 3.0f;
+    return f;
+}
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
@@ -49,6 +58,7 @@ fp4mr_status_t quantize_common(const void* x, int64_t rows, int64_t K, int had_b
 {
     if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return FP4MR_ERR_FMT;
     if (flags & ~kQuantFlags) return FP4MR_ERR_FMT;
+    if ((flags & FP4MR_SCALE_ROUND43) && (fmt != FP4MR_MXFP4 || (flags & FP4MR_SCALE_MSE))) return FP4MR_ERR_FMT;
     if (!x || !codes || !scales) return FP4MR_ERR_NULL;
     if (fmt == FP4MR_NVFP4 && !tensor_scale) return FP4MR_ERR_NULL;
     if (had_block != 1 && had_block != 16 && had_block != 32 && had_block != 64 && had_block != 128) return FP4MR_ERR_HAD_BLOCK;
@@ -66,7 +76,8 @@ fp4mr_status_t quantize_common(const void* x, int64_t rows, int64_t K, int had_b
 
     const hipError_t e = launch_rotate_quantize(x, rows, K, had_block, rot, (int)fmt, (flags & FP4MR_INPUT_F32) != 0,
                                                 (flags & FP4MR_LAYOUT_GEMM) ? 1 : 0, (flags & FP4MR_STATIC_TENSOR_SCALE) != 0,
-                                                (flags & FP4MR_SCALE_MSE) != 0, codes, scales, tensor_scale, workspace, !env_flag("FP4MR_SW_CODEC"),
+                                                (flags & FP4MR_SCALE_MSE) ? 1 : ((flags & FP4MR_SCALE_ROUND43) ? 2 : 0), codes, scales, tensor_scale,
+                                                workspace, !env_flag("FP4MR_SW_CODEC"),
                                                 static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
 }
@@ -77,14 +88,14 @@ fp4mr_status_t few_token_linear(const void* x, int64_t M, int64_t K, int had_blo
                                 int64_t N, fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream, bool weight_only)
 {
     if (fmt != FP4MR_MXFP4) return FP4MR_ERR_FMT;  // NVFP4 needs the tensor abs-max first: not a one-pass operation
-    if (flags & ~(uint32_t)(FP4MR_OUT_F32 | FP4MR_W_LAYOUT_GEMM)) return FP4MR_ERR_FMT;
+    if (flags & ~(uint32_t)(FP4MR_OUT_F32 | FP4MR_W_LAYOUT_GEMM | FP4MR_W_SCALE43)) return FP4MR_ERR_FMT;
     if (!(flags & FP4MR_W_LAYOUT_GEMM)) return FP4MR_ERR_FMT;
     if (!x || !w_codes || !w_scales || !out) return FP4MR_ERR_NULL;
     if (had_block != 16 && had_block != 32 && had_block != 64 && had_block != 128) return FP4MR_ERR_HAD_BLOCK;
     if (M <= 0 || M > 16 || N <= 0 || K <= 0 || K % 128 != 0 || N > (1 << 24) || K > (1 << 24)) return FP4MR_ERR_SHAPE;
     if (!aligned16(x) || !aligned16(w_codes) || !aligned16(w_scales) || !aligned16(out)) return FP4MR_ERR_ALIGN;
     const hipError_t e = launch_fused_decode(x, M, K, had_block, w_codes, w_scales, N, out, (flags & FP4MR_OUT_F32) != 0,
-                                             weight_only, static_cast<hipStream_t>(stream));
+                                             weight_only, scale43_factor(flags), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
 }
 
@@ -122,6 +133,7 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
     if (flags & ~kGemmFlags) return FP4MR_ERR_FMT;
     if (!a_codes || !a_scales || !w_codes || !w_scales || !out) return FP4MR_ERR_NULL;
     if (fmt == FP4MR_NVFP4 && (!a_tensor_scale || !w_tensor_scale)) return FP4MR_ERR_NULL;
+    if (fmt == FP4MR_NVFP4 && (flags & (FP4MR_A_SCALE43 | FP4MR_W_SCALE43))) return FP4MR_ERR_FMT;
     if (M <= 0 || N <= 0 || K <= 0 || K % 128 != 0) return FP4MR_ERR_SHAPE;
     if (M > (1 << 24) || N > (1 << 24) || K > (1 << 24)) return FP4MR_ERR_SHAPE;
     if (!aligned16(a_codes) || !aligned16(a_scales) || !aligned16(w_codes) || !aligned16(w_scales) || !aligned16(out)) return FP4MR_ERR_ALIGN;
@@ -147,15 +159,16 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
         w_scales = s;
     }
     const bool out_f32 = (flags & FP4MR_OUT_F32) != 0;
+    const float alpha = scale43_factor(flags);
     const int variant = env_int("FP4MR_GEMM_VARIANT", 0);
     // Few tokens: the weight-streaming kernel, except MXFP4 with more than one 16-token block and a very wide layer,
     // where its per-token-block re-reads of the activations from L2 cost more than the 64 x 256 tile kernel does
     // (M = 64, N = 28672, K = 4096: 29.6 us against 13.7 us).
     const bool wide_mx = fmt == FP4MR_MXFP4 && M > 16 && N >= 16384;
     if (M <= 64 && variant == 0 && !wide_mx)
-        e = launch_gemm_skinny(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M, N, K, (int)fmt, out, out_f32, st);
+        e = launch_gemm_skinny(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M, N, K, (int)fmt, out, out_f32, alpha, st);
     else if (fmt == FP4MR_MXFP4)
-        e = launch_gemm_mxfp4(a_codes, a_scales, w_codes, w_scales, M, N, K, out, out_f32, variant, st);
+        e = launch_gemm_mxfp4(a_codes, a_scales, w_codes, w_scales, M, N, K, out, out_f32, variant, alpha, st);
     else
         e = launch_gemm_nvfp4(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M, N, K, out, out_f32, variant, st);
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;

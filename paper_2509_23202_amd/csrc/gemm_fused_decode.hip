@@ -28,6 +28,7 @@ struct FusedArgs {
     void* out;
     int M, N, K, b;
     float c_hi, c_lo;        // 1/sqrt(b) split in two floats
+    float alpha;             // factor on the result (4/3 when the weights' scales carry the tensor-level 4/3), else 1
 };
 
 // MP = token rows kept in the staging area (4 or 16): rows of the activation fragments beyond MP are zero by construction
@@ -137,6 +138,7 @@ __global__ __launch_bounds__(kFusedWaves * 64) void gemm_fused_decode_kernel(Fus
         float s = 0.0f;
 #pragma unroll
         for (int w = 0; w < kFusedWaves; ++w) s += partial[w][e];
+        s *= a.alpha;
         const int m = l & 15;
         const int n = rb * 16 + (l >> 4) * 4 + v;
         if (m < a.M && n < a.N) {
@@ -262,6 +264,7 @@ __global__ __launch_bounds__(kFusedWaves * 64) void gemm_w4a16_decode_kernel(Fus
         float s = 0.0f;
 #pragma unroll
         for (int w = 0; w < kFusedWaves; ++w) s += partial[w][e];
+        s *= a.alpha;
         const int m = l & 15;
         const int n = rb * 16 + (l >> 4) * 4 + v;
         if (m < a.M && n < a.N) {
@@ -274,7 +277,7 @@ __global__ __launch_bounds__(kFusedWaves * 64) void gemm_w4a16_decode_kernel(Fus
 }  // namespace
 
 hipError_t launch_fused_decode(const void* x, int64_t M, int64_t K, int b, const void* w_codes, const void* w_scales,
-                               int64_t N, void* out, bool out_f32, bool weight_only, hipStream_t st)
+                               int64_t N, void* out, bool out_f32, bool weight_only, float alpha, hipStream_t st)
 {
     FusedArgs a{};
     a.x = static_cast<const uint16_t*>(x);
@@ -288,6 +291,7 @@ hipError_t launch_fused_decode(const void* x, int64_t M, int64_t K, int b, const
     const double c = 1.0 / sqrt((double)b);
     a.c_hi = (float)c;
     a.c_lo = (float)(c - (double)a.c_hi);
+    a.alpha = alpha;
     const dim3 grid((unsigned)((N + 15) / 16)), block(kFusedWaves * 64);
     if (weight_only) {
         if (M <= 4) {

@@ -36,6 +36,7 @@ struct GemmArgs {
     void* out;
     int64_t M, N, K;
     int tiles_m, tiles_n;
+    float alpha;  // factor on the result: powers of 4/3 for operands whose scales carry the tensor-level 4/3, else 1
 };
 
 template <int N>
@@ -331,6 +332,12 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
         // cannot hoist it above the tile loop and carry it (in registers the main loop needs) through every K-step
         int el = lane;
         asm volatile("" : "+v"(el));
+        if (g.alpha != 1.0f) {
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int j = 0; j < TM; ++j) acc[i][j] *= g.alpha;
+        }
         if (STAGED && (g.N & 7) == 0) {
             char* const mine = smem + (STAGES - 1) * STAGE_BYTES + wave * STAGING;
             typedef __bf16 v4bf __attribute__((ext_vector_type(4)));
@@ -447,9 +454,10 @@ hipError_t launch_variant(const GemmArgs& g0, bool out_f32, hipStream_t st)
 
 // variant: 0 = pick by shape; 1.. = force a tile configuration (used by the benchmark's sweep)
 hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const void* w_codes, const void* w_scales,
-                             int64_t M, int64_t N, int64_t K, void* out, bool out_f32, int variant, hipStream_t st)
+                             int64_t M, int64_t N, int64_t K, void* out, bool out_f32, int variant, float alpha, hipStream_t st)
 {
     GemmArgs g{};
+    g.alpha = alpha;
     g.a_codes = static_cast<const uint8_t*>(a_codes);
     g.a_scales = static_cast<const uint8_t*>(a_scales);
     g.w_codes = static_cast<const uint8_t*>(w_codes);

@@ -26,6 +26,7 @@ struct SkinnyArgs {
     const float* w_ts;
     void* out;
     int M, N, K;
+    float alpha;  // MXFP4: factor on the result (powers of 4/3 for operands whose scales carry the tensor-level 4/3), else 1
 };
 
 template <int FMT, int MT, bool OUT_F32>
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_kernel(SkinnyAr
         *reinterpret_cast<v4f*>(&partial[wave][t][lane * 4]) = acc[t];
     __syncthreads();
 
-    float ts = 1.0f;
+    float ts = g.alpha;
     if constexpr (FMT == 1) ts = (*g.a_ts) * (*g.w_ts);
     for (int e = threadIdx.x; e < MT * 256; e += kSkinnyWaves * 64) {
         const int t = e >> 8, r = e & 255, l = r >> 2, v = r & 3;
@@ -146,9 +147,10 @@ hipError_t launch_fmt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
 
 hipError_t launch_gemm_skinny(const void* a_codes, const void* a_scales, const float* a_ts, const void* w_codes,
                               const void* w_scales, const float* w_ts, int64_t M, int64_t N, int64_t K, int fmt, void* out,
-                              bool out_f32, hipStream_t st)
+                              bool out_f32, float alpha, hipStream_t st)
 {
     SkinnyArgs g{};
+    g.alpha = alpha;
     g.a_codes = static_cast<const uint8_t*>(a_codes);
     g.a_scales = static_cast<const uint8_t*>(a_scales);
     g.w_codes = static_cast<const uint8_t*>(w_codes);

@@ -8,19 +8,20 @@
 
 namespace fp4mr {
 
-// mse: group scales by the squared-error search instead of abs-max.
+// policy: group scales by 0 abs-max, 1 squared-error search, 2 rounded exponent with the 4/3 factor (MXFP4 only).
 // rot: null for the normalised Hadamard of size b, else a bf16 [b, b] row-major matrix (y = x . rot per block)
 hipError_t launch_rotate_quantize(const void* x, int64_t rows, int64_t K, int b, const void* rot, int fmt, bool in_f32,
-                                  int layout_gemm, bool static_scale, bool mse, void* codes, void* scales,
+                                  int layout_gemm, bool static_scale, int policy, void* codes, void* scales,
                                   float* tensor_scale, void* workspace, bool hw_codec, hipStream_t st);
 
 // canonical -> GEMM layout copy of one quantized operand (codes and scales)
 hipError_t launch_repack_to_gemm(const void* codes, const void* scales, int64_t rows, int64_t K, int fmt,
                                  void* codes_gemm, void* scales_gemm, hipStream_t st);
 
-// both operands in GEMM layout
+// both operands in GEMM layout; alpha multiplies the result (1, or powers of 4/3 for operands quantized with the
+// rounded-exponent rule whose scale bytes leave that tensor-level factor out)
 hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const void* w_codes, const void* w_scales,
-                             int64_t M, int64_t N, int64_t K, void* out, bool out_f32, int variant, hipStream_t st);
+                             int64_t M, int64_t N, int64_t K, void* out, bool out_f32, int variant, float alpha, hipStream_t st);
 
 hipError_t launch_gemm_nvfp4(const void* a_codes, const void* a_scales, const float* a_ts, const void* w_codes,
                              const void* w_scales, const float* w_ts, int64_t M, int64_t N, int64_t K, void* out,
@@ -29,11 +30,11 @@ hipError_t launch_gemm_nvfp4(const void* a_codes, const void* a_scales, const fl
 // few-token (M <= 64) weight-streaming GEMM, both formats, operands in GEMM layout
 hipError_t launch_gemm_skinny(const void* a_codes, const void* a_scales, const float* a_ts, const void* w_codes,
                               const void* w_scales, const float* w_ts, int64_t M, int64_t N, int64_t K, int fmt, void* out,
-                              bool out_f32, hipStream_t st);
+                              bool out_f32, float alpha, hipStream_t st);
 
 // M <= 16, MXFP4: rotation + quantization of the activations inside the weight-streaming GEMM (W in GEMM layout);
 // weight_only: the rotated activations stay bf16 (W4A16)
 hipError_t launch_fused_decode(const void* x, int64_t M, int64_t K, int b, const void* w_codes, const void* w_scales,
-                               int64_t N, void* out, bool out_f32, bool weight_only, hipStream_t st);
+                               int64_t N, void* out, bool out_f32, bool weight_only, float alpha, hipStream_t st);
 
 }  // namespace fp4mr

@@ -131,7 +131,7 @@ __device__ __forceinline__ void build_dense_operand(v8bf (&hop)[BP / 16][BP / 32
 // Work item = FR * (128/BP) supertiles = FR * 2048 elements.
 //   canonical: supertiles are consecutive runs of 16 vectors in flat (row-major) order;
 //   GEMM:      an item is FR fragments (16 rows x 128 K); supertile u covers K-offset u*BP of all 16 rows.
-template <int BP, int G, int LAYOUT, int PASS, bool HW, int FR, bool MSE>
+template <int BP, int G, int LAYOUT, int PASS, bool HW, int FR, int POL>
 __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
 {
     constexpr int S = BP / 32;           // K-steps of the contraction
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
                     y[4 * t + v] = __fmaf_rn(h, a.c_hi, h * a.c_lo);
                 }
             uint32_t out[GQ::ND], sc[GQ::NG];
-            GQ::template run<MSE>(y, s_T, out, sc);
+            GQ::template run<POL>(y, s_T, out, sc);
 
             if constexpr (LAYOUT == 0) {
                 if (valid[u]) {
@@ -271,7 +271,7 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
 //     NVFP4: 128 bytes per fragment).
 // One item per workgroup, no grid-stride loop: the dispatcher balances the load.  Input loads and all stores are
 // non-temporal: every byte is touched exactly once.
-template <int BP, int G, bool HW, int KI, bool MSE>
+template <int BP, int G, bool HW, int KI, int POL>
 __global__ __launch_bounds__(kThreads) void rq_frag_kernel(RqArgs a)
 {
     constexpr int S = BP / 32, T = BP / 16, NO = BP / 4;
@@ -354,7 +354,7 @@ __global__ __launch_bounds__(kThreads) void rq_frag_kernel(RqArgs a)
                     y[4 * t + v] = __fmaf_rn(h, a.c_hi, h * a.c_lo);
                 }
             uint32_t out[GQ::ND], sc[GQ::NG];
-            GQ::template run<MSE>(y, s_T, out, sc);
+            GQ::template run<POL>(y, s_T, out, sc);
             const int rr = wib * RPW + u;  // row inside the row-block
             const int fr = kk * (BP / 8) + (e_grp >> 7), e0 = e_grp & 127;  // fragment of the item, offset inside it
             const int d = fr * 256 + ((((e0 >> 5) * 16 + rr) << 2) + ((e0 & 31) >> 3));
@@ -407,7 +407,7 @@ __global__ __launch_bounds__(kThreads) void rq_frag_kernel(RqArgs a)
 // No-rotation kernel (had_block = 1), bf16 or fp32 input.  Lane handles 8 consecutive elements; a group of G
 // spans G/8 adjacent lanes.  Work item = 2048 elements (256 lane-pieces, 4 per lane).
 //   canonical: flat;   GEMM: item = fragment, piece p = j*64+lane: row = p/16, K-offset 8*(p%16).
-template <typename TIN, int G, int LAYOUT, int PASS, bool HW, bool MSE>
+template <typename TIN, int G, int LAYOUT, int PASS, bool HW, int POL>
 __global__ __launch_bounds__(kThreads) void q_direct_kernel(RqArgs a)
 {
     using GQ = GroupQuant<G, 8, 1, HW>;
@@ -468,7 +468,7 @@ __global__ __launch_bounds__(kThreads) void q_direct_kernel(RqArgs a)
                 continue;
             }
             uint32_t out[1], sc[1];
-            GQ::template run<MSE>(y, s_T, out, sc);
+            GQ::template run<POL>(y, s_T, out, sc);
             if constexpr (LAYOUT == 0) {
                 if (valid) {
                     *reinterpret_cast<uint32_t*>(a.codes + (e0 >> 1)) = out[0];
@@ -507,7 +507,7 @@ __global__ __launch_bounds__(1024) void amax_finalize_kernel(const uint32_t* par
 }
 
 // ------------------------------------------------------------------------------------------------------
-template <int BP, int G, bool HW, bool MSE>
+template <int BP, int G, bool HW, int POL>
 hipError_t launch_frag(const RqArgs& a0, int grid_cap, hipStream_t st, int* blocks_out)
 {
     RqArgs a = a0;
@@ -520,7 +520,7 @@ hipError_t launch_frag(const RqArgs& a0, int grid_cap, hipStream_t st, int* bloc
     const int64_t gy = rbs < 32768 ? rbs : 32768, gz = (rbs + gy - 1) / gy;
     if (rbs < 1 || gz > 65535 || ipr > 0x7fffffffll) return hipErrorInvalidValue;
     if (blocks_out) *blocks_out = (int)(ipr * gy * gz);
-    hipLaunchKernelGGL((rq_frag_kernel<BP, G, HW, KI, MSE>), dim3((unsigned)ipr, (unsigned)gy, (unsigned)gz), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((rq_frag_kernel<BP, G, HW, KI, POL>), dim3((unsigned)ipr, (unsigned)gy, (unsigned)gz), dim3(kThreads), 0, st, a);
     return hipGetLastError();
 }
 
@@ -531,13 +531,13 @@ inline bool frag_kernel_eligible(const RqArgs& a)
     return round_up(a.rows, 16) / 16 * ((a.K + 511) / 512) >= 1024 && !a.rot;
 }
 
-template <int BP, int G, int LAYOUT, int PASS, bool HW, bool MSE>
+template <int BP, int G, int LAYOUT, int PASS, bool HW, int POL>
 hipError_t launch_mfma(const RqArgs& a0, int grid_cap, hipStream_t st, int* blocks_out)
 {
     if constexpr (LAYOUT == 1 && PASS == 0 && BP <= 64) {
         // The fragment-shaped kernel walks 16 rows x 512 K per wave, which is what HBM likes for big tensors; a
         // few-token call has too few of those items to fill the GPU, so it keeps the one-fragment-per-wave kernel.
-        if (frag_kernel_eligible(a0)) return launch_frag<BP, G, HW, MSE>(a0, grid_cap, st, blocks_out);
+        if (frag_kernel_eligible(a0)) return launch_frag<BP, G, HW, POL>(a0, grid_cap, st, blocks_out);
     }
     // two fragments' worth of loads in flight per wave for the widest block (canonical order only: there an
     // item may run past the end and is masked per vector; GEMM-order items are whole fragments)
@@ -555,11 +555,11 @@ hipError_t launch_mfma(const RqArgs& a0, int grid_cap, hipStream_t st, int* bloc
     if (blocks > grid_cap) blocks = grid_cap;
     if (blocks < 1) blocks = 1;
     if (blocks_out) *blocks_out = (int)blocks;
-    hipLaunchKernelGGL((rq_mfma_kernel<BP, G, LAYOUT, PASS, HW, FR, MSE>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((rq_mfma_kernel<BP, G, LAYOUT, PASS, HW, FR, POL>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
     return hipGetLastError();
 }
 
-template <typename TIN, int G, int LAYOUT, int PASS, bool HW, bool MSE>
+template <typename TIN, int G, int LAYOUT, int PASS, bool HW, int POL>
 hipError_t launch_direct(const RqArgs& a0, int grid_cap, hipStream_t st, int* blocks_out)
 {
     RqArgs a = a0;
@@ -569,38 +569,38 @@ hipError_t launch_direct(const RqArgs& a0, int grid_cap, hipStream_t st, int* bl
     if (blocks > grid_cap) blocks = grid_cap;
     if (blocks < 1) blocks = 1;
     if (blocks_out) *blocks_out = (int)blocks;
-    hipLaunchKernelGGL((q_direct_kernel<TIN, G, LAYOUT, PASS, HW, MSE>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((q_direct_kernel<TIN, G, LAYOUT, PASS, HW, POL>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
     return hipGetLastError();
 }
 
-template <int G, int LAYOUT, int PASS, bool HW, bool MSE>
+template <int G, int LAYOUT, int PASS, bool HW, int POL>
 hipError_t dispatch_block(const RqArgs& a, bool in_f32, int grid_cap, hipStream_t st, int* blocks_out)
 {
     if (a.b == 1) {
-        if (in_f32) return launch_direct<float, G, LAYOUT, PASS, HW, MSE>(a, grid_cap, st, blocks_out);
-        return launch_direct<uint16_t, G, LAYOUT, PASS, HW, MSE>(a, grid_cap, st, blocks_out);
+        if (in_f32) return launch_direct<float, G, LAYOUT, PASS, HW, POL>(a, grid_cap, st, blocks_out);
+        return launch_direct<uint16_t, G, LAYOUT, PASS, HW, POL>(a, grid_cap, st, blocks_out);
     }
-    if (a.b <= 32) return launch_mfma<32, G, LAYOUT, PASS, HW, MSE>(a, grid_cap, st, blocks_out);
+    if (a.b <= 32) return launch_mfma<32, G, LAYOUT, PASS, HW, POL>(a, grid_cap, st, blocks_out);
     // Hadamard blocks of 64 and 128 run on the 32-wide kernels plus butterfly levels across lanes wherever the
     // vectors of an MFMA group are consecutive along K: canonical order, and the big-call GEMM-order kernel.
     const bool k_consecutive = LAYOUT == 0 || frag_kernel_eligible(a);
-    if (!a.rot && k_consecutive) return launch_mfma<32, G, LAYOUT, PASS, HW, MSE>(a, grid_cap, st, blocks_out);
-    if (a.b == 64) return launch_mfma<64, G, LAYOUT, PASS, HW, MSE>(a, grid_cap, st, blocks_out);
-    return launch_mfma<128, G, LAYOUT, PASS, HW, MSE>(a, grid_cap, st, blocks_out);
+    if (!a.rot && k_consecutive) return launch_mfma<32, G, LAYOUT, PASS, HW, POL>(a, grid_cap, st, blocks_out);
+    if (a.b == 64) return launch_mfma<64, G, LAYOUT, PASS, HW, POL>(a, grid_cap, st, blocks_out);
+    return launch_mfma<128, G, LAYOUT, PASS, HW, POL>(a, grid_cap, st, blocks_out);
 }
 
-template <int G, bool HW, bool MSE = false>
+template <int G, bool HW, int POL = 0>
 hipError_t dispatch_layout_pass(const RqArgs& a, bool in_f32, int layout, int pass, int grid_cap, hipStream_t st, int* blocks_out = nullptr)
 {
-    if (pass == 1) return dispatch_block<G, 0, 1, HW, false>(a, in_f32, grid_cap, st, blocks_out);  // layout and scale policy do not matter for the abs-max pass
-    if (layout == 0) return dispatch_block<G, 0, 0, HW, MSE>(a, in_f32, grid_cap, st, blocks_out);
-    return dispatch_block<G, 1, 0, HW, MSE>(a, in_f32, grid_cap, st, blocks_out);
+    if (pass == 1) return dispatch_block<G, 0, 1, HW, 0>(a, in_f32, grid_cap, st, blocks_out);  // layout and scale policy do not matter for the abs-max pass
+    if (layout == 0) return dispatch_block<G, 0, 0, HW, POL>(a, in_f32, grid_cap, st, blocks_out);
+    return dispatch_block<G, 1, 0, HW, POL>(a, in_f32, grid_cap, st, blocks_out);
 }
 
 }  // namespace
 
 hipError_t launch_rotate_quantize(const void* x, int64_t rows, int64_t K, int b, const void* rot, int fmt, bool in_f32,
-                                  int layout_gemm, bool static_scale, bool mse, void* codes, void* scales,
+                                  int layout_gemm, bool static_scale, int policy, void* codes, void* scales,
                                   float* tensor_scale, void* workspace, bool hw_codec, hipStream_t st)
 {
     RqArgs a{};
@@ -641,10 +641,15 @@ hipError_t launch_rotate_quantize(const void* x, int64_t rows, int64_t K, int b,
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
     }
-    if (mse) {
+    if (policy == 1) {
         // the scale search is written with the hardware converts only
-        return fmt == 0 ? dispatch_layout_pass<32, true, true>(a, in_f32, layout_gemm, 0, grid_cap, st)
-                        : dispatch_layout_pass<16, true, true>(a, in_f32, layout_gemm, 0, grid_cap, st);
+        return fmt == 0 ? dispatch_layout_pass<32, true, 1>(a, in_f32, layout_gemm, 0, grid_cap, st)
+                        : dispatch_layout_pass<16, true, 1>(a, in_f32, layout_gemm, 0, grid_cap, st);
+    }
+    if (policy == 2) {
+        if (fmt != 0) return hipErrorInvalidValue;
+        return hw_codec ? dispatch_layout_pass<32, true, 2>(a, in_f32, layout_gemm, 0, grid_cap, st)
+                        : dispatch_layout_pass<32, false, 2>(a, in_f32, layout_gemm, 0, grid_cap, st);
     }
     if (fmt == 0)
         return hw_codec ? dispatch_layout_pass<32, true>(a, in_f32, layout_gemm, 0, grid_cap, st)

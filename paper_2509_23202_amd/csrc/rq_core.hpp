@@ -193,13 +193,60 @@ struct GroupQuant {
         }
     }
 
-    template <bool MSE>
+    // ---- rounded, 4/3-rescaled E8M0 scale (appendix on MXFP scale fitting, first equation): exponent
+    // k = round(log2(amax / 6)), scale (4/3) 2^k; the byte stores k, the factor 4/3 is the tensor's.
+    // With amax = m 2^e (1 <= m < 2): log2(amax / 6) = e - 2 + log2(m / 1.5) and m / 1.5 lies in [2/3, 4/3), so the
+    // rounded exponent is e - 2, less one when m / 1.5 < 2^-1/2, i.e. when m < 1.5 / sqrt 2 -- decided on the
+    // mantissa field against the smallest binary32 mantissa above that (irrational) bound: an exact decision.
+    // Elements: E2M1(0.75 y 2^-k).  0.75 y is not always a binary32 number, and rounding it to one before the
+    // convert rounds again could land on (or cross) a tie of the E2M1 grid; the product is therefore rounded TO ODD
+    // (truncate, then set the last mantissa bit if anything was lost -- the fma gives the lost part exactly), after
+    // which the convert's round-to-nearest-even returns the correctly rounded code (24 bits against the grid's 2).
+    __device__ static __forceinline__ float mul_075_to_odd(float v)
+    {
+        const float p = v * 0.75f;
+        const float r = __fmaf_rn(v, 0.75f, -p);  // exact: what the rounding of p dropped
+        const uint32_t pb = __float_as_uint(p);
+        // r and p of opposite sign: |p| was rounded up, step back to the truncated magnitude
+        const uint32_t odd = (pb - ((pb ^ __float_as_uint(r)) >> 31)) | 1u;
+        return __uint_as_float((r != 0.0f && (pb << 1) != 0u) ? odd : pb);  // (a product that underflowed to zero stays zero)
+    }
+
+    __device__ static __forceinline__ void mx43(const float (&y)[NO], uint32_t (&out)[ND], uint32_t (&sc)[NG])
+    {
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) {
+            float amax = 0.0f;
+#pragma unroll
+            for (int i = 0; i < VG; ++i) amax = fabs_max(amax, y[gi * VG + i]);
+            if constexpr (LG >= 2) amax = fmaxf(amax, __shfl_xor(amax, XOR_LO));
+            if constexpr (LG >= 4) amax = fmaxf(amax, __shfl_xor(amax, XOR_LO * 2));
+            const uint32_t ab = __float_as_uint(amax);
+            const int ef = (int)((ab >> 23) & 0xffu);
+            const int below = (ab & 0x7fffffu) < 0x7c3b7u ? 1 : 0;  // mantissa under 1.5 / sqrt 2
+            const uint32_t byte = (uint32_t)max(ef - 2 - below, 0);
+            sc[gi] = byte;
+#pragma unroll
+            for (int d = 0; d < VG / 8; ++d) {
+                float t[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) t[i] = mul_075_to_odd(y[gi * VG + d * 8 + i]);
+                out[gi * (VG / 8) + d] = e2m1_pack8_e8m0<HW>(t, byte);
+            }
+        }
+    }
+
+    // POL: 0 abs-max, 1 squared-error search, 2 rounded exponent with the 4/3 factor (MXFP4 only)
+    template <int POL>
     __device__ static __forceinline__ void run(const float (&y)[NO], float s_T, uint32_t (&out)[ND], uint32_t (&sc)[NG])
     {
+        static_assert(POL >= 0 && POL <= 2 && (POL != 2 || G == 32), "scale policy");
         if constexpr (G == 32) {
-            if constexpr (MSE) mx_mse(y, out, sc); else mx(y, out, sc);
+            if constexpr (POL == 1) mx_mse(y, out, sc);
+            else if constexpr (POL == 2) mx43(y, out, sc);
+            else mx(y, out, sc);
         } else {
-            if constexpr (MSE) nv_mse(y, s_T, out, sc); else nv(y, s_T, out, sc);
+            if constexpr (POL == 1) nv_mse(y, s_T, out, sc); else nv(y, s_T, out, sc);
         }
     }
 };

@@ -39,7 +39,8 @@ def test_binding_imports_and_matches_header():
     for n in ("fp4_rotate_quantize", "fp4_rotate_quantize_dense", "fp4_quantize_weights", "fp4_gemm"):
         assert callable(getattr(binding, n))
     hdr = HEADER.read_text()
-    for name in ("LAYOUT_GEMM", "INPUT_F32", "STATIC_TENSOR_SCALE", "A_LAYOUT_GEMM", "W_LAYOUT_GEMM", "OUT_F32", "SCALE_MSE"):
+    for name in ("LAYOUT_GEMM", "INPUT_F32", "STATIC_TENSOR_SCALE", "A_LAYOUT_GEMM", "W_LAYOUT_GEMM", "OUT_F32", "SCALE_MSE",
+                 "SCALE_ROUND43", "A_SCALE43", "W_SCALE43"):
         m = re.search(rf"FP4MR_{name}\s*=\s*1u\s*<<\s*(\d+)", hdr)
         assert m and getattr(binding, name) == 1 << int(m.group(1)), name
 
@@ -76,6 +77,8 @@ def test_argument_validation_happens_before_any_launch(lib):
     assert q(fmt=2) == 4 and q(flags=1 << 9) == 4                # fmt / flags
     assert q(x=fake + 4) == 5 and q(codes=fake + 8) == 5         # alignment
     assert q(fmt=1) == 1                        # NVFP4 needs the tensor-scale pointer
+    assert q(fmt=1, ts=fake, ws=fake, wsz=1 << 20, flags=b.SCALE_ROUND43) == 4   # the 4/3 rule is an MXFP4 rule
+    assert q(flags=b.SCALE_ROUND43 | b.SCALE_MSE) == 4                           # one scale policy at a time
     assert q(fmt=1, ts=fake) == 6               # ... and a workspace
     assert q(fmt=1, ts=fake, ws=fake, wsz=8) == 6
     g = lambda **kw: L.fp4_gemm(kw.get("a", fake), fake, kw.get("ats", None), fake, fake, None, kw.get("M", 16), kw.get("N", 16),
@@ -86,6 +89,7 @@ def test_argument_validation_happens_before_any_launch(lib):
     assert g(fmt=3) == 4 and g(flags=1 << 12) == 4
     assert g(out=fake + 2) == 5
     assert g(fmt=1) == 1                        # NVFP4 needs both tensor scales
+    assert g(fmt=1, ats=fake, flags=b.A_LAYOUT_GEMM | b.W_LAYOUT_GEMM | b.W_SCALE43) in (1, 4)   # (w_ts NULL is caught first)
     assert g(flags=0) == 6                      # canonical operands need the repack workspace
     assert L.fp4_status_string(2).decode().startswith("bad shape")
     for s in range(8):
