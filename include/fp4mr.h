@@ -72,7 +72,7 @@ enum {
 };
 
 /* operation selector for fp4_workspace_bytes */
-enum { FP4MR_OP_ROTATE_QUANTIZE = 0, FP4MR_OP_QUANTIZE_WEIGHTS = 1, FP4MR_OP_GEMM = 2 };
+enum { FP4MR_OP_ROTATE_QUANTIZE = 0, FP4MR_OP_QUANTIZE_WEIGHTS = 1, FP4MR_OP_GEMM = 2, FP4MR_OP_GPTQ = 3 };
 
 /*
  * Online rotation + quantization of activations: codes, scales = Q(X H_b)   (Section 4.2 item 1: rotation
@@ -167,6 +167,31 @@ fp4mr_status_t fp4_fused_linear(const void* x, int64_t M, int64_t K, int had_blo
  */
 fp4mr_status_t fp4_w4a16_linear(const void* x, int64_t M, int64_t K, int had_block, const void* w_codes, const void* w_scales,
                                 int64_t N, fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream);
+
+/*
+ * Offline MR-GPTQ weight quantizer, the part that runs over the weight matrix (Section 4: all rows are quantized in one
+ * fixed column order, each rounded column's error is pushed onto the columns still to come by the optimal-brain update;
+ * Section 4.1: on the rotated weights W H_b, with the scales fixed beforehand in the original column order -- abs-max,
+ * or FP4MR_SCALE_MSE / FP4MR_SCALE_ROUND43 -- and the columns visited in a static activation order).  Accumulating
+ * the Hessian of the rotated calibration inputs, ordering, dampening, inverting and factoring it are dense
+ * linear-algebra steps left to the caller, who passes their result:
+ *   w            [N,K] bf16 row-major, N <= 65535, K % 64 == 0 and K % lcm(b, G) == 0
+ *   had_block    b in {1,16,32,64,128}
+ *   hinv_u       [K,K] fp32 row-major, device: upper-triangular U with U^T U = (H[perm][:,perm] + lambda I)^-1, rows and
+ *                columns in visiting order; only the upper triangle is read; the diagonal must be non-zero
+ *   perm         [K] int32, device: perm[j] = original index of the column visited j-th (NULL: 0, 1, 2, ...).  Must be a
+ *                permutation; entries outside [0,K) are clamped (garbage codes, no fault)
+ *   codes_out, scales_out   canonical layout, as fp4_quantize_weights writes them (scales_out equals its output bit for
+ *                bit: the sweep changes codes only); tensor_scale as there (NVFP4)
+ *   workspace    fp4_workspace_bytes(FP4MR_OP_GPTQ, N, 0, K, fmt, flags) bytes
+ *   flags        FP4MR_SCALE_MSE or FP4MR_SCALE_ROUND43 (optional); anything else: FP4MR_ERR_FMT
+ * Per column j (visiting order), for every row:  q = E2M1(w_j / s),  e = (w_j - q s) / U[j,j],  w_k -= e U[j,k] (k > j),
+ * in fp32; s is the fixed scale of the group the column belongs to in the ORIGINAL order.
+ */
+fp4mr_status_t fp4_gptq_quantize_weights(const void* w, int64_t N, int64_t K, int had_block, fp4mr_fmt_t fmt,
+                                         const float* hinv_u, const int32_t* perm, void* codes_out, void* scales_out,
+                                         float* tensor_scale, void* workspace, size_t workspace_bytes, uint32_t flags,
+                                         void* stream);
 
 /* Bytes of device scratch the given operation needs (0 = none).  rows = M for the quantize ops. */
 size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t fmt, uint32_t flags);

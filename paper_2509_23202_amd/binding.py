@@ -30,7 +30,7 @@ SCALE_MSE = 1 << 6
 SCALE_ROUND43 = 1 << 7
 A_SCALE43 = 1 << 8
 W_SCALE43 = 1 << 9
-OP_ROTATE_QUANTIZE, OP_QUANTIZE_WEIGHTS, OP_GEMM = 0, 1, 2
+OP_ROTATE_QUANTIZE, OP_QUANTIZE_WEIGHTS, OP_GEMM, OP_GPTQ = 0, 1, 2, 3
 
 _p, _i64, _i32, _u32, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32, ctypes.c_size_t
 _quant_sig = [_p, _i64, _i64, _i32, _i32, _p, _p, _p, _p, _sz, _u32, _p]
@@ -44,6 +44,8 @@ lib.fp4_fused_linear.argtypes = [_p, _i64, _i64, _i32, _p, _p, _i64, _i32, _p, _
 lib.fp4_fused_linear.restype = _i32
 lib.fp4_w4a16_linear.argtypes = lib.fp4_fused_linear.argtypes
 lib.fp4_w4a16_linear.restype = _i32
+lib.fp4_gptq_quantize_weights.argtypes = [_p, _i64, _i64, _i32, _i32, _p, _p, _p, _p, _p, _p, _sz, _u32, _p]
+lib.fp4_gptq_quantize_weights.restype = _i32
 lib.fp4_gemm.argtypes = [_p, _p, _p, _p, _p, _p, _i64, _i64, _i64, _i32, _p, _p, _sz, _u32, _p]
 lib.fp4_gemm.restype = _i32
 lib.fp4_workspace_bytes.argtypes = [_i32, _i64, _i64, _i64, _i32, _u32]
@@ -135,6 +137,26 @@ def fp4_quantize_weights(w, had_block: int, fmt: int, *, flags: int = 0, tensor_
                          workspace=None):
     """Offline RTN weight preparation, codes, scales, tensor_scale = Q(W H_b).  w: [N,K] bf16 cuda tensor."""
     return _quantize(lib.fp4_quantize_weights, OP_QUANTIZE_WEIGHTS, w, had_block, fmt, flags, tensor_scale, codes, scales, workspace)
+
+
+def fp4_gptq_quantize_weights(w, had_block: int, fmt: int, hinv_u, perm=None, *, flags: int = 0, workspace=None):
+    """MR-GPTQ sweep: w bf16 [N,K], hinv_u fp32 [K,K] (upper factor of the damped inverse Hessian in visiting order),
+    perm int32 [K] or None.  Returns (codes, scales, tensor_scale) in canonical layout."""
+    assert w.is_cuda and w.dim() == 2 and w.is_contiguous() and w.dtype == torch.bfloat16
+    N, K = w.shape
+    assert hinv_u.is_cuda and hinv_u.dtype == torch.float32 and hinv_u.is_contiguous() and tuple(hinv_u.shape) == (K, K)
+    if perm is not None:
+        assert perm.is_cuda and perm.dtype == torch.int32 and perm.is_contiguous() and perm.numel() == K
+    cb, sb = packed_bytes(N, K, fmt, 0)
+    codes = torch.empty(cb, dtype=torch.uint8, device=w.device)
+    scales = torch.empty(sb, dtype=torch.uint8, device=w.device)
+    ts = torch.empty(1, dtype=torch.float32, device=w.device) if fmt == NVFP4 else None
+    need = workspace_bytes(OP_GPTQ, N, 0, K, fmt, flags)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=w.device)
+    _check(lib.fp4_gptq_quantize_weights(w.data_ptr(), N, K, had_block, fmt, hinv_u.data_ptr(), _ptr(perm), codes.data_ptr(),
+                                         scales.data_ptr(), _ptr(ts), workspace.data_ptr(), workspace.numel(), flags, _stream()))
+    return codes, scales, ts
 
 
 def fp4_gemm(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M: int, N: int, K: int, fmt: int, *,

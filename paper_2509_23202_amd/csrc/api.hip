@@ -174,6 +174,31 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
 }
 
+fp4mr_status_t fp4_gptq_quantize_weights(const void* w, int64_t N, int64_t K, int had_block, fp4mr_fmt_t fmt,
+                                         const float* hinv_u, const int32_t* perm, void* codes_out, void* scales_out,
+                                         float* tensor_scale, void* workspace, size_t workspace_bytes, uint32_t flags,
+                                         void* stream)
+{
+    if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return FP4MR_ERR_FMT;
+    if (flags & ~(uint32_t)(FP4MR_SCALE_MSE | FP4MR_SCALE_ROUND43)) return FP4MR_ERR_FMT;
+    if (!hinv_u) return FP4MR_ERR_NULL;
+    if (N > 65535 || K <= 0 || K % 64 != 0) return FP4MR_ERR_SHAPE;
+    if (!aligned16(hinv_u) || (perm && !aligned16(perm))) return FP4MR_ERR_ALIGN;
+    const size_t need = fp4_workspace_bytes(FP4MR_OP_GPTQ, N, 0, K, fmt, flags);
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return FP4MR_ERR_WORKSPACE;
+    // 1. the grid: scales (and the NVFP4 tensor scale) of the rotated weights in their original order; the codes this
+    //    writes are the round-to-nearest ones, replaced below
+    const size_t qws = align256(quant_workspace(fmt, flags));
+    const fp4mr_status_t s = quantize_common(w, N, K, had_block, nullptr, fmt, codes_out, scales_out, tensor_scale, workspace, qws, flags, stream);
+    if (s != FP4MR_OK) return s;
+    // 2. the sweep
+    const hipError_t e = launch_gptq_sweep(w, N, K, had_block, (int)fmt, hinv_u, reinterpret_cast<const int*>(perm), scales_out,
+                                           fmt == FP4MR_NVFP4 ? tensor_scale : nullptr,
+                                           (flags & FP4MR_SCALE_ROUND43) ? 4.0f / 3.0f : 1.0f, codes_out,
+                                           static_cast<char*>(workspace) + qws, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
+}
+
 fp4mr_status_t fp4_fused_linear(const void* x, int64_t M, int64_t K, int had_block, const void* w_codes, const void* w_scales,
                                 int64_t N, fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream)
 {
@@ -190,6 +215,7 @@ size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t 
 {
     if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return 0;
     if (op == FP4MR_OP_ROTATE_QUANTIZE || op == FP4MR_OP_QUANTIZE_WEIGHTS) return quant_workspace(fmt, flags);
+    if (op == FP4MR_OP_GPTQ) return (M > 0 && K > 0) ? align256(quant_workspace(fmt, flags)) + gptq_workspace_bytes(M, K) : 0;
     if (op == FP4MR_OP_GEMM) {
         if (M <= 0 || N <= 0 || K <= 0 || K % 128 != 0) return 0;
         size_t n = 0;

@@ -26,7 +26,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert {"fp4_rotate_quantize", "fp4_rotate_quantize_dense", "fp4_fused_linear", "fp4_w4a16_linear", "fp4_quantize_weights", "fp4_gemm", "fp4_workspace_bytes",
+    assert {"fp4_rotate_quantize", "fp4_rotate_quantize_dense", "fp4_fused_linear", "fp4_w4a16_linear", "fp4_quantize_weights", "fp4_gptq_quantize_weights", "fp4_gemm", "fp4_workspace_bytes",
             "fp4_packed_bytes", "fp4_status_string", "fp4_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -91,6 +91,12 @@ def test_argument_validation_happens_before_any_launch(lib):
     assert g(fmt=1) == 1                        # NVFP4 needs both tensor scales
     assert g(fmt=1, ats=fake, flags=b.A_LAYOUT_GEMM | b.W_LAYOUT_GEMM | b.W_SCALE43) in (1, 4)   # (w_ts NULL is caught first)
     assert g(flags=0) == 6                      # canonical operands need the repack workspace
+    gq = lambda **kw: L.fp4_gptq_quantize_weights(fake, kw.get("N", 16), kw.get("K", 128), 32, kw.get("fmt", 0), kw.get("U", fake),
+                                                  kw.get("perm", None), fake, fake, None, kw.get("ws", fake), kw.get("wsz", 1 << 30),
+                                                  kw.get("flags", 0), None)
+    assert gq(U=None) == 1 and gq(K=96) == 2 and gq(N=70000) == 2 and gq(flags=b.LAYOUT_GEMM) == 4
+    assert gq(U=fake + 4) == 5 and gq(perm=fake + 4) == 5 and gq(ws=None) == 6 and gq(wsz=1024) == 6
+    assert b.workspace_bytes(b.OP_GPTQ, 128, 0, 256, b.MXFP4) >= 128 * 256 * 5 + 128 * 64 * 4 + 256 * 4
     assert L.fp4_status_string(2).decode().startswith("bad shape")
     for s in range(8):
         assert L.fp4_status_string(s)

@@ -1,0 +1,134 @@
+"""GPU parity of the MR-GPTQ sweep (fp4_gptq_quantize_weights) against the NumPy oracle (oracle/gptq.py).
+
+The sweep rounds a running value that carries the accumulated updates of every earlier column; the kernel keeps it in
+fp32, the oracle in fp64.  Where all the arithmetic is exact in both (dyadic weights and factor entries, errors pushed
+one step only) the codes must be bit-exact.  On realistic inputs a rounding may flip where the running value sits
+within fp32 noise of a grid midpoint, and a flip changes what later columns of that row see -- so the bar there is: the
+scale bytes are the round-to-nearest ones bit for bit, nearly all codes equal the oracle's, and the quantity GPTQ
+minimises, the layer's output error tr(dW H dW^T), is the oracle's within 1e-3 relative.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2509_23202_amd import inputs
+from tests.gpu_util import MX, NV, to_dev, to_dev_bf16, unpack
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def fp4():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2509_23202_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def gptq():
+    from oracle import gptq
+    return gptq
+
+
+def np_(t):
+    return t.detach().cpu().numpy()
+
+
+def test_sweep_is_bit_exact_where_the_arithmetic_is_exact(fp4, oracle, gptq):
+    """Weights on a 2^-6 lattice, no rotation, unit diagonal, and every even column (in visiting order) pushing its error
+    onto a few later odd columns with factors +-2^-3, +-2^-4 (odd columns push nothing): every product and sum is exact
+    in fp32, so the codes must equal the oracle's everywhere -- across the 64-column block boundaries (update kernel),
+    through a random visiting order, with a ragged last group of rows."""
+    import torch
+    rng = np.random.default_rng(0)
+    N, K = 70, 256
+    w = (rng.integers(-200, 201, (N, K)) / 64.0).astype(np.float32)
+    wb = inputs.f32_to_bf16_bits(w)
+    assert np.array_equal(inputs.bf16_bits_to_f32(wb), w)      # the lattice values are bf16 numbers
+    perm = rng.permutation(K).astype(np.int32)
+    U = np.eye(K, dtype=np.float32)
+    for j in range(0, K, 2):
+        for d, mag in ((1, 0.125), (3, 0.0625), (65, 0.125), (131, 0.0625)):
+            if j + d < K:
+                U[j, j + d] = mag * rng.choice([-1.0, 1.0])
+    y = oracle.rotate(wb, 1)
+    _, scales, _ = oracle.quantize(y, MX)
+    want, _ = gptq.sweep(y, scales, MX, None, U, perm)
+    rtn, _, _ = oracle.quantize(y, MX)
+    say("gptq exact lattice case")
+    c, s, _ = fp4.fp4_gptq_quantize_weights(to_dev_bf16(wb), 1, MX, to_dev(U), to_dev(perm))
+    torch.cuda.synchronize()
+    assert np.array_equal(np_(s).reshape(N, -1), scales)
+    assert np.array_equal(np_(c).reshape(N, -1), want)
+    assert (want != rtn).mean() > 0.02          # the pushed errors did change codes
+
+
+@pytest.mark.parametrize("fmt", [MX, NV])
+def test_diagonal_factor_gives_round_to_nearest(fp4, oracle, fmt):
+    import torch
+    N, K, b = 33, 512, 32
+    wb = inputs.RECIPES[6].w(N, K, salt=9)
+    U = np.diag(np.random.default_rng(1).uniform(0.5, 2.0, K)).astype(np.float32)
+    say(f"gptq diagonal fmt={fmt}")
+    c, s, T = fp4.fp4_gptq_quantize_weights(to_dev_bf16(wb), b, fmt, to_dev(U), None)
+    c0, s0, T0 = fp4.fp4_quantize_weights(to_dev_bf16(wb), b, fmt)
+    torch.cuda.synchronize()
+    assert np.array_equal(np_(s), np_(s0))
+    if fmt == NV:
+        assert np_(T)[0] == np_(T0)[0]
+    diff = unpack(np_(c).reshape(N, -1)) != unpack(np_(c0).reshape(N, -1))
+    # MXFP4: w / s is exact both ways.  NVFP4: the quantizer multiplies by a rounded reciprocal, the sweep divides
+    assert diff.mean() <= (0.0 if fmt == MX else 1e-4)
+
+
+@pytest.mark.parametrize("fmt,policy,b", [(MX, "absmax", 32), (MX, "mse", 128), (MX, "round43", 32), (NV, "absmax", 16), (NV, "mse", 32)])
+def test_sweep_matches_the_oracle_on_synthetic_hessians(fp4, oracle, gptq, fmt, policy, b):
+    import torch
+    N, K, T = 100, 512, 1024
+    r = inputs.RECIPES[6]
+    wb, xb = r.w(N, K, salt=40), r.x(T, K, salt=41)
+    X = oracle.rotate(xb, b).astype(np.float64)
+    H = X.T @ X
+    perm = gptq.act_order(H).astype(np.int32)
+    U = gptq.inverse_factor(H, perm, damp=1e-2).astype(np.float32)
+    y = oracle.rotate(wb, b)
+    c_rtn, scales, sT = oracle.quantize(y, fmt, policy=policy)
+    want, _ = gptq.sweep(y, scales, fmt, sT, U, perm)
+    flags = {"absmax": 0, "mse": fp4.SCALE_MSE, "round43": fp4.SCALE_ROUND43}[policy]
+    say(f"gptq synthetic fmt={fmt} policy={policy} b={b}")
+    c, s, Tg = fp4.fp4_gptq_quantize_weights(to_dev_bf16(wb), b, fmt, to_dev(U), to_dev(perm), flags=flags)
+    torch.cuda.synchronize()
+    got_c, got_s = np_(c).reshape(N, -1), np_(s).reshape(N, -1)
+    assert (got_s != scales).mean() <= 1e-3
+    if fmt == NV:
+        assert abs(float(np_(Tg)[0]) - float(sT)) <= 2 * np.spacing(np.float32(sT))
+    rows_ok = (got_s == scales).all(axis=1)
+    diff = unpack(got_c) != unpack(want)
+    e_got = gptq.layer_error(y[rows_ok], got_c[rows_ok], scales[rows_ok], fmt, sT, H)
+    e_ref = gptq.layer_error(y[rows_ok], want[rows_ok], scales[rows_ok], fmt, sT, H)
+    e_rtn = gptq.layer_error(y[rows_ok], c_rtn[rows_ok], scales[rows_ok], fmt, sT, H)
+    say(f"   codes differing from the oracle: {diff[rows_ok].mean():.2e}; layer error {e_got:.6e} vs oracle {e_ref:.6e} (round-to-nearest {e_rtn:.4e})")
+    assert diff[rows_ok].mean() <= 5e-3
+    assert abs(e_got - e_ref) <= 1e-3 * e_ref
+    assert e_got < 0.8 * e_rtn
+
+
+def test_gptq_argument_validation(fp4):
+    import torch
+    w = torch.zeros((16, 128), dtype=torch.bfloat16, device="cuda")
+    U = torch.eye(128, dtype=torch.float32, device="cuda")
+    with pytest.raises(Exception):
+        fp4.fp4_gptq_quantize_weights(w, 32, MX, U, None, flags=fp4.LAYOUT_GEMM)
+    w96 = torch.zeros((16, 96), dtype=torch.bfloat16, device="cuda")
+    U96 = torch.eye(96, dtype=torch.float32, device="cuda")
+    with pytest.raises(Exception):
+        fp4.fp4_gptq_quantize_weights(w96, 32, MX, U96, None)
+    with pytest.raises(Exception):
+        fp4.fp4_gptq_quantize_weights(w, 32, MX, U, None, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
