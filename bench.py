@@ -335,6 +335,29 @@ def main():
         except Exception as exc:  # noqa: BLE001 - reported in the JSON line
             extras_errors["decode"] = repr(exc)
 
+        try:
+            # ---- offline MR-GPTQ sweep of one [4096, 4096] layer (not part of the step; fp32 vector arithmetic): the
+            # factor is a random upper-triangular matrix with a positive diagonal (timing does not depend on its values)
+            Ng, Kg = 4096, 4096
+            wg = (torch.randn(Ng, Kg, device="cuda") * 0.02).to(torch.bfloat16)
+            Ug = torch.triu(torch.randn(Kg, Kg, device="cuda") * 0.01, diagonal=1) + torch.diag(torch.rand(Kg, device="cuda") + 0.5)
+            pg = torch.randperm(Kg, device="cuda").to(torch.int32)
+            wsg = torch.empty(fp4.workspace_bytes(fp4.OP_GPTQ, Ng, 0, Kg, fp4.MXFP4, 0), dtype=torch.uint8, device="cuda")
+            fp4.fp4_gptq_quantize_weights(wg, b, fp4.MXFP4, Ug, pg, workspace=wsg)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(3):
+                fp4.fp4_gptq_quantize_weights(wg, b, fp4.MXFP4, Ug, pg, workspace=wsg)
+            torch.cuda.synchronize()
+            tg = (time.perf_counter() - t0) / 3
+            fl = float(Ng) * Kg * Kg      # N K^2 / 2 multiply-adds
+            result["gptq_offline"] = {"workload": f"W [{Ng}, {Kg}] bf16, MXFP4, Hadamard block {b}, act-order permutation, random factor",
+                                      "ms": round(tg * 1e3, 3), "bound": "alu", "achieved": round(fl / tg / 1e12, 2),
+                                      "peak": 157.3, "unit": "TFLOP/s", "frac": round(fl / tg / 1e12 / 157.3, 4)}
+            del wg, Ug, pg, wsg
+        except Exception as exc:  # noqa: BLE001 - reported in the JSON line
+            extras_errors["gptq_offline"] = repr(exc)
+
         if extras_errors:
             result["extras_errors"] = extras_errors
 

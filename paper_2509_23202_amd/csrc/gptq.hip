@@ -7,18 +7,21 @@
 //     q = Q(w_j / s),   e = (w_j - q s) / U[j,j],   w_k -= e U[j,k]  for every later column k.
 // Rows never interact, so the sweep is data-parallel over the N rows and strictly sequential along K.  It is blocked
 // 64 columns at a time: four lanes share a row and keep the block's 64 working weights in registers while the 64 x 64
-// triangle of U is read from LDS (block kernel); the block's 64 errors per row then update all later columns in
-// one rank-64 product (update kernel).  Working weights live in visiting order in an fp32 scratch matrix, codes in a
+// triangle of U is read from LDS (block kernel); the block's 64 errors per row then update the later columns of the
+// same 512-column outer block in a rank-64 product, and a finished outer block updates everything behind it in one
+// rank-512 product (update kernel).  Working weights live in visiting order in an fp32 scratch matrix, codes in a
 // byte-per-code scratch matrix, and a last kernel packs them back to the original column positions.
 #include "device_util.hpp"
 #include "internal.hpp"
 
+#include <algorithm>
 #include <cmath>
 
 namespace fp4mr {
 namespace {
 
-constexpr int kB = 64;  // columns per block
+constexpr int kB = 64;       // columns per block of the sequential sweep
+constexpr int kOuter = 512;  // columns per outer block: later columns receive its errors in one rank-512 update
 
 struct GptqArgs {
     const uint16_t* w;      // [N,K] bf16
@@ -27,7 +30,7 @@ struct GptqArgs {
     int* iperm;             // [K] scratch
     float* wp;              // [N,K] scratch: working weights, visiting order
     uint8_t* q;             // [N,K] scratch: one code per byte, visiting order
-    float* err;             // [N,kB] scratch
+    float* err;             // [N,kOuter] scratch: the errors of the current outer block
     const uint8_t* scales;  // [N,K/G] canonical
     const float* s_T;       // NVFP4 tensor scale (device), else null
     uint8_t* codes;         // [N,K/2] canonical
@@ -151,7 +154,7 @@ __device__ __forceinline__ void sweep_part(float (&w)[16], const float* Us, cons
 }
 
 template <int FMT>
-__global__ __launch_bounds__(64) void gptq_block_kernel(GptqArgs a, int b0)
+__global__ __launch_bounds__(64) void gptq_block_kernel(GptqArgs a, int b0, int e0)
 {
     __shared__ __attribute__((aligned(16))) float Us[kB * kB];
     __shared__ float Ss[kB * 16];  // [column][row of the wave]
@@ -185,7 +188,7 @@ __global__ __launch_bounds__(64) void gptq_block_kernel(GptqArgs a, int b0)
         Ss[j * 16 + row] = decode_scale<FMT>(srow[cols[j] / a.G], s_T, a.factor);
     }
     __syncthreads();  // the scale of a column is read by every lane of its row's quad
-    float* const erow = a.err + (int64_t)n * kB;
+    float* const erow = a.err + (int64_t)n * kOuter + e0;
     uint8_t* const qrow = a.q + (int64_t)n * a.K + b0;
     sweep_part<FMT, 0>(w, Us, Ss, row, part, live, erow, qrow);
     sweep_part<FMT, 1>(w, Us, Ss, row, part, live, erow, qrow);
@@ -193,20 +196,78 @@ __global__ __launch_bounds__(64) void gptq_block_kernel(GptqArgs a, int b0)
     sweep_part<FMT, 3>(w, Us, Ss, row, part, live, erow, qrow);
 }
 
-// wp[n, c] -= sum_j err[n, j] * U[b0 + j, c] for the columns c >= b0 + 64 (visiting order), applied one j at a time
-// in ascending order like the column-by-column definition.  64 x 64 output tile per workgroup, 4 x 4 per thread.
-__global__ __launch_bounds__(256) void gptq_update_kernel(GptqArgs a, int b0)
+// wp[n, c] -= sum_{j < rank} err[n, e0 + j] * U[u0 + j, c] for the columns c_begin <= c < c_end (visiting order), the
+// terms applied one j at a time in ascending order like the column-by-column definition.  128 x 128 output tile per
+// workgroup, 8 x 8 per thread, the errors and the rows of U staged through LDS 32 terms at a time.
+__global__ __launch_bounds__(256) void gptq_update_kernel(GptqArgs a, int u0, int e0, int rank, int c_begin, int c_end)
 {
-    __shared__ float Es[kB][kB + 1];  // [row][j]
-    __shared__ float Ut[kB][kB];      // [j][col]
-    const int c0 = b0 + kB + blockIdx.x * kB;
+    constexpr int T = 128, KC = 32;
+    __shared__ __attribute__((aligned(16))) float Et[KC][T];  // [term][row]
+    __shared__ __attribute__((aligned(16))) float Ut[KC][T];  // [term][column]
+    const int c0 = c_begin + blockIdx.x * T;
+    const int n0 = blockIdx.y * T;
+    const int tid = threadIdx.x;
+    const int ty = tid / 16, tx = tid % 16;
+    float acc[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int n = min(n0 + ty * 8 + i, a.N - 1);
+        const float* src = a.wp + (int64_t)n * a.K + c0 + tx * 8;
+        const bool in = c0 + tx * 8 < c_end;  // c_end and the tile start are multiples of 64: 8 columns are in or out together
+        const float4 lo = in ? *reinterpret_cast<const float4*>(src) : make_float4(0.f, 0.f, 0.f, 0.f);
+        const float4 hi = in ? *reinterpret_cast<const float4*>(src + 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        acc[i][0] = lo.x; acc[i][1] = lo.y; acc[i][2] = lo.z; acc[i][3] = lo.w;
+        acc[i][4] = hi.x; acc[i][5] = hi.y; acc[i][6] = hi.z; acc[i][7] = hi.w;
+    }
+    for (int r0 = 0; r0 < rank; r0 += KC) {
+        __syncthreads();
+        for (int idx = tid; idx < KC * T; idx += 256) {
+            const int x = idx % T, t = idx / T;
+            const int n = min(n0 + x, a.N - 1);
+            Et[t][x] = a.err[(int64_t)n * kOuter + e0 + r0 + t];
+            Ut[t][x] = (c0 + x < c_end) ? a.U[(int64_t)(u0 + r0 + t) * a.K + c0 + x] : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int t = 0; t < KC; ++t) {
+            const float4 e0v = *reinterpret_cast<const float4*>(&Et[t][ty * 8]);
+            const float4 e1v = *reinterpret_cast<const float4*>(&Et[t][ty * 8 + 4]);
+            const float4 u0v = *reinterpret_cast<const float4*>(&Ut[t][tx * 8]);
+            const float4 u1v = *reinterpret_cast<const float4*>(&Ut[t][tx * 8 + 4]);
+            const float e[8] = {e0v.x, e0v.y, e0v.z, e0v.w, e1v.x, e1v.y, e1v.z, e1v.w};
+            const float u[8] = {u0v.x, u0v.y, u0v.z, u0v.w, u1v.x, u1v.y, u1v.z, u1v.w};
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int k = 0; k < 8; ++k) acc[i][k] = __fmaf_rn(-e[i], u[k], acc[i][k]);
+        }
+    }
+    if (c0 + tx * 8 >= c_end) return;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int n = n0 + ty * 8 + i;
+        if (n >= a.N) continue;
+        float* dst = a.wp + (int64_t)n * a.K + c0 + tx * 8;
+        *reinterpret_cast<float4*>(dst) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+        *reinterpret_cast<float4*>(dst + 4) = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
+    }
+}
+
+// The same update for the 64 errors of one block onto the few hundred remaining columns of its outer block: 64 x 64
+// tiles, 4 x 4 per thread -- many small workgroups, since there is little work and it sits on the critical path
+// between two sequential block kernels.
+__global__ __launch_bounds__(256) void gptq_update_inner_kernel(GptqArgs a, int u0, int e0, int c_begin, int c_end)
+{
+    __shared__ float Es[kB][kB + 1];  // [row][term]
+    __shared__ float Ut[kB][kB];      // [term][column]
+    const int c0 = c_begin + blockIdx.x * kB;
     const int n0 = blockIdx.y * kB;
     const int tid = threadIdx.x;
     for (int i = tid; i < kB * kB; i += 256) {
         const int r = i / kB, c = i % kB;
         const int n = min(n0 + r, a.N - 1);
-        Es[r][c] = a.err[(int64_t)n * kB + c];
-        Ut[r][c] = (c0 + c < a.K) ? a.U[(int64_t)(b0 + r) * a.K + c0 + c] : 0.0f;
+        Es[r][c] = a.err[(int64_t)n * kOuter + e0 + c];
+        Ut[r][c] = (c0 + c < c_end) ? a.U[(int64_t)(u0 + r) * a.K + c0 + c] : 0.0f;
     }
     __syncthreads();
     const int ty = tid / 16, tx = tid % 16;
@@ -217,7 +278,7 @@ __global__ __launch_bounds__(256) void gptq_update_kernel(GptqArgs a, int b0)
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int c = c0 + tx * 4 + k;
-            acc[i][k] = (c < a.K) ? a.wp[(int64_t)n * a.K + c] : 0.0f;
+            acc[i][k] = (c < c_end) ? a.wp[(int64_t)n * a.K + c] : 0.0f;
         }
     }
     for (int j = 0; j < kB; ++j) {
@@ -235,7 +296,7 @@ __global__ __launch_bounds__(256) void gptq_update_kernel(GptqArgs a, int b0)
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int c = c0 + tx * 4 + k;
-            if (c < a.K) a.wp[(int64_t)n * a.K + c] = acc[i][k];
+            if (c < c_end) a.wp[(int64_t)n * a.K + c] = acc[i][k];
         }
     }
 }
@@ -257,7 +318,7 @@ inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 size_t gptq_workspace_bytes(int64_t N, int64_t K)
 {
-    return align256((size_t)N * K * 4) + align256((size_t)N * K) + align256((size_t)N * kB * 4) + align256((size_t)K * 4);
+    return align256((size_t)N * K * 4) + align256((size_t)N * K) + align256((size_t)N * kOuter * 4) + align256((size_t)K * 4);
 }
 
 hipError_t launch_gptq_sweep(const void* w, int64_t N, int64_t K, int b, int fmt, const float* U, const int* perm,
@@ -273,7 +334,7 @@ hipError_t launch_gptq_sweep(const void* w, int64_t N, int64_t K, int b, int fmt
     a.q = reinterpret_cast<uint8_t*>(ws);
     ws += align256((size_t)N * K);
     a.err = reinterpret_cast<float*>(ws);
-    ws += align256((size_t)N * kB * 4);
+    ws += align256((size_t)N * kOuter * 4);
     a.iperm = reinterpret_cast<int*>(ws);
     a.scales = static_cast<const uint8_t*>(scales);
     a.s_T = s_T;
@@ -292,12 +353,23 @@ hipError_t launch_gptq_sweep(const void* w, int64_t N, int64_t K, int b, int fmt
     hipLaunchKernelGGL(gptq_iperm_fill_kernel, dim3(kblocks), dim3(256), 0, st, a);
     hipLaunchKernelGGL(gptq_iperm_kernel, dim3(kblocks), dim3(256), 0, st, a);
     hipLaunchKernelGGL(gptq_rotate_gather_kernel, dim3(kblocks, (unsigned)N), dim3(256), 0, st, a);
-    const unsigned row_groups = (unsigned)((N + 63) / 64), row16 = (unsigned)((N + 15) / 16);
-    for (int b0 = 0; b0 < (int)K; b0 += kB) {
-        if (fmt == 0) hipLaunchKernelGGL(gptq_block_kernel<0>, dim3(row16), dim3(64), 0, st, a, b0);
-        else hipLaunchKernelGGL(gptq_block_kernel<1>, dim3(row16), dim3(64), 0, st, a, b0);
-        const int rest = (int)K - b0 - kB;
-        if (rest > 0) hipLaunchKernelGGL(gptq_update_kernel, dim3((unsigned)(rest / kB), row_groups), dim3(256), 0, st, a, b0);
+    const unsigned row128 = (unsigned)((N + 127) / 128), row16 = (unsigned)((N + 15) / 16);
+    auto update = [&](int u0, int e0, int rank, int c_begin, int c_end) {
+        const unsigned tiles = (unsigned)((c_end - c_begin + 127) / 128);
+        hipLaunchKernelGGL(gptq_update_kernel, dim3(tiles, row128), dim3(256), 0, st, a, u0, e0, rank, c_begin, c_end);
+    };
+    for (int o = 0; o < (int)K; o += kOuter) {
+        const int oe = std::min(o + kOuter, (int)K);
+        for (int b0 = o; b0 < oe; b0 += kB) {
+            if (fmt == 0) hipLaunchKernelGGL(gptq_block_kernel<0>, dim3(row16), dim3(64), 0, st, a, b0, b0 - o);
+            else hipLaunchKernelGGL(gptq_block_kernel<1>, dim3(row16), dim3(64), 0, st, a, b0, b0 - o);
+            // the rest of the outer block sees this block's errors at once ...
+            if (b0 + kB < oe)
+                hipLaunchKernelGGL(gptq_update_inner_kernel, dim3((unsigned)((oe - b0 - kB) / kB), (unsigned)((N + 63) / 64)), dim3(256), 0,
+                                   st, a, b0, b0 - o, b0 + kB, oe);
+        }
+        // ... everything behind the outer block sees all of its errors in one pass
+        if (oe < (int)K) update(o, 0, oe - o, oe, (int)K);
     }
     hipLaunchKernelGGL(gptq_pack_kernel, dim3((unsigned)((K / 2 + 255) / 256), (unsigned)N), dim3(256), 0, st, a);
     return hipGetLastError();

@@ -41,28 +41,28 @@ def np_(t):
     return t.detach().cpu().numpy()
 
 
-def test_sweep_is_bit_exact_where_the_arithmetic_is_exact(fp4, oracle, gptq):
+@pytest.mark.parametrize("N,K", [(70, 256), (150, 1088)])
+def test_sweep_is_bit_exact_where_the_arithmetic_is_exact(fp4, oracle, gptq, N, K):
     """Weights on a 2^-6 lattice, no rotation, unit diagonal, and every even column (in visiting order) pushing its error
     onto a few later odd columns with factors +-2^-3, +-2^-4 (odd columns push nothing): every product and sum is exact
-    in fp32, so the codes must equal the oracle's everywhere -- across the 64-column block boundaries (update kernel),
-    through a random visiting order, with a ragged last group of rows."""
+    in fp32, so the codes must equal the oracle's everywhere -- across the 64-column block boundaries and (K = 1088)
+    the 512-column outer blocks of the update kernel, through a random visiting order, with ragged row groups."""
     import torch
-    rng = np.random.default_rng(0)
-    N, K = 70, 256
+    rng = np.random.default_rng(K)
     w = (rng.integers(-200, 201, (N, K)) / 64.0).astype(np.float32)
     wb = inputs.f32_to_bf16_bits(w)
     assert np.array_equal(inputs.bf16_bits_to_f32(wb), w)      # the lattice values are bf16 numbers
     perm = rng.permutation(K).astype(np.int32)
     U = np.eye(K, dtype=np.float32)
     for j in range(0, K, 2):
-        for d, mag in ((1, 0.125), (3, 0.0625), (65, 0.125), (131, 0.0625)):
+        for d, mag in ((1, 0.125), (3, 0.0625), (65, 0.125), (131, 0.0625), (513, 0.125), (701, 0.0625)):
             if j + d < K:
                 U[j, j + d] = mag * rng.choice([-1.0, 1.0])
     y = oracle.rotate(wb, 1)
     _, scales, _ = oracle.quantize(y, MX)
     want, _ = gptq.sweep(y, scales, MX, None, U, perm)
     rtn, _, _ = oracle.quantize(y, MX)
-    say("gptq exact lattice case")
+    say(f"gptq exact lattice case N={N} K={K}")
     c, s, _ = fp4.fp4_gptq_quantize_weights(to_dev_bf16(wb), 1, MX, to_dev(U), to_dev(perm))
     torch.cuda.synchronize()
     assert np.array_equal(np_(s).reshape(N, -1), scales)
