@@ -155,7 +155,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     // Software pipeline of the LDS reads: the X fragments of step kt+1 are read into the other half of xf[2][.]
     // while step kt computes, and the W fragments run through a 4-deep register ring two groups of TM MFMAs ahead
     // of their use -- so no MFMA waits on LDS latency, at a cost of 2*TM*4 + 16 fragment registers.
-    constexpr int RING = (RD <= 3) ? 4 : 8;  // W-fragment register ring; RD = how many MFMA groups ahead it is filled
+    // W-fragment register ring; RD = how many MFMA groups ahead it is filled (three slots when TN is not a multiple of 4)
+    constexpr int RING = (TN % 4 != 0) ? 3 : ((RD <= 3) ? 4 : 8);
     v4i xf[2][TM], wring[RING];
     static_assert(TN % RING == 0 && RD < RING && RD <= TN, "the W-fragment ring index must be static");
     // every wave issues exactly LPW fragment loads per stage and NS scale loads per batch so that the vmcnt
@@ -192,7 +193,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
         xf[P][j] = *(reinterpret_cast<const v4i*>(smem + (kt % STAGES) * STAGE_BYTES + (wm * TM + j) * 1024) + lane);
     };
     auto read_w = [&](int kt, int i) {  // into ring slot i % 4 (i is a compile-time constant after unrolling)
-        wring[i & (RING - 1)] = *(reinterpret_cast<const v4i*>(smem + (kt % STAGES) * STAGE_BYTES + (FX + wn * TN + i) * 1024) + lane);
+        wring[i % RING] = *(reinterpret_cast<const v4i*>(smem + (kt % STAGES) * STAGE_BYTES + (FX + wn * TN + i) * 1024) + lane);
     };
 
     // prologue of a tile: scales of super-step 0 and STAGES-1 stages on their way into ring slots 0 .. STAGES-2
@@ -252,7 +253,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
             for (int j = i * XPG; j < (i + 1) * XPG && j < TM; ++j) read_x(kt + 1, std::integral_constant<int, 1 - P>{}, j);
 #pragma unroll
             for (int j = 0; j < TM; ++j) {
-                acc[i][j] = mfma_fp4<J>(wring[i & (RING - 1)], xf[P][j], acc[i][j], sw[i], sx[j]);
+                acc[i][j] = mfma_fp4<J>(wring[i % RING], xf[P][j], acc[i][j], sw[i], sx[j]);
                 if (j == SKEW) {
                     // the four waves of a workgroup run in lockstep (one barrier per step); issuing their loads at
                     // different points of the group keeps them from queueing up behind each other at the CU's one
@@ -287,7 +288,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     // slot; the other slots are free for the next tile's prologue loads while the stores drain.
     constexpr int CPR = WN / 8;                  // 16-byte chunks per staged row
     constexpr int STAGING = 16 * WN * 2;         // bytes per wave
-    constexpr bool STAGED = !OUT_F32 && NW * STAGING <= STAGE_BYTES && (CPR == 8 || CPR == 16);
+    constexpr bool STAGED = !OUT_F32 && NW * STAGING <= STAGE_BYTES && (CPR == 8 || CPR == 12 || CPR == 16);
+    constexpr int SWZ = (CPR == 12) ? 3 : CPR - 1;  // chunk swizzle mask: XOR stays inside an aligned group of SWZ + 1 chunks
 
     for (;;) {
         // stage 0 and the first scale batch have landed (this wave's copies: the vmcnt wait before this point)
@@ -348,14 +350,14 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
                 for (int i = 0; i < TN; ++i) {
                     const v4f v = acc[i][j];
                     const v4bf p = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3]};
-                    const int ch = (2 * i + (wq >> 1)) ^ (wr & (CPR - 1));
+                    const int ch = (2 * i + (wq >> 1)) ^ (wr & SWZ);
                     *reinterpret_cast<v4bf*>(mine + wr * (WN * 2) + ch * 16 + (wq & 1) * 8) = p;
                 }
 #pragma unroll
                 for (int it = 0; it < 16 * CPR / 64; ++it) {
                     const int c = it * 64 + el;
                     const int row = c / CPR, ch = c % CPR;
-                    const v4i v = *reinterpret_cast<const v4i*>(mine + row * (WN * 2) + ((ch ^ (row & (CPR - 1))) * 16));
+                    const v4i v = *reinterpret_cast<const v4i*>(mine + row * (WN * 2) + ((ch ^ (row & SWZ)) * 16));
                     const int64_t m = m0 + 16 * j + row, n = n0 + ch * 8;
                     // an interior tile issues exactly NST stores per wave (what the follow-on tile's vmcnt allowance counts)
                     if (interior || (m < g.M && n < g.N)) __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(static_cast<__bf16*>(g.out) + m * g.N + n));
@@ -485,6 +487,10 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
             double best = t10;
             if (t5 < best * 0.97) { variant = 5; best = t5; }
             if (t2 < best * 0.97) { variant = 2; best = t2; }
+            // 256x192: for widths where it tiles into fewer rounds than the square tile (N = 6144 on 256 compute units:
+            // 512 tiles, two full rounds of three quarters the work each, against 384 tiles = one and a half rounds)
+            const double t13 = rounds(tiles(256, 192), cus) * (10.0 + kt * 0.56);
+            if (t13 < best * 0.97) { variant = 13; best = t13; }
             // more 256x256 tiles than compute units: persistent workgroups, which prefetch the next tile's first stages
             // and let the output stores drain under its first K-steps (1.5-6% on such shapes, never slower)
             if (variant == 10 && tiles(256, 256) > cus) variant = 11;
@@ -503,6 +509,8 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
         case 10: return launch_variant<256, 256, 64, 128, 4, 3>(g, out_f32, st);
         case 11: return launch_variant<256, 256, 64, 128, 4, 3, true>(g, out_f32, st);
         case 12: return launch_variant<256, 128, 128, 64, 4, 2, true>(g, out_f32, st);
+        case 13: return launch_variant<256, 192, 64, 96, 4, 2>(g, out_f32, st);
+        case 14: return launch_variant<256, 192, 64, 96, 4, 2, true>(g, out_f32, st);
         default: return hipErrorInvalidValue;
     }
 }
