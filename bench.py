@@ -29,7 +29,7 @@ RQ_BYTES_PER_ELEM_MX = 2.0 + 0.5 + 1.0 / 32.0   # bf16 in, 4-bit code out, one s
 # HBM-side bytes per launch from hardware counters (FETCH_SIZE, WRITE_SIZE; two rocprofv3 --pmc runs of this script,
 # each scaled by the reading for a plain 1 GiB device copy: x2.000 and x1.000).  Summary and commands:
 # profiles/hbm_traffic__llama3_8b_prefill_m4096_and_rq_16384x8192__pmc.txt
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 265.7e6    # mean over the four GEMMs of a step: 177.5 MB fetched + 88.1 MB written
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 265.9e6    # mean over the four GEMMs of a step (fetched + written; 89.5 MB of it is the outputs)
 RQ_TRAFFIC_BYTES_PER_LAUNCH = 339.9e6      # [16384, 8192]: 268.6 MB fetched + 71.3 MB written (algorithmic: 339.7 MB)
 
 
