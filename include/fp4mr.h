@@ -175,7 +175,7 @@ fp4mr_status_t fp4_w4a16_linear(const void* x, int64_t M, int64_t K, int had_blo
  * or FP4MR_SCALE_MSE / FP4MR_SCALE_ROUND43 -- and the columns visited in a static activation order).  Accumulating
  * the Hessian of the rotated calibration inputs, ordering, dampening, inverting and factoring it are dense
  * linear-algebra steps left to the caller, who passes their result:
- *   w            [N,K] bf16 row-major, N <= 65535, K % 64 == 0 and K % lcm(b, G) == 0
+ *   w            [N,K] bf16 row-major, K % 64 == 0, K % lcm(b, G) == 0, K <= 24576
  *   had_block    b in {1,16,32,64,128}
  *   hinv_u       [K,K] fp32 row-major, device: upper-triangular U with U^T U = (H[perm][:,perm] + lambda I)^-1, rows and
  *                columns in visiting order; only the upper triangle is read; the diagonal must be non-zero

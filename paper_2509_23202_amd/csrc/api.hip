@@ -182,7 +182,7 @@ fp4mr_status_t fp4_gptq_quantize_weights(const void* w, int64_t N, int64_t K, in
     if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return FP4MR_ERR_FMT;
     if (flags & ~(uint32_t)(FP4MR_SCALE_MSE | FP4MR_SCALE_ROUND43)) return FP4MR_ERR_FMT;
     if (!hinv_u) return FP4MR_ERR_NULL;
-    if (N > 65535 || K <= 0 || K % 64 != 0) return FP4MR_ERR_SHAPE;
+    if (N > (1 << 24) || K <= 0 || K % 64 != 0 || K > 24576) return FP4MR_ERR_SHAPE;
     if (!aligned16(hinv_u) || (perm && !aligned16(perm))) return FP4MR_ERR_ALIGN;
     const size_t need = fp4_workspace_bytes(FP4MR_OP_GPTQ, N, 0, K, fmt, flags);
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return FP4MR_ERR_WORKSPACE;

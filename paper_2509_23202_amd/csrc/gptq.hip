@@ -58,45 +58,30 @@ __global__ void gptq_iperm_kernel(GptqArgs a)
     if (j < a.K) a.iperm[visit_col(a, j)] = j;
 }
 
-// wp[n, j] = (W H_b)[n, perm[j]]: the rotated weight of the column visited j-th.  Sums of up to 128 bf16 values in fp32
-// (exact unless their exponents spread over more than 16 bits), then one multiplication by 1/sqrt(b) carried in two
-// floats.
-__global__ void gptq_rotate_gather_kernel(GptqArgs a)
+// wp[n, j] = (W H_b)[n, perm[j]]: the rotated weight of the column visited j-th.  One workgroup per row: the row is
+// copied to LDS and rotated there in natural column order (sums of up to 128 bf16 values in fp32 -- exact unless their exponents spread
+// over more than 16 bits -- then one multiplication by 1/sqrt(b) carried in two floats; neighbouring threads read the
+// same block, so the loads are broadcasts), and read back from LDS in visiting order for coalesced stores.
+__global__ __launch_bounds__(256) void gptq_rotate_gather_kernel(GptqArgs a)
 {
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    const int n = blockIdx.y;
-    if (j >= a.K) return;
-    const int col = visit_col(a, j);
-    const int j0 = col & ~(a.b - 1), c = col - j0;
-    const uint16_t* x = a.w + (int64_t)n * a.K + j0;
-    float sum = 0.0f;
-    for (int r = 0; r < a.b; ++r) {
-        const float v = __uint_as_float((uint32_t)x[r] << 16);
-        sum += (__popc((unsigned)(r & c)) & 1) ? -v : v;
+    extern __shared__ float rowbuf[];  // K floats (the rotated row), then K bf16 (the row as read)
+    uint16_t* const xs = reinterpret_cast<uint16_t*>(rowbuf + a.K);
+    const int n = blockIdx.x;
+    const uint32_t* x2 = reinterpret_cast<const uint32_t*>(a.w + (int64_t)n * a.K);
+    for (int i = threadIdx.x; i < a.K / 2; i += 256) reinterpret_cast<uint32_t*>(xs)[i] = x2[i];
+    __syncthreads();
+    for (int col = threadIdx.x; col < a.K; col += 256) {
+        const int j0 = col & ~(a.b - 1), c = col - j0;
+        float sum = 0.0f;
+#pragma unroll 8
+        for (int r = 0; r < a.b; ++r) {
+            const float v = __uint_as_float((uint32_t)xs[j0 + r] << 16);
+            sum += (__popc((unsigned)(r & c)) & 1) ? -v : v;
+        }
+        rowbuf[col] = (a.b == 1) ? sum : __fmaf_rn(sum, a.c_hi, sum * a.c_lo);
     }
-    a.wp[(int64_t)n * a.K + j] = (a.b == 1) ? sum : __fmaf_rn(sum, a.c_hi, sum * a.c_lo);
-}
-
-// nearest E2M1 code (ties to the even code, saturating), sign in bit 3
-__device__ __forceinline__ uint32_t e2m1_code(float t)
-{
-    const float m = fabsf(t);
-    uint32_t c = 0;
-    c += m > 0.25f;
-    c += m >= 0.75f;
-    c += m > 1.25f;
-    c += m >= 1.75f;
-    c += m > 2.5f;
-    c += m >= 3.5f;
-    c += m > 5.0f;
-    return c | ((__float_as_uint(t) >> 31) << 3);
-}
-
-__device__ __forceinline__ float e2m1_value(uint32_t code)
-{
-    const uint32_t m = code & 7u, e = m >> 1, man = m & 1u;
-    const float mag = (e == 0) ? 0.5f * (float)man : __uint_as_float((126u + e) << 23) * (1.0f + 0.5f * (float)man);
-    return (code & 8u) ? -mag : mag;
+    __syncthreads();
+    for (int j = threadIdx.x; j < a.K; j += 256) a.wp[(int64_t)n * a.K + j] = rowbuf[visit_col(a, j)];
 }
 
 template <int FMT>
@@ -123,23 +108,30 @@ __device__ __forceinline__ float quad_owner_value(float v)
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), ctrl, 0xf, 0xf, true));
 }
 
-template <int FMT, int P>
-__device__ __forceinline__ void sweep_part(float (&w)[16], const float* Us, const float* Ss, int row, int part, bool live,
-                                           float* erow, uint8_t* qrow)
+typedef float v2f_t __attribute__((ext_vector_type(2)));
+
+// Columns 16 P .. 16 P + 15 of the block.  The rounding uses the converting instructions (round-to-nearest-even onto
+// E2M1, saturating; decode back to fp32); the two divisions of the definition are multiplications by reciprocals
+// formed once per block (exact for power-of-two scales and a unit diagonal).  The owner lanes keep their errors and
+// codes in registers (ek, ck) and store them once at the end.
+template <int P>
+__device__ __forceinline__ void sweep_part(float (&w)[16], float (&ek)[16], uint32_t (&ck)[4], const float* Us, const float* Ru,
+                                           const v2f_t* Sc, int row, int part)
 {
+    const bool mine = part == P;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        constexpr int base = P * 16;
-        const int j = base + i;
-        const float s = Ss[j * 16 + row];
-        const float wj = w[i];  // meaningful in the lanes with part == P
-        const uint32_t code = (s > 0.0f) ? e2m1_code(wj / s) : 0u;
-        const float dq = e2m1_value(code) * s;
-        const float e_own = (wj - dq) / Us[j * kB + j];
-        if (live && part == P) {
-            erow[j] = e_own;
-            qrow[j] = (uint8_t)code;
-        }
+        const int j = P * 16 + i;
+        const v2f_t sc = Sc[j * 16 + row];  // scale, 1 / scale (0 for a zero scale)
+        const float wj = w[i];              // meaningful in the lanes with part == P
+        const float t = wj * sc[1];
+        const uint32_t pk = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, t, t, 1.0f, 0);
+        const uint32_t code = (sc[0] > 0.0f) ? (pk & 15u) : 0u;
+        const v2f_t qv = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(code, 1.0f, 0);
+        const float dq = qv[0] * sc[0];
+        const float e_own = (wj - dq) * Ru[j];
+        ek[i] = mine ? e_own : ek[i];
+        ck[i / 4] = mine ? (ck[i / 4] | (code << (8 * (i & 3)))) : ck[i / 4];
         const float e = quad_owner_value<P>(e_own);
         const float4* u4 = reinterpret_cast<const float4*>(Us + j * kB + part * 16);
 #pragma unroll
@@ -157,13 +149,18 @@ template <int FMT>
 __global__ __launch_bounds__(64) void gptq_block_kernel(GptqArgs a, int b0, int e0)
 {
     __shared__ __attribute__((aligned(16))) float Us[kB * kB];
-    __shared__ float Ss[kB * 16];  // [column][row of the wave]
+    __shared__ float Ru[kB];                                    // 1 / U[j,j]
+    __shared__ __attribute__((aligned(8))) v2f_t Sc[kB * 16];   // [column][row of the wave]: scale and its reciprocal
     __shared__ int cols[kB];
     const int lane = threadIdx.x;
-    for (int i = lane; i < kB * kB; i += 64) {
+    // (unrolled so that the loads are in flight together: rolled, every LDS store would wait for its own load)
+#pragma unroll 16
+    for (int it = 0; it < kB * kB / 64; ++it) {
+        const int i = it * 64 + lane;
         const int r = i / kB, c = i % kB;
         Us[i] = (c >= r) ? a.U[(int64_t)(b0 + r) * a.K + b0 + c] : 0.0f;
     }
+    Ru[lane] = 1.0f / a.U[(int64_t)(b0 + lane) * a.K + b0 + lane];
     cols[lane] = visit_col(a, b0 + lane);
     __syncthreads();
 
@@ -183,17 +180,31 @@ __global__ __launch_bounds__(64) void gptq_block_kernel(GptqArgs a, int b0, int 
         w[4 * v + 2] = t.z;
         w[4 * v + 3] = t.w;
     }
+    const int gshift = (a.G == 32) ? 5 : 4;
+    uint32_t sbyte[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sbyte[i] = srow[cols[part * 16 + i] >> gshift];  // sixteen independent loads in flight
+#pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int j = part * 16 + i;
-        Ss[j * 16 + row] = decode_scale<FMT>(srow[cols[j] / a.G], s_T, a.factor);
+        const float sv = decode_scale<FMT>(sbyte[i], s_T, a.factor);
+        Sc[j * 16 + row] = v2f_t{sv, sv > 0.0f ? 1.0f / sv : 0.0f};
     }
     __syncthreads();  // the scale of a column is read by every lane of its row's quad
-    float* const erow = a.err + (int64_t)n * kOuter + e0;
-    uint8_t* const qrow = a.q + (int64_t)n * a.K + b0;
-    sweep_part<FMT, 0>(w, Us, Ss, row, part, live, erow, qrow);
-    sweep_part<FMT, 1>(w, Us, Ss, row, part, live, erow, qrow);
-    sweep_part<FMT, 2>(w, Us, Ss, row, part, live, erow, qrow);
-    sweep_part<FMT, 3>(w, Us, Ss, row, part, live, erow, qrow);
+    float ek[16];
+    uint32_t ck[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) ek[i] = 0.0f;
+    sweep_part<0>(w, ek, ck, Us, Ru, Sc, row, part);
+    sweep_part<1>(w, ek, ck, Us, Ru, Sc, row, part);
+    sweep_part<2>(w, ek, ck, Us, Ru, Sc, row, part);
+    sweep_part<3>(w, ek, ck, Us, Ru, Sc, row, part);
+    if (live) {
+        float4* ed = reinterpret_cast<float4*>(a.err + (int64_t)n * kOuter + e0 + part * 16);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) ed[v] = make_float4(ek[4 * v], ek[4 * v + 1], ek[4 * v + 2], ek[4 * v + 3]);
+        *reinterpret_cast<uint4*>(a.q + (int64_t)n * a.K + b0 + part * 16) = make_uint4(ck[0], ck[1], ck[2], ck[3]);
+    }
 }
 
 // wp[n, c] -= sum_{j < rank} err[n, e0 + j] * U[u0 + j, c] for the columns c_begin <= c < c_end (visiting order), the
@@ -221,7 +232,9 @@ __global__ __launch_bounds__(256) void gptq_update_kernel(GptqArgs a, int u0, in
     }
     for (int r0 = 0; r0 < rank; r0 += KC) {
         __syncthreads();
-        for (int idx = tid; idx < KC * T; idx += 256) {
+#pragma unroll
+        for (int it = 0; it < KC * T / 256; ++it) {
+            const int idx = it * 256 + tid;
             const int x = idx % T, t = idx / T;
             const int n = min(n0 + x, a.N - 1);
             Et[t][x] = a.err[(int64_t)n * kOuter + e0 + r0 + t];
@@ -263,7 +276,9 @@ __global__ __launch_bounds__(256) void gptq_update_inner_kernel(GptqArgs a, int 
     const int c0 = c_begin + blockIdx.x * kB;
     const int n0 = blockIdx.y * kB;
     const int tid = threadIdx.x;
-    for (int i = tid; i < kB * kB; i += 256) {
+#pragma unroll
+    for (int it = 0; it < kB * kB / 256; ++it) {
+        const int i = it * 256 + tid;
         const int r = i / kB, c = i % kB;
         const int n = min(n0 + r, a.N - 1);
         Es[r][c] = a.err[(int64_t)n * kOuter + e0 + c];
@@ -302,14 +317,14 @@ __global__ __launch_bounds__(256) void gptq_update_inner_kernel(GptqArgs a, int 
 }
 
 // codes[n, kb] = code of column 2 kb | code of column 2 kb + 1 << 4, fetched from their visiting positions
-__global__ void gptq_pack_kernel(GptqArgs a)
+__global__ __launch_bounds__(256) void gptq_pack_kernel(GptqArgs a)
 {
-    const int kb = blockIdx.x * blockDim.x + threadIdx.x;
-    const int n = blockIdx.y;
-    if (kb >= a.K / 2) return;
+    const int n = blockIdx.x;
     const uint8_t* qr = a.q + (int64_t)n * a.K;
-    const uint32_t lo = qr[a.iperm[2 * kb]] & 15u, hi = qr[a.iperm[2 * kb + 1]] & 15u;
-    a.codes[(int64_t)n * (a.K / 2) + kb] = (uint8_t)(lo | (hi << 4));
+    for (int kb = threadIdx.x; kb < a.K / 2; kb += 256) {
+        const uint32_t lo = qr[a.iperm[2 * kb]] & 15u, hi = qr[a.iperm[2 * kb + 1]] & 15u;
+        a.codes[(int64_t)n * (a.K / 2) + kb] = (uint8_t)(lo | (hi << 4));
+    }
 }
 
 inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
@@ -347,12 +362,18 @@ hipError_t launch_gptq_sweep(const void* w, int64_t N, int64_t K, int b, int fmt
     a.c_hi = (float)c;
     a.c_lo = (float)(c - (double)a.c_hi);
     a.factor = factor;
-    if (K % kB != 0 || N <= 0) return hipErrorInvalidValue;
+    if (K % kB != 0 || N <= 0 || K > 24576) return hipErrorInvalidValue;  // (a row is staged in LDS twice, as read and rotated: 6 K bytes)
 
     const unsigned kblocks = (unsigned)((K + 255) / 256);
     hipLaunchKernelGGL(gptq_iperm_fill_kernel, dim3(kblocks), dim3(256), 0, st, a);
     hipLaunchKernelGGL(gptq_iperm_kernel, dim3(kblocks), dim3(256), 0, st, a);
-    hipLaunchKernelGGL(gptq_rotate_gather_kernel, dim3(kblocks, (unsigned)N), dim3(256), 0, st, a);
+    const size_t row_lds = (size_t)K * 6;
+    if (row_lds > 48 * 1024) {
+        const hipError_t le = hipFuncSetAttribute(reinterpret_cast<const void*>(gptq_rotate_gather_kernel),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)row_lds);
+        if (le != hipSuccess) return le;
+    }
+    hipLaunchKernelGGL(gptq_rotate_gather_kernel, dim3((unsigned)N), dim3(256), row_lds, st, a);
     const unsigned row128 = (unsigned)((N + 127) / 128), row16 = (unsigned)((N + 15) / 16);
     auto update = [&](int u0, int e0, int rank, int c_begin, int c_end) {
         const unsigned tiles = (unsigned)((c_end - c_begin + 127) / 128);
@@ -371,7 +392,7 @@ hipError_t launch_gptq_sweep(const void* w, int64_t N, int64_t K, int b, int fmt
         // ... everything behind the outer block sees all of its errors in one pass
         if (oe < (int)K) update(o, 0, oe - o, oe, (int)K);
     }
-    hipLaunchKernelGGL(gptq_pack_kernel, dim3((unsigned)((K / 2 + 255) / 256), (unsigned)N), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(gptq_pack_kernel, dim3((unsigned)N), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 

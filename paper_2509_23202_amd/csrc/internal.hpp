@@ -38,7 +38,7 @@ hipError_t launch_fused_decode(const void* x, int64_t M, int64_t K, int b, const
                                int64_t N, void* out, bool out_f32, bool weight_only, float alpha, hipStream_t st);
 
 // MR-GPTQ sweep over fixed scales (canonical layout) with the factor U of the damped inverse Hessian in visiting order;
-// workspace of gptq_workspace_bytes(N, K) bytes; K % 64 == 0, N <= 65535
+// workspace of gptq_workspace_bytes(N, K) bytes; K % 64 == 0, K <= 24576
 size_t gptq_workspace_bytes(int64_t N, int64_t K);
 hipError_t launch_gptq_sweep(const void* w, int64_t N, int64_t K, int b, int fmt, const float* U, const int* perm,
                              const void* scales, const float* s_T, float factor, void* codes, void* workspace, hipStream_t st);

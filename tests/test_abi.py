@@ -94,7 +94,7 @@ def test_argument_validation_happens_before_any_launch(lib):
     gq = lambda **kw: L.fp4_gptq_quantize_weights(fake, kw.get("N", 16), kw.get("K", 128), 32, kw.get("fmt", 0), kw.get("U", fake),
                                                   kw.get("perm", None), fake, fake, None, kw.get("ws", fake), kw.get("wsz", 1 << 30),
                                                   kw.get("flags", 0), None)
-    assert gq(U=None) == 1 and gq(K=96) == 2 and gq(N=70000) == 2 and gq(flags=b.LAYOUT_GEMM) == 4
+    assert gq(U=None) == 1 and gq(K=96) == 2 and gq(K=65536) == 2 and gq(flags=b.LAYOUT_GEMM) == 4
     assert gq(U=fake + 4) == 5 and gq(perm=fake + 4) == 5 and gq(ws=None) == 6 and gq(wsz=1024) == 6
     assert b.workspace_bytes(b.OP_GPTQ, 128, 0, 256, b.MXFP4) >= 128 * 256 * 5 + 128 * 64 * 4 + 256 * 4
     assert L.fp4_status_string(2).decode().startswith("bad shape")
