@@ -72,7 +72,7 @@ enum {
 };
 
 /* operation selector for fp4_workspace_bytes */
-enum { FP4MR_OP_ROTATE_QUANTIZE = 0, FP4MR_OP_QUANTIZE_WEIGHTS = 1, FP4MR_OP_GEMM = 2, FP4MR_OP_GPTQ = 3 };
+enum { FP4MR_OP_ROTATE_QUANTIZE = 0, FP4MR_OP_QUANTIZE_WEIGHTS = 1, FP4MR_OP_GEMM = 2, FP4MR_OP_GPTQ = 3, FP4MR_OP_GPTQ_PREPARE = 4 };
 
 /*
  * Online rotation + quantization of activations: codes, scales = Q(X H_b)   (Section 4.2 item 1: rotation
@@ -173,8 +173,8 @@ fp4mr_status_t fp4_w4a16_linear(const void* x, int64_t M, int64_t K, int had_blo
  * fixed column order, each rounded column's error is pushed onto the columns still to come by the optimal-brain update;
  * Section 4.1: on the rotated weights W H_b, with the scales fixed beforehand in the original column order -- abs-max,
  * or FP4MR_SCALE_MSE / FP4MR_SCALE_ROUND43 -- and the columns visited in a static activation order).  Accumulating
- * the Hessian of the rotated calibration inputs, ordering, dampening, inverting and factoring it are dense
- * linear-algebra steps left to the caller, who passes their result:
+ * the Hessian of the rotated calibration inputs is the caller's; fp4_gptq_prepare (below) turns a Hessian into the two
+ * inputs taken here:
  *   w            [N,K] bf16 row-major, K % 64 == 0, K % lcm(b, G) == 0, K <= 24576
  *   had_block    b in {1,16,32,64,128}
  *   hinv_u       [K,K] fp32 row-major, device: upper-triangular U with U^T U = (H[perm][:,perm] + lambda I)^-1, rows and
@@ -192,6 +192,22 @@ fp4mr_status_t fp4_gptq_quantize_weights(const void* w, int64_t N, int64_t K, in
                                          const float* hinv_u, const int32_t* perm, void* codes_out, void* scales_out,
                                          float* tensor_scale, void* workspace, size_t workspace_bytes, uint32_t flags,
                                          void* stream);
+
+/*
+ * From a layer's Hessian to the two inputs of fp4_gptq_quantize_weights (Section 4 "Standard GPTQ"; Section 4.1
+ * "Ingredient 2": static activation order; Section 5 "Algorithms": dampening 1e-2):
+ *   perm_out    [K] int32, device: columns by descending Hessian diagonal, equal entries in ascending index order
+ *               (the identity when act_order == 0)
+ *   hinv_u_out  [K,K] fp32 row-major, device: upper-triangular U with U^T U = (H[perm][:,perm] + damp mean(diag H) I)^-1,
+ *               zero below the diagonal.  Computed in fp32 as the inverse of the upper factor R of A = R R^T (blocked
+ *               Cholesky of the index-reversed matrix, triangular inversion by recursive doubling); no inverse of A is formed.
+ *   hessian     [K,K] fp32 row-major, device, symmetric positive semi-definite: X'^T X' of the ROTATED calibration inputs
+ *               (only read); K <= 24576; damp > 0 makes the dampened matrix positive definite
+ *   workspace   fp4_workspace_bytes(FP4MR_OP_GPTQ_PREPARE, 0, 0, K, fmt ignored, 0) bytes (about 2.5 K^2 floats)
+ * A Hessian that is not positive definite after dampening yields NaNs in hinv_u_out (no fault).
+ */
+fp4mr_status_t fp4_gptq_prepare(const float* hessian, int64_t K, float damp, int act_order, int32_t* perm_out, float* hinv_u_out,
+                                void* workspace, size_t workspace_bytes, void* stream);
 
 /* Bytes of device scratch the given operation needs (0 = none).  rows = M for the quantize ops. */
 size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t fmt, uint32_t flags);

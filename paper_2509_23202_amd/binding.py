@@ -30,7 +30,7 @@ SCALE_MSE = 1 << 6
 SCALE_ROUND43 = 1 << 7
 A_SCALE43 = 1 << 8
 W_SCALE43 = 1 << 9
-OP_ROTATE_QUANTIZE, OP_QUANTIZE_WEIGHTS, OP_GEMM, OP_GPTQ = 0, 1, 2, 3
+OP_ROTATE_QUANTIZE, OP_QUANTIZE_WEIGHTS, OP_GEMM, OP_GPTQ, OP_GPTQ_PREPARE = 0, 1, 2, 3, 4
 
 _p, _i64, _i32, _u32, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32, ctypes.c_size_t
 _quant_sig = [_p, _i64, _i64, _i32, _i32, _p, _p, _p, _p, _sz, _u32, _p]
@@ -46,6 +46,8 @@ lib.fp4_w4a16_linear.argtypes = lib.fp4_fused_linear.argtypes
 lib.fp4_w4a16_linear.restype = _i32
 lib.fp4_gptq_quantize_weights.argtypes = [_p, _i64, _i64, _i32, _i32, _p, _p, _p, _p, _p, _p, _sz, _u32, _p]
 lib.fp4_gptq_quantize_weights.restype = _i32
+lib.fp4_gptq_prepare.argtypes = [_p, _i64, ctypes.c_float, _i32, _p, _p, _p, _sz, _p]
+lib.fp4_gptq_prepare.restype = _i32
 lib.fp4_gemm.argtypes = [_p, _p, _p, _p, _p, _p, _i64, _i64, _i64, _i32, _p, _p, _sz, _u32, _p]
 lib.fp4_gemm.restype = _i32
 lib.fp4_workspace_bytes.argtypes = [_i32, _i64, _i64, _i64, _i32, _u32]
@@ -137,6 +139,21 @@ def fp4_quantize_weights(w, had_block: int, fmt: int, *, flags: int = 0, tensor_
                          workspace=None):
     """Offline RTN weight preparation, codes, scales, tensor_scale = Q(W H_b).  w: [N,K] bf16 cuda tensor."""
     return _quantize(lib.fp4_quantize_weights, OP_QUANTIZE_WEIGHTS, w, had_block, fmt, flags, tensor_scale, codes, scales, workspace)
+
+
+def fp4_gptq_prepare(hessian, damp: float = 1e-2, act_order: bool = True, *, workspace=None):
+    """Hessian fp32 [K,K] -> (perm int32 [K], hinv_u fp32 [K,K]) for fp4_gptq_quantize_weights."""
+    assert hessian.is_cuda and hessian.dtype == torch.float32 and hessian.is_contiguous() and hessian.dim() == 2
+    K = hessian.shape[0]
+    assert hessian.shape[1] == K
+    perm = torch.empty(K, dtype=torch.int32, device=hessian.device)
+    U = torch.empty((K, K), dtype=torch.float32, device=hessian.device)
+    need = workspace_bytes(OP_GPTQ_PREPARE, 0, 0, K, MXFP4, 0)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=hessian.device)
+    _check(lib.fp4_gptq_prepare(hessian.data_ptr(), K, float(damp), 1 if act_order else 0, perm.data_ptr(), U.data_ptr(),
+                                workspace.data_ptr(), workspace.numel(), _stream()))
+    return perm, U
 
 
 def fp4_gptq_quantize_weights(w, had_block: int, fmt: int, hinv_u, perm=None, *, flags: int = 0, workspace=None):

@@ -199,6 +199,19 @@ fp4mr_status_t fp4_gptq_quantize_weights(const void* w, int64_t N, int64_t K, in
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
 }
 
+fp4mr_status_t fp4_gptq_prepare(const float* hessian, int64_t K, float damp, int act_order, int32_t* perm_out, float* hinv_u_out,
+                                void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!hessian || !perm_out || !hinv_u_out) return FP4MR_ERR_NULL;
+    if (K <= 0 || K > 24576 || !(damp >= 0.0f)) return FP4MR_ERR_SHAPE;
+    if (!aligned16(hessian) || !aligned16(perm_out) || !aligned16(hinv_u_out)) return FP4MR_ERR_ALIGN;
+    const size_t need = gptq_prepare_workspace_bytes(K);
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return FP4MR_ERR_WORKSPACE;
+    const hipError_t e = launch_gptq_prepare(hessian, K, damp, act_order != 0, reinterpret_cast<int*>(perm_out), hinv_u_out, workspace,
+                                             static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
+}
+
 fp4mr_status_t fp4_fused_linear(const void* x, int64_t M, int64_t K, int had_block, const void* w_codes, const void* w_scales,
                                 int64_t N, fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream)
 {
@@ -215,6 +228,7 @@ size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t 
 {
     if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return 0;
     if (op == FP4MR_OP_ROTATE_QUANTIZE || op == FP4MR_OP_QUANTIZE_WEIGHTS) return quant_workspace(fmt, flags);
+    if (op == FP4MR_OP_GPTQ_PREPARE) return K > 0 ? gptq_prepare_workspace_bytes(K) : 0;
     if (op == FP4MR_OP_GPTQ) return (M > 0 && K > 0) ? align256(quant_workspace(fmt, flags)) + gptq_workspace_bytes(M, K) : 0;
     if (op == FP4MR_OP_GEMM) {
         if (M <= 0 || N <= 0 || K <= 0 || K % 128 != 0) return 0;

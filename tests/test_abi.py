@@ -26,7 +26,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert {"fp4_rotate_quantize", "fp4_rotate_quantize_dense", "fp4_fused_linear", "fp4_w4a16_linear", "fp4_quantize_weights", "fp4_gptq_quantize_weights", "fp4_gemm", "fp4_workspace_bytes",
+    assert {"fp4_rotate_quantize", "fp4_rotate_quantize_dense", "fp4_fused_linear", "fp4_w4a16_linear", "fp4_quantize_weights", "fp4_gptq_quantize_weights", "fp4_gptq_prepare", "fp4_gemm", "fp4_workspace_bytes",
             "fp4_packed_bytes", "fp4_status_string", "fp4_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -96,6 +96,13 @@ def test_argument_validation_happens_before_any_launch(lib):
                                                   kw.get("flags", 0), None)
     assert gq(U=None) == 1 and gq(K=96) == 2 and gq(K=65536) == 2 and gq(flags=b.LAYOUT_GEMM) == 4
     assert gq(U=fake + 4) == 5 and gq(perm=fake + 4) == 5 and gq(ws=None) == 6 and gq(wsz=1024) == 6
+    L.fp4_gptq_prepare.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_float, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                   ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    gp = lambda **kw: L.fp4_gptq_prepare(kw.get("H", fake), kw.get("K", 128), kw.get("damp", 0.01), 1, kw.get("perm", fake), kw.get("U", fake),
+                                         kw.get("ws", fake), kw.get("wsz", 1 << 30), None)
+    assert gp(H=None) == 1 and gp(perm=None) == 1 and gp(K=0) == 2 and gp(K=30000) == 2 and gp(damp=-1.0) == 2
+    assert gp(U=fake + 8) == 5 and gp(ws=None) == 6 and gp(wsz=4096) == 6
+    assert b.workspace_bytes(b.OP_GPTQ_PREPARE, 0, 0, 256, b.MXFP4) >= 256 * 256 * 10
     assert b.workspace_bytes(b.OP_GPTQ, 128, 0, 256, b.MXFP4) >= 128 * 256 * 5 + 128 * 64 * 4 + 256 * 4
     assert L.fp4_status_string(2).decode().startswith("bad shape")
     for s in range(8):

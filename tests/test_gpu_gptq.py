@@ -132,3 +132,82 @@ def test_gptq_argument_validation(fp4):
         fp4.fp4_gptq_quantize_weights(w96, 32, MX, U96, None)
     with pytest.raises(Exception):
         fp4.fp4_gptq_quantize_weights(w, 32, MX, U, None, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+
+
+def synthetic_hessian(oracle, K, T, b, salt):
+    xb = inputs.RECIPES[6].x(T, K, salt=salt)
+    X = oracle.rotate(xb, b).astype(np.float64)
+    return X.T @ X
+
+
+@pytest.mark.parametrize("K", [64, 200, 320, 512, 1088])
+def test_prepare_matches_the_oracle_order_and_factor(fp4, oracle, gptq, K):
+    """Order: the same permutation as a stable descending sort of the diagonal.  Factor: fp32 blocked Cholesky and
+    triangular inversion against NumPy in fp64 -- compared as matrices and through the identity U^T U A = I that
+    defines it.  K = 200 and 320 have a ragged last block / an odd number of blocks (the doubling levels' tails)."""
+    import torch
+    b = 8 if K == 200 else 32
+    H = synthetic_hessian(oracle, K, 2 * K + 100, b, salt=50 + K)
+    H32 = H.astype(np.float32)
+    say(f"gptq prepare K={K}")
+    perm, U = fp4.fp4_gptq_prepare(to_dev(H32), 1e-2, True)
+    torch.cuda.synchronize()
+    perm, U = np_(perm), np_(U).astype(np.float64)
+    want_perm = gptq.act_order(H32.astype(np.float64))
+    assert np.array_equal(perm, want_perm)
+    want_U = gptq.inverse_factor(H32.astype(np.float64), want_perm, damp=1e-2)
+    assert np.all(np.tril(U, -1) == 0)
+    rel = np.linalg.norm(U - want_U) / np.linalg.norm(want_U)
+    A = H32.astype(np.float64)[np.ix_(want_perm, want_perm)]
+    A[np.diag_indices(K)] += 1e-2 * np.mean(np.diag(A))
+    resid = np.abs(U.T @ U @ A - np.eye(K)).max()
+    say(f"   relative error of U {rel:.2e}; max |U^T U A - I| {resid:.2e}")
+    assert rel <= 5e-4 and resid <= 2e-3
+    # no re-ordering on request
+    perm0, U0 = fp4.fp4_gptq_prepare(to_dev(H32), 1e-2, False)
+    torch.cuda.synchronize()
+    assert np.array_equal(np_(perm0), np.arange(K))
+    want_U0 = gptq.inverse_factor(H32.astype(np.float64), np.arange(K), damp=1e-2)
+    assert np.linalg.norm(np_(U0) - want_U0) / np.linalg.norm(want_U0) <= 5e-4
+
+
+def test_prepare_orders_equal_diagonal_entries_by_index(fp4, gptq):
+    import torch
+    K = 128
+    d = np.repeat(np.array([3.0, 1.0, 2.0, 3.0], dtype=np.float32), K // 4)
+    H = np.diag(d).astype(np.float32)
+    perm, U = fp4.fp4_gptq_prepare(to_dev(H), 1e-2, True)
+    torch.cuda.synchronize()
+    assert np.array_equal(np_(perm), gptq.act_order(H.astype(np.float64)))
+    lam = 1e-2 * d.mean()
+    assert np.allclose(np.diag(np_(U)), 1.0 / np.sqrt(d[np_(perm)] + lam), rtol=1e-6)
+
+
+@pytest.mark.parametrize("fmt,policy", [(MX, "mse"), (NV, "absmax")])
+def test_hessian_to_codes_entirely_on_the_gpu(fp4, oracle, gptq, fmt, policy):
+    """H -> fp4_gptq_prepare -> fp4_gptq_quantize_weights against the oracle's whole quantizer (fp64 factor): same
+    order, layer error within 1% of the oracle's and far below round-to-nearest."""
+    import torch
+    N, K, b = 96, 768, 32
+    wb = inputs.RECIPES[6].w(N, K, salt=70)
+    H = synthetic_hessian(oracle, K, 2048, b, salt=71).astype(np.float32)
+    say(f"gptq whole path fmt={fmt} policy={policy}")
+    perm, U = fp4.fp4_gptq_prepare(to_dev(H), 1e-2, True)
+    flags = {"absmax": 0, "mse": fp4.SCALE_MSE}[policy]
+    c, s, T = fp4.fp4_gptq_quantize_weights(to_dev_bf16(wb), b, fmt, U, perm, flags=flags)
+    torch.cuda.synchronize()
+    H64 = H.astype(np.float64)
+    want_c, want_s, sT, want_perm, _ = gptq.mr_gptq(wb, H64, b, fmt, policy=policy)
+    assert np.array_equal(np_(perm), want_perm)
+    got_c, got_s = np_(c).reshape(N, -1), np_(s).reshape(N, -1)
+    ok = (got_s == want_s).all(axis=1)
+    assert ok.mean() >= 0.98
+    y = oracle.rotate(wb, b)
+    c_rtn, _, _ = oracle.quantize(y, fmt, policy=policy)
+    e_got = gptq.layer_error(y[ok], got_c[ok], want_s[ok], fmt, sT, H64)
+    e_ref = gptq.layer_error(y[ok], want_c[ok], want_s[ok], fmt, sT, H64)
+    e_rtn = gptq.layer_error(y[ok], c_rtn[ok], want_s[ok], fmt, sT, H64)
+    diff = (unpack(got_c) != unpack(want_c))[ok].mean()
+    say(f"   codes differing from the oracle: {diff:.2e}; layer error {e_got:.5e} vs oracle {e_ref:.5e} (round-to-nearest {e_rtn:.3e})")
+    assert abs(e_got - e_ref) <= 1e-2 * e_ref
+    assert e_got < 0.8 * e_rtn
