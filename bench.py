@@ -340,9 +340,16 @@ def main():
             # factor is a random upper-triangular matrix with a positive diagonal (timing does not depend on its values)
             Ng, Kg = 4096, 4096
             wg = (torch.randn(Ng, Kg, device="cuda") * 0.02).to(torch.bfloat16)
-            xg = torch.randn(2 * Kg, Kg, device="cuda") * (1.0 + 9.0 * (torch.rand(Kg, device="cuda") < 0.01))   # a few loud channels
-            Hg = (xg.t() @ xg).contiguous()            # synthetic Hessian of 8192 calibration rows (input generation only)
-            del xg
+            xg = (torch.randn(2 * Kg, Kg, device="cuda") * (1.0 + 9.0 * (torch.rand(Kg, device="cuda") < 0.01))).to(torch.bfloat16)  # a few loud channels
+            wsh = torch.empty(fp4.workspace_bytes(fp4.OP_GPTQ_HESSIAN, 2 * Kg, 0, Kg, fp4.MXFP4, 0), dtype=torch.uint8, device="cuda")
+            Hg = fp4.fp4_gptq_accumulate_hessian(xg, b, workspace=wsh)     # Hessian of 8192 synthetic calibration rows
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fp4.fp4_gptq_accumulate_hessian(xg, b, Hg, workspace=wsh)
+            torch.cuda.synchronize()
+            th = time.perf_counter() - t0
+            Hg = fp4.fp4_gptq_accumulate_hessian(xg, b, workspace=wsh)
+            del xg, wsh
             wsp = torch.empty(fp4.workspace_bytes(fp4.OP_GPTQ_PREPARE, 0, 0, Kg, fp4.MXFP4, 0), dtype=torch.uint8, device="cuda")
             pg, Ug = fp4.fp4_gptq_prepare(Hg, 1e-2, True, workspace=wsp)
             torch.cuda.synchronize()
@@ -365,7 +372,8 @@ def main():
             result["gptq_offline"] = {"workload": f"W [{Ng}, {Kg}] bf16, MXFP4, Hadamard block {b}, Hessian of 8192 synthetic rows, act-order",
                                       "sweep_ms": round(tg * 1e3, 3), "bound": "alu", "achieved": round(fl / tg / 1e12, 2),
                                       "peak": 157.3, "unit": "TFLOP/s", "frac": round(fl / tg / 1e12 / 157.3, 4),
-                                      "prepare_ms": round(tp * 1e3, 3), "prepare_tflops": round(flp / tp / 1e12, 2)}
+                                      "prepare_ms": round(tp * 1e3, 3), "prepare_tflops": round(flp / tp / 1e12, 2),
+                                      "hessian_ms": round(th * 1e3, 3), "hessian_tflops": round(2.0 * 2 * Kg * Kg * Kg / th / 1e12, 2)}
             del wg, Ug, pg, wsg, Hg
         except Exception as exc:  # noqa: BLE001 - reported in the JSON line
             extras_errors["gptq_offline"] = repr(exc)

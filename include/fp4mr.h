@@ -72,7 +72,7 @@ enum {
 };
 
 /* operation selector for fp4_workspace_bytes */
-enum { FP4MR_OP_ROTATE_QUANTIZE = 0, FP4MR_OP_QUANTIZE_WEIGHTS = 1, FP4MR_OP_GEMM = 2, FP4MR_OP_GPTQ = 3, FP4MR_OP_GPTQ_PREPARE = 4 };
+enum { FP4MR_OP_ROTATE_QUANTIZE = 0, FP4MR_OP_QUANTIZE_WEIGHTS = 1, FP4MR_OP_GEMM = 2, FP4MR_OP_GPTQ = 3, FP4MR_OP_GPTQ_PREPARE = 4, FP4MR_OP_GPTQ_HESSIAN = 5 };
 
 /*
  * Online rotation + quantization of activations: codes, scales = Q(X H_b)   (Section 4.2 item 1: rotation
@@ -173,8 +173,8 @@ fp4mr_status_t fp4_w4a16_linear(const void* x, int64_t M, int64_t K, int had_blo
  * fixed column order, each rounded column's error is pushed onto the columns still to come by the optimal-brain update;
  * Section 4.1: on the rotated weights W H_b, with the scales fixed beforehand in the original column order -- abs-max,
  * or FP4MR_SCALE_MSE / FP4MR_SCALE_ROUND43 -- and the columns visited in a static activation order).  Accumulating
- * the Hessian of the rotated calibration inputs is the caller's; fp4_gptq_prepare (below) turns a Hessian into the two
- * inputs taken here:
+ * the Hessian of the rotated calibration inputs comes from fp4_gptq_accumulate_hessian, and fp4_gptq_prepare turns it
+ * into the two inputs taken here (both below):
  *   w            [N,K] bf16 row-major, K % 64 == 0, K % lcm(b, G) == 0, K <= 24576
  *   had_block    b in {1,16,32,64,128}
  *   hinv_u       [K,K] fp32 row-major, device: upper-triangular U with U^T U = (H[perm][:,perm] + lambda I)^-1, rows and
@@ -192,6 +192,16 @@ fp4mr_status_t fp4_gptq_quantize_weights(const void* w, int64_t N, int64_t K, in
                                          const float* hinv_u, const int32_t* perm, void* codes_out, void* scales_out,
                                          float* tensor_scale, void* workspace, size_t workspace_bytes, uint32_t flags,
                                          void* stream);
+
+/*
+ * Hessian of a layer from calibration inputs (Section 4 "Standard GPTQ": the second-order information of
+ * ||X What - X W||^2 is X^T X; Section 4.1 "Ingredient 3": of the ROTATED inputs):  H (+)= (X H_b)^T (X H_b), fp32.
+ *   x          [T,K] bf16 row-major, device (T calibration rows; rows = M in fp4_workspace_bytes), K <= 24576
+ *   hessian    [K,K] fp32 row-major, device; overwritten, or added to when accumulate != 0 (batches of rows)
+ *   workspace  fp4_workspace_bytes(FP4MR_OP_GPTQ_HESSIAN, T, 0, K, fmt ignored, 0) = 4 T K bytes
+ */
+fp4mr_status_t fp4_gptq_accumulate_hessian(const void* x, int64_t T, int64_t K, int had_block, float* hessian, int accumulate,
+                                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * From a layer's Hessian to the two inputs of fp4_gptq_quantize_weights (Section 4 "Standard GPTQ"; Section 4.1

@@ -30,7 +30,7 @@ SCALE_MSE = 1 << 6
 SCALE_ROUND43 = 1 << 7
 A_SCALE43 = 1 << 8
 W_SCALE43 = 1 << 9
-OP_ROTATE_QUANTIZE, OP_QUANTIZE_WEIGHTS, OP_GEMM, OP_GPTQ, OP_GPTQ_PREPARE = 0, 1, 2, 3, 4
+OP_ROTATE_QUANTIZE, OP_QUANTIZE_WEIGHTS, OP_GEMM, OP_GPTQ, OP_GPTQ_PREPARE, OP_GPTQ_HESSIAN = 0, 1, 2, 3, 4, 5
 
 _p, _i64, _i32, _u32, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32, ctypes.c_size_t
 _quant_sig = [_p, _i64, _i64, _i32, _i32, _p, _p, _p, _p, _sz, _u32, _p]
@@ -46,6 +46,8 @@ lib.fp4_w4a16_linear.argtypes = lib.fp4_fused_linear.argtypes
 lib.fp4_w4a16_linear.restype = _i32
 lib.fp4_gptq_quantize_weights.argtypes = [_p, _i64, _i64, _i32, _i32, _p, _p, _p, _p, _p, _p, _sz, _u32, _p]
 lib.fp4_gptq_quantize_weights.restype = _i32
+lib.fp4_gptq_accumulate_hessian.argtypes = [_p, _i64, _i64, _i32, _p, _i32, _p, _sz, _p]
+lib.fp4_gptq_accumulate_hessian.restype = _i32
 lib.fp4_gptq_prepare.argtypes = [_p, _i64, ctypes.c_float, _i32, _p, _p, _p, _sz, _p]
 lib.fp4_gptq_prepare.restype = _i32
 lib.fp4_gemm.argtypes = [_p, _p, _p, _p, _p, _p, _i64, _i64, _i64, _i32, _p, _p, _sz, _u32, _p]
@@ -139,6 +141,22 @@ def fp4_quantize_weights(w, had_block: int, fmt: int, *, flags: int = 0, tensor_
                          workspace=None):
     """Offline RTN weight preparation, codes, scales, tensor_scale = Q(W H_b).  w: [N,K] bf16 cuda tensor."""
     return _quantize(lib.fp4_quantize_weights, OP_QUANTIZE_WEIGHTS, w, had_block, fmt, flags, tensor_scale, codes, scales, workspace)
+
+
+def fp4_gptq_accumulate_hessian(x, had_block: int, hessian=None, *, workspace=None):
+    """H (+)= (x H_b)^T (x H_b): x bf16 [T,K]; hessian fp32 [K,K] to add to, or None for a fresh one.  Returns hessian."""
+    assert x.is_cuda and x.dim() == 2 and x.is_contiguous() and x.dtype == torch.bfloat16
+    T, K = x.shape
+    acc = hessian is not None
+    if not acc:
+        hessian = torch.empty((K, K), dtype=torch.float32, device=x.device)
+    assert hessian.is_cuda and hessian.dtype == torch.float32 and hessian.is_contiguous() and tuple(hessian.shape) == (K, K)
+    need = workspace_bytes(OP_GPTQ_HESSIAN, T, 0, K, MXFP4, 0)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    _check(lib.fp4_gptq_accumulate_hessian(x.data_ptr(), T, K, had_block, hessian.data_ptr(), 1 if acc else 0,
+                                           workspace.data_ptr(), workspace.numel(), _stream()))
+    return hessian
 
 
 def fp4_gptq_prepare(hessian, damp: float = 1e-2, act_order: bool = True, *, workspace=None):

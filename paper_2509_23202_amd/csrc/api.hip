@@ -199,6 +199,21 @@ fp4mr_status_t fp4_gptq_quantize_weights(const void* w, int64_t N, int64_t K, in
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
 }
 
+fp4mr_status_t fp4_gptq_accumulate_hessian(const void* x, int64_t T, int64_t K, int had_block, float* hessian, int accumulate,
+                                           void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !hessian) return FP4MR_ERR_NULL;
+    if (had_block != 1 && had_block != 16 && had_block != 32 && had_block != 64 && had_block != 128) return FP4MR_ERR_HAD_BLOCK;
+    if (T <= 0 || T > (1 << 24) || K <= 0 || K > 24576 || K % had_block != 0 || K % 2 != 0) return FP4MR_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(hessian)) return FP4MR_ERR_ALIGN;
+    const size_t need = align256((size_t)T * K * 4);
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return FP4MR_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float* xr = static_cast<float*>(workspace);
+    if (launch_gptq_rotate_rows(x, T, K, had_block, xr, st) != hipSuccess) return FP4MR_ERR_DEVICE;
+    return launch_gptq_hessian_product(xr, T, K, hessian, accumulate != 0, st) == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
+}
+
 fp4mr_status_t fp4_gptq_prepare(const float* hessian, int64_t K, float damp, int act_order, int32_t* perm_out, float* hinv_u_out,
                                 void* workspace, size_t workspace_bytes, void* stream)
 {
@@ -228,6 +243,7 @@ size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t 
 {
     if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return 0;
     if (op == FP4MR_OP_ROTATE_QUANTIZE || op == FP4MR_OP_QUANTIZE_WEIGHTS) return quant_workspace(fmt, flags);
+    if (op == FP4MR_OP_GPTQ_HESSIAN) return (M > 0 && K > 0) ? align256((size_t)M * K * 4) : 0;
     if (op == FP4MR_OP_GPTQ_PREPARE) return K > 0 ? gptq_prepare_workspace_bytes(K) : 0;
     if (op == FP4MR_OP_GPTQ) return (M > 0 && K > 0) ? align256(quant_workspace(fmt, flags)) + gptq_workspace_bytes(M, K) : 0;
     if (op == FP4MR_OP_GEMM) {

@@ -336,6 +336,30 @@ size_t gptq_workspace_bytes(int64_t N, int64_t K)
     return align256((size_t)N * K * 4) + align256((size_t)N * K) + align256((size_t)N * kOuter * 4) + align256((size_t)K * 4);
 }
 
+// out[t, :] = x[t, :] H_b in fp32, natural column order (the calibration rows a Hessian is accumulated from)
+hipError_t launch_gptq_rotate_rows(const void* x, int64_t T, int64_t K, int b, float* out, hipStream_t st)
+{
+    GptqArgs a{};
+    a.w = static_cast<const uint16_t*>(x);
+    a.perm = nullptr;
+    a.wp = out;
+    a.N = (int)T;
+    a.K = (int)K;
+    a.b = b;
+    const double c = 1.0 / sqrt((double)b);
+    a.c_hi = (float)c;
+    a.c_lo = (float)(c - (double)a.c_hi);
+    if (K <= 0 || T <= 0 || K > 24576) return hipErrorInvalidValue;
+    const size_t row_lds = (size_t)K * 6;
+    if (row_lds > 48 * 1024) {
+        const hipError_t le = hipFuncSetAttribute(reinterpret_cast<const void*>(gptq_rotate_gather_kernel),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)row_lds);
+        if (le != hipSuccess) return le;
+    }
+    hipLaunchKernelGGL(gptq_rotate_gather_kernel, dim3((unsigned)T), dim3(256), row_lds, st, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_gptq_sweep(const void* w, int64_t N, int64_t K, int b, int fmt, const float* U, const int* perm,
                              const void* scales, const float* s_T, float factor, void* codes, void* workspace, hipStream_t st)
 {

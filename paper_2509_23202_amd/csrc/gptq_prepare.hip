@@ -142,7 +142,8 @@ __global__ __launch_bounds__(64) void diag_block_kernel(float* A, float* V, floa
 }
 
 // ---------------------------------------------------------------- plain fp32 product
-// C[m x n] = beta C + alpha A[m x k] op(B),  op(B) = B[k x n] or B^T with B stored [n x k]; row-major with leading
+// C[m x n] = beta C + alpha op(A) op(B),  op(A) = A[m x k] or A^T with A stored [k x m], op(B) = B[k x n] or B^T with
+// B stored [n x k]; row-major with leading
 // dimensions; 64 x 64 tile per workgroup, 4 x 4 per thread, k in chunks of 16 through LDS; results are written after
 // all inputs of the tile have been read (a tile may overwrite its own A rows when n fits one tile).
 // Batches along blockIdx.z: pointers advance by the given strides.  ragged > 0 (the pairs of the triangular
@@ -157,6 +158,7 @@ struct GemmF32 {
     int m, n, k;
     float alpha, beta;
     int transB, ragged, total, k_is_rows, lower_only;
+    int transA;  // A stored [k x m] (the product is A^T op(B))
 };
 
 __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g)
@@ -185,7 +187,11 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g)
 #pragma unroll
         for (int it = 0; it < KC * T / 256; ++it) {
             const int idx = it * 256 + tid;
-            {   // A tile: rows r0.., k kk..: consecutive threads along k (contiguous in memory)
+            if (g.transA) {  // A stored [k x m]: consecutive threads along the row index (contiguous in memory)
+                const int rr = idx % T, kx = idx / T;
+                const int row = r0 + rr, kc = kk + kx;
+                As[kx][rr] = (row < m && kc < k) ? A[(int64_t)kc * g.lda + row] : 0.0f;
+            } else {         // A stored [m x k]: consecutive threads along k
                 const int kx = idx % KC, rr = idx / KC;
                 const int row = r0 + rr, kc = kk + kx;
                 As[kx][rr] = (row < m && kc < k) ? A[(int64_t)row * g.lda + kc] : 0.0f;
@@ -254,6 +260,23 @@ size_t gptq_prepare_workspace_bytes(int64_t K)
 {
     // At, V: K x K each; T: K x K / 2; the diagonal block's inverse; the diagonal; the mean
     return 2 * align256((size_t)K * K * 4) + align256((size_t)K * K * 2) + align256((size_t)NB * NB * 4) + align256((size_t)K * 4) + 256;
+}
+
+// H = (accumulate ? H : 0) + Xr^T Xr for rotated calibration rows Xr [T, K] (fp32, row-major)
+hipError_t launch_gptq_hessian_product(const float* Xr, int64_t T, int64_t K, float* H, bool accumulate, hipStream_t st)
+{
+    GemmF32 g{};
+    g.C = H;
+    g.A = Xr;
+    g.B = Xr;
+    g.ldc = g.lda = g.ldb = K;
+    g.m = (int)K;
+    g.n = (int)K;
+    g.k = (int)T;
+    g.alpha = 1.0f;
+    g.beta = accumulate ? 1.0f : 0.0f;
+    g.transA = 1;
+    return gemm_f32(g, 1, st);
 }
 
 hipError_t launch_gptq_prepare(const float* H, int64_t K64, float damp, bool use_order, int* perm, float* U, void* workspace,

@@ -48,4 +48,8 @@ size_t gptq_prepare_workspace_bytes(int64_t K);
 hipError_t launch_gptq_prepare(const float* H, int64_t K, float damp, bool use_order, int* perm, float* U, void* workspace,
                                hipStream_t st);
 
+// Hessian of rotated calibration rows: Xr = x H_b (fp32 scratch [T,K]), H (+)= Xr^T Xr
+hipError_t launch_gptq_rotate_rows(const void* x, int64_t T, int64_t K, int b, float* out, hipStream_t st);
+hipError_t launch_gptq_hessian_product(const float* Xr, int64_t T, int64_t K, float* H, bool accumulate, hipStream_t st);
+
 }  // namespace fp4mr

@@ -26,7 +26,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert {"fp4_rotate_quantize", "fp4_rotate_quantize_dense", "fp4_fused_linear", "fp4_w4a16_linear", "fp4_quantize_weights", "fp4_gptq_quantize_weights", "fp4_gptq_prepare", "fp4_gemm", "fp4_workspace_bytes",
+    assert {"fp4_rotate_quantize", "fp4_rotate_quantize_dense", "fp4_fused_linear", "fp4_w4a16_linear", "fp4_quantize_weights", "fp4_gptq_quantize_weights", "fp4_gptq_prepare", "fp4_gptq_accumulate_hessian", "fp4_gemm", "fp4_workspace_bytes",
             "fp4_packed_bytes", "fp4_status_string", "fp4_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -102,6 +102,10 @@ def test_argument_validation_happens_before_any_launch(lib):
                                          kw.get("ws", fake), kw.get("wsz", 1 << 30), None)
     assert gp(H=None) == 1 and gp(perm=None) == 1 and gp(K=0) == 2 and gp(K=30000) == 2 and gp(damp=-1.0) == 2
     assert gp(U=fake + 8) == 5 and gp(ws=None) == 6 and gp(wsz=4096) == 6
+    gh = lambda **kw: L.fp4_gptq_accumulate_hessian(kw.get("x", fake), kw.get("T", 64), kw.get("K", 128), kw.get("b", 32), kw.get("H", fake), 0,
+                                                    kw.get("ws", fake), kw.get("wsz", 1 << 30), None)
+    assert gh(x=None) == 1 and gh(H=None) == 1 and gh(T=0) == 2 and gh(K=100) == 2 and gh(b=8) == 3 and gh(ws=None) == 6 and gh(wsz=64) == 6
+    assert b.workspace_bytes(b.OP_GPTQ_HESSIAN, 64, 0, 128, b.MXFP4) == 64 * 128 * 4
     assert b.workspace_bytes(b.OP_GPTQ_PREPARE, 0, 0, 256, b.MXFP4) >= 256 * 256 * 10
     assert b.workspace_bytes(b.OP_GPTQ, 128, 0, 256, b.MXFP4) >= 128 * 256 * 5 + 128 * 64 * 4 + 256 * 4
     assert L.fp4_status_string(2).decode().startswith("bad shape")

@@ -211,3 +211,49 @@ def test_hessian_to_codes_entirely_on_the_gpu(fp4, oracle, gptq, fmt, policy):
     say(f"   codes differing from the oracle: {diff:.2e}; layer error {e_got:.5e} vs oracle {e_ref:.5e} (round-to-nearest {e_rtn:.3e})")
     assert abs(e_got - e_ref) <= 1e-2 * e_ref
     assert e_got < 0.8 * e_rtn
+
+
+@pytest.mark.parametrize("b", [1, 32, 128])
+def test_hessian_accumulation_matches_the_fp64_product(fp4, oracle, b):
+    """H = (X H_b)^T (X H_b) in fp32 against the oracle's rotation and a NumPy fp64 product; every entry within
+    2e-5 of sqrt(H_ii H_jj) (its Cauchy-Schwarz scale; 700 terms of fp32 rounding each), symmetric, and two batches of
+    rows accumulate to the same matrix."""
+    import torch
+    T, K = 700, 384
+    xb = inputs.RECIPES[6].x(T, K, salt=90 + b)
+    X = oracle.rotate(xb, b).astype(np.float64)
+    want = X.T @ X
+    say(f"gptq hessian b={b}")
+    H = fp4.fp4_gptq_accumulate_hessian(to_dev_bf16(xb), b)
+    H2 = fp4.fp4_gptq_accumulate_hessian(to_dev_bf16(xb[:300]), b)
+    H2 = fp4.fp4_gptq_accumulate_hessian(to_dev_bf16(xb[300:]), b, H2)
+    torch.cuda.synchronize()
+    scale = np.sqrt(np.outer(np.diag(want), np.diag(want)))
+    for got in (np_(H).astype(np.float64), np_(H2).astype(np.float64)):
+        assert np.all(np.abs(got - want) <= 2e-5 * scale)
+        assert np.array_equal(got, got.T)
+
+
+def test_calibration_rows_to_codes_entirely_on_the_gpu(fp4, oracle, gptq):
+    import torch
+    N, K, T, b = 64, 512, 1536, 32
+    r = inputs.RECIPES[6]
+    wb, xb = r.w(N, K, salt=95), r.x(T, K, salt=96)
+    say("gptq calibration rows -> codes")
+    H = fp4.fp4_gptq_accumulate_hessian(to_dev_bf16(xb), b)
+    perm, U = fp4.fp4_gptq_prepare(H, 1e-2, True)
+    c, s, _ = fp4.fp4_gptq_quantize_weights(to_dev_bf16(wb), b, MX, U, perm)
+    torch.cuda.synchronize()
+    X = oracle.rotate(xb, b).astype(np.float64)
+    H64 = X.T @ X
+    want_c, want_s, sT, want_perm, _ = gptq.mr_gptq(wb, H64, b, MX)
+    assert np.array_equal(np_(perm), want_perm)
+    got_c, got_s = np_(c).reshape(N, -1), np_(s).reshape(N, -1)
+    assert np.array_equal(got_s, want_s)
+    y = oracle.rotate(wb, b)
+    c_rtn, _, _ = oracle.quantize(y, MX)
+    e_got = gptq.layer_error(y, got_c, want_s, MX, sT, H64)
+    e_ref = gptq.layer_error(y, want_c, want_s, MX, sT, H64)
+    e_rtn = gptq.layer_error(y, c_rtn, want_s, MX, sT, H64)
+    say(f"   codes differing: {(unpack(got_c) != unpack(want_c)).mean():.2e}; layer error {e_got:.5e} vs oracle {e_ref:.5e} (round-to-nearest {e_rtn:.3e})")
+    assert abs(e_got - e_ref) <= 1e-2 * e_ref and e_got < 0.8 * e_rtn
