@@ -41,7 +41,7 @@ def np_(t):
     return t.detach().cpu().numpy()
 
 
-@pytest.mark.parametrize("N,K", [(70, 256), (150, 1088)])
+@pytest.mark.parametrize("N,K", [(5, 64), (70, 256), (150, 1088)])
 def test_sweep_is_bit_exact_where_the_arithmetic_is_exact(fp4, oracle, gptq, N, K):
     """Weights on a 2^-6 lattice, no rotation, unit diagonal, and every even column (in visiting order) pushing its error
     onto a few later odd columns with factors +-2^-3, +-2^-4 (odd columns push nothing): every product and sum is exact
