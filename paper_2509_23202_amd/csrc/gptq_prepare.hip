@@ -95,6 +95,7 @@ __device__ __forceinline__ float lane_value(float v, int lane)
 __global__ __launch_bounds__(64) void diag_block_kernel(float* A, float* V, float* Linv, int K, int k0, int nb)
 {
     __shared__ float t[NB][NB + 1];
+    __shared__ float xs[NB][NB + 1];
     const int r = threadIdx.x;
     // memory is walked a row per step with the lane as the column (coalesced); LDS transposes to a row per lane
 #pragma unroll 16
@@ -111,17 +112,9 @@ __global__ __launch_bounds__(64) void diag_block_kernel(float* A, float* V, floa
         row[j] = (r == j) ? d : row[j] / d;
 #pragma unroll
         for (int c = j + 1; c < NB; ++c) row[c] = fmaf(-row[j], lane_value(row[j], c), row[c]);
+        __builtin_amdgcn_sched_barrier(0);  // (keeps the scheduler's regions, and the compile time, small)
     }
-    // inverse, column by column: lane c solves L x = e_c by forward substitution (x[i] = 0 for i < c comes out by itself)
-    float x[NB];
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-        float s = (i == r) ? 1.0f : 0.0f;
-#pragma unroll
-        for (int u = 0; u < i; ++u) s = fmaf(-lane_value(row[u], i), x[u], s);
-        x[i] = s / lane_value(row[i], i);
-    }
-    // back through LDS for coalesced stores: L rows first, then the inverse (x[i] of lane c is inv[i][c])
+    // L goes to LDS (row per lane -> row-major) for the coalesced store and for the inversion
     __syncthreads();
 #pragma unroll
     for (int c = 0; c < NB; ++c) t[r][c] = row[c];
@@ -129,13 +122,21 @@ __global__ __launch_bounds__(64) void diag_block_kernel(float* A, float* V, floa
 #pragma unroll 16
     for (int rr = 0; rr < NB; ++rr)
         if (rr < nb && r < nb && r <= rr) A[(int64_t)(k0 + rr) * K + k0 + r] = t[rr][r];
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < NB; ++i) t[i][r] = x[i];
+    // inverse, column by column: lane c solves L x = e_c by forward substitution, its x in LDS column c; every lane reads
+    // the same L[i][u] (a broadcast).  A rolled loop: unrolled like the factorization it costs minutes of compile time.
+    {
+        const int c = r;
+        for (int i = 0; i < NB; ++i) {
+            float sum = (i == c) ? 1.0f : 0.0f;
+#pragma unroll 8
+            for (int u = 0; u < i; ++u) sum = fmaf(-t[i][u], xs[u][c], sum);
+            xs[i][c] = (i >= c) ? sum / t[i][i] : 0.0f;
+        }
+    }
     __syncthreads();
 #pragma unroll 16
     for (int rr = 0; rr < NB; ++rr) {
-        const float v = (rr < nb && r < nb && r <= rr) ? t[rr][r] : 0.0f;
+        const float v = (rr < nb && r < nb && r <= rr) ? xs[rr][r] : 0.0f;
         if (rr < nb && r < nb) V[(int64_t)(k0 + rr) * K + k0 + r] = v;
         Linv[rr * NB + r] = v;
     }
