@@ -147,7 +147,9 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
  * Few tokens in one launch: out = Q(X H_b) Q(W H_b)^T with the activations rotated and quantized inside the GEMM
  * (Section 4.2 items 1 and 2 fused; the paper's appendix on inference regimes: at small batch its separate kernels give
  * little).  Result bit-identical to fp4_rotate_quantize followed by fp4_gemm for had_block <= 32.
- *   x            [M,K] bf16 row-major, 1 <= M <= 16, K % 128 == 0
+ *   x            [M,K] bf16 row-major, 1 <= M <= 16, K % 128 == 0.  Meant for M <= 4: every workgroup (one per 16 rows of
+ *                W) repeats the rotation and quantization of all M tokens, which hides under its weight stream up to
+ *                four tokens; from five tokens on the two calls (fp4_rotate_quantize, fp4_gemm) are faster
  *   had_block    b in {16,32,64,128}
  *   w_codes, w_scales   [N,K] operand in GEMM layout (flags must contain FP4MR_W_LAYOUT_GEMM)
  *   fmt          FP4MR_MXFP4 only (NVFP4's tensor scale needs a pass over all of X first: FP4MR_ERR_FMT)
