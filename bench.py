@@ -36,8 +36,8 @@ RQ_TRAFFIC_BYTES_PER_LAUNCH = 339.9e6      # [16384, 8192]: 268.6 MB fetched + 7
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=64)
-    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--steps", type=int, default=192)
+    ap.add_argument("--warmup", type=int, default=24)
     ap.add_argument("--tokens", type=int, default=4096, help="M of the prefill workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the bf16 baseline and the standalone rotate+quantize figure")
