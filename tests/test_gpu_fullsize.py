@@ -110,6 +110,14 @@ def test_nvfp4_70b_qkv_layer(fp4, oracle, M):
     check_layer(fp4, oracle, inputs.RECIPES[4], M, L.K, L.N, NV, 16, n_m=min(M, 32), n_n=48)
 
 
+@pytest.mark.parametrize("li,M", [(1, 16), (1, 4096), (2, 16), (2, 4096)])
+def test_nvfp4_70b_wide_and_deep_layers(fp4, oracle, li, M):
+    """The other two layers of the NVFP4 configuration: gate_up (N = 57344) through the weight-streaming kernel, down
+    (K = 28672) through both kernels."""
+    L = inputs.LLAMA3_70B_LAYERS[li]
+    check_layer(fp4, oracle, inputs.RECIPES[4], M, L.K, L.N, NV, 16, n_m=min(M, 32), n_n=48)
+
+
 @pytest.mark.parametrize("b", [16, 32, 64, 128])
 def test_block_sweep_2048_8192(fp4, oracle, b):
     check_layer(fp4, oracle, inputs.RECIPES[5], 2048, 8192, 8192, MX, b, n_m=24, n_n=32, salt=b)
