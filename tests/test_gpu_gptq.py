@@ -257,3 +257,54 @@ def test_calibration_rows_to_codes_entirely_on_the_gpu(fp4, oracle, gptq):
     e_rtn = gptq.layer_error(y, c_rtn, want_s, MX, sT, H64)
     say(f"   codes differing: {(unpack(got_c) != unpack(want_c)).mean():.2e}; layer error {e_got:.5e} vs oracle {e_ref:.5e} (round-to-nearest {e_rtn:.3e})")
     assert abs(e_got - e_ref) <= 1e-2 * e_ref and e_got < 0.8 * e_rtn
+
+
+def test_sweep_at_layer_size_on_sampled_rows(fp4, oracle, gptq):
+    """A whole [4096, 4096] layer through the library (the benchmark's shape: 64 blocks, 8 outer blocks), checked against the
+    oracle on 32 sampled rows -- rows never interact, so the oracle sweeps just those rows with the same factor."""
+    import torch
+    N, K, T, b = 4096, 4096, 4608, 32
+    r = inputs.RECIPES[6]
+    wb = r.w(N, K, salt=120)
+    H = synthetic_hessian(oracle, K, T, b, salt=121)
+    perm = gptq.act_order(H).astype(np.int32)
+    U = gptq.inverse_factor(H, perm, damp=1e-2).astype(np.float32)
+    say("gptq layer size: N = K = 4096")
+    c, s, _ = fp4.fp4_gptq_quantize_weights(to_dev_bf16(wb), b, MX, to_dev(U), to_dev(perm))
+    torch.cuda.synchronize()
+    rows = np.sort(np.random.default_rng(5).choice(N, 32, replace=False))
+    y = oracle.rotate(wb[rows], b)
+    c_rtn, scales, _ = oracle.quantize(y, MX)
+    want, _ = gptq.sweep(y, scales, MX, None, U, perm)
+    got_c, got_s = np_(c).reshape(N, -1)[rows], np_(s).reshape(N, -1)[rows]
+    ok = (got_s == scales).all(axis=1)
+    assert ok.mean() >= 0.9
+    diff = (unpack(got_c) != unpack(want))[ok].mean()
+    e_got = gptq.layer_error(y[ok], got_c[ok], scales[ok], MX, None, H)
+    e_ref = gptq.layer_error(y[ok], want[ok], scales[ok], MX, None, H)
+    e_rtn = gptq.layer_error(y[ok], c_rtn[ok], scales[ok], MX, None, H)
+    say(f"   codes differing from the oracle: {diff:.2e}; layer error {e_got:.5e} vs oracle {e_ref:.5e} (round-to-nearest {e_rtn:.3e})")
+    assert diff <= 5e-3 and abs(e_got - e_ref) <= 2e-3 * e_ref and e_got < 0.8 * e_rtn
+
+
+def test_prepare_at_layer_size(fp4, oracle, gptq):
+    """K = 4096 (64 diagonal blocks, six doubling levels of the triangular inversion) against the fp64 factor, and the
+    defining identity on 64 sampled columns."""
+    import torch
+    K = 4096
+    H32 = synthetic_hessian(oracle, K, 4608, 32, salt=121).astype(np.float32)
+    say("gptq prepare K=4096")
+    perm, U = fp4.fp4_gptq_prepare(to_dev(H32), 1e-2, True)
+    torch.cuda.synchronize()
+    perm, U = np_(perm), np_(U).astype(np.float64)
+    H64 = H32.astype(np.float64)
+    want_perm = gptq.act_order(H64)
+    assert np.array_equal(perm, want_perm)
+    want_U = gptq.inverse_factor(H64, want_perm, damp=1e-2)
+    rel = np.linalg.norm(U - want_U) / np.linalg.norm(want_U)
+    A = H64[np.ix_(want_perm, want_perm)]
+    A[np.diag_indices(K)] += 1e-2 * np.mean(np.diag(A))
+    cols = np.sort(np.random.default_rng(6).choice(K, 64, replace=False))
+    resid = np.abs(U.T @ (U @ A[:, cols]) - np.eye(K)[:, cols]).max()
+    say(f"   relative error of U {rel:.2e}; max |U^T U A - I| on 64 columns {resid:.2e}")
+    assert rel <= 1e-3 and resid <= 5e-3
