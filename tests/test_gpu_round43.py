@@ -204,3 +204,25 @@ def test_round43_is_rejected_for_nvfp4_and_with_mse(fp4):
         fp4.fp4_rotate_quantize(x, 32, NV, flags=fp4.SCALE_ROUND43)
     with pytest.raises(Exception):
         fp4.fp4_rotate_quantize(x, 32, MX, flags=fp4.SCALE_ROUND43 | fp4.SCALE_MSE)
+
+
+@pytest.mark.parametrize("variant", [11, 13, 14])
+def test_tensor_level_factor_in_the_persistent_and_wide_tile_kernels(fp4, oracle, variant, monkeypatch):
+    """The factor is applied per tile before the epilogue: persistent workgroups walking several tiles (variants 11, 14)
+    and the 256 x 192 tile (13, 14), bf16 output through the staged epilogue."""
+    import torch
+    monkeypatch.setenv("FP4MR_GEMM_VARIANT", str(variant))
+    monkeypatch.setenv("FP4MR_GEMM_GRID", "2")
+    M, N, K, b = 272, 528, 1280, 32
+    r = inputs.RECIPES[1]
+    xb, wb = r.x(M, K, salt=11), r.w(N, K, salt=12)
+    ac, asc, aT = oracle.quantize(oracle.rotate(xb, b), MX, policy="round43")
+    wc, wsc, wT = oracle.quantize(oracle.rotate(wb, b), MX, policy="round43")
+    Y, S = oracle.matmul(oracle.dequantize(ac, asc, MX, aT), oracle.dequantize(wc, wsc, MX, wT))
+    say(f"round43 product, variant {variant}")
+    out = fp4.fp4_gemm(to_dev(ac.reshape(-1)), to_dev(asc.reshape(-1)), None, to_dev(wc.reshape(-1)), to_dev(wsc.reshape(-1)),
+                       None, M, N, K, MX, flags=fp4.A_SCALE43 | fp4.W_SCALE43)
+    torch.cuda.synchronize()
+    got = np_(out.float()).astype(np.float64)
+    # bf16 output: half an ulp of bf16 on top of the GEMM tolerance
+    assert np.all(np.abs(got - Y) <= 1e-3 * S + 2.0 ** -8 * np.abs(Y) + 1e-30)
