@@ -264,7 +264,7 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
 //   * a work item is 16 rows x (KI * 16 * b') K = NF = KI * b'/8 fragments of one row-block (1024 K either way), and
 //     it belongs to one workgroup: each of the four waves takes four of the rows.  The 16 vectors of one MFMA group
 //     are 16 consecutive vectors of ONE row, so a load instruction reads 32 * b' contiguous bytes (1 KB for b' = 32)
-//     and a wave has all its 8 KB of loads in flight at once (few registers: many resident waves);
+//     and a wave has all its loads (4 KB for b' = 32) in flight at once (few registers: many resident waves);
 //   * packed codes are staged through NF KB of LDS per workgroup and leave as one 16-byte-per-lane store per fragment
 //     (1 KB contiguous, the fragment itself; the item's fragments are adjacent in memory), NF/4 fragments per wave;
 //   * scale bytes are staged likewise and leave as whole dwords (MXFP4: four fragments complete each lane's dword;
@@ -511,7 +511,9 @@ template <int BP, int G, bool HW, int POL>
 hipError_t launch_frag(const RqArgs& a0, int grid_cap, hipStream_t st, int* blocks_out)
 {
     RqArgs a = a0;
-    constexpr int KI = (BP == 32) ? 2 : 1;  // 8 KB of loads per wave either way
+    // One group of 16 vectors per row and item.  Twice that for b' = 32 (8 KB of loads per wave instead of 4) measured
+    // 3-8 % slower at every size tried: the smaller workgroups keep more waves resident and drain more evenly.
+    constexpr int KI = 1;
     constexpr int IK = KI * 16 * BP;
     (void)grid_cap;
     // one item per workgroup: x = items along K, (y, z) = row-blocks
