@@ -90,8 +90,14 @@ __device__ __forceinline__ void remap_block(int bid, int nblocks, int tiles_m, i
     tn = in_band / gsz;
 }
 
+// Four-wave workgroups with a three-stage ring are sized so that two of them share a compute unit (registers: 256 per
+// wave; LDS: under 80 KB): while one converts and stores its tile the other keeps the matrix pipes busy.
+template <int BM, int BN, int WM, int WN, int STAGES>
+constexpr int kWgsPerCu = ((BM / WM) * (BN / WN) == 4 && STAGES == 3) ? 2 : 1;
+
 template <int BM, int BN, int WM, int WN, int STAGES, bool OUT_F32, int RD = 2, bool PERSIST = false>
-__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(GemmArgs g)
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) __attribute__((amdgpu_waves_per_eu(kWgsPerCu<BM, BN, WM, WN, STAGES>)))
+void gemm_mx_kernel(GemmArgs g)
 {
     constexpr int NWM = BM / WM, NWN = BN / WN, NW = NWM * NWN;
     constexpr int FX = BM / 16, FW = BN / 16, F = FX + FW;  // fragments per stage
@@ -147,6 +153,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     // the main loop) and are read back once per 4 K-steps.
     constexpr int NS = LPW;                                 // scale-block loads per wave per batch
     constexpr int SCALE_BYTES = F * 256;
+    // The scale ring is two batches deep, or one with a three-stage operand ring: a batch is read into registers at the
+    // end of the step before the one that issues its successor, with that step's barrier in between.
+    constexpr int SD = (STAGES == 3) ? 1 : 2;
     char* const scale_ring = smem + STAGES * STAGE_BYTES;
     const int kc_bytes = (int)KC * 1024, ks_bytes = (int)KS * 256;
 
@@ -166,7 +175,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
     // whenever the X fragments divide evenly among the waves, which keeps the step body free of branches
     auto is_x = [&](int f, int i) { return (FX % NW == 0) ? (i < FX / NW) : (f < FX); };
     auto issue_scale_one = [&](int ss, int i) {
-        char* base = scale_ring + (ss & 1) * SCALE_BYTES;
+        char* base = scale_ring + (ss & (SD - 1)) * SCALE_BYTES;
         ss = ss < (int)KS ? ss : (int)KS - 1;  // the batch past the end re-reads the last one
         const int f = min(wave + i * NW, F - 1);
         if (is_x(f, i)) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_as, (lds_void*)(base + f * 256), 4, lane4, min(f, a_rb_last) * ks_bytes + ss * 256, 0, 0);
@@ -182,7 +191,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
         for (int i = 0; i < NS; ++i) issue_scale_one(ss, i);
     };
     auto read_scales = [&](int64_t ss, uint32_t (&dx)[TM], uint32_t (&dw)[TN]) {
-        const char* base = scale_ring + (ss & 1) * SCALE_BYTES;
+        const char* base = scale_ring + (ss & (SD - 1)) * SCALE_BYTES;
 #pragma unroll
         for (int j = 0; j < TM; ++j) dx[j] = *(reinterpret_cast<const uint32_t*>(base + (wm * TM + j) * 256) + lane);
 #pragma unroll
@@ -225,11 +234,12 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mx_kernel(Gem
         constexpr int P = J & 1;
         constexpr bool batch_after = (J >= 1 && J <= STAGES - 3);
         constexpr int ALLOWED = (STAGES - 3) * LPW + (batch_after ? NS : 0);
-        if constexpr (PERSIST && J < 2) {
-            // first two steps of a follow-on tile: the previous tile's NST output stores were issued after this tile's
-            // prefetched stages and may still be in flight (vector memory operations complete in issue order, so the
-            // stages in front of them can be waited for without waiting for the stores)
-            if (pend && kt < 2) wait_vmcnt<ALLOWED + NST>(); else wait_vmcnt<ALLOWED>();
+        if constexpr (PERSIST && J <= STAGES - 3) {
+            // first steps of a follow-on tile, as long as the stage they wait for (kt + 1) is one of the STAGES - 1 that
+            // were prefetched: the previous tile's NST output stores were issued after those and may still be in flight
+            // (vector memory operations complete in issue order, so the stages in front of the stores can be waited for
+            // without waiting for the stores)
+            if (pend && kt <= STAGES - 3) wait_vmcnt<ALLOWED + NST>(); else wait_vmcnt<ALLOWED>();
         } else {
             wait_vmcnt<ALLOWED>();
         }
@@ -429,11 +439,11 @@ hipError_t launch_variant(const GemmArgs& g0, bool out_f32, hipStream_t st)
     g.tiles_m = (int)((g.M + BM - 1) / BM);
     g.tiles_n = (int)((g.N + BN - 1) / BN);
     constexpr int threads = (BM / WM) * (BN / WN) * 64;
-    constexpr size_t lds = (size_t)STAGES * (BM + BN) / 16 * 1024 + 2 * (size_t)(BM + BN) / 16 * 256;
+    constexpr size_t lds = (size_t)STAGES * (BM + BN) / 16 * 1024 + (STAGES == 3 ? 1 : 2) * (size_t)(BM + BN) / 16 * 256;
     const int ntiles = g.tiles_m * g.tiles_n;
     int nwg = ntiles;
     if (PERSIST) {
-        nwg = std::min(ntiles, compute_units());
+        nwg = std::min(ntiles, compute_units() * kWgsPerCu<BM, BN, WM, WN, STAGES>);
         // FP4MR_GEMM_GRID caps the persistent grid (a testing aid: a small grid walks many tiles per workgroup)
         const char* cap = std::getenv("FP4MR_GEMM_GRID");
         if (cap && *cap && std::atoi(cap) > 0) nwg = std::min(nwg, std::atoi(cap));
@@ -494,6 +504,11 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
             // more 256x256 tiles than compute units: persistent workgroups, which prefetch the next tile's first stages
             // and let the output stores drain under its first K-steps (1.5-6% on such shapes, never slower)
             if (variant == 10 && tiles(256, 256) > cus) variant = 11;
+            // K around 1024: a tile is 8 K-steps, about as long as its own start-up and stores.  128x256 tiles with two
+            // workgroups per compute unit overlap one workgroup's epilogue with the other's main loop: 10-13 % faster
+            // there, level at K = 1536-2048, slower beyond (three stages, one and a half times the operand traffic) and
+            // below (K = 512: the persistent 256x256 workgroups win).
+            if ((variant == 10 || variant == 11) && K >= 768 && K <= 1280) variant = tiles(128, 256) > 2.0 * cus ? 16 : 15;
         }
     }
     switch (variant) {
@@ -511,6 +526,8 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
         case 12: return launch_variant<256, 128, 128, 64, 4, 2, true>(g, out_f32, st);
         case 13: return launch_variant<256, 192, 64, 96, 4, 2>(g, out_f32, st);
         case 14: return launch_variant<256, 192, 64, 96, 4, 2, true>(g, out_f32, st);
+        case 15: return launch_variant<128, 256, 64, 128, 3, 3>(g, out_f32, st);
+        case 16: return launch_variant<128, 256, 64, 128, 3, 3, true>(g, out_f32, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -171,3 +171,10 @@ def test_persistent_gemm_with_edge_tiles_at_scale(fp4, oracle):
     """425 tiles of 256 x 256 on 256 workgroups, the last tile row and column ragged (M = 4113, N = 6152): interior
     tiles (stores draining under the next tile) and edge tiles (full wait) alternate inside one workgroup."""
     check_layer(fp4, oracle, inputs.RECIPES[3], 4113, 512, 6152, MX, 32, n_m=48, n_n=64, salt=77)
+
+
+@pytest.mark.parametrize("M,N", [(2048, 8192), (4099, 14344)])
+def test_short_k_layers_take_the_two_workgroups_per_unit_tiles(fp4, oracle, M, N):
+    """K = 1024 with more 256 x 256 tiles than one round of compute units: the shape rule picks 128 x 256 tiles, two
+    workgroups per unit -- one round for the first shape, persistent workgroups with ragged edge tiles for the second."""
+    check_layer(fp4, oracle, inputs.RECIPES[3], M, 1024, N, MX, 32, n_m=48, n_n=64, salt=M)

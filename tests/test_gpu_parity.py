@@ -199,13 +199,13 @@ def test_gemm_gemm_layout_operands_bf16_out(fp4, oracle, fmt):
     _gemm_case(fp4, oracle, fmt, 200, 520, 1024 + 384, seed=5, out_f32=False, layout_gemm=True)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16])
 def test_gemm_mxfp4_every_tile_variant(fp4, oracle, variant, monkeypatch):
     monkeypatch.setenv("FP4MR_GEMM_VARIANT", str(variant))
     _gemm_case(fp4, oracle, MX, 272, 528, 1280, seed=variant, out_f32=True, layout_gemm=True)
 
 
-@pytest.mark.parametrize("variant", [2, 5, 10, 13])
+@pytest.mark.parametrize("variant", [2, 5, 10, 13, 15])
 def test_gemm_mxfp4_tile_variants_bf16_output_through_the_staged_epilogue(fp4, oracle, variant, monkeypatch):
     """bf16 output goes through the LDS transpose of the epilogue, whose chunk swizzle depends on the wave tile's width
     (64, 96 and 128 columns here); ragged last tile row and column."""
@@ -223,7 +223,7 @@ def test_gemm_mxfp4_persistent_workgroups_walk_several_tiles(fp4, oracle, grid, 
     _gemm_case(fp4, oracle, MX, 272, 528, 1280, seed=40 + grid, out_f32=out_f32, layout_gemm=True)
 
 
-@pytest.mark.parametrize("variant", [11, 12, 14])
+@pytest.mark.parametrize("variant", [11, 12, 14, 16])
 @pytest.mark.parametrize("K", [128, 256, 384, 1152])
 @pytest.mark.parametrize("grid", [1, 2])
 def test_gemm_mxfp4_persistent_interior_tiles_overlap_their_stores(fp4, oracle, grid, K, variant, monkeypatch):
