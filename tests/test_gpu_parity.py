@@ -224,7 +224,7 @@ def test_gemm_mxfp4_persistent_workgroups_walk_several_tiles(fp4, oracle, grid, 
 
 
 @pytest.mark.parametrize("variant", [11, 12, 14, 16])
-@pytest.mark.parametrize("K", [128, 256, 384, 1152])
+@pytest.mark.parametrize("K", [128, 256, 384, 1024, 1152, 3072])
 @pytest.mark.parametrize("grid", [1, 2])
 def test_gemm_mxfp4_persistent_interior_tiles_overlap_their_stores(fp4, oracle, grid, K, variant, monkeypatch):
     """All tiles interior (M, N multiples of the tile): every follow-on tile starts its main loop while the previous
@@ -232,6 +232,18 @@ def test_gemm_mxfp4_persistent_interior_tiles_overlap_their_stores(fp4, oracle, 
     monkeypatch.setenv("FP4MR_GEMM_VARIANT", str(variant))
     monkeypatch.setenv("FP4MR_GEMM_GRID", str(grid))
     _gemm_case(fp4, oracle, MX, 512, 768, K, seed=60 + grid + K, out_f32=False, layout_gemm=True)
+
+
+@pytest.mark.parametrize("variant", [11, 12, 14, 16])
+@pytest.mark.parametrize("grid", [1, 3])
+@pytest.mark.parametrize("out_f32", [False, True])
+def test_gemm_mxfp4_persistent_variants_across_ragged_tiles(fp4, oracle, grid, out_f32, variant, monkeypatch):
+    """Every persistent tile shape on 1 and 3 workgroups over a ragged tile grid (K = 3072): uneven tile counts per
+    workgroup, interior tiles followed by edge tiles (full wait) and the other way round, bf16 (staged) and fp32 (direct)
+    epilogues."""
+    monkeypatch.setenv("FP4MR_GEMM_VARIANT", str(variant))
+    monkeypatch.setenv("FP4MR_GEMM_GRID", str(grid))
+    _gemm_case(fp4, oracle, MX, 528, 784, 3072, seed=90 + grid + variant, out_f32=out_f32, layout_gemm=True)
 
 
 def test_gemm_mxfp4_exact_on_small_integers(fp4, oracle):
