@@ -308,3 +308,53 @@ def test_prepare_at_layer_size(fp4, oracle, gptq):
     resid = np.abs(U.T @ (U @ A[:, cols]) - np.eye(K)[:, cols]).max()
     say(f"   relative error of U {rel:.2e}; max |U^T U A - I| on 64 columns {resid:.2e}")
     assert rel <= 1e-3 and resid <= 5e-3
+
+
+def test_widest_layer_of_the_benchmark_model(fp4, oracle, gptq):
+    """K = 14336 (the down projection: 224 diagonal blocks, eight doubling levels, an 822 MB factor): the order against
+    the oracle's, the factor through the identity that defines it, U^T U (H_perm + lambda I) = I, on sampled columns
+    (an fp64 inverse of this size is minutes of CPU), and the sweep of 48 rows with that factor against the oracle's
+    sweep of 12 of them.  The Hessian is a rank-96 Gram matrix plus a positive diagonal, built directly."""
+    import torch
+    K, N, b = 14336, 48, 32
+    rng = np.random.default_rng(140)
+    V = rng.standard_normal((K, 96)) * rng.uniform(0.3, 2.0, (K, 1))
+    H64 = V @ V.T / 96.0
+    H64[np.diag_indices(K)] += rng.uniform(0.5, 2.0, K)
+    H32 = H64.astype(np.float32)
+    H64 = H32.astype(np.float64)
+    say("gptq prepare K=14336")
+    perm_d, U_d = fp4.fp4_gptq_prepare(to_dev(H32), 1e-2, True)
+    torch.cuda.synchronize()
+    perm = np_(perm_d)
+    want_perm = gptq.act_order(H64)
+    assert np.array_equal(perm, want_perm)
+    U = np_(U_d).astype(np.float64)
+    assert np.all(np.diag(U) > 0)
+    cols = np.sort(rng.choice(K, 16, replace=False))
+    A_cols = H64[np.ix_(want_perm, want_perm[cols])]
+    A_cols[cols, np.arange(16)] += 1e-2 * np.mean(np.diag(H64))
+    E = np.zeros((K, 16))
+    E[cols, np.arange(16)] = 1.0
+    resid = np.abs(U.T @ (U @ A_cols) - E).max()
+    below = max(np.abs(U[r, :r]).max() for r in (1, K // 2, K - 1))
+    say(f"   max |U^T U A - I| on 16 columns {resid:.2e}")
+    assert resid <= 5e-3 and below == 0.0
+
+    wb = inputs.RECIPES[6].w(N, K, salt=141)
+    say("gptq sweep N=48 K=14336")
+    c, s, _ = fp4.fp4_gptq_quantize_weights(to_dev_bf16(wb), b, MX, U_d, perm_d)
+    torch.cuda.synchronize()
+    rows = np.arange(0, N, 4)
+    y = oracle.rotate(wb[rows], b)
+    c_rtn, scales, _ = oracle.quantize(y, MX)
+    want, _ = gptq.sweep(y, scales, MX, None, U, perm)
+    got_c, got_s = np_(c).reshape(N, -1)[rows], np_(s).reshape(N, -1)[rows]
+    ok = (got_s == scales).all(axis=1)
+    assert ok.mean() >= 0.9
+    diff = (unpack(got_c) != unpack(want))[ok].mean()
+    e_got = gptq.layer_error(y[ok], got_c[ok], scales[ok], MX, None, H64)
+    e_ref = gptq.layer_error(y[ok], want[ok], scales[ok], MX, None, H64)
+    e_rtn = gptq.layer_error(y[ok], c_rtn[ok], scales[ok], MX, None, H64)
+    say(f"   codes differing from the oracle: {diff:.2e}; layer error {e_got:.5e} vs oracle {e_ref:.5e} (round-to-nearest {e_rtn:.3e})")
+    assert diff <= 5e-3 and abs(e_got - e_ref) <= 2e-3 * e_ref and e_got < 0.9 * e_rtn
