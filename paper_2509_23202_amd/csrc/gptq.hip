@@ -207,63 +207,83 @@ __global__ __launch_bounds__(64) void gptq_block_kernel(GptqArgs a, int b0, int 
     }
 }
 
-// wp[n, c] -= sum_{j < rank} err[n, e0 + j] * U[u0 + j, c] for the columns c_begin <= c < c_end (visiting order), the
-// terms applied one j at a time in ascending order like the column-by-column definition.  128 x 128 output tile per
-// workgroup, 8 x 8 per thread, the errors and the rows of U staged through LDS 32 terms at a time.
+// wp[n, c] -= sum_{j < rank} err[n, e0 + j] * U[u0 + j, c] for the columns c_begin <= c < c_end (visiting order): a dense
+// fp32 contraction, on the fp32 MFMA (v_mfma_f32_16x16x4_f32; the terms enter four at a time in ascending order, where the
+// column-by-column definition applies them singly -- the same sum up to fp32 rounding order).  128 x 128 output tile per
+// workgroup, a 64 x 64 quarter per wave (16 MFMA tiles whose accumulators start as the working weights), the negated
+// errors and the rows of U staged through LDS 32 terms at a time, the next 32 fetched while the current ones multiply.
 __global__ __launch_bounds__(256) void gptq_update_kernel(GptqArgs a, int u0, int e0, int rank, int c_begin, int c_end)
 {
-    constexpr int T = 128, KC = 32;
-    __shared__ __attribute__((aligned(16))) float Et[KC][T];  // [term][row]
-    __shared__ __attribute__((aligned(16))) float Ut[KC][T];  // [term][column]
+    constexpr int T = 128, KC = 32, LD = T + 20, NT = 4, NL = KC * T / 256;
+    __shared__ float Et[KC][LD];  // [term][row], negated
+    __shared__ float Ut[KC][LD];  // [term][column]
     const int c0 = c_begin + blockIdx.x * T;
     const int n0 = blockIdx.y * T;
     const int tid = threadIdx.x;
-    const int ty = tid / 16, tx = tid % 16;
-    float acc[8][8];
+    const int wave = tid >> 6, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
+    const int wr = (wave >> 1) * 64, wc = (wave & 1) * 64;
+    // a lane holds rows 4q .. 4q+3 of column l16 of every 16 x 16 tile; c_end and the tile start are multiples of 64, so
+    // a wave's 64 columns are in or out together
+    const bool in = c0 + wc < c_end;
+    v4f acc[NT][NT];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int n = min(n0 + ty * 8 + i, a.N - 1);
-        const float* src = a.wp + (int64_t)n * a.K + c0 + tx * 8;
-        const bool in = c0 + tx * 8 < c_end;  // c_end and the tile start are multiples of 64: 8 columns are in or out together
-        const float4 lo = in ? *reinterpret_cast<const float4*>(src) : make_float4(0.f, 0.f, 0.f, 0.f);
-        const float4 hi = in ? *reinterpret_cast<const float4*>(src + 4) : make_float4(0.f, 0.f, 0.f, 0.f);
-        acc[i][0] = lo.x; acc[i][1] = lo.y; acc[i][2] = lo.z; acc[i][3] = lo.w;
-        acc[i][4] = hi.x; acc[i][5] = hi.y; acc[i][6] = hi.z; acc[i][7] = hi.w;
-    }
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int n = min(n0 + wr + i * 16 + 4 * q + v, a.N - 1);
+            const float* src = a.wp + (int64_t)n * a.K + c0 + wc + l16;
+#pragma unroll
+            for (int j = 0; j < NT; ++j) acc[i][j][v] = in ? src[j * 16] : 0.0f;
+        }
+    float re[NL], ru[NL];
+    auto fetch = [&](int r0) {
+#pragma unroll
+        for (int it = 0; it < NL; ++it) {
+            const int idx = it * 256 + tid;
+            // both reads run along the contiguous index: the errors of a row are consecutive over the terms, a row of U over
+            // the columns
+            const int te = idx % KC, xe = idx / KC;
+            const int n = min(n0 + xe, a.N - 1);
+            re[it] = -a.err[(int64_t)n * kOuter + e0 + r0 + te];
+            const int x = idx % T, t = idx / T;
+            ru[it] = (c0 + x < c_end) ? a.U[(int64_t)(u0 + r0 + t) * a.K + c0 + x] : 0.0f;
+        }
+    };
+    fetch(0);
     for (int r0 = 0; r0 < rank; r0 += KC) {
         __syncthreads();
 #pragma unroll
-        for (int it = 0; it < KC * T / 256; ++it) {
+        for (int it = 0; it < NL; ++it) {
             const int idx = it * 256 + tid;
-            const int x = idx % T, t = idx / T;
-            const int n = min(n0 + x, a.N - 1);
-            Et[t][x] = a.err[(int64_t)n * kOuter + e0 + r0 + t];
-            Ut[t][x] = (c0 + x < c_end) ? a.U[(int64_t)(u0 + r0 + t) * a.K + c0 + x] : 0.0f;
+            Et[idx % KC][idx / KC] = re[it];
+            Ut[idx / T][idx % T] = ru[it];
         }
         __syncthreads();
-#pragma unroll 4
-        for (int t = 0; t < KC; ++t) {
-            const float4 e0v = *reinterpret_cast<const float4*>(&Et[t][ty * 8]);
-            const float4 e1v = *reinterpret_cast<const float4*>(&Et[t][ty * 8 + 4]);
-            const float4 u0v = *reinterpret_cast<const float4*>(&Ut[t][tx * 8]);
-            const float4 u1v = *reinterpret_cast<const float4*>(&Ut[t][tx * 8 + 4]);
-            const float e[8] = {e0v.x, e0v.y, e0v.z, e0v.w, e1v.x, e1v.y, e1v.z, e1v.w};
-            const float u[8] = {u0v.x, u0v.y, u0v.z, u0v.w, u1v.x, u1v.y, u1v.z, u1v.w};
+        if (r0 + KC < rank) fetch(r0 + KC);
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
+        for (int ks = 0; ks < KC / 4; ++ks) {
+            float e[NT], u[NT];
 #pragma unroll
-                for (int k = 0; k < 8; ++k) acc[i][k] = __fmaf_rn(-e[i], u[k], acc[i][k]);
+            for (int i = 0; i < NT; ++i) e[i] = Et[ks * 4 + q][wr + i * 16 + l16];
+#pragma unroll
+            for (int j = 0; j < NT; ++j) u[j] = Ut[ks * 4 + q][wc + j * 16 + l16];
+#pragma unroll
+            for (int i = 0; i < NT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(e[i], u[j], acc[i][j], 0, 0, 0);
         }
     }
-    if (c0 + tx * 8 >= c_end) return;
+    if (!in) return;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int n = n0 + ty * 8 + i;
-        if (n >= a.N) continue;
-        float* dst = a.wp + (int64_t)n * a.K + c0 + tx * 8;
-        *reinterpret_cast<float4*>(dst) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
-        *reinterpret_cast<float4*>(dst + 4) = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
-    }
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int n = n0 + wr + i * 16 + 4 * q + v;
+            if (n >= a.N) continue;
+            float* dst = a.wp + (int64_t)n * a.K + c0 + wc + l16;
+#pragma unroll
+            for (int j = 0; j < NT; ++j) dst[j * 16] = acc[i][j][v];
+        }
 }
 
 // The same update for the 64 errors of one block onto the few hundred remaining columns of its outer block: 64 x 64

@@ -10,7 +10,8 @@
 //      panel  L21 = A21 L11^-T  as a product with that inverse, trailing update  A22 -= L21 L21^T
 //   3. V = L^-1 by recursive doubling over the diagonal blocks: [L11 0; L21 L22]^-1 = [V11 0; -V22 L21 V11, V22]
 //   4. U[i][j] = V[K-1-i][K-1-j]
-// All in fp32; the products run on one plain tiled kernel.
+// All in fp32; the products run on one tiled kernel on the fp32 MFMA.
+#include "device_util.hpp"
 #include "internal.hpp"
 
 #include <algorithm>
@@ -144,9 +145,10 @@ __global__ __launch_bounds__(64) void diag_block_kernel(float* A, float* V, floa
 
 // ---------------------------------------------------------------- plain fp32 product
 // C[m x n] = beta C + alpha op(A) op(B),  op(A) = A[m x k] or A^T with A stored [k x m], op(B) = B[k x n] or B^T with
-// B stored [n x k]; row-major with leading
-// dimensions; 64 x 64 tile per workgroup, 4 x 4 per thread, k in chunks of 16 through LDS; results are written after
-// all inputs of the tile have been read (a tile may overwrite its own A rows when n fits one tile).
+// B stored [n x k]; row-major with leading dimensions.  A dense fp32 contraction, so it runs on the fp32 MFMA
+// (v_mfma_f32_16x16x4_f32: true fp32 products and sums): T x T tile per workgroup (T = 64, or 128 for big products),
+// one quarter of it per wave as (T/32)^2 MFMA tiles, k in chunks of 16 (32 for the wide tile) through LDS with the next chunk prefetched into registers; results are written after all
+// inputs of the tile have been read (a tile may overwrite its own A rows when n fits one tile).
 // Batches along blockIdx.z: pointers advance by the given strides.  ragged > 0 (the pairs of the triangular
 // inversion): batch z covers rows [z 2s + s, z 2s + 2s) of a matrix with `total` rows, s = ragged; its row count is
 // clipped to what exists, and so is k when k_is_rows is set.  lower_only skips tiles strictly above the diagonal.
@@ -162,11 +164,16 @@ struct GemmF32 {
     int transA;  // A stored [k x m] (the product is A^T op(B))
 };
 
+template <int T>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g)
 {
-    constexpr int T = 64, KC = 16;
-    __shared__ float As[KC][T + 4];  // [k][row]
-    __shared__ float Bs[KC][T + 4];  // [k][col]
+    constexpr int KC = (T == 128) ? 32 : 16;  // k per chunk
+    // row pitch = 20 mod 64 banks: the fills along k (16 k-rows x 4 rows per wave store) hit 64 different banks, and the
+    // four k-rows of an MFMA operand read (16 consecutive floats each) overlap in 12 banks only
+    constexpr int LD = T + 20;
+    constexpr int WT = T / 2, NT = WT / 16;  // wave tile and its MFMA tiles per side
+    __shared__ float As[KC][LD];  // [k][row]
+    __shared__ float Bs[KC][LD];  // [k][col]
     const int z = blockIdx.z;
     int m = g.m, k = g.k;
     if (g.ragged > 0) {
@@ -181,57 +188,84 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g)
     const float* A = g.A + (int64_t)z * g.sA;
     const float* B = g.B + (int64_t)z * g.sB;
     float* C = g.C + (int64_t)z * g.sC;
-    const int tid = threadIdx.x, ty = tid / 16, tx = tid % 16;
-    float acc[4][4] = {};
-    for (int kk = 0; kk < k; kk += KC) {
-        __syncthreads();
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
+    const int wr = (wave >> 1) * WT, wc = (wave & 1) * WT;  // this wave's corner inside the tile
+    v4f acc[NT][NT];
 #pragma unroll
-        for (int it = 0; it < KC * T / 256; ++it) {
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
+    // the next chunk's elements travel from global memory into registers while the MFMAs of the current chunk run
+    constexpr int NL = KC * T / 256;
+    float ra[NL], rb[NL];
+    auto fetch = [&](int kk) {
+#pragma unroll
+        for (int it = 0; it < NL; ++it) {
             const int idx = it * 256 + tid;
             if (g.transA) {  // A stored [k x m]: consecutive threads along the row index (contiguous in memory)
                 const int rr = idx % T, kx = idx / T;
                 const int row = r0 + rr, kc = kk + kx;
-                As[kx][rr] = (row < m && kc < k) ? A[(int64_t)kc * g.lda + row] : 0.0f;
+                ra[it] = (row < m && kc < k) ? A[(int64_t)kc * g.lda + row] : 0.0f;
             } else {         // A stored [m x k]: consecutive threads along k
                 const int kx = idx % KC, rr = idx / KC;
                 const int row = r0 + rr, kc = kk + kx;
-                As[kx][rr] = (row < m && kc < k) ? A[(int64_t)row * g.lda + kc] : 0.0f;
+                ra[it] = (row < m && kc < k) ? A[(int64_t)row * g.lda + kc] : 0.0f;
             }
             if (g.transB) {  // B stored [n x k]
                 const int kx = idx % KC, cc = idx / KC;
                 const int col = c0 + cc, kc = kk + kx;
-                Bs[kx][cc] = (col < g.n && kc < k) ? B[(int64_t)col * g.ldb + kc] : 0.0f;
+                rb[it] = (col < g.n && kc < k) ? B[(int64_t)col * g.ldb + kc] : 0.0f;
             } else {         // B stored [k x n]
                 const int cc = idx % T, kx = idx / T;
                 const int col = c0 + cc, kc = kk + kx;
-                Bs[kx][cc] = (col < g.n && kc < k) ? B[(int64_t)kc * g.ldb + col] : 0.0f;
+                rb[it] = (col < g.n && kc < k) ? B[(int64_t)kc * g.ldb + col] : 0.0f;
             }
         }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int it = 0; it < NL; ++it) {
+            const int idx = it * 256 + tid;
+            if (g.transA) As[idx / T][idx % T] = ra[it]; else As[idx % KC][idx / KC] = ra[it];
+            if (g.transB) Bs[idx % KC][idx / KC] = rb[it]; else Bs[idx / T][idx % T] = rb[it];
+        }
+    };
+    fetch(0);
+    for (int kk = 0; kk < k; kk += KC) {
+        __syncthreads();  // the previous chunk's MFMA operands have been read
+        stash();
         __syncthreads();
+        if (kk + KC < k) fetch(kk + KC);
+        // one MFMA = 16 x 16 outputs over 4 k: lane (l16, q) supplies op(A)[row l16][k q] and op(B)[k q][col l16]
 #pragma unroll
-        for (int kx = 0; kx < KC; ++kx) {
-            float a[4], b[4];
+        for (int ks = 0; ks < KC / 4; ++ks) {
+            float a[NT], b[NT];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = As[kx][ty * 4 + i];
+            for (int i = 0; i < NT; ++i) a[i] = As[ks * 4 + q][wr + i * 16 + l16];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) b[j] = Bs[kx][tx * 4 + j];
+            for (int j = 0; j < NT; ++j) b[j] = Bs[ks * 4 + q][wc + j * 16 + l16];
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < NT; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+                for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i], b[j], acc[i][j], 0, 0, 0);
         }
     }
     __syncthreads();  // every thread of the tile has read its inputs
+    // a lane holds rows 4q .. 4q+3 of column l16 of every MFMA tile
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = r0 + ty * 4 + i;
-        if (row >= m) continue;
+    for (int i = 0; i < NT; ++i) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int col = c0 + tx * 4 + j;
-            if (col >= g.n) continue;
-            float* p = C + (int64_t)row * g.ldc + col;
-            *p = (g.beta == 0.0f) ? g.alpha * acc[i][j] : g.beta * (*p) + g.alpha * acc[i][j];
+        for (int v = 0; v < 4; ++v) {
+            const int row = r0 + wr + i * 16 + 4 * q + v;
+            if (row >= m) continue;
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const int col = c0 + wc + j * 16 + l16;
+                if (col >= g.n) continue;
+                float* p = C + (int64_t)row * g.ldc + col;
+                *p = (g.beta == 0.0f) ? g.alpha * acc[i][j][v] : g.beta * (*p) + g.alpha * acc[i][j][v];
+            }
         }
     }
 }
@@ -239,8 +273,15 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g)
 hipError_t gemm_f32(const GemmF32& g, int batches, hipStream_t st)
 {
     if (g.m <= 0 || g.n <= 0 || batches <= 0) return hipSuccess;
-    const dim3 grid((unsigned)((g.n + 63) / 64), (unsigned)((g.m + 63) / 64), (unsigned)batches);
-    hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, st, g);
+    // the wide tile for products with enough tiles of it to fill the chip and enough k to pay for its larger fills (never
+    // the in-place panel, whose n is one narrow tile, nor the rank-64 trailing updates, which want many small tiles)
+    if (g.m >= 1024 && g.n >= 1024 && g.k >= 256) {
+        const dim3 grid((unsigned)((g.n + 127) / 128), (unsigned)((g.m + 127) / 128), (unsigned)batches);
+        hipLaunchKernelGGL(gemm_f32_kernel<128>, grid, dim3(256), 0, st, g);
+    } else {
+        const dim3 grid((unsigned)((g.n + 63) / 64), (unsigned)((g.m + 63) / 64), (unsigned)batches);
+        hipLaunchKernelGGL(gemm_f32_kernel<64>, grid, dim3(256), 0, st, g);
+    }
     return hipGetLastError();
 }
 
