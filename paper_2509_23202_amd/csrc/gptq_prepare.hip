@@ -123,15 +123,42 @@ __global__ __launch_bounds__(64) void diag_block_kernel(float* A, float* V, floa
 #pragma unroll 16
     for (int rr = 0; rr < NB; ++rr)
         if (rr < nb && r < nb && r <= rr) A[(int64_t)(k0 + rr) * K + k0 + r] = t[rr][r];
-    // inverse, column by column: lane c solves L x = e_c by forward substitution, its x in LDS column c; every lane reads
-    // the same L[i][u] (a broadcast).  A rolled loop: unrolled like the factorization it costs minutes of compile time.
+    // inverse, column by column: lane c solves L x = e_c by forward substitution, its x in LDS column c.  Eight rows at a
+    // time: their sums over the rows already solved are eight independent chains fed by one read of x and two 16-byte
+    // broadcast reads of a transposed copy of L; then the 8 x 8 triangle in registers.  The loops over row groups and
+    // solved rows stay rolled: unrolled like the factorization they cost minutes of compile time.
+    __shared__ __attribute__((aligned(16))) float tT[NB][NB + 4];  // tT[u][i] = L[i][u]
+#pragma unroll
+    for (int c = 0; c < NB; ++c) tT[c][r] = row[c];
+    __syncthreads();
     {
         const int c = r;
-        for (int i = 0; i < NB; ++i) {
-            float sum = (i == c) ? 1.0f : 0.0f;
-#pragma unroll 8
-            for (int u = 0; u < i; ++u) sum = fmaf(-t[i][u], xs[u][c], sum);
-            xs[i][c] = (i >= c) ? sum / t[i][i] : 0.0f;
+        for (int i0 = 0; i0 < NB; i0 += 8) {
+            float sum[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) sum[k] = (i0 + k == c) ? 1.0f : 0.0f;
+#pragma unroll 4
+            for (int u = 0; u < i0; ++u) {
+                const float xv = xs[u][c];
+                const float4 la = *reinterpret_cast<const float4*>(&tT[u][i0]);
+                const float4 lb = *reinterpret_cast<const float4*>(&tT[u][i0 + 4]);
+                sum[0] = fmaf(-la.x, xv, sum[0]);
+                sum[1] = fmaf(-la.y, xv, sum[1]);
+                sum[2] = fmaf(-la.z, xv, sum[2]);
+                sum[3] = fmaf(-la.w, xv, sum[3]);
+                sum[4] = fmaf(-lb.x, xv, sum[4]);
+                sum[5] = fmaf(-lb.y, xv, sum[5]);
+                sum[6] = fmaf(-lb.z, xv, sum[6]);
+                sum[7] = fmaf(-lb.w, xv, sum[7]);
+            }
+            float x[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+#pragma unroll
+                for (int k2 = 0; k2 < k; ++k2) sum[k] = fmaf(-tT[i0 + k2][i0 + k], x[k2], sum[k]);
+                x[k] = (i0 + k >= c) ? sum[k] / tT[i0 + k][i0 + k] : 0.0f;
+                xs[i0 + k][c] = x[k];
+            }
         }
     }
     __syncthreads();
