@@ -145,65 +145,157 @@ __device__ __forceinline__ void sweep_part(float (&w)[16], float (&ek)[16], uint
     }
 }
 
+// One outer block (columns o .. oe-1 in visiting order) of 16 rows, one wave, no other wave involved: rows never
+// interact, so the wave walks the outer block's 64-column blocks by itself -- sweep a block, then push that block's 64
+// errors onto the rest of the outer block for its own rows -- and the whole outer block is a single launch.
+//   * sweep: sweep_part above (four lanes per row);
+//   * push: wp[rows, c] -= sum_j e[rows, j] U[b0 + j, c] for b0 + 64 <= c < oe, a [16 x 64] x [64 x 16] product per 16
+//     columns on the fp32 MFMA (v_mfma_f32_16x16x4_f32): the negated errors go through LDS into the A operand once per
+//     block, the rows of U come straight from global memory as the B operand (64 bytes per row per load), and the
+//     accumulator starts as the working weights;
+//   * the next block's columns were just written by other lanes of this wave: a workgroup-scope fence orders the stores
+//     before the loads (one compute unit, one vector cache).
+// The errors also go to err[N, kOuter] for the rank-512 update of everything behind the outer block.
 template <int FMT>
-__global__ __launch_bounds__(64) void gptq_block_kernel(GptqArgs a, int b0, int e0)
+__global__ __launch_bounds__(64) void gptq_outer_kernel(GptqArgs a, int o, int oe)
 {
-    __shared__ __attribute__((aligned(16))) float Us[kB * kB];
-    __shared__ float Ru[kB];                                    // 1 / U[j,j]
+    // the block's triangle of U, 1 / U[j,j] and the columns' original positions: two buffers, the next block's set is
+    // fetched into registers before the push and stored after it (its latency hides behind the push)
+    __shared__ __attribute__((aligned(16))) float Us2[2][kB * kB];
+    __shared__ float Ru2[2][kB];
+    __shared__ int cols2[2][kB];
     __shared__ __attribute__((aligned(8))) v2f_t Sc[kB * 16];   // [column][row of the wave]: scale and its reciprocal
-    __shared__ int cols[kB];
+    __shared__ __attribute__((aligned(16))) float Es[16][kB + 4];  // negated errors of the block: [row][term]
     const int lane = threadIdx.x;
-    // (unrolled so that the loads are in flight together: rolled, every LDS store would wait for its own load)
-#pragma unroll 16
-    for (int it = 0; it < kB * kB / 64; ++it) {
-        const int i = it * 64 + lane;
-        const int r = i / kB, c = i % kB;
-        Us[i] = (c >= r) ? a.U[(int64_t)(b0 + r) * a.K + b0 + c] : 0.0f;
-    }
-    Ru[lane] = 1.0f / a.U[(int64_t)(b0 + lane) * a.K + b0 + lane];
-    cols[lane] = visit_col(a, b0 + lane);
-    __syncthreads();
-
-    const int row = lane >> 2, part = lane & 3;
+    const int row = lane >> 2, part = lane & 3;  // sweep: four lanes per row
+    const int l16 = lane & 15, q = lane >> 4;    // push: MFMA operand coordinates
     const int n_raw = blockIdx.x * 16 + row;
     const bool live = n_raw < a.N;
     const int n = live ? n_raw : a.N - 1;  // idle lanes shadow the last row and store nothing
     const float s_T = (FMT == 1) ? *a.s_T : 1.0f;
     const uint8_t* srow = a.scales + (int64_t)n * (a.K / a.G);
-    float w[16];
-    const float4* src = reinterpret_cast<const float4*>(a.wp + (int64_t)n * a.K + b0 + part * 16);
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        const float4 t = src[v];
-        w[4 * v] = t.x;
-        w[4 * v + 1] = t.y;
-        w[4 * v + 2] = t.z;
-        w[4 * v + 3] = t.w;
-    }
     const int gshift = (a.G == 32) ? 5 : 4;
-    uint32_t sbyte[16];
+    const float* __restrict__ Ug = a.U;
+    float up[kB * kB / 64];  // a block's triangle on its way to LDS: element (it, lane) = row it, column lane
+    float rup;
+    int cup;
+    auto fetch_block = [&](int bb) {  // (unrolled: all 64 loads in flight together)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) sbyte[i] = srow[cols[part * 16 + i] >> gshift];  // sixteen independent loads in flight
+        for (int it = 0; it < kB * kB / 64; ++it) up[it] = (lane >= it) ? Ug[(int64_t)(bb + it) * a.K + bb + lane] : 0.0f;
+        rup = Ug[(int64_t)(bb + lane) * a.K + bb + lane];
+        cup = visit_col(a, bb + lane);
+    };
+    auto stash_block = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int j = part * 16 + i;
-        const float sv = decode_scale<FMT>(sbyte[i], s_T, a.factor);
-        Sc[j * 16 + row] = v2f_t{sv, sv > 0.0f ? 1.0f / sv : 0.0f};
-    }
-    __syncthreads();  // the scale of a column is read by every lane of its row's quad
-    float ek[16];
-    uint32_t ck[4] = {0u, 0u, 0u, 0u};
+        for (int it = 0; it < kB * kB / 64; ++it) Us2[buf][it * 64 + lane] = up[it];
+        Ru2[buf][lane] = 1.0f / rup;
+        cols2[buf][lane] = cup;
+    };
+    fetch_block(o);
+    stash_block(0);
+    __syncthreads();
+    for (int b0 = o; b0 < oe; b0 += kB) {
+        const int cur = ((b0 - o) / kB) & 1;
+        const float* Us = Us2[cur];
+        const float* Ru = Ru2[cur];
+        const int* cols = cols2[cur];
+
+        float w[16];
+        const float4* src = reinterpret_cast<const float4*>(a.wp + (int64_t)n * a.K + b0 + part * 16);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) ek[i] = 0.0f;
-    sweep_part<0>(w, ek, ck, Us, Ru, Sc, row, part);
-    sweep_part<1>(w, ek, ck, Us, Ru, Sc, row, part);
-    sweep_part<2>(w, ek, ck, Us, Ru, Sc, row, part);
-    sweep_part<3>(w, ek, ck, Us, Ru, Sc, row, part);
-    if (live) {
-        float4* ed = reinterpret_cast<float4*>(a.err + (int64_t)n * kOuter + e0 + part * 16);
+        for (int v = 0; v < 4; ++v) {
+            const float4 t = src[v];
+            w[4 * v] = t.x;
+            w[4 * v + 1] = t.y;
+            w[4 * v + 2] = t.z;
+            w[4 * v + 3] = t.w;
+        }
+        uint32_t sbyte[16];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) ed[v] = make_float4(ek[4 * v], ek[4 * v + 1], ek[4 * v + 2], ek[4 * v + 3]);
-        *reinterpret_cast<uint4*>(a.q + (int64_t)n * a.K + b0 + part * 16) = make_uint4(ck[0], ck[1], ck[2], ck[3]);
+        for (int i = 0; i < 16; ++i) sbyte[i] = srow[cols[part * 16 + i] >> gshift];  // sixteen independent loads in flight
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int j = part * 16 + i;
+            const float sv = decode_scale<FMT>(sbyte[i], s_T, a.factor);
+            Sc[j * 16 + row] = v2f_t{sv, sv > 0.0f ? 1.0f / sv : 0.0f};
+        }
+        __syncthreads();  // the scale of a column is read by every lane of its row's quad
+        float ek[16];
+        uint32_t ck[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 16; ++i) ek[i] = 0.0f;
+        sweep_part<0>(w, ek, ck, Us, Ru, Sc, row, part);
+        sweep_part<1>(w, ek, ck, Us, Ru, Sc, row, part);
+        sweep_part<2>(w, ek, ck, Us, Ru, Sc, row, part);
+        sweep_part<3>(w, ek, ck, Us, Ru, Sc, row, part);
+        if (live) {
+            float4* ed = reinterpret_cast<float4*>(a.err + (int64_t)n * kOuter + (b0 - o) + part * 16);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) ed[v] = make_float4(ek[4 * v], ek[4 * v + 1], ek[4 * v + 2], ek[4 * v + 3]);
+            *reinterpret_cast<uint4*>(a.q + (int64_t)n * a.K + b0 + part * 16) = make_uint4(ck[0], ck[1], ck[2], ck[3]);
+        }
+        if (b0 + kB >= oe) break;
+
+        fetch_block(b0 + kB);  // lands while the push below runs
+        // push the block's errors onto the rest of the outer block
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            *reinterpret_cast<float4*>(&Es[row][part * 16 + 4 * v]) = make_float4(-ek[4 * v], -ek[4 * v + 1], -ek[4 * v + 2], -ek[4 * v + 3]);
+        __syncthreads();
+        float ea[16];  // A operand of the 16 MFMAs of a column tile: row l16, terms 4 ks + q
+#pragma unroll
+        for (int ks = 0; ks < 16; ++ks) ea[ks] = Es[l16][ks * 4 + q];
+        // a lane holds rows 4q .. 4q+3 of column l16 of the output tile
+        int64_t wrow[4];
+        bool wlive[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int nn = blockIdx.x * 16 + 4 * q + v;
+            wlive[v] = nn < a.N;
+            wrow[v] = (int64_t)min(nn, a.N - 1) * a.K;
+        }
+        const float* __restrict__ ub = Ug + (int64_t)(b0 + q) * a.K + l16;  // + 4 ks K + c0
+        // 64 columns (four tiles) per trip, the next trip's operands loaded before this trip's MFMAs: a single wave has
+        // nothing else to cover the loads' latency with
+        v4f acc[4], accn[4];
+        float u[4][16], un[4][16];
+        auto fetch = [&](int c0, v4f (&ac)[4], float (&uu)[4][16]) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) ac[t][v] = a.wp[wrow[v] + c0 + 16 * t + l16];
+#pragma unroll
+                for (int ks = 0; ks < 16; ++ks) uu[t][ks] = ub[(int64_t)ks * 4 * a.K + c0 + 16 * t];
+            }
+        };
+        fetch(b0 + kB, acc, u);
+        for (int c0 = b0 + kB; c0 < oe; c0 += 2 * kB) {  // two trips per iteration so that the buffers swap statically
+            const bool second = c0 + kB < oe;
+            if (second) fetch(c0 + kB, accn, un);
+#pragma unroll
+            for (int ks = 0; ks < 16; ++ks)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ea[ks], u[t][ks], acc[t], 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (wlive[v]) a.wp[wrow[v] + c0 + 16 * t + l16] = acc[t][v];
+            if (!second) break;
+            if (c0 + 2 * kB < oe) fetch(c0 + 2 * kB, acc, u);
+#pragma unroll
+            for (int ks = 0; ks < 16; ++ks)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) accn[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ea[ks], un[t][ks], accn[t], 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (wlive[v]) a.wp[wrow[v] + c0 + kB + 16 * t + l16] = accn[t][v];
+        }
+        stash_block(cur ^ 1);
+        __threadfence_block();  // the next block's working weights were written by other lanes of this wave
+        __syncthreads();
     }
 }
 
@@ -284,56 +376,6 @@ __global__ __launch_bounds__(256) void gptq_update_kernel(GptqArgs a, int u0, in
 #pragma unroll
             for (int j = 0; j < NT; ++j) dst[j * 16] = acc[i][j][v];
         }
-}
-
-// The same update for the 64 errors of one block onto the few hundred remaining columns of its outer block: 64 x 64
-// tiles, 4 x 4 per thread -- many small workgroups, since there is little work and it sits on the critical path
-// between two sequential block kernels.
-__global__ __launch_bounds__(256) void gptq_update_inner_kernel(GptqArgs a, int u0, int e0, int c_begin, int c_end)
-{
-    __shared__ float Es[kB][kB + 1];  // [row][term]
-    __shared__ float Ut[kB][kB];      // [term][column]
-    const int c0 = c_begin + blockIdx.x * kB;
-    const int n0 = blockIdx.y * kB;
-    const int tid = threadIdx.x;
-#pragma unroll
-    for (int it = 0; it < kB * kB / 256; ++it) {
-        const int i = it * 256 + tid;
-        const int r = i / kB, c = i % kB;
-        const int n = min(n0 + r, a.N - 1);
-        Es[r][c] = a.err[(int64_t)n * kOuter + e0 + c];
-        Ut[r][c] = (c0 + c < c_end) ? a.U[(int64_t)(u0 + r) * a.K + c0 + c] : 0.0f;
-    }
-    __syncthreads();
-    const int ty = tid / 16, tx = tid % 16;
-    float acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int n = min(n0 + ty * 4 + i, a.N - 1);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int c = c0 + tx * 4 + k;
-            acc[i][k] = (c < c_end) ? a.wp[(int64_t)n * a.K + c] : 0.0f;
-        }
-    }
-    for (int j = 0; j < kB; ++j) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float e = Es[ty * 4 + i][j];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) acc[i][k] = __fmaf_rn(-e, Ut[j][tx * 4 + k], acc[i][k]);
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int n = n0 + ty * 4 + i;
-        if (n >= a.N) continue;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int c = c0 + tx * 4 + k;
-            if (c < c_end) a.wp[(int64_t)n * a.K + c] = acc[i][k];
-        }
-    }
 }
 
 // codes[n, kb] = code of column 2 kb | code of column 2 kb + 1 << 4, fetched from their visiting positions
@@ -425,14 +467,10 @@ hipError_t launch_gptq_sweep(const void* w, int64_t N, int64_t K, int b, int fmt
     };
     for (int o = 0; o < (int)K; o += kOuter) {
         const int oe = std::min(o + kOuter, (int)K);
-        for (int b0 = o; b0 < oe; b0 += kB) {
-            if (fmt == 0) hipLaunchKernelGGL(gptq_block_kernel<0>, dim3(row16), dim3(64), 0, st, a, b0, b0 - o);
-            else hipLaunchKernelGGL(gptq_block_kernel<1>, dim3(row16), dim3(64), 0, st, a, b0, b0 - o);
-            // the rest of the outer block sees this block's errors at once ...
-            if (b0 + kB < oe)
-                hipLaunchKernelGGL(gptq_update_inner_kernel, dim3((unsigned)((oe - b0 - kB) / kB), (unsigned)((N + 63) / 64)), dim3(256), 0,
-                                   st, a, b0, b0 - o, b0 + kB, oe);
-        }
+        // the outer block itself: every wave sweeps its 16 rows through the block's columns, pushing each 64-column
+        // block's errors onto the rest of the outer block as it goes ...
+        if (fmt == 0) hipLaunchKernelGGL(gptq_outer_kernel<0>, dim3(row16), dim3(64), 0, st, a, o, oe);
+        else hipLaunchKernelGGL(gptq_outer_kernel<1>, dim3(row16), dim3(64), 0, st, a, o, oe);
         // ... everything behind the outer block sees all of its errors in one pass
         if (oe < (int)K) update(o, 0, oe - o, oe, (int)K);
     }
