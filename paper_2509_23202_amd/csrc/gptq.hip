@@ -7,9 +7,9 @@
 //     q = Q(w_j / s),   e = (w_j - q s) / U[j,j],   w_k -= e U[j,k]  for every later column k.
 // Rows never interact, so the sweep is data-parallel over the N rows and strictly sequential along K.  It is blocked
 // 64 columns at a time: four lanes share a row and keep the block's 64 working weights in registers while the 64 x 64
-// triangle of U is read from LDS (block kernel); the block's 64 errors per row then update the later columns of the
-// same 512-column outer block in a rank-64 product, and a finished outer block updates everything behind it in one
-// rank-512 product (update kernel).  Working weights live in visiting order in an fp32 scratch matrix, codes in a
+// triangle of U is read from LDS; the block's 64 errors per row then update the later columns of the same 512-column
+// outer block in a rank-64 product -- both by the wave that owns the 16 rows, one launch per outer block (outer
+// kernel) -- and a finished outer block updates everything behind it in one rank-512 product (update kernel).  Working weights live in visiting order in an fp32 scratch matrix, codes in a
 // byte-per-code scratch matrix, and a last kernel packs them back to the original column positions.
 #include "device_util.hpp"
 #include "internal.hpp"
