@@ -30,7 +30,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 # vector registers saves one v_accvgpr_read per value (the GEMM kernels keep their accumulators where the
 # compiler puts them).
 EXTRA_FLAGS = {"rotate_quantize.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
-               "gemm_fused_decode.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+               "gemm_fused_decode.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+               # (dequantized fragments come out of the vector ALU: as MFMA operands they should stay in vector registers)
+               "gemm_nvfp4.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _compile(src: str) -> Path:

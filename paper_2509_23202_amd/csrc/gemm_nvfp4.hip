@@ -20,6 +20,8 @@
 #include "layout.hpp"
 #include "nv_dequant.hpp"
 
+#include <cmath>
+
 namespace fp4mr {
 namespace {
 
@@ -65,37 +67,30 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_nv_kernel(NvG
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    // the wave index is uniform across the wavefront: telling the compiler keeps every fragment's position in scalar
+    // registers, so that the loads below cost no vector address arithmetic (the vector ALU is what bounds this kernel)
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int wm = wave % NWM, wn = wave / NWM;
     const int tm = blockIdx.x % g.tiles_m, tn = blockIdx.x / g.tiles_m;
 
     const int64_t KC = g.K >> 7;
     const int KT = (int)KC;
-    const int64_t rbx_max = (g.M + 15) / 16 - 1, rbw_max = (g.N + 15) / 16 - 1;
-
-    const uint8_t* gsrc[LPW];
-    const uint8_t* ssrc[LPW];
-    int foff[LPW];
-#pragma unroll
-    for (int i = 0; i < LPW; ++i) {
-        const int f = min(wave + i * NW, F - 1);
-        int64_t rb;
-        const uint8_t *cbase, *sbase;
-        if (f < FX) {
-            rb = (int64_t)tm * FX + f;
-            rb = rb > rbx_max ? rbx_max : rb;
-            cbase = g.a_codes;
-            sbase = g.a_scales;
-        } else {
-            rb = (int64_t)tn * FW + (f - FX);
-            rb = rb > rbw_max ? rbw_max : rb;
-            cbase = g.w_codes;
-            sbase = g.w_scales;
-        }
-        gsrc[i] = cbase + rb * KC * 1024 + lane * 16;
-        ssrc[i] = sbase + rb * KC * 128 + (lane & 31) * 4;
-        foff[i] = f;
-    }
+    // Operands are addressed through buffer resources based at the tile's first row-block: one VGPR (16 or 4 times the
+    // lane) is the only per-lane address, every fragment's position is a scalar offset.  Row-blocks past the end of an
+    // operand (last tile) are clamped to its last row-block: the duplicates only feed outputs that are never stored.
+    const int a_rbs = (int)((g.M + 15) / 16), w_rbs = (int)((g.N + 15) / 16);
+    const int a_rb0 = min(tm * FX, a_rbs - 1), w_rb0 = min(tn * FW, w_rbs - 1);
+    const int a_rb_last = a_rbs - 1 - a_rb0, w_rb_last = w_rbs - 1 - w_rb0;
+    auto make_rsrc = [](const uint8_t* base, int64_t bytes) {
+        const uint32_t n = bytes > 0xffffffffll ? 0xffffffffu : (uint32_t)bytes;
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, (int)n, 0x00020000);
+    };
+    const __amdgpu_buffer_rsrc_t rs_ac = make_rsrc(g.a_codes + (int64_t)a_rb0 * KC * 1024, (int64_t)(a_rbs - a_rb0) * KC * 1024);
+    const __amdgpu_buffer_rsrc_t rs_wc = make_rsrc(g.w_codes + (int64_t)w_rb0 * KC * 1024, (int64_t)(w_rbs - w_rb0) * KC * 1024);
+    const __amdgpu_buffer_rsrc_t rs_as = make_rsrc(g.a_scales + (int64_t)a_rb0 * KC * 128, (int64_t)(a_rbs - a_rb0) * KC * 128);
+    const __amdgpu_buffer_rsrc_t rs_ws = make_rsrc(g.w_scales + (int64_t)w_rb0 * KC * 128, (int64_t)(w_rbs - w_rb0) * KC * 128);
+    const uint32_t lane16 = (uint32_t)lane * 16u, lane4 = (uint32_t)(lane & 31) * 4u;
+    const int kc_bytes = (int)KC * 1024, ks_bytes = (int)KC * 128;
 
     v4f acc[TN][TM];
 #pragma unroll
@@ -107,11 +102,21 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_nv_kernel(NvG
         char* base = smem + (kt % STAGES) * STAGE_BYTES;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            __builtin_amdgcn_global_load_lds((global_void*)(gsrc[i] + (int64_t)kt * 1024), (lds_void*)(base + foff[i] * 1024), 16, 0, 0);
-            // direct-to-LDS loads place lane l's data at 4*l whatever the access size is below a dword, so the
-            // 128-byte scale block is copied as 32 lanes x 4 bytes (the upper half-wave is masked off)
-            if (lane < 32)
-                __builtin_amdgcn_global_load_lds((global_void*)(ssrc[i] + (int64_t)kt * 128), (lds_void*)(base + SCALE_OFF + foff[i] * 128), 4, 0, 0);
+            const int f = min(wave + i * NW, F - 1);  // spare slots re-copy the last fragment (same bytes to the same place)
+            const bool is_x = (FX % NW == 0) ? (i < FX / NW) : (f < FX);
+            if (is_x) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_ac, (lds_void*)(base + f * 1024), 16, lane16, min(f, a_rb_last) * kc_bytes + kt * 1024, 0, 0);
+            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_wc, (lds_void*)(base + f * 1024), 16, lane16, min(f - FX, w_rb_last) * kc_bytes + kt * 1024, 0, 0);
+        }
+        // direct-to-LDS loads place lane l's data at 4*l whatever the access size is below a dword, so a 128-byte scale
+        // block is copied as 32 lanes x 4 bytes (the upper half-wave is masked off; one branch for all the blocks)
+        if (lane < 32) {
+#pragma unroll
+            for (int i = 0; i < LPW; ++i) {
+                const int f = min(wave + i * NW, F - 1);
+                const bool is_x = (FX % NW == 0) ? (i < FX / NW) : (f < FX);
+                if (is_x) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_as, (lds_void*)(base + SCALE_OFF + f * 128), 4, lane4, min(f, a_rb_last) * ks_bytes + kt * 128, 0, 0);
+                else __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_ws, (lds_void*)(base + SCALE_OFF + f * 128), 4, lane4, min(f - FX, w_rb_last) * ks_bytes + kt * 128, 0, 0);
+            }
         }
     };
 
@@ -223,10 +228,25 @@ hipError_t launch_gemm_nvfp4(const void* a_codes, const void* a_scales, const fl
     g.M = M;
     g.N = N;
     g.K = K;
-    if (variant == 0) variant = (M <= 16) ? 2 : 1;
+    if (variant == 0) {
+        if (M <= 16) variant = 2;
+        else {
+            // 256 x 256 tiles on eight waves (wave tile 64 x 128: 12 fragment conversions per 128 MFMAs, against 8 per 64
+            // with 128 x 128 tiles on four waves) when they tile the chip in no more time: rounds of workgroups times
+            // (fixed cost + K-steps x measured step time; the small tile runs two workgroups per compute unit)
+            int cus = 256, dev = 0;
+            if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+            const double kt = (double)(K >> 7);
+            auto tiles = [&](int bm, int bn) { return (double)((M + bm - 1) / bm) * (double)((N + bn - 1) / bn); };
+            const double t3 = ceil(tiles(256, 256) / cus) * (10.0 + kt * 3.47);
+            const double t1 = ceil(tiles(128, 128) / (2.0 * cus)) * (8.0 + kt * 2.0);
+            variant = t3 < t1 ? 3 : 1;
+        }
+    }
     switch (variant) {
         case 1: return launch_variant<128, 128, 64, 64, 4>(g, out_f32, st);
         case 2: return launch_variant<16, 256, 16, 64, 4>(g, out_f32, st);
+        case 3: return launch_variant<256, 256, 64, 128, 4>(g, out_f32, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -205,6 +205,15 @@ def test_gemm_mxfp4_every_tile_variant(fp4, oracle, variant, monkeypatch):
     _gemm_case(fp4, oracle, MX, 272, 528, 1280, seed=variant, out_f32=True, layout_gemm=True)
 
 
+@pytest.mark.parametrize("out_f32", [False, True])
+@pytest.mark.parametrize("variant", [1, 2, 3])
+def test_gemm_nvfp4_every_tile_variant(fp4, oracle, variant, out_f32, monkeypatch):
+    """128 x 128, 16 x 256 and 256 x 256 tiles of the dequantizing NVFP4 kernel on a ragged tile grid (last tile row and
+    column partly outside: clamped row-blocks, masked stores), K not a multiple of 512."""
+    monkeypatch.setenv("FP4MR_GEMM_VARIANT", str(variant))
+    _gemm_case(fp4, oracle, NV, 272, 528, 1280, seed=30 + variant, out_f32=out_f32, layout_gemm=True)
+
+
 @pytest.mark.parametrize("variant", [2, 5, 10, 13, 15])
 def test_gemm_mxfp4_tile_variants_bf16_output_through_the_staged_epilogue(fp4, oracle, variant, monkeypatch):
     """bf16 output goes through the LDS transpose of the epilogue, whose chunk swizzle depends on the wave tile's width
