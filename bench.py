@@ -402,6 +402,44 @@ def main():
         except Exception as exc:  # noqa: BLE001 - reported in the JSON line
             extras_errors["gptq_offline"] = repr(exc)
 
+        try:
+            # ---- NVFP4 prefill on Llama-3-70B-shaped layers (M = 4096): the dequantizing fp16-MFMA kernel against the bf16
+            # library GEMM on the same shapes
+            nv = {}
+            for name, Kn, Nn in (("qkv", 8192, 10240), ("gate_up", 8192, 57344), ("down", 28672, 8192)):
+                xn = torch.randn(M, Kn, device="cuda").to(torch.bfloat16)
+                wn = (torch.randn(Nn, Kn, device="cuda") * 0.02).to(torch.bfloat16)
+                qa = fp4.fp4_rotate_quantize(xn, 16, fp4.NVFP4, flags=fp4.LAYOUT_GEMM)
+                qw = fp4.fp4_quantize_weights(wn, 16, fp4.NVFP4, flags=fp4.LAYOUT_GEMM)
+                on = torch.empty((M, Nn), dtype=torch.bfloat16, device="cuda")
+                gfl = fp4.A_LAYOUT_GEMM | fp4.W_LAYOUT_GEMM
+
+                def run_nv():
+                    fp4.fp4_gemm(qa[0], qa[1], qa[2], qw[0], qw[1], qw[2], M, Nn, Kn, fp4.NVFP4, flags=gfl, out=on)
+
+                def run_bf():
+                    torch.matmul(xn, wn.t(), out=on)
+
+                def time_us(fn, n=12):
+                    for _ in range(4):
+                        fn()
+                    torch.cuda.synchronize()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(n):
+                        fn()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    return e0.elapsed_time(e1) / n * 1e3
+                tn, tb = time_us(run_nv), time_us(run_bf)
+                fl = 2.0 * M * Nn * Kn
+                nv[name] = {"K": Kn, "N": Nn, "gemm_us": round(tn, 1), "gemm_tflops": round(fl / tn / 1e6, 1),
+                            "bf16_gemm_us": round(tb, 1), "speedup_vs_bf16": round(tb / tn, 3)}
+                del xn, wn, qa, qw, on
+            result["nvfp4_prefill_70b_shapes"] = nv
+        except Exception as exc:  # noqa: BLE001 - reported in the JSON line
+            extras_errors["nvfp4_prefill"] = repr(exc)
+
         if extras_errors:
             result["extras_errors"] = extras_errors
 
