@@ -124,20 +124,35 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_nv_kernel(NvG
     for (int s = 0; s < STAGES - 1; ++s)
         if (s < KT) issue(s);
 
+    // The X fragments of a step are read from LDS (as codes) at the end of the step before, so that their latency runs
+    // under that step's last MFMAs instead of stalling both waves of a SIMD at the top of the step; that needs stage
+    // kt + 1 in LDS when step kt starts, so one stage (not two) may be in flight at the top of a step.
+    static_assert(STAGES >= 4, "one stage in flight, one being read ahead, one being consumed, one being refilled");
+    v4i xcode[TM];
+    uint32_t xscale[TM];
+    auto read_x = [&](int kt) {
+        const char* base = smem + (kt % STAGES) * STAGE_BYTES;
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int f = wm * TM + j;
+            xcode[j] = *(reinterpret_cast<const v4i*>(base + f * 1024) + lane);
+            xscale[j] = *(reinterpret_cast<const uint16_t*>(base + SCALE_OFF + f * 128) + lane);
+        }
+    };
+    // stage 0: with all STAGES - 1 stages of the prologue issued, the STAGES - 2 behind it may still be in flight
+    if (KT >= STAGES - 1) wait_vmcnt<(STAGES - 2) * 2 * LPW>(); else wait_vmcnt<0>();
+    block_barrier();
+    read_x(0);
+
     for (int kt = 0; kt < KT; ++kt) {
-        if (kt + STAGES - 2 < KT) wait_vmcnt<(STAGES - 2) * 2 * LPW>(); else wait_vmcnt<0>();
+        if (kt + STAGES - 2 < KT) wait_vmcnt<(STAGES - 3) * 2 * LPW>(); else wait_vmcnt<0>();  // stage kt + 1 has landed
         block_barrier();
         if (kt + STAGES - 1 < KT) issue(kt + STAGES - 1);
 
         const char* base = smem + (kt % STAGES) * STAGE_BYTES;
         NvFrag16 xf[TM];
 #pragma unroll
-        for (int j = 0; j < TM; ++j) {
-            const int f = wm * TM + j;
-            const v4i c = *(reinterpret_cast<const v4i*>(base + f * 1024) + lane);
-            const uint32_t sc = *(reinterpret_cast<const uint16_t*>(base + SCALE_OFF + f * 128) + lane);
-            xf[j] = nv_dequant_frag(c, sc);
-        }
+        for (int j = 0; j < TM; ++j) xf[j] = nv_dequant_frag(xcode[j], xscale[j]);
 #pragma unroll
         for (int i = 0; i < TN; ++i) {
             const int f = FX + wn * TN + i;
@@ -150,6 +165,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_nv_kernel(NvG
                 for (int s = 0; s < 4; ++s)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf.s[s], xf[j].s[s], acc[i][j], 0, 0, 0);
         }
+        read_x(kt + 1);  // (past the last step: stale bytes of the ring that nothing consumes)
     }
 
     const float ts = (*g.a_ts) * (*g.w_ts);
