@@ -20,6 +20,7 @@
 #include "layout.hpp"
 #include "nv_dequant.hpp"
 
+#include <algorithm>
 #include <cmath>
 
 namespace fp4mr {
@@ -35,6 +36,7 @@ struct NvGemmArgs {
     void* out;
     int64_t M, N, K;
     int tiles_m, tiles_n;
+    int tn0, tn_count;  // this launch covers the tile columns tn0 .. tn0 + tn_count - 1 (tn_count = 0: all of them)
 };
 
 template <int N>
@@ -71,7 +73,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_nv_kernel(NvG
     // registers, so that the loads below cost no vector address arithmetic (the vector ALU is what bounds this kernel)
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int wm = wave % NWM, wn = wave / NWM;
-    const int tm = blockIdx.x % g.tiles_m, tn = blockIdx.x / g.tiles_m;
+    const int tm = blockIdx.x % g.tiles_m, tn = g.tn0 + blockIdx.x / g.tiles_m;
 
     const int64_t KC = g.K >> 7;
     const int KT = (int)KC;
@@ -213,7 +215,9 @@ hipError_t launch_variant(const NvGemmArgs& g0, bool out_f32, hipStream_t st)
     g.tiles_n = (int)((g.N + BN - 1) / BN);
     constexpr int threads = (BM / WM) * (BN / WN) * 64;
     constexpr size_t lds = (size_t)STAGES * (BM + BN) / 16 * (1024 + 128);
-    const dim3 grid((unsigned)(g.tiles_m * g.tiles_n));
+    const int cols = g.tn_count > 0 ? std::min(g.tn_count, g.tiles_n - g.tn0) : g.tiles_n - g.tn0;
+    if (cols <= 0) return hipSuccess;
+    const dim3 grid((unsigned)(g.tiles_m * cols));
     hipError_t e;
     if (out_f32) {
         auto k = gemm_nv_kernel<BM, BN, WM, WN, STAGES, true>;
@@ -254,9 +258,28 @@ hipError_t launch_gemm_nvfp4(const void* a_codes, const void* a_scales, const fl
             if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
             const double kt = (double)(K >> 7);
             auto tiles = [&](int bm, int bn) { return (double)((M + bm - 1) / bm) * (double)((N + bn - 1) / bn); };
-            const double t3 = ceil(tiles(256, 256) / cus) * (10.0 + kt * 3.47);
-            const double t1 = ceil(tiles(128, 128) / (2.0 * cus)) * (8.0 + kt * 2.0);
+            const double s3 = 10.0 + kt * 3.47, s1 = 8.0 + kt * 1.94;  // one round of each tile, microseconds
+            const double t3 = ceil(tiles(256, 256) / cus) * s3;
+            const double t1 = ceil(tiles(128, 128) / (2.0 * cus)) * s1;
             variant = t3 < t1 ? 3 : 1;
+            // Whole rounds of 256 x 256 tiles for the tile columns they fill, the remaining columns as 128 x 128 tiles in a
+            // second launch: N = 10240 at M = 4096 is 640 big tiles = two and a half rounds -- two rounds of them and one
+            // round of 512 small tiles instead of three rounds (or five of small tiles).
+            const int tiles_m = (int)((M + 255) / 256), tiles_n = (int)((N + 255) / 256);
+            const int full_cols = (int)((int64_t)(tiles_m * tiles_n / cus) * cus / tiles_m);  // tile columns inside whole rounds
+            if (full_cols > 0 && full_cols < tiles_n) {
+                const double rest = (double)((M + 127) / 128) * (double)((N - (int64_t)full_cols * 256 + 127) / 128);
+                const double ts = ceil((double)full_cols * tiles_m / cus) * s3 + ceil(rest / (2.0 * cus)) * s1;
+                if (ts < 0.97 * std::min(t3, t1)) {
+                    g.tn0 = 0;
+                    g.tn_count = full_cols;
+                    const hipError_t e = launch_variant<256, 256, 64, 128, 4>(g, out_f32, st);
+                    if (e != hipSuccess) return e;
+                    g.tn0 = full_cols * 2;
+                    g.tn_count = 0;
+                    return launch_variant<128, 128, 64, 64, 4>(g, out_f32, st);
+                }
+            }
         }
     }
     switch (variant) {

@@ -178,3 +178,11 @@ def test_short_k_layers_take_the_two_workgroups_per_unit_tiles(fp4, oracle, M, N
     """K = 1024 with more 256 x 256 tiles than one round of compute units: the shape rule picks 128 x 256 tiles, two
     workgroups per unit -- one round for the first shape, persistent workgroups with ragged edge tiles for the second."""
     check_layer(fp4, oracle, inputs.RECIPES[3], M, 1024, N, MX, 32, n_m=48, n_n=64, salt=M)
+
+
+@pytest.mark.parametrize("M,N", [(2048, 10240), (2053, 10248)])
+def test_nvfp4_two_launch_split_of_the_tile_grid(fp4, oracle, M, N):
+    """More 256 x 256 tiles than one round of compute units and a partial round left over: the shape rule runs the tile
+    columns that fill whole rounds as 256 x 256 tiles and the remaining columns as 128 x 128 tiles in a second launch
+    (ragged last tile row and column in the second case)."""
+    check_layer(fp4, oracle, inputs.RECIPES[4], M, 512, N, NV, 16, n_m=48, n_n=96, salt=M)
