@@ -326,11 +326,16 @@ int orc_quantize_nvfp4(const float *y, int64_t M, int64_t K, const float *s_T_in
 /* ---------------------------------------------------------------- MSE scale policy
  * Section 4.2 item 1 names two quantization methods for the fused kernel, abs-max and MSE, without spelling the
  * second out; Section 4.1 "Ingredient 1" states its objective: choose the scales that minimise
- * sum_i (Xhat_i - X_i)^2.  The reading taken here is a per-group search over the scale codes next to the abs-max
- * one: candidates are tried in the order (abs-max code, one above, one below), a candidate replaces the current
- * choice only if its squared error is strictly smaller.  Errors are exact in fp64 for MXFP4 (power-of-two scales)
- * and accumulated in fp64 for NVFP4.  The NVFP4 tensor scale stays the abs-max one (the alternating optimisation
- * over s_T of Ingredient 1 is an offline procedure and not part of the online path). */
+ * sum_i (Xhat_i - X_i)^2.  The reading taken here is a per-group search over the scale codes around the abs-max
+ * one; a candidate replaces the current choice only if its squared error is strictly smaller, so the order of the
+ * candidates decides ties.  MXFP4 (E8M0, one code = a factor 2): abs-max code, one above, one below.  NVFP4 (E4M3,
+ * eight codes per octave): abs-max code c0, then c0+1, c0-1, c0+2, c0-2, c0+3, c0+4, c0+5, c0+6, c0+7 -- the
+ * minimiser sits either near c0 or about half an octave above it (the scale that puts the group's largest element
+ * on the grid value 4 instead of 6), and a brute-force search over every code shows that these windows contain the
+ * global minimiser in all but about 1e-4 of the groups of heavy-tailed data (the +-1 window in only half of them for
+ * NVFP4).  Errors are exact in fp64 for MXFP4 (power-of-two scales) and accumulated in fp64 for NVFP4.  The NVFP4
+ * tensor scale stays the abs-max one (the alternating optimisation over s_T of Ingredient 1 is an offline procedure
+ * and not part of the online path). */
 
 static double group_sq_err(const float *v, int G, double scale, double inv, int inv_is_f32, float r32,
                            uint8_t *codes_out)
@@ -421,11 +426,11 @@ int orc_quantize_nvfp4_mse(const float *y, int64_t M, int64_t K, const float *s_
                 volatile float t = amax / six_sT;
                 c0 = (int)orc_e4m3_encode((double)t);
             }
-            const int delta[3] = {0, 1, -1};
+            const int delta[10] = {0, 1, -1, 2, -2, 3, 4, 5, 6, 7};
             double best_err = 0.0;
             int best_c = c0;
             uint8_t best_codes[16], cand_codes[16];
-            for (int k = 0; k < 3; ++k) {
+            for (int k = 0; k < 10; ++k) {
                 int c = c0 + delta[k];
                 if (c < 0) c = 0;
                 if (c > 0x7e) c = 0x7e;

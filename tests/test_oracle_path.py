@@ -436,7 +436,12 @@ def test_mse_policy_never_loses_to_absmax_and_moves_by_one_code(oracle, fmt):
     e0 = _group_err(y, oracle.dequantize(c0, s0, fmt, T0), G)
     e1 = _group_err(y, oracle.dequantize(c1, s1, fmt, T1), G)
     assert np.all(e1 <= e0)                  # abs-max is one of the candidates
-    assert np.all(np.abs(s1.astype(int) - s0.astype(int)) <= 1)
+    move = s1.astype(int) - s0.astype(int)
+    if fmt == MX:
+        assert np.all(np.abs(move) <= 1)     # E8M0: the abs-max byte and its two neighbours
+    else:
+        assert move.min() >= -2 and move.max() <= 7   # E4M3: two codes below to seven above
+        assert (move >= 3).mean() > 0.1      # the second mode of the minimiser (largest element on 4 instead of 6) is found
     assert (s1 != s0).mean() > 0.05          # and the search is not vacuous on heavy-tailed data
     assert e1.sum() < 0.97 * e0.sum()
     # where the scale did not move, nothing else did
@@ -492,7 +497,7 @@ def test_mse_policy_nvfp4_candidates_by_independent_recipe(oracle):
         for g in range(8):
             v = yg[m, g]
             best, best_c = None, None
-            for d in (0, 1, -1):
+            for d in (0, 1, -1, 2, -2, 3, 4, 5, 6, 7):
                 code = int(np.clip(int(s_abs[m, g]) + d, 0, 0x7e))
                 sg = torch.tensor([code], dtype=torch.uint8).view(torch.float8_e4m3fn).float().numpy()[0]
                 dd = np.float32(T) * np.float32(sg)
@@ -511,6 +516,72 @@ def test_mse_policy_nvfp4_candidates_by_independent_recipe(oracle):
                 if best is None or err < best:
                     best, best_c = err, code
             assert s[m, g] == best_c
+
+
+def _e2m1_round_np(t):
+    """Nearest E2M1 value by thresholds (midpoints go to the neighbour with an even mantissa bit), saturating."""
+    a = np.abs(t)
+    mids = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0])
+    idx = np.searchsorted(mids, a, side="left")          # a == midpoint: the lower neighbour for now
+    idx = np.where(np.isin(a, mids) & (idx % 2 == 1), idx + 1, idx)   # ... unless its code is odd
+    return np.sign(t) * E2M1_GRID[idx]
+
+
+def _mse_inputs():
+    """Rotated values of the three activation recipes of the benchmark configurations (normal + outlier channels,
+    Student-t, Laplace + outlier channels), a few thousand groups each."""
+    from paper_2509_23202_amd import inputs
+    return [(rid, b, inputs.RECIPES[rid].x(48, 2048, salt=rid)) for rid, b in ((1, 32), (4, 16), (6, 32), (6, 128))]
+
+
+def test_mse_policy_mxfp4_reaches_the_global_minimum_over_every_scale_byte(oracle):
+    """Section 4.1 "Ingredient 1" asks for the scales that MINIMISE sum (xhat - x)^2.  Brute force: every E8M0 byte
+    0..254 for every group, independent NumPy arithmetic; the three-candidate search must land on a global minimiser
+    (equal error) in at least 99.9 % of the groups.  Measured: 100 % on all four inputs."""
+    for rid, b, xb in _mse_inputs():
+        y = oracle.rotate(xb, b)
+        c, s, _ = oracle.quantize(y, MX, policy="mse")
+        g = y.astype(np.float64).reshape(-1, 32)
+        chosen = ((oracle.dequantize(c, s, MX).reshape(-1, 32) - g) ** 2).sum(1)
+        best = np.full(len(g), np.inf)
+        for e in range(255):
+            sc = 2.0 ** (e - 127)
+            best = np.minimum(best, ((_e2m1_round_np(g / sc) * sc - g) ** 2).sum(1))
+        nz = np.abs(g).max(1) > 0
+        rate = float((chosen <= best * (1 + 1e-12))[nz].mean())
+        print(f"MXFP4 MSE search, recipe {rid} block {b}: global minimiser found in {rate * 100:.3f}% of {int(nz.sum())} groups")
+        assert np.all(chosen >= best * (1 - 1e-12))       # the brute force really is a lower bound
+        assert rate >= 0.999
+
+
+def test_mse_policy_nvfp4_reaches_the_global_minimum_over_every_scale_code(oracle):
+    """The same for NVFP4: every E4M3 code 0..0x7e per group with the abs-max tensor scale, elements encoded by the
+    format's own rule (binary32 product with the rounded reciprocal).  The ten-candidate window (two codes below the
+    abs-max code to seven above) must contain a global minimiser in at least 99.9 % of the groups; the three-candidate
+    window it replaced managed 51-60 %.  Measured: 99.99-100 %."""
+    e4 = np.array([(c & 7) * 2.0 ** -9 if (c >> 3) == 0 else (1 + (c & 7) / 8) * 2.0 ** ((c >> 3) - 7) for c in range(0x7f)])
+    for rid, b, xb in _mse_inputs():
+        y = oracle.rotate(xb, b)
+        c, s, T = oracle.quantize(y, NV, policy="mse")
+        g32 = y.reshape(-1, 16)
+        g = g32.astype(np.float64)
+        chosen = ((oracle.dequantize(c, s, NV, T).reshape(-1, 16) - g) ** 2).sum(1)
+        best = np.full(len(g), np.inf)
+        for code in range(0x7f):
+            d = np.float32(T) * np.float32(e4[code])
+            if d == 0:
+                err = (g ** 2).sum(1)
+            else:
+                t = (g32 * (np.float32(1.0) / d)).astype(np.float32).astype(np.float64)
+                err = ((_e2m1_round_np(t) * (float(T) * float(e4[code])) - g) ** 2).sum(1)    # xhat = s_T s_G q, exact
+            best = np.minimum(best, err)
+        nz = np.abs(g).max(1) > 0
+        # (the search itself measures its candidates against the binary32 product s_T s_G: 6e-8 relative away)
+        rate = float((chosen <= best * (1 + 1e-6))[nz].mean())
+        print(f"NVFP4 MSE search, recipe {rid} block {b}: global minimiser found in {rate * 100:.3f}% of {int(nz.sum())} groups; "
+              f"squared error {chosen[nz].sum() / best[nz].sum():.5f} of the optimum")
+        assert np.all(chosen >= best * (1 - 1e-12))
+        assert rate >= 0.999
 
 
 # ---------------------------------------------------------------- weight-only (W4A16) reference
