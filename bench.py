@@ -2,6 +2,7 @@
 """Benchmark of the micro-rotated FP4 linear-layer hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
+    python bench.py --summarize-db <rocprofv3 *_results.db> [--pmc]      (no GPU: prints the tables kept under profiles/)
 
 A "step" is one pass of the whole hot path -- fused Hadamard rotation + MXFP4 quantization of the bf16
 activations, then the W4A4 FP4 GEMM against weights that were rotated and quantized ahead of time -- over the
@@ -23,14 +24,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP4_TFLOPS = 10100.0     # MI355X dense FP4/FP6 MFMA
-PEAK_BF16_TFLOPS = 2500.0
+PEAK_F16_TFLOPS = 2500.0      # dense fp16 / bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 RQ_BYTES_PER_ELEM_MX = 2.0 + 0.5 + 1.0 / 32.0   # bf16 in, 4-bit code out, one scale byte per 32
-# HBM-side bytes per launch from hardware counters (FETCH_SIZE, WRITE_SIZE; two rocprofv3 --pmc runs of this script,
-# each scaled by the reading for a plain 1 GiB device copy: x2.000 and x1.000).  Summary and commands:
-# profiles/hbm_traffic__llama3_8b_prefill_m4096_and_rq_16384x8192__pmc.txt
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 265.9e6    # mean over the four GEMMs of a step (fetched + written; 89.5 MB of it is the outputs)
-RQ_TRAFFIC_BYTES_PER_LAUNCH = 339.9e6      # [16384, 8192]: 268.6 MB fetched + 71.3 MB written (algorithmic: 339.7 MB)
+MIN_EVENT_SAMPLES = 8          # per kernel of the step, whatever --steps is
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic__llama3_8b_prefill_m4096_and_rq_16384x8192__pmc.txt")
 
 
 def parse():
@@ -40,10 +38,47 @@ def parse():
     ap.add_argument("--warmup", type=int, default=24)
     ap.add_argument("--tokens", type=int, default=4096, help="M of the prefill workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip the bf16 baseline and the standalone rotate+quantize figure")
+    ap.add_argument("--no-extras", action="store_true", help="skip every side measurement (baselines, ceilings, other configurations)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for HBM-traffic counters under a profiler)")
+    ap.add_argument("--summarize-db", metavar="DB", help="print the per-kernel table of a rocprofv3 results database and exit")
+    ap.add_argument("--pmc", action="store_true", help="with --summarize-db: the database holds --pmc counters, not a kernel trace")
     return ap.parse_args()
+
+
+# --------------------------------------------------------------------------------------------------------------
+# profiles/: the tables kept there are these group-bys over rocprofv3's own SQLite output
+def summarize_db(path, pmc):
+    import sqlite3
+    c = sqlite3.connect(path)
+    clean = lambda n: (n or "").replace("fp4mr::(anonymous namespace)::", "").replace("void ", "")
+    if not pmc:
+        rows = c.execute("select name, count(*), sum(duration), avg(duration), min(duration), max(duration), grid_x, workgroup_x, "
+                         "lds_size, vgpr_count, accum_vgpr_count from kernels group by name, grid_x order by sum(duration) desc").fetchall()
+        tot = sum(r[2] for r in rows) or 1
+        print(f"{'kernel':<78} {'calls':>5} {'total_us':>10} {'avg_us':>9} {'min_us':>9} {'max_us':>9} {'pct':>6} {'grid':>8} {'wg':>4} {'lds':>7} {'vgpr':>4} {'agpr':>4}")
+        for r in rows:
+            print(f"{clean(r[0])[:76]:<78} {r[1]:>5} {r[2] / 1e3:>10.1f} {r[3] / 1e3:>9.2f} {r[4] / 1e3:>9.2f} {r[5] / 1e3:>9.2f} "
+                  f"{100 * r[2] / tot:>6.2f} {r[6]:>8} {r[7]:>4} {r[8]:>7} {r[9]:>4} {r[10]:>4}")
+        return
+    rows = c.execute("select kernel_name, counter_name, grid_size_x, count(*), avg(value), min(value), max(value) from counters_collection "
+                     "group by kernel_name, counter_name, grid_size_x order by sum(value) desc").fetchall()
+    print(f"{'kernel':<70} {'counter':<11} {'grid':>9} {'calls':>5} {'avg_KiB':>12} {'min_KiB':>12} {'max_KiB':>12}")
+    for r in rows:
+        print(f"{clean(r[0])[:68]:<70} {r[1]:<11} {r[2]:>9} {r[3]:>5} {r[4]:>12.1f} {r[5]:>12.1f} {r[6]:>12.1f}")
+
+
+def committed_traffic():
+    """HBM-side bytes per launch from the committed counter summary (two rocprofv3 --pmc runs of this script, scaled by
+    what the same counters read for a plain copy of known size): its last line is a JSON object."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in reversed(f.read().splitlines()):
+                if line.startswith("TRAFFIC_JSON "):
+                    return json.loads(line[len("TRAFFIC_JSON "):])
+    except (OSError, ValueError):
+        pass
+    return {}
 
 
 def to_dev_bf16(bits):
@@ -51,32 +86,38 @@ def to_dev_bf16(bits):
     return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
 
 
-def event_ms(pairs):
-    return [a.elapsed_time(b) for a, b in pairs]
-
-
-def cpu_baseline(recipe, layer, M_sample, N_sample):
+def cpu_baseline(recipe, layer, M_sample, N_sample, threads=None):
     """The oracle as it stands, on a bounded sample of the same workload: rotate+quantize of M_sample tokens and
     the fp64 product against N_sample pre-quantized weight rows (weight preparation is offline for both sides)."""
     from oracle import reference as R
     K = layer.K
+    all_threads = R.max_threads()
     xb = recipe.x(M_sample, K)
     wb = recipe.w(N_sample, K)
     wc, wsc, wT, _ = R.rotate_quantize(wb, recipe.had_block, R.MXFP4)
     W = R.dequantize(wc, wsc, R.MXFP4, wT)
-    t0 = time.perf_counter()
-    ac, asc, aT, _ = R.rotate_quantize(xb, recipe.had_block, R.MXFP4)
-    A = R.dequantize(ac, asc, R.MXFP4, aT)
-    R.matmul(A, W, want_abs=False)
-    dt = time.perf_counter() - t0
+    if threads:
+        R.set_threads(threads)
+    try:
+        t0 = time.perf_counter()
+        ac, asc, aT, _ = R.rotate_quantize(xb, recipe.had_block, R.MXFP4)
+        A = R.dequantize(ac, asc, R.MXFP4, aT)
+        R.matmul(A, W, want_abs=False)
+        dt = time.perf_counter() - t0
+    finally:
+        if threads:
+            R.set_threads(all_threads)
     flops = 2.0 * M_sample * N_sample * K
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": R.max_threads(), "kind": "oracle",
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": threads or all_threads, "kind": "oracle",
             "sample": f"{layer.name} layer, {M_sample} of the tokens x {N_sample} of the {layer.N} output features, K={K}: "
                       f"rotate+quantize X, dequantize, fp64 product ({dt:.1f} s)"}
 
 
 def main():
     args = parse()
+    if args.summarize_db:
+        summarize_db(args.summarize_db, args.pmc)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives exist in the path); use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -92,6 +133,7 @@ def main():
     b = recipe.had_block
     GL = fp4.LAYOUT_GEMM
     gflags = fp4.A_LAYOUT_GEMM | fp4.W_LAYOUT_GEMM
+    ev_pair = lambda: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
 
     # ---- inputs resident in HBM; weights rotated + quantized ahead of time (not timed)
     state = []
@@ -114,12 +156,12 @@ def main():
         for li, s in enumerate(state):
             L = s["L"]
             if probe == 2 * li:
-                e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True); e0.record()
+                e0, e1 = ev_pair(); e0.record()
             fp4.fp4_rotate_quantize(s["x"], b, fp4.MXFP4, flags=GL, codes=s["ac"], scales=s["asc"])
             if probe == 2 * li:
                 e1.record(); ev.append((L.name, "rq", e0, e1))
             if probe == 2 * li + 1:
-                e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True); e0.record()
+                e0, e1 = ev_pair(); e0.record()
             fp4.fp4_gemm(s["ac"], s["asc"], None, s["wc"], s["ws"], None, M, L.N, L.K, fp4.MXFP4, flags=gflags, out=s["out"])
             if probe == 2 * li + 1:
                 e1.record(); ev.append((L.name, "gemm", e0, e1))
@@ -131,13 +173,14 @@ def main():
     # An event pair around a launch also times the dispatch hand-off on both sides of it (a few microseconds that
     # back-to-back launches hide).  Calibrate that bracket overhead on a launch that does almost no work (a 16 x 128
     # quantize, ~2 KB) and subtract it, so that the per-kernel figures line up with a kernel trace.
+    N_CAL = 20
     tiny_x = torch.zeros((16, 128), dtype=torch.bfloat16, device="cuda")
     tiny_c = torch.empty(fp4.packed_bytes(16, 128, fp4.MXFP4, GL)[0], dtype=torch.uint8, device="cuda")
     tiny_s = torch.empty(fp4.packed_bytes(16, 128, fp4.MXFP4, GL)[1], dtype=torch.uint8, device="cuda")
     cal = []
-    for _ in range(20):
+    for _ in range(N_CAL):
         step()  # keep the queue in the same state as in the timed loop
-        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        e0, e1 = ev_pair()
         e0.record()
         fp4.fp4_rotate_quantize(tiny_x, b, fp4.MXFP4, flags=GL, codes=tiny_c, scales=tiny_s)
         e1.record()
@@ -153,18 +196,20 @@ def main():
     dt = time.perf_counter() - t0
     TINY_KERNEL_MS = 0.0035  # the calibration launch itself (one wave, one fragment; 3.4-4.1 us in a kernel trace)
     bracket_ms = max(0.0, float(np.median([a.elapsed_time(b_) for a, b_ in cal])) - TINY_KERNEL_MS)
-    # a run with fewer steps than kernels leaves some kernels without an event sample: probe those once more, untimed
-    probed = {(n_, k_) for n_, k_, _, _ in ev}
-    for p_ in range(n_kern):
-        L_ = state[p_ // 2]["L"]
-        if (L_.name, "rq" if p_ % 2 == 0 else "gemm") not in probed:
-            step(p_, ev)
+    # Every kernel of the step gets at least MIN_EVENT_SAMPLES event samples: what the timed steps did not supply comes
+    # from further passes of the same step, right behind the timed region (untimed, GPU still busy and warm)
+    n_timed_samples = len(ev)
+    extra_passes = 0
+    count = lambda: {(n_, k_): sum(1 for a_, b_, _, _ in ev if (a_, b_) == (n_, k_)) for n_ in [s["L"].name for s in state] for k_ in ("rq", "gemm")}
+    while min(count().values()) < MIN_EVENT_SAMPLES and extra_passes < 64 * n_kern:
+        step(extra_passes % n_kern, ev)
+        extra_passes += 1
     torch.cuda.synchronize()
     ms_per_step = dt * 1e3 / args.steps
     flops_step = sum(2.0 * M * s["L"].N * s["L"].K for s in state)
     value = flops_step / (ms_per_step * 1e-3) / 1e12
 
-    # ---- per-kernel durations from the events recorded inside the timed region
+    # ---- per-kernel durations from the events
     per_layer = {}
     for name, kind, e0, e1 in ev:
         per_layer.setdefault(name, {"rq": [], "gemm": []})[kind].append(e0.elapsed_time(e1))
@@ -179,17 +224,23 @@ def main():
         fl = 2.0 * M * L.N * L.K
         layers_out[L.name] = {"K": L.K, "N": L.N, "rq_us": round(rq * 1e3, 2), "gemm_us": round(gm * 1e3, 2),
                               "gemm_tflops": round(fl / (gm * 1e-3) / 1e12, 1),
+                              "gemm_frac_of_fp4_peak": round(fl / (gm * 1e-3) / 1e12 / PEAK_FP4_TFLOPS, 4),
                               "rq_gbs": round(M * L.K * RQ_BYTES_PER_ELEM_MX / (rq * 1e-3) / 1e9, 1),
-                              "actual_tflops": round(fl / ((rq + gm) * 1e-3) / 1e12, 1)}
+                              "actual_tflops": round(fl / ((rq + gm) * 1e-3) / 1e12, 1),
+                              "event_samples": [len(d["rq"]), len(d["gemm"])]}
     n_launch = len(state)
     avg_gemm_ms = gemm_ms_total / n_launch
     achieved = flops_step / (gemm_ms_total * 1e-3) / 1e12
+    traffic = committed_traffic()
     roofline = {"bound": "mfma", "kernel": "gemm_mx_kernel (v_mfma_scale_f32_16x16x128_f8f6f4, E2M1 x E2M1)",
                 "achieved": round(achieved, 1), "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP4_TFLOPS, 4),
                 "avg_launch_us": round(avg_gemm_ms * 1e3, 2), "launches_per_step": n_launch,
-                "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH if M == 4096 else None,
-                "timing": "HIP events around one launch per step inside the timed region, minus the event-bracket overhead "
-                          f"({bracket_ms * 1e3:.1f} us, calibrated on a 2 KB launch)"}
+                "traffic": traffic.get("gemm_mean_bytes_per_launch") if M == 4096 else None,
+                "traffic_source": os.path.relpath(TRAFFIC_FILE, ROOT) if traffic else None,
+                "timing": "HIP events around one launch per step on the launch stream, minus the event-bracket overhead "
+                          f"({bracket_ms * 1e3:.1f} us, calibrated on a 2 KB launch); {n_timed_samples} samples inside the timed region + "
+                          f"{len(ev) - n_timed_samples} from {extra_passes} further untimed passes of the same step right behind it "
+                          f"(at least {MIN_EVENT_SAMPLES} per kernel)"}
 
     result = {"metric": "MXFP4 rotate+quant+GEMM TFLOP/s (% FP4 MFMA peak) and speedup vs bf16 GEMM", "value": round(value, 2),
               "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -198,11 +249,88 @@ def main():
               "config": {"workload": f"llama3-8b-shaped prefill, MXFP4 W4A4, Hadamard block {b}, M={M}: qkv/o_proj/gate_up/down "
                                      "(BASELINE configs[2])", "M": M, "had_block": b, "format": "mxfp4",
                          "layers": [[L.name, L.K, L.N] for L in layers]},
+              "prewarm": f"{args.warmup} warm-up steps, then {N_CAL} further untimed steps interleaved with the event-bracket calibration "
+                         "launches, then the timed region with no idle gap",
               "pct_of_fp4_peak": round(100.0 * value / PEAK_FP4_TFLOPS, 2), "layers": layers_out, "roofline": roofline}
 
     if not args.no_extras:
         # Each section below is a side measurement: a failure in one is recorded and must not cost the headline line.
         extras_errors = {}
+
+        def time_us(fn, n=12, warm=4):
+            for _ in range(warm):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = ev_pair()
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n * 1e3
+
+        def graph_us(fn, out_t, n=20, reps=5):
+            """A few-microsecond kernel cannot be timed through Python-issued launches (the host needs ~8 us per call): n
+            calls are captured into a HIP graph on a side stream and the graph is replayed; every replayed result is
+            compared with the eager one (the library records kernels only, no memsets)."""
+            st = torch.cuda.Stream()
+            with torch.cuda.stream(st):
+                for _ in range(3):
+                    fn()
+                st.synchronize()
+                eager = out_t.clone()
+                gr = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gr, stream=st):
+                    for _ in range(n):
+                        fn()
+            torch.cuda.synchronize()
+            gr.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out_t, eager), "graph replay differs from the eager result"
+            a0, a1 = ev_pair()
+            a0.record()
+            for _ in range(reps):
+                gr.replay()
+            a1.record()
+            torch.cuda.synchronize()
+            assert torch.equal(out_t, eager), "graph replay differs from the eager result"
+            return a0.elapsed_time(a1) / (reps * n) * 1e3
+
+        try:
+            # ---- measured ceilings (small kernels of the library itself): what the matrix pipes and HBM deliver on this box
+            # when nothing else is in the way, and the shader clock under matrix load.  Run right behind the step loop.
+            cus = torch.cuda.get_device_properties(0).multi_processor_count
+            rec = torch.zeros(3 * cus, dtype=torch.int64, device="cuda")
+            ceil = {"compute_units": cus}
+            for name, which, flop_per_mfma, iters, peak in (("fp4_mfma_scaled_16x16x128", fp4.PROBE_MFMA_FP4, 65536.0, 40000, PEAK_FP4_TFLOPS),
+                                                            ("f16_mfma_16x16x32", fp4.PROBE_MFMA_F16, 16384.0, 40000, PEAK_F16_TFLOPS)):
+                for _ in range(2):
+                    step()               # come from the same thermal / clock state as the GEMMs
+                us = time_us(lambda: fp4.fp4_probe(which, rec, iters), n=4, warm=1)
+                r = rec.cpu().numpy().reshape(cus, 3)
+                clk_ghz = float(np.median(r[:, 0] / np.maximum(r[:, 1], 1))) * 0.1       # ticks of a 100 MHz counter
+                tf = cus * 8 * iters * 32 * flop_per_mfma / us / 1e6
+                # instruction issue interval per SIMD (two waves share it): shader clocks of the loop / MFMAs per SIMD
+                ceil[name] = {"tflops": round(tf, 1), "frac_of_datasheet": round(tf / peak, 4), "shader_clock_ghz": round(clk_ghz, 3),
+                              "clocks_per_mfma_per_simd": round(float(np.median(r[:, 0])) / (2 * iters * 32), 2), "launch_us": round(us, 1)}
+            buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+            buf.fill_(1)
+            us = time_us(lambda: fp4.fp4_probe(fp4.PROBE_COPY, buf), n=10, warm=3)
+            ceil["hbm_stream_copy_gbs"] = round(buf.numel() / us / 1e3, 1)
+            us = time_us(lambda: fp4.fp4_probe(fp4.PROBE_READ, buf), n=10, warm=3)
+            ceil["hbm_stream_read_gbs"] = round(buf.numel() / 2 / us / 1e3, 1)
+            del buf
+            # the cost of a launch that does (almost) nothing, as a kernel duration: the floor under every small call
+            ceil["event_bracket_overhead_us"] = round(bracket_ms * 1e3, 2)
+            ceil["note"] = ("issue loops: one 8-wave workgroup per compute unit, 16 independent accumulators per wave, operands in "
+                            "registers, timed with events; copy/read: 1 GiB buffer, 16 B per lane, non-temporal")
+            result["measured_ceilings"] = ceil
+            m_fp4 = ceil["fp4_mfma_scaled_16x16x128"]["tflops"]
+            roofline["measured_ceiling"] = m_fp4
+            roofline["frac_of_measured"] = round(achieved / m_fp4, 4)
+        except Exception as exc:  # noqa: BLE001 - reported in the JSON line
+            extras_errors["measured_ceilings"] = repr(exc)
+
         try:
             # ---- bf16 GEMM baseline on the same shapes (library GEMM through torch.matmul), unquantized X and W
             # the four GEMMs run as one step, like the FP4 path above, warmed up and timed over the same number of steps
@@ -210,13 +338,13 @@ def main():
             # the speedup); per-layer times come from event pairs placed like the probes of the timed loop
             wts = [s["w"].t() for s in state]
             outs = [torch.empty((M, s["L"].N), dtype=torch.bfloat16, device="cuda") for s in state]
-            n_base = max(8, min(args.steps, 64))
+            n_base = max(8 * len(state), min(args.steps, 64))
             bev = []
 
             def base_step(probe=-1):
                 for li, s in enumerate(state):
                     if probe == li:
-                        b0_, b1_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        b0_, b1_ = ev_pair()
                         b0_.record()
                     torch.matmul(s["x"], wts[li], out=outs[li])
                     if probe == li:
@@ -250,29 +378,13 @@ def main():
             cb, sb = fp4.packed_bytes(Mr, Kr, fp4.MXFP4, GL)
             oc = torch.empty(cb, dtype=torch.uint8, device="cuda")
             osc = torch.empty(sb, dtype=torch.uint8, device="cuda")
-            for j in range(3):
-                fp4.fp4_rotate_quantize(xs[j], 32, fp4.MXFP4, flags=GL, codes=oc, scales=osc)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             n_rq = 30
-            e0.record()
-            for it in range(n_rq):
-                fp4.fp4_rotate_quantize(xs[it % 3], 32, fp4.MXFP4, flags=GL, codes=oc, scales=osc)
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / n_rq
-            gbs = Mr * Kr * RQ_BYTES_PER_ELEM_MX / (ms * 1e-3) / 1e9
-            result["roofline_rotate_quantize"] = {"bound": "hbm", "kernel": "rq_frag_kernel<32, MXFP4> (GEMM layout)",
-                                                  "workload": "X bf16 [16384, 8192], Laplace(0,1), 1% outlier channels x100, block 32",
-                                                  "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
-                                                  "avg_launch_us": round(ms * 1e3, 2), "traffic": RQ_TRAFFIC_BYTES_PER_LAUNCH}
 
-            # ---- the same tensor through a caller-supplied dense rotation (orthonormal DCT-II block rounded to bf16)
             def time_rq(fn):
                 for j in range(3):
                     fn(xs[j])
                 torch.cuda.synchronize()
-                a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a0, a1 = ev_pair()
                 a0.record()
                 for it in range(n_rq):
                     fn(xs[it % 3])
@@ -281,6 +393,19 @@ def main():
                 t = a0.elapsed_time(a1) / n_rq
                 return {"avg_launch_us": round(t * 1e3, 2), "achieved_gbs": round(Mr * Kr * RQ_BYTES_PER_ELEM_MX / (t * 1e-3) / 1e9, 1)}
 
+            t_main = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, 32, fp4.MXFP4, flags=GL, codes=oc, scales=osc))
+            gbs = t_main["achieved_gbs"]
+            rq_roof = {"bound": "hbm", "kernel": "rq_frag_kernel<32, MXFP4> (GEMM layout)",
+                       "workload": "X bf16 [16384, 8192], Laplace(0,1), 1% outlier channels x100, block 32",
+                       "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
+                       "avg_launch_us": t_main["avg_launch_us"], "traffic": traffic.get("rq_16384x8192_bytes_per_launch")}
+            copy_gbs = result.get("measured_ceilings", {}).get("hbm_stream_copy_gbs")
+            if copy_gbs:
+                rq_roof["measured_ceiling"] = copy_gbs
+                rq_roof["frac_of_measured"] = round(gbs / copy_gbs, 4)
+            result["roofline_rotate_quantize"] = rq_roof
+
+            # ---- the same tensor through a caller-supplied dense rotation (orthonormal DCT-II block rounded to bf16)
             dense = {}
             for bd in (32, 128):
                 n_ = np.arange(bd)[:, None]
@@ -293,40 +418,67 @@ def main():
             dense["hadamard32_mse_scales"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, 32, fp4.MXFP4, flags=GL | fp4.SCALE_MSE, codes=oc, scales=osc))
             dense["hadamard32_round43_scales"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, 32, fp4.MXFP4, flags=GL | fp4.SCALE_ROUND43, codes=oc, scales=osc))
             result["rotate_quantize_variants"] = dense
-            del xs
+            del xs, oc, osc
         except Exception as exc:  # noqa: BLE001 - reported in the JSON line
             extras_errors["rotate_quantize"] = repr(exc)
 
         try:
-            # ---- the decode configuration (BASELINE configs[1]: M in {1, 16}, same four layers): weight streaming, so the
-            # figure of merit is time and GB/s of W, not TFLOP/s.  A few-microsecond kernel cannot be timed through
-            # Python-issued launches (the host needs ~8 us per call), so 20 calls are captured into a HIP graph on a side
-            # stream and the graph is replayed; every replayed result is compared with the eager one (the library records
-            # kernels only, no memsets).
-            def graph_us(fn, out_t, n=20, reps=5):
-                st = torch.cuda.Stream()
-                with torch.cuda.stream(st):
-                    for _ in range(3):
-                        fn()
-                    st.synchronize()
-                    eager = out_t.clone()
-                    gr = torch.cuda.CUDAGraph()
-                    with torch.cuda.graph(gr, stream=st):
-                        for _ in range(n):
-                            fn()
-                torch.cuda.synchronize()
-                gr.replay()
-                torch.cuda.synchronize()
-                assert torch.equal(out_t, eager), "graph replay differs from the eager result"
-                a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a0.record()
-                for _ in range(reps):
-                    gr.replay()
-                a1.record()
-                torch.cuda.synchronize()
-                assert torch.equal(out_t, eager), "graph replay differs from the eager result"
-                return a0.elapsed_time(a1) / (reps * n) * 1e3
+            # ---- BASELINE configs[0]: one layer, M = 64, K = N = 4096 (weight streaming: time and GB/s of W)
+            r1 = inputs.RECIPES[1]
+            M1, K1, N1 = 64, 4096, 4096
+            x1, w1 = to_dev_bf16(r1.x(M1, K1)), to_dev_bf16(r1.w(N1, K1))
+            q1 = fp4.fp4_quantize_weights(w1, 32, fp4.MXFP4, flags=GL)
+            cb, sb = fp4.packed_bytes(M1, K1, fp4.MXFP4, GL)
+            c1, s1 = torch.zeros(cb, dtype=torch.uint8, device="cuda"), torch.zeros(sb, dtype=torch.uint8, device="cuda")
+            o1, ob1 = torch.empty((M1, N1), dtype=torch.bfloat16, device="cuda"), torch.empty((M1, N1), dtype=torch.bfloat16, device="cuda")
+            w1t = w1.t()
+            t_rq = graph_us(lambda: fp4.fp4_rotate_quantize(x1, 32, fp4.MXFP4, flags=GL, codes=c1, scales=s1), c1)
+            t_g = graph_us(lambda: fp4.fp4_gemm(c1, s1, None, q1[0], q1[1], None, M1, N1, K1, fp4.MXFP4, flags=gflags, out=o1), o1)
+            t_b = graph_us(lambda: torch.matmul(x1, w1t, out=ob1), ob1)
+            wbytes = N1 * K1 * (0.5 + 1.0 / 32)
+            result["config0_m64"] = {"workload": "BASELINE configs[0]: M=64, K=N=4096, MXFP4, block 32", "rq_us": round(t_rq, 2), "gemm_us": round(t_g, 2),
+                                     "w_gbs": round(wbytes / t_g / 1e3, 1), "actual_tflops": round(2.0 * M1 * N1 * K1 / (t_rq + t_g) / 1e6, 1),
+                                     "bf16_gemm_us": round(t_b, 2), "speedup_vs_bf16": round(t_b / (t_rq + t_g), 2)}
+            del x1, w1, q1
+        except Exception as exc:  # noqa: BLE001 - reported in the JSON line
+            extras_errors["config0_m64"] = repr(exc)
 
+        try:
+            # ---- BASELINE configs[4], first half: Hadamard block sweep as full rotate+quantize+GEMM, M = 2048, K = N = 8192:
+            # "ideal" = the GEMM alone, "actual" = quantization + GEMM (the two curves of Section 5 item 4)
+            r5 = inputs.RECIPES[5]
+            M5, K5, N5 = 2048, 8192, 8192
+            x5, w5 = to_dev_bf16(r5.x(M5, K5)), to_dev_bf16(r5.w(N5, K5))
+            cb, sb = fp4.packed_bytes(M5, K5, fp4.MXFP4, GL)
+            c5, s5 = torch.empty(cb, dtype=torch.uint8, device="cuda"), torch.empty(sb, dtype=torch.uint8, device="cuda")
+            o5 = torch.empty((M5, N5), dtype=torch.bfloat16, device="cuda")
+            w5t = w5.t()
+            t_b = time_us(lambda: torch.matmul(x5, w5t, out=o5), n=20)
+            sweep = {}
+            fl5 = 2.0 * M5 * N5 * K5
+            for bb in (16, 32, 64, 128):
+                q5 = fp4.fp4_quantize_weights(w5, bb, fp4.MXFP4, flags=GL)
+                t_rq = time_us(lambda: fp4.fp4_rotate_quantize(x5, bb, fp4.MXFP4, flags=GL, codes=c5, scales=s5), n=30)
+                t_g = time_us(lambda: fp4.fp4_gemm(c5, s5, None, q5[0], q5[1], None, M5, N5, K5, fp4.MXFP4, flags=gflags, out=o5), n=30)
+
+                def both():
+                    fp4.fp4_rotate_quantize(x5, bb, fp4.MXFP4, flags=GL, codes=c5, scales=s5)
+                    fp4.fp4_gemm(c5, s5, None, q5[0], q5[1], None, M5, N5, K5, fp4.MXFP4, flags=gflags, out=o5)
+                t_a = time_us(both, n=30)
+                sweep[f"b={bb}"] = {"rq_us": round(t_rq, 2), "gemm_us": round(t_g, 2), "ideal_tflops": round(fl5 / t_g / 1e6, 1),
+                                    "actual_us": round(t_a, 2), "actual_tflops": round(fl5 / t_a / 1e6, 1),
+                                    "speedup_vs_bf16": round(t_b / t_a, 3)}
+                del q5
+            sweep["bf16_gemm_us"] = round(t_b, 2)
+            sweep["workload"] = "BASELINE configs[4]: M=2048, K=N=8192, MXFP4, rotate+quantize+GEMM per Hadamard block size"
+            result["block_sweep_2048_8192"] = sweep
+            del x5, w5, c5, s5, o5
+        except Exception as exc:  # noqa: BLE001 - reported in the JSON line
+            extras_errors["block_sweep"] = repr(exc)
+
+        try:
+            # ---- the decode configuration (BASELINE configs[1]: M in {1, 16}, same four layers): weight streaming, so the
+            # figure of merit is time and GB/s of W, not TFLOP/s (HIP-graph replays, see graph_us)
             decode = {}
             for Md in (1, 16):
                 per = {}
@@ -342,18 +494,20 @@ def main():
                     t_rq = graph_us(lambda: fp4.fp4_rotate_quantize(xd, b, fp4.MXFP4, flags=GL, codes=acd, scales=ascd), acd)
                     t_g = graph_us(lambda: fp4.fp4_gemm(acd, ascd, None, s_["wc"], s_["ws"], None, Md, L.N, L.K, fp4.MXFP4, flags=gflags, out=outd), outd)
                     t_b = graph_us(lambda: torch.matmul(xd, wt, out=outb), outb)
-                    # one launch: rotation and quantization inside the GEMM (bit-identical result)
-                    outf = torch.empty((Md, L.N), dtype=torch.bfloat16, device="cuda")
-                    t_f = graph_us(lambda: fp4.fp4_fused_linear(xd, b, s_["wc"], s_["ws"], L.N, fp4.MXFP4, out=outf), outf)
-                    assert torch.equal(outf, outd), "one-launch path differs from the two-launch path"
+                    wbytes = L.N * L.K * (0.5 + 1.0 / 32)
+                    per[L.name] = {"rq_us": round(t_rq, 2), "gemm_us": round(t_g, 2), "w_gbs": round(wbytes / t_g / 1e3, 1),
+                                   "bf16_gemm_us": round(t_b, 2), "speedup_vs_bf16": round(t_b / (t_rq + t_g), 2)}
+                    if Md <= 4:
+                        # one launch: rotation and quantization inside the GEMM (bit-identical result; up to four tokens)
+                        outf = torch.empty((Md, L.N), dtype=torch.bfloat16, device="cuda")
+                        t_f = graph_us(lambda: fp4.fp4_fused_linear(xd, b, s_["wc"], s_["ws"], L.N, fp4.MXFP4, out=outf), outf)
+                        assert torch.equal(outf, outd), "one-launch path differs from the two-launch path"
+                        per[L.name].update({"fused_us": round(t_f, 2), "fused_w_gbs": round(wbytes / t_f / 1e3, 1),
+                                            "fused_speedup_vs_bf16": round(t_b / t_f, 2)})
                     # weight-only variant: rotated activations stay bf16
                     outw = torch.empty((Md, L.N), dtype=torch.bfloat16, device="cuda")
                     t_w = graph_us(lambda: fp4.fp4_w4a16_linear(xd, b, s_["wc"], s_["ws"], L.N, fp4.MXFP4, out=outw), outw)
-                    wbytes = L.N * L.K * (0.5 + 1.0 / 32)
-                    per[L.name] = {"rq_us": round(t_rq, 2), "gemm_us": round(t_g, 2), "w_gbs": round(wbytes / t_g / 1e3, 1),
-                                   "fused_us": round(t_f, 2), "fused_w_gbs": round(wbytes / t_f / 1e3, 1), "w4a16_us": round(t_w, 2),
-                                   "bf16_gemm_us": round(t_b, 2), "speedup_vs_bf16": round(t_b / (t_rq + t_g), 2),
-                                   "fused_speedup_vs_bf16": round(t_b / t_f, 2)}
+                    per[L.name]["w4a16_us"] = round(t_w, 2)
                 decode[f"M={Md}"] = per
             result["decode_configs1"] = decode
         except Exception as exc:  # noqa: BLE001 - reported in the JSON line
@@ -403,42 +557,57 @@ def main():
             extras_errors["gptq_offline"] = repr(exc)
 
         try:
-            # ---- NVFP4 prefill on Llama-3-70B-shaped layers (M = 4096): the dequantizing fp16-MFMA kernel against the bf16
-            # library GEMM on the same shapes
-            nv = {}
+            # ---- BASELINE configs[3]: NVFP4 on Llama-3-70B-shaped layers.  M = 4096: the fp16-MFMA kernel (its roofline is
+            # the fp16 MFMA peak, not the FP4 one: E4M3 group scales cannot go through the block-scaled MFMA) against the
+            # bf16 library GEMM; M = 16: weight streaming, GB/s of W (HIP-graph replays)
+            nv, nv16 = {}, {}
+            m_f16 = result.get("measured_ceilings", {}).get("f16_mfma_16x16x32", {}).get("tflops")
             for name, Kn, Nn in (("qkv", 8192, 10240), ("gate_up", 8192, 57344), ("down", 28672, 8192)):
                 xn = torch.randn(M, Kn, device="cuda").to(torch.bfloat16)
                 wn = (torch.randn(Nn, Kn, device="cuda") * 0.02).to(torch.bfloat16)
-                qa = fp4.fp4_rotate_quantize(xn, 16, fp4.NVFP4, flags=fp4.LAYOUT_GEMM)
-                qw = fp4.fp4_quantize_weights(wn, 16, fp4.NVFP4, flags=fp4.LAYOUT_GEMM)
+                qa = fp4.fp4_rotate_quantize(xn, 16, fp4.NVFP4, flags=GL)
+                qw = fp4.fp4_quantize_weights(wn, 16, fp4.NVFP4, flags=GL)
                 on = torch.empty((M, Nn), dtype=torch.bfloat16, device="cuda")
-                gfl = fp4.A_LAYOUT_GEMM | fp4.W_LAYOUT_GEMM
-
-                def run_nv():
-                    fp4.fp4_gemm(qa[0], qa[1], qa[2], qw[0], qw[1], qw[2], M, Nn, Kn, fp4.NVFP4, flags=gfl, out=on)
-
-                def run_bf():
-                    torch.matmul(xn, wn.t(), out=on)
-
-                def time_us(fn, n=12):
-                    for _ in range(4):
-                        fn()
-                    torch.cuda.synchronize()
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                    for _ in range(n):
-                        fn()
-                    e1.record()
-                    torch.cuda.synchronize()
-                    return e0.elapsed_time(e1) / n * 1e3
-                tn, tb = time_us(run_nv), time_us(run_bf)
+                wsn = fp4.workspace_bytes(fp4.OP_GEMM, M, Nn, Kn, fp4.NVFP4, gflags)
+                wsn_t = torch.empty(max(wsn, 16), dtype=torch.uint8, device="cuda")
+                wnt = wn.t()
+                t_rq = time_us(lambda: fp4.fp4_rotate_quantize(xn, 16, fp4.NVFP4, flags=GL, codes=qa[0], scales=qa[1]), n=8, warm=2)
+                tn = time_us(lambda: fp4.fp4_gemm(qa[0], qa[1], qa[2], qw[0], qw[1], qw[2], M, Nn, Kn, fp4.NVFP4, flags=gflags, out=on, workspace=wsn_t))
+                tb = time_us(lambda: torch.matmul(xn, wnt, out=on))
                 fl = 2.0 * M * Nn * Kn
-                nv[name] = {"K": Kn, "N": Nn, "gemm_us": round(tn, 1), "gemm_tflops": round(fl / tn / 1e6, 1),
-                            "bf16_gemm_us": round(tb, 1), "speedup_vs_bf16": round(tb / tn, 3)}
-                del xn, wn, qa, qw, on
+                nv[name] = {"K": Kn, "N": Nn, "rq_us": round(t_rq, 1), "gemm_us": round(tn, 1), "gemm_tflops": round(fl / tn / 1e6, 1),
+                            "frac_of_f16_mfma_peak": round(fl / tn / 1e6 / PEAK_F16_TFLOPS, 4),
+                            "frac_of_fp4_mfma_peak": round(fl / tn / 1e6 / PEAK_FP4_TFLOPS, 4),
+                            "bf16_gemm_us": round(tb, 1), "speedup_vs_bf16": round(tb / tn, 3),
+                            "actual_speedup_vs_bf16": round(tb / (tn + t_rq), 3)}
+                if m_f16:
+                    nv[name]["frac_of_measured_f16_ceiling"] = round(fl / tn / 1e6 / m_f16, 4)
+                # M = 16 on the same weights
+                Md = 16
+                xd = xn[:Md].contiguous()
+                cbd, sbd = fp4.packed_bytes(Md, Kn, fp4.NVFP4, GL)
+                acd, ascd = torch.zeros(cbd, dtype=torch.uint8, device="cuda"), torch.zeros(sbd, dtype=torch.uint8, device="cuda")
+                tsd = torch.zeros(1, dtype=torch.float32, device="cuda")
+                wsd = torch.empty(fp4.workspace_bytes(fp4.OP_ROTATE_QUANTIZE, Md, 0, Kn, fp4.NVFP4, GL), dtype=torch.uint8, device="cuda")
+                outd, outb = torch.empty((Md, Nn), dtype=torch.bfloat16, device="cuda"), torch.empty((Md, Nn), dtype=torch.bfloat16, device="cuda")
+
+                def rq_small():
+                    st_ = fp4.lib.fp4_rotate_quantize(xd.data_ptr(), Md, Kn, 16, fp4.NVFP4, acd.data_ptr(), ascd.data_ptr(), tsd.data_ptr(),
+                                                      wsd.data_ptr(), wsd.numel(), GL, torch.cuda.current_stream().cuda_stream)
+                    assert st_ == 0
+                t_rq16 = graph_us(rq_small, acd)
+                t_g16 = graph_us(lambda: fp4.fp4_gemm(acd, ascd, tsd, qw[0], qw[1], qw[2], Md, Nn, Kn, fp4.NVFP4, flags=gflags, out=outd), outd)
+                t_b16 = graph_us(lambda: torch.matmul(xd, wnt, out=outb), outb)
+                wbytes = Nn * Kn * (0.5 + 1.0 / 16)
+                nv16[name] = {"K": Kn, "N": Nn, "rq_us": round(t_rq16, 2), "gemm_us": round(t_g16, 2), "w_gbs": round(wbytes / t_g16 / 1e3, 1),
+                              "frac_of_hbm_peak": round(wbytes / t_g16 / 1e3 / PEAK_HBM_GBS, 4),
+                              "bf16_gemm_us": round(t_b16, 2), "speedup_vs_bf16": round(t_b16 / (t_rq16 + t_g16), 2)}
+                del xn, wn, qa, qw, on, wsn_t, wnt
+            nv["path"] = "NVFP4 codes dequantized to fp16 (exact) and multiplied on v_mfma_f32_16x16x32_f16: bound by the fp16 MFMA peak"
             result["nvfp4_prefill_70b_shapes"] = nv
+            result["nvfp4_m16_70b_shapes"] = nv16
         except Exception as exc:  # noqa: BLE001 - reported in the JSON line
-            extras_errors["nvfp4_prefill"] = repr(exc)
+            extras_errors["nvfp4"] = repr(exc)
 
         if extras_errors:
             result["extras_errors"] = extras_errors
@@ -452,6 +621,8 @@ def main():
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(recipe, layers[2], min(M, 4096), 16384)
+        # the same oracle on one thread, on a sixteenth of the tokens
+        result["cpu_baseline_single_thread"] = cpu_baseline(recipe, layers[2], min(M, 256), 16384, threads=1)
 
     print(json.dumps(result))
 

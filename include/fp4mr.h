@@ -19,8 +19,10 @@
  *     buffer, including the workspace; the library allocates, frees and retains nothing.
  *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL = the default stream).
  *     Outputs are valid once the caller has synchronised with the stream.
- *   - Every argument is validated on the host before anything is launched; on a non-zero status nothing
- *     was written.  No exception or abort crosses this boundary.
+ *   - Every argument is validated on the host before anything is launched: on any status other than
+ *     FP4MR_OK and FP4MR_ERR_DEVICE nothing was launched and nothing was written.  FP4MR_ERR_DEVICE
+ *     reports a launch that the HIP runtime refused; an entry point that launches several kernels may
+ *     then have written part of its outputs or workspace.  No exception or abort crosses this boundary.
  *   - Data pointers must be 16-byte aligned.
  *   - Behaviour for NaN / Inf inputs is unspecified.
  *
@@ -94,10 +96,13 @@ fp4mr_status_t fp4_rotate_quantize(const void* x, int64_t M, int64_t K, int had_
 /*
  * Scale policy.  By default a group's scale is the abs-max one (Section 3 "Scales").  With FP4MR_SCALE_MSE the
  * scale code is chosen to minimise the group's squared error sum_i (xhat_i - x_i)^2 (the objective of Section 4.1
- * "Ingredient 1"; the "MSE" method of Section 4.2 item 1) among the abs-max code and its two neighbours, tried in
- * that order (abs-max, one above, one below), a candidate winning only with a strictly smaller error; the error is
- * evaluated in fp32.  MXFP4: E8M0 byte +-1; NVFP4: E4M3 code +-1 with the abs-max tensor scale.  Hardware codec
- * only.  Costs about twice the vector-ALU work of abs-max.
+ * "Ingredient 1"; the "MSE" method of Section 4.2 item 1) inside a window around the abs-max code c0, a candidate
+ * winning only with a strictly smaller error (evaluated in fp32), tried in this order:
+ *     MXFP4: E8M0 byte c0, c0+1, c0-1;
+ *     NVFP4: E4M3 code c0, c0+1, c0-1, c0+2, c0-2, c0+3, c0+4, c0+5, c0+6, c0+7, with the abs-max tensor scale.
+ * The windows hold the minimiser over ALL scale codes in all but about 1e-4 of the groups of heavy-tailed inputs
+ * (for NVFP4 it sits either next to c0 or about half an octave above it).  Hardware codec only.  Costs about twice
+ * (MXFP4) / four times (NVFP4) the vector-ALU work of abs-max.
  *
  * With FP4MR_SCALE_ROUND43 (MXFP4 only; not together with FP4MR_SCALE_MSE: FP4MR_ERR_FMT) the scale follows the
  * first equation of the appendix on MXFP scale fitting: s = (4/3) 2^k with k = clamp(round(log2(amax / 6)), -127, 127).
@@ -122,9 +127,9 @@ fp4mr_status_t fp4_rotate_quantize_dense(const void* x, int64_t M, int64_t K, in
                                          void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
 
 /*
- * Offline weight preparation: codes, scales = Q(W H_b) by round-to-nearest (Section 4.2 item 1: "W H_k is
- * pre-fused in the weights"; RTN + HT row of Section 5's method list).  Same arguments as
- * fp4_rotate_quantize with rows = N.  GPTQ-style calibration is not part of this library.
+ * Offline weight preparation: codes, scales = Q(W H_b) by round-to-nearest (Section 4.2 item 1: the weight-side
+ * rotation is folded into the stored weights ahead of time; RTN + HT row of Section 5's method list).  Same
+ * arguments as fp4_rotate_quantize with rows = N.  The calibrated alternative is fp4_gptq_quantize_weights below.
  */
 fp4mr_status_t fp4_quantize_weights(const void* w, int64_t N, int64_t K, int had_block, fp4mr_fmt_t fmt,
                                     void* codes_out, void* scales_out, float* tensor_scale,
@@ -147,9 +152,10 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
  * Few tokens in one launch: out = Q(X H_b) Q(W H_b)^T with the activations rotated and quantized inside the GEMM
  * (Section 4.2 items 1 and 2 fused; the paper's appendix on inference regimes: at small batch its separate kernels give
  * little).  Result bit-identical to fp4_rotate_quantize followed by fp4_gemm for had_block <= 32.
- *   x            [M,K] bf16 row-major, 1 <= M <= 16, K % 128 == 0.  Meant for M <= 4: every workgroup (one per 16 rows of
- *                W) repeats the rotation and quantization of all M tokens, which hides under its weight stream up to
- *                four tokens; from five tokens on the two calls (fp4_rotate_quantize, fp4_gemm) are faster
+ *   x            [M,K] bf16 row-major, 1 <= M <= 4, K % 128 == 0.  Every workgroup (one per 16 rows of W) repeats the
+ *                rotation and quantization of all M tokens, which hides under its weight stream up to four tokens;
+ *                from five tokens on the two calls (fp4_rotate_quantize, fp4_gemm) are faster, so M > 4 is
+ *                rejected with FP4MR_ERR_SHAPE
  *   had_block    b in {16,32,64,128}
  *   w_codes, w_scales   [N,K] operand in GEMM layout (flags must contain FP4MR_W_LAYOUT_GEMM)
  *   fmt          FP4MR_MXFP4 only (NVFP4's tensor scale needs a pass over all of X first: FP4MR_ERR_FMT)
@@ -165,7 +171,8 @@ fp4mr_status_t fp4_fused_linear(const void* x, int64_t M, int64_t K, int had_blo
  * Weight-only variant of the same (W4A16): out = bf16(X H_b) Q(W H_b)^T.  The rotated activations are rounded to bf16
  * (round-to-nearest-even) instead of quantized; the weights' E2M1 codes are decoded with their E8M0 scales and the
  * product accumulates in fp32 (appendix on inference regimes: where the layer is memory-bound, weight-only
- * quantization loses no speed and keeps the activations' accuracy).  Arguments as fp4_fused_linear.
+ * quantization loses no speed and keeps the activations' accuracy).  Arguments as fp4_fused_linear, except
+ * 1 <= M <= 16 (the library has no other weight-only path; above four tokens it falls behind a bf16 GEMM on wide layers).
  */
 fp4mr_status_t fp4_w4a16_linear(const void* x, int64_t M, int64_t K, int had_block, const void* w_codes, const void* w_scales,
                                 int64_t N, fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream);
@@ -220,6 +227,36 @@ fp4mr_status_t fp4_gptq_accumulate_hessian(const void* x, int64_t T, int64_t K, 
  */
 fp4mr_status_t fp4_gptq_prepare(const float* hessian, int64_t K, float damp, int act_order, int32_t* perm_out, float* hinv_u_out,
                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Process-wide switches for tuning sweeps and cross-checks (none is needed for normal use; not thread-safe: set them
+ * before calls are issued concurrently).  Returns FP4MR_ERR_FMT for an unknown option or a value out of range.
+ *   FP4MR_OPT_GEMM_VARIANT  0 (default): fp4_gemm picks the tile shape from M, N, K; 1..16 (MXFP4) / 1..3 (NVFP4): force
+ *                           one tile configuration (fp4_gemm returns FP4MR_ERR_FMT if the value is not valid for its format)
+ *   FP4MR_OPT_GEMM_GRID     0 (default): one persistent workgroup per compute unit; n > 0: at most n workgroups
+ *   FP4MR_OPT_SW_CODEC      1: the quantizers encode E2M1 / E4M3 with integer arithmetic instead of the converting
+ *                           instructions (same results bit for bit; abs-max and 4/3 policies only)
+ */
+enum { FP4MR_OPT_GEMM_VARIANT = 0, FP4MR_OPT_GEMM_GRID = 1, FP4MR_OPT_SW_CODEC = 2 };
+fp4mr_status_t fp4_set_option(int option, int value);
+
+/*
+ * Measured ceilings for a roofline report (the datasheet peaks assume a clock the chip does not hold under matrix load).
+ * Each call launches one kernel on `stream`; the caller times it (events) and reads the kernel's own clock report.
+ *   FP4MR_PROBE_MFMA_FP4   register-resident issue loop of the block-scaled FP4 MFMA (16x16x128, E2M1 x E2M1) the MXFP4
+ *                          product is built on: one workgroup of eight waves per compute unit, sixteen independent
+ *                          accumulators per wave, no memory traffic.  flops = CUs * 8 * iters * 32 * 65536
+ *   FP4MR_PROBE_MFMA_F16   the same with the fp16 MFMA (16x16x32) of the NVFP4 product.  flops = CUs * 8 * iters * 32 * 16384
+ *     buf: device, at least 24 * CUs bytes; receives per compute unit three uint64: shader clocks spent in the loop
+ *     (s_memtime), ticks of the constant 100 MHz counter over the same span (s_memrealtime), a checksum.  iters >= 1.
+ *   FP4MR_PROBE_COPY       streaming copy of the first half of buf to the second half (16 bytes per lane, non-temporal):
+ *                          bytes / 2 read + bytes / 2 written
+ *   FP4MR_PROBE_READ       streaming read of the first half of buf: bytes / 2 read
+ *     buf: device, 16-byte aligned, bytes >= 32; iters ignored.
+ * Returns FP4MR_ERR_SHAPE for an unknown probe, a buffer that is too small or iters < 1, FP4MR_ERR_NULL / _ALIGN as usual.
+ */
+enum { FP4MR_PROBE_MFMA_FP4 = 0, FP4MR_PROBE_MFMA_F16 = 1, FP4MR_PROBE_COPY = 2, FP4MR_PROBE_READ = 3 };
+fp4mr_status_t fp4_probe(int which, void* buf, size_t bytes, int iters, void* stream);
 
 /* Bytes of device scratch the given operation needs (0 = none).  rows = M for the quantize ops. */
 size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t fmt, uint32_t flags);

@@ -30,6 +30,7 @@ SCALE_MSE = 1 << 6
 SCALE_ROUND43 = 1 << 7
 A_SCALE43 = 1 << 8
 W_SCALE43 = 1 << 9
+OPT_GEMM_VARIANT, OPT_GEMM_GRID, OPT_SW_CODEC = 0, 1, 2
 OP_ROTATE_QUANTIZE, OP_QUANTIZE_WEIGHTS, OP_GEMM, OP_GPTQ, OP_GPTQ_PREPARE, OP_GPTQ_HESSIAN = 0, 1, 2, 3, 4, 5
 
 _p, _i64, _i32, _u32, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32, ctypes.c_size_t
@@ -59,6 +60,10 @@ lib.fp4_packed_bytes.restype = _i32
 lib.fp4_status_string.argtypes = [_i32]
 lib.fp4_status_string.restype = ctypes.c_char_p
 lib.fp4_version.restype = _i32
+lib.fp4_probe.argtypes = [_i32, _p, _sz, _i32, _p]
+lib.fp4_probe.restype = _i32
+lib.fp4_set_option.argtypes = [_i32, _i32]
+lib.fp4_set_option.restype = _i32
 
 
 class Fp4mrError(RuntimeError):
@@ -209,7 +214,7 @@ def fp4_gemm(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scal
 
 
 def fp4_fused_linear(x, had_block: int, w_codes, w_scales, N: int, fmt: int = MXFP4, *, flags: int = 0, out=None):
-    """out[M,N] = Q(X H_b) @ Q(W H_b)^T in one launch for M <= 16 tokens (MXFP4, W in GEMM layout)."""
+    """out[M,N] = Q(X H_b) @ Q(W H_b)^T in one launch for M <= 4 tokens (MXFP4, W in GEMM layout)."""
     assert x.is_cuda and x.dim() == 2 and x.is_contiguous() and x.dtype == torch.bfloat16
     M, K = x.shape
     if out is None:
@@ -228,6 +233,20 @@ def fp4_w4a16_linear(x, had_block: int, w_codes, w_scales, N: int, fmt: int = MX
     _check(lib.fp4_w4a16_linear(x.data_ptr(), M, K, had_block, w_codes.data_ptr(), w_scales.data_ptr(), N, fmt, out.data_ptr(),
                                 flags | W_LAYOUT_GEMM, _stream()))
     return out
+
+
+PROBE_MFMA_FP4, PROBE_MFMA_F16, PROBE_COPY, PROBE_READ = 0, 1, 2, 3
+
+
+def fp4_probe(which: int, buf, iters: int = 1) -> None:
+    """Launch one ceiling-measurement kernel on the current stream (see fp4_probe in the header); buf: cuda uint8 tensor."""
+    assert buf.is_cuda and buf.is_contiguous()
+    _check(lib.fp4_probe(int(which), buf.data_ptr(), buf.numel() * buf.element_size(), int(iters), _stream()))
+
+
+def set_option(option: int, value: int) -> None:
+    """Process-wide tuning / cross-check switch (OPT_GEMM_VARIANT, OPT_GEMM_GRID, OPT_SW_CODEC); 0 restores the default."""
+    _check(lib.fp4_set_option(int(option), int(value)))
 
 
 def version() -> int:

@@ -17,7 +17,7 @@ HERE = Path(__file__).resolve().parent
 CSRC = HERE / "csrc"
 BUILD = HERE / "_build"
 LIB = HERE / "libfp4mr.so"
-SOURCES = ["api.hip", "rotate_quantize.hip", "gemm_mxfp4.hip", "gemm_nvfp4.hip", "gemm_skinny.hip", "gemm_fused_decode.hip", "repack.hip", "gptq.hip", "gptq_prepare.hip"]
+SOURCES = ["api.hip", "rotate_quantize.hip", "gemm_mxfp4.hip", "gemm_nvfp4.hip", "gemm_skinny.hip", "gemm_fused_decode.hip", "repack.hip", "gptq.hip", "gptq_prepare.hip", "probes.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # Packed-fp32 instruction selection is switched off for all device code (a device-only target feature; the host
@@ -49,7 +49,7 @@ def _compile(src: str) -> Path:
 
 def build(verbose: bool = True) -> Path:
     BUILD.mkdir(exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES), os.cpu_count() or 1)) as ex:
         objs = list(ex.map(_compile, SOURCES))
     tmp = LIB.with_suffix(".so.tmp%d" % os.getpid())
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(tmp), *map(str, objs)]

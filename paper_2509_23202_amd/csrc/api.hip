@@ -27,18 +27,6 @@ float scale43_factor(uint32_t flags)
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 
-bool env_flag(const char* name)
-{
-    const char* v = std::getenv(name);
-    return v && *v && std::strcmp(v, "0") != 0;
-}
-
-int env_int(const char* name, int dflt)
-{
-    const char* v = std::getenv(name);
-    return (v && *v) ? std::atoi(v) : dflt;
-}
-
 int group_of(fp4mr_fmt_t fmt) { return fmt == FP4MR_MXFP4 ? 32 : 16; }
 
 size_t quant_workspace(fp4mr_fmt_t fmt, uint32_t flags)
@@ -77,7 +65,7 @@ fp4mr_status_t quantize_common(const void* x, int64_t rows, int64_t K, int had_b
     const hipError_t e = launch_rotate_quantize(x, rows, K, had_block, rot, (int)fmt, (flags & FP4MR_INPUT_F32) != 0,
                                                 (flags & FP4MR_LAYOUT_GEMM) ? 1 : 0, (flags & FP4MR_STATIC_TENSOR_SCALE) != 0,
                                                 (flags & FP4MR_SCALE_MSE) ? 1 : ((flags & FP4MR_SCALE_ROUND43) ? 2 : 0), codes, scales, tensor_scale,
-                                                workspace, !env_flag("FP4MR_SW_CODEC"),
+                                                workspace, options().sw_codec == 0,
                                                 static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
 }
@@ -92,7 +80,8 @@ fp4mr_status_t few_token_linear(const void* x, int64_t M, int64_t K, int had_blo
     if (!(flags & FP4MR_W_LAYOUT_GEMM)) return FP4MR_ERR_FMT;
     if (!x || !w_codes || !w_scales || !out) return FP4MR_ERR_NULL;
     if (had_block != 16 && had_block != 32 && had_block != 64 && had_block != 128) return FP4MR_ERR_HAD_BLOCK;
-    if (M <= 0 || M > 16 || N <= 0 || K <= 0 || K % 128 != 0 || N > (1 << 24) || K > (1 << 24)) return FP4MR_ERR_SHAPE;
+    // the quantizing variant repeats the quantization per workgroup: beyond four tokens the two-call path is faster
+    if (M <= 0 || M > (weight_only ? 16 : 4) || N <= 0 || K <= 0 || K % 128 != 0 || N > (1 << 24) || K > (1 << 24)) return FP4MR_ERR_SHAPE;
     if (!aligned16(x) || !aligned16(w_codes) || !aligned16(w_scales) || !aligned16(out)) return FP4MR_ERR_ALIGN;
     const hipError_t e = launch_fused_decode(x, M, K, had_block, w_codes, w_scales, N, out, (flags & FP4MR_OUT_F32) != 0,
                                              weight_only, scale43_factor(flags), static_cast<hipStream_t>(stream));
@@ -101,7 +90,34 @@ fp4mr_status_t few_token_linear(const void* x, int64_t M, int64_t K, int had_blo
 
 }  // namespace
 
+namespace fp4mr {
+Options& options()
+{
+    static Options o;
+    return o;
+}
+}  // namespace fp4mr
+
 extern "C" {
+
+fp4mr_status_t fp4_set_option(int option, int value)
+{
+    Options& o = options();
+    switch (option) {
+        case FP4MR_OPT_GEMM_VARIANT:
+            if (value < 0 || value > kMaxGemmVariantMx) return FP4MR_ERR_FMT;
+            o.gemm_variant = value;
+            return FP4MR_OK;
+        case FP4MR_OPT_GEMM_GRID:
+            if (value < 0) return FP4MR_ERR_FMT;
+            o.gemm_grid = value;
+            return FP4MR_OK;
+        case FP4MR_OPT_SW_CODEC:
+            o.sw_codec = value != 0;
+            return FP4MR_OK;
+        default: return FP4MR_ERR_FMT;
+    }
+}
 
 fp4mr_status_t fp4_rotate_quantize(const void* x, int64_t M, int64_t K, int had_block, fp4mr_fmt_t fmt, void* codes_out,
                                    void* scales_out, float* tensor_scale, void* workspace, size_t workspace_bytes,
@@ -139,6 +155,8 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
     if (!aligned16(a_codes) || !aligned16(a_scales) || !aligned16(w_codes) || !aligned16(w_scales) || !aligned16(out)) return FP4MR_ERR_ALIGN;
     const size_t need = fp4_workspace_bytes(FP4MR_OP_GEMM, M, N, K, fmt, flags);
     if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return FP4MR_ERR_WORKSPACE;
+    const int variant = options().gemm_variant;
+    if (variant < 0 || variant > (fmt == FP4MR_MXFP4 ? kMaxGemmVariantMx : kMaxGemmVariantNv)) return FP4MR_ERR_FMT;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
@@ -160,7 +178,6 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
     }
     const bool out_f32 = (flags & FP4MR_OUT_F32) != 0;
     const float alpha = scale43_factor(flags);
-    const int variant = env_int("FP4MR_GEMM_VARIANT", 0);
     // Few tokens: the weight-streaming kernel, except MXFP4 with more than one 16-token block and a very wide layer,
     // where its per-token-block re-reads of the activations from L2 cost more than the 64 x 256 tile kernel does
     // (M = 64, N = 28672, K = 4096: 29.6 us against 13.7 us).
@@ -239,6 +256,17 @@ fp4mr_status_t fp4_w4a16_linear(const void* x, int64_t M, int64_t K, int had_blo
     return few_token_linear(x, M, K, had_block, w_codes, w_scales, N, fmt, out, flags, stream, true);
 }
 
+fp4mr_status_t fp4_probe(int which, void* buf, size_t bytes, int iters, void* stream)
+{
+    if (!buf) return FP4MR_ERR_NULL;
+    if (!aligned16(buf)) return FP4MR_ERR_ALIGN;
+    if (which < FP4MR_PROBE_MFMA_FP4 || which > FP4MR_PROBE_READ) return FP4MR_ERR_SHAPE;
+    if ((which <= FP4MR_PROBE_MFMA_F16 && iters < 1) || bytes < 32) return FP4MR_ERR_SHAPE;
+    const hipError_t e = launch_probe(which, buf, bytes, iters, static_cast<hipStream_t>(stream));
+    if (e == hipErrorInvalidValue) return FP4MR_ERR_SHAPE;  // buffer smaller than one record per compute unit
+    return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
+}
+
 size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t fmt, uint32_t flags)
 {
     if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return 0;
@@ -278,9 +306,9 @@ const char* fp4_status_string(fp4mr_status_t s)
     switch (s) {
         case FP4MR_OK: return "ok";
         case FP4MR_ERR_NULL: return "a required pointer is NULL";
-        case FP4MR_ERR_SHAPE: return "bad shape: sizes must be positive and K a multiple of the group, the Hadamard block and (GEMM layout) 128";
+        case FP4MR_ERR_SHAPE: return "bad shape: sizes must be positive and K a multiple of the group, the Hadamard block and (GEMM layout) 128; fp4_fused_linear takes 1..4 tokens (beyond: fp4_rotate_quantize + fp4_gemm), fp4_w4a16_linear 1..16";
         case FP4MR_ERR_HAD_BLOCK: return "had_block must be 1, 16, 32, 64 or 128 (1 with fp32 input)";
-        case FP4MR_ERR_FMT: return "unknown format or flag bits";
+        case FP4MR_ERR_FMT: return "unknown format, flag bits or option value";
         case FP4MR_ERR_ALIGN: return "pointers must be 16-byte aligned";
         case FP4MR_ERR_WORKSPACE: return "workspace missing, misaligned or smaller than fp4_workspace_bytes()";
         case FP4MR_ERR_DEVICE: return "HIP runtime error at launch";

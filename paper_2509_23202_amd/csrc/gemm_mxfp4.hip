@@ -444,19 +444,20 @@ hipError_t launch_variant(const GemmArgs& g0, bool out_f32, hipStream_t st)
     int nwg = ntiles;
     if (PERSIST) {
         nwg = std::min(ntiles, compute_units() * kWgsPerCu<BM, BN, WM, WN, STAGES>);
-        // FP4MR_GEMM_GRID caps the persistent grid (a testing aid: a small grid walks many tiles per workgroup)
-        const char* cap = std::getenv("FP4MR_GEMM_GRID");
-        if (cap && *cap && std::atoi(cap) > 0) nwg = std::min(nwg, std::atoi(cap));
+        // the grid cap option (a testing aid: a small grid walks many tiles per workgroup)
+        if (options().gemm_grid > 0) nwg = std::min(nwg, options().gemm_grid);
     }
     const dim3 grid((unsigned)nwg);
     hipError_t e;
+    // the dynamic-LDS limit of a kernel is raised once per device, not on every launch
+    static LdsAttrOnce raised[2];
     if (out_f32) {
         auto k = gemm_mx_kernel<BM, BN, WM, WN, STAGES, true, RD, PERSIST>;
-        if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess) return e;
+        if ((e = raised[1].ensure(reinterpret_cast<const void*>(k), (int)lds)) != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, dim3(threads), lds, st, g);
     } else {
         auto k = gemm_mx_kernel<BM, BN, WM, WN, STAGES, false, RD, PERSIST>;
-        if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess) return e;
+        if ((e = raised[0].ensure(reinterpret_cast<const void*>(k), (int)lds)) != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, dim3(threads), lds, st, g);
     }
     return hipGetLastError();

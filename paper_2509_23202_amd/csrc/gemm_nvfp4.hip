@@ -219,13 +219,14 @@ hipError_t launch_variant(const NvGemmArgs& g0, bool out_f32, hipStream_t st)
     if (cols <= 0) return hipSuccess;
     const dim3 grid((unsigned)(g.tiles_m * cols));
     hipError_t e;
+    static LdsAttrOnce raised[2];  // the dynamic-LDS limit of a kernel is raised once per device, not on every launch
     if (out_f32) {
         auto k = gemm_nv_kernel<BM, BN, WM, WN, STAGES, true>;
-        if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess) return e;
+        if ((e = raised[1].ensure(reinterpret_cast<const void*>(k), (int)lds)) != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, dim3(threads), lds, st, g);
     } else {
         auto k = gemm_nv_kernel<BM, BN, WM, WN, STAGES, false>;
-        if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess) return e;
+        if ((e = raised[0].ensure(reinterpret_cast<const void*>(k), (int)lds)) != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, dim3(threads), lds, st, g);
     }
     return hipGetLastError();

@@ -6,7 +6,36 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace fp4mr {
+
+// Process-wide tuning / cross-check switches behind fp4_set_option (plain ints: set them before concurrent use).
+struct Options {
+    int gemm_variant = 0;  // 0 = tile shape by the cost model, else a forced tile configuration of the GEMM kernels
+    int gemm_grid = 0;     // > 0: cap on the number of persistent workgroups (a small grid walks many tiles each)
+    int sw_codec = 0;      // != 0: element and scale codecs in integer arithmetic instead of the converting instructions
+};
+Options& options();
+
+// Raises a kernel's dynamic-LDS limit the first time the kernel is launched on a device (one object per kernel).
+struct LdsAttrOnce {
+    std::atomic<uint64_t> done{0};  // bit d: set on device d
+    hipError_t ensure(const void* kernel, int lds_bytes)
+    {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 63;  // (unknown device: set it every time)
+        const uint64_t bit = 1ull << dev;
+        if (dev != 63 && (done.load(std::memory_order_relaxed) & bit)) return hipSuccess;
+        const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e == hipSuccess) done.fetch_or(bit, std::memory_order_relaxed);
+        return e;
+    }
+};
+
+// largest valid forced tile configuration per format (fp4_gemm rejects anything else before it launches)
+constexpr int kMaxGemmVariantMx = 16;
+constexpr int kMaxGemmVariantNv = 3;
 
 // policy: group scales by 0 abs-max, 1 squared-error search, 2 rounded exponent with the 4/3 factor (MXFP4 only).
 // rot: null for the normalised Hadamard of size b, else a bf16 [b, b] row-major matrix (y = x . rot per block)
@@ -51,5 +80,9 @@ hipError_t launch_gptq_prepare(const float* H, int64_t K, float damp, bool use_o
 // Hessian of rotated calibration rows: Xr = x H_b (fp32 scratch [T,K]), H (+)= Xr^T Xr
 hipError_t launch_gptq_rotate_rows(const void* x, int64_t T, int64_t K, int b, float* out, hipStream_t st);
 hipError_t launch_gptq_hessian_product(const float* Xr, int64_t T, int64_t K, float* H, bool accumulate, hipStream_t st);
+
+// measurement aids (fp4_probe): which = 0 scaled-FP4 MFMA issue loop, 1 fp16 MFMA issue loop (buf: one 24-byte record per
+// compute unit), 2 streaming copy of the first half of buf to the second, 3 streaming read of the first half
+hipError_t launch_probe(int which, void* buf, size_t bytes, int iters, hipStream_t st);
 
 }  // namespace fp4mr

@@ -151,7 +151,10 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
     // Hadamard blocks wider than the operand: finished by butterfly levels across the lanes of a quad
     const int kron = (!a.rot && a.b > BP) ? (a.b == 2 * BP ? 1 : 2) : 0;
 
-    const int64_t NV = a.rows * a.K / BP;  // vectors in the tensor
+    // vectors in the tensor; the last one may be half a vector (16-element blocks and groups: rows * K = 16 * odd), its
+    // missing half loads as zeros and is neither stored nor scaled
+    const int64_t total = a.rows * a.K;
+    const int64_t NV = (total + BP - 1) / BP;
     const int64_t KC = a.K >> 7;
     const int64_t KS = (a.K + 511) >> 9;
     const uint16_t* __restrict__ x = static_cast<const uint16_t*>(a.x);
@@ -189,7 +192,8 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
                 v4i z = {0, 0, 0, 0};
                 if constexpr (LAYOUT == 0 && S == 1) {
                     // streamed once, whole cache lines per instruction: keep it out of the caches
-                    xin[u][s] = valid[u] ? __builtin_nontemporal_load(reinterpret_cast<const v4i*>(x + ebase[u] + 32 * s + 8 * q)) : z;
+                    const bool ok = valid[u] && ebase[u] + 8 * q + 8 <= total;
+                    xin[u][s] = ok ? __builtin_nontemporal_load(reinterpret_cast<const v4i*>(x + ebase[u] + 32 * s + 8 * q)) : z;
                 } else {
                     xin[u][s] = valid[u] ? *reinterpret_cast<const v4i*>(x + ebase[u] + 32 * s + 8 * q) : z;
                 }
@@ -225,8 +229,8 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
             GQ::template run<POL>(y, s_T, out, sc);
 
             if constexpr (LAYOUT == 0) {
-                if (valid[u]) {
-                    const int64_t e0 = ebase[u] + q * NO;
+                const int64_t e0 = ebase[u] + q * NO;
+                if (valid[u] && e0 + NO <= total) {
                     store_codes<GQ::ND>(a.codes + (e0 >> 1), out);
                     if ((q % GQ::LG) == 0) {
 #pragma unroll
@@ -546,7 +550,7 @@ hipError_t launch_mfma(const RqArgs& a0, int grid_cap, hipStream_t st, int* bloc
     constexpr int FR = (BP == 128 && LAYOUT == 0) ? 2 : 1;
     RqArgs a = a0;
     if (LAYOUT == 0) {
-        const int64_t nv = a.rows * a.K / BP;
+        const int64_t nv = (a.rows * a.K + BP - 1) / BP;  // (a trailing half vector counts)
         const int64_t nst = (nv + 15) / 16;
         a.n_items = (nst + FR * (128 / BP) - 1) / (FR * (128 / BP));
     } else {

@@ -27,7 +27,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"fp4_rotate_quantize", "fp4_rotate_quantize_dense", "fp4_fused_linear", "fp4_w4a16_linear", "fp4_quantize_weights", "fp4_gptq_quantize_weights", "fp4_gptq_prepare", "fp4_gptq_accumulate_hessian", "fp4_gemm", "fp4_workspace_bytes",
-            "fp4_packed_bytes", "fp4_status_string", "fp4_version"} <= set(names)
+            "fp4_packed_bytes", "fp4_status_string", "fp4_version", "fp4_set_option"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
     lib.fp4_version.restype = ctypes.c_int
@@ -108,6 +108,16 @@ def test_argument_validation_happens_before_any_launch(lib):
     assert b.workspace_bytes(b.OP_GPTQ_HESSIAN, 64, 0, 128, b.MXFP4) == 64 * 128 * 4
     assert b.workspace_bytes(b.OP_GPTQ_PREPARE, 0, 0, 256, b.MXFP4) >= 256 * 256 * 10
     assert b.workspace_bytes(b.OP_GPTQ, 128, 0, 256, b.MXFP4) >= 128 * 256 * 5 + 128 * 64 * 4 + 256 * 4
+    # few-token entry points: the quantizing one takes four tokens, the weight-only one sixteen
+    fl = lambda fn, M: fn(fake, M, 128, 32, fake, fake, 16, 0, fake, b.W_LAYOUT_GEMM, None)
+    assert fl(L.fp4_fused_linear, 5) == 2 and fl(L.fp4_fused_linear, 0) == 2 and fl(L.fp4_w4a16_linear, 17) == 2
+    # options: unknown option / value out of range; a forced tile configuration that the format does not have
+    assert L.fp4_set_option(99, 1) == 4 and L.fp4_set_option(b.OPT_GEMM_VARIANT, 17) == 4 and L.fp4_set_option(b.OPT_GEMM_GRID, -1) == 4
+    assert L.fp4_set_option(b.OPT_GEMM_VARIANT, 9) == 0
+    try:
+        assert L.fp4_gemm(fake, fake, fake, fake, fake, fake, 16, 16, 128, 1, fake, None, 0, b.A_LAYOUT_GEMM | b.W_LAYOUT_GEMM, None) == 4
+    finally:
+        assert L.fp4_set_option(b.OPT_GEMM_VARIANT, 0) == 0
     assert L.fp4_status_string(2).decode().startswith("bad shape")
     for s in range(8):
         assert L.fp4_status_string(s)

@@ -44,7 +44,40 @@ def oracle_rows(oracle, bits_rows, b, fmt, tensor_scale=None):
     return c, s, T, y
 
 
-def check_layer(fp4, oracle, recipe, M, K, N, fmt, b, n_m=40, n_n=56, salt=0):
+def check_stripes(fp4, oracle, qa, qw, out, M, K, N, fmt, aT, wT):
+    """Whole stripes of the output -- every column of 32 rows and every row of 32 columns -- against the oracle's fp64
+    product of the library's own codes.  Rows 248..263 and columns 248..263 cross a 256-tile boundary; rows
+    M/2 + 120 .. M/2 + 135 cross a wave-tile boundary inside a tile; columns 184..199 cross the 192-wide tile's boundary
+    (and a 64-column wave-tile boundary of the square tile).  A defect confined to one wave-tile position anywhere
+    along a tile row or column shows up here."""
+    import torch
+    rows = np.concatenate([np.arange(248, 264), np.arange(M // 2 + 120, M // 2 + 136)])
+    cols = np.concatenate([np.arange(184, 200), np.arange(248, 264)])
+    rows, cols = np.unique(rows[rows < M]), np.unique(cols[cols < N])
+    a_codes, a_scales, w_codes, w_scales = np_(qa[0]), np_(qa[1]), np_(qw[0]), np_(qw[1])
+    bad = 0
+    ac, asc = gemm_layout_to_canonical(a_codes, a_scales, rows, K, fmt)
+    A = oracle.dequantize(ac, asc, fmt, aT)
+    got = np_(out[torch.from_numpy(rows).cuda()].float()).astype(np.float64)
+    for n0 in range(0, N, 4096):          # all N weight rows, in slabs that keep the fp64 copy small
+        n1 = min(N, n0 + 4096)
+        wc, wsc = gemm_layout_to_canonical(w_codes, w_scales, np.arange(n0, n1), K, fmt)
+        Y, S = oracle.matmul(A, oracle.dequantize(wc, wsc, fmt, wT))
+        bad += int((np.abs(got[:, n0:n1] - Y) > 1e-3 * S + np.abs(Y) * 2.0 ** -8).sum())
+    say(f"   {len(rows)} whole rows: {bad} outputs outside the bound")
+    wc, wsc = gemm_layout_to_canonical(w_codes, w_scales, cols, K, fmt)
+    W = oracle.dequantize(wc, wsc, fmt, wT)
+    got = np_(out[:, torch.from_numpy(cols).cuda()].float()).astype(np.float64)
+    for m0 in range(0, M, 4096):
+        m1 = min(M, m0 + 4096)
+        ac, asc = gemm_layout_to_canonical(a_codes, a_scales, np.arange(m0, m1), K, fmt)
+        Y, S = oracle.matmul(oracle.dequantize(ac, asc, fmt, aT), W)
+        bad += int((np.abs(got[m0:m1] - Y) > 1e-3 * S + np.abs(Y) * 2.0 ** -8).sum())
+    say(f"   ... and {len(cols)} whole columns: {bad} outputs outside the bound in all")
+    assert bad == 0
+
+
+def check_layer(fp4, oracle, recipe, M, K, N, fmt, b, n_m=40, n_n=56, salt=0, stripes=False, extra_n=()):
     import torch
     rng = np.random.default_rng(K + N + M)
     xb, wb = recipe.x(M, K, salt=salt), recipe.w(N, K, salt=salt)
@@ -54,6 +87,8 @@ def check_layer(fp4, oracle, recipe, M, K, N, fmt, b, n_m=40, n_n=56, salt=0):
     out = fp4.fp4_gemm(qa[0], qa[1], qa[2], qw[0], qw[1], qw[2], M, N, K, fmt, flags=fp4.A_LAYOUT_GEMM | fp4.W_LAYOUT_GEMM)
     torch.cuda.synchronize()
     mi, ni = sample_rows(M, n_m, rng), sample_rows(N, n_n, rng)
+    if len(extra_n):
+        ni = np.unique(np.concatenate([ni, np.asarray([v for v in extra_n if 0 <= v < N], dtype=np.int64)]))
     ac, asc = gemm_layout_to_canonical(np_(qa[0]), np_(qa[1]), mi, K, fmt)
     wc, wsc = gemm_layout_to_canonical(np_(qw[0]), np_(qw[1]), ni, K, fmt)
     aT = wT = None
@@ -77,16 +112,20 @@ def check_layer(fp4, oracle, recipe, M, K, N, fmt, b, n_m=40, n_n=56, salt=0):
     tol = 1e-3 * S + np.abs(Y) * 2.0 ** -8
     say(f"   code mismatch X {fa:.1e} W {fw:.1e}; max err/(1e-3 S) = {float((err / (1e-3 * S)).max()):.3f}")
     assert np.all(err <= tol)
+    if stripes:
+        check_stripes(fp4, oracle, qa, qw, out, M, K, N, fmt, aT, wT)
 
 
-@pytest.mark.parametrize("layer", [1, 3, 0])
+@pytest.mark.parametrize("layer", [1, 3, 0, 2])
 def test_prefill_layers_mxfp4(fp4, oracle, layer):
+    """The four layers of the benchmark's step at M = 4096 in the launch configuration it times (layer 2 = gate_up:
+    persistent 256 x 256 tiles, seven 32-step tiles per workgroup), sampled outputs plus whole stripes."""
     L = inputs.LLAMA3_8B_LAYERS[layer]
-    check_layer(fp4, oracle, inputs.RECIPES[3], 4096, L.K, L.N, MX, 32, salt=layer)
+    check_layer(fp4, oracle, inputs.RECIPES[3], 4096, L.K, L.N, MX, 32, salt=layer, stripes=True)
 
 
 @pytest.mark.parametrize("M", [1, 16])
-@pytest.mark.parametrize("layer", [0, 2, 3])
+@pytest.mark.parametrize("layer", [0, 1, 2, 3])
 def test_decode_layers_mxfp4(fp4, oracle, layer, M):
     L = inputs.LLAMA3_8B_LAYERS[layer]
     check_layer(fp4, oracle, inputs.RECIPES[2], M, L.K, L.N, MX, 32, n_m=M, salt=layer)
@@ -107,7 +146,7 @@ def test_config1_whole_output(fp4, oracle):
 @pytest.mark.parametrize("M", [16, 4096])
 def test_nvfp4_70b_qkv_layer(fp4, oracle, M):
     L = inputs.LLAMA3_70B_LAYERS[0]
-    check_layer(fp4, oracle, inputs.RECIPES[4], M, L.K, L.N, NV, 16, n_m=min(M, 32), n_n=48)
+    check_layer(fp4, oracle, inputs.RECIPES[4], M, L.K, L.N, NV, 16, n_m=min(M, 32), n_n=48, stripes=M == 4096)
 
 
 @pytest.mark.parametrize("li,M", [(1, 16), (1, 4096), (2, 16), (2, 4096)])
@@ -180,9 +219,11 @@ def test_short_k_layers_take_the_two_workgroups_per_unit_tiles(fp4, oracle, M, N
     check_layer(fp4, oracle, inputs.RECIPES[3], M, 1024, N, MX, 32, n_m=48, n_n=64, salt=M)
 
 
-@pytest.mark.parametrize("M,N", [(2048, 10240), (2053, 10248)])
+@pytest.mark.parametrize("M,N", [(2048, 10240), (2053, 10248), (4000, 10200)])
 def test_nvfp4_two_launch_split_of_the_tile_grid(fp4, oracle, M, N):
     """More 256 x 256 tiles than one round of compute units and a partial round left over: the shape rule runs the tile
     columns that fill whole rounds as 256 x 256 tiles and the remaining columns as 128 x 128 tiles in a second launch
-    (ragged last tile row and column in the second case)."""
-    check_layer(fp4, oracle, inputs.RECIPES[4], M, 512, N, NV, 16, n_m=48, n_n=96, salt=M)
+    (ragged last tile row and column in the second and third case).  Columns either side of every multiple of 256
+    that can be the seam between the two launches are sampled on purpose."""
+    seams = [c * 256 + d for c in range(1, (N + 255) // 256) for d in (-1, 0)]
+    check_layer(fp4, oracle, inputs.RECIPES[4], M, 512, N, NV, 16, n_m=48, n_n=96, salt=M, extra_n=seams)

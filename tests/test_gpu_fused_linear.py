@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 from paper_2509_23202_amd import inputs
-from tests.gpu_util import MX, NV, to_dev_bf16
+from tests.gpu_util import MX, NV, compare_codes, to_dev_bf16
 
 pytestmark = pytest.mark.gpu
 
@@ -29,8 +29,8 @@ def np_(t):
 
 
 @pytest.mark.parametrize("out_f32", [False, True])
-@pytest.mark.parametrize("M,N,K,b", [(1, 256, 512, 32), (1, 4096, 4096, 32), (3, 520, 1152, 16), (16, 264, 128 * 9, 32),
-                                     (7, 136, 128 * 37, 32), (16, 1032, 4096, 16), (5, 24, 128, 32)])
+@pytest.mark.parametrize("M,N,K,b", [(1, 256, 512, 32), (1, 4096, 4096, 32), (3, 520, 1152, 16), (4, 264, 128 * 9, 32),
+                                     (2, 136, 128 * 37, 32), (4, 1032, 4096, 16), (3, 24, 128, 32)])
 def test_fused_equals_two_launch_path(fp4, M, N, K, b, out_f32):
     import torch
     r = inputs.RECIPES[2]
@@ -46,8 +46,12 @@ def test_fused_equals_two_launch_path(fp4, M, N, K, b, out_f32):
 
 
 @pytest.mark.parametrize("b", [16, 32, 64, 128])
-@pytest.mark.parametrize("M", [1, 16])
+@pytest.mark.parametrize("M", [1, 4])
 def test_fused_against_oracle(fp4, oracle, M, b):
+    """The one-launch result against the oracle's fp64 product of the codes the library itself produces for the same
+    inputs (stand-alone quantizer, canonical order), to the bare accumulation bound; those codes are in turn held to
+    the end-to-end rule against the oracle's.  One differing code can therefore neither hide in a widened product
+    tolerance nor break it."""
     import torch
     N, K = 272, 2048 + 384
     r = inputs.RECIPES[2]
@@ -55,17 +59,20 @@ def test_fused_against_oracle(fp4, oracle, M, b):
     qw = fp4.fp4_quantize_weights(to_dev_bf16(wb), b, MX, flags=fp4.LAYOUT_GEMM)
     say(f"fused vs oracle M={M} b={b}")
     got = fp4.fp4_fused_linear(to_dev_bf16(xb), b, qw[0], qw[1], N, MX, flags=fp4.OUT_F32)
+    qa_c = fp4.fp4_rotate_quantize(to_dev_bf16(xb), b, MX)
+    qw_c = fp4.fp4_quantize_weights(to_dev_bf16(wb), b, MX)
     torch.cuda.synchronize()
-    ac, asc, _, _ = oracle.rotate_quantize(xb, b, MX)
-    wc, wsc, _, _ = oracle.rotate_quantize(wb, b, MX)
+    ac, asc = np_(qa_c[0]).reshape(M, -1), np_(qa_c[1]).reshape(M, -1)
+    wc, wsc = np_(qw_c[0]).reshape(N, -1), np_(qw_c[1]).reshape(N, -1)
+    rac, rasc, _, ya = oracle.rotate_quantize(xb, b, MX)
+    rwc, rwsc, _, yw = oracle.rotate_quantize(wb, b, MX)
+    compare_codes(ac, asc, rac, rasc, ya, MX)
+    compare_codes(wc, wsc, rwc, rwsc, yw, MX)
     Y, S = oracle.matmul(oracle.dequantize(ac, asc, MX), oracle.dequantize(wc, wsc, MX))
     err = np.abs(np_(got).astype(np.float64) - Y)
-    # codes may differ from the oracle's on <= 1e-4 of the elements by one grid step (end-to-end rule): allow for a
-    # handful of such steps per output on top of the accumulation tolerance
-    step = 2.0 * np.abs(oracle.dequantize(wc, wsc, MX)).max() * np.abs(oracle.dequantize(ac, asc, MX)).max()
-    bad = err > 1e-3 * S
-    assert bad.mean() <= 0.02, bad.mean()
-    assert np.all(err <= 1e-3 * S + 4 * step)
+    # the in-GEMM quantizer runs the same rotation (32-wide operand, butterfly levels for wider blocks) and the same
+    # group quantizer as the stand-alone canonical-order kernel: same codes, so the bare accumulation bound applies
+    assert np.all(err <= 1e-3 * S)
 
 
 def test_fused_full_size_decode_layers(fp4, oracle):
@@ -90,7 +97,13 @@ def test_fused_rejects_what_it_cannot_do(fp4):
     w = torch.zeros(16 * 128, dtype=torch.uint8, device="cuda")
     with pytest.raises(fp4.Fp4mrError) as e:
         fp4.fp4_fused_linear(x, 32, w, w, 16, MX)
-    assert e.value.status == 2            # more than 16 tokens
+    assert e.value.status == 2            # more than four tokens
+    with pytest.raises(fp4.Fp4mrError) as e:
+        fp4.fp4_fused_linear(x[:5].contiguous(), 32, w, w, 16, MX)
+    assert e.value.status == 2 and "1..4 tokens" in str(e.value)
+    with pytest.raises(fp4.Fp4mrError) as e:
+        fp4.fp4_w4a16_linear(x, 32, w, w, 16, MX)
+    assert e.value.status == 2            # the weight-only variant takes up to 16
     with pytest.raises(fp4.Fp4mrError) as e:
         fp4.fp4_fused_linear(x[:4].contiguous(), 32, w, w, 16, NV)
     assert e.value.status == 4            # NVFP4 is not a one-pass operation

@@ -1,6 +1,6 @@
 """GPU parity for the squared-error scale policy (FP4MR_SCALE_MSE) against the CPU oracle.
 
-The policy takes an integer decision (which of three scale codes) from floating-point sums.  The oracle evaluates
+The policy takes an integer decision (which of three or ten scale codes) from floating-point sums.  The oracle evaluates
 the sums in fp64, the kernel in fp32, so the bar is: the scale codes are equal except for groups where the two best
 candidates are a near-tie (their fp64 errors differ by less than 1e-5 relative), the number of such groups is
 tiny, and wherever the scale code is equal the element codes are bit-exact (fed the oracle's fp32 values) or
@@ -48,7 +48,8 @@ def check_against_oracle(oracle, y, got_c, got_s, fmt, T, ref_c, ref_s, exact_co
         e_got = group_err(oracle, y, got_c, got_s, fmt, T)[~same]
         e_ref = group_err(oracle, y, ref_c, ref_s, fmt, T)[~same]
         assert np.all(np.abs(e_got - e_ref) <= tie_rtol * np.maximum(e_ref, e_got)), "scale differs away from a tie"
-        assert np.all(np.abs(got_s[~same].astype(int) - ref_s[~same].astype(int)) <= 2)
+        # (an NVFP4 near-tie may be between the two modes of the minimiser, half an octave apart)
+        assert np.all(np.abs(got_s[~same].astype(int) - ref_s[~same].astype(int)) <= (2 if fmt == MX else 9))
         assert n_diff <= max(2, int(2e-4 * same.size)), n_diff
     mask = np.repeat(same, G, axis=1)
     steps = grid_steps(unpack(got_c), unpack(ref_c))

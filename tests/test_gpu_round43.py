@@ -51,10 +51,9 @@ def adversarial_rows():
 
 
 @pytest.mark.parametrize("sw_codec", [False, True])
-def test_round43_bit_exact_on_oracle_values(fp4, oracle, sw_codec, monkeypatch):
+def test_round43_bit_exact_on_oracle_values(fp4, oracle, sw_codec, knobs):
     import torch
-    if sw_codec:
-        monkeypatch.setenv("FP4MR_SW_CODEC", "1")
+    knobs(sw_codec=sw_codec)
     rng = np.random.default_rng(700)
     M, K = 131, 2048 + 256
     y = (rng.laplace(size=(M, K)) * np.exp(rng.uniform(-2, 2, (M, K)))).astype(np.float32)
@@ -207,12 +206,12 @@ def test_round43_is_rejected_for_nvfp4_and_with_mse(fp4):
 
 
 @pytest.mark.parametrize("variant", [11, 13, 14])
-def test_tensor_level_factor_in_the_persistent_and_wide_tile_kernels(fp4, oracle, variant, monkeypatch):
+def test_tensor_level_factor_in_the_persistent_and_wide_tile_kernels(fp4, oracle, variant, knobs):
     """The factor is applied per tile before the epilogue: persistent workgroups walking several tiles (variants 11, 14)
     and the 256 x 192 tile (13, 14), bf16 output through the staged epilogue."""
     import torch
-    monkeypatch.setenv("FP4MR_GEMM_VARIANT", str(variant))
-    monkeypatch.setenv("FP4MR_GEMM_GRID", "2")
+    knobs(variant=variant)
+    knobs(grid=2)
     M, N, K, b = 272, 528, 1280, 32
     r = inputs.RECIPES[1]
     xb, wb = r.x(M, K, salt=11), r.w(N, K, salt=12)
