@@ -94,6 +94,25 @@ fp4mr_status_t fp4_rotate_quantize(const void* x, int64_t M, int64_t K, int had_
                                    void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
 
 /*
+ * fp4_rotate_quantize for callers that cannot allocate or pass device scratch -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc: the same operation, same kernels and bit-identical results, with the
+ * tensor-scale pass's scratch (FP4MR_STATIC_SCRATCH_BYTES: the per-wave partial maxima and the reduced maximum of an NVFP4
+ * call with a dynamic tensor scale) in a device array that lives inside the library, one copy per GPU, held until the
+ * process ends.  The call allocates nothing and frees nothing; its first use on a device asks the HIP runtime for the
+ * array's address (make that first call outside a graph capture).  Arguments as fp4_rotate_quantize without the
+ * workspace pair; M * K <= FP4MR_STATIC_MAX_ELEMENTS, beyond which the call returns FP4MR_ERR_SHAPE and launches
+ * nothing.  Every call on a GPU shares that GPU's array: two NVFP4 calls without FP4MR_STATIC_TENSOR_SCALE that overlap
+ * in time on one GPU (different streams, or different host threads) race on it and may return each other's tensor scale;
+ * calls on one stream, MXFP4 calls and static-scale calls do not touch it.  Nothing in the array needs clearing
+ * between calls: every word a call reads was written by that call's own first pass.
+ */
+#define FP4MR_STATIC_SCRATCH_BYTES (256 + 4096 * 4)
+#define FP4MR_STATIC_MAX_ELEMENTS (1ll << 36)
+fp4mr_status_t fp4_rotate_quantize_static(const void* x, int64_t M, int64_t K, int had_block, fp4mr_fmt_t fmt,
+                                          void* codes_out, void* scales_out, float* tensor_scale, uint32_t flags,
+                                          void* stream);
+
+/*
  * Scale policy.  By default a group's scale is the abs-max one (Section 3 "Scales").  With FP4MR_SCALE_MSE the
  * scale code is chosen to minimise the group's squared error sum_i (xhat_i - x_i)^2 (the objective of Section 4.1
  * "Ingredient 1"; the "MSE" method of Section 4.2 item 1) inside a window around the abs-max code c0, a candidate

@@ -39,6 +39,8 @@ lib.fp4_rotate_quantize.argtypes = _quant_sig
 lib.fp4_rotate_quantize.restype = _i32
 lib.fp4_quantize_weights.argtypes = _quant_sig
 lib.fp4_quantize_weights.restype = _i32
+lib.fp4_rotate_quantize_static.argtypes = [_p, _i64, _i64, _i32, _i32, _p, _p, _p, _u32, _p]
+lib.fp4_rotate_quantize_static.restype = _i32
 lib.fp4_rotate_quantize_dense.argtypes = [_p, _i64, _i64, _i32, _p, _i32, _p, _p, _p, _p, _sz, _u32, _p]
 lib.fp4_rotate_quantize_dense.restype = _i32
 lib.fp4_fused_linear.argtypes = [_p, _i64, _i64, _i32, _p, _p, _i64, _i32, _p, _u32, _p]
@@ -132,6 +134,17 @@ def fp4_rotate_quantize(x, had_block: int, fmt: int, *, flags: int = 0, tensor_s
     With flags=LAYOUT_GEMM the outputs are in the opaque GEMM layout; else canonical flat byte tensors
     (codes [M*K/2], scales [M*K/G])."""
     return _quantize(lib.fp4_rotate_quantize, OP_ROTATE_QUANTIZE, x, had_block, fmt, flags, tensor_scale, codes, scales, workspace)
+
+
+def fp4_rotate_quantize_static(x, had_block: int, fmt: int, *, flags: int = 0, tensor_scale, codes, scales):
+    """fp4_rotate_quantize without a workspace: the library's own static device scratch is used and nothing is allocated,
+    here or in the library -- the caller passes every output (tensor_scale: a 1-element float32 cuda tensor for NVFP4,
+    written unless flags has STATIC_TENSOR_SCALE; None for MXFP4)."""
+    assert x.is_cuda and x.dim() == 2 and x.is_contiguous() and x.dtype == torch.bfloat16
+    rows, K = x.shape
+    _check(lib.fp4_rotate_quantize_static(x.data_ptr(), rows, K, had_block, fmt, codes.data_ptr(), scales.data_ptr(),
+                                          _ptr(tensor_scale), flags, _stream()))
+    return codes, scales, tensor_scale
 
 
 def fp4_rotate_quantize_dense(x, rot, fmt: int, *, flags: int = 0, tensor_scale=None, codes=None, scales=None, workspace=None):

@@ -4,11 +4,19 @@
 
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "internal.hpp"
 #include "layout.hpp"
 
 using namespace fp4mr;
+
+// Scratch of fp4_rotate_quantize_static: the abs-max partials and the reduced abs-max of the NVFP4 tensor-scale pass
+// (what fp4_rotate_quantize takes as its workspace).  One copy per GPU, held until the process ends.  Host code never
+// uses this name as an address: static_scratch() asks the runtime for the array's device address once per device.
+constexpr size_t kStaticScratchBytes = 256 + 4096 * 4;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static_assert(kStaticScratchBytes == FP4MR_STATIC_SCRATCH_BYTES, "the header states the size of the static scratch");
 
 namespace {
 
@@ -40,9 +48,25 @@ size_t repack_bytes(int64_t rows, int64_t K, fp4mr_fmt_t fmt)
     return align256((size_t)gemm_codes_bytes(rows, K)) + align256((size_t)gemm_scales_bytes(rows, K, (int)fmt));
 }
 
+fp4mr_status_t static_scratch(void** out)
+{
+    static std::mutex mu;
+    static void* ptr[64] = {};  // per device: each GPU holds its own copy of the array at its own address
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return FP4MR_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return FP4MR_ERR_DEVICE;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return FP4MR_OK;
+}
+
 fp4mr_status_t quantize_common(const void* x, int64_t rows, int64_t K, int had_block, const void* rot, fp4mr_fmt_t fmt,
                                void* codes, void* scales, float* tensor_scale, void* workspace, size_t workspace_bytes,
-                               uint32_t flags, void* stream)
+                               uint32_t flags, void* stream, bool library_scratch = false)
 {
     if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return FP4MR_ERR_FMT;
     if (flags & ~kQuantFlags) return FP4MR_ERR_FMT;
@@ -60,7 +84,16 @@ fp4mr_status_t quantize_common(const void* x, int64_t rows, int64_t K, int had_b
     if (rows > ((int64_t)1 << 40) / K) return FP4MR_ERR_SHAPE;
     if (!aligned16(x) || !aligned16(codes) || !aligned16(scales)) return FP4MR_ERR_ALIGN;
     const size_t need = quant_workspace(fmt, flags);
-    if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return FP4MR_ERR_WORKSPACE;
+    if (library_scratch) {
+        // the allocation-free entry point: its scratch is the library's own device array (looked up after validation)
+        if (need > kStaticScratchBytes) return FP4MR_ERR_WORKSPACE;
+        if (need) {
+            const fp4mr_status_t s = static_scratch(&workspace);
+            if (s != FP4MR_OK) return s;
+        }
+    } else if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) {
+        return FP4MR_ERR_WORKSPACE;
+    }
 
     const hipError_t e = launch_rotate_quantize(x, rows, K, had_block, rot, (int)fmt, (flags & FP4MR_INPUT_F32) != 0,
                                                 (flags & FP4MR_LAYOUT_GEMM) ? 1 : 0, (flags & FP4MR_STATIC_TENSOR_SCALE) != 0,
@@ -124,6 +157,13 @@ fp4mr_status_t fp4_rotate_quantize(const void* x, int64_t M, int64_t K, int had_
                                    uint32_t flags, void* stream)
 {
     return quantize_common(x, M, K, had_block, nullptr, fmt, codes_out, scales_out, tensor_scale, workspace, workspace_bytes, flags, stream);
+}
+
+fp4mr_status_t fp4_rotate_quantize_static(const void* x, int64_t M, int64_t K, int had_block, fp4mr_fmt_t fmt, void* codes_out,
+                                          void* scales_out, float* tensor_scale, uint32_t flags, void* stream)
+{
+    if (M > 0 && K > 0 && M > (int64_t)FP4MR_STATIC_MAX_ELEMENTS / K) return FP4MR_ERR_SHAPE;
+    return quantize_common(x, M, K, had_block, nullptr, fmt, codes_out, scales_out, tensor_scale, nullptr, 0, flags, stream, true);
 }
 
 fp4mr_status_t fp4_rotate_quantize_dense(const void* x, int64_t M, int64_t K, int block, const void* rot_bf16, fp4mr_fmt_t fmt,

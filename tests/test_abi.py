@@ -27,7 +27,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"fp4_rotate_quantize", "fp4_rotate_quantize_dense", "fp4_fused_linear", "fp4_w4a16_linear", "fp4_quantize_weights", "fp4_gptq_quantize_weights", "fp4_gptq_prepare", "fp4_gptq_accumulate_hessian", "fp4_gemm", "fp4_workspace_bytes",
-            "fp4_packed_bytes", "fp4_status_string", "fp4_version", "fp4_set_option"} <= set(names)
+            "fp4_packed_bytes", "fp4_status_string", "fp4_version", "fp4_set_option", "fp4_rotate_quantize_static"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
     lib.fp4_version.restype = ctypes.c_int
@@ -108,6 +108,11 @@ def test_argument_validation_happens_before_any_launch(lib):
     assert b.workspace_bytes(b.OP_GPTQ_HESSIAN, 64, 0, 128, b.MXFP4) == 64 * 128 * 4
     assert b.workspace_bytes(b.OP_GPTQ_PREPARE, 0, 0, 256, b.MXFP4) >= 256 * 256 * 10
     assert b.workspace_bytes(b.OP_GPTQ, 128, 0, 256, b.MXFP4) >= 128 * 256 * 5 + 128 * 64 * 4 + 256 * 4
+    # the allocation-free variant validates like the ordinary one, and has its own size limit
+    qs = lambda **kw: L.fp4_rotate_quantize_static(kw.get("x", fake), kw.get("M", 4), kw.get("K", 128), kw.get("b", 32), kw.get("fmt", 0),
+                                                   fake, fake, kw.get("ts", None), kw.get("flags", 0), None)
+    assert qs(x=None) == 1 and qs(K=48) == 2 and qs(b=8) == 3 and qs(fmt=2) == 4 and qs(fmt=1) == 1
+    assert qs(M=1 << 20, K=1 << 17) == 2        # above FP4MR_STATIC_MAX_ELEMENTS
     # few-token entry points: the quantizing one takes four tokens, the weight-only one sixteen
     fl = lambda fn, M: fn(fake, M, 128, 32, fake, fake, 16, 0, fake, b.W_LAYOUT_GEMM, None)
     assert fl(L.fp4_fused_linear, 5) == 2 and fl(L.fp4_fused_linear, 0) == 2 and fl(L.fp4_w4a16_linear, 17) == 2

@@ -50,7 +50,10 @@ def check_against_oracle(oracle, y, got_c, got_s, fmt, T, ref_c, ref_s, exact_co
         assert np.all(np.abs(e_got - e_ref) <= tie_rtol * np.maximum(e_ref, e_got)), "scale differs away from a tie"
         # (an NVFP4 near-tie may be between the two modes of the minimiser, half an octave apart)
         assert np.all(np.abs(got_s[~same].astype(int) - ref_s[~same].astype(int)) <= (2 if fmt == MX else 9))
-        assert n_diff <= max(2, int(2e-4 * same.size)), n_diff
+        # how many groups may sit in a near-tie: with the oracle's own values as input (tie tolerance 1e-5) a handful; end
+        # to end (tolerance 1e-3, the library's rotation differs by fp32 rounding) the ten NVFP4 candidates are E4M3
+        # neighbours whose errors lie within 1e-3 of each other in about one group in a hundred
+        assert n_diff <= max(2, int((2e-4 if exact_codes else 2e-2) * same.size)), n_diff
     mask = np.repeat(same, G, axis=1)
     steps = grid_steps(unpack(got_c), unpack(ref_c))
     if exact_codes:
