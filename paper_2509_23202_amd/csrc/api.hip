@@ -215,6 +215,7 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
         if ((e = launch_repack_to_gemm(w_codes, w_scales, N, K, (int)fmt, c, s, st)) != hipSuccess) return FP4MR_ERR_DEVICE;
         w_codes = c;
         w_scales = s;
+        ws += repack_bytes(N, K, fmt);
     }
     const bool out_f32 = (flags & FP4MR_OUT_F32) != 0;
     const float alpha = scale43_factor(flags);
@@ -227,7 +228,7 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
     else if (fmt == FP4MR_MXFP4)
         e = launch_gemm_mxfp4(a_codes, a_scales, w_codes, w_scales, M, N, K, out, out_f32, variant, alpha, st);
     else
-        e = launch_gemm_nvfp4(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M, N, K, out, out_f32, variant, st);
+        e = launch_gemm_nvfp4(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M, N, K, out, out_f32, variant, ws, st);
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
 }
 
@@ -319,6 +320,8 @@ size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t 
         size_t n = 0;
         if (!(flags & FP4MR_A_LAYOUT_GEMM)) n += repack_bytes(M, K, fmt);
         if (!(flags & FP4MR_W_LAYOUT_GEMM)) n += repack_bytes(N, K, fmt);
+        // NVFP4 with more than 64 tokens: the activations are dequantized once to fp16 (2 bytes per element)
+        if (fmt == FP4MR_NVFP4 && M > 64) n += align256(nv16_workspace_bytes(M, K));
         return n;
     }
     return 0;

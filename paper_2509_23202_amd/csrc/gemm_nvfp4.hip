@@ -236,8 +236,11 @@ hipError_t launch_variant(const NvGemmArgs& g0, bool out_f32, hipStream_t st)
 
 hipError_t launch_gemm_nvfp4(const void* a_codes, const void* a_scales, const float* a_ts, const void* w_codes,
                              const void* w_scales, const float* w_ts, int64_t M, int64_t N, int64_t K, void* out,
-                             bool out_f32, int variant, hipStream_t st)
+                             bool out_f32, int variant, void* workspace, hipStream_t st)
 {
+    // By default many-token products go to the kernel that takes its activations as fp16 (gemm_nv16.hip); the tile
+    // kernels of this file, which dequantize both operands inside the product, remain as forced configurations.
+    if (variant == 0) return launch_gemm_nv16(a_codes, a_scales, a_ts, w_codes, w_scales, w_ts, M, N, K, out, out_f32, workspace, st);
     NvGemmArgs g{};
     g.a_codes = static_cast<const uint8_t*>(a_codes);
     g.a_scales = static_cast<const uint8_t*>(a_scales);
@@ -249,40 +252,6 @@ hipError_t launch_gemm_nvfp4(const void* a_codes, const void* a_scales, const fl
     g.M = M;
     g.N = N;
     g.K = K;
-    if (variant == 0) {
-        if (M <= 16) variant = 2;
-        else {
-            // 256 x 256 tiles on eight waves (wave tile 64 x 128: 12 fragment conversions per 128 MFMAs, against 8 per 64
-            // with 128 x 128 tiles on four waves) when they tile the chip in no more time: rounds of workgroups times
-            // (fixed cost + K-steps x measured step time; the small tile runs two workgroups per compute unit)
-            int cus = 256, dev = 0;
-            if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-            const double kt = (double)(K >> 7);
-            auto tiles = [&](int bm, int bn) { return (double)((M + bm - 1) / bm) * (double)((N + bn - 1) / bn); };
-            const double s3 = 10.0 + kt * 3.47, s1 = 8.0 + kt * 1.94;  // one round of each tile, microseconds
-            const double t3 = ceil(tiles(256, 256) / cus) * s3;
-            const double t1 = ceil(tiles(128, 128) / (2.0 * cus)) * s1;
-            variant = t3 < t1 ? 3 : 1;
-            // Whole rounds of 256 x 256 tiles for the tile columns they fill, the remaining columns as 128 x 128 tiles in a
-            // second launch: N = 10240 at M = 4096 is 640 big tiles = two and a half rounds -- two rounds of them and one
-            // round of 512 small tiles instead of three rounds (or five of small tiles).
-            const int tiles_m = (int)((M + 255) / 256), tiles_n = (int)((N + 255) / 256);
-            const int full_cols = (int)((int64_t)(tiles_m * tiles_n / cus) * cus / tiles_m);  // tile columns inside whole rounds
-            if (full_cols > 0 && full_cols < tiles_n) {
-                const double rest = (double)((M + 127) / 128) * (double)((N - (int64_t)full_cols * 256 + 127) / 128);
-                const double ts = ceil((double)full_cols * tiles_m / cus) * s3 + ceil(rest / (2.0 * cus)) * s1;
-                if (ts < 0.97 * std::min(t3, t1)) {
-                    g.tn0 = 0;
-                    g.tn_count = full_cols;
-                    const hipError_t e = launch_variant<256, 256, 64, 128, 4>(g, out_f32, st);
-                    if (e != hipSuccess) return e;
-                    g.tn0 = full_cols * 2;
-                    g.tn_count = 0;
-                    return launch_variant<128, 128, 64, 64, 4>(g, out_f32, st);
-                }
-            }
-        }
-    }
     switch (variant) {
         case 1: return launch_variant<128, 128, 64, 64, 4>(g, out_f32, st);
         case 2: return launch_variant<16, 256, 16, 64, 4>(g, out_f32, st);
