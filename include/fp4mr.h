@@ -161,6 +161,10 @@ fp4mr_status_t fp4_quantize_weights(const void* w, int64_t N, int64_t K, int had
  *   a_tensor_scale, w_tensor_scale   NVFP4: device floats s_T of each operand; MXFP4: NULL
  *   out          [M,N] row-major
  *   flags        layouts, FP4MR_OUT_F32, and for MXFP4 FP4MR_A_SCALE43 / FP4MR_W_SCALE43 (FP4MR_ERR_FMT with NVFP4)
+ *   workspace    fp4_workspace_bytes(FP4MR_OP_GEMM, M, N, K, fmt, flags) bytes: room for operands handed over in
+ *                row-major layout (they are re-tiled first), and, for NVFP4 with M > 64, 2 bytes per element of the
+ *                activation operand (its exact fp16 values code * s_G are written once, so that the product kernel
+ *                converts only W).  May be NULL when that size is 0 (MXFP4 with both operands in GEMM layout).
  */
 fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* a_tensor_scale,
                         const void* w_codes, const void* w_scales, const float* w_tensor_scale,

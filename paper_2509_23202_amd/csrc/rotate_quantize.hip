@@ -102,25 +102,35 @@ __device__ __forceinline__ void store_codes(uint8_t* p, const uint32_t (&w)[ND])
 
 // The same operand for a caller-supplied rotation (arXiv 2509.23202, Section 4.2 item 1: below k = 256 a dense
 // k x k transform stays memory-bound, so any rotation costs what the Hadamard costs): A[i][k] = R[32s + k][c(t,i)]
-// taken from the bf16 matrix R [b, b] in global memory, block-diagonal when b < BP.
+// taken from the bf16 matrix R [b, b] in global memory (16-byte aligned), block-diagonal when b < BP.
+// A lane's eight operand elements run down a COLUMN of R, so the workgroup first writes the b' x b' matrix transposed
+// into LDS (rows read with 16-byte loads, lanes along the rows of R: the 2-byte LDS writes of a wave fall into
+// consecutive addresses), then every lane fetches its BP*BP/64 elements with 16-byte LDS reads.  Row stride b' + 8
+// elements keeps those reads 16-byte aligned.  All threads of the workgroup must call this (it has a barrier).
 template <int BP>
-__device__ __forceinline__ void build_dense_operand(v8bf (&hop)[BP / 16][BP / 32], int g, int q, int b, const uint16_t* __restrict__ rot)
+constexpr int kDenseLdsBytes = BP * (BP + 8) * 2;
+
+template <int BP>
+__device__ __forceinline__ void build_dense_operand(v8bf (&hop)[BP / 16][BP / 32], int g, int q, int b, const uint16_t* __restrict__ rot,
+                                                    unsigned char* lds)
 {
-    constexpr int S = BP / 32, T = BP / 16, NO = BP / 4;
+    constexpr int S = BP / 32, T = BP / 16, NO = BP / 4, STRIDE = BP + 8;
+    uint16_t* const rt = reinterpret_cast<uint16_t*>(lds);
     const unsigned bm = (unsigned)b - 1u;
+    for (int idx = (int)threadIdx.x; idx < BP * BP / 8; idx += (int)blockDim.x) {
+        const unsigned r = (unsigned)idx % BP, c0 = 8u * ((unsigned)idx / BP);
+        const bool same = (r & ~bm) == (c0 & ~bm);  // b >= 16: a chunk of eight columns stays inside one diagonal block
+        v4i v = {0, 0, 0, 0};
+        if (same) v = *reinterpret_cast<const v4i*>(rot + (size_t)(r & bm) * (unsigned)b + (c0 & bm));
+#pragma unroll
+        for (unsigned e = 0; e < 8; ++e) rt[(c0 + e) * STRIDE + r] = (uint16_t)((uint32_t)v[e >> 1] >> (16 * (e & 1)));
+    }
+    __syncthreads();
 #pragma unroll
     for (int t = 0; t < T; ++t) {
-        const unsigned c = (unsigned)((g >> 2) * NO + 4 * t + (g & 3));
+        const int c = (g >> 2) * NO + 4 * t + (g & 3);
 #pragma unroll
-        for (int s = 0; s < S; ++s) {
-            const unsigned r_hi = (unsigned)(32 * s + 8 * q);
-            const bool same = (r_hi & ~bm) == (c & ~bm);
-            typedef unsigned short v8us __attribute__((ext_vector_type(8)));
-            v8us bits;
-#pragma unroll
-            for (unsigned e = 0; e < 8; ++e) bits[e] = same ? rot[((r_hi + e) & bm) * (unsigned)b + (c & bm)] : (unsigned short)0;
-            hop[t][s] = __builtin_bit_cast(v8bf, bits);
-        }
+        for (int s = 0; s < S; ++s) hop[t][s] = *reinterpret_cast<const v8bf*>(rt + c * STRIDE + 32 * s + 8 * q);
     }
 }
 
@@ -140,13 +150,15 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
     constexpr int NST = FR * (128 / BP); // supertiles per item
     using GQ = GroupQuant<G, NO, 16, HW>;
 
+    extern __shared__ __attribute__((aligned(16))) unsigned char rq_dyn_lds[];  // dense rotations: kDenseLdsBytes<BP>
+
     const int lane = threadIdx.x & 63;
     const int g = lane & 15, q = lane >> 4;
     const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
     const int64_t n_waves = (int64_t)gridDim.x * kWavesPerBlock;
 
     v8bf hop[T][S];
-    if (a.rot) build_dense_operand<BP>(hop, g, q, a.b, a.rot);
+    if (a.rot) build_dense_operand<BP>(hop, g, q, a.b, a.rot, rq_dyn_lds);  // (uniform branch: every thread takes it)
     else build_hadamard_operand<BP>(hop, g, q, a.b < BP ? a.b : BP);
     // Hadamard blocks wider than the operand: finished by butterfly levels across the lanes of a quad
     const int kron = (!a.rot && a.b > BP) ? (a.b == 2 * BP ? 1 : 2) : 0;
@@ -169,13 +181,14 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
     for (int64_t item = wave; item < a.n_items; item += n_waves) {
         int64_t ebase[NST];
         int64_t row[NST], k0[NST];
-        bool valid[NST];
+        bool valid[NST], frag_ok[NST];
         v4i xin[NST][S];
 #pragma unroll
         for (int u = 0; u < NST; ++u) {
             if constexpr (LAYOUT == 0) {
                 const int64_t v = (item * NST + u) * 16 + g;
                 valid[u] = v < NV;
+                frag_ok[u] = true;
                 ebase[u] = v * BP;
                 row[u] = 0;
                 k0[u] = 0;
@@ -184,7 +197,8 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
                 const int64_t rb = f / KC, kc = f - rb * KC;
                 row[u] = rb * 16 + g;
                 k0[u] = kc * 128 + (u % (128 / BP)) * BP;
-                valid[u] = row[u] < a.rows && rb * 16 < round_up(a.rows, 16);
+                valid[u] = row[u] < a.rows;
+                frag_ok[u] = rb * 16 < a.rows;  // (the last item may hold fewer than FR fragments)
                 ebase[u] = row[u] * a.K + k0[u];
             }
 #pragma unroll
@@ -239,6 +253,7 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
                 }
             } else {
                 // padded rows are written too (zeros come out of zero inputs), the buffers include the padding
+                if (!frag_ok[u]) continue;
                 const int64_t kk = k0[u] + q * NO;
                 store_codes<GQ::ND>(a.codes + codes_offset_gemm<1>(row[u], kk, KC), out);
                 if ((q % GQ::LG) == 0) {
@@ -322,10 +337,9 @@ __global__ __launch_bounds__(kThreads) void rq_frag_kernel(RqArgs a)
     }
 
     v8bf hop[T][S];
-    if (a.rot) build_dense_operand<BP>(hop, g, q, a.b, a.rot);
-    else build_hadamard_operand<BP>(hop, g, q, a.b < BP ? a.b : BP);
+    build_hadamard_operand<BP>(hop, g, q, a.b < BP ? a.b : BP);  // (the launcher sends dense rotations to rq_mfma_kernel)
     // Hadamard blocks wider than the operand: finished by butterfly levels across the lanes of a quad
-    const int kron = (!a.rot && a.b > BP) ? (a.b == 2 * BP ? 1 : 2) : 0;
+    const int kron = a.b > BP ? (a.b == 2 * BP ? 1 : 2) : 0;
 
     float s_T = 0.0f;
     if constexpr (G == 16) {
@@ -545,9 +559,9 @@ hipError_t launch_mfma(const RqArgs& a0, int grid_cap, hipStream_t st, int* bloc
         // few-token call has too few of those items to fill the GPU, so it keeps the one-fragment-per-wave kernel.
         if (frag_kernel_eligible(a0)) return launch_frag<BP, G, HW, POL>(a0, grid_cap, st, blocks_out);
     }
-    // two fragments' worth of loads in flight per wave for the widest block (canonical order only: there an
-    // item may run past the end and is masked per vector; GEMM-order items are whole fragments)
-    constexpr int FR = (BP == 128 && LAYOUT == 0) ? 2 : 1;
+    // two fragments' worth of loads in flight per wave for the widest block (its operand takes half the registers,
+    // so few waves are resident); an item may run past the end and is masked per vector / per fragment
+    constexpr int FR = (BP == 128) ? 2 : 1;
     RqArgs a = a0;
     if (LAYOUT == 0) {
         const int64_t nv = (a.rows * a.K + BP - 1) / BP;  // (a trailing half vector counts)
@@ -555,13 +569,14 @@ hipError_t launch_mfma(const RqArgs& a0, int grid_cap, hipStream_t st, int* bloc
         a.n_items = (nst + FR * (128 / BP) - 1) / (FR * (128 / BP));
     } else {
         const int64_t nf = round_up(a.rows, 16) / 16 * (a.K / 128);
-        a.n_items = nf;
+        a.n_items = (nf + FR - 1) / FR;
     }
     int64_t blocks = (a.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > grid_cap) blocks = grid_cap;
     if (blocks < 1) blocks = 1;
     if (blocks_out) *blocks_out = (int)blocks;
-    hipLaunchKernelGGL((rq_mfma_kernel<BP, G, LAYOUT, PASS, HW, FR, POL>), dim3((unsigned)blocks), dim3(kThreads), 0, st, a);
+    const size_t lds = a.rot ? (size_t)kDenseLdsBytes<BP> : 0;  // staging of the transposed rotation matrix
+    hipLaunchKernelGGL((rq_mfma_kernel<BP, G, LAYOUT, PASS, HW, FR, POL>), dim3((unsigned)blocks), dim3(kThreads), lds, st, a);
     return hipGetLastError();
 }
 
@@ -625,9 +640,10 @@ hipError_t launch_rotate_quantize(const void* x, int64_t rows, int64_t K, int b,
     a.static_scale = static_scale ? 1 : 0;
     // One work item per wave: the hardware's workgroup dispatcher balances the load better than a grid-stride loop
     // over resident waves does (measured on [16384, 8192]: 53 us against 59 us), and the per-wave set-up is cheap.
-    // A dense rotation gathers its operand from memory (up to 256 two-byte loads per lane for b = 128): there the
-    // grid is capped at 8 workgroups per compute unit and each wave walks several items.
-    const int grid_cap = rot ? 256 * 8 : 1 << 20;
+    // A dense rotation stages its operand through LDS once per workgroup: there the grid is capped at the workgroups
+    // that are resident at once (b = 128: the operand takes 128 registers, two workgroups per compute unit; else eight)
+    // and each wave walks several items.
+    const int grid_cap = rot ? (b > 64 ? 256 * 2 : 256 * 8) : 1 << 20;
 
     hipError_t e;
     if (fmt == 1 && !static_scale) {
