@@ -298,7 +298,7 @@ def main():
 
         try:
             # ---- measured ceilings (small kernels of the library itself): what the matrix pipes and HBM deliver on this machine
-            # when nothing else is in the way, and the shader clock under matrix load.  Run right behind the step loop.
+            # when nothing else is in the way.  Run right behind the step loop.
             cus = torch.cuda.get_device_properties(0).multi_processor_count
             rec = torch.zeros(3 * cus, dtype=torch.int64, device="cuda")
             ceil = {"compute_units": cus}
@@ -307,12 +307,13 @@ def main():
                 for _ in range(2):
                     step()               # come from the same thermal / clock state as the GEMMs
                 us = time_us(lambda: fp4.fp4_probe(which, rec, iters), n=4, warm=1)
-                r = rec.cpu().numpy().reshape(cus, 3)
-                clk_ghz = float(np.median(r[:, 0] / np.maximum(r[:, 1], 1))) * 0.1       # ticks of a 100 MHz counter
                 tf = cus * 8 * iters * 32 * flop_per_mfma / us / 1e6
-                # instruction issue interval per SIMD (two waves share it): shader clocks of the loop / MFMAs per SIMD
-                ceil[name] = {"tflops": round(tf, 1), "frac_of_datasheet": round(tf / peak, 4), "shader_clock_ghz": round(clk_ghz, 3),
-                              "clocks_per_mfma_per_simd": round(float(np.median(r[:, 0])) / (2 * iters * 32), 2), "launch_us": round(us, 1)}
+                # time between two MFMAs of one SIMD (two waves share it), from the event-timed launch alone: the
+                # datasheet rate is one per 16 clocks of 2.4 GHz = 6.67 ns.  (The kernel also records the shader's own
+                # cycle and reference counters; on this machine neither ticks at a documented rate, so they are not used.)
+                ceil[name] = {"tflops": round(tf, 1), "frac_of_datasheet": round(tf / peak, 4),
+                              "ns_per_mfma_per_simd": round(us * 1e3 / (2 * iters * 32), 2), "datasheet_ns_per_mfma_per_simd": 6.67,
+                              "launch_us": round(us, 1)}
             buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
             buf.fill_(1)
             us = time_us(lambda: fp4.fp4_probe(fp4.PROBE_COPY, buf), n=10, warm=3)
@@ -320,6 +321,25 @@ def main():
             us = time_us(lambda: fp4.fp4_probe(fp4.PROBE_READ, buf), n=10, warm=3)
             ceil["hbm_stream_read_gbs"] = round(buf.numel() / 2 / us / 1e3, 1)
             del buf
+            # the same copy at the size of one rotate+quantize call of the timed step (bf16 [4096, 4096] in, codes and
+            # scales out: 42.5 MB of traffic): start-up and drain are a visible share of a kernel this short, so this is
+            # the ceiling for the per-layer rq_gbs figures.  Cold operands: 24 buffers cycled (about 1 GB).
+            small_n = 42_500_000 // 32 * 32
+            smalls = [torch.ones(small_n, dtype=torch.uint8, device="cuda") for _ in range(24)]
+            for b_ in smalls[:4]:
+                fp4.fp4_probe(fp4.PROBE_COPY, b_)
+            torch.cuda.synchronize()
+            e0, e1 = ev_pair()
+            e0.record()
+            for b_ in smalls:
+                fp4.fp4_probe(fp4.PROBE_COPY, b_)
+            e1.record()
+            torch.cuda.synchronize()
+            ceil["hbm_stream_copy_gbs_at_42mb"] = round(small_n / (e0.elapsed_time(e1) / len(smalls) * 1e3) / 1e3, 1)
+            del smalls
+            for name_, l_ in result.get("layers", {}).items():
+                if isinstance(l_, dict) and "rq_gbs" in l_ and name_ != "down":
+                    l_["rq_frac_of_copy_at_size"] = round(l_["rq_gbs"] / ceil["hbm_stream_copy_gbs_at_42mb"], 3)
             # the cost of a launch that does (almost) nothing, as a kernel duration: the floor under every small call
             ceil["event_bracket_overhead_us"] = round(bracket_ms * 1e3, 2)
             ceil["note"] = ("issue loops: one 8-wave workgroup per compute unit, 16 independent accumulators per wave, operands in "

@@ -265,13 +265,15 @@ fp4mr_status_t fp4_set_option(int option, int value);
 
 /*
  * Measured ceilings for a roofline report (the datasheet peaks assume a clock the chip does not hold under matrix load).
- * Each call launches one kernel on `stream`; the caller times it (events) and reads the kernel's own clock report.
+ * Each call launches one kernel on `stream`; the caller times it with events.
  *   FP4MR_PROBE_MFMA_FP4   register-resident issue loop of the block-scaled FP4 MFMA (16x16x128, E2M1 x E2M1) the MXFP4
  *                          product is built on: one workgroup of eight waves per compute unit, sixteen independent
  *                          accumulators per wave, no memory traffic.  flops = CUs * 8 * iters * 32 * 65536
  *   FP4MR_PROBE_MFMA_F16   the same with the fp16 MFMA (16x16x32) of the NVFP4 product.  flops = CUs * 8 * iters * 32 * 16384
- *     buf: device, at least 24 * CUs bytes; receives per compute unit three uint64: shader clocks spent in the loop
- *     (s_memtime), ticks of the constant 100 MHz counter over the same span (s_memrealtime), a checksum.  iters >= 1.
+ *     buf: device, at least 24 * CUs bytes; receives per compute unit three uint64: the raw differences of the two
+ *     shader-readable counters (s_memtime, s_memrealtime) over the loop, and a checksum.  The counters' rates are
+ *     machine-dependent (measured against host time on an MI355X: about half the shader clock and about 52 MHz), so
+ *     rates are to be computed from the caller's event timing, not from them.  iters >= 1.
  *   FP4MR_PROBE_COPY       streaming copy of the first half of buf to the second half (16 bytes per lane, non-temporal):
  *                          bytes / 2 read + bytes / 2 written
  *   FP4MR_PROBE_READ       streaming read of the first half of buf: bytes / 2 read

@@ -3,10 +3,11 @@
 //   * a register-resident issue loop of the block-scaled FP4 MFMA the MXFP4 GEMM is built on, and of the fp16 MFMA
 //     the NVFP4 GEMM is built on -- eight waves per compute unit (two per SIMD, as in the GEMM kernels), sixteen
 //     independent accumulators per wave, no memory traffic at all: what the matrix pipes deliver when nothing else
-//     is in the way, together with the shader clock they run at while doing so;
+//     is in the way;
 //   * a streaming copy and a streaming read of a large buffer, 16 bytes per lane, non-temporal: what HBM delivers to
 //     the access pattern the rotate+quantize kernel uses.
-// The host times the launches with events; the kernels report their own clock.
+// The host times the launches with events.  The issue loops also record the raw differences of the two shader-readable
+// counters; their tick rates are machine-dependent, so no rate is derived from them here.
 #include "device_util.hpp"
 #include "internal.hpp"
 
@@ -14,8 +15,8 @@ namespace fp4mr {
 namespace {
 
 struct ProbeOut {
-    uint64_t shader_clocks;  // s_memtime ticks over the loop (shader clock)
-    uint64_t ref_ticks;      // s_memrealtime ticks over the loop (constant 100 MHz)
+    uint64_t shader_clocks;  // s_memtime ticks over the loop
+    uint64_t ref_ticks;      // s_memrealtime ticks over the loop
     uint64_t checksum;       // keeps the accumulators alive
 };
 
