@@ -174,11 +174,30 @@ def main():
     N_PRE = max(0, 128 - args.warmup)
     for _ in range(N_PRE):
         step()
-    torch.cuda.synchronize()
 
+    ev = []
+    # (nothing between this synchronize and the timed loop: a GPU left idle for even a millisecond comes back at a lower
+    # clock and needs some twenty steps to recover, which a short timed region would be charged for)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i % n_kern, ev)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    # Every kernel of the step gets at least MIN_EVENT_SAMPLES event samples: what the timed steps did not supply comes
+    # from further passes of the same step, right behind the timed region (untimed, GPU still busy and warm)
+    n_timed_samples = len(ev)
+    extra_passes = 0
+    count = lambda: {(n_, k_): sum(1 for a_, b_, _, _ in ev if (a_, b_) == (n_, k_)) for n_ in [s["L"].name for s in state] for k_ in ("rq", "gemm")}
+    while min(count().values()) < MIN_EVENT_SAMPLES and extra_passes < 64 * n_kern:
+        step(extra_passes % n_kern, ev)
+        extra_passes += 1
+    torch.cuda.synchronize()
     # An event pair around a launch also times the dispatch hand-off on both sides of it (a few microseconds that
     # back-to-back launches hide).  Calibrate that bracket overhead on a launch that does almost no work (a 16 x 128
-    # quantize, ~2 KB) and subtract it, so that the per-kernel figures line up with a kernel trace.
+    # quantize, ~2 KB) and subtract it, so that the per-kernel figures line up with a kernel trace.  This runs BEHIND the
+    # timed region: twenty near-empty launches in front of it leave the GPU at a lower clock for the next ~20 steps.
     N_CAL = 20
     tiny_x = torch.zeros((16, 128), dtype=torch.bfloat16, device="cuda")
     tiny_c = torch.empty(fp4.packed_bytes(16, 128, fp4.MXFP4, GL)[0], dtype=torch.uint8, device="cuda")
@@ -191,26 +210,9 @@ def main():
         fp4.fp4_rotate_quantize(tiny_x, b, fp4.MXFP4, flags=GL, codes=tiny_c, scales=tiny_s)
         e1.record()
         cal.append((e0, e1))
-    ev = []
-    # (nothing between this synchronize and the timed loop: a GPU left idle for even a millisecond comes back at a lower
-    # clock and needs some twenty steps to recover, which a short timed region would be charged for)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i % n_kern, ev)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
     TINY_KERNEL_MS = 0.0035  # the calibration launch itself (one wave, one fragment; 3.4-4.1 us in a kernel trace)
     bracket_ms = max(0.0, float(np.median([a.elapsed_time(b_) for a, b_ in cal])) - TINY_KERNEL_MS)
-    # Every kernel of the step gets at least MIN_EVENT_SAMPLES event samples: what the timed steps did not supply comes
-    # from further passes of the same step, right behind the timed region (untimed, GPU still busy and warm)
-    n_timed_samples = len(ev)
-    extra_passes = 0
-    count = lambda: {(n_, k_): sum(1 for a_, b_, _, _ in ev if (a_, b_) == (n_, k_)) for n_ in [s["L"].name for s in state] for k_ in ("rq", "gemm")}
-    while min(count().values()) < MIN_EVENT_SAMPLES and extra_passes < 64 * n_kern:
-        step(extra_passes % n_kern, ev)
-        extra_passes += 1
-    torch.cuda.synchronize()
     ms_per_step = dt * 1e3 / args.steps
     flops_step = sum(2.0 * M * s["L"].N * s["L"].K for s in state)
     value = flops_step / (ms_per_step * 1e-3) / 1e12
@@ -255,8 +257,8 @@ def main():
               "config": {"workload": f"llama3-8b-shaped prefill, MXFP4 W4A4, Hadamard block {b}, M={M}: qkv/o_proj/gate_up/down "
                                      "(BASELINE configs[2])", "M": M, "had_block": b, "format": "mxfp4",
                          "layers": [[L.name, L.K, L.N] for L in layers]},
-              "prewarm": f"{args.warmup} warm-up steps, then {N_PRE} further untimed steps (clock pre-warm: 128 untimed steps in all), then {N_CAL} "
-                         "untimed steps interleaved with the event-bracket calibration launches, then the timed region with no idle gap",
+              "prewarm": f"{args.warmup} warm-up steps, then {N_PRE} further untimed steps (clock pre-warm: 128 untimed steps in all), then the "
+                         f"timed region with no idle gap; the event-bracket calibration ({N_CAL} untimed steps) runs behind it",
               "pct_of_fp4_peak": round(100.0 * value / PEAK_FP4_TFLOPS, 2), "layers": layers_out, "roofline": roofline}
 
     if not args.no_extras:
