@@ -14,8 +14,8 @@
 // operand (columns = m).  A lane then owns four consecutive n of one m, i.e. one 8-byte bf16x4 store.
 //
 // Block tile BM x BN, K-step 128, STAGES-deep LDS ring fed by direct-to-LDS loads (tracked with vmcnt), one
-// barrier per K-step.  Scales take the same route (4-byte direct-to-LDS loads, two-deep ring), one dword per lane per
-// fragment row-block per 4 K-steps.
+// barrier per K-step.  Scales take the same route into a single LDS buffer: with four and more stages one 16-byte
+// copy per pair of row-blocks and 8 K-steps, with three stages one 4-byte copy per row-block and 4 K-steps.
 #include "device_util.hpp"
 #include "internal.hpp"
 #include "layout.hpp"
@@ -149,13 +149,25 @@ void gemm_mx_kernel(GemmArgs g)
     set_tile(tile);
 
     // Scales: every (row-block, 4 K-steps) owns 256 bytes = one dword per lane.  They travel global -> LDS with
-    // 4-byte direct-to-LDS loads into a two-deep ring (so no VGPR is ever the target of an in-flight load inside
-    // the main loop) and are read back once per 4 K-steps.
-    constexpr int NS = LPW;                                 // scale-block loads per wave per batch
-    constexpr int SCALE_BYTES = F * 256;
+    // direct-to-LDS loads (so no VGPR is ever the target of an in-flight load inside the main loop) and are read back
+    // once per 4 K-steps.
+    //   SC8 (four and more stages): a batch is 8 K-steps.  One 16-byte-per-lane copy fetches 512 bytes (two
+    //   consecutive 4-step blocks) of TWO row-blocks -- lanes 0..31 the first, lanes 32..63 the second; the address is
+    //   per lane, the LDS side is base + 16 * lane -- so a workgroup needs (FX + FW) / 2 copies per 8 K-steps instead of
+    //   2 * (FX + FW) four-byte ones.  The vector-memory path is a co-limiter of this loop (extra address traffic
+    //   measured far more expensive than its bytes), which is what this saves.  One buffer: the batch of steps
+    //   8b+8 .. 8b+15 is requested in step 8b+4, after every wave has read the second half of batch b into registers
+    //   (end of step 8b+3, then that step's barrier), and it has landed before the read at the end of step 8b+7
+    //   (loads complete in order, and step 8b+7 has waited for the stage requested in step 8b+5).
+    //   Otherwise (three stages): 4-byte copies, a batch is 4 K-steps.
+    constexpr bool SC8 = STAGES >= 4;
+    constexpr int XP = (FX + 1) / 2, WP = (FW + 1) / 2;    // pairs of row-blocks
+    constexpr int NS = SC8 ? (XP + WP + NW - 1) / NW : LPW; // scale loads per wave per batch
+    constexpr int SCALE_BYTES = SC8 ? (XP + WP) * 1024 : F * 256;
+    static_assert(NS <= LPW, "a scale load is issued in front of a fragment load of the same step");
     // The scale ring is two batches deep, or one with a three-stage operand ring: a batch is read into registers at the
     // end of the step before the one that issues its successor, with that step's barrier in between.
-    constexpr int SD = (STAGES == 3) ? 1 : 2;
+    constexpr int SD = 1;
     char* const scale_ring = smem + STAGES * STAGE_BYTES;
     const int kc_bytes = (int)KC * 1024, ks_bytes = (int)KS * 256;
 
@@ -175,7 +187,22 @@ void gemm_mx_kernel(GemmArgs g)
     // whenever the X fragments divide evenly among the waves, which keeps the step body free of branches
     auto is_x = [&](int f, int i) { return (FX % NW == 0) ? (i < FX / NW) : (f < FX); };
     auto issue_scale_one = [&](int ss, int i) {
-        char* base = scale_ring + (ss & (SD - 1)) * SCALE_BYTES;
+        if constexpr (SC8) {
+            // ss = the batch: 4-step blocks 2 * ss and 2 * ss + 1 (past the end: the last block again; what lies behind it
+            // in the 512 bytes is never used, and reads beyond the operand return zeros)
+            const int blk = min(2 * ss, (int)KS - 1);
+            const int p = min(wave + i * NW, XP + WP - 1);
+            const uint32_t half = (uint32_t)lane >> 5, col = ((uint32_t)lane & 31u) * 16u;
+            if ((XP % NW == 0) ? (i < XP / NW) : (p < XP)) {
+                const uint32_t rb = (uint32_t)min(2 * p + (int)half, a_rb_last);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_as, (lds_void*)(scale_ring + p * 1024), 16, rb * (uint32_t)ks_bytes + col, blk * 256, 0, 0);
+            } else {
+                const uint32_t rb = (uint32_t)min(2 * (p - XP) + (int)half, w_rb_last);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_ws, (lds_void*)(scale_ring + p * 1024), 16, rb * (uint32_t)ks_bytes + col, blk * 256, 0, 0);
+            }
+            return;
+        }
+        char* base = scale_ring;
         ss = ss < (int)KS ? ss : (int)KS - 1;  // the batch past the end re-reads the last one
         const int f = min(wave + i * NW, F - 1);
         if (is_x(f, i)) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_as, (lds_void*)(base + f * 256), 4, lane4, min(f, a_rb_last) * ks_bytes + ss * 256, 0, 0);
@@ -190,12 +217,20 @@ void gemm_mx_kernel(GemmArgs g)
 #pragma unroll
         for (int i = 0; i < NS; ++i) issue_scale_one(ss, i);
     };
-    auto read_scales = [&](int64_t ss, uint32_t (&dx)[TM], uint32_t (&dw)[TN]) {
-        const char* base = scale_ring + (ss & (SD - 1)) * SCALE_BYTES;
+    auto read_scales = [&](int64_t ss, uint32_t (&dx)[TM], uint32_t (&dw)[TN]) {  // ss = 4-step block
+        if constexpr (SC8) {
+            const char* base = scale_ring + (ss & 1) * 256;  // a row-block's 512 bytes: even block, odd block
 #pragma unroll
-        for (int j = 0; j < TM; ++j) dx[j] = *(reinterpret_cast<const uint32_t*>(base + (wm * TM + j) * 256) + lane);
+            for (int j = 0; j < TM; ++j) dx[j] = *(reinterpret_cast<const uint32_t*>(base + (wm * TM + j) * 512) + lane);
 #pragma unroll
-        for (int i = 0; i < TN; ++i) dw[i] = *(reinterpret_cast<const uint32_t*>(base + (FX + wn * TN + i) * 256) + lane);
+            for (int i = 0; i < TN; ++i) dw[i] = *(reinterpret_cast<const uint32_t*>(base + (2 * XP + wn * TN + i) * 512) + lane);
+        } else {
+            const char* base = scale_ring;
+#pragma unroll
+            for (int j = 0; j < TM; ++j) dx[j] = *(reinterpret_cast<const uint32_t*>(base + (wm * TM + j) * 256) + lane);
+#pragma unroll
+            for (int i = 0; i < TN; ++i) dw[i] = *(reinterpret_cast<const uint32_t*>(base + (FX + wn * TN + i) * 256) + lane);
+        }
     };
     auto read_x = [&](int kt, auto ptag, int j) {
         constexpr int P = decltype(ptag)::value;
@@ -217,7 +252,7 @@ void gemm_mx_kernel(GemmArgs g)
     issue_prologue();
     wait_vmcnt<(STAGES - 2) * LPW>();
 
-    // One K-step.  J = kt % 4 selects the scale byte (op_sel) and the X register half (J & 1).
+    // One K-step.  J = kt % 8 (SC8) or kt % 4: J & 3 selects the scale byte (op_sel), J & 1 the X register half.
     //   top:    stage kt+1 must have landed (this wave's copies: vmcnt; everybody's: barrier).  The same barrier
     //           says that every wave is done reading stage kt-1, whose LDS buffer is refilled with stage kt+STAGES-1.
     //   vmcnt:  allowed in flight = the STAGES-3 stages after kt+1, plus one scale batch when it was issued after
@@ -232,7 +267,8 @@ void gemm_mx_kernel(GemmArgs g)
         constexpr int J = decltype(jtag)::value;
         constexpr int SKEW = (2 * decltype(wtag)::value) % TM;  // MFMA index inside a group after which this wave issues its loads
         constexpr int P = J & 1;
-        constexpr bool batch_after = (J >= 1 && J <= STAGES - 3);
+        constexpr int JB = SC8 ? 4 : 0;  // the step of a period that requests the next scale batch
+        constexpr bool batch_after = (J >= JB + 1 && J <= JB + STAGES - 3);
         constexpr int ALLOWED = (STAGES - 3) * LPW + (batch_after ? NS : 0);
         if constexpr (PERSIST && J <= STAGES - 3) {
             // first steps of a follow-on tile, as long as the stage they wait for (kt + 1) is one of the STAGES - 1 that
@@ -263,7 +299,7 @@ void gemm_mx_kernel(GemmArgs g)
             for (int j = i * XPG; j < (i + 1) * XPG && j < TM; ++j) read_x(kt + 1, std::integral_constant<int, 1 - P>{}, j);
 #pragma unroll
             for (int j = 0; j < TM; ++j) {
-                acc[i][j] = mfma_fp4<J>(wring[i % RING], xf[P][j], acc[i][j], sw[i], sx[j]);
+                acc[i][j] = mfma_fp4<(J & 3)>(wring[i % RING], xf[P][j], acc[i][j], sw[i], sx[j]);
                 if (j == SKEW) {
                     // the four waves of a workgroup run in lockstep (one barrier per step); issuing their loads at
                     // different points of the group keeps them from queueing up behind each other at the CU's one
@@ -271,7 +307,9 @@ void gemm_mx_kernel(GemmArgs g)
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int d = i * DPG; d < (i + 1) * DPG && d < LPW; ++d) {
-                        if constexpr (J == 0) issue_scale_one((kt >> 2) + 1, d);
+                        if constexpr (J == JB) {
+                            if (d < NS) issue_scale_one(SC8 ? (kt >> 3) + 1 : (kt >> 2) + 1, d);
+                        }
                         issue_frag_one(kt_load, load_base, d);
                     }
                     __builtin_amdgcn_sched_barrier(0);
@@ -282,15 +320,21 @@ void gemm_mx_kernel(GemmArgs g)
             __builtin_amdgcn_sched_barrier(0);
         }
         // scales of the next four steps (their batch landed before this step's barrier)
-        if constexpr (J == 3) read_scales((kt >> 2) + 1, sx, sw);
+        if constexpr ((J & 3) == 3) read_scales((kt >> 2) + 1, sx, sw);
     };
 
     auto main_loop = [&](auto wtag) {
-        for (int kt0 = 0; kt0 < KT; kt0 += 4) {
+        for (int kt0 = 0; kt0 < KT; kt0 += (SC8 ? 8 : 4)) {
             step(kt0, std::integral_constant<int, 0>{}, wtag);
             if (kt0 + 1 < KT) step(kt0 + 1, std::integral_constant<int, 1>{}, wtag);
             if (kt0 + 2 < KT) step(kt0 + 2, std::integral_constant<int, 2>{}, wtag);
             if (kt0 + 3 < KT) step(kt0 + 3, std::integral_constant<int, 3>{}, wtag);
+            if constexpr (SC8) {
+                if (kt0 + 4 < KT) step(kt0 + 4, std::integral_constant<int, 4>{}, wtag);
+                if (kt0 + 5 < KT) step(kt0 + 5, std::integral_constant<int, 5>{}, wtag);
+                if (kt0 + 6 < KT) step(kt0 + 6, std::integral_constant<int, 6>{}, wtag);
+                if (kt0 + 7 < KT) step(kt0 + 7, std::integral_constant<int, 7>{}, wtag);
+            }
         }
     };
 
@@ -314,11 +358,17 @@ void gemm_mx_kernel(GemmArgs g)
 #pragma unroll
             for (int j = 0; j < TM; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
 
-        switch (wave & 3) {
-            case 0: main_loop(std::integral_constant<int, 0>{}); break;
-            case 1: main_loop(std::integral_constant<int, 1>{}); break;
-            case 2: main_loop(std::integral_constant<int, 2>{}); break;
-            default: main_loop(std::integral_constant<int, 3>{}); break;
+        if constexpr (SC8) {
+            // (the eight-step period doubles the loop body: one copy of it, every wave issuing its loads at the same
+            // point of an MFMA group; the per-wave skew below measured within noise)
+            main_loop(std::integral_constant<int, 0>{});
+        } else {
+            switch (wave & 3) {
+                case 0: main_loop(std::integral_constant<int, 0>{}); break;
+                case 1: main_loop(std::integral_constant<int, 1>{}); break;
+                case 2: main_loop(std::integral_constant<int, 2>{}); break;
+                default: main_loop(std::integral_constant<int, 3>{}); break;
+            }
         }
         wait_vmcnt<0>();  // the clamped loads of the last steps
         wait_lgkmcnt0();
@@ -439,7 +489,9 @@ hipError_t launch_variant(const GemmArgs& g0, bool out_f32, hipStream_t st)
     g.tiles_m = (int)((g.M + BM - 1) / BM);
     g.tiles_n = (int)((g.N + BN - 1) / BN);
     constexpr int threads = (BM / WM) * (BN / WN) * 64;
-    constexpr size_t lds = (size_t)STAGES * (BM + BN) / 16 * 1024 + (STAGES == 3 ? 1 : 2) * (size_t)(BM + BN) / 16 * 256;
+    // operand ring + scale buffer (four and more stages: 1 KB per pair of row-blocks; three stages: 256 B per row-block)
+    constexpr size_t lds = (size_t)STAGES * (BM + BN) / 16 * 1024 +
+                           (STAGES >= 4 ? (size_t)((BM / 16 + 1) / 2 + (BN / 16 + 1) / 2) * 1024 : (size_t)(BM + BN) / 16 * 256);
     const int ntiles = g.tiles_m * g.tiles_n;
     int nwg = ntiles;
     if (PERSIST) {
