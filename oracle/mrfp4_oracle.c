@@ -461,6 +461,48 @@ int orc_quantize_nvfp4_mse(const float *y, int64_t M, int64_t K, const float *s_
     return 0;
 }
 
+/* ---------------------------------------------------------------- alternating optimisation of the NVFP4 scales
+ * Section 4.1 "Ingredient 1": minimise sum_i (Xhat_i - X_i)^2 over the tensor scale s_T and the group scales
+ * s_G1..s_Gk "by alternating optimization over the block scales and the per-tensor scale".  The paper gives no
+ * further detail; the reading taken here:
+ *     start:        s_T = amax_T / 2688 (the abs-max tensor scale)
+ *     block step:   with s_T fixed, every group takes the E4M3 code of the squared-error search above
+ *                   (orc_quantize_nvfp4_mse) and its elements are rounded to nearest
+ *     tensor step:  with codes and group scales fixed, Xhat_i = s_T * v_i with v_i = s_G(i) * E2M1(code_i), and the
+ *                   minimiser is the least-squares factor  s_T = sum_i X_i v_i / sum_i v_i^2  (sums in fp64 in index
+ *                   order, quotient rounded once to binary32); if the denominator or the numerator is not positive
+ *                   s_T is kept and the iteration stops
+ *     `rounds` times (block step, tensor step), then one last block step so that the returned codes are the
+ *     round-to-nearest codes of the returned scales.
+ * s_T_trace (may be NULL) receives the rounds + 1 tensor scales in order. */
+int orc_quantize_nvfp4_mse_alt(const float *y, int64_t M, int64_t K, int rounds, uint8_t *codes, uint8_t *scales,
+                               float *s_T_out, float *s_T_trace)
+{
+    const int G = 16;
+    if (K % G != 0 || rounds < 0) return -1;
+    float s_T = 0.0f;
+    if (orc_quantize_nvfp4_mse(y, M, K, NULL, codes, scales, &s_T) != 0) return -1;
+    if (s_T_trace) s_T_trace[0] = s_T;
+    for (int r = 0; r < rounds; ++r) {
+        double num = 0.0, den = 0.0;
+        for (int64_t i = 0; i < M * K; ++i) {
+            const uint8_t byte = codes[i / 2];
+            const uint8_t code = (i & 1) ? (uint8_t)(byte >> 4) : (uint8_t)(byte & 15);
+            const double v = orc_e2m1_decode(code) * orc_e4m3_decode(scales[i / G]);
+            num += (double)y[i] * v;
+            den += v * v;
+        }
+        if (den > 0.0 && num > 0.0) {
+            s_T = (float)(num / den);
+            float unused;
+            if (orc_quantize_nvfp4_mse(y, M, K, &s_T, codes, scales, &unused) != 0) return -1;
+        }
+        if (s_T_trace) s_T_trace[r + 1] = s_T;
+    }
+    *s_T_out = s_T;
+    return 0;
+}
+
 /* ---------------------------------------------------------------- rounded, 4/3-rescaled E8M0 scale
  * Appendix "MXFP scale fitting", first equation (and Appendix "Scale quantization analysis"): the scale of a group
  * is quantized as  (4/3) * 2^clamp(round(log2 s)).  Readings taken here: s is the ideal abs-max scale amax / 6 (the

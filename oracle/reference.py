@@ -72,6 +72,8 @@ def _load():
         L.orc_quantize_mxfp4_mse.restype = i32
         L.orc_quantize_nvfp4_mse.argtypes = [p, i64, i64, p, p, p, p]
         L.orc_quantize_nvfp4_mse.restype = i32
+        L.orc_quantize_nvfp4_mse_alt.argtypes = [p, i64, i64, i32, p, p, p, p]
+        L.orc_quantize_nvfp4_mse_alt.restype = i32
         L.orc_quantize_mxfp4_round43.argtypes = [p, i64, i64, p, p]
         L.orc_quantize_mxfp4_round43.restype = i32
         L.orc_e8m0_round43_from_amax.argtypes = [ctypes.c_double]
@@ -197,6 +199,22 @@ def quantize(y_f32: np.ndarray, fmt: int, tensor_scale: float | None = None, pol
     if rc != 0:
         raise ValueError("quantize failed")
     return codes, scales, s_T
+
+
+def quantize_nvfp4_alternating(y_f32: np.ndarray, rounds: int = 3):
+    """NVFP4 with the alternating optimisation of group scales and tensor scale (Section 4.1 "Ingredient 1").
+    fp32 [M,K] -> (codes, scales, s_T float32, trace float32[rounds + 1] of the tensor scales)."""
+    y = np.ascontiguousarray(y_f32, dtype=np.float32)
+    M, K = y.shape
+    if K % 16:
+        raise ValueError(f"quantize: K={K} not a multiple of 16")
+    codes = np.empty((M, K // 2), dtype=np.uint8)
+    scales = np.empty((M, K // 16), dtype=np.uint8)
+    s_out = np.zeros(1, dtype=np.float32)
+    trace = np.zeros(rounds + 1, dtype=np.float32)
+    if _load().orc_quantize_nvfp4_mse_alt(_ptr(y), M, K, int(rounds), _ptr(codes), _ptr(scales), _ptr(s_out), _ptr(trace)) != 0:
+        raise ValueError("quantize failed")
+    return codes, scales, np.float32(s_out[0]), trace
 
 
 def dequantize(codes: np.ndarray, scales: np.ndarray, fmt: int, s_T=None) -> np.ndarray:

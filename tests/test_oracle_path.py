@@ -584,6 +584,83 @@ def test_mse_policy_nvfp4_reaches_the_global_minimum_over_every_scale_code(oracl
         assert rate >= 0.999
 
 
+# ---------------------------------------------------------------- alternating optimisation (group scales / tensor scale)
+def _e4m3_table():
+    return np.array([(c & 7) * 2.0 ** -9 if (c >> 3) == 0 else (1 + (c & 7) / 8) * 2.0 ** ((c >> 3) - 7) for c in range(0x7f)])
+
+
+def _unit_values(codes, scales):
+    """v_i = s_G * E2M1(code_i): the quantized tensor without its tensor scale, from independent NumPy tables."""
+    grid = np.array([0, .5, 1, 1.5, 2, 3, 4, 6, -0.0, -.5, -1, -1.5, -2, -3, -4, -6])
+    lo, hi = codes & 15, codes >> 4
+    q = np.stack([grid[lo], grid[hi]], axis=-1).reshape(codes.shape[0], -1)
+    return q * np.repeat(_e4m3_table()[scales], 16, axis=1)
+
+
+def test_alternating_nvfp4_zero_rounds_is_the_mse_policy(oracle):
+    rng = np.random.default_rng(91)
+    y = rng.standard_t(3, size=(24, 512)).astype(np.float32)
+    c0, s0, T0 = oracle.quantize(y, NV, policy="mse")
+    c, s, T, trace = oracle.quantize_nvfp4_alternating(y, 0)
+    assert T == T0 and trace[0] == T0 and np.array_equal(c, c0) and np.array_equal(s, s0)
+
+
+def test_alternating_nvfp4_tensor_step_is_the_least_squares_optimum(oracle):
+    """Section 4.1 "Ingredient 1": the tensor scale that minimises sum (s_T v_i - x_i)^2 for fixed codes and group scales.
+    Checked without the closed form: for the codes of the block step at trace[r], the error at trace[r + 1] is not above the
+    error at trace[r], nor above the error at trace[r + 1] moved by +-1e-4 and +-1e-2 relative (a parabola's minimum, up
+    to the binary32 rounding of the scale)."""
+    from paper_2509_23202_amd import inputs
+    for rid, b in ((4, 1), (4, 16), (6, 1)):
+        y = oracle.rotate(inputs.RECIPES[rid].x(32, 1024, salt=3), b)
+        c, s, T, trace = oracle.quantize_nvfp4_alternating(y, 3)
+        g = y.astype(np.float64)
+        for r in range(3):
+            cr, sr, _ = oracle.quantize(y, NV, tensor_scale=float(trace[r]), policy="mse")
+            v = _unit_values(cr, sr)
+            err = lambda t: float(((t * v - g) ** 2).sum())
+            e_new = err(float(trace[r + 1]))
+            assert e_new <= err(float(trace[r])) * (1 + 1e-12)
+            for rel in (1e-4, -1e-4, 1e-2, -1e-2):
+                assert e_new <= err(float(trace[r + 1]) * (1 + rel)) * (1 + 1e-9), (rid, b, r, rel)
+        # the returned codes are the round-to-nearest codes of the returned scales (one last block step)
+        cf, sf, _ = oracle.quantize(y, NV, tensor_scale=float(T), policy="mse")
+        assert np.array_equal(cf, c) and np.array_equal(sf, s) and T == trace[3]
+
+
+def test_alternating_nvfp4_never_ends_above_the_abs_max_tensor_scale(oracle):
+    """Direction only (the paper reports "consistent improvements" for NVFP4 without rotations, no numbers): the total
+    squared error after the alternation is not above the one of the group search with the abs-max tensor scale."""
+    from paper_2509_23202_amd import inputs
+    for rid in (1, 4, 6):
+        y = oracle.rotate(inputs.RECIPES[rid].x(32, 1024, salt=5), 1)
+        c0, s0, T0 = oracle.quantize(y, NV, policy="mse")
+        c, s, T, _ = oracle.quantize_nvfp4_alternating(y, 3)
+        e0 = ((oracle.dequantize(c0, s0, NV, T0) - y) ** 2).sum()
+        e1 = ((oracle.dequantize(c, s, NV, T) - y) ** 2).sum()
+        print(f"recipe {rid}: squared error {e1 / e0:.5f} of the abs-max tensor scale's, s_T {T0:.6g} -> {T:.6g}")
+        assert e1 <= e0 * (1 + 1e-9)
+
+
+def test_alternating_nvfp4_keeps_an_exactly_representable_tensor(oracle):
+    """grid value x E4M3 value x s_T with the tensor's largest element on (6, 448): zero error before, zero error and the
+    same tensor scale after (the least-squares factor of an exact fit is the scale itself)."""
+    rng = np.random.default_rng(93)
+    grid = np.array([0, .5, 1, 1.5, 2, 3, 4, 6])
+    e4 = _e4m3_table()
+    M, K = 8, 256
+    sc = e4[rng.integers(0x40, 0x7f, size=(M, K // 16))]
+    q = grid[rng.integers(0, 8, size=(M, K))] * rng.choice([-1.0, 1.0], size=(M, K))
+    q.reshape(M, K // 16, 16)[:, :, 0] = 6.0          # every group's largest element sits on the top grid value
+    sc[0, 0] = 448.0
+    s_T = 2.0 ** -7
+    y = (q * np.repeat(sc, 16, axis=1) * s_T).astype(np.float32)
+    assert np.array_equal(y.astype(np.float64), q * np.repeat(sc, 16, axis=1) * s_T)   # exact in binary32
+    c, s, T, trace = oracle.quantize_nvfp4_alternating(y, 3)
+    assert np.all(trace == np.float32(s_T)) and T == np.float32(s_T)
+    assert np.array_equal(oracle.dequantize(c, s, NV, T), y.astype(np.float64))
+
+
 # ---------------------------------------------------------------- weight-only (W4A16) reference
 def test_round_to_bf16_against_torch_cast(oracle):
     import torch
