@@ -70,7 +70,8 @@ enum {
     FP4MR_SCALE_MSE = 1u << 6,            /* quantize ops: group scale by squared-error search (below)        */
     FP4MR_SCALE_ROUND43 = 1u << 7,        /* MXFP4 quantize ops: rounded exponent, scale (4/3) 2^k (below)    */
     FP4MR_A_SCALE43 = 1u << 8,            /* MXFP4 products: the A operand was quantized with SCALE_ROUND43   */
-    FP4MR_W_SCALE43 = 1u << 9             /* MXFP4 products: the W operand was quantized with SCALE_ROUND43   */
+    FP4MR_W_SCALE43 = 1u << 9,            /* MXFP4 products: the W operand was quantized with SCALE_ROUND43   */
+    FP4MR_SCALE_FIT_TENSOR = 1u << 10     /* NVFP4 quantize ops, with SCALE_MSE: also fit the tensor scale    */
 };
 
 /* operation selector for fp4_workspace_bytes */
@@ -122,6 +123,15 @@ fp4mr_status_t fp4_rotate_quantize_static(const void* x, int64_t M, int64_t K, i
  * The windows hold the minimiser over ALL scale codes in all but about 1e-4 of the groups of heavy-tailed inputs
  * (for NVFP4 it sits either next to c0 or about half an octave above it).  Hardware codec only.  Costs about twice
  * (MXFP4) / four times (NVFP4) the vector-ALU work of abs-max.
+ *
+ * With FP4MR_SCALE_MSE | FP4MR_SCALE_FIT_TENSOR (NVFP4 only, not with FP4MR_STATIC_TENSOR_SCALE: FP4MR_ERR_FMT) the tensor
+ * scale is fitted too -- the alternating optimisation over the block scales and the per-tensor scale of Section 4.1
+ * "Ingredient 1", meant for weights (offline): starting from the abs-max tensor scale, three times { group search as
+ * above with s_T fixed; s_T = sum_i x_i v_i / sum_i v_i^2 with v_i = s_G * E2M1(code_i), the least-squares factor for
+ * fixed codes and group scales, sums in fp64, one rounding to binary32 }, then the quantization proper with the final
+ * s_T.  Eight passes over the input instead of two; workspace per fp4_workspace_bytes (about 80 KB).  Deterministic;
+ * the fp64 sums are added in a fixed order that differs from a sequential one, so s_T can differ from a sequential
+ * evaluation in its last bit.
  *
  * With FP4MR_SCALE_ROUND43 (MXFP4 only; not together with FP4MR_SCALE_MSE: FP4MR_ERR_FMT) the scale follows the
  * first equation of the appendix on MXFP scale fitting: s = (4/3) 2^k with k = clamp(round(log2(amax / 6)), -127, 127).

@@ -28,6 +28,7 @@ W_LAYOUT_GEMM = 1 << 4
 OUT_F32 = 1 << 5
 SCALE_MSE = 1 << 6
 SCALE_ROUND43 = 1 << 7
+SCALE_FIT_TENSOR = 1 << 10
 A_SCALE43 = 1 << 8
 W_SCALE43 = 1 << 9
 OPT_GEMM_VARIANT, OPT_GEMM_GRID, OPT_SW_CODEC = 0, 1, 2

@@ -34,7 +34,52 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWavesPerBlock = kThreads / kWave;
-constexpr int kAmaxPassBlocks = 1024;  // grid cap of the NVFP4 abs-max pass (4096 partials)
+constexpr int kAmaxPassBlocks = 1024;  // grid cap of the NVFP4 abs-max pass and of the tensor-scale fit pass (4096 partials)
+constexpr int kFitRounds = 3;          // alternations of the tensor-scale fit
+
+// Tensor-scale fit (Section 4.1 "Ingredient 1": alternating optimisation over the block scales and the per-tensor scale).
+// With codes and group scales fixed the quantized tensor is s_T * v, v_i = s_G * E2M1(code_i), and the minimiser of
+// sum (s_T v_i - x_i)^2 is sum x v / sum v v.  A lane adds its values' terms in fp64: v has at most 6 significant bits
+// and x is binary32, so every product is exact and only the additions round.
+template <int NO, int ND, int NG, bool HW>
+__device__ __forceinline__ void fit_accumulate(const float (&y)[NO], const uint32_t (&out)[ND], const uint32_t (&sc)[NG], double& num, double& den)
+{
+    typedef float v2f_t __attribute__((ext_vector_type(2)));
+    constexpr int DPG = ND / NG;  // code dwords per group
+#pragma unroll
+    for (int gi = 0; gi < NG; ++gi) {
+        const float s_G = e4m3_decode<HW>(sc[gi]);
+#pragma unroll
+        for (int d = 0; d < DPG; ++d) {
+            const uint32_t p = out[gi * DPG + d];
+            const v2f_t q0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(p, 1.0f, 0);
+            const v2f_t q1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(p, 1.0f, 1);
+            const v2f_t q2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(p, 1.0f, 2);
+            const v2f_t q3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(p, 1.0f, 3);
+            const float q[8] = {q0[0], q0[1], q1[0], q1[1], q2[0], q2[1], q3[0], q3[1]};
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const double v = (double)(q[i] * s_G);  // exact in binary32
+                num = fma((double)y[(gi * DPG + d) * 8 + i], v, num);
+                den = fma(v, v, den);
+            }
+        }
+    }
+}
+
+// the wave's two sums -> its slot of the partials (one slot per wave, no atomics: fixed order, deterministic)
+__device__ __forceinline__ void fit_store_partial(double num, double den, double* partial, int64_t wave, int lane)
+{
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+        num += __shfl_xor(num, m);
+        den += __shfl_xor(den, m);
+    }
+    if (lane == 0) {
+        partial[2 * wave] = num;
+        partial[2 * wave + 1] = den;
+    }
+}
 
 struct RqArgs {
     const void* x;
@@ -44,6 +89,7 @@ struct RqArgs {
     uint32_t* amax_bits;   // NVFP4 dynamic: bit pattern of max |y| over the tensor (workspace)
     uint32_t* amax_partial;  // NVFP4 dynamic: one partial maximum per wave of the abs-max pass (workspace)
     int n_partials;          // > 0: the quantize pass reduces that many partials itself (small calls: no finalize launch)
+    double* fit_partial;     // tensor-scale fit: per wave of the fit pass, sum x v and sum v v (workspace)
     int64_t rows, K;
     int64_t n_items;
     int b;                 // rotation block (1 = none)
@@ -172,11 +218,12 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
     const uint16_t* __restrict__ x = static_cast<const uint16_t*>(a.x);
 
     float s_T = 0.0f;
-    if constexpr (G == 16 && PASS == 0) {
+    if constexpr (G == 16 && PASS != 1) {
         s_T = load_tensor_scale(a, (int)(threadIdx.x & 63));
         if (!a.static_scale && blockIdx.x == 0 && threadIdx.x == 0) *a.tensor_scale = s_T;
     }
     float hmax = 0.0f;
+    double fit_num = 0.0, fit_den = 0.0;
 
     for (int64_t item = wave; item < a.n_items; item += n_waves) {
         int64_t ebase[NST];
@@ -241,6 +288,11 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
                 }
             uint32_t out[GQ::ND], sc[GQ::NG];
             GQ::template run<POL>(y, s_T, out, sc);
+            if constexpr (PASS == 2) {
+                // (vectors past the end were loaded as zeros: they add nothing)
+                if constexpr (G == 16) fit_accumulate<NO, GQ::ND, GQ::NG, HW>(y, out, sc, fit_num, fit_den);
+                continue;
+            }
 
             if constexpr (LAYOUT == 0) {
                 const int64_t e0 = ebase[u] + q * NO;
@@ -275,6 +327,7 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
             a.amax_partial[wave] = __float_as_uint(ymax);  // one slot per wave, reduced by amax_finalize_kernel
         }
     }
+    if constexpr (PASS == 2) fit_store_partial(fit_num, fit_den, a.fit_partial, wave, lane);
 }
 
 // ------------------------------------------------------------------------------------------------------
@@ -438,11 +491,12 @@ __global__ __launch_bounds__(kThreads) void q_direct_kernel(RqArgs a)
     const TIN* __restrict__ x = static_cast<const TIN*>(a.x);
 
     float s_T = 0.0f;
-    if constexpr (G == 16 && PASS == 0) {
+    if constexpr (G == 16 && PASS != 1) {
         s_T = load_tensor_scale(a, (int)(threadIdx.x & 63));
         if (!a.static_scale && blockIdx.x == 0 && threadIdx.x == 0) *a.tensor_scale = s_T;
     }
     float hmax = 0.0f;
+    double fit_num = 0.0, fit_den = 0.0;
 
     for (int64_t item = wave; item < a.n_items; item += n_waves) {
 #pragma unroll
@@ -487,6 +541,10 @@ __global__ __launch_bounds__(kThreads) void q_direct_kernel(RqArgs a)
             }
             uint32_t out[1], sc[1];
             GQ::template run<POL>(y, s_T, out, sc);
+            if constexpr (PASS == 2) {
+                if constexpr (G == 16) fit_accumulate<8, 1, 1, HW>(y, out, sc, fit_num, fit_den);
+                continue;
+            }
             if constexpr (LAYOUT == 0) {
                 if (valid) {
                     *reinterpret_cast<uint32_t*>(a.codes + (e0 >> 1)) = out[0];
@@ -506,6 +564,7 @@ __global__ __launch_bounds__(kThreads) void q_direct_kernel(RqArgs a)
         for (int m = 1; m < 64; m <<= 1) hmax = fmaxf(hmax, __shfl_xor(hmax, m));
         if (lane == 0) a.amax_partial[wave] = __float_as_uint(hmax);
     }
+    if constexpr (PASS == 2) fit_store_partial(fit_num, fit_den, a.fit_partial, wave, lane);
 }
 
 // max over the per-wave partials of the abs-max pass (non-negative floats order like their bit patterns)
@@ -522,6 +581,35 @@ __global__ __launch_bounds__(1024) void amax_finalize_kernel(const uint32_t* par
         for (int w = 1; w < 16; ++w) m = max(m, red[w]);
         *out = m;
     }
+}
+
+// s_T = amax / 2688 from the reduced abs-max (the tensor-scale fit starts from the abs-max tensor scale)
+__global__ void tensor_scale_from_amax_kernel(const uint32_t* amax_bits, float* tensor_scale)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) *tensor_scale = __fdiv_rn(__uint_as_float(*amax_bits), 2688.0f);
+}
+
+// tensor step of the fit: the partial sums are added in a fixed order (thread t takes slots t, t + 256, ...; then a
+// tree over the 256 threads), s_T = sum x v / sum v v rounded once to binary32; kept as it is when a sum is not positive
+__global__ __launch_bounds__(256) void fit_finalize_kernel(const double* partial, int n_waves, float* tensor_scale)
+{
+    __shared__ double red[2][256];
+    double num = 0.0, den = 0.0;
+    for (int i = threadIdx.x; i < n_waves; i += 256) {
+        num += partial[2 * i];
+        den += partial[2 * i + 1];
+    }
+    red[0][threadIdx.x] = num;
+    red[1][threadIdx.x] = den;
+    __syncthreads();
+    for (int w = 128; w >= 1; w >>= 1) {
+        if ((int)threadIdx.x < w) {
+            red[0][threadIdx.x] += red[0][threadIdx.x + w];
+            red[1][threadIdx.x] += red[1][threadIdx.x + w];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0 && red[1][0] > 0.0 && red[0][0] > 0.0) *tensor_scale = (float)(red[0][0] / red[1][0]);
 }
 
 // ------------------------------------------------------------------------------------------------------
@@ -614,6 +702,9 @@ template <int G, bool HW, int POL = 0>
 hipError_t dispatch_layout_pass(const RqArgs& a, bool in_f32, int layout, int pass, int grid_cap, hipStream_t st, int* blocks_out = nullptr)
 {
     if (pass == 1) return dispatch_block<G, 0, 1, HW, 0>(a, in_f32, grid_cap, st, blocks_out);  // layout and scale policy do not matter for the abs-max pass
+    if constexpr (G == 16 && HW && POL == 1) {
+        if (pass == 2) return dispatch_block<G, 0, 2, HW, 1>(a, in_f32, grid_cap, st, blocks_out);  // tensor-scale fit: sums only
+    }
     if (layout == 0) return dispatch_block<G, 0, 0, HW, POL>(a, in_f32, grid_cap, st, blocks_out);
     return dispatch_block<G, 1, 0, HW, POL>(a, in_f32, grid_cap, st, blocks_out);
 }
@@ -656,12 +747,30 @@ hipError_t launch_rotate_quantize(const void* x, int64_t rows, int64_t K, int b,
         if (e != hipSuccess) return e;
         // blocks that had no item still wrote their (zero) partial: every wave of the grid stores one
         const int n_partials = pass_blocks * kWavesPerBlock;
-        if (n_partials <= 256) {
+        if (n_partials <= 256 && policy != 3) {
             a.n_partials = n_partials;  // few-token calls: one launch less, the quantize pass reduces the partials itself
         } else {
             hipLaunchKernelGGL(amax_finalize_kernel, dim3(1), dim3(1024), 0, st, a.amax_partial, n_partials, a.amax_bits);
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
+    }
+    if (policy == 3) {
+        // Alternating optimisation of the group scales and the tensor scale (Section 4.1 "Ingredient 1"): from the abs-max
+        // tensor scale, kFitRounds times { group search with s_T fixed -> sums of x v and v v -> least-squares s_T }, then
+        // the quantize pass proper with the final s_T.  Every pass reads *tensor_scale (written on the stream before it).
+        if (fmt != 1 || static_scale) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(tensor_scale_from_amax_kernel, dim3(1), dim3(64), 0, st, a.amax_bits, a.tensor_scale);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        a.static_scale = 1;
+        a.n_partials = 0;
+        a.fit_partial = reinterpret_cast<double*>(static_cast<char*>(workspace) + 256 + 4096 * 4);
+        for (int r = 0; r < kFitRounds; ++r) {
+            int fit_blocks = 0;
+            if ((e = dispatch_layout_pass<16, true, 1>(a, in_f32, 0, 2, kAmaxPassBlocks, st, &fit_blocks)) != hipSuccess) return e;
+            hipLaunchKernelGGL(fit_finalize_kernel, dim3(1), dim3(256), 0, st, a.fit_partial, fit_blocks * kWavesPerBlock, a.tensor_scale);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+        }
+        return dispatch_layout_pass<16, true, 1>(a, in_f32, layout_gemm, 0, grid_cap, st);
     }
     if (policy == 1) {
         // the scale search is written with the hardware converts only

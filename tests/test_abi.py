@@ -40,7 +40,7 @@ def test_binding_imports_and_matches_header():
         assert callable(getattr(binding, n))
     hdr = HEADER.read_text()
     for name in ("LAYOUT_GEMM", "INPUT_F32", "STATIC_TENSOR_SCALE", "A_LAYOUT_GEMM", "W_LAYOUT_GEMM", "OUT_F32", "SCALE_MSE",
-                 "SCALE_ROUND43", "A_SCALE43", "W_SCALE43"):
+                 "SCALE_ROUND43", "A_SCALE43", "W_SCALE43", "SCALE_FIT_TENSOR"):
         m = re.search(rf"FP4MR_{name}\s*=\s*1u\s*<<\s*(\d+)", hdr)
         assert m and getattr(binding, name) == 1 << int(m.group(1)), name
 
@@ -56,6 +56,9 @@ def test_sizes(lib):
     assert b.workspace_bytes(b.OP_ROTATE_QUANTIZE, 64, 0, 4096, b.MXFP4) == 0
     assert b.workspace_bytes(b.OP_ROTATE_QUANTIZE, 64, 0, 4096, b.NVFP4) > 0
     assert b.workspace_bytes(b.OP_ROTATE_QUANTIZE, 64, 0, 4096, b.NVFP4, b.STATIC_TENSOR_SCALE) == 0
+    # the tensor-scale fit adds two fp64 sums per wave of its reduction pass
+    assert (b.workspace_bytes(b.OP_QUANTIZE_WEIGHTS, 64, 0, 4096, b.NVFP4, b.SCALE_MSE | b.SCALE_FIT_TENSOR)
+            == b.workspace_bytes(b.OP_QUANTIZE_WEIGHTS, 64, 0, 4096, b.NVFP4, b.SCALE_MSE) + 4096 * 16)
     assert b.workspace_bytes(b.OP_GEMM, 64, 64, 4096, b.MXFP4, b.A_LAYOUT_GEMM | b.W_LAYOUT_GEMM) == 0
     assert b.workspace_bytes(b.OP_GEMM, 64, 64, 4096, b.MXFP4) > 0
 
@@ -79,6 +82,11 @@ def test_argument_validation_happens_before_any_launch(lib):
     assert q(fmt=1) == 1                        # NVFP4 needs the tensor-scale pointer
     assert q(fmt=1, ts=fake, ws=fake, wsz=1 << 20, flags=b.SCALE_ROUND43) == 4   # the 4/3 rule is an MXFP4 rule
     assert q(flags=b.SCALE_ROUND43 | b.SCALE_MSE) == 4                           # one scale policy at a time
+    FIT = b.SCALE_MSE | b.SCALE_FIT_TENSOR
+    assert q(flags=FIT) == 4                                                     # the tensor-scale fit is an NVFP4 policy,
+    assert q(fmt=1, ts=fake, ws=fake, wsz=1 << 20, flags=b.SCALE_FIT_TENSOR) == 4     # on top of the group search,
+    assert q(fmt=1, ts=fake, ws=fake, wsz=1 << 20, flags=FIT | b.STATIC_TENSOR_SCALE) == 4   # with a fitted, not a given, s_T
+    assert q(fmt=1, ts=fake, ws=fake, wsz=256 + 4096 * 4, flags=FIT) == 6        # and needs its larger workspace
     assert q(fmt=1, ts=fake) == 6               # ... and a workspace
     assert q(fmt=1, ts=fake, ws=fake, wsz=8) == 6
     g = lambda **kw: L.fp4_gemm(kw.get("a", fake), fake, kw.get("ats", None), fake, fake, None, kw.get("M", 16), kw.get("N", 16),
