@@ -289,6 +289,38 @@ def test_gemm_mxfp4_persistent_variants_across_ragged_tiles(fp4, oracle, grid, o
     _gemm_case(fp4, oracle, MX, 528, 784, 3072, seed=90 + grid + variant, out_f32=out_f32, layout_gemm=True)
 
 
+@pytest.mark.parametrize("variant", [10, 11, 13, 3, 15])
+@pytest.mark.parametrize("K", [640, 1152, 2176])
+def test_gemm_mxfp4_scales_that_differ_per_row_block_and_k_block(fp4, oracle, variant, K, knobs):
+    """The tile kernels fetch scale bytes in batches (eight K-steps of two row-blocks per copy with four stages, four
+    K-steps of one row-block with three): every 16-row block and every 128-wide K-block gets its own magnitude, so a byte
+    taken from the wrong row-block, K-step or batch changes a product by a power of two.  K / 128 = 5, 9, 17: batches that
+    end inside the last scale dword, ragged M and N."""
+    import torch
+    M, N = 272, 400
+    rng = np.random.default_rng(7000 + K + variant)
+
+    def operand(rows):
+        v = rng.standard_normal((rows, K))
+        v *= 2.0 ** ((np.arange(rows)[:, None] // 16 * 5) % 11 - 5)          # per row-block
+        v *= 2.0 ** ((np.arange(K)[None, :] // 128 * 3) % 7 - 3)             # per K-step
+        return v.astype(np.float32)
+
+    ya, yw = operand(M), operand(N)
+    ac, asc, _ = oracle.quantize(ya, MX)
+    wc, wsc, _ = oracle.quantize(yw, MX)
+    assert len(np.unique(asc)) >= 12
+    Y, S = oracle.matmul(oracle.dequantize(ac, asc, MX), oracle.dequantize(wc, wsc, MX))
+    knobs(variant=variant)
+    say(f"gemm scale batches variant={variant} K={K}")
+    qa = fp4.fp4_rotate_quantize(to_dev(ya), 1, MX, flags=fp4.LAYOUT_GEMM | fp4.INPUT_F32)
+    qw = fp4.fp4_quantize_weights(to_dev(yw), 1, MX, flags=fp4.LAYOUT_GEMM | fp4.INPUT_F32)
+    out = fp4.fp4_gemm(qa[0], qa[1], None, qw[0], qw[1], None, M, N, K, MX, flags=fp4.OUT_F32 | fp4.A_LAYOUT_GEMM | fp4.W_LAYOUT_GEMM)
+    torch.cuda.synchronize()
+    err = np.abs(np_(out).astype(np.float64) - Y)
+    assert np.all(err <= 1e-3 * S), float((err / (1e-3 * S + 1e-300)).max())
+
+
 def test_gemm_mxfp4_exact_on_small_integers(fp4, oracle):
     """With scale bytes chosen freely and on-grid codes, 4*a*w are small integers: the fp32 accumulator must be
     EXACT (any summation order), and distinct scales per K-group pin the scale-to-group wiring."""
