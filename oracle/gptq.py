@@ -102,7 +102,10 @@ def mr_gptq(w_bf16_bits: np.ndarray, H: np.ndarray, b: int, fmt: int, policy: st
     """Whole weight quantizer: rotate, fix the scales, order, factor, sweep.  H is the Hessian X'^T X' of the ROTATED
     calibration inputs [K,K].  Returns (codes, scales, s_T, perm, U)."""
     y = ref.rotate(w_bf16_bits, b)
-    _, scales, s_T = ref.quantize(y, fmt, policy=policy)
+    if policy == "mse_alt":      # NVFP4: group scales and tensor scale by the alternating optimisation (Section 4.1 Ingredient 1)
+        _, scales, s_T, _ = ref.quantize_nvfp4_alternating(y, 3)
+    else:
+        _, scales, s_T = ref.quantize(y, fmt, policy=policy)
     K = y.shape[1]
     perm = act_order(H) if order else np.arange(K)
     U = inverse_factor(H, perm, damp)

@@ -242,7 +242,7 @@ fp4mr_status_t fp4_gptq_quantize_weights(const void* w, int64_t N, int64_t K, in
                                          void* stream)
 {
     if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return FP4MR_ERR_FMT;
-    if (flags & ~(uint32_t)(FP4MR_SCALE_MSE | FP4MR_SCALE_ROUND43)) return FP4MR_ERR_FMT;
+    if (flags & ~(uint32_t)(FP4MR_SCALE_MSE | FP4MR_SCALE_ROUND43 | FP4MR_SCALE_FIT_TENSOR)) return FP4MR_ERR_FMT;
     if (!hinv_u) return FP4MR_ERR_NULL;
     if (N > (1 << 24) || K <= 0 || K % 64 != 0 || K > 24576) return FP4MR_ERR_SHAPE;
     if (!aligned16(hinv_u) || (perm && !aligned16(perm))) return FP4MR_ERR_ALIGN;

@@ -88,7 +88,8 @@ def test_diagonal_factor_gives_round_to_nearest(fp4, oracle, fmt):
     assert diff.mean() <= (0.0 if fmt == MX else 1e-4)
 
 
-@pytest.mark.parametrize("fmt,policy,b", [(MX, "absmax", 32), (MX, "mse", 128), (MX, "round43", 32), (NV, "absmax", 16), (NV, "mse", 32)])
+@pytest.mark.parametrize("fmt,policy,b", [(MX, "absmax", 32), (MX, "mse", 128), (MX, "round43", 32), (NV, "absmax", 16), (NV, "mse", 32),
+                                          (NV, "mse_alt", 16), (NV, "mse_alt", 1)])
 def test_sweep_matches_the_oracle_on_synthetic_hessians(fp4, oracle, gptq, fmt, policy, b):
     import torch
     N, K, T = 100, 512, 1024
@@ -99,9 +100,12 @@ def test_sweep_matches_the_oracle_on_synthetic_hessians(fp4, oracle, gptq, fmt, 
     perm = gptq.act_order(H).astype(np.int32)
     U = gptq.inverse_factor(H, perm, damp=1e-2).astype(np.float32)
     y = oracle.rotate(wb, b)
-    c_rtn, scales, sT = oracle.quantize(y, fmt, policy=policy)
+    if policy == "mse_alt":   # the grid of Ingredient 1 in full: group scales and tensor scale by alternating optimisation
+        c_rtn, scales, sT, _ = oracle.quantize_nvfp4_alternating(y, 3)
+    else:
+        c_rtn, scales, sT = oracle.quantize(y, fmt, policy=policy)
     want, _ = gptq.sweep(y, scales, fmt, sT, U, perm)
-    flags = {"absmax": 0, "mse": fp4.SCALE_MSE, "round43": fp4.SCALE_ROUND43}[policy]
+    flags = {"absmax": 0, "mse": fp4.SCALE_MSE, "round43": fp4.SCALE_ROUND43, "mse_alt": fp4.SCALE_MSE | fp4.SCALE_FIT_TENSOR}[policy]
     say(f"gptq synthetic fmt={fmt} policy={policy} b={b}")
     c, s, Tg = fp4.fp4_gptq_quantize_weights(to_dev_bf16(wb), b, fmt, to_dev(U), to_dev(perm), flags=flags)
     torch.cuda.synchronize()
