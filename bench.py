@@ -637,6 +637,24 @@ def main():
         except Exception as exc:  # noqa: BLE001 - reported in the JSON line
             extras_errors["nvfp4"] = repr(exc)
 
+        try:
+            # ---- offline NVFP4 weight preparation under the three scale policies (Section 4.1 Ingredient 1): abs-max, the
+            # per-group squared-error search, and the search alternated with a least-squares tensor scale
+            Nw, Kw = 8192, 8192
+            ww = (torch.randn(Nw, Kw, device="cuda") * 0.015).to(torch.bfloat16)
+            cbw, sbw = fp4.packed_bytes(Nw, Kw, fp4.NVFP4, GL)
+            ocw = torch.empty(cbw, dtype=torch.uint8, device="cuda")
+            osw = torch.empty(sbw, dtype=torch.uint8, device="cuda")
+            prep = {"workload": f"W [{Nw}, {Kw}] bf16 -> NVFP4, Hadamard block 16, GEMM layout"}
+            for key, fl_ in (("absmax", 0), ("mse", fp4.SCALE_MSE), ("mse_fit_tensor", fp4.SCALE_MSE | fp4.SCALE_FIT_TENSOR)):
+                wsw = torch.empty(max(256, fp4.workspace_bytes(fp4.OP_QUANTIZE_WEIGHTS, Nw, 0, Kw, fp4.NVFP4, GL | fl_)), dtype=torch.uint8, device="cuda")
+                prep[key + "_us"] = round(time_us(lambda: fp4.fp4_quantize_weights(ww, 16, fp4.NVFP4, flags=GL | fl_, codes=ocw, scales=osw,
+                                                                                    workspace=wsw), n=6, warm=2), 1)
+            result["nvfp4_weight_prep_8192x8192"] = prep
+            del ww, ocw, osw
+        except Exception as exc:  # noqa: BLE001 - reported in the JSON line
+            extras_errors["nvfp4_weight_prep"] = repr(exc)
+
         if extras_errors:
             result["extras_errors"] = extras_errors
 
