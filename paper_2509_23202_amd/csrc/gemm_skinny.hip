@@ -7,10 +7,18 @@
 // comes from L2.  Each W fragment is multiplied against up to four 16-row X fragments (MT), so M <= 64 streams W once.
 // Partial sums of the 8 waves meet in LDS and are added in a fixed order (deterministic), then written as bf16/fp32.
 // No split-K workspace, no atomics, one launch.
+//
+// Two kernels share that scheme.  gemm_skinny_kernel launches one workgroup per row-block; its loads drain before the
+// reduction, so each workgroup pays one memory latency with nothing in flight.  gemm_stream_kernel (MXFP4, M <= 16,
+// layers with more row-blocks than the chip holds workgroups) keeps a fixed grid resident, walks the row-blocks with a
+// stride and holds two register batches per wave, so the loads of the next row-block are in flight while the partial
+// sums of the current one meet in LDS.  Both add the eight partials in wave order: their results are bit-identical.
 #include "device_util.hpp"
 #include "internal.hpp"
 #include "layout.hpp"
 #include "nv_dequant.hpp"
+
+#include <algorithm>
 
 namespace fp4mr {
 namespace {
@@ -121,6 +129,213 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_kernel(SkinnyAr
     }
 }
 
+// ------------------------------------------------------------------------------------------------------
+// Up to 16 tokens (one X row-block): the same decomposition as above -- a workgroup per 16-column block of the output,
+// its 8 waves splitting K, partial sums added through LDS in a fixed order -- but the workgroups are PERSISTENT: the grid
+// is what fits on the chip at once and a workgroup walks the row-blocks of W with a stride of the grid.  A one-shot
+// workgroup streams 32 KB (K = 4096) and spends most of its life on its own start-up, its load latency and its
+// reduction, none of which overlap; here the loads of the next batch of fragments (of this row-block or the next) are in
+// flight while the current batch is multiplied and while the row-block's partial sums are reduced and stored, so HBM
+// sees a continuous stream.  Two register buffers of U fragments each (W codes and scales, X codes and scales); the
+// barrier per row-block is a bare s_barrier (no vmcnt drain) and the partial sums are double-buffered in LDS, so one
+// barrier per row-block suffices.  Bit-identical to the one-shot kernel (same K split, same order of additions).
+// XRES: the wave's share of K is at most U fragments (one batch per row-block), and since that share is the same for every
+// row-block its X fragments are loaded once and stay in registers: a batch is then W only.
+template <int FMT, bool OUT_F32, int U, bool XRES>
+__global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyArgs g)
+{
+    __shared__ float partial[2][kSkinnyWaves][256];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int KC = g.K >> 7, KS = (g.K + 511) >> 9;
+    const int per = (KC + kSkinnyWaves - 1) / kSkinnyWaves;
+    const int k_begin = min(wave * per, KC), k_end = min(k_begin + per, KC);
+    const int nb = (k_end - k_begin + U - 1) / U;       // batches per row-block for this wave (0 for a wave without a K share)
+    const int n_rb = (g.N + 15) >> 4;
+    const int G = (int)gridDim.x;
+
+    // Buffer resources: the only per-lane addresses are 16 / 4 / 2 times the lane id, every fragment's position is a scalar
+    // offset (64-bit per-load addresses in vector registers would cost the occupancy this kernel lives on).
+    auto make_rsrc = [](const uint8_t* base, int64_t bytes) {
+        const uint32_t n = bytes > 0xffffffffll ? 0xffffffffu : (uint32_t)bytes;
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, (int)n, 0x00020000);
+    };
+    constexpr int SCB = FMT == 0 ? 256 : 128;            // scale bytes per (row-block, MXFP4: four fragments / NVFP4: fragment)
+    const int sc_per_rb = FMT == 0 ? KS : KC;
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(g.a_codes, (int64_t)KC * 1024);
+    const __amdgpu_buffer_rsrc_t rs_xs = make_rsrc(g.a_scales, (int64_t)sc_per_rb * SCB);
+    const int lane16 = lane * 16, lane_sc = FMT == 0 ? lane * 4 : lane * 2;
+    auto load_scale = [&](__amdgpu_buffer_rsrc_t rs, int kc) -> uint32_t {
+        if constexpr (FMT == 0) return __builtin_amdgcn_raw_buffer_load_b32(rs, lane_sc, (kc >> 2) * 256, 0);
+        else return (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rs, lane_sc, kc * 128, 0);
+    };
+
+    struct Batch {
+        v4i wf[U], xf[XRES ? 1 : U];
+        uint32_t sw[U], sx[XRES ? 1 : U];
+    };
+    // loads per batch and wave: a compile-time constant (the vmcnt bookkeeping below counts on it)
+    constexpr int LPB = (XRES ? 2 : 4) * U;
+    auto load_batch = [&](Batch& b, int rb, int kc0) {
+        const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(g.w_codes + (int64_t)rb * KC * 1024, (int64_t)KC * 1024);
+        const __amdgpu_buffer_rsrc_t rs_ws = make_rsrc(g.w_scales + (int64_t)rb * sc_per_rb * SCB, (int64_t)sc_per_rb * SCB);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int kc = min(kc0 + u, k_end - 1);  // the tail repeats the last fragment; its product is skipped
+            b.wf[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rs_w, lane16, kc * 1024, 2));  // streamed once
+            b.sw[u] = load_scale(rs_ws, kc);
+            if constexpr (!XRES) {
+                b.xf[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rs_x, lane16, kc * 1024, 0));
+                b.sx[u] = load_scale(rs_xs, kc);
+            }
+        }
+    };
+    v4i xres[XRES ? U : 1];
+    uint32_t sxres[XRES ? U : 1];
+    if constexpr (XRES) {
+        if (nb > 0) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int kc = min(k_begin + u, k_end - 1);
+                xres[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rs_x, lane16, kc * 1024, 0));
+                sxres[u] = load_scale(rs_xs, kc);
+            }
+        }
+    }
+    auto consume = [&](const Batch& b, int kc0, v4f& acc) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (kc0 + u < k_end) {
+                const v4i xf = XRES ? xres[u] : b.xf[XRES ? 0 : u];
+                const uint32_t sx = XRES ? sxres[u] : b.sx[XRES ? 0 : u];
+                if constexpr (FMT == 0) {
+                    const int kc = kc0 + u;
+                    const v8i a8 = {b.wf[u][0], b.wf[u][1], b.wf[u][2], b.wf[u][3], 0, 0, 0, 0};
+                    const v8i b8 = {xf[0], xf[1], xf[2], xf[3], 0, 0, 0, 0};
+                    acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, acc, 4, 4, 0, (int)(b.sw[u] >> (8 * (kc & 3))), 0,
+                                                                         (int)(sx >> (8 * (kc & 3))));
+                } else {
+                    const NvFrag16 w16 = nv_dequant_frag(b.wf[u], b.sw[u]);
+                    const NvFrag16 x16 = nv_dequant_frag(xf, sx);
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(w16.s[s], x16.s[s], acc, 0, 0, 0);
+                }
+            }
+        }
+    };
+
+    float ts = g.alpha;
+    if constexpr (FMT == 1) ts = (*g.a_ts) * (*g.w_ts);
+
+    // The two batch buffers are addressed with compile-time indices only (a run-time index would put them in scratch
+    // memory): a row-block's batches alternate between them, two per trip of the loop, and a row-block with an odd number
+    // of batches hands the next one the other buffer first (`first`, uniform).
+    Batch buf0, buf1;
+    int first = 0;
+    int rb = (int)blockIdx.x;
+    if (nb > 0 && rb < n_rb) load_batch(buf0, rb, k_begin);
+    for (int it = 0; rb < n_rb; ++it, rb += G) {
+        v4f acc = {0.f, 0.f, 0.f, 0.f};
+        // one batch: request the one after it into `nxt`, wait for `cur`, multiply
+        auto step = [&](Batch& cur, Batch& nxt, int b) {
+            const bool more_here = b + 1 < nb, more_rb = rb + G < n_rb;
+            if (more_here) load_batch(nxt, rb, k_begin + (b + 1) * U);
+            else if (more_rb) load_batch(nxt, rb + G, k_begin);
+            // memory operations retire in issue order: everything but the batch just requested may be waited for (nothing
+            // else was issued behind the current batch except, before a row-block's first batch, the previous row-block's
+            // one output store)
+            if (more_here || more_rb) {
+                if (b == 0 && it > 0) __builtin_amdgcn_s_waitcnt(((LPB + 1) & 15) | (((LPB + 1) >> 4) << 14) | 0x0f70);
+                else __builtin_amdgcn_s_waitcnt((LPB & 15) | ((LPB >> 4) << 14) | 0x0f70);
+            } else {
+                __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+            }
+            consume(cur, k_begin + b * U, acc);
+        };
+        if (first == 0) {
+            for (int b = 0; b < nb; b += 2) {
+                step(buf0, buf1, b);
+                if (b + 1 < nb) step(buf1, buf0, b + 1);
+            }
+        } else {
+            for (int b = 0; b < nb; b += 2) {
+                step(buf1, buf0, b);
+                if (b + 1 < nb) step(buf0, buf1, b + 1);
+            }
+        }
+        first ^= nb & 1;
+        // partial sums meet in LDS (two buffers, alternating: a buffer is written again two row-blocks later, behind the
+        // next row-block's barrier, when every wave has long finished reading it)
+        float* mine = &partial[it & 1][wave][0];
+        *reinterpret_cast<v4f*>(mine + lane * 4) = acc;
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the LDS write has landed
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        // every wave reduces 32 of the 256 outputs, lanes 0..31 one each, adding the eight partials in wave order (the order
+        // of additions of the one-shot kernel)
+        const int r = wave * 32 + (lane & 31);
+        float sum = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kSkinnyWaves; ++w) sum += partial[it & 1][w][r];
+        sum *= ts;
+        const int l = r >> 2, v = r & 3;
+        const int m = l & 15;
+        const int n = rb * 16 + (l >> 4) * 4 + v;
+        // exactly one store instruction per wave and row-block (lanes masked by the condition), which the wait above counts
+        if (lane < 32 && m < g.M && n < g.N) {
+            if constexpr (OUT_F32) static_cast<float*>(g.out)[(int64_t)m * g.N + n] = sum;
+            else static_cast<__bf16*>(g.out)[(int64_t)m * g.N + n] = (__bf16)sum;
+        }
+    }
+}
+
+// compute units of the current device
+int stream_cus()
+{
+    int cus = 256, dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    return cus;
+}
+
+// workgroups of the persistent kernel that are resident at once on one compute unit: asked of the runtime once per kernel
+template <int U, bool XRES>
+int stream_resident(bool out_f32)
+{
+    static int resident[2] = {0, 0};
+    int& per_cu = resident[out_f32 ? 1 : 0];
+    if (per_cu == 0) {
+        int n = 0;
+        const hipError_t e = out_f32 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, gemm_stream_kernel<0, true, U, XRES>, kSkinnyWaves * 64, 0)
+                                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, gemm_stream_kernel<0, false, U, XRES>, kSkinnyWaves * 64, 0);
+        per_cu = (e == hipSuccess && n > 0) ? n : 1;
+    }
+    return per_cu;
+}
+
+// MXFP4, up to 16 tokens.  Returns false (nothing launched) where the one-shot kernel is the better choice: the persistent
+// kernel wins by keeping loads in flight across batches and row-blocks (N = 28672, K = 4096: 10.9 us against 13.7;
+// N = 4096, K = 14336: 7.8 against 8.4), which needs either several batches per row-block or more row-blocks than
+// resident workgroups; a layer that fits the chip in one go (N <= 8192 at K = 4096) is launch-bound and 0.1-0.4 us
+// faster with the one-shot kernel's higher occupancy.  NVFP4 stays with the one-shot kernel too: its in-register
+// dequantization needs the registers that the second batch buffer takes (one workgroup per compute unit: 68 us against 54
+// on N = 57344, K = 8192).
+template <int U, bool XRES>
+bool try_stream(const SkinnyArgs& g, bool out_f32, int per, hipStream_t st, hipError_t* err)
+{
+    const int n_rb = (g.N + 15) / 16;
+    int cap = stream_cus() * stream_resident<U, XRES>(out_f32);
+    // (the grid-cap option, a testing aid: a small grid makes every workgroup walk many row-blocks)
+    if (options().gemm_grid > 0 && options().gemm_grid < cap) cap = options().gemm_grid;
+    if (per <= U && n_rb <= cap) return false;
+    const dim3 grid((unsigned)std::min(n_rb, cap)), block(kSkinnyWaves * 64);
+    if (out_f32) hipLaunchKernelGGL((gemm_stream_kernel<0, true, U, XRES>), grid, block, 0, st, g);
+    else hipLaunchKernelGGL((gemm_stream_kernel<0, false, U, XRES>), grid, block, 0, st, g);
+    *err = hipGetLastError();
+    return true;
+}
+
 template <int FMT, int MT>
 hipError_t launch_mt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
 {
@@ -135,7 +350,13 @@ hipError_t launch_fmt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
 {
     const int mt = (g.M + 15) / 16;
     switch (mt) {
-        case 1: return launch_mt<FMT, 1>(g, out_f32, st);
+        case 1:
+            if constexpr (FMT == 0) {
+                const int per = ((g.K >> 7) + kSkinnyWaves - 1) / kSkinnyWaves;  // fragments of K per wave
+                hipError_t e = hipSuccess;
+                if (per <= 4 ? try_stream<4, true>(g, out_f32, per, st, &e) : try_stream<4, false>(g, out_f32, per, st, &e)) return e;
+            }
+            return launch_mt<FMT, 1>(g, out_f32, st);
         case 2: return launch_mt<FMT, 2>(g, out_f32, st);
         case 3: return launch_mt<FMT, 3>(g, out_f32, st);
         case 4: return launch_mt<FMT, 4>(g, out_f32, st);

@@ -321,6 +321,19 @@ def test_gemm_mxfp4_scales_that_differ_per_row_block_and_k_block(fp4, oracle, va
     assert np.all(err <= 1e-3 * S), float((err / (1e-3 * S + 1e-300)).max())
 
 
+@pytest.mark.parametrize("grid", [1, 3])
+@pytest.mark.parametrize("M,N,K,out_f32", [(1, 400, 512, True), (16, 784, 2176, False), (9, 1040, 4096, False), (16, 272, 640, True),
+                                           (3, 200, 128, False)])
+def test_gemm_mxfp4_persistent_weight_streaming_kernel(fp4, oracle, grid, M, N, K, out_f32, knobs):
+    """Up to 16 tokens on MXFP4 go to the persistent weight-streaming kernel when there are more 16-column blocks than
+    resident workgroups (or several batches of K per wave); a grid cap of 1 or 3 workgroups makes every workgroup walk
+    many row-blocks with the next batch's loads in flight across the reduction: K / 128 = 1, 4, 5, 17, 32 covers waves
+    without a K share, one batch and several batches per row-block (X resident in registers / travelling with W), odd
+    batch counts (the two register buffers swap roles between row-blocks), ragged N."""
+    knobs(grid=grid)
+    _gemm_case(fp4, oracle, MX, M, N, K, seed=300 + grid + K, out_f32=out_f32, layout_gemm=True)
+
+
 def test_gemm_mxfp4_exact_on_small_integers(fp4, oracle):
     """With scale bytes chosen freely and on-grid codes, 4*a*w are small integers: the fp32 accumulator must be
     EXACT (any summation order), and distinct scales per K-group pin the scale-to-group wiring."""
