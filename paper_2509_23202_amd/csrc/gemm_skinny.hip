@@ -8,11 +8,12 @@
 // Partial sums of the 8 waves meet in LDS and are added in a fixed order (deterministic), then written as bf16/fp32.
 // No split-K workspace, no atomics, one launch.
 //
-// Two kernels share that scheme.  gemm_skinny_kernel launches one workgroup per row-block; its loads drain before the
+// Three kernels share that scheme.  gemm_skinny_kernel launches one workgroup per row-block; its loads drain before the
 // reduction, so each workgroup pays one memory latency with nothing in flight.  gemm_stream_kernel (MXFP4, M <= 16,
 // layers with more row-blocks than the chip holds workgroups) keeps a fixed grid resident, walks the row-blocks with a
 // stride and holds two register batches per wave, so the loads of the next row-block are in flight while the partial
-// sums of the current one meet in LDS.  Both add the eight partials in wave order: their results are bit-identical.
+// sums of the current one meet in LDS.  gemm_skinny_nv_kernel (NVFP4, M <= 16) gives a workgroup two row-blocks so that
+// each dequantized X fragment serves two W fragments.  All add the eight partials in wave order: bit-identical results.
 #include "device_util.hpp"
 #include "internal.hpp"
 #include "layout.hpp"
@@ -122,6 +123,92 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_kernel(SkinnyAr
         s *= ts;
         const int m = t * 16 + (l & 15);
         const int n = rb * 16 + (l >> 4) * 4 + v;
+        if (m < g.M && n < g.N) {
+            if constexpr (OUT_F32) static_cast<float*>(g.out)[(int64_t)m * g.N + n] = s;
+            else static_cast<__bf16*>(g.out)[(int64_t)m * g.N + n] = (__bf16)s;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------
+// NVFP4, up to 16 tokens.  The in-register dequantization (16 conversions, 16 packed multiplies and two scale decodes per
+// fragment and operand) is what bounds the kernel above in this format: about 100 vector instructions per 1 KB of W, half
+// of them spent on the X fragment, which is the same for every row-block.  Here a workgroup owns NT adjacent row-blocks
+// and a wave multiplies each dequantized X fragment against the NT W fragments of its K position, so the X share of the
+// arithmetic drops to 1/NT.  Same K split over the waves, same order of additions per output: bit-identical to the
+// kernel above.  Row-blocks past the end of W (odd counts) re-read the last one and are not stored.
+template <int NT, bool OUT_F32>
+__global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nv_kernel(SkinnyArgs g)
+{
+    constexpr int U = 4;  // K positions in flight per wave (NT W fragments each)
+    __shared__ float partial[kSkinnyWaves][NT][256];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int n_rb = (g.N + 15) >> 4;
+    const int rb0 = blockIdx.x * NT;
+    const int KC = g.K >> 7;
+    const int per = (KC + kSkinnyWaves - 1) / kSkinnyWaves;
+    const int k_begin = min(wave * per, KC), k_end = min(k_begin + per, KC);
+
+    const v4i* xfrag = reinterpret_cast<const v4i*>(g.a_codes) + lane;
+    const uint16_t* xsc = reinterpret_cast<const uint16_t*>(g.a_scales) + lane;
+    const v4i* wfrag[NT];
+    const uint16_t* wsc[NT];
+#pragma unroll
+    for (int r = 0; r < NT; ++r) {
+        const int rb = min(rb0 + r, n_rb - 1);
+        wfrag[r] = reinterpret_cast<const v4i*>(g.w_codes + (int64_t)rb * KC * 1024) + lane;
+        wsc[r] = reinterpret_cast<const uint16_t*>(g.w_scales) + (int64_t)rb * KC * 64 + lane;
+    }
+
+    v4f acc[NT];
+#pragma unroll
+    for (int r = 0; r < NT; ++r) acc[r] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    for (int kc0 = k_begin; kc0 < k_end; kc0 += U) {
+        v4i wf[U][NT], xf[U];
+        uint32_t swv[U][NT], sxv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int kc = min(kc0 + u, k_end - 1);  // the tail repeats the last fragment; its products are skipped below
+#pragma unroll
+            for (int r = 0; r < NT; ++r) {
+                wf[u][r] = __builtin_nontemporal_load(wfrag[r] + (int64_t)kc * 64);
+                swv[u][r] = wsc[r][(int64_t)kc * 64];
+            }
+            xf[u] = xfrag[(int64_t)kc * 64];
+            sxv[u] = xsc[(int64_t)kc * 64];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (kc0 + u < k_end) {
+                const NvFrag16 x16 = nv_dequant_frag(xf[u], sxv[u]);
+#pragma unroll
+                for (int r = 0; r < NT; ++r) {
+                    const NvFrag16 w16 = nv_dequant_frag(wf[u][r], swv[u][r]);
+#pragma unroll
+                    for (int s = 0; s < 4; ++s)
+                        acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w16.s[s], x16.s[s], acc[r], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+#pragma unroll
+    for (int r = 0; r < NT; ++r)
+        *reinterpret_cast<v4f*>(&partial[wave][r][lane * 4]) = acc[r];
+    __syncthreads();
+
+    const float ts = (*g.a_ts) * (*g.w_ts);
+    for (int e = threadIdx.x; e < NT * 256; e += kSkinnyWaves * 64) {
+        const int r = e >> 8, q = e & 255, l = q >> 2, v = q & 3;
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kSkinnyWaves; ++w) s += partial[w][r][q];
+        s *= ts;
+        const int m = l & 15;
+        const int n = (rb0 + r) * 16 + (l >> 4) * 4 + v;
         if (m < g.M && n < g.N) {
             if constexpr (OUT_F32) static_cast<float*>(g.out)[(int64_t)m * g.N + n] = s;
             else static_cast<__bf16*>(g.out)[(int64_t)m * g.N + n] = (__bf16)s;
@@ -300,15 +387,15 @@ int stream_cus()
 }
 
 // workgroups of the persistent kernel that are resident at once on one compute unit: asked of the runtime once per kernel
-template <int U, bool XRES>
+template <int FMT, int U, bool XRES>
 int stream_resident(bool out_f32)
 {
     static int resident[2] = {0, 0};
     int& per_cu = resident[out_f32 ? 1 : 0];
     if (per_cu == 0) {
         int n = 0;
-        const hipError_t e = out_f32 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, gemm_stream_kernel<0, true, U, XRES>, kSkinnyWaves * 64, 0)
-                                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, gemm_stream_kernel<0, false, U, XRES>, kSkinnyWaves * 64, 0);
+        const hipError_t e = out_f32 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, gemm_stream_kernel<FMT, true, U, XRES>, kSkinnyWaves * 64, 0)
+                                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, gemm_stream_kernel<FMT, false, U, XRES>, kSkinnyWaves * 64, 0);
         per_cu = (e == hipSuccess && n > 0) ? n : 1;
     }
     return per_cu;
@@ -321,17 +408,17 @@ int stream_resident(bool out_f32)
 // faster with the one-shot kernel's higher occupancy.  NVFP4 stays with the one-shot kernel too: its in-register
 // dequantization needs the registers that the second batch buffer takes (one workgroup per compute unit: 68 us against 54
 // on N = 57344, K = 8192).
-template <int U, bool XRES>
+template <int FMT, int U, bool XRES>
 bool try_stream(const SkinnyArgs& g, bool out_f32, int per, hipStream_t st, hipError_t* err)
 {
     const int n_rb = (g.N + 15) / 16;
-    int cap = stream_cus() * stream_resident<U, XRES>(out_f32);
+    int cap = stream_cus() * stream_resident<FMT, U, XRES>(out_f32);
     // (the grid-cap option, a testing aid: a small grid makes every workgroup walk many row-blocks)
     if (options().gemm_grid > 0 && options().gemm_grid < cap) cap = options().gemm_grid;
     if (per <= U && n_rb <= cap) return false;
     const dim3 grid((unsigned)std::min(n_rb, cap)), block(kSkinnyWaves * 64);
-    if (out_f32) hipLaunchKernelGGL((gemm_stream_kernel<0, true, U, XRES>), grid, block, 0, st, g);
-    else hipLaunchKernelGGL((gemm_stream_kernel<0, false, U, XRES>), grid, block, 0, st, g);
+    if (out_f32) hipLaunchKernelGGL((gemm_stream_kernel<FMT, true, U, XRES>), grid, block, 0, st, g);
+    else hipLaunchKernelGGL((gemm_stream_kernel<FMT, false, U, XRES>), grid, block, 0, st, g);
     *err = hipGetLastError();
     return true;
 }
@@ -354,7 +441,17 @@ hipError_t launch_fmt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
             if constexpr (FMT == 0) {
                 const int per = ((g.K >> 7) + kSkinnyWaves - 1) / kSkinnyWaves;  // fragments of K per wave
                 hipError_t e = hipSuccess;
-                if (per <= 4 ? try_stream<4, true>(g, out_f32, per, st, &e) : try_stream<4, false>(g, out_f32, per, st, &e)) return e;
+                if (per <= 4 ? try_stream<0, 4, true>(g, out_f32, per, st, &e) : try_stream<0, 4, false>(g, out_f32, per, st, &e)) return e;
+            } else {
+                // two row-blocks per workgroup halve the X share of the dequantization; below about 0.6 workgroups per
+                // compute unit the halved grid costs more than that saves (K = 14336, N = 4096: 14.1 us against 11.2)
+                const int n_rb = (g.N + 15) / 16, wgs = (n_rb + 1) / 2;
+                if (5 * wgs >= 3 * stream_cus()) {
+                    const dim3 grid((unsigned)wgs), block(kSkinnyWaves * 64);
+                    if (out_f32) hipLaunchKernelGGL((gemm_skinny_nv_kernel<2, true>), grid, block, 0, st, g);
+                    else hipLaunchKernelGGL((gemm_skinny_nv_kernel<2, false>), grid, block, 0, st, g);
+                    return hipGetLastError();
+                }
             }
             return launch_mt<FMT, 1>(g, out_f32, st);
         case 2: return launch_mt<FMT, 2>(g, out_f32, st);

@@ -334,6 +334,15 @@ def test_gemm_mxfp4_persistent_weight_streaming_kernel(fp4, oracle, grid, M, N, 
     _gemm_case(fp4, oracle, MX, M, N, K, seed=300 + grid + K, out_f32=out_f32, layout_gemm=True)
 
 
+@pytest.mark.parametrize("M,N,K,out_f32", [(1, 5000, 512, True), (16, 4944, 1152, False), (9, 5136, 128, False), (16, 8200, 640, True)])
+def test_gemm_nvfp4_few_tokens_two_row_blocks_per_workgroup(fp4, oracle, M, N, K, out_f32):
+    """Up to 16 tokens on NVFP4 with at least 0.6 workgroups per compute unit go to the kernel whose workgroups own two
+    16-column blocks of the output (one dequantized X fragment per two W fragments): odd block counts (the last workgroup
+    re-reads the last block and stores it once), ragged N, K / 128 = 1, 4, 5, 9 (waves without a K share, ragged tails of
+    the four-deep load batches)."""
+    _gemm_case(fp4, oracle, NV, M, N, K, seed=4100 + N + K, out_f32=out_f32, layout_gemm=True)
+
+
 def test_gemm_mxfp4_exact_on_small_integers(fp4, oracle):
     """With scale bytes chosen freely and on-grid codes, 4*a*w are small integers: the fp32 accumulator must be
     EXACT (any summation order), and distinct scales per K-group pin the scale-to-group wiring."""
