@@ -24,6 +24,9 @@
  *   orc_quantize_mxfp4_round43  MXFP4 with the scale rounded in the log domain and re-scaled by 4/3,
  *                       s = (4/3) * 2^clamp(round(log2 s)) (Appendix "MXFP scale fitting", first equation;
  *                       Appendix "Scale quantization analysis").
+ *   orc_quantize_mxfp4_fit  MXFP4 with the scale byte re-mapped onto the tensor's own range of scales,
+ *                       s = 2^(alpha q + beta) (Appendix "MXFP scale fitting": the modified format MXFP4-dagger);
+ *                       orc_quantize_given_scales / orc_dequantize_table: elements against a given table of scale values.
  *   orc_dequantize      the decoding side of the same definitions.
  *   orc_matmul          Y = Ahat * What^T as a plain triple loop in fp64, plus S = |Ahat| * |What|^T.
  *
@@ -545,6 +548,117 @@ int orc_quantize_mxfp4_round43(const float *y, int64_t M, int64_t K, uint8_t *co
             }
         }
     }
+    return 0;
+}
+
+/* ---------------------------------------------------------------- scale byte fitted to the tensor's range of scales
+ * Appendix "MXFP scale fitting": the 256 codes of the scale byte are spread over the range of scales that the tensor
+ * actually has instead of over 2^-127 .. 2^127.  With s the ideal abs-max scale of a group (amax / 6, as in the first
+ * equation of that appendix) and s_min, s_max its smallest and largest value over the tensor,
+ *     q = clamp(round(255 (log2 s - log2 s_min) / (log2 s_max - log2 s_min)), 0, 255)
+ *     s_hat = 2^(alpha q + beta),   alpha = (log2 s_max - log2 s_min) / 255,   beta = log2 s_min.
+ * Readings taken here (the appendix prints the second equation without the division by 255 in the exponent; it is
+ * needed for q = 255 to decode to s_max, and the third equation, s = 2^(alpha q + beta) with alpha in (0, 1), says the
+ * same): groups that are all zero take no part in s_min, get q = 0 and zero codes; a tensor with a single distinct
+ * scale has alpha = 0; an all-zero tensor has alpha = beta = 0.  Elements are rounded to the nearest E2M1 value of
+ * v / s_hat (saturating at 6: s_hat can be below s by up to half a step of the grid, 2^(alpha/2)).
+ * If ab_in is non-NULL its (alpha, beta) are used instead of the fitted ones (a layer whose weights and activations must
+ * share alpha, last paragraph of the appendix) and q is clamped to the byte.
+ * y: fp32 [M,K];  codes [M,K/2];  q [M,K/32];  ab_out[2] = (alpha, beta);  table[256] = s_hat(0..255).  All fp64. */
+int orc_quantize_mxfp4_fit(const float *y, int64_t M, int64_t K, const double *ab_in, uint8_t *codes, uint8_t *q,
+                           double *ab_out, double *table)
+{
+    const int G = 32;
+    if (K % G != 0) return -1;
+    const int64_t NG = M * (K / G);
+    double *amax = (double *)malloc(sizeof(double) * (size_t)(NG > 0 ? NG : 1));
+    if (!amax) return -2;
+    double lo = INFINITY, hi = 0.0;
+    for (int64_t g = 0; g < NG; ++g) {
+        double a = 0.0;
+        for (int i = 0; i < G; ++i) {
+            double t = fabs((double)y[g * G + i]);
+            if (t > a) a = t;
+        }
+        amax[g] = a;
+        if (a > 0.0 && a < lo) lo = a;
+        if (a > hi) hi = a;
+    }
+    double alpha = 0.0, beta = 0.0;
+    if (ab_in) {
+        alpha = ab_in[0];
+        beta = ab_in[1];
+    } else if (hi > 0.0) {
+        beta = log2(lo / 6.0);
+        alpha = (log2(hi / 6.0) - beta) / 255.0;
+    }
+    ab_out[0] = alpha;
+    ab_out[1] = beta;
+    for (int c = 0; c < 256; ++c) table[c] = exp2(alpha * c + beta);
+    for (int64_t g = 0; g < NG; ++g) {
+        int c = 0;
+        if (amax[g] > 0.0 && alpha > 0.0) {
+            const double t = (log2(amax[g] / 6.0) - beta) / alpha;
+            c = (int)floor(t + 0.5);
+            if (c < 0) c = 0;
+            if (c > 255) c = 255;
+        }
+        q[g] = (uint8_t)c;
+        for (int i = 0; i < G; i += 2) {
+            uint8_t l = 0, h = 0;
+            if (amax[g] > 0.0) {
+                l = orc_e2m1_encode((double)y[g * G + i] / table[c]);
+                h = orc_e2m1_encode((double)y[g * G + i + 1] / table[c]);
+            }
+            codes[(g * G + i) / 2] = (uint8_t)(l | (h << 4));
+        }
+    }
+    free(amax);
+    return 0;
+}
+
+/* Elements of [M,K] against GIVEN scales: group g uses the binary32 value table[q[g]], and the arithmetic is the binary32
+ * chain of orc_quantize_nvfp4 (r = 1 / d rounded, y * r rounded, then the nearest E2M1 value); a group whose values are
+ * all zero gets zero codes.  G = 32. */
+int orc_quantize_given_scales(const float *y, int64_t M, int64_t K, const uint8_t *q, const float *table, uint8_t *codes)
+{
+    const int G = 32;
+    if (K % G != 0) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < M * (K / G); ++g) {
+        const float *v = y + g * G;
+        float amax = 0.0f;
+        for (int i = 0; i < G; ++i) {
+            float a = fabsf(v[i]);
+            if (a > amax) amax = a;
+        }
+        volatile float d = table[q[g]];
+        if (amax == 0.0f || d == 0.0f) {
+            for (int i = 0; i < G; i += 2) codes[(g * G + i) / 2] = 0;
+            continue;
+        }
+        volatile float r = 1.0f / d;
+        for (int i = 0; i < G; i += 2) {
+            volatile float a0 = v[i] * r;
+            volatile float a1 = v[i + 1] * r;
+            codes[(g * G + i) / 2] = (uint8_t)(orc_e2m1_encode((double)a0) | (orc_e2m1_encode((double)a1) << 4));
+        }
+    }
+    return 0;
+}
+
+/* out[m,k] = E2M1(code) * table[q of the group]  (G = 32; table in fp64). */
+int orc_dequantize_table(const uint8_t *codes, const uint8_t *q, const double *table, int64_t M, int64_t K, double *out)
+{
+    const int G = 32;
+    if (K % G != 0) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            uint8_t byte = codes[(m * K + k) / 2];
+            uint8_t code = (k & 1) ? (uint8_t)(byte >> 4) : (uint8_t)(byte & 15);
+            out[m * K + k] = orc_e2m1_decode(code) * table[q[m * (K / G) + k / G]];
+        }
     return 0;
 }
 

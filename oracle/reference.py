@@ -78,6 +78,12 @@ def _load():
         L.orc_quantize_mxfp4_round43.restype = i32
         L.orc_e8m0_round43_from_amax.argtypes = [ctypes.c_double]
         L.orc_e8m0_round43_from_amax.restype = ctypes.c_uint8
+        L.orc_quantize_mxfp4_fit.argtypes = [p, i64, i64, p, p, p, p, p]
+        L.orc_quantize_mxfp4_fit.restype = i32
+        L.orc_quantize_given_scales.argtypes = [p, i64, i64, p, p, p]
+        L.orc_quantize_given_scales.restype = i32
+        L.orc_dequantize_table.argtypes = [p, p, p, i64, i64, p]
+        L.orc_dequantize_table.restype = i32
         L.orc_dequantize.argtypes = [p, p, dbl, i32, i64, i64, p]
         L.orc_dequantize.restype = i32
         L.orc_matmul.argtypes = [p, p, i64, i64, i64, p, p]
@@ -215,6 +221,52 @@ def quantize_nvfp4_alternating(y_f32: np.ndarray, rounds: int = 3):
     if _load().orc_quantize_nvfp4_mse_alt(_ptr(y), M, K, int(rounds), _ptr(codes), _ptr(scales), _ptr(s_out), _ptr(trace)) != 0:
         raise ValueError("quantize failed")
     return codes, scales, np.float32(s_out[0]), trace
+
+
+def quantize_mxfp4_fit(y_f32: np.ndarray, alpha_beta=None):
+    """MXFP4 with the scale byte fitted to the tensor's range of scales (Appendix "MXFP scale fitting", s = 2^(alpha q + beta)).
+    fp32 [M,K] -> (codes u8 [M,K/2], q u8 [M,K/32], (alpha, beta) fp64, table fp64[256] of the 256 scale values).
+    alpha_beta: use these instead of fitting them (weights and activations of a layer sharing alpha)."""
+    y = np.ascontiguousarray(y_f32, dtype=np.float32)
+    M, K = y.shape
+    if K % 32:
+        raise ValueError(f"quantize: K={K} not a multiple of 32")
+    codes = np.empty((M, K // 2), dtype=np.uint8)
+    q = np.empty((M, K // 32), dtype=np.uint8)
+    ab = np.zeros(2, dtype=np.float64)
+    table = np.zeros(256, dtype=np.float64)
+    ab_in = None
+    if alpha_beta is not None:
+        ab_arr = np.array(alpha_beta, dtype=np.float64)
+        ab_in = _ptr(ab_arr)
+    if _load().orc_quantize_mxfp4_fit(_ptr(y), M, K, ab_in, _ptr(codes), _ptr(q), _ptr(ab), _ptr(table)) != 0:
+        raise ValueError("quantize failed")
+    return codes, q, (float(ab[0]), float(ab[1])), table
+
+
+def quantize_given_scales(y_f32: np.ndarray, q: np.ndarray, table_f32: np.ndarray) -> np.ndarray:
+    """Elements of fp32 [M,K] against given scales (group g: binary32 table_f32[q[g]], binary32 arithmetic) -> codes."""
+    y = np.ascontiguousarray(y_f32, dtype=np.float32)
+    M, K = y.shape
+    qq = np.ascontiguousarray(q, dtype=np.uint8)
+    tab = np.ascontiguousarray(table_f32, dtype=np.float32)
+    assert qq.size == M * (K // 32) and tab.size == 256
+    codes = np.empty((M, K // 2), dtype=np.uint8)
+    if _load().orc_quantize_given_scales(_ptr(y), M, K, _ptr(qq), _ptr(tab), _ptr(codes)) != 0:
+        raise ValueError("quantize failed")
+    return codes
+
+
+def dequantize_table(codes: np.ndarray, q: np.ndarray, table: np.ndarray) -> np.ndarray:
+    """codes [M,K/2], q [M,K/32], table[256] -> fp64 [M,K] = E2M1(code) * table[q]."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    qq = np.ascontiguousarray(q, dtype=np.uint8)
+    tab = np.ascontiguousarray(table, dtype=np.float64)
+    M, K2 = codes.shape
+    out = np.empty((M, 2 * K2), dtype=np.float64)
+    if _load().orc_dequantize_table(_ptr(codes), _ptr(qq), _ptr(tab), M, 2 * K2, _ptr(out)) != 0:
+        raise ValueError("dequantize failed")
+    return out
 
 
 def dequantize(codes: np.ndarray, scales: np.ndarray, fmt: int, s_T=None) -> np.ndarray:

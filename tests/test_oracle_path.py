@@ -787,3 +787,133 @@ def test_round43_scale_stays_within_the_rounding_band(oracle):
     assert set(np.unique(top)) <= {3.0, 4.0, 6.0}
     with pytest.raises(ValueError):
         oracle.quantize(y, NV, policy="round43")
+
+
+# ---------------------------------------------------------------- scale byte fitted to the tensor's range (Appendix "MXFP scale fitting")
+def _laplace_with_scale_spread(seed, M=48, K=1024, spread=1.2):
+    rng = np.random.default_rng(seed)
+    return (rng.laplace(size=(M, K)) * np.exp(rng.normal(size=(M, 1)) * spread)).astype(np.float32)
+
+
+def test_fit_range_two_level_tensor_is_reproduced_exactly(oracle):
+    """Groups whose abs-max is 6 * 2^-3 or 6 * 2^5 and whose values sit on the E2M1 grid times that scale: s_min = 2^-3,
+    s_max = 2^5, so alpha = 8 / 255, beta = -3, the bytes are 0 and 255, and the tensor decodes to itself."""
+    rng = np.random.default_rng(11)
+    M, K = 8, 256
+    sel = rng.integers(0, 2, size=(M, K // 32))
+    sc = np.where(sel == 1, 2.0 ** 5, 2.0 ** -3)
+    vals = GRID[rng.integers(0, 8, size=(M, K))] * rng.choice([-1.0, 1.0], size=(M, K))
+    vals = vals.reshape(M, K // 32, 32)
+    vals[:, :, 0] = 6.0                                   # every group reaches the top of the grid
+    y = (vals * sc[:, :, None]).reshape(M, K).astype(np.float32)
+    codes, q, (alpha, beta), table = oracle.quantize_mxfp4_fit(y)
+    assert abs(alpha - 8.0 / 255.0) < 1e-15 and abs(beta + 3.0) < 1e-15
+    assert np.array_equal(q, np.where(sel == 1, 255, 0))
+    assert table[0] == 2.0 ** -3 and abs(table[255] / 2.0 ** 5 - 1.0) < 1e-14
+    back = oracle.dequantize_table(codes, q, table)
+    assert np.allclose(back, y.astype(np.float64), rtol=1e-13, atol=0.0)
+
+
+def test_fit_range_byte_is_the_nearest_of_the_256_scales_in_the_log_domain(oracle):
+    """Brute force over all 256 bytes per group, recomputed here with NumPy: the chosen byte minimises |log2 s_hat(q) - log2 s|,
+    the smallest and the largest scale of the tensor get bytes 0 and 255, and no scale is further than half a step away."""
+    y = _laplace_with_scale_spread(3)
+    codes, q, (alpha, beta), table = oracle.quantize_mxfp4_fit(y)
+    amax = np.abs(y.astype(np.float64)).reshape(y.shape[0], -1, 32).max(axis=2)
+    ls = np.log2(amax / 6.0)
+    assert abs(beta - ls.min()) < 1e-12 and abs(alpha - (ls.max() - ls.min()) / 255.0) < 1e-14
+    assert np.allclose(np.log2(table), alpha * np.arange(256) + beta, rtol=0, atol=1e-12)
+    dist = np.abs(np.log2(table)[None, None, :] - ls[:, :, None])          # [M, groups, 256]
+    best = dist.argmin(axis=2)
+    chosen = np.take_along_axis(dist, q[:, :, None].astype(np.int64), axis=2)[:, :, 0]
+    assert np.all(chosen <= dist.min(axis=2) + 1e-12)
+    assert (best != q).mean() < 1e-3                                        # (exact ties aside)
+    assert q[ls == ls.min()].tolist() == [0] and q[ls == ls.max()].tolist() == [255]
+    assert chosen.max() <= alpha / 2 + 1e-12
+
+
+def test_fit_range_codes_are_the_nearest_grid_points_of_v_over_s_hat(oracle):
+    y = _laplace_with_scale_spread(5, M=16, K=512)
+    codes, q, _, table = oracle.quantize_mxfp4_fit(y)
+    t = y.astype(np.float64).reshape(16, -1, 32) / table[q][:, :, None]
+    signed = np.concatenate([-GRID[::-1], GRID])
+    near = signed[np.abs(t[..., None] - signed).argmin(axis=-1)]
+    got = decode_codes(unpack(codes)).reshape(16, -1, 32)
+    d_got, d_near = np.abs(got - t), np.abs(near - t)
+    assert np.all(d_got <= d_near + 1e-12)                                  # (ties: any nearest point)
+    assert np.abs(t).max() <= 6.0 * 2.0 ** (np.log2(table[1] / table[0]) / 2) + 1e-9   # saturation is at most half a step
+
+
+def test_fit_range_is_invariant_under_powers_of_two(oracle):
+    y = _laplace_with_scale_spread(7, M=8, K=512)
+    c0, q0, (a0, b0), _ = oracle.quantize_mxfp4_fit(y)
+    c1, q1, (a1, b1), _ = oracle.quantize_mxfp4_fit(y * np.float32(2.0 ** -9))
+    assert np.array_equal(c0, c1) and np.array_equal(q0, q1)
+    assert abs(a0 - a1) < 1e-14 and abs((b0 - 9.0) - b1) < 1e-12
+
+
+def test_fit_range_beats_the_power_of_two_scale_in_squared_error(oracle):
+    """The appendix's claim, in direction: a scale grid fitted to the data range leaves less error than the E8M0 grid
+    (floor rule or the rounded exponent with 4/3), and comes close to NVFP4's."""
+    y = _laplace_with_scale_spread(9, M=64, K=2048)
+    y64 = y.astype(np.float64)
+    rel = lambda d: float(((d - y64) ** 2).sum() / (y64 ** 2).sum())
+    c, q, _, t = oracle.quantize_mxfp4_fit(y)
+    e_fit = rel(oracle.dequantize_table(c, q, t))
+    c, s, _ = oracle.quantize(y, MX)
+    e_mx = rel(oracle.dequantize(c, s, MX))
+    c, s, f = oracle.quantize(y, MX, policy="round43")
+    e_43 = rel(oracle.dequantize(c, s, MX, f))
+    c, s, sT = oracle.quantize(y, NV)
+    e_nv = rel(oracle.dequantize(c, s, NV, sT))
+    assert e_fit < 0.8 * e_mx and e_fit < 0.8 * e_43 and e_fit < 1.5 * e_nv, (e_fit, e_mx, e_43, e_nv)
+
+
+def test_fit_range_degenerate_tensors(oracle):
+    z = np.zeros((2, 64), dtype=np.float32)
+    c, q, ab, t = oracle.quantize_mxfp4_fit(z)
+    assert ab == (0.0, 0.0) and not c.any() and not q.any() and np.all(t == 1.0)
+    one = z.copy()
+    one[1, 40] = -3.0                                    # a single non-zero group: one distinct scale, alpha = 0
+    c, q, (alpha, beta), t = oracle.quantize_mxfp4_fit(one)
+    assert alpha == 0.0 and abs(beta - np.log2(0.5)) < 1e-15 and not q.any()
+    back = oracle.dequantize_table(c, q, t)
+    assert back[1, 40] == -3.0 and np.count_nonzero(back) == 1
+    assert not c[0].any()                                # the all-zero groups keep zero codes
+
+
+def test_fit_range_with_given_alpha_and_beta_clamps_the_byte(oracle):
+    """A shared (alpha, beta) (weights and activations of one layer): scales below 2^beta clamp to byte 0, scales above
+    2^(255 alpha + beta) to byte 255, and the elements of an overshooting group saturate at 6."""
+    y = np.zeros((1, 96), dtype=np.float32)
+    y[0, 0], y[0, 32], y[0, 64] = 6.0 * 2.0 ** -6, 6.0 * 2.0 ** 0.5, 6.0 * 2.0 ** 7
+    c, q, ab, t = oracle.quantize_mxfp4_fit(y, alpha_beta=(1.0 / 64.0, -2.0))
+    assert ab == (1.0 / 64.0, -2.0)
+    assert q[0].tolist() == [0, 160, 255]                # (0.5 + 2) * 64 = 160
+    back = oracle.dequantize_table(c, q, t)
+    assert back[0, 0] == GRID[1] * 2.0 ** -2             # 6 * 2^-6 / 2^-2 = 0.375: nearest grid point 0.5
+    assert abs(back[0, 32] / (6.0 * 2.0 ** 0.5) - 1.0) < 1e-12   # 2^(160 / 64 - 2) = 2^0.5: the group's own ideal scale
+    assert abs(back[0, 64] - 6.0 * t[255]) < 1e-9        # saturated
+
+
+def test_quantize_given_scales_is_the_binary32_chain(oracle):
+    """orc_quantize_given_scales re-computed with NumPy float32 arithmetic (one rounding per operation) and a nearest
+    search on the grid; with an exact table (powers of two) it equals the E8M0 quantizer given the same bytes."""
+    y = _laplace_with_scale_spread(13, M=8, K=256)
+    rng = np.random.default_rng(13)
+    table = (2.0 ** rng.uniform(-6, 6, size=256)).astype(np.float32)
+    amax = np.abs(y).reshape(8, -1, 32).max(axis=2)
+    q = np.abs(np.log2(table.astype(np.float64))[None, None, :] - np.log2(amax / 6.0)[:, :, None]).argmin(axis=2).astype(np.uint8)
+    codes = oracle.quantize_given_scales(y, q, table)
+    r = (np.float32(1.0) / table[q]).astype(np.float32)
+    t = (y.reshape(8, -1, 32) * r[:, :, None]).astype(np.float32).astype(np.float64)
+    signed = np.concatenate([-GRID[::-1], GRID])
+    near = np.abs(t[..., None] - signed).min(axis=-1)
+    got = decode_codes(unpack(codes)).reshape(8, -1, 32)
+    assert np.all(np.abs(got - t) <= near + 1e-12)
+    # power-of-two table = E8M0: same codes as the MXFP4 quantizer produces for its own bytes
+    c_mx, s_mx, _ = oracle.quantize(y, MX)
+    pow2 = (2.0 ** (np.arange(256) - 127.0)).astype(np.float32)
+    pow2[0] = np.float32(2.0 ** -126)                    # (byte 0 is 2^-127, a subnormal: not used by this input)
+    assert s_mx.min() > 0
+    assert np.array_equal(oracle.quantize_given_scales(y, s_mx, pow2), c_mx)
