@@ -457,6 +457,8 @@ def main():
                 dense[f"hadamard{bd}"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, bd, fp4.MXFP4, flags=GL, codes=oc, scales=osc))
             dense["hadamard32_mse_scales"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, 32, fp4.MXFP4, flags=GL | fp4.SCALE_MSE, codes=oc, scales=osc))
             dense["hadamard32_round43_scales"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, 32, fp4.MXFP4, flags=GL | fp4.SCALE_ROUND43, codes=oc, scales=osc))
+            # scale byte fitted to the tensor's range of scales (appendix on MXFP scale fitting): a range pre-pass, then the quantize pass
+            dense["hadamard32_fit_range_scales"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, 32, fp4.MXFP4, flags=GL | fp4.SCALE_FIT_RANGE, codes=oc, scales=osc))
             result["rotate_quantize_variants"] = dense
             del xs, oc, osc
         except Exception as exc:  # noqa: BLE001 - reported in the JSON line

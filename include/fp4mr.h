@@ -71,7 +71,8 @@ enum {
     FP4MR_SCALE_ROUND43 = 1u << 7,        /* MXFP4 quantize ops: rounded exponent, scale (4/3) 2^k (below)    */
     FP4MR_A_SCALE43 = 1u << 8,            /* MXFP4 products: the A operand was quantized with SCALE_ROUND43   */
     FP4MR_W_SCALE43 = 1u << 9,            /* MXFP4 products: the W operand was quantized with SCALE_ROUND43   */
-    FP4MR_SCALE_FIT_TENSOR = 1u << 10     /* NVFP4 quantize ops, with SCALE_MSE: also fit the tensor scale    */
+    FP4MR_SCALE_FIT_TENSOR = 1u << 10,    /* NVFP4 quantize ops, with SCALE_MSE: also fit the tensor scale    */
+    FP4MR_SCALE_FIT_RANGE = 1u << 11      /* MXFP4 quantize ops: scale byte fitted to the tensor's range (below) */
 };
 
 /* operation selector for fp4_workspace_bytes */
@@ -86,7 +87,7 @@ enum { FP4MR_OP_ROTATE_QUANTIZE = 0, FP4MR_OP_QUANTIZE_WEIGHTS = 1, FP4MR_OP_GEM
  *                GEMM layout).
  *   codes_out    canonical: M*K/2 bytes;  scales_out: M*K/G bytes (see fp4_packed_bytes for GEMM layout)
  *   tensor_scale NVFP4 only (NULL for MXFP4): one device float; written with s_T, or read if
- *                FP4MR_STATIC_TENSOR_SCALE is set.
+ *                FP4MR_STATIC_TENSOR_SCALE is set.  (FP4MR_SCALE_FIT_RANGE: FP4MR_FIT_RANGE_FLOATS floats, see below.)
  *   workspace    device scratch of at least fp4_workspace_bytes(FP4MR_OP_ROTATE_QUANTIZE, ...) bytes
  *                (0 for MXFP4: may be NULL).
  */
@@ -104,7 +105,8 @@ fp4mr_status_t fp4_rotate_quantize(const void* x, int64_t M, int64_t K, int had_
  * workspace pair; M * K <= FP4MR_STATIC_MAX_ELEMENTS, beyond which the call returns FP4MR_ERR_SHAPE and launches
  * nothing.  Every call on a GPU shares that GPU's array: two NVFP4 calls without FP4MR_STATIC_TENSOR_SCALE that overlap
  * in time on one GPU (different streams, or different host threads) race on it and may return each other's tensor scale;
- * calls on one stream, MXFP4 calls and static-scale calls do not touch it.  Nothing in the array needs clearing
+ * calls on one stream, MXFP4 calls (other than FP4MR_SCALE_FIT_RANGE ones, whose range pass uses it the same way) and
+ * static-scale calls do not touch it.  Nothing in the array needs clearing
  * between calls: every word a call reads was written by that call's own first pass.
  */
 #define FP4MR_STATIC_SCRATCH_BYTES (256 + 4096 * 4)
@@ -138,7 +140,25 @@ fp4mr_status_t fp4_rotate_quantize_static(const void* x, int64_t M, int64_t K, i
  * The scale byte stores k + 127; elements are E2M1(x / s), correctly rounded.  The factor 4/3 is not representable in
  * E8M0: it is a constant of the whole tensor, and the products take it as a flag -- FP4MR_A_SCALE43 / FP4MR_W_SCALE43
  * multiply the result by 4/3 for each operand so quantized (in fp32, before the output is rounded).
+ *
+ * With FP4MR_SCALE_FIT_RANGE (MXFP4 only, no other scale policy beside it: FP4MR_ERR_FMT) the scale byte is re-mapped
+ * onto the range of scales the tensor actually has -- the modified format of the appendix on MXFP scale fitting,
+ * s = 2^(alpha q + beta):
+ *     alpha = (log2 a_max - log2 a_min) / 255,  beta = log2(a_min / 6),   a_min / a_max = the smallest non-zero / the largest
+ *     group abs-max of the (rotated) tensor;   q = clamp(round((log2(amax / 6) - beta) / alpha), 0, 255) per group;
+ *     elements = E2M1(x / s(q)), saturating (s(q) can lie below amax / 6 by half a step, 2^(alpha / 2)).
+ * An all-zero group gets q = 0 and zero codes; one distinct scale gives alpha = 0; an all-zero tensor alpha = beta = 0.
+ * tensor_scale must then point to FP4MR_FIT_RANGE_FLOATS device floats (FP4MR_ERR_NULL otherwise):
+ *     [0] alpha, [1] beta, [2 + q] = s(q) for q = 0 .. 255, the binary32 scale values the elements were divided by
+ * (log2 and exp2 are the GPU's binary32 instructions: decode with these 256 numbers, not by re-evaluating the formula).
+ * With FP4MR_STATIC_TENSOR_SCALE the caller's alpha and beta in [0], [1] are used (weights and activations of a layer
+ * sharing alpha, last paragraph of that appendix), the byte clamps to 0 .. 255, and [2 ..] is still written.
+ * Three launches, two passes over the input; workspace per fp4_workspace_bytes (none when static).  scales_out holds q
+ * in the place and layout of the E8M0 bytes.  Such operands are NOT inputs of fp4_gemm, fp4_fused_linear or
+ * fp4_w4a16_linear: their bytes are not E8M0 exponents and the scaled matrix instruction cannot take a fractional
+ * alpha (the paper evaluates this format in emulation); the decoded tensor is E2M1(code) * s(q).
  */
+#define FP4MR_FIT_RANGE_FLOATS 258
 
 /*
  * The same with a caller-supplied rotation instead of the Hadamard: codes, scales = Q(X R) with R block-diagonal,

@@ -29,6 +29,8 @@ OUT_F32 = 1 << 5
 SCALE_MSE = 1 << 6
 SCALE_ROUND43 = 1 << 7
 SCALE_FIT_TENSOR = 1 << 10
+SCALE_FIT_RANGE = 1 << 11
+FIT_RANGE_FLOATS = 258
 A_SCALE43 = 1 << 8
 W_SCALE43 = 1 << 9
 OPT_GEMM_VARIANT, OPT_GEMM_GRID, OPT_SW_CODEC = 0, 1, 2
@@ -110,7 +112,15 @@ def _quantize(fn, op, x, had_block, fmt, flags, tensor_scale, codes, scales, wor
         codes = torch.empty(cb, dtype=torch.uint8, device=x.device)
         scales = torch.empty(sb, dtype=torch.uint8, device=x.device)
     ts = None
-    if fmt == NVFP4:
+    if flags & SCALE_FIT_RANGE:
+        # [alpha, beta, 256 scale values]; a caller-supplied tensor (its first two floats set) means: use that alpha, beta
+        if tensor_scale is not None:
+            assert tensor_scale.is_cuda and tensor_scale.dtype == torch.float32 and tensor_scale.numel() >= FIT_RANGE_FLOATS
+            flags |= STATIC_TENSOR_SCALE
+            ts = tensor_scale
+        else:
+            ts = torch.empty(FIT_RANGE_FLOATS, dtype=torch.float32, device=x.device)
+    elif fmt == NVFP4:
         if tensor_scale is not None:
             flags |= STATIC_TENSOR_SCALE
             ts = tensor_scale

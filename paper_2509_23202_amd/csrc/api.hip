@@ -20,7 +20,8 @@ static_assert(kStaticScratchBytes == FP4MR_STATIC_SCRATCH_BYTES, "the header sta
 
 namespace {
 
-constexpr uint32_t kQuantFlags = FP4MR_LAYOUT_GEMM | FP4MR_INPUT_F32 | FP4MR_STATIC_TENSOR_SCALE | FP4MR_SCALE_MSE | FP4MR_SCALE_ROUND43 | FP4MR_SCALE_FIT_TENSOR;
+constexpr uint32_t kQuantFlags = FP4MR_LAYOUT_GEMM | FP4MR_INPUT_F32 | FP4MR_STATIC_TENSOR_SCALE | FP4MR_SCALE_MSE | FP4MR_SCALE_ROUND43 | FP4MR_SCALE_FIT_TENSOR |
+                                 FP4MR_SCALE_FIT_RANGE;
 constexpr uint32_t kGemmFlags = FP4MR_A_LAYOUT_GEMM | FP4MR_W_LAYOUT_GEMM | FP4MR_OUT_F32 | FP4MR_A_SCALE43 | FP4MR_W_SCALE43;
 
 // result factor for operands whose scales carry the tensor-level 4/3 (FP4MR_SCALE_ROUND43)
@@ -41,7 +42,9 @@ size_t quant_workspace(fp4mr_fmt_t fmt, uint32_t flags)
 {
     // 256 bytes for the tensor abs-max plus one 4-byte partial per wave of the abs-max pass (1024 blocks x 4 waves)
     // (+ two fp64 sums per wave of the tensor-scale fit pass with FP4MR_SCALE_FIT_TENSOR)
-    if (fmt != FP4MR_NVFP4 || (flags & FP4MR_STATIC_TENSOR_SCALE)) return 0;
+    // (the range pre-pass of FP4MR_SCALE_FIT_RANGE: two 4-byte extremes per wave of 512 blocks x 4 waves, the same size)
+    if (flags & FP4MR_STATIC_TENSOR_SCALE) return 0;
+    if (fmt != FP4MR_NVFP4) return (flags & FP4MR_SCALE_FIT_RANGE) ? 256 + 4096 * 4 : 0;
     return 256 + 4096 * 4 + ((flags & FP4MR_SCALE_FIT_TENSOR) ? 4096 * 16 : 0);
 }
 
@@ -75,8 +78,10 @@ fp4mr_status_t quantize_common(const void* x, int64_t rows, int64_t K, int had_b
     if ((flags & FP4MR_SCALE_ROUND43) && (fmt != FP4MR_MXFP4 || (flags & FP4MR_SCALE_MSE))) return FP4MR_ERR_FMT;
     // the tensor-scale fit is the NVFP4 squared-error search plus a fitted (hence not caller-supplied) tensor scale
     if ((flags & FP4MR_SCALE_FIT_TENSOR) && (fmt != FP4MR_NVFP4 || !(flags & FP4MR_SCALE_MSE) || (flags & FP4MR_STATIC_TENSOR_SCALE))) return FP4MR_ERR_FMT;
+    // the fitted scale range is a format of its own: MXFP4 groups, no other scale policy beside it
+    if ((flags & FP4MR_SCALE_FIT_RANGE) && (fmt != FP4MR_MXFP4 || (flags & (FP4MR_SCALE_MSE | FP4MR_SCALE_ROUND43 | FP4MR_SCALE_FIT_TENSOR)))) return FP4MR_ERR_FMT;
     if (!x || !codes || !scales) return FP4MR_ERR_NULL;
-    if (fmt == FP4MR_NVFP4 && !tensor_scale) return FP4MR_ERR_NULL;
+    if ((fmt == FP4MR_NVFP4 || (flags & FP4MR_SCALE_FIT_RANGE)) && !tensor_scale) return FP4MR_ERR_NULL;
     if (had_block != 1 && had_block != 16 && had_block != 32 && had_block != 64 && had_block != 128) return FP4MR_ERR_HAD_BLOCK;
     if ((flags & FP4MR_INPUT_F32) && had_block != 1) return FP4MR_ERR_HAD_BLOCK;
     if (rot && (had_block == 1 || !aligned16(rot))) return had_block == 1 ? FP4MR_ERR_HAD_BLOCK : FP4MR_ERR_ALIGN;
@@ -101,7 +106,7 @@ fp4mr_status_t quantize_common(const void* x, int64_t rows, int64_t K, int had_b
 
     const hipError_t e = launch_rotate_quantize(x, rows, K, had_block, rot, (int)fmt, (flags & FP4MR_INPUT_F32) != 0,
                                                 (flags & FP4MR_LAYOUT_GEMM) ? 1 : 0, (flags & FP4MR_STATIC_TENSOR_SCALE) != 0,
-                                                (flags & FP4MR_SCALE_FIT_TENSOR) ? 3 : ((flags & FP4MR_SCALE_MSE) ? 1 : ((flags & FP4MR_SCALE_ROUND43) ? 2 : 0)), codes, scales, tensor_scale,
+                                                (flags & FP4MR_SCALE_FIT_RANGE) ? 4 : (flags & FP4MR_SCALE_FIT_TENSOR) ? 3 : ((flags & FP4MR_SCALE_MSE) ? 1 : ((flags & FP4MR_SCALE_ROUND43) ? 2 : 0)), codes, scales, tensor_scale,
                                                 workspace, options().sw_codec == 0,
                                                 static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;

@@ -36,6 +36,7 @@ constexpr int kThreads = 256;
 constexpr int kWavesPerBlock = kThreads / kWave;
 constexpr int kAmaxPassBlocks = 1024;  // grid cap of the NVFP4 abs-max pass and of the tensor-scale fit pass (4096 partials)
 constexpr int kFitRounds = 3;          // alternations of the tensor-scale fit
+constexpr int kRangePassBlocks = 512;  // grid cap of the range pre-pass (two partials per wave: the same 4096 slots)
 
 // Tensor-scale fit (Section 4.1 "Ingredient 1": alternating optimisation over the block scales and the per-tensor scale).
 // With codes and group scales fixed the quantized tensor is s_T * v, v_i = s_G * E2M1(code_i), and the minimiser of
@@ -85,9 +86,9 @@ struct RqArgs {
     const void* x;
     uint8_t* codes;
     uint8_t* scales;
-    float* tensor_scale;   // NVFP4: s_T (written by the quantize pass unless static)
+    float* tensor_scale;   // NVFP4: s_T (written by the quantize pass unless static); fitted scale range: alpha, beta, 256 scale values
     uint32_t* amax_bits;   // NVFP4 dynamic: bit pattern of max |y| over the tensor (workspace)
-    uint32_t* amax_partial;  // NVFP4 dynamic: one partial maximum per wave of the abs-max pass (workspace)
+    uint32_t* amax_partial;  // NVFP4 dynamic: one partial maximum per wave of the abs-max pass (workspace); range pass: max and min per wave
     int n_partials;          // > 0: the quantize pass reduces that many partials itself (small calls: no finalize launch)
     double* fit_partial;     // tensor-scale fit: per wave of the fit pass, sum x v and sum v v (workspace)
     int64_t rows, K;
@@ -97,6 +98,37 @@ struct RqArgs {
     float c_hi, c_lo;      // 1/sqrt(b) split in two floats (1 and 0 for a dense rotation)
     int static_scale;
 };
+
+// Fitted scale range (appendix on MXFP scale fitting): what the quantize pass needs of (alpha, beta), read from the
+// buffer that the range pre-pass (or the caller) filled: [0] alpha, [1] beta, [2 .. 257] the 256 scale values.
+constexpr float kLog2Of6 = 2.5849625007211562f;
+struct FitRange {
+    float lmin, inv;
+    const float* table;
+};
+__device__ __forceinline__ FitRange load_fit_range(const RqArgs& a)
+{
+    const float alpha = a.tensor_scale[0], beta = a.tensor_scale[1];
+    FitRange f;
+    f.lmin = beta + kLog2Of6;
+    f.inv = alpha > 0.0f ? __fdiv_rn(1.0f, alpha) : 0.0f;
+    f.table = a.tensor_scale + 2;
+    return f;
+}
+
+// range pre-pass: the wave's largest group abs-max and its smallest non-zero one -> its two slots of the partials
+__device__ __forceinline__ void range_store_partial(float rmax, float rmin, uint32_t* partial, int64_t wave, int lane)
+{
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+        rmax = fmaxf(rmax, __shfl_xor(rmax, m));
+        rmin = fminf(rmin, __shfl_xor(rmin, m));
+    }
+    if (lane == 0) {
+        partial[2 * wave] = __float_as_uint(rmax);
+        partial[2 * wave + 1] = __float_as_uint(rmin);  // +inf: the wave saw no non-zero group
+    }
+}
 
 // NVFP4 tensor scale as the quantize pass sees it: caller-supplied, or abs-max / 2688 with the abs-max taken from the
 // finalized word or -- small calls -- reduced here from the abs-max pass's per-wave partials (every wave computes the
@@ -182,7 +214,8 @@ __device__ __forceinline__ void build_dense_operand(v8bf (&hop)[BP / 16][BP / 32
 
 // ------------------------------------------------------------------------------------------------------
 // MFMA rotation kernel.  BP = b' in {32,64,128}; G = 32 (MXFP4) or 16 (NVFP4); LAYOUT 0 canonical / 1 GEMM;
-// PASS 0 = quantize, 1 = tensor abs-max only (NVFP4 pre-pass).
+// PASS 0 = quantize, 1 = tensor abs-max only (NVFP4 pre-pass), 2 = sums of the tensor-scale fit, 3 = largest and smallest
+// non-zero group abs-max (pre-pass of the fitted scale range).  POL = scale policy (GroupQuant::run; 3 = fitted range).
 //
 // Work item = FR * (128/BP) supertiles = FR * 2048 elements.
 //   canonical: supertiles are consecutive runs of 16 vectors in flat (row-major) order;
@@ -224,6 +257,9 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
     }
     float hmax = 0.0f;
     double fit_num = 0.0, fit_den = 0.0;
+    float rmax = 0.0f, rmin = __builtin_inff();
+    FitRange fr{0.0f, 0.0f, nullptr};
+    if constexpr (POL == 3 && PASS == 0) fr = load_fit_range(a);
 
     for (int64_t item = wave; item < a.n_items; item += n_waves) {
         int64_t ebase[NST];
@@ -286,8 +322,19 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
                     const float h = acc[t][v];
                     y[4 * t + v] = __fmaf_rn(h, a.c_hi, h * a.c_lo);
                 }
+            if constexpr (PASS == 3) {
+                // (vectors past the end were loaded as zeros: an all-zero group takes no part)
+#pragma unroll
+                for (int gi = 0; gi < GQ::NG; ++gi) {
+                    const float am = GQ::group_amax(y, gi);
+                    rmax = fmaxf(rmax, am);
+                    if (am > 0.0f) rmin = fminf(rmin, am);
+                }
+                continue;
+            }
             uint32_t out[GQ::ND], sc[GQ::NG];
-            GQ::template run<POL>(y, s_T, out, sc);
+            if constexpr (POL == 3) GQ::mx_fit(y, fr.lmin, fr.inv, fr.table, out, sc);
+            else GQ::template run<POL>(y, s_T, out, sc);
             if constexpr (PASS == 2) {
                 // (vectors past the end were loaded as zeros: they add nothing)
                 if constexpr (G == 16) fit_accumulate<NO, GQ::ND, GQ::NG, HW>(y, out, sc, fit_num, fit_den);
@@ -328,6 +375,7 @@ __global__ __launch_bounds__(kThreads) void rq_mfma_kernel(RqArgs a)
         }
     }
     if constexpr (PASS == 2) fit_store_partial(fit_num, fit_den, a.fit_partial, wave, lane);
+    if constexpr (PASS == 3) range_store_partial(rmax, rmin, a.amax_partial, wave, lane);
 }
 
 // ------------------------------------------------------------------------------------------------------
@@ -400,6 +448,9 @@ __global__ __launch_bounds__(kThreads) void rq_frag_kernel(RqArgs a)
         if (!a.static_scale && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) *a.tensor_scale = s_T;
     }
 
+    FitRange fr{0.0f, 0.0f, nullptr};
+    if constexpr (POL == 3) fr = load_fit_range(a);
+
     // this lane's NO outputs of a vector of group kk start at element kk*16*BP + e_grp of the item's K range
     const int e_grp = g * BP + q * NO;
 
@@ -425,7 +476,8 @@ __global__ __launch_bounds__(kThreads) void rq_frag_kernel(RqArgs a)
                     y[4 * t + v] = __fmaf_rn(h, a.c_hi, h * a.c_lo);
                 }
             uint32_t out[GQ::ND], sc[GQ::NG];
-            GQ::template run<POL>(y, s_T, out, sc);
+            if constexpr (POL == 3) GQ::mx_fit(y, fr.lmin, fr.inv, fr.table, out, sc);
+            else GQ::template run<POL>(y, s_T, out, sc);
             const int rr = wib * RPW + u;  // row inside the row-block
             const int fr = kk * (BP / 8) + (e_grp >> 7), e0 = e_grp & 127;  // fragment of the item, offset inside it
             const int d = fr * 256 + ((((e0 >> 5) * 16 + rr) << 2) + ((e0 & 31) >> 3));
@@ -497,6 +549,9 @@ __global__ __launch_bounds__(kThreads) void q_direct_kernel(RqArgs a)
     }
     float hmax = 0.0f;
     double fit_num = 0.0, fit_den = 0.0;
+    float rmax = 0.0f, rmin = __builtin_inff();
+    FitRange fr{0.0f, 0.0f, nullptr};
+    if constexpr (POL == 3 && PASS == 0) fr = load_fit_range(a);
 
     for (int64_t item = wave; item < a.n_items; item += n_waves) {
 #pragma unroll
@@ -539,8 +594,15 @@ __global__ __launch_bounds__(kThreads) void q_direct_kernel(RqArgs a)
                 for (int i = 0; i < 8; ++i) hmax = fabs_max(hmax, y[i]);
                 continue;
             }
+            if constexpr (PASS == 3) {
+                const float am = GQ::group_amax(y, 0);
+                rmax = fmaxf(rmax, am);
+                if (am > 0.0f) rmin = fminf(rmin, am);
+                continue;
+            }
             uint32_t out[1], sc[1];
-            GQ::template run<POL>(y, s_T, out, sc);
+            if constexpr (POL == 3) GQ::mx_fit(y, fr.lmin, fr.inv, fr.table, out, sc);
+            else GQ::template run<POL>(y, s_T, out, sc);
             if constexpr (PASS == 2) {
                 if constexpr (G == 16) fit_accumulate<8, 1, 1, HW>(y, out, sc, fit_num, fit_den);
                 continue;
@@ -565,6 +627,7 @@ __global__ __launch_bounds__(kThreads) void q_direct_kernel(RqArgs a)
         if (lane == 0) a.amax_partial[wave] = __float_as_uint(hmax);
     }
     if constexpr (PASS == 2) fit_store_partial(fit_num, fit_den, a.fit_partial, wave, lane);
+    if constexpr (PASS == 3) range_store_partial(rmax, rmin, a.amax_partial, wave, lane);
 }
 
 // max over the per-wave partials of the abs-max pass (non-negative floats order like their bit patterns)
@@ -610,6 +673,51 @@ __global__ __launch_bounds__(256) void fit_finalize_kernel(const double* partial
         __syncthreads();
     }
     if (threadIdx.x == 0 && red[1][0] > 0.0 && red[0][0] > 0.0) *tensor_scale = (float)(red[0][0] / red[1][0]);
+}
+
+// Fitted scale range: (alpha, beta) from the per-wave extremes of the range pre-pass (n_waves > 0) or as the caller left
+// them in out[0..1] (n_waves == 0), then the 256 scale values 2^(alpha q + beta), one per thread.
+//     alpha = (log2 amax_max - log2 amax_min) / 255,   beta = log2 amax_min - log2 6      (binary32, v_log_f32 / v_exp_f32)
+// No non-zero group at all: alpha = beta = 0.
+__global__ __launch_bounds__(256) void range_finalize_kernel(const uint32_t* partial, int n_waves, float* out)
+{
+    __shared__ uint32_t red[2][256];
+    __shared__ float ab[2];
+    if (n_waves > 0) {
+        uint32_t hi = 0, lo = 0x7f800000u;  // non-negative floats order like their bit patterns
+        for (int i = threadIdx.x; i < n_waves; i += 256) {
+            hi = max(hi, partial[2 * i]);
+            lo = min(lo, partial[2 * i + 1]);
+        }
+        red[0][threadIdx.x] = hi;
+        red[1][threadIdx.x] = lo;
+        __syncthreads();
+        for (int w = 128; w >= 1; w >>= 1) {
+            if ((int)threadIdx.x < w) {
+                red[0][threadIdx.x] = max(red[0][threadIdx.x], red[0][threadIdx.x + w]);
+                red[1][threadIdx.x] = min(red[1][threadIdx.x], red[1][threadIdx.x + w]);
+            }
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) {
+            const float amax = __uint_as_float(red[0][0]), amin = __uint_as_float(red[1][0]);
+            float alpha = 0.0f, beta = 0.0f;
+            if (amax > 0.0f) {
+                const float lmin = __log2f(amin), lmax = __log2f(amax);
+                alpha = __fdiv_rn(lmax - lmin, 255.0f);
+                beta = lmin - kLog2Of6;
+            }
+            ab[0] = alpha;
+            ab[1] = beta;
+            out[0] = alpha;
+            out[1] = beta;
+        }
+    } else if (threadIdx.x == 0) {
+        ab[0] = out[0];
+        ab[1] = out[1];
+    }
+    __syncthreads();
+    out[2 + threadIdx.x] = exp2f(__fmaf_rn(ab[0], (float)threadIdx.x, ab[1]));
 }
 
 // ------------------------------------------------------------------------------------------------------
@@ -702,6 +810,9 @@ template <int G, bool HW, int POL = 0>
 hipError_t dispatch_layout_pass(const RqArgs& a, bool in_f32, int layout, int pass, int grid_cap, hipStream_t st, int* blocks_out = nullptr)
 {
     if (pass == 1) return dispatch_block<G, 0, 1, HW, 0>(a, in_f32, grid_cap, st, blocks_out);  // layout and scale policy do not matter for the abs-max pass
+    if constexpr (G == 32 && HW) {
+        if (pass == 3) return dispatch_block<G, 0, 3, HW, 0>(a, in_f32, grid_cap, st, blocks_out);  // range pre-pass: extremes only
+    }
     if constexpr (G == 16 && HW && POL == 1) {
         if (pass == 2) return dispatch_block<G, 0, 2, HW, 1>(a, in_f32, grid_cap, st, blocks_out);  // tensor-scale fit: sums only
     }
@@ -771,6 +882,20 @@ hipError_t launch_rotate_quantize(const void* x, int64_t rows, int64_t K, int b,
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
         return dispatch_layout_pass<16, true, 1>(a, in_f32, layout_gemm, 0, grid_cap, st);
+    }
+    if (policy == 4) {
+        // Scale byte fitted to the tensor's range of scales (appendix on MXFP scale fitting).  Dynamic: range pre-pass (one
+        // pair of extremes per wave) -> (alpha, beta) and the 256 scale values -> quantize pass.  Static: the caller's
+        // (alpha, beta) are in tensor_scale[0..1]; only the scale values are computed.
+        if (fmt != 0 || !tensor_scale) return hipErrorInvalidValue;
+        int range_blocks = 0;
+        if (!static_scale) {
+            a.amax_partial = a.amax_bits + 64;
+            if ((e = dispatch_layout_pass<32, true>(a, in_f32, 0, 3, kRangePassBlocks, st, &range_blocks)) != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(range_finalize_kernel, dim3(1), dim3(256), 0, st, a.amax_partial, range_blocks * kWavesPerBlock, a.tensor_scale);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        return dispatch_layout_pass<32, true, 3>(a, in_f32, layout_gemm, 0, grid_cap, st);
     }
     if (policy == 1) {
         // the scale search is written with the hardware converts only

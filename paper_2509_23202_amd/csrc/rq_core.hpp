@@ -243,6 +243,45 @@ struct GroupQuant {
         }
     }
 
+    // ---- scale byte fitted to the tensor's range of scales (appendix on MXFP scale fitting: s = 2^(alpha q + beta), the
+    // modified format MXFP4-dagger).  The byte is the index of the nearest of 256 scale values that are evenly spaced
+    // in the log domain between the smallest and the largest ideal group scale (amax / 6) of the tensor:
+    //     q = clamp(round((log2 amax - lmin) * inv), 0, 255),  lmin = beta + log2 6,  inv = 1 / alpha  (0 when alpha = 0)
+    // and the group's scale is table[q], the binary32 value of 2^(alpha q + beta) that the range pre-pass published.
+    // Elements follow the NVFP4 chain (correctly rounded reciprocal, one multiply, the converting pack: saturating).
+    // A group that is all zero gets byte 0 and zero codes.
+    __device__ static __forceinline__ float group_amax(const float (&y)[NO], int gi)
+    {
+        float amax = 0.0f;
+#pragma unroll
+        for (int i = 0; i < VG; ++i) amax = fabs_max(amax, y[gi * VG + i]);
+        if constexpr (LG >= 2) amax = fmaxf(amax, __shfl_xor(amax, XOR_LO));
+        if constexpr (LG >= 4) amax = fmaxf(amax, __shfl_xor(amax, XOR_LO * 2));
+        return amax;
+    }
+
+    __device__ static __forceinline__ void mx_fit(const float (&y)[NO], float lmin, float inv, const float* __restrict__ table,
+                                                  uint32_t (&out)[ND], uint32_t (&sc)[NG])
+    {
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) {
+            const float amax = group_amax(y, gi);
+            int q = 0;
+            if (amax > 0.0f) q = min(max((int)rintf((__log2f(amax) - lmin) * inv), 0), 255);
+            sc[gi] = (uint32_t)q;
+            const float d = table[q];
+            const float r = (amax > 0.0f && d > 0.0f) ? __fdiv_rn(1.0f, d) : 0.0f;
+#pragma unroll
+            for (int dd = 0; dd < VG / 8; ++dd) {
+                float t[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) t[i] = y[gi * VG + dd * 8 + i] * r;
+                const uint32_t p = e2m1_pack8<HW>(t);
+                out[gi * (VG / 8) + dd] = (r == 0.0f) ? 0u : p;
+            }
+        }
+    }
+
     // POL: 0 abs-max, 1 squared-error search, 2 rounded exponent with the 4/3 factor (MXFP4 only)
     template <int POL>
     __device__ static __forceinline__ void run(const float (&y)[NO], float s_T, uint32_t (&out)[ND], uint32_t (&sc)[NG])

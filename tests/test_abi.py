@@ -40,9 +40,11 @@ def test_binding_imports_and_matches_header():
         assert callable(getattr(binding, n))
     hdr = HEADER.read_text()
     for name in ("LAYOUT_GEMM", "INPUT_F32", "STATIC_TENSOR_SCALE", "A_LAYOUT_GEMM", "W_LAYOUT_GEMM", "OUT_F32", "SCALE_MSE",
-                 "SCALE_ROUND43", "A_SCALE43", "W_SCALE43", "SCALE_FIT_TENSOR"):
+                 "SCALE_ROUND43", "A_SCALE43", "W_SCALE43", "SCALE_FIT_TENSOR", "SCALE_FIT_RANGE"):
         m = re.search(rf"FP4MR_{name}\s*=\s*1u\s*<<\s*(\d+)", hdr)
         assert m and getattr(binding, name) == 1 << int(m.group(1)), name
+    m = re.search(r"#define FP4MR_FIT_RANGE_FLOATS\s+(\d+)", hdr)
+    assert m and binding.FIT_RANGE_FLOATS == int(m.group(1)) == 2 + 256
 
 
 def test_sizes(lib):
@@ -59,6 +61,9 @@ def test_sizes(lib):
     # the tensor-scale fit adds two fp64 sums per wave of its reduction pass
     assert (b.workspace_bytes(b.OP_QUANTIZE_WEIGHTS, 64, 0, 4096, b.NVFP4, b.SCALE_MSE | b.SCALE_FIT_TENSOR)
             == b.workspace_bytes(b.OP_QUANTIZE_WEIGHTS, 64, 0, 4096, b.NVFP4, b.SCALE_MSE) + 4096 * 16)
+    # the fitted scale range has a range pre-pass (two extremes per wave), unless alpha and beta are given
+    assert b.workspace_bytes(b.OP_ROTATE_QUANTIZE, 64, 0, 4096, b.MXFP4, b.SCALE_FIT_RANGE) == 256 + 4096 * 4
+    assert b.workspace_bytes(b.OP_ROTATE_QUANTIZE, 64, 0, 4096, b.MXFP4, b.SCALE_FIT_RANGE | b.STATIC_TENSOR_SCALE) == 0
     assert b.workspace_bytes(b.OP_GEMM, 64, 64, 4096, b.MXFP4, b.A_LAYOUT_GEMM | b.W_LAYOUT_GEMM) == 0
     assert b.workspace_bytes(b.OP_GEMM, 64, 64, 4096, b.MXFP4) > 0
 
@@ -88,6 +93,11 @@ def test_argument_validation_happens_before_any_launch(lib):
     assert q(fmt=1, ts=fake, ws=fake, wsz=1 << 20, flags=FIT | b.STATIC_TENSOR_SCALE) == 4   # with a fitted, not a given, s_T
     assert q(fmt=1, ts=fake, ws=fake, wsz=256 + 4096 * 4, flags=FIT) == 6        # and needs its larger workspace
     assert q(fmt=1, ts=fake) == 6               # ... and a workspace
+    RNG = b.SCALE_FIT_RANGE
+    assert q(fmt=1, ts=fake, ws=fake, wsz=1 << 20, flags=RNG) == 4               # the fitted scale range is an MXFP4 format
+    assert q(flags=RNG | b.SCALE_MSE, ts=fake) == 4 and q(flags=RNG | b.SCALE_ROUND43, ts=fake) == 4   # and a policy of its own
+    assert q(flags=RNG) == 1                                                     # needs the buffer for alpha, beta and the scale values
+    assert q(flags=RNG, ts=fake) == 6 and q(flags=RNG, ts=fake, ws=fake, wsz=4096) == 6   # and the range pass's workspace
     assert q(fmt=1, ts=fake, ws=fake, wsz=8) == 6
     g = lambda **kw: L.fp4_gemm(kw.get("a", fake), fake, kw.get("ats", None), fake, fake, None, kw.get("M", 16), kw.get("N", 16),
                                 kw.get("K", 128), kw.get("fmt", 0), kw.get("out", fake), kw.get("ws", None), kw.get("wsz", 0),
