@@ -459,6 +459,12 @@ def main():
             dense["hadamard32_round43_scales"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, 32, fp4.MXFP4, flags=GL | fp4.SCALE_ROUND43, codes=oc, scales=osc))
             # scale byte fitted to the tensor's range of scales (appendix on MXFP scale fitting): a range pre-pass, then the quantize pass
             dense["hadamard32_fit_range_scales"] = time_rq(lambda x_: fp4.fp4_rotate_quantize(x_, 32, fp4.MXFP4, flags=GL | fp4.SCALE_FIT_RANGE, codes=oc, scales=osc))
+            # the decoding side (fp4_dequantize): the codes just written, GEMM layout, back to bf16 [16384, 8192]
+            fp4.fp4_rotate_quantize(xs[0], 32, fp4.MXFP4, flags=GL, codes=oc, scales=osc)
+            dq_out = torch.empty((Mr, Kr), dtype=torch.bfloat16, device="cuda")
+            t_dq = time_us(lambda: fp4.fp4_dequantize(oc, osc, None, Mr, Kr, fp4.MXFP4, flags=GL, out=dq_out), n=n_rq, warm=3)
+            dense["dequantize_to_bf16"] = {"avg_launch_us": round(t_dq, 2), "achieved_gbs": round(Mr * Kr * (0.5 + 1.0 / 32 + 2.0) / t_dq / 1e3, 1)}
+            del dq_out
             result["rotate_quantize_variants"] = dense
             del xs, oc, osc
         except Exception as exc:  # noqa: BLE001 - reported in the JSON line

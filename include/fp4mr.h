@@ -283,6 +283,22 @@ fp4mr_status_t fp4_gptq_prepare(const float* hessian, int64_t K, float damp, int
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The decoding side of the formats (Section 2: scale times element per group; Section 4.1 "Ingredient 1": NVFP4 with its
+ * tensor scale; appendix on MXFP scale fitting): out[m, k] = E2M1(code) * scale of its group -- what an emulated
+ * evaluation multiplies, and the consumer of FP4MR_SCALE_FIT_RANGE tensors.
+ *   codes, scales   device pointers, as written by the quantize calls: canonical, or GEMM layout with FP4MR_LAYOUT_GEMM
+ *   tensor_scale    NVFP4: one device float; FP4MR_SCALE_FIT_RANGE: the FP4MR_FIT_RANGE_FLOATS floats of the quantize call
+ *                   (its 256 scale values are used); NULL otherwise
+ *   out             device pointer, [rows, K] row-major bf16 (fp32 with FP4MR_OUT_F32), 16-byte aligned, written in full
+ *   flags           FP4MR_LAYOUT_GEMM, FP4MR_OUT_F32, FP4MR_SCALE_ROUND43 (MXFP4: times the tensor-level 4/3),
+ *                   FP4MR_SCALE_FIT_RANGE (MXFP4: the byte indexes the scale values); others: FP4MR_ERR_FMT
+ * Binary32 arithmetic: MXFP4 exact; 4/3 rule, fitted range and NVFP4 (element times group scale is exact, then the tensor
+ * scale) one rounding; bf16 output rounds that value to nearest even.  No workspace.  Errors as the quantize calls.
+ */
+fp4mr_status_t fp4_dequantize(const void* codes, const void* scales, const float* tensor_scale, int64_t rows, int64_t K,
+                              fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream);
+
+/*
  * Process-wide switches for tuning sweeps and cross-checks (none is needed for normal use; not thread-safe: set them
  * before calls are issued concurrently).  Returns FP4MR_ERR_FMT for an unknown option or a value out of range.
  *   FP4MR_OPT_GEMM_VARIANT  0 (default): fp4_gemm picks the tile shape from M, N, K; 1..16 (MXFP4) / 1..3 (NVFP4): force

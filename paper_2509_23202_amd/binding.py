@@ -67,6 +67,8 @@ lib.fp4_status_string.restype = ctypes.c_char_p
 lib.fp4_version.restype = _i32
 lib.fp4_probe.argtypes = [_i32, _p, _sz, _i32, _p]
 lib.fp4_probe.restype = _i32
+lib.fp4_dequantize.argtypes = [_p, _p, _p, _i64, _i64, _i32, _p, _u32, _p]
+lib.fp4_dequantize.restype = _i32
 lib.fp4_set_option.argtypes = [_i32, _i32]
 lib.fp4_set_option.restype = _i32
 
@@ -260,6 +262,16 @@ def fp4_w4a16_linear(x, had_block: int, w_codes, w_scales, N: int, fmt: int = MX
 
 
 PROBE_MFMA_FP4, PROBE_MFMA_F16, PROBE_COPY, PROBE_READ = 0, 1, 2, 3
+
+
+def fp4_dequantize(codes, scales, tensor_scale, rows: int, K: int, fmt: int, *, flags: int = 0, out=None):
+    """xhat [rows, K] = E2M1(code) * scale, bf16 (fp32 with OUT_F32), from canonical or (LAYOUT_GEMM) GEMM-layout operands.
+    tensor_scale: the NVFP4 tensor scale, the FIT_RANGE_FLOATS buffer of a SCALE_FIT_RANGE call, else None."""
+    assert codes.is_cuda and scales.is_cuda
+    if out is None:
+        out = torch.empty((rows, K), dtype=torch.float32 if flags & OUT_F32 else torch.bfloat16, device=codes.device)
+    _check(lib.fp4_dequantize(codes.data_ptr(), scales.data_ptr(), _ptr(tensor_scale), rows, K, fmt, out.data_ptr(), flags, _stream()))
+    return out
 
 
 def fp4_probe(which: int, buf, iters: int = 1) -> None:

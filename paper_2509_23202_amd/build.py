@@ -17,7 +17,7 @@ HERE = Path(__file__).resolve().parent
 CSRC = HERE / "csrc"
 BUILD = HERE / "_build"
 LIB = HERE / "libfp4mr.so"
-SOURCES = ["api.hip", "rotate_quantize.hip", "gemm_mxfp4.hip", "gemm_nvfp4.hip", "gemm_nv16.hip", "gemm_skinny.hip", "gemm_fused_decode.hip", "repack.hip", "gptq.hip", "gptq_prepare.hip", "probes.hip"]
+SOURCES = ["api.hip", "rotate_quantize.hip", "gemm_mxfp4.hip", "gemm_nvfp4.hip", "gemm_nv16.hip", "gemm_skinny.hip", "gemm_fused_decode.hip", "repack.hip", "gptq.hip", "gptq_prepare.hip", "probes.hip", "dequantize.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # Packed-fp32 instruction selection is switched off for all device code (a device-only target feature; the host

@@ -336,6 +336,25 @@ size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t 
     return 0;
 }
 
+fp4mr_status_t fp4_dequantize(const void* codes, const void* scales, const float* tensor_scale, int64_t rows, int64_t K,
+                              fp4mr_fmt_t fmt, void* out, uint32_t flags, void* stream)
+{
+    if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return FP4MR_ERR_FMT;
+    if (flags & ~(uint32_t)(FP4MR_LAYOUT_GEMM | FP4MR_OUT_F32 | FP4MR_SCALE_ROUND43 | FP4MR_SCALE_FIT_RANGE)) return FP4MR_ERR_FMT;
+    if ((flags & (FP4MR_SCALE_ROUND43 | FP4MR_SCALE_FIT_RANGE)) && fmt != FP4MR_MXFP4) return FP4MR_ERR_FMT;
+    if ((flags & FP4MR_SCALE_ROUND43) && (flags & FP4MR_SCALE_FIT_RANGE)) return FP4MR_ERR_FMT;
+    if (!codes || !scales || !out) return FP4MR_ERR_NULL;
+    if ((fmt == FP4MR_NVFP4 || (flags & FP4MR_SCALE_FIT_RANGE)) && !tensor_scale) return FP4MR_ERR_NULL;
+    if (rows <= 0 || K <= 0 || K % group_of(fmt) != 0) return FP4MR_ERR_SHAPE;
+    if ((flags & FP4MR_LAYOUT_GEMM) && K % 128 != 0) return FP4MR_ERR_SHAPE;
+    if (rows > ((int64_t)1 << 40) / K) return FP4MR_ERR_SHAPE;
+    if (!aligned16(codes) || !aligned16(scales) || !aligned16(out)) return FP4MR_ERR_ALIGN;
+    const int mode = fmt == FP4MR_NVFP4 ? 2 : ((flags & FP4MR_SCALE_FIT_RANGE) ? 3 : ((flags & FP4MR_SCALE_ROUND43) ? 1 : 0));
+    const hipError_t e = launch_dequantize(codes, scales, tensor_scale, rows, K, mode, (flags & FP4MR_LAYOUT_GEMM) != 0, out,
+                                           (flags & FP4MR_OUT_F32) != 0, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
+}
+
 fp4mr_status_t fp4_packed_bytes(int64_t rows, int64_t K, fp4mr_fmt_t fmt, uint32_t flags, size_t* codes_bytes, size_t* scales_bytes)
 {
     if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return FP4MR_ERR_FMT;

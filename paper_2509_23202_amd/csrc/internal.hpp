@@ -91,6 +91,10 @@ hipError_t launch_gptq_hessian_product(const float* Xr, int64_t T, int64_t K, fl
 
 // measurement aids (fp4_probe): which = 0 scaled-FP4 MFMA issue loop, 1 fp16 MFMA issue loop (buf: one 24-byte record per
 // compute unit), 2 streaming copy of the first half of buf to the second, 3 streaming read of the first half
+// mode: 0 MXFP4, 1 MXFP4 with the tensor-level 4/3, 2 NVFP4, 3 scale byte fitted to the tensor's range (table at tensor_scale + 2)
+hipError_t launch_dequantize(const void* codes, const void* scales, const float* tensor_scale, int64_t rows, int64_t K, int mode,
+                             bool gemm_layout, void* out, bool out_f32, hipStream_t st);
+
 hipError_t launch_probe(int which, void* buf, size_t bytes, int iters, hipStream_t st);
 
 }  // namespace fp4mr

@@ -40,4 +40,21 @@ __host__ __device__ inline int64_t gemm_scales_bytes(int64_t rows, int64_t K, in
     return rb * (K / kFragK) * 128;                      // NVFP4: 64 lanes x 2 bytes per fragment
 }
 
+// byte offsets of the formulas above (row = row of the tensor, k = element along K, kg = k / 32, g16 = k / 16;
+// KC = K / 128, KS = ceil(K / 512))
+__host__ __device__ inline int64_t gemm_codes_offset(int64_t row, int64_t k, int64_t KC)
+{
+    return ((row >> 4) * KC + (k >> 7)) * 1024 + ((((k & 127) >> 5) * 16 + (row & 15)) << 4) + ((k & 31) >> 1);
+}
+
+__host__ __device__ inline int64_t gemm_mx_scale_offset(int64_t row, int64_t kg, int64_t KS)
+{
+    return ((((row >> 4) * KS + (kg >> 4)) * 64 + ((kg & 3) * 16 + (row & 15))) << 2) + ((kg >> 2) & 3);
+}
+
+__host__ __device__ inline int64_t gemm_nv_scale_offset(int64_t row, int64_t g16, int64_t KC)
+{
+    return ((((row >> 4) * KC + (g16 >> 3)) * 64 + (((g16 & 7) >> 1) * 16 + (row & 15))) << 1) + (g16 & 1);
+}
+
 }  // namespace fp4mr
