@@ -153,7 +153,8 @@ fp4mr_status_t fp4_rotate_quantize_static(const void* x, int64_t M, int64_t K, i
  * (log2 and exp2 are the GPU's binary32 instructions: decode with these 256 numbers, not by re-evaluating the formula).
  * With FP4MR_STATIC_TENSOR_SCALE the caller's alpha and beta in [0], [1] are used (weights and activations of a layer
  * sharing alpha, last paragraph of that appendix), the byte clamps to 0 .. 255, and [2 ..] is still written.
- * Three launches, two passes over the input; workspace per fp4_workspace_bytes (none when static).  scales_out holds q
+ * Three launches, two passes over the input; workspace per fp4_workspace_bytes (none when static).  The converting
+ * instructions are used whatever the software-codec option says.  scales_out holds q
  * in the place and layout of the E8M0 bytes.  Such operands are NOT inputs of fp4_gemm, fp4_fused_linear or
  * fp4_w4a16_linear: their bytes are not E8M0 exponents and the scaled matrix instruction cannot take a fractional
  * alpha (the paper evaluates this format in emulation); the decoded tensor is E2M1(code) * s(q).
