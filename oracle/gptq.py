@@ -65,18 +65,22 @@ def column_scales(scales: np.ndarray, fmt: int, s_T) -> np.ndarray:
     return ref.dequantize(ones, scales, fmt, s_T)[:, ::ref.GROUP[fmt]]
 
 
-def sweep(w_rot: np.ndarray, scales: np.ndarray, fmt: int, s_T, U: np.ndarray, perm: np.ndarray, stop: int | None = None):
+def sweep(w_rot: np.ndarray, scales: np.ndarray, fmt: int, s_T, U: np.ndarray, perm: np.ndarray, stop: int | None = None,
+          table: np.ndarray | None = None):
     """The GPTQ sweep on fixed scales.  w_rot [N,K] rotated weights, scales [N,K/G] bytes (original column order),
     U [K,K] upper factor in act-order coordinates, perm [K].  Visits the columns perm[0], perm[1], ...:
 
         q = Q(w / s) ;  e = (w - q s) / U[j,j] ;  w[later columns] -= e * U[j, later]
 
     Returns (codes [N,K/2] packed in original order, work [N,K] = the working weights in act-order coordinates after
-    `stop` columns (all of them by default): quantized values in the visited columns, updated weights in the rest)."""
+    `stop` columns (all of them by default): quantized values in the visited columns, updated weights in the rest).
+    table: 256 scale values; a group's scale is then table[byte] (the scale byte fitted to the tensor's range of scales,
+    appendix on MXFP scale fitting) instead of the decoded E8M0 / E4M3 byte."""
     G = ref.GROUP[fmt]
     W = np.asarray(w_rot, dtype=np.float64)[:, perm].copy()
     N, K = W.shape
-    S = column_scales(scales, fmt, s_T)[:, np.asarray(perm) // G]      # scale of every visited column
+    S_groups = column_scales(scales, fmt, s_T) if table is None else np.asarray(table, dtype=np.float64)[np.asarray(scales)]
+    S = S_groups[:, np.asarray(perm) // G]      # scale of every visited column
     U = np.asarray(U, dtype=np.float64)
     Q = np.zeros((N, K), dtype=np.uint8)
     n_cols = K if stop is None else stop
@@ -102,18 +106,23 @@ def mr_gptq(w_bf16_bits: np.ndarray, H: np.ndarray, b: int, fmt: int, policy: st
     """Whole weight quantizer: rotate, fix the scales, order, factor, sweep.  H is the Hessian X'^T X' of the ROTATED
     calibration inputs [K,K].  Returns (codes, scales, s_T, perm, U)."""
     y = ref.rotate(w_bf16_bits, b)
+    table = None
     if policy == "mse_alt":      # NVFP4: group scales and tensor scale by the alternating optimisation (Section 4.1 Ingredient 1)
         _, scales, s_T, _ = ref.quantize_nvfp4_alternating(y, 3)
+    elif policy == "fit_range":  # MXFP4 with the scale byte fitted to the range of scales: s_T is then the table of 256 scale values
+        _, scales, _, table = ref.quantize_mxfp4_fit(y)
+        s_T = table
     else:
         _, scales, s_T = ref.quantize(y, fmt, policy=policy)
     K = y.shape[1]
     perm = act_order(H) if order else np.arange(K)
     U = inverse_factor(H, perm, damp)
-    codes, _ = sweep(y, scales, fmt, s_T, U, perm)
+    codes, _ = sweep(y, scales, fmt, None if table is not None else s_T, U, perm, table=table)
     return codes, scales, s_T, perm, U
 
 
-def layer_error(w_rot: np.ndarray, codes: np.ndarray, scales: np.ndarray, fmt: int, s_T, H: np.ndarray) -> float:
-    """tr((What - W) H (What - W)^T) = ||X' What^T - X' W^T||^2 for the rotated weights and inputs."""
-    D = ref.dequantize(codes, scales, fmt, s_T) - np.asarray(w_rot, dtype=np.float64)
+def layer_error(w_rot: np.ndarray, codes: np.ndarray, scales: np.ndarray, fmt: int, s_T, H: np.ndarray, table=None) -> float:
+    """tr((What - W) H (What - W)^T) = ||X' What^T - X' W^T||^2 for the rotated weights and inputs (table: see sweep)."""
+    What = ref.dequantize(codes, scales, fmt, s_T) if table is None else ref.dequantize_table(codes, scales, table)
+    D = What - np.asarray(w_rot, dtype=np.float64)
     return float(np.einsum("nk,kl,nl->", D, np.asarray(H, dtype=np.float64), D))
