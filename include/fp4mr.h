@@ -247,8 +247,10 @@ fp4mr_status_t fp4_w4a16_linear(const void* x, int64_t M, int64_t K, int had_blo
  *   codes_out, scales_out   canonical layout, as fp4_quantize_weights writes them (scales_out equals its output bit for
  *                bit: the sweep changes codes only); tensor_scale as there (NVFP4)
  *   workspace    fp4_workspace_bytes(FP4MR_OP_GPTQ, N, 0, K, fmt, flags) bytes
- *   flags        FP4MR_SCALE_MSE, FP4MR_SCALE_MSE | FP4MR_SCALE_FIT_TENSOR (NVFP4) or FP4MR_SCALE_ROUND43 (MXFP4), all
- *                optional: how the fixed grid is found; anything else: FP4MR_ERR_FMT
+ *   flags        FP4MR_SCALE_MSE, FP4MR_SCALE_MSE | FP4MR_SCALE_FIT_TENSOR (NVFP4), FP4MR_SCALE_ROUND43 or
+ *                FP4MR_SCALE_FIT_RANGE (MXFP4; tensor_scale then receives the FP4MR_FIT_RANGE_FLOATS floats and the sweep
+ *                takes each group's scale from its 256 scale values), all optional: how the fixed grid is found;
+ *                anything else: FP4MR_ERR_FMT
  * Per column j (visiting order), for every row:  q = E2M1(w_j / s),  e = (w_j - q s) / U[j,j],  w_k -= e U[j,k] (k > j),
  * in fp32; s is the fixed scale of the group the column belongs to in the ORIGINAL order.
  */

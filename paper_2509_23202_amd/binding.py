@@ -217,6 +217,8 @@ def fp4_gptq_quantize_weights(w, had_block: int, fmt: int, hinv_u, perm=None, *,
     codes = torch.empty(cb, dtype=torch.uint8, device=w.device)
     scales = torch.empty(sb, dtype=torch.uint8, device=w.device)
     ts = torch.empty(1, dtype=torch.float32, device=w.device) if fmt == NVFP4 else None
+    if flags & SCALE_FIT_RANGE:
+        ts = torch.empty(FIT_RANGE_FLOATS, dtype=torch.float32, device=w.device)
     need = workspace_bytes(OP_GPTQ, N, 0, K, fmt, flags)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=w.device)

@@ -247,7 +247,7 @@ fp4mr_status_t fp4_gptq_quantize_weights(const void* w, int64_t N, int64_t K, in
                                          void* stream)
 {
     if (fmt != FP4MR_MXFP4 && fmt != FP4MR_NVFP4) return FP4MR_ERR_FMT;
-    if (flags & ~(uint32_t)(FP4MR_SCALE_MSE | FP4MR_SCALE_ROUND43 | FP4MR_SCALE_FIT_TENSOR)) return FP4MR_ERR_FMT;
+    if (flags & ~(uint32_t)(FP4MR_SCALE_MSE | FP4MR_SCALE_ROUND43 | FP4MR_SCALE_FIT_TENSOR | FP4MR_SCALE_FIT_RANGE)) return FP4MR_ERR_FMT;
     if (!hinv_u) return FP4MR_ERR_NULL;
     if (N > (1 << 24) || K <= 0 || K % 64 != 0 || K > 24576) return FP4MR_ERR_SHAPE;
     if (!aligned16(hinv_u) || (perm && !aligned16(perm))) return FP4MR_ERR_ALIGN;
@@ -261,6 +261,7 @@ fp4mr_status_t fp4_gptq_quantize_weights(const void* w, int64_t N, int64_t K, in
     // 2. the sweep
     const hipError_t e = launch_gptq_sweep(w, N, K, had_block, (int)fmt, hinv_u, reinterpret_cast<const int*>(perm), scales_out,
                                            fmt == FP4MR_NVFP4 ? tensor_scale : nullptr,
+                                           (flags & FP4MR_SCALE_FIT_RANGE) ? tensor_scale + 2 : nullptr,  // the scale values just published
                                            (flags & FP4MR_SCALE_ROUND43) ? 4.0f / 3.0f : 1.0f, codes_out,
                                            static_cast<char*>(workspace) + qws, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;

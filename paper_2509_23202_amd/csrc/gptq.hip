@@ -33,6 +33,7 @@ struct GptqArgs {
     float* err;             // [N,kOuter] scratch: the errors of the current outer block
     const uint8_t* scales;  // [N,K/G] canonical
     const float* s_T;       // NVFP4 tensor scale (device), else null
+    const float* table;     // 256 scale values indexed by the scale byte (fitted scale range), else null
     uint8_t* codes;         // [N,K/2] canonical
     int N, K, b, G;
     float c_hi, c_lo;       // 1/sqrt(b) in two floats
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(64) void gptq_outer_kernel(GptqArgs a, int o, int o
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int j = part * 16 + i;
-            const float sv = decode_scale<FMT>(sbyte[i], s_T, a.factor);
+            const float sv = a.table ? a.table[sbyte[i]] : decode_scale<FMT>(sbyte[i], s_T, a.factor);
             Sc[j * 16 + row] = v2f_t{sv, sv > 0.0f ? 1.0f / sv : 0.0f};
         }
         __syncthreads();  // the scale of a column is read by every lane of its row's quad
@@ -423,7 +424,7 @@ hipError_t launch_gptq_rotate_rows(const void* x, int64_t T, int64_t K, int b, f
 }
 
 hipError_t launch_gptq_sweep(const void* w, int64_t N, int64_t K, int b, int fmt, const float* U, const int* perm,
-                             const void* scales, const float* s_T, float factor, void* codes, void* workspace, hipStream_t st)
+                             const void* scales, const float* s_T, const float* table, float factor, void* codes, void* workspace, hipStream_t st)
 {
     GptqArgs a{};
     a.w = static_cast<const uint16_t*>(w);
@@ -439,6 +440,7 @@ hipError_t launch_gptq_sweep(const void* w, int64_t N, int64_t K, int b, int fmt
     a.iperm = reinterpret_cast<int*>(ws);
     a.scales = static_cast<const uint8_t*>(scales);
     a.s_T = s_T;
+    a.table = table;
     a.codes = static_cast<uint8_t*>(codes);
     a.N = (int)N;
     a.K = (int)K;

@@ -78,7 +78,8 @@ hipError_t launch_fused_decode(const void* x, int64_t M, int64_t K, int b, const
 // workspace of gptq_workspace_bytes(N, K) bytes; K % 64 == 0, K <= 24576
 size_t gptq_workspace_bytes(int64_t N, int64_t K);
 hipError_t launch_gptq_sweep(const void* w, int64_t N, int64_t K, int b, int fmt, const float* U, const int* perm,
-                             const void* scales, const float* s_T, float factor, void* codes, void* workspace, hipStream_t st);
+                             const void* scales, const float* s_T, const float* table, float factor, void* codes, void* workspace,
+                             hipStream_t st);
 
 // Hessian [K,K] fp32 -> static activation order and the upper-triangular U with U^T U = (H[perm][:,perm] + damp mean(diag) I)^-1
 size_t gptq_prepare_workspace_bytes(int64_t K);

@@ -124,6 +124,36 @@ def test_sweep_matches_the_oracle_on_synthetic_hessians(fp4, oracle, gptq, fmt, 
     assert e_got < 0.8 * e_rtn
 
 
+def test_gptq_on_the_fitted_scale_range(fp4, oracle, gptq):
+    """MR-GPTQ with the scale byte fitted to the tensor's range as the fixed grid (appendix on MXFP scale fitting, table:
+    MR-GPTQ on MXFP4-dagger): the grid is the library's own (bytes and the 256 scale values it publishes; its parity
+    with the oracle's fit is tested with the quantizer), the sweep is compared with the oracle's sweep on that grid."""
+    import torch
+    b, N, K, T = 32, 100, 512, 1024
+    r = inputs.RECIPES[6]
+    wb, xb = r.w(N, K, salt=60), r.x(T, K, salt=61)
+    X = oracle.rotate(xb, b).astype(np.float64)
+    H = X.T @ X
+    perm = gptq.act_order(H).astype(np.int32)
+    U = gptq.inverse_factor(H, perm, damp=1e-2).astype(np.float32)
+    y = oracle.rotate(wb, b)
+    say("gptq on the fitted scale range")
+    c, s, ts = fp4.fp4_gptq_quantize_weights(to_dev_bf16(wb), b, MX, to_dev(U), to_dev(perm), flags=fp4.SCALE_FIT_RANGE)
+    c0, s0, ts0 = fp4.fp4_quantize_weights(to_dev_bf16(wb), b, MX, flags=fp4.SCALE_FIT_RANGE)
+    torch.cuda.synchronize()
+    assert torch.equal(s, s0) and torch.equal(ts, ts0)          # the grid is the round-to-nearest call's, bit for bit
+    got_c, q, table = np_(c).reshape(N, -1), np_(s).reshape(N, -1), np_(ts)[2:258].astype(np.float64)
+    want, _ = gptq.sweep(y, q, MX, None, U, perm, table=table)
+    diff = unpack(got_c) != unpack(want)
+    e_got = gptq.layer_error(y, got_c, q, MX, None, H, table=table)
+    e_ref = gptq.layer_error(y, want, q, MX, None, H, table=table)
+    e_rtn = gptq.layer_error(y, np_(c0).reshape(N, -1), q, MX, None, H, table=table)
+    say(f"   codes differing from the oracle: {diff.mean():.2e}; layer error {e_got:.6e} vs oracle {e_ref:.6e} (round-to-nearest {e_rtn:.4e})")
+    assert diff.mean() <= 1e-3
+    assert abs(e_got - e_ref) <= 1e-3 * e_ref
+    assert e_got < 0.8 * e_rtn
+
+
 def test_gptq_argument_validation(fp4):
     import torch
     w = torch.zeros((16, 128), dtype=torch.bfloat16, device="cuda")
