@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(DqArgs a)
             p = *reinterpret_cast<const uint32_t*>(a.codes + gemm_codes_offset(row, k, KC));
             sb = (G == 32) ? a.scales[gemm_mx_scale_offset(row, k >> 5, KS)] : a.scales[gemm_nv_scale_offset(row, k >> 4, KC)];
         } else {
-            p = *reinterpret_cast<const uint32_t*>(a.codes + (e0 >> 1));
+            p = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(a.codes + (e0 >> 1)));  // read once
             sb = a.scales[e0 / G];
         }
         float s;
@@ -61,13 +61,14 @@ __global__ __launch_bounds__(256) void dequantize_kernel(DqArgs a)
             if constexpr (MODE == 2) v[j] *= s_T;
         }
         if constexpr (OUT_F32) {
-            float* o = static_cast<float*>(a.out) + e0;
-            *reinterpret_cast<float4*>(o) = make_float4(v[0], v[1], v[2], v[3]);
-            *reinterpret_cast<float4*>(o + 4) = make_float4(v[4], v[5], v[6], v[7]);
+            // written once, never read here: streaming stores
+            v4f* o = reinterpret_cast<v4f*>(static_cast<float*>(a.out) + e0);
+            __builtin_nontemporal_store(v4f{v[0], v[1], v[2], v[3]}, o);
+            __builtin_nontemporal_store(v4f{v[4], v[5], v[6], v[7]}, o + 1);
         } else {
             typedef __bf16 v8b __attribute__((ext_vector_type(8)));
             const v8b o = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3], (__bf16)v[4], (__bf16)v[5], (__bf16)v[6], (__bf16)v[7]};
-            *reinterpret_cast<v8b*>(static_cast<__bf16*>(a.out) + e0) = o;
+            __builtin_nontemporal_store(__builtin_bit_cast(v4i, o), reinterpret_cast<v4i*>(static_cast<__bf16*>(a.out) + e0));
         }
     }
 }
