@@ -76,7 +76,8 @@ enum {
 };
 
 /* operation selector for fp4_workspace_bytes */
-enum { FP4MR_OP_ROTATE_QUANTIZE = 0, FP4MR_OP_QUANTIZE_WEIGHTS = 1, FP4MR_OP_GEMM = 2, FP4MR_OP_GPTQ = 3, FP4MR_OP_GPTQ_PREPARE = 4, FP4MR_OP_GPTQ_HESSIAN = 5 };
+enum { FP4MR_OP_ROTATE_QUANTIZE = 0, FP4MR_OP_QUANTIZE_WEIGHTS = 1, FP4MR_OP_GEMM = 2, FP4MR_OP_GPTQ = 3, FP4MR_OP_GPTQ_PREPARE = 4, FP4MR_OP_GPTQ_HESSIAN = 5,
+       FP4MR_OP_GEMM_SPLIT_K = 6 /* fp4_gemm with room for split-K partials: see fp4_gemm's workspace */ };
 
 /*
  * Online rotation + quantization of activations: codes, scales = Q(X H_b)   (Section 4.2 item 1: rotation
@@ -196,6 +197,11 @@ fp4mr_status_t fp4_quantize_weights(const void* w, int64_t N, int64_t K, int had
  *                row-major layout (they are re-tiled first), and, for NVFP4 with M > 64, 2 bytes per element of the
  *                activation operand (its exact fp16 values code * s_G are written once, so that the product kernel
  *                converts only W).  May be NULL when that size is 0 (MXFP4 with both operands in GEMM layout).
+ *                Optional: with at least fp4_workspace_bytes(FP4MR_OP_GEMM_SPLIT_K, ...) bytes (the same plus room for
+ *                fp32 partial results; equal to the former where the shape has nothing to gain) a product with few
+ *                output tiles and a long K -- 65 to a few hundred tokens against a narrow layer -- is split along K
+ *                over otherwise idle compute units and the partial results are added in a fixed order (deterministic;
+ *                the fp32 sums are grouped per split, so the result can differ from the unsplit one in its last bits).
  */
 fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* a_tensor_scale,
                         const void* w_codes, const void* w_scales, const float* w_tensor_scale,

@@ -34,7 +34,7 @@ FIT_RANGE_FLOATS = 258
 A_SCALE43 = 1 << 8
 W_SCALE43 = 1 << 9
 OPT_GEMM_VARIANT, OPT_GEMM_GRID, OPT_SW_CODEC = 0, 1, 2
-OP_ROTATE_QUANTIZE, OP_QUANTIZE_WEIGHTS, OP_GEMM, OP_GPTQ, OP_GPTQ_PREPARE, OP_GPTQ_HESSIAN = 0, 1, 2, 3, 4, 5
+OP_ROTATE_QUANTIZE, OP_QUANTIZE_WEIGHTS, OP_GEMM, OP_GPTQ, OP_GPTQ_PREPARE, OP_GPTQ_HESSIAN, OP_GEMM_SPLIT_K = 0, 1, 2, 3, 4, 5, 6
 
 _p, _i64, _i32, _u32, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32, ctypes.c_size_t
 _quant_sig = [_p, _i64, _i64, _i32, _i32, _p, _p, _p, _p, _sz, _u32, _p]
@@ -232,7 +232,7 @@ def fp4_gemm(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scal
     """out[M,N] = Ahat @ What^T (bf16, or fp32 with OUT_F32).  Operand layouts per A_LAYOUT_GEMM / W_LAYOUT_GEMM."""
     if out is None:
         out = torch.empty((M, N), dtype=torch.float32 if flags & OUT_F32 else torch.bfloat16, device=a_codes.device)
-    need = workspace_bytes(OP_GEMM, M, N, K, fmt, flags)
+    need = workspace_bytes(OP_GEMM_SPLIT_K, M, N, K, fmt, flags)   # (what the call needs plus optional split-K room)
     if need and workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=a_codes.device)
     wsz = 0 if workspace is None else workspace.numel()

@@ -232,12 +232,18 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
     // where its per-token-block re-reads of the activations from L2 cost more than the 64 x 256 tile kernel does
     // (M = 64, N = 28672, K = 4096: 29.6 us against 13.7 us).
     const bool wide_mx = fmt == FP4MR_MXFP4 && M > 16 && N >= 16384;
+    // Optional split-K room behind what the call needs (FP4MR_OP_GEMM_SPLIT_K): used when the caller passed that much
+    void* partial = nullptr;
+    if (M > 64 && variant == 0) {
+        const size_t extra = fmt == FP4MR_MXFP4 ? gemm_mx_split_k_bytes(M, N, K) : nv16_split_k_bytes(M, N, K);
+        if (extra && workspace && aligned16(workspace) && workspace_bytes >= align256(need) + extra) partial = static_cast<char*>(workspace) + align256(need);
+    }
     if (M <= 64 && variant == 0 && !wide_mx)
         e = launch_gemm_skinny(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M, N, K, (int)fmt, out, out_f32, alpha, st);
     else if (fmt == FP4MR_MXFP4)
-        e = launch_gemm_mxfp4(a_codes, a_scales, w_codes, w_scales, M, N, K, out, out_f32, variant, alpha, st);
+        e = launch_gemm_mxfp4(a_codes, a_scales, w_codes, w_scales, M, N, K, out, out_f32, variant, alpha, partial, st);
     else
-        e = launch_gemm_nvfp4(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M, N, K, out, out_f32, variant, ws, st);
+        e = launch_gemm_nvfp4(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M, N, K, out, out_f32, variant, ws, partial, st);
     return e == hipSuccess ? FP4MR_OK : FP4MR_ERR_DEVICE;
 }
 
@@ -325,13 +331,18 @@ size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t 
     if (op == FP4MR_OP_GPTQ_HESSIAN) return (M > 0 && K > 0) ? align256((size_t)M * K * 4) : 0;
     if (op == FP4MR_OP_GPTQ_PREPARE) return K > 0 ? gptq_prepare_workspace_bytes(K) : 0;
     if (op == FP4MR_OP_GPTQ) return (M > 0 && K > 0) ? align256(quant_workspace(fmt, flags)) + gptq_workspace_bytes(M, K) : 0;
-    if (op == FP4MR_OP_GEMM) {
+    if (op == FP4MR_OP_GEMM || op == FP4MR_OP_GEMM_SPLIT_K) {
         if (M <= 0 || N <= 0 || K <= 0 || K % 128 != 0) return 0;
         size_t n = 0;
         if (!(flags & FP4MR_A_LAYOUT_GEMM)) n += repack_bytes(M, K, fmt);
         if (!(flags & FP4MR_W_LAYOUT_GEMM)) n += repack_bytes(N, K, fmt);
         // NVFP4 with more than 64 tokens: the activations are dequantized once to fp16 (2 bytes per element)
         if (fmt == FP4MR_NVFP4 && M > 64) n += align256(nv16_workspace_bytes(M, K));
+        // what fp4_gemm needs, plus -- optional -- the fp32 partials of a split-K run where the shape has one
+        if (op == FP4MR_OP_GEMM_SPLIT_K && M > 64) {
+            const size_t extra = fmt == FP4MR_MXFP4 ? gemm_mx_split_k_bytes(M, N, K) : nv16_split_k_bytes(M, N, K);
+            if (extra) n = align256(n) + extra;
+        }
         return n;
     }
     return 0;

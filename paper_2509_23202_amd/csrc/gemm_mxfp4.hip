@@ -37,6 +37,7 @@ struct GemmArgs {
     int64_t M, N, K;
     int tiles_m, tiles_n;
     float alpha;  // factor on the result: powers of 4/3 for operands whose scales carry the tensor-level 4/3, else 1
+    int split_steps;  // split-K launches: K-steps per split (a multiple of 8); blockIdx.y is the split, out the fp32 partials
 };
 
 template <int N>
@@ -95,7 +96,7 @@ __device__ __forceinline__ void remap_block(int bid, int nblocks, int tiles_m, i
 template <int BM, int BN, int WM, int WN, int STAGES>
 constexpr int kWgsPerCu = ((BM / WM) * (BN / WN) == 4 && STAGES == 3) ? 2 : 1;
 
-template <int BM, int BN, int WM, int WN, int STAGES, bool OUT_F32, int RD = 2, bool PERSIST = false>
+template <int BM, int BN, int WM, int WN, int STAGES, bool OUT_F32, int RD = 2, bool PERSIST = false, bool SPLITK = false>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) __attribute__((amdgpu_waves_per_eu(kWgsPerCu<BM, BN, WM, WN, STAGES>)))
 void gemm_mx_kernel(GemmArgs g)
 {
@@ -120,9 +121,14 @@ void gemm_mx_kernel(GemmArgs g)
     const int ntiles = g.tiles_m * g.tiles_n;
     int tile = blockIdx.x;
 
-    const int64_t KC = g.K >> 7;            // K-steps
-    const int64_t KS = (g.K + 511) >> 9;    // scale super-steps
-    const int KT = (int)KC;
+    const int64_t KC = g.K >> 7;            // K-steps (of a row-block in memory)
+    const int64_t KS = (g.K + 511) >> 9;    // scale super-steps (likewise)
+    // SPLITK: this workgroup multiplies K-steps kt0 .. kt0 + KT - 1 only (kt0 a multiple of 8: whole scale batches) and
+    // writes its fp32 partial tile to slice blockIdx.y of the output, which a reduction kernel adds up in split order
+    static_assert(!SPLITK || (OUT_F32 && !PERSIST), "split-K workgroups write fp32 partials, one tile each");
+    const int kt0 = SPLITK ? (int)blockIdx.y * g.split_steps : 0;
+    const int KT = SPLITK ? min(g.split_steps, (int)KC - kt0) : (int)KC;
+    const int KS_rem = (int)KS - (kt0 >> 2);  // scale blocks from kt0 to the end of K
 
     // Operands are addressed through buffer resources: one VGPR (16 * lane) is the only per-lane address and every
     // fragment's position is a scalar offset.  Row-blocks past the end of an operand (last tile) are clamped to its
@@ -139,10 +145,11 @@ void gemm_mx_kernel(GemmArgs g)
     auto set_tile = [&](int t) {
         remap_block(t, ntiles, g.tiles_m, g.tiles_n, tm, tn);
         const int a_rb0 = min(tm * FX, a_rbs - 1), w_rb0 = min(tn * FW, w_rbs - 1);
-        rs_ac = make_rsrc(g.a_codes + (int64_t)a_rb0 * KC * 1024, (int64_t)(a_rbs - a_rb0) * KC * 1024);
-        rs_wc = make_rsrc(g.w_codes + (int64_t)w_rb0 * KC * 1024, (int64_t)(w_rbs - w_rb0) * KC * 1024);
-        rs_as = make_rsrc(g.a_scales + (int64_t)a_rb0 * KS * 256, (int64_t)(a_rbs - a_rb0) * KS * 256);
-        rs_ws = make_rsrc(g.w_scales + (int64_t)w_rb0 * KS * 256, (int64_t)(w_rbs - w_rb0) * KS * 256);
+        const int64_t c0 = (int64_t)kt0 * 1024, s0 = (int64_t)(kt0 >> 2) * 256;  // (0 unless SPLITK)
+        rs_ac = make_rsrc(g.a_codes + (int64_t)a_rb0 * KC * 1024 + c0, (int64_t)(a_rbs - a_rb0) * KC * 1024 - c0);
+        rs_wc = make_rsrc(g.w_codes + (int64_t)w_rb0 * KC * 1024 + c0, (int64_t)(w_rbs - w_rb0) * KC * 1024 - c0);
+        rs_as = make_rsrc(g.a_scales + (int64_t)a_rb0 * KS * 256 + s0, (int64_t)(a_rbs - a_rb0) * KS * 256 - s0);
+        rs_ws = make_rsrc(g.w_scales + (int64_t)w_rb0 * KS * 256 + s0, (int64_t)(w_rbs - w_rb0) * KS * 256 - s0);
         a_rb_last = a_rbs - 1 - a_rb0;
         w_rb_last = w_rbs - 1 - w_rb0;
     };
@@ -190,7 +197,7 @@ void gemm_mx_kernel(GemmArgs g)
         if constexpr (SC8) {
             // ss = the batch: 4-step blocks 2 * ss and 2 * ss + 1 (past the end: the last block again; what lies behind it
             // in the 512 bytes is never used, and reads beyond the operand return zeros)
-            const int blk = min(2 * ss, (int)KS - 1);
+            const int blk = min(2 * ss, KS_rem - 1);
             const int p = min(wave + i * NW, XP + WP - 1);
             const uint32_t half = (uint32_t)lane >> 5, col = ((uint32_t)lane & 31u) * 16u;
             if ((XP % NW == 0) ? (i < XP / NW) : (p < XP)) {
@@ -203,7 +210,7 @@ void gemm_mx_kernel(GemmArgs g)
             return;
         }
         char* base = scale_ring;
-        ss = ss < (int)KS ? ss : (int)KS - 1;  // the batch past the end re-reads the last one
+        ss = ss < KS_rem ? ss : KS_rem - 1;  // the batch past the end re-reads the last one
         const int f = min(wave + i * NW, F - 1);
         if (is_x(f, i)) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_as, (lds_void*)(base + f * 256), 4, lane4, min(f, a_rb_last) * ks_bytes + ss * 256, 0, 0);
         else __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_ws, (lds_void*)(base + f * 256), 4, lane4, min(f - FX, w_rb_last) * ks_bytes + ss * 256, 0, 0);
@@ -438,7 +445,7 @@ void gemm_mx_kernel(GemmArgs g)
                     if (n >= g.N) continue;
                     const v4f v = acc[i][j];
                     if constexpr (OUT_F32) {
-                        float* o = static_cast<float*>(g.out) + m * g.N + n;
+                        float* o = static_cast<float*>(g.out) + (SPLITK ? (int64_t)blockIdx.y * g.M * g.N : 0) + m * g.N + n;
                         if (n + 3 < g.N && (g.N & 3) == 0) {
                             *reinterpret_cast<float4*>(o) = make_float4(v[0], v[1], v[2], v[3]);
                         } else {
@@ -482,12 +489,55 @@ int compute_units()
     return cached[dev];
 }
 
+// out[i] = alpha * (partial[0][i] + partial[1][i] + ...), the splits added in their order (deterministic), as bf16 or fp32
+template <bool OUT_F32>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int splits, int64_t mn, float alpha, void* out)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < mn; i += (int64_t)gridDim.x * 256) {
+        float s = partial[i];
+        for (int p = 1; p < splits; ++p) s += partial[(int64_t)p * mn + i];
+        s *= alpha;
+        if constexpr (OUT_F32) static_cast<float*>(out)[i] = s;
+        else static_cast<__bf16*>(out)[i] = (__bf16)s;
+    }
+}
+
+// the tile shapes that have a split-K instantiation (the ones the cost model picks for shapes with few tiles)
+template <int BM, int BN, int WM, int RD, bool PERSIST>
+constexpr bool kHasSplitK = !PERSIST && ((BM == 128 && BN == 128) || (BM == 256 && BN == 128 && WM == 128 && RD == 2) ||
+                                         (BM == 256 && BN == 256 && WM == 64 && RD == 3));
+
+// splits > 1: every tile is computed by `splits` workgroups, split y taking K-steps y * split_steps .. and writing its
+// fp32 partial tile to slice y of `partial`; the caller then runs splitk_reduce_kernel
 template <int BM, int BN, int WM, int WN, int STAGES, int RD = 2, bool PERSIST = false>
-hipError_t launch_variant(const GemmArgs& g0, bool out_f32, hipStream_t st)
+hipError_t launch_variant(const GemmArgs& g0, bool out_f32, hipStream_t st, int splits = 1, int split_steps = 0, float* partial = nullptr)
 {
     GemmArgs g = g0;
     g.tiles_m = (int)((g.M + BM - 1) / BM);
     g.tiles_n = (int)((g.N + BN - 1) / BN);
+    if (splits > 1) {
+        if constexpr (kHasSplitK<BM, BN, WM, RD, PERSIST>) {
+            constexpr int threads_s = (BM / WM) * (BN / WN) * 64;
+            constexpr size_t lds_s = (size_t)STAGES * (BM + BN) / 16 * 1024 +
+                                     (STAGES >= 4 ? (size_t)((BM / 16 + 1) / 2 + (BN / 16 + 1) / 2) * 1024 : (size_t)(BM + BN) / 16 * 256);
+            g.out = partial;
+            g.alpha = 1.0f;
+            g.split_steps = split_steps;
+            static LdsAttrOnce raised_s;
+            auto k = gemm_mx_kernel<BM, BN, WM, WN, STAGES, true, RD, false, true>;
+            hipError_t es;
+            if ((es = raised_s.ensure(reinterpret_cast<const void*>(k), (int)lds_s)) != hipSuccess) return es;
+            hipLaunchKernelGGL(k, dim3((unsigned)(g.tiles_m * g.tiles_n), (unsigned)splits), dim3(threads_s), lds_s, st, g);
+            if ((es = hipGetLastError()) != hipSuccess) return es;
+            const int64_t mn = g.M * g.N;
+            const unsigned rblocks = (unsigned)std::min<int64_t>((mn + 255) / 256, 256 * 16);
+            if (out_f32) hipLaunchKernelGGL(splitk_reduce_kernel<true>, dim3(rblocks), dim3(256), 0, st, partial, splits, mn, g0.alpha, g0.out);
+            else hipLaunchKernelGGL(splitk_reduce_kernel<false>, dim3(rblocks), dim3(256), 0, st, partial, splits, mn, g0.alpha, g0.out);
+            return hipGetLastError();
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
     constexpr int threads = (BM / WM) * (BN / WN) * 64;
     // operand ring + scale buffer (four and more stages: 1 KB per pair of row-blocks; three stages: 256 B per row-block)
     constexpr size_t lds = (size_t)STAGES * (BM + BN) / 16 * 1024 +
@@ -515,11 +565,100 @@ hipError_t launch_variant(const GemmArgs& g0, bool out_f32, hipStream_t st)
     return hipGetLastError();
 }
 
+// tile configuration by shape (the numbers of launch_gemm_mxfp4's switch)
+int pick_variant_mx(int64_t M, int64_t N, int64_t K)
+{
+    int variant;
+    if (M <= 16) variant = 4;
+    else if (M <= 64) variant = 3;
+    else {
+        // Pick the tile by a small cost model: rounds of workgroups over the chip times (fixed cost per tile + K-steps
+        // times the measured step time of that tile).  256x256 and 256x128 hold one workgroup per compute unit,
+        // 128x128 two (and runs faster still when a compute unit has a single one).
+        const int cus = compute_units();
+        const double kt = (double)(K >> 7);
+        auto tiles = [&](int bm, int bn) { return (double)((M + bm - 1) / bm) * (double)((N + bn - 1) / bn); };
+        auto rounds = [](double t, double slots) { return t <= slots ? 1.0 : ceil(t / slots); };
+        const double t10 = rounds(tiles(256, 256), cus) * (9.5 + kt * 0.74);
+        const double t5 = rounds(tiles(256, 128), cus) * (9.0 + kt * 0.37);
+        const double n2 = tiles(128, 128);
+        const double t2 = rounds(n2, 2.0 * cus) * (8.0 + kt * (n2 <= cus ? 0.15 : 0.40));
+        variant = 10;
+        double best = t10;
+        if (t5 < best * 0.97) { variant = 5; best = t5; }
+        if (t2 < best * 0.97) { variant = 2; best = t2; }
+        // 256x192: for widths where it tiles into fewer rounds than the square tile (N = 6144 on 256 compute units:
+        // 512 tiles, two full rounds of three quarters the work each, against 384 tiles = one and a half rounds)
+        const double t13 = rounds(tiles(256, 192), cus) * (10.0 + kt * 0.56);
+        if (t13 < best * 0.97) { variant = 13; best = t13; }
+        // more 256x256 tiles than compute units: persistent workgroups, which prefetch the next tile's first stages
+        // and let the output stores drain under its first K-steps (1.5-6% on such shapes, never slower)
+        if (variant == 10 && tiles(256, 256) > cus) variant = 11;
+        // K around 1024: a tile is 8 K-steps, about as long as its own start-up and stores.  128x256 tiles with two
+        // workgroups per compute unit overlap one workgroup's epilogue with the other's main loop: 10-13 % faster
+        // there, level at K = 1536-2048, slower beyond (three stages, one and a half times the operand traffic) and
+        // below (K = 512: the persistent 256x256 workgroups win).
+        if ((variant == 10 || variant == 11) && K >= 768 && K <= 1280) variant = tiles(128, 256) > 2.0 * cus ? 16 : 15;
+    }
+    return variant;
+}
+
+// Split-K plan for a product the cost model gives to 128x128, 256x128 or 256x256 tiles (more than 64 tokens).  With few
+// tiles and a long K -- 65 to a few hundred tokens against a narrow layer, the batched-decoding regime -- a handful of
+// compute units each stream a long K range alone and the launch is bound by the latency of their few loads in flight
+// (M = 128, N = 4096, K = 14336: 32 tiles, 42 us, 0.7 TB/s).  Every tile's K range can then be cut into up to eight
+// parts of at least 16 K-steps (whole scale batches of eight), each part one workgroup (17 us on that shape, reduction
+// included).  The number of parts minimises an estimate in microseconds, measured on such shapes:
+//     fixed cost of a tile + K-steps per part x step time + (split only) 3 for the reduction's launch
+//                                                          + splits x M x N x 8 bytes of partials written and read at 4 TB/s
+// and the product is split only for an estimated gain of at least 10 % (a tile of 32 K-steps is mostly fixed cost:
+// N = 4096, K = 4096, M = 128 measured 14.1 us split against 13.8).  splits == 1: leave the product alone.
+void plan_split_k_mx(int64_t M, int64_t N, int64_t K, int variant, int* splits, int* steps)
+{
+    *splits = 1;
+    *steps = 0;
+    int bm, bn, per_cu;
+    double fixed, step_alone, step_shared;  // step time with at most one workgroup per compute unit / with more
+    if (variant == 2) { bm = 128; bn = 128; per_cu = 2; fixed = 8.0; step_alone = 0.30; step_shared = 0.40; }
+    else if (variant == 5) { bm = 256; bn = 128; per_cu = 1; fixed = 9.0; step_alone = step_shared = 0.45; }
+    else if (variant == 10) { bm = 256; bn = 256; per_cu = 1; fixed = 9.5; step_alone = step_shared = 0.74; }
+    else return;
+    const int cus = compute_units();
+    const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+    const int64_t slots = (int64_t)cus * per_cu;
+    const int kt = (int)(K >> 7);
+    const int64_t s_max = std::min<int64_t>(std::min<int64_t>(slots / tiles, kt / 16), 8);
+    const double t1 = fixed + kt * (tiles <= cus ? step_alone : step_shared);
+    double best = 0.9 * t1;
+    for (int64_t s = 2; s <= s_max; ++s) {
+        const int st = (int)(((kt + s - 1) / s + 7) / 8 * 8);
+        const int64_t n = (kt + st - 1) / st;  // parts of st steps that cover K (the last may be shorter)
+        if (n < 2) continue;
+        const double t = fixed + st * (tiles * n <= cus ? step_alone : step_shared) + 3.0 + (double)n * (double)M * (double)N * 8.0 / 4.0e6;
+        if (t < best) {
+            best = t;
+            *splits = (int)n;
+            *steps = st;
+        }
+    }
+}
+
 }  // namespace
 
+// bytes of fp32 partials a split-K run of this product needs (0: the product is not split)
+size_t gemm_mx_split_k_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (M <= 64) return 0;
+    int splits, steps;
+    plan_split_k_mx(M, N, K, pick_variant_mx(M, N, K), &splits, &steps);
+    return splits > 1 ? (size_t)splits * (size_t)M * (size_t)N * 4 : 0;
+}
+
 // variant: 0 = pick by shape; 1.. = force a tile configuration (used by the benchmark's sweep)
+// partial: room for gemm_mx_split_k_bytes(M, N, K) bytes, or null (then the product is never split)
 hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const void* w_codes, const void* w_scales,
-                             int64_t M, int64_t N, int64_t K, void* out, bool out_f32, int variant, float alpha, hipStream_t st)
+                             int64_t M, int64_t N, int64_t K, void* out, bool out_f32, int variant, float alpha, void* partial,
+                             hipStream_t st)
 {
     GemmArgs g{};
     g.alpha = alpha;
@@ -531,50 +670,23 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
     g.M = M;
     g.N = N;
     g.K = K;
+    int splits = 1, split_steps = 0;
     if (variant == 0) {
-        if (M <= 16) variant = 4;
-        else if (M <= 64) variant = 3;
-        else {
-            // Pick the tile by a small cost model: rounds of workgroups over the chip times (fixed cost per tile + K-steps
-            // times the measured step time of that tile).  256x256 and 256x128 hold one workgroup per compute unit,
-            // 128x128 two (and runs faster still when a compute unit has a single one).
-            const int cus = compute_units();
-            const double kt = (double)(K >> 7);
-            auto tiles = [&](int bm, int bn) { return (double)((M + bm - 1) / bm) * (double)((N + bn - 1) / bn); };
-            auto rounds = [](double t, double slots) { return t <= slots ? 1.0 : ceil(t / slots); };
-            const double t10 = rounds(tiles(256, 256), cus) * (9.5 + kt * 0.74);
-            const double t5 = rounds(tiles(256, 128), cus) * (9.0 + kt * 0.37);
-            const double n2 = tiles(128, 128);
-            const double t2 = rounds(n2, 2.0 * cus) * (8.0 + kt * (n2 <= cus ? 0.15 : 0.40));
-            variant = 10;
-            double best = t10;
-            if (t5 < best * 0.97) { variant = 5; best = t5; }
-            if (t2 < best * 0.97) { variant = 2; best = t2; }
-            // 256x192: for widths where it tiles into fewer rounds than the square tile (N = 6144 on 256 compute units:
-            // 512 tiles, two full rounds of three quarters the work each, against 384 tiles = one and a half rounds)
-            const double t13 = rounds(tiles(256, 192), cus) * (10.0 + kt * 0.56);
-            if (t13 < best * 0.97) { variant = 13; best = t13; }
-            // more 256x256 tiles than compute units: persistent workgroups, which prefetch the next tile's first stages
-            // and let the output stores drain under its first K-steps (1.5-6% on such shapes, never slower)
-            if (variant == 10 && tiles(256, 256) > cus) variant = 11;
-            // K around 1024: a tile is 8 K-steps, about as long as its own start-up and stores.  128x256 tiles with two
-            // workgroups per compute unit overlap one workgroup's epilogue with the other's main loop: 10-13 % faster
-            // there, level at K = 1536-2048, slower beyond (three stages, one and a half times the operand traffic) and
-            // below (K = 512: the persistent 256x256 workgroups win).
-            if ((variant == 10 || variant == 11) && K >= 768 && K <= 1280) variant = tiles(128, 256) > 2.0 * cus ? 16 : 15;
-        }
+        variant = pick_variant_mx(M, N, K);
+        if (partial && M > 64) plan_split_k_mx(M, N, K, variant, &splits, &split_steps);
     }
+    float* const pp = static_cast<float*>(partial);
     switch (variant) {
         case 1: return launch_variant<256, 256, 128, 128, 4>(g, out_f32, st);
-        case 2: return launch_variant<128, 128, 64, 64, 4>(g, out_f32, st);
+        case 2: return launch_variant<128, 128, 64, 64, 4>(g, out_f32, st, splits, split_steps, pp);
         case 3: return launch_variant<64, 256, 64, 64, 4>(g, out_f32, st);
         case 4: return launch_variant<16, 256, 16, 64, 4>(g, out_f32, st);
-        case 5: return launch_variant<256, 128, 128, 64, 4>(g, out_f32, st);
+        case 5: return launch_variant<256, 128, 128, 64, 4>(g, out_f32, st, splits, split_steps, pp);
         case 6: return launch_variant<256, 256, 128, 64, 4>(g, out_f32, st);
         case 7: return launch_variant<256, 256, 64, 128, 4>(g, out_f32, st);
         case 8: return launch_variant<256, 256, 128, 128, 4, 4>(g, out_f32, st);
         case 9: return launch_variant<256, 256, 128, 128, 4, 6>(g, out_f32, st);
-        case 10: return launch_variant<256, 256, 64, 128, 4, 3>(g, out_f32, st);
+        case 10: return launch_variant<256, 256, 64, 128, 4, 3>(g, out_f32, st, splits, split_steps, pp);
         case 11: return launch_variant<256, 256, 64, 128, 4, 3, true>(g, out_f32, st);
         case 12: return launch_variant<256, 128, 128, 64, 4, 2, true>(g, out_f32, st);
         case 13: return launch_variant<256, 192, 64, 96, 4, 2>(g, out_f32, st);

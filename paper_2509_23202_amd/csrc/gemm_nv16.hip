@@ -43,6 +43,7 @@ struct Nv16Args {
     int tiles_m;
     int n_first;   // first output column of this launch (a multiple of 256)
     int n_cols;    // number of output columns this launch covers (to the end of N when the tile grid is ragged)
+    int split_steps;  // split-K launches: K-steps of 64 per split (a multiple of 8); blockIdx.y is the split, out the fp32 partials
 };
 
 template <int N>
@@ -85,9 +86,12 @@ __global__ __launch_bounds__(256) void nv_x16_kernel(const uint8_t* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-template <int BN, bool OUT_F32, int STAGES = 3>
+// SPLITK: the workgroup multiplies K-steps blockIdx.y * split_steps .. only and writes its fp32 partial tile, without the
+// tensor scales, to slice blockIdx.y of the output; nv16_reduce_kernel adds the slices in split order.
+template <int BN, bool OUT_F32, int STAGES = 3, bool SPLITK = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void gemm_nv16_kernel(Nv16Args g)
 {
+    static_assert(!SPLITK || OUT_F32, "split-K workgroups write fp32 partials");
     constexpr int BM = 128, NW = 4;
     constexpr int WN = BN / NW;            // 64 or 32 columns per wave
     constexpr int TM = BM / 16, TN = WN / 16;
@@ -106,7 +110,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void g
     const int tm = blockIdx.x % g.tiles_m, tn = blockIdx.x / g.tiles_m;   // consecutive workgroups share a W column band
     const int64_t n_tile0 = (int64_t)g.n_first + (int64_t)tn * BN;
 
-    const int KH = (int)(g.K >> 6), KC = (int)(g.K >> 7);
+    const int KH_all = (int)(g.K >> 6), KC = (int)(g.K >> 7);   // K-steps of 64 / fragments of 128 per row-block in memory
+    const int kh0 = SPLITK ? (int)blockIdx.y * g.split_steps : 0;  // (even: a split starts on a fragment)
+    const int KH = SPLITK ? min(g.split_steps, KH_all - kh0) : KH_all;
     const int a_rbs = (int)((g.M + 15) / 16), w_rbs = (int)((g.N + 15) / 16);
     const int a_rb0 = min(tm * FX, a_rbs - 1), w_rb0 = min((int)(n_tile0 / 16), w_rbs - 1);
     const int a_rb_last = a_rbs - 1 - a_rb0, w_rb_last = w_rbs - 1 - w_rb0;
@@ -114,11 +120,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void g
         const uint32_t n = bytes > 0xffffffffll ? 0xffffffffu : (uint32_t)bytes;
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, (int)n, 0x00020000);
     };
-    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(g.x16 + (int64_t)a_rb0 * KH * 2048, (int64_t)(a_rbs - a_rb0) * KH * 2048);
-    const __amdgpu_buffer_rsrc_t rs_wc = make_rsrc(g.w_codes + (int64_t)w_rb0 * KC * 1024, (int64_t)(w_rbs - w_rb0) * KC * 1024);
-    const __amdgpu_buffer_rsrc_t rs_ws = make_rsrc(g.w_scales + (int64_t)w_rb0 * KC * 128, (int64_t)(w_rbs - w_rb0) * KC * 128);
+    const int64_t x0 = (int64_t)kh0 * 2048, c0 = (int64_t)(kh0 >> 1) * 1024, s0 = (int64_t)(kh0 >> 1) * 128;  // (0 unless SPLITK)
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(g.x16 + (int64_t)a_rb0 * KH_all * 2048 + x0, (int64_t)(a_rbs - a_rb0) * KH_all * 2048 - x0);
+    const __amdgpu_buffer_rsrc_t rs_wc = make_rsrc(g.w_codes + (int64_t)w_rb0 * KC * 1024 + c0, (int64_t)(w_rbs - w_rb0) * KC * 1024 - c0);
+    const __amdgpu_buffer_rsrc_t rs_ws = make_rsrc(g.w_scales + (int64_t)w_rb0 * KC * 128 + s0, (int64_t)(w_rbs - w_rb0) * KC * 128 - s0);
     const uint32_t lane16 = (uint32_t)lane * 16u;
-    const int x_rb_bytes = KH * 2048, wc_rb_bytes = KC * 1024, ws_rb_bytes = KC * 128;
+    const int x_rb_bytes = KH_all * 2048, wc_rb_bytes = KC * 1024, ws_rb_bytes = KC * 128;
 
     // Row-blocks past the end of an operand (last tile) are clamped to its last row-block: the duplicates only feed
     // outputs that are never stored.  A stage's copies are issued in three pieces (X, W codes, W scales) at three points of
@@ -263,7 +270,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void g
     wait_vmcnt<0>();   // (the repeated copies of the last steps: nothing may be in flight into LDS when the workgroup ends)
 
     // A lane owns out[m][n .. n+3] with m = m0 + 16 j + lane % 16, n = n0 + 16 i + 4 (lane / 16).
-    const float ts = (*g.a_ts) * (*g.w_ts);
+    const float ts = SPLITK ? 1.0f : (*g.a_ts) * (*g.w_ts);
     const int64_t n_lim = (int64_t)g.n_first + g.n_cols;
     const int64_t n_end = n_lim < g.N ? n_lim : g.N;
     const int64_t m_base = (int64_t)tm * BM + (lane & 15);
@@ -280,7 +287,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void g
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] *= ts;
             if constexpr (OUT_F32) {
-                float* o = static_cast<float*>(g.out) + m * g.N + n;
+                float* o = static_cast<float*>(g.out) + (SPLITK ? (int64_t)blockIdx.y * g.M * g.N : 0) + m * g.N + n;
                 if (n + 3 < n_end && (g.N & 3) == 0) {
                     *reinterpret_cast<float4*>(o) = make_float4(v[0], v[1], v[2], v[3]);
                 } else {
@@ -302,12 +309,70 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void g
     }
 }
 
+// out[i] = s_T(A) s_T(W) (partial[0][i] + partial[1][i] + ...), the splits added in their order, as bf16 or fp32
+template <bool OUT_F32>
+__global__ __launch_bounds__(256) void nv16_reduce_kernel(const float* __restrict__ partial, int splits, int64_t mn, const float* a_ts,
+                                                          const float* w_ts, void* out)
+{
+    const float ts = (*a_ts) * (*w_ts);
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < mn; i += (int64_t)gridDim.x * 256) {
+        float s = partial[i];
+        for (int p = 1; p < splits; ++p) s += partial[(int64_t)p * mn + i];
+        s *= ts;
+        if constexpr (OUT_F32) static_cast<float*>(out)[i] = s;
+        else static_cast<__bf16*>(out)[i] = (__bf16)s;
+    }
+}
+
+// Split-K plan (see the MXFP4 kernels' plan: few tiles and a long K leave the launch bound by the latency of a handful of
+// compute units' loads; here M = 128, N = 8192, K = 28672 is 32 tiles and 411 us, slower than a bf16 GEMM).  128 x 256
+// tiles, two workgroups per compute unit, K-steps of 64 at about 0.93 us each, at least 32 per part, at most eight parts.
+// The number of parts minimises the estimate (microseconds)
+//     10 + K-steps per part x 0.93 + (split only) 3 + splits x M x N x 8 bytes of partials at 4 TB/s
+// and the product is split only for an estimated gain of at least 10 %.
+void plan_split_k_nv16(int64_t M, int64_t N, int64_t K, int cus, int* splits, int* steps)
+{
+    *splits = 1;
+    *steps = 0;
+    const int64_t tiles = ((M + 127) / 128) * ((N + 255) / 256);
+    const int64_t slots = 2 * (int64_t)cus;
+    const int kh = (int)(K >> 6);
+    const int64_t s_max = std::min<int64_t>(std::min<int64_t>(slots / tiles, kh / 32), 8);
+    double best = 0.9 * (10.0 + kh * 0.93);
+    for (int64_t s = 2; s <= s_max; ++s) {
+        const int st = (int)(((kh + s - 1) / s + 7) / 8 * 8);
+        const int64_t n = (kh + st - 1) / st;
+        if (n < 2) continue;
+        const double t = 10.0 + st * 0.93 + 3.0 + (double)n * (double)M * (double)N * 8.0 / 4.0e6;
+        if (t < best) {
+            best = t;
+            *splits = (int)n;
+            *steps = st;
+        }
+    }
+}
+
+int device_cus()
+{
+    int cus = 256, dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    return cus;
+}
+
 template <int BN, int STAGES = 3>
-hipError_t launch_tiles(const Nv16Args& g, bool out_f32, hipStream_t st)
+hipError_t launch_tiles(const Nv16Args& g, bool out_f32, hipStream_t st, int splits = 1)
 {
     if (g.n_cols <= 0) return hipSuccess;
     constexpr size_t lds = STAGES * (size_t)(8 * 2048 + (BN / 16) * 512 + 4 * 256);
     const int tiles_n = (g.n_cols + BN - 1) / BN;
+    if (splits > 1) {
+        static LdsAttrOnce raised_s;
+        auto k = gemm_nv16_kernel<BN, true, STAGES, true>;
+        hipError_t es;
+        if ((es = raised_s.ensure(reinterpret_cast<const void*>(k), (int)lds)) != hipSuccess) return es;
+        hipLaunchKernelGGL(k, dim3((unsigned)(g.tiles_m * tiles_n), (unsigned)splits), dim3(256), lds, st, g);
+        return hipGetLastError();
+    }
     const dim3 grid((unsigned)(g.tiles_m * tiles_n));
     hipError_t e;
     static LdsAttrOnce raised[2];
@@ -330,9 +395,17 @@ size_t nv16_workspace_bytes(int64_t M, int64_t K)
     return (size_t)(round_up(M, 16) * K * 2);
 }
 
+// bytes of fp32 partials a split-K run of this product needs (0: the product is not split)
+size_t nv16_split_k_bytes(int64_t M, int64_t N, int64_t K)
+{
+    int splits, steps;
+    plan_split_k_nv16(M, N, K, device_cus(), &splits, &steps);
+    return splits > 1 ? (size_t)splits * (size_t)M * (size_t)N * 4 : 0;
+}
+
 hipError_t launch_gemm_nv16(const void* a_codes, const void* a_scales, const float* a_ts, const void* w_codes,
                             const void* w_scales, const float* w_ts, int64_t M, int64_t N, int64_t K, void* out,
-                            bool out_f32, void* workspace, hipStream_t st)
+                            bool out_f32, void* workspace, void* partial, hipStream_t st)
 {
     // 1. activations -> fp16 in operand order (workspace)
     const int64_t n_frags = round_up(M, 16) / 16 * (K / 128);
@@ -356,8 +429,24 @@ hipError_t launch_gemm_nv16(const void* a_codes, const void* a_scales, const flo
     g.N = N;
     g.K = K;
     g.tiles_m = (int)((M + 127) / 128);
-    int cus = 256, dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    const int cus = device_cus();
+    if (partial) {
+        // few tiles, long K: every tile's K range shared by several workgroups, partial results added by a second kernel
+        int splits, steps;
+        plan_split_k_nv16(M, N, K, cus, &splits, &steps);
+        if (splits > 1) {
+            g.out = partial;
+            g.n_first = 0;
+            g.n_cols = (int)N;
+            g.split_steps = steps;
+            if ((e = launch_tiles<256>(g, true, st, splits)) != hipSuccess) return e;
+            const int64_t mn = M * N;
+            const unsigned rblocks = (unsigned)std::min<int64_t>((mn + 255) / 256, 256 * 16);
+            if (out_f32) hipLaunchKernelGGL(nv16_reduce_kernel<true>, dim3(rblocks), dim3(256), 0, st, static_cast<const float*>(partial), splits, mn, a_ts, w_ts, out);
+            else hipLaunchKernelGGL(nv16_reduce_kernel<false>, dim3(rblocks), dim3(256), 0, st, static_cast<const float*>(partial), splits, mn, a_ts, w_ts, out);
+            return hipGetLastError();
+        }
+    }
     const int64_t slots = 2 * (int64_t)cus;
     const int64_t cols_w = (N + 255) / 256;                         // wide tile columns
     const int64_t tiles_w = cols_w * g.tiles_m;

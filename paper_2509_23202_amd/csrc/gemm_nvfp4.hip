@@ -236,11 +236,11 @@ hipError_t launch_variant(const NvGemmArgs& g0, bool out_f32, hipStream_t st)
 
 hipError_t launch_gemm_nvfp4(const void* a_codes, const void* a_scales, const float* a_ts, const void* w_codes,
                              const void* w_scales, const float* w_ts, int64_t M, int64_t N, int64_t K, void* out,
-                             bool out_f32, int variant, void* workspace, hipStream_t st)
+                             bool out_f32, int variant, void* workspace, void* partial, hipStream_t st)
 {
     // By default many-token products go to the kernel that takes its activations as fp16 (gemm_nv16.hip); the tile
     // kernels of this file, which dequantize both operands inside the product, remain as forced configurations.
-    if (variant == 0) return launch_gemm_nv16(a_codes, a_scales, a_ts, w_codes, w_scales, w_ts, M, N, K, out, out_f32, workspace, st);
+    if (variant == 0) return launch_gemm_nv16(a_codes, a_scales, a_ts, w_codes, w_scales, w_ts, M, N, K, out, out_f32, workspace, partial, st);
     NvGemmArgs g{};
     g.a_codes = static_cast<const uint8_t*>(a_codes);
     g.a_scales = static_cast<const uint8_t*>(a_scales);

@@ -50,19 +50,24 @@ hipError_t launch_repack_to_gemm(const void* codes, const void* scales, int64_t 
 // both operands in GEMM layout; alpha multiplies the result (1, or powers of 4/3 for operands quantized with the
 // rounded-exponent rule whose scale bytes leave that tensor-level factor out)
 hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const void* w_codes, const void* w_scales,
-                             int64_t M, int64_t N, int64_t K, void* out, bool out_f32, int variant, float alpha, hipStream_t st);
+                             int64_t M, int64_t N, int64_t K, void* out, bool out_f32, int variant, float alpha, void* partial,
+                             hipStream_t st);
+// fp32 partials of a split-K run (few tiles, long K: every tile's K range shared by several workgroups); 0 = not split
+size_t gemm_mx_split_k_bytes(int64_t M, int64_t N, int64_t K);
 
 // variant 0: the fp16-activation kernel below (needs its workspace); 1..3: the tile kernels that dequantize both operands
 hipError_t launch_gemm_nvfp4(const void* a_codes, const void* a_scales, const float* a_ts, const void* w_codes,
                              const void* w_scales, const float* w_ts, int64_t M, int64_t N, int64_t K, void* out,
-                             bool out_f32, int variant, void* workspace, hipStream_t st);
+                             bool out_f32, int variant, void* workspace, void* partial, hipStream_t st);
 
 // NVFP4 product for many tokens: the activations are dequantized once to fp16 into `workspace`
 // (nv16_workspace_bytes(M, K) bytes, 256-byte aligned), then multiplied against W dequantized on the fly
 size_t nv16_workspace_bytes(int64_t M, int64_t K);
 hipError_t launch_gemm_nv16(const void* a_codes, const void* a_scales, const float* a_ts, const void* w_codes,
                             const void* w_scales, const float* w_ts, int64_t M, int64_t N, int64_t K, void* out,
-                            bool out_f32, void* workspace, hipStream_t st);
+                            bool out_f32, void* workspace, void* partial, hipStream_t st);
+// fp32 partials of a split-K run of that product (`partial`, may be null: then it is never split); 0 = not split
+size_t nv16_split_k_bytes(int64_t M, int64_t N, int64_t K);
 
 // few-token (M <= 64) weight-streaming GEMM, both formats, operands in GEMM layout
 hipError_t launch_gemm_skinny(const void* a_codes, const void* a_scales, const float* a_ts, const void* w_codes,

@@ -343,6 +343,63 @@ def test_gemm_nvfp4_few_tokens_two_row_blocks_per_workgroup(fp4, oracle, M, N, K
     _gemm_case(fp4, oracle, NV, M, N, K, seed=4100 + N + K, out_f32=out_f32, layout_gemm=True)
 
 
+@pytest.mark.parametrize("M,N,K,out_f32", [(65, 400, 8192, True), (128, 1024, 14336, False), (200, 1000, 12416, False), (300, 272, 16512, True),
+                                           (512, 520, 9088, False)])
+def test_gemm_mxfp4_split_k(fp4, oracle, M, N, K, out_f32):
+    """More than 64 tokens against a narrow layer with a long K: with the optional workspace the tiles' K ranges are
+    shared by several workgroups (fp32 partials, added in split order).  Ragged M and N, K / 128 = 64, 71, 97, 112, 129
+    (a last split of one K-step; splits that end inside a scale batch of eight steps), both output types; the same call
+    with the minimum workspace runs unsplit and must meet the same bound."""
+    import torch
+    r = inputs.RECIPES[1]
+    xb, wb = r.x(M, K, salt=M + K), r.w(N, K, salt=M + K)
+    ya, yw = oracle.rotate(xb, 32), oracle.rotate(wb, 32)
+    ac, asc, _ = oracle.quantize(ya, MX)
+    wc, wsc, _ = oracle.quantize(yw, MX)
+    Y, S = oracle.matmul(oracle.dequantize(ac, asc, MX), oracle.dequantize(wc, wsc, MX))
+    qa = fp4.fp4_rotate_quantize(to_dev(ya), 1, MX, flags=fp4.LAYOUT_GEMM)
+    qw = fp4.fp4_quantize_weights(to_dev(yw), 1, MX, flags=fp4.LAYOUT_GEMM)
+    gfl = fp4.A_LAYOUT_GEMM | fp4.W_LAYOUT_GEMM | (fp4.OUT_F32 if out_f32 else 0)
+    full = fp4.workspace_bytes(fp4.OP_GEMM_SPLIT_K, M, N, K, MX, gfl)
+    assert fp4.workspace_bytes(fp4.OP_GEMM, M, N, K, MX, gfl) == 0 and full >= 2 * M * N * 4   # these shapes do split
+    say(f"gemm split-K M={M} N={N} K={K} out_f32={out_f32}: {full // (M * N * 4)} splits")
+    tol = 1e-3 * S + (0 if out_f32 else np.abs(Y) * 2.0 ** -8)
+    for name, ws in (("split", None), ("unsplit", torch.empty(16, dtype=torch.uint8, device="cuda"))):
+        out = fp4.fp4_gemm(qa[0], qa[1], None, qw[0], qw[1], None, M, N, K, MX, flags=gfl, workspace=ws)
+        torch.cuda.synchronize()
+        err = np.abs(np_(out.float()).astype(np.float64) - Y)
+        assert np.all(err <= tol), (name, float((err / (1e-3 * S + 1e-300)).max()))
+
+
+@pytest.mark.parametrize("M,N,K,out_f32", [(65, 400, 8192, True), (128, 1024, 14336, False), (200, 1000, 10368, False), (300, 528, 16512, True)])
+def test_gemm_nvfp4_split_k(fp4, oracle, M, N, K, out_f32):
+    """The NVFP4 many-token kernel with its K range shared by several workgroups (optional workspace): ragged M and N,
+    K / 64 = 128, 162, 224, 258 (a last split of two K-steps of 64, i.e. one fragment; ragged last splits),
+    both output types; the same call with the minimum workspace runs unsplit and must meet the same bound."""
+    import torch
+    r = inputs.RECIPES[4]
+    xb, wb = r.x(M, K, salt=M + K), r.w(N, K, salt=M + K)
+    ya, yw = oracle.rotate(xb, 16), oracle.rotate(wb, 16)
+    ac, asc, aT = oracle.quantize(ya, NV)
+    wc, wsc, wT = oracle.quantize(yw, NV)
+    Y, S = oracle.matmul(oracle.dequantize(ac, asc, NV, aT), oracle.dequantize(wc, wsc, NV, wT))
+    qa = fp4.fp4_rotate_quantize(to_dev(ya), 1, NV, flags=fp4.LAYOUT_GEMM)
+    qw = fp4.fp4_quantize_weights(to_dev(yw), 1, NV, flags=fp4.LAYOUT_GEMM)
+    assert np_(qa[2])[0] == aT and np_(qw[2])[0] == wT
+    gfl = fp4.A_LAYOUT_GEMM | fp4.W_LAYOUT_GEMM | (fp4.OUT_F32 if out_f32 else 0)
+    base = fp4.workspace_bytes(fp4.OP_GEMM, M, N, K, NV, gfl)
+    full = fp4.workspace_bytes(fp4.OP_GEMM_SPLIT_K, M, N, K, NV, gfl)
+    assert full - base >= 2 * M * N * 4                      # these shapes do split
+    say(f"nvfp4 gemm split-K M={M} N={N} K={K} out_f32={out_f32}: {(full - base) // (M * N * 4)} splits")
+    tol = 1e-3 * S + (0 if out_f32 else np.abs(Y) * 2.0 ** -8)
+    for name, nbytes in (("split", full), ("unsplit", base)):
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        out = fp4.fp4_gemm(qa[0], qa[1], qa[2], qw[0], qw[1], qw[2], M, N, K, NV, flags=gfl, workspace=ws)
+        torch.cuda.synchronize()
+        err = np.abs(np_(out.float()).astype(np.float64) - Y)
+        assert np.all(err <= tol), (name, float((err / (1e-3 * S + 1e-300)).max()))
+
+
 def test_gemm_mxfp4_exact_on_small_integers(fp4, oracle):
     """With scale bytes chosen freely and on-grid codes, 4*a*w are small integers: the fp32 accumulator must be
     EXACT (any summation order), and distinct scales per K-group pin the scale-to-group wiring."""
