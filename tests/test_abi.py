@@ -66,6 +66,14 @@ def test_sizes(lib):
     assert b.workspace_bytes(b.OP_ROTATE_QUANTIZE, 64, 0, 4096, b.MXFP4, b.SCALE_FIT_RANGE | b.STATIC_TENSOR_SCALE) == 0
     assert b.workspace_bytes(b.OP_GEMM, 64, 64, 4096, b.MXFP4, b.A_LAYOUT_GEMM | b.W_LAYOUT_GEMM) == 0
     assert b.workspace_bytes(b.OP_GEMM, 64, 64, 4096, b.MXFP4) > 0
+    # optional split-K room: the minimum plus whole fp32 copies of the output where few tiles meet a long K, nothing else
+    lay = b.A_LAYOUT_GEMM | b.W_LAYOUT_GEMM
+    for fmt in (b.MXFP4, b.NVFP4):
+        base = b.workspace_bytes(b.OP_GEMM, 128, 4096, 14336, fmt, lay)
+        extra = b.workspace_bytes(b.OP_GEMM_SPLIT_K, 128, 4096, 14336, fmt, lay) - base
+        assert extra > 0 and extra % (128 * 4096 * 4) <= 255 and 2 <= extra // (128 * 4096 * 4) <= 8
+        assert b.workspace_bytes(b.OP_GEMM_SPLIT_K, 4096, 4096, 4096, fmt, lay) == b.workspace_bytes(b.OP_GEMM, 4096, 4096, 4096, fmt, lay)
+        assert b.workspace_bytes(b.OP_GEMM_SPLIT_K, 16, 4096, 14336, fmt, lay) == b.workspace_bytes(b.OP_GEMM, 16, 4096, 14336, fmt, lay)
 
 
 def test_argument_validation_happens_before_any_launch(lib):
