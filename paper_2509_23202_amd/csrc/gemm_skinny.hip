@@ -12,7 +12,7 @@
 // reduction, so each workgroup pays one memory latency with nothing in flight.  gemm_stream_kernel (MXFP4, M <= 16,
 // layers with more row-blocks than the chip holds workgroups) keeps a fixed grid resident, walks the row-blocks with a
 // stride and holds two register batches per wave, so the loads of the next row-block are in flight while the partial
-// sums of the current one meet in LDS.  gemm_skinny_nv_kernel (NVFP4, M <= 16) gives a workgroup two row-blocks so that
+// sums of the current one meet in LDS.  gemm_skinny_nv_kernel (NVFP4) gives a workgroup two row-blocks so that
 // each dequantized X fragment serves two W fragments.  All add the eight partials in wave order: bit-identical results.
 #include "device_util.hpp"
 #include "internal.hpp"
@@ -137,22 +137,31 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_kernel(SkinnyAr
 // and a wave multiplies each dequantized X fragment against the NT W fragments of its K position, so the X share of the
 // arithmetic drops to 1/NT.  Same K split over the waves, same order of additions per output: bit-identical to the
 // kernel above.  Row-blocks past the end of W (odd counts) re-read the last one and are not stored.
-template <int NT, bool OUT_F32>
+// MT = 16-token blocks of X (M <= 16 MT): every W fragment meets MT dequantized X fragments, each of them shared by the NT
+// row-blocks (the arithmetic per KB of W is 48 (1 + MT / NT) instructions instead of 48 (1 + MT)).
+template <int NT, int MT, bool OUT_F32>
 __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nv_kernel(SkinnyArgs g)
 {
-    constexpr int U = 4;  // K positions in flight per wave (NT W fragments each)
-    __shared__ float partial[kSkinnyWaves][NT][256];
+    constexpr int U = MT == 1 ? 4 : 2;  // K positions in flight per wave (NT W fragments and MT X fragments each)
+    __shared__ float partial[kSkinnyWaves][NT * MT][256];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int n_rb = (g.N + 15) >> 4;
+    const int a_rbs = (g.M + 15) >> 4;
     const int rb0 = blockIdx.x * NT;
     const int KC = g.K >> 7;
     const int per = (KC + kSkinnyWaves - 1) / kSkinnyWaves;
     const int k_begin = min(wave * per, KC), k_end = min(k_begin + per, KC);
 
-    const v4i* xfrag = reinterpret_cast<const v4i*>(g.a_codes) + lane;
-    const uint16_t* xsc = reinterpret_cast<const uint16_t*>(g.a_scales) + lane;
+    const v4i* xfrag[MT];
+    const uint16_t* xsc[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        const int mrb = min(t, a_rbs - 1);  // (token blocks past the end re-read the last one and are not stored)
+        xfrag[t] = reinterpret_cast<const v4i*>(g.a_codes + (int64_t)mrb * KC * 1024) + lane;
+        xsc[t] = reinterpret_cast<const uint16_t*>(g.a_scales) + (int64_t)mrb * KC * 64 + lane;
+    }
     const v4i* wfrag[NT];
     const uint16_t* wsc[NT];
 #pragma unroll
@@ -162,13 +171,15 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nv_kernel(Skinn
         wsc[r] = reinterpret_cast<const uint16_t*>(g.w_scales) + (int64_t)rb * KC * 64 + lane;
     }
 
-    v4f acc[NT];
+    v4f acc[NT][MT];
 #pragma unroll
-    for (int r = 0; r < NT; ++r) acc[r] = v4f{0.f, 0.f, 0.f, 0.f};
+    for (int r = 0; r < NT; ++r)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) acc[r][t] = v4f{0.f, 0.f, 0.f, 0.f};
 
     for (int kc0 = k_begin; kc0 < k_end; kc0 += U) {
-        v4i wf[U][NT], xf[U];
-        uint32_t swv[U][NT], sxv[U];
+        v4i wf[U][NT], xf[U][MT];
+        uint32_t swv[U][NT], sxv[U][MT];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int kc = min(kc0 + u, k_end - 1);  // the tail repeats the last fragment; its products are skipped below
@@ -177,19 +188,38 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nv_kernel(Skinn
                 wf[u][r] = __builtin_nontemporal_load(wfrag[r] + (int64_t)kc * 64);
                 swv[u][r] = wsc[r][(int64_t)kc * 64];
             }
-            xf[u] = xfrag[(int64_t)kc * 64];
-            sxv[u] = xsc[(int64_t)kc * 64];
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                xf[u][t] = xfrag[t][(int64_t)kc * 64];
+                sxv[u][t] = xsc[t][(int64_t)kc * 64];
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (kc0 + u < k_end) {
-                const NvFrag16 x16 = nv_dequant_frag(xf[u], sxv[u]);
+                if constexpr (MT == 1) {
+                    // one X fragment: dequantize it once, then one W fragment at a time (fewest live registers)
+                    const NvFrag16 x16 = nv_dequant_frag(xf[u][0], sxv[u][0]);
 #pragma unroll
-                for (int r = 0; r < NT; ++r) {
-                    const NvFrag16 w16 = nv_dequant_frag(wf[u][r], swv[u][r]);
+                    for (int r = 0; r < NT; ++r) {
+                        const NvFrag16 w16 = nv_dequant_frag(wf[u][r], swv[u][r]);
 #pragma unroll
-                    for (int s = 0; s < 4; ++s)
-                        acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w16.s[s], x16.s[s], acc[r], 0, 0, 0);
+                        for (int s = 0; s < 4; ++s)
+                            acc[r][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w16.s[s], x16.s[s], acc[r][0], 0, 0, 0);
+                    }
+                } else {
+                    NvFrag16 w16[NT];
+#pragma unroll
+                    for (int r = 0; r < NT; ++r) w16[r] = nv_dequant_frag(wf[u][r], swv[u][r]);
+#pragma unroll
+                    for (int t = 0; t < MT; ++t) {
+                        const NvFrag16 x16 = nv_dequant_frag(xf[u][t], sxv[u][t]);
+#pragma unroll
+                        for (int r = 0; r < NT; ++r)
+#pragma unroll
+                            for (int s = 0; s < 4; ++s)
+                                acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w16[r].s[s], x16.s[s], acc[r][t], 0, 0, 0);
+                    }
                 }
             }
         }
@@ -197,17 +227,19 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nv_kernel(Skinn
 
 #pragma unroll
     for (int r = 0; r < NT; ++r)
-        *reinterpret_cast<v4f*>(&partial[wave][r][lane * 4]) = acc[r];
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+            *reinterpret_cast<v4f*>(&partial[wave][r * MT + t][lane * 4]) = acc[r][t];
     __syncthreads();
 
     const float ts = (*g.a_ts) * (*g.w_ts);
-    for (int e = threadIdx.x; e < NT * 256; e += kSkinnyWaves * 64) {
-        const int r = e >> 8, q = e & 255, l = q >> 2, v = q & 3;
+    for (int e = threadIdx.x; e < NT * MT * 256; e += kSkinnyWaves * 64) {
+        const int rt = e >> 8, r = rt / MT, t = rt - r * MT, q = e & 255, l = q >> 2, v = q & 3;
         float s = 0.0f;
 #pragma unroll
-        for (int w = 0; w < kSkinnyWaves; ++w) s += partial[w][r][q];
+        for (int w = 0; w < kSkinnyWaves; ++w) s += partial[w][rt][q];
         s *= ts;
-        const int m = l & 15;
+        const int m = t * 16 + (l & 15);
         const int n = (rb0 + r) * 16 + (l >> 4) * 4 + v;
         if (m < g.M && n < g.N) {
             if constexpr (OUT_F32) static_cast<float*>(g.out)[(int64_t)m * g.N + n] = s;
@@ -432,6 +464,31 @@ hipError_t launch_mt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
     return hipGetLastError();
 }
 
+// NVFP4: two row-blocks per workgroup halve the X share of the dequantization; below about 0.6 workgroups per compute
+// unit the halved grid costs more than that saves (K = 14336, N = 4096, M <= 16: 14.1 us against 11.2).  Returns false
+// (nothing launched) when the one-row-block kernel is the better choice.
+template <int MT>
+bool try_nv_two_row_blocks(const SkinnyArgs& g, bool out_f32, hipStream_t st, hipError_t* err)
+{
+    const int n_rb = (g.N + 15) / 16, wgs = (n_rb + 1) / 2;
+    if (5 * wgs < 3 * stream_cus()) return false;
+    const dim3 grid((unsigned)wgs), block(kSkinnyWaves * 64);
+    if (out_f32) hipLaunchKernelGGL((gemm_skinny_nv_kernel<2, MT, true>), grid, block, 0, st, g);
+    else hipLaunchKernelGGL((gemm_skinny_nv_kernel<2, MT, false>), grid, block, 0, st, g);
+    *err = hipGetLastError();
+    return true;
+}
+
+template <int FMT, int MT>
+hipError_t launch_tokens(const SkinnyArgs& g, bool out_f32, hipStream_t st)
+{
+    if constexpr (FMT == 1) {
+        hipError_t e = hipSuccess;
+        if (try_nv_two_row_blocks<MT>(g, out_f32, st, &e)) return e;
+    }
+    return launch_mt<FMT, MT>(g, out_f32, st);
+}
+
 template <int FMT>
 hipError_t launch_fmt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
 {
@@ -442,21 +499,11 @@ hipError_t launch_fmt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
                 const int per = ((g.K >> 7) + kSkinnyWaves - 1) / kSkinnyWaves;  // fragments of K per wave
                 hipError_t e = hipSuccess;
                 if (per <= 4 ? try_stream<0, 4, true>(g, out_f32, per, st, &e) : try_stream<0, 4, false>(g, out_f32, per, st, &e)) return e;
-            } else {
-                // two row-blocks per workgroup halve the X share of the dequantization; below about 0.6 workgroups per
-                // compute unit the halved grid costs more than that saves (K = 14336, N = 4096: 14.1 us against 11.2)
-                const int n_rb = (g.N + 15) / 16, wgs = (n_rb + 1) / 2;
-                if (5 * wgs >= 3 * stream_cus()) {
-                    const dim3 grid((unsigned)wgs), block(kSkinnyWaves * 64);
-                    if (out_f32) hipLaunchKernelGGL((gemm_skinny_nv_kernel<2, true>), grid, block, 0, st, g);
-                    else hipLaunchKernelGGL((gemm_skinny_nv_kernel<2, false>), grid, block, 0, st, g);
-                    return hipGetLastError();
-                }
             }
-            return launch_mt<FMT, 1>(g, out_f32, st);
-        case 2: return launch_mt<FMT, 2>(g, out_f32, st);
-        case 3: return launch_mt<FMT, 3>(g, out_f32, st);
-        case 4: return launch_mt<FMT, 4>(g, out_f32, st);
+            return launch_tokens<FMT, 1>(g, out_f32, st);
+        case 2: return launch_tokens<FMT, 2>(g, out_f32, st);
+        case 3: return launch_tokens<FMT, 3>(g, out_f32, st);
+        case 4: return launch_tokens<FMT, 4>(g, out_f32, st);
         default: return hipErrorInvalidValue;
     }
 }

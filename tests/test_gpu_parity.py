@@ -334,12 +334,14 @@ def test_gemm_mxfp4_persistent_weight_streaming_kernel(fp4, oracle, grid, M, N, 
     _gemm_case(fp4, oracle, MX, M, N, K, seed=300 + grid + K, out_f32=out_f32, layout_gemm=True)
 
 
-@pytest.mark.parametrize("M,N,K,out_f32", [(1, 5000, 512, True), (16, 4944, 1152, False), (9, 5136, 128, False), (16, 8200, 640, True)])
+@pytest.mark.parametrize("M,N,K,out_f32", [(1, 5000, 512, True), (16, 4944, 1152, False), (9, 5136, 128, False), (16, 8200, 640, True),
+                                           (17, 5000, 512, False), (32, 4944, 1152, True), (40, 5136, 384, False), (64, 5000, 640, False),
+                                           (50, 8200, 128, True)])
 def test_gemm_nvfp4_few_tokens_two_row_blocks_per_workgroup(fp4, oracle, M, N, K, out_f32):
-    """Up to 16 tokens on NVFP4 with at least 0.6 workgroups per compute unit go to the kernel whose workgroups own two
+    """Up to 64 tokens on NVFP4 with at least 0.6 workgroups per compute unit go to the kernel whose workgroups own two
     16-column blocks of the output (one dequantized X fragment per two W fragments): odd block counts (the last workgroup
-    re-reads the last block and stores it once), ragged N, K / 128 = 1, 4, 5, 9 (waves without a K share, ragged tails of
-    the four-deep load batches)."""
+    re-reads the last block and stores it once), ragged N, K / 128 = 1, 3, 4, 5, 9 (waves without a K share, ragged tails of
+    the load batches), one to four 16-token blocks with ragged M (a token block past the end re-reads the last one)."""
     _gemm_case(fp4, oracle, NV, M, N, K, seed=4100 + N + K, out_f32=out_f32, layout_gemm=True)
 
 
