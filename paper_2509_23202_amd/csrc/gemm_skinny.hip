@@ -12,7 +12,7 @@
 // reduction, so each workgroup pays one memory latency with nothing in flight.  gemm_stream_kernel (MXFP4, M <= 16,
 // layers with more row-blocks than the chip holds workgroups) keeps a fixed grid resident, walks the row-blocks with a
 // stride and holds two register batches per wave, so the loads of the next row-block are in flight while the partial
-// sums of the current one meet in LDS.  gemm_skinny_nv_kernel (NVFP4) gives a workgroup two row-blocks so that
+// sums of the current one meet in LDS.  gemm_skinny_nt_kernel (NVFP4; MXFP4 above 16 tokens) gives a workgroup two row-blocks so that
 // each dequantized X fragment serves two W fragments.  All add the eight partials in wave order: bit-identical results.
 #include "device_util.hpp"
 #include "internal.hpp"
@@ -139,8 +139,10 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_kernel(SkinnyAr
 // kernel above.  Row-blocks past the end of W (odd counts) re-read the last one and are not stored.
 // MT = 16-token blocks of X (M <= 16 MT): every W fragment meets MT dequantized X fragments, each of them shared by the NT
 // row-blocks (the arithmetic per KB of W is 48 (1 + MT / NT) instructions instead of 48 (1 + MT)).
-template <int NT, int MT, bool OUT_F32>
-__global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nv_kernel(SkinnyArgs g)
+// FMT 0 (MXFP4, two to four token blocks): no dequantization there, but the X fragments come from L2 once per W fragment in
+// the kernel above and once per NT of them here.
+template <int FMT, int NT, int MT, bool OUT_F32>
+__global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nt_kernel(SkinnyArgs g)
 {
     constexpr int U = MT == 1 ? 4 : 2;  // K positions in flight per wave (NT W fragments and MT X fragments each)
     __shared__ float partial[kSkinnyWaves][NT * MT][256];
@@ -150,25 +152,33 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nv_kernel(Skinn
     const int n_rb = (g.N + 15) >> 4;
     const int a_rbs = (g.M + 15) >> 4;
     const int rb0 = blockIdx.x * NT;
-    const int KC = g.K >> 7;
+    const int KC = g.K >> 7, KS = (g.K + 511) >> 9;
     const int per = (KC + kSkinnyWaves - 1) / kSkinnyWaves;
     const int k_begin = min(wave * per, KC), k_end = min(k_begin + per, KC);
 
+    // scale of fragment kc of a row-block: NVFP4 two bytes per lane and fragment; MXFP4 one dword per lane and four
+    // fragments, the fragment's byte shifted down to bits 7:0 (where the MFMA's op_sel 0 reads it)
+    auto load_scale = [&](const uint8_t* row_block_scales, int kc) -> uint32_t {
+        if constexpr (FMT == 1) return *(reinterpret_cast<const uint16_t*>(row_block_scales) + (int64_t)kc * 64 + lane);
+        else return *(reinterpret_cast<const uint32_t*>(row_block_scales) + (int64_t)(kc >> 2) * 64 + lane) >> (8 * (kc & 3));
+    };
+    const int64_t sc_rb_bytes = FMT == 1 ? (int64_t)KC * 128 : (int64_t)KS * 256;
+
     const v4i* xfrag[MT];
-    const uint16_t* xsc[MT];
+    const uint8_t* xsc[MT];
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
         const int mrb = min(t, a_rbs - 1);  // (token blocks past the end re-read the last one and are not stored)
         xfrag[t] = reinterpret_cast<const v4i*>(g.a_codes + (int64_t)mrb * KC * 1024) + lane;
-        xsc[t] = reinterpret_cast<const uint16_t*>(g.a_scales) + (int64_t)mrb * KC * 64 + lane;
+        xsc[t] = g.a_scales + mrb * sc_rb_bytes;
     }
     const v4i* wfrag[NT];
-    const uint16_t* wsc[NT];
+    const uint8_t* wsc[NT];
 #pragma unroll
     for (int r = 0; r < NT; ++r) {
         const int rb = min(rb0 + r, n_rb - 1);
         wfrag[r] = reinterpret_cast<const v4i*>(g.w_codes + (int64_t)rb * KC * 1024) + lane;
-        wsc[r] = reinterpret_cast<const uint16_t*>(g.w_scales) + (int64_t)rb * KC * 64 + lane;
+        wsc[r] = g.w_scales + rb * sc_rb_bytes;
     }
 
     v4f acc[NT][MT];
@@ -186,18 +196,28 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nv_kernel(Skinn
 #pragma unroll
             for (int r = 0; r < NT; ++r) {
                 wf[u][r] = __builtin_nontemporal_load(wfrag[r] + (int64_t)kc * 64);
-                swv[u][r] = wsc[r][(int64_t)kc * 64];
+                swv[u][r] = load_scale(wsc[r], kc);
             }
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
                 xf[u][t] = xfrag[t][(int64_t)kc * 64];
-                sxv[u][t] = xsc[t][(int64_t)kc * 64];
+                sxv[u][t] = load_scale(xsc[t], kc);
             }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (kc0 + u < k_end) {
-                if constexpr (MT == 1) {
+                if constexpr (FMT == 0) {
+#pragma unroll
+                    for (int t = 0; t < MT; ++t) {
+                        const v8i b8 = {xf[u][t][0], xf[u][t][1], xf[u][t][2], xf[u][t][3], 0, 0, 0, 0};
+#pragma unroll
+                        for (int r = 0; r < NT; ++r) {
+                            const v8i a8 = {wf[u][r][0], wf[u][r][1], wf[u][r][2], wf[u][r][3], 0, 0, 0, 0};
+                            acc[r][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, acc[r][t], 4, 4, 0, (int)swv[u][r], 0, (int)sxv[u][t]);
+                        }
+                    }
+                } else if constexpr (MT == 1) {
                     // one X fragment: dequantize it once, then one W fragment at a time (fewest live registers)
                     const NvFrag16 x16 = nv_dequant_frag(xf[u][0], sxv[u][0]);
 #pragma unroll
@@ -232,7 +252,8 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nv_kernel(Skinn
             *reinterpret_cast<v4f*>(&partial[wave][r * MT + t][lane * 4]) = acc[r][t];
     __syncthreads();
 
-    const float ts = (*g.a_ts) * (*g.w_ts);
+    float ts = g.alpha;
+    if constexpr (FMT == 1) ts = (*g.a_ts) * (*g.w_ts);
     for (int e = threadIdx.x; e < NT * MT * 256; e += kSkinnyWaves * 64) {
         const int rt = e >> 8, r = rt / MT, t = rt - r * MT, q = e & 255, l = q >> 2, v = q & 3;
         float s = 0.0f;
@@ -464,17 +485,18 @@ hipError_t launch_mt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
     return hipGetLastError();
 }
 
-// NVFP4: two row-blocks per workgroup halve the X share of the dequantization; below about 0.6 workgroups per compute
-// unit the halved grid costs more than that saves (K = 14336, N = 4096, M <= 16: 14.1 us against 11.2).  Returns false
-// (nothing launched) when the one-row-block kernel is the better choice.
-template <int MT>
-bool try_nv_two_row_blocks(const SkinnyArgs& g, bool out_f32, hipStream_t st, hipError_t* err)
+// Two row-blocks per workgroup.  NVFP4: halves the X share of the dequantization; MXFP4 with two to four token blocks:
+// halves the reads of the X fragments from L2.  Below about 0.6 workgroups per compute unit the halved grid costs more
+// than that saves (NVFP4, K = 14336, N = 4096, M <= 16: 14.1 us against 11.2).  Returns false (nothing launched) when the
+// one-row-block kernel is the better choice.
+template <int FMT, int MT>
+bool try_two_row_blocks(const SkinnyArgs& g, bool out_f32, hipStream_t st, hipError_t* err)
 {
     const int n_rb = (g.N + 15) / 16, wgs = (n_rb + 1) / 2;
     if (5 * wgs < 3 * stream_cus()) return false;
     const dim3 grid((unsigned)wgs), block(kSkinnyWaves * 64);
-    if (out_f32) hipLaunchKernelGGL((gemm_skinny_nv_kernel<2, MT, true>), grid, block, 0, st, g);
-    else hipLaunchKernelGGL((gemm_skinny_nv_kernel<2, MT, false>), grid, block, 0, st, g);
+    if (out_f32) hipLaunchKernelGGL((gemm_skinny_nt_kernel<FMT, 2, MT, true>), grid, block, 0, st, g);
+    else hipLaunchKernelGGL((gemm_skinny_nt_kernel<FMT, 2, MT, false>), grid, block, 0, st, g);
     *err = hipGetLastError();
     return true;
 }
@@ -482,9 +504,11 @@ bool try_nv_two_row_blocks(const SkinnyArgs& g, bool out_f32, hipStream_t st, hi
 template <int FMT, int MT>
 hipError_t launch_tokens(const SkinnyArgs& g, bool out_f32, hipStream_t st)
 {
-    if constexpr (FMT == 1) {
+    // (MXFP4 with two token blocks measured level with the one-row-block kernel, with three and four 5-11 % faster:
+    // N = 6144, K = 4096, M = 64: 8.5 us against 9.6; N = K = 8192: 14.4 against 16.1)
+    if constexpr (FMT == 1 || MT >= 3) {
         hipError_t e = hipSuccess;
-        if (try_nv_two_row_blocks<MT>(g, out_f32, st, &e)) return e;
+        if (try_two_row_blocks<FMT, MT>(g, out_f32, st, &e)) return e;
     }
     return launch_mt<FMT, MT>(g, out_f32, st);
 }

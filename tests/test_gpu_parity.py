@@ -345,6 +345,14 @@ def test_gemm_nvfp4_few_tokens_two_row_blocks_per_workgroup(fp4, oracle, M, N, K
     _gemm_case(fp4, oracle, NV, M, N, K, seed=4100 + N + K, out_f32=out_f32, layout_gemm=True)
 
 
+@pytest.mark.parametrize("M,N,K,out_f32", [(33, 5000, 512, False), (48, 4944, 1152, True), (64, 5136, 384, False), (50, 8200, 128, True)])
+def test_gemm_mxfp4_three_and_four_token_blocks_two_row_blocks_per_workgroup(fp4, oracle, M, N, K, out_f32):
+    """33 to 64 tokens on MXFP4 with at least 0.6 workgroups per compute unit (and N < 16384): the kernel whose workgroups
+    own two 16-column blocks, so that every X fragment read from L2 serves two W fragments.  Ragged M, N, odd block counts,
+    K / 128 = 1, 3, 4, 9."""
+    _gemm_case(fp4, oracle, MX, M, N, K, seed=5100 + N + K, out_f32=out_f32, layout_gemm=True)
+
+
 @pytest.mark.parametrize("M,N,K,out_f32", [(65, 400, 8192, True), (128, 1024, 14336, False), (200, 1000, 12416, False), (300, 272, 16512, True),
                                            (512, 520, 9088, False)])
 def test_gemm_mxfp4_split_k(fp4, oracle, M, N, K, out_f32):
