@@ -281,10 +281,13 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nt_kernel(Skinn
 // barrier per row-block suffices.  Bit-identical to the one-shot kernel (same K split, same order of additions).
 // XRES: the wave's share of K is at most U fragments (one batch per row-block), and since that share is the same for every
 // row-block its X fragments are loaded once and stay in registers: a batch is then W only.
-template <int FMT, bool OUT_F32, int U, bool XRES>
+// MT > 1 (XRES only): up to MT 16-token blocks of X stay in registers, a W fragment meets all of them, and nothing of X is
+// read again for the rest of the launch -- the one-shot kernels fetch MT X fragments from L2 per W fragment.
+template <int FMT, bool OUT_F32, int U, bool XRES, int MT = 1>
 __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyArgs g)
 {
-    __shared__ float partial[2][kSkinnyWaves][256];
+    static_assert(MT == 1 || XRES, "several token blocks only with the X fragments resident");
+    __shared__ float partial[2][kSkinnyWaves][MT][256];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -303,12 +306,13 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
     };
     constexpr int SCB = FMT == 0 ? 256 : 128;            // scale bytes per (row-block, MXFP4: four fragments / NVFP4: fragment)
     const int sc_per_rb = FMT == 0 ? KS : KC;
-    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(g.a_codes, (int64_t)KC * 1024);
-    const __amdgpu_buffer_rsrc_t rs_xs = make_rsrc(g.a_scales, (int64_t)sc_per_rb * SCB);
+    const int a_rbs = (g.M + 15) >> 4;
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(g.a_codes, (int64_t)a_rbs * KC * 1024);
+    const __amdgpu_buffer_rsrc_t rs_xs = make_rsrc(g.a_scales, (int64_t)a_rbs * sc_per_rb * SCB);
     const int lane16 = lane * 16, lane_sc = FMT == 0 ? lane * 4 : lane * 2;
-    auto load_scale = [&](__amdgpu_buffer_rsrc_t rs, int kc) -> uint32_t {
-        if constexpr (FMT == 0) return __builtin_amdgcn_raw_buffer_load_b32(rs, lane_sc, (kc >> 2) * 256, 0);
-        else return (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rs, lane_sc, kc * 128, 0);
+    auto load_scale = [&](__amdgpu_buffer_rsrc_t rs, int kc, int rb_off = 0) -> uint32_t {
+        if constexpr (FMT == 0) return __builtin_amdgcn_raw_buffer_load_b32(rs, lane_sc, rb_off + (kc >> 2) * 256, 0);
+        else return (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rs, lane_sc, rb_off + kc * 128, 0);
     };
 
     struct Batch {
@@ -331,35 +335,45 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
             }
         }
     };
-    v4i xres[XRES ? U : 1];
-    uint32_t sxres[XRES ? U : 1];
+    v4i xres[MT][XRES ? U : 1];
+    uint32_t sxres[MT][XRES ? U : 1];
     if constexpr (XRES) {
         if (nb > 0) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int kc = min(k_begin + u, k_end - 1);
-                xres[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rs_x, lane16, kc * 1024, 0));
-                sxres[u] = load_scale(rs_xs, kc);
+            for (int t = 0; t < MT; ++t) {
+                const int mrb = min(t, a_rbs - 1);  // (a token block past the end re-reads the last one and is not stored)
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int kc = min(k_begin + u, k_end - 1);
+                    xres[t][u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rs_x, lane16, mrb * KC * 1024 + kc * 1024, 0));
+                    sxres[t][u] = load_scale(rs_xs, kc, mrb * sc_per_rb * SCB);
+                }
             }
         }
     }
-    auto consume = [&](const Batch& b, int kc0, v4f& acc) {
+    auto consume = [&](const Batch& b, int kc0, v4f (&acc)[MT]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (kc0 + u < k_end) {
-                const v4i xf = XRES ? xres[u] : b.xf[XRES ? 0 : u];
-                const uint32_t sx = XRES ? sxres[u] : b.sx[XRES ? 0 : u];
                 if constexpr (FMT == 0) {
                     const int kc = kc0 + u;
                     const v8i a8 = {b.wf[u][0], b.wf[u][1], b.wf[u][2], b.wf[u][3], 0, 0, 0, 0};
-                    const v8i b8 = {xf[0], xf[1], xf[2], xf[3], 0, 0, 0, 0};
-                    acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, acc, 4, 4, 0, (int)(b.sw[u] >> (8 * (kc & 3))), 0,
-                                                                         (int)(sx >> (8 * (kc & 3))));
+#pragma unroll
+                    for (int t = 0; t < MT; ++t) {
+                        const v4i xf = XRES ? xres[t][u] : b.xf[XRES ? 0 : u];
+                        const uint32_t sx = XRES ? sxres[t][u] : b.sx[XRES ? 0 : u];
+                        const v8i b8 = {xf[0], xf[1], xf[2], xf[3], 0, 0, 0, 0};
+                        acc[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, acc[t], 4, 4, 0, (int)(b.sw[u] >> (8 * (kc & 3))), 0,
+                                                                                (int)(sx >> (8 * (kc & 3))));
+                    }
                 } else {
                     const NvFrag16 w16 = nv_dequant_frag(b.wf[u], b.sw[u]);
-                    const NvFrag16 x16 = nv_dequant_frag(xf, sx);
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(w16.s[s], x16.s[s], acc, 0, 0, 0);
+                    for (int t = 0; t < MT; ++t) {
+                        const NvFrag16 x16 = nv_dequant_frag(XRES ? xres[t][u] : b.xf[XRES ? 0 : u], XRES ? sxres[t][u] : b.sx[XRES ? 0 : u]);
+#pragma unroll
+                        for (int s = 0; s < 4; ++s) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w16.s[s], x16.s[s], acc[t], 0, 0, 0);
+                    }
                 }
             }
         }
@@ -371,12 +385,29 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
     // The two batch buffers are addressed with compile-time indices only (a run-time index would put them in scratch
     // memory): a row-block's batches alternate between them, two per trip of the loop, and a row-block with an odd number
     // of batches hands the next one the other buffer first (`first`, uniform).
+    // vmcnt(LPB + stores): the batch just requested, and the output stores issued in front of it, may stay in flight.  The
+    // count has to be exact -- a store that no lane of the wave takes part in (token rows or columns past the end) is not
+    // in flight, and counting it would let the wait return with a load of the current batch still outstanding.
+    auto wait_allowing = [&](int stores) {
+        static_assert(LPB + MT < 64, "vmcnt is a 6-bit counter");
+        switch (stores) {
+            case 0: __builtin_amdgcn_s_waitcnt((LPB & 15) | ((LPB >> 4) << 14) | 0x0f70); break;
+            case 1: __builtin_amdgcn_s_waitcnt(((LPB + 1) & 15) | (((LPB + 1) >> 4) << 14) | 0x0f70); break;
+            case 2: __builtin_amdgcn_s_waitcnt(((LPB + (MT >= 2 ? 2 : 0)) & 15) | (((LPB + (MT >= 2 ? 2 : 0)) >> 4) << 14) | 0x0f70); break;
+            case 3: __builtin_amdgcn_s_waitcnt(((LPB + (MT >= 3 ? 3 : 0)) & 15) | (((LPB + (MT >= 3 ? 3 : 0)) >> 4) << 14) | 0x0f70); break;
+            default: __builtin_amdgcn_s_waitcnt(((LPB + (MT >= 4 ? 4 : 0)) & 15) | (((LPB + (MT >= 4 ? 4 : 0)) >> 4) << 14) | 0x0f70); break;
+        }
+    };
+    static_assert(MT <= 4, "wait_allowing counts up to four stores");
+    int prev_stores = 0;  // output stores this wave issued for the row-block before the current one (uniform)
     Batch buf0, buf1;
     int first = 0;
     int rb = (int)blockIdx.x;
     if (nb > 0 && rb < n_rb) load_batch(buf0, rb, k_begin);
     for (int it = 0; rb < n_rb; ++it, rb += G) {
-        v4f acc = {0.f, 0.f, 0.f, 0.f};
+        v4f acc[MT];
+#pragma unroll
+        for (int t = 0; t < MT; ++t) acc[t] = v4f{0.f, 0.f, 0.f, 0.f};
         // one batch: request the one after it into `nxt`, wait for `cur`, multiply
         auto step = [&](Batch& cur, Batch& nxt, int b) {
             const bool more_here = b + 1 < nb, more_rb = rb + G < n_rb;
@@ -384,10 +415,10 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
             else if (more_rb) load_batch(nxt, rb + G, k_begin);
             // memory operations retire in issue order: everything but the batch just requested may be waited for (nothing
             // else was issued behind the current batch except, before a row-block's first batch, the previous row-block's
-            // one output store)
+            // MT output stores)
             if (more_here || more_rb) {
-                if (b == 0 && it > 0) __builtin_amdgcn_s_waitcnt(((LPB + 1) & 15) | (((LPB + 1) >> 4) << 14) | 0x0f70);
-                else __builtin_amdgcn_s_waitcnt((LPB & 15) | ((LPB >> 4) << 14) | 0x0f70);
+                if (b == 0) wait_allowing(prev_stores);
+                else wait_allowing(0);
             } else {
                 __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
             }
@@ -407,26 +438,35 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
         first ^= nb & 1;
         // partial sums meet in LDS (two buffers, alternating: a buffer is written again two row-blocks later, behind the
         // next row-block's barrier, when every wave has long finished reading it)
-        float* mine = &partial[it & 1][wave][0];
-        *reinterpret_cast<v4f*>(mine + lane * 4) = acc;
-        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the LDS write has landed
+#pragma unroll
+        for (int t = 0; t < MT; ++t) *reinterpret_cast<v4f*>(&partial[it & 1][wave][t][lane * 4]) = acc[t];
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the LDS writes have landed
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        // every wave reduces 32 of the 256 outputs, lanes 0..31 one each, adding the eight partials in wave order (the order
-        // of additions of the one-shot kernel)
+        // every wave reduces 32 of the 256 outputs of each token block, lanes 0..31 one each, adding the eight partials in
+        // wave order (the order of additions of the one-shot kernel)
         const int r = wave * 32 + (lane & 31);
-        float sum = 0.0f;
-#pragma unroll
-        for (int w = 0; w < kSkinnyWaves; ++w) sum += partial[it & 1][w][r];
-        sum *= ts;
         const int l = r >> 2, v = r & 3;
-        const int m = l & 15;
         const int n = rb * 16 + (l >> 4) * 4 + v;
-        // exactly one store instruction per wave and row-block (lanes masked by the condition), which the wait above counts
-        if (lane < 32 && m < g.M && n < g.N) {
-            if constexpr (OUT_F32) static_cast<float*>(g.out)[(int64_t)m * g.N + n] = sum;
-            else static_cast<__bf16*>(g.out)[(int64_t)m * g.N + n] = (__bf16)sum;
+        // The wave's 32 outputs of a token block are rows t * 16 + 8 (wave % 2) .. + 7 and columns rb * 16 + 4 (wave / 2) .. + 3:
+        // one store instruction per token block that has any of them inside the matrix (uniform), none otherwise.
+        const bool cols_in = rb * 16 + (wave >> 1) * 4 < g.N;
+        prev_stores = 0;
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            float sum = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kSkinnyWaves; ++w) sum += partial[it & 1][w][t][r];
+            sum *= ts;
+            const int m = t * 16 + (l & 15);
+            if (cols_in && t * 16 + (wave & 1) * 8 < g.M) {  // (uniform)
+                ++prev_stores;
+                if (lane < 32 && m < g.M && n < g.N) {
+                    if constexpr (OUT_F32) static_cast<float*>(g.out)[(int64_t)m * g.N + n] = sum;
+                    else static_cast<__bf16*>(g.out)[(int64_t)m * g.N + n] = (__bf16)sum;
+                }
+            }
         }
     }
 }
@@ -440,38 +480,38 @@ int stream_cus()
 }
 
 // workgroups of the persistent kernel that are resident at once on one compute unit: asked of the runtime once per kernel
-template <int FMT, int U, bool XRES>
+template <int FMT, int U, bool XRES, int MT>
 int stream_resident(bool out_f32)
 {
     static int resident[2] = {0, 0};
     int& per_cu = resident[out_f32 ? 1 : 0];
     if (per_cu == 0) {
         int n = 0;
-        const hipError_t e = out_f32 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, gemm_stream_kernel<FMT, true, U, XRES>, kSkinnyWaves * 64, 0)
-                                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, gemm_stream_kernel<FMT, false, U, XRES>, kSkinnyWaves * 64, 0);
+        const hipError_t e = out_f32 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, gemm_stream_kernel<FMT, true, U, XRES, MT>, kSkinnyWaves * 64, 0)
+                                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, gemm_stream_kernel<FMT, false, U, XRES, MT>, kSkinnyWaves * 64, 0);
         per_cu = (e == hipSuccess && n > 0) ? n : 1;
     }
     return per_cu;
 }
 
-// MXFP4, up to 16 tokens.  Returns false (nothing launched) where the one-shot kernel is the better choice: the persistent
-// kernel wins by keeping loads in flight across batches and row-blocks (N = 28672, K = 4096: 10.9 us against 13.7;
-// N = 4096, K = 14336: 7.8 against 8.4), which needs either several batches per row-block or more row-blocks than
-// resident workgroups; a layer that fits the chip in one go (N <= 8192 at K = 4096) is launch-bound and 0.1-0.4 us
-// faster with the one-shot kernel's higher occupancy.  NVFP4 stays with the one-shot kernel too: its in-register
-// dequantization needs the registers that the second batch buffer takes (one workgroup per compute unit: 68 us against 54
-// on N = 57344, K = 8192).
-template <int FMT, int U, bool XRES>
+// MXFP4, up to 16 tokens (MT = 1) or, with the X fragments resident, up to 64.  Returns false (nothing launched) where a
+// one-shot kernel is the better choice: the persistent kernel wins by keeping loads in flight across batches and row-blocks
+// (N = 28672, K = 4096: 10.9 us against 13.7; N = 4096, K = 14336: 7.8 against 8.4), which needs either several batches
+// per row-block or more row-blocks than resident workgroups; a layer that fits the chip in one go (N <= 8192 at K = 4096)
+// is launch-bound and 0.1-0.4 us faster with the one-shot kernel's higher occupancy.  NVFP4 stays with the one-shot
+// kernels: its in-register dequantization needs the registers that the second batch buffer takes (one workgroup per
+// compute unit: 68 us against 54 on N = 57344, K = 8192).
+template <int FMT, int U, bool XRES, int MT = 1>
 bool try_stream(const SkinnyArgs& g, bool out_f32, int per, hipStream_t st, hipError_t* err)
 {
     const int n_rb = (g.N + 15) / 16;
-    int cap = stream_cus() * stream_resident<FMT, U, XRES>(out_f32);
+    int cap = stream_cus() * stream_resident<FMT, U, XRES, MT>(out_f32);
     // (the grid-cap option, a testing aid: a small grid makes every workgroup walk many row-blocks)
     if (options().gemm_grid > 0 && options().gemm_grid < cap) cap = options().gemm_grid;
     if (per <= U && n_rb <= cap) return false;
     const dim3 grid((unsigned)std::min(n_rb, cap)), block(kSkinnyWaves * 64);
-    if (out_f32) hipLaunchKernelGGL((gemm_stream_kernel<FMT, true, U, XRES>), grid, block, 0, st, g);
-    else hipLaunchKernelGGL((gemm_stream_kernel<FMT, false, U, XRES>), grid, block, 0, st, g);
+    if (out_f32) hipLaunchKernelGGL((gemm_stream_kernel<FMT, true, U, XRES, MT>), grid, block, 0, st, g);
+    else hipLaunchKernelGGL((gemm_stream_kernel<FMT, false, U, XRES, MT>), grid, block, 0, st, g);
     *err = hipGetLastError();
     return true;
 }
@@ -504,6 +544,12 @@ bool try_two_row_blocks(const SkinnyArgs& g, bool out_f32, hipStream_t st, hipEr
 template <int FMT, int MT>
 hipError_t launch_tokens(const SkinnyArgs& g, bool out_f32, hipStream_t st)
 {
+    if constexpr (FMT == 0 && MT >= 2) {
+        // K <= 4096: the wave's share of K is one batch, so all MT token blocks of X stay in registers of the persistent kernel
+        const int per = ((g.K >> 7) + kSkinnyWaves - 1) / kSkinnyWaves;
+        hipError_t e = hipSuccess;
+        if (per <= 4 && try_stream<0, 4, true, MT>(g, out_f32, per, st, &e)) return e;
+    }
     // (MXFP4 with two token blocks measured level with the one-row-block kernel, with three and four 5-11 % faster:
     // N = 6144, K = 4096, M = 64: 8.5 us against 9.6; N = K = 8192: 14.4 against 16.1)
     if constexpr (FMT == 1 || MT >= 3) {

@@ -323,13 +323,16 @@ def test_gemm_mxfp4_scales_that_differ_per_row_block_and_k_block(fp4, oracle, va
 
 @pytest.mark.parametrize("grid", [1, 3])
 @pytest.mark.parametrize("M,N,K,out_f32", [(1, 400, 512, True), (16, 784, 2176, False), (9, 1040, 4096, False), (16, 272, 640, True),
-                                           (3, 200, 128, False)])
+                                           (3, 200, 128, False), (17, 400, 512, False), (40, 784, 2176, True), (64, 1040, 4096, False),
+                                           (33, 200, 128, True), (56, 1000, 384, False)])
 def test_gemm_mxfp4_persistent_weight_streaming_kernel(fp4, oracle, grid, M, N, K, out_f32, knobs):
     """Up to 16 tokens on MXFP4 go to the persistent weight-streaming kernel when there are more 16-column blocks than
     resident workgroups (or several batches of K per wave); a grid cap of 1 or 3 workgroups makes every workgroup walk
     many row-blocks with the next batch's loads in flight across the reduction: K / 128 = 1, 4, 5, 17, 32 covers waves
     without a K share, one batch and several batches per row-block (X resident in registers / travelling with W), odd
-    batch counts (the two register buffers swap roles between row-blocks), ragged N."""
+    batch counts (the two register buffers swap roles between row-blocks), ragged N.  With 17 to 64 tokens and K <= 4096 the
+    same kernel keeps two to four 16-token blocks of X resident (ragged M: a token block past the end re-reads the last one;
+    waves whose rows or columns lie outside the matrix issue no store, which the in-flight count must know)."""
     knobs(grid=grid)
     _gemm_case(fp4, oracle, MX, M, N, K, seed=300 + grid + K, out_f32=out_f32, layout_gemm=True)
 
