@@ -567,6 +567,39 @@ def main():
                 decode[f"M={Md}"] = per
             decode["weights"] = "cold: every call of a replayed graph takes the next of several identical weight copies (>= 640 MB in all), for the bf16 baseline too"
             result["decode_configs1"] = decode
+            # ---- batched decoding, M = 128 on the same four layers (not a BASELINE config: the regime between the few-token
+            # kernels and prefill, where narrow layers leave most of the chip without a tile and fp4_gemm splits K when it is
+            # given the FP4MR_OP_GEMM_SPLIT_K workspace)
+            mid = {}
+            Mm = 128
+            for s_ in state:
+                L = s_["L"]
+                xd = s_["x"][:Mm].contiguous()
+                cbd, sbd = fp4.packed_bytes(Mm, L.K, fp4.MXFP4, GL)
+                acd = torch.zeros(cbd, dtype=torch.uint8, device="cuda")
+                ascd = torch.zeros(sbd, dtype=torch.uint8, device="cuda")
+                outd = torch.empty((Mm, L.N), dtype=torch.bfloat16, device="cuda")
+                outb = torch.empty((Mm, L.N), dtype=torch.bfloat16, device="cuda")
+                wbytes = L.N * L.K * (0.5 + 1.0 / 32)
+                wq = cold_copies((s_["wc"], s_["ws"]), wbytes)
+                wb = cold_copies((s_["w"],), L.N * L.K * 2.0)
+                nq, nb_ = len(wq), len(wb)
+                need_s = fp4.workspace_bytes(fp4.OP_GEMM_SPLIT_K, Mm, L.N, L.K, fp4.MXFP4, gflags)
+                wss = torch.empty(max(need_s, 16), dtype=torch.uint8, device="cuda")
+                ws0 = torch.empty(16, dtype=torch.uint8, device="cuda")
+                fp4.fp4_rotate_quantize(xd, b, fp4.MXFP4, flags=GL, codes=acd, scales=ascd)
+                t_rq = graph_us(lambda i: fp4.fp4_rotate_quantize(xd, b, fp4.MXFP4, flags=GL, codes=acd, scales=ascd), acd)
+                t_g = graph_us(lambda i: fp4.fp4_gemm(acd, ascd, None, wq[i % nq][0], wq[i % nq][1], None, Mm, L.N, L.K, fp4.MXFP4,
+                                                     flags=gflags, out=outd, workspace=wss), outd, n=max(20, nq))
+                t_g0 = graph_us(lambda i: fp4.fp4_gemm(acd, ascd, None, wq[i % nq][0], wq[i % nq][1], None, Mm, L.N, L.K, fp4.MXFP4,
+                                                      flags=gflags, out=outd, workspace=ws0), outd, n=max(20, nq))
+                t_b = graph_us(lambda i: torch.matmul(xd, wb[i % nb_][0].t(), out=outb), outb, n=max(20, nb_))
+                mid[L.name] = {"rq_us": round(t_rq, 2), "gemm_us": round(t_g, 2), "gemm_unsplit_us": round(t_g0, 2),
+                               "split_k_parts": int(need_s // (Mm * L.N * 4)), "bf16_gemm_us": round(t_b, 2),
+                               "speedup_vs_bf16": round(t_b / (t_rq + t_g), 2)}
+                del wq, wb
+            mid["weights"] = "cold (copies cycled), bf16 baseline too"
+            result["batched_decode_m128"] = mid
         except Exception as exc:  # noqa: BLE001 - reported in the JSON line
             extras_errors["decode"] = repr(exc)
 
