@@ -105,7 +105,7 @@ void gemm_mx_kernel(GemmArgs g)
     constexpr int LPW = (F + NW - 1) / NW;                  // fragment loads per wave per stage
     constexpr int TM = WM / 16, TN = WN / 16;               // MFMA tiles per wave
     constexpr int STAGE_BYTES = F * 1024;
-    static_assert(STAGES >= 3 && STAGES <= 5, "ring bookkeeping is written for 3 to 5 stages");
+    static_assert(STAGES >= 3 && STAGES <= 8, "ring bookkeeping is written for 3 to 8 stages");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
@@ -172,9 +172,11 @@ void gemm_mx_kernel(GemmArgs g)
     constexpr int NS = SC8 ? (XP + WP + NW - 1) / NW : LPW; // scale loads per wave per batch
     constexpr int SCALE_BYTES = SC8 ? (XP + WP) * 1024 : F * 256;
     static_assert(NS <= LPW, "a scale load is issued in front of a fragment load of the same step");
-    // The scale ring is two batches deep, or one with a three-stage operand ring: a batch is read into registers at the
-    // end of the step before the one that issues its successor, with that step's barrier in between.
-    constexpr int SD = 1;
+    // One scale buffer up to five stages.  From six stages on the stage a step waits for was requested more than four steps
+    // earlier, so a batch requested in step 8b+4 would no longer be covered by the wait of step 8b+7 (loads complete in
+    // issue order: a wait for stage kt+1 covers what was requested before it): the batch is then requested in step 8b+0,
+    // into the other of TWO buffers (the one whose batch was last read at the end of step 8b-5).
+    constexpr int SD = (SC8 && STAGES >= 6) ? 2 : 1;
     char* const scale_ring = smem + STAGES * STAGE_BYTES;
     const int kc_bytes = (int)KC * 1024, ks_bytes = (int)KS * 256;
 
@@ -202,10 +204,10 @@ void gemm_mx_kernel(GemmArgs g)
             const uint32_t half = (uint32_t)lane >> 5, col = ((uint32_t)lane & 31u) * 16u;
             if ((XP % NW == 0) ? (i < XP / NW) : (p < XP)) {
                 const uint32_t rb = (uint32_t)min(2 * p + (int)half, a_rb_last);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_as, (lds_void*)(scale_ring + p * 1024), 16, rb * (uint32_t)ks_bytes + col, blk * 256, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_as, (lds_void*)(scale_ring + (SD == 2 ? (ss & 1) * SCALE_BYTES : 0) + p * 1024), 16, rb * (uint32_t)ks_bytes + col, blk * 256, 0, 0);
             } else {
                 const uint32_t rb = (uint32_t)min(2 * (p - XP) + (int)half, w_rb_last);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_ws, (lds_void*)(scale_ring + p * 1024), 16, rb * (uint32_t)ks_bytes + col, blk * 256, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_ws, (lds_void*)(scale_ring + (SD == 2 ? (ss & 1) * SCALE_BYTES : 0) + p * 1024), 16, rb * (uint32_t)ks_bytes + col, blk * 256, 0, 0);
             }
             return;
         }
@@ -226,7 +228,8 @@ void gemm_mx_kernel(GemmArgs g)
     };
     auto read_scales = [&](int64_t ss, uint32_t (&dx)[TM], uint32_t (&dw)[TN]) {  // ss = 4-step block
         if constexpr (SC8) {
-            const char* base = scale_ring + (ss & 1) * 256;  // a row-block's 512 bytes: even block, odd block
+            // a row-block's 512 bytes: even block, odd block (two buffers: batch ss / 2 is in buffer (ss / 2) % 2)
+            const char* base = scale_ring + (SD == 2 ? (int)((ss >> 1) & 1) * SCALE_BYTES : 0) + (ss & 1) * 256;
 #pragma unroll
             for (int j = 0; j < TM; ++j) dx[j] = *(reinterpret_cast<const uint32_t*>(base + (wm * TM + j) * 512) + lane);
 #pragma unroll
@@ -274,8 +277,10 @@ void gemm_mx_kernel(GemmArgs g)
         constexpr int J = decltype(jtag)::value;
         constexpr int SKEW = (2 * decltype(wtag)::value) % TM;  // MFMA index inside a group after which this wave issues its loads
         constexpr int P = J & 1;
-        constexpr int JB = SC8 ? 4 : 0;  // the step of a period that requests the next scale batch
-        constexpr bool batch_after = (J >= JB + 1 && J <= JB + STAGES - 3);
+        constexpr int JB = (SC8 && SD == 1) ? 4 : 0;  // the step of a period that requests the next scale batch
+        constexpr int PER = SC8 ? 8 : 4;                // steps per scale batch
+        // the batch was requested 1 .. STAGES - 3 steps ago, i.e. behind the loads of the stage this step waits for
+        constexpr bool batch_after = ((J - JB - 1 + PER) % PER) <= STAGES - 4;
         constexpr int ALLOWED = (STAGES - 3) * LPW + (batch_after ? NS : 0);
         if constexpr (PERSIST && J <= STAGES - 3) {
             // first steps of a follow-on tile, as long as the stage they wait for (kt + 1) is one of the STAGES - 1 that
@@ -503,8 +508,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 }
 
 // the tile shapes that have a split-K instantiation (the ones the cost model picks for shapes with few tiles)
-template <int BM, int BN, int WM, int RD, bool PERSIST>
-constexpr bool kHasSplitK = !PERSIST && ((BM == 128 && BN == 128) || (BM == 256 && BN == 128 && WM == 128 && RD == 2) ||
+template <int BM, int BN, int WM, int RD, bool PERSIST, int STAGES>
+constexpr bool kHasSplitK = !PERSIST && STAGES == 4 && ((BM == 128 && BN == 128) || (BM == 256 && BN == 128 && WM == 128 && RD == 2) ||
                                          (BM == 256 && BN == 256 && WM == 64 && RD == 3));
 
 // splits > 1: every tile is computed by `splits` workgroups, split y taking K-steps y * split_steps .. and writing its
@@ -516,10 +521,10 @@ hipError_t launch_variant(const GemmArgs& g0, bool out_f32, hipStream_t st, int 
     g.tiles_m = (int)((g.M + BM - 1) / BM);
     g.tiles_n = (int)((g.N + BN - 1) / BN);
     if (splits > 1) {
-        if constexpr (kHasSplitK<BM, BN, WM, RD, PERSIST>) {
+        if constexpr (kHasSplitK<BM, BN, WM, RD, PERSIST, STAGES>) {
             constexpr int threads_s = (BM / WM) * (BN / WN) * 64;
             constexpr size_t lds_s = (size_t)STAGES * (BM + BN) / 16 * 1024 +
-                                     (STAGES >= 4 ? (size_t)((BM / 16 + 1) / 2 + (BN / 16 + 1) / 2) * 1024 : (size_t)(BM + BN) / 16 * 256);
+                                     (STAGES >= 4 ? (size_t)((BM / 16 + 1) / 2 + (BN / 16 + 1) / 2) * 1024 * (STAGES >= 6 ? 2 : 1) : (size_t)(BM + BN) / 16 * 256);
             g.out = partial;
             g.alpha = 1.0f;
             g.split_steps = split_steps;
@@ -541,7 +546,7 @@ hipError_t launch_variant(const GemmArgs& g0, bool out_f32, hipStream_t st, int 
     constexpr int threads = (BM / WM) * (BN / WN) * 64;
     // operand ring + scale buffer (four and more stages: 1 KB per pair of row-blocks; three stages: 256 B per row-block)
     constexpr size_t lds = (size_t)STAGES * (BM + BN) / 16 * 1024 +
-                           (STAGES >= 4 ? (size_t)((BM / 16 + 1) / 2 + (BN / 16 + 1) / 2) * 1024 : (size_t)(BM + BN) / 16 * 256);
+                           (STAGES >= 4 ? (size_t)((BM / 16 + 1) / 2 + (BN / 16 + 1) / 2) * 1024 * (STAGES >= 6 ? 2 : 1) : (size_t)(BM + BN) / 16 * 256);
     const int ntiles = g.tiles_m * g.tiles_n;
     int nwg = ntiles;
     if (PERSIST) {
@@ -599,6 +604,10 @@ int pick_variant_mx(int64_t M, int64_t N, int64_t K)
         // there, level at K = 1536-2048, slower beyond (three stages, one and a half times the operand traffic) and
         // below (K = 512: the persistent 256x256 workgroups win).
         if ((variant == 10 || variant == 11) && K >= 768 && K <= 1280) variant = tiles(128, 256) > 2.0 * cus ? 16 : 15;
+        // 128x128 tiles that leave compute units without a tile: one workgroup per unit at most, bound by what a single
+        // unit can pull in -- the eight-stage ring keeps twice the bytes in flight (N = 4096, M = 128: K = 4096 14.3 ->
+        // 12.5 us, K = 14336 43 -> 35 us)
+        if (variant == 2 && n2 <= cus) variant = 17;
     }
     return variant;
 }
@@ -619,7 +628,7 @@ void plan_split_k_mx(int64_t M, int64_t N, int64_t K, int variant, int* splits, 
     *steps = 0;
     int bm, bn, per_cu;
     double fixed, step_alone, step_shared;  // step time with at most one workgroup per compute unit / with more
-    if (variant == 2) { bm = 128; bn = 128; per_cu = 2; fixed = 8.0; step_alone = 0.30; step_shared = 0.40; }
+    if (variant == 2 || variant == 17) { bm = 128; bn = 128; per_cu = 2; fixed = 8.0; step_alone = variant == 17 ? 0.25 : 0.30; step_shared = 0.40; }
     else if (variant == 5) { bm = 256; bn = 128; per_cu = 1; fixed = 9.0; step_alone = step_shared = 0.45; }
     else if (variant == 10) { bm = 256; bn = 256; per_cu = 1; fixed = 9.5; step_alone = step_shared = 0.74; }
     else return;
@@ -674,6 +683,7 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
     if (variant == 0) {
         variant = pick_variant_mx(M, N, K);
         if (partial && M > 64) plan_split_k_mx(M, N, K, variant, &splits, &split_steps);
+        if (variant == 17 && splits > 1) variant = 2;  // the parts run as four-stage workgroups, two per compute unit where needed
     }
     float* const pp = static_cast<float*>(partial);
     switch (variant) {
@@ -693,6 +703,7 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
         case 14: return launch_variant<256, 192, 64, 96, 4, 2, true>(g, out_f32, st);
         case 15: return launch_variant<128, 256, 64, 128, 3, 3>(g, out_f32, st);
         case 16: return launch_variant<128, 256, 64, 128, 3, 3, true>(g, out_f32, st);
+        case 17: return launch_variant<128, 128, 64, 64, 8>(g, out_f32, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -233,7 +233,7 @@ def test_gemm_gemm_layout_operands_bf16_out(fp4, oracle, fmt):
     _gemm_case(fp4, oracle, fmt, 200, 520, 1024 + 384, seed=5, out_f32=False, layout_gemm=True)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17])
 def test_gemm_mxfp4_every_tile_variant(fp4, oracle, variant, knobs):
     knobs(variant=variant)
     _gemm_case(fp4, oracle, MX, 272, 528, 1280, seed=variant, out_f32=True, layout_gemm=True)
@@ -248,12 +248,43 @@ def test_gemm_nvfp4_every_tile_variant(fp4, oracle, variant, out_f32, knobs):
     _gemm_case(fp4, oracle, NV, 272, 528, 1280, seed=30 + variant, out_f32=out_f32, layout_gemm=True)
 
 
-@pytest.mark.parametrize("variant", [2, 5, 10, 13, 15])
+@pytest.mark.parametrize("variant", [2, 5, 10, 13, 15, 17])
 def test_gemm_mxfp4_tile_variants_bf16_output_through_the_staged_epilogue(fp4, oracle, variant, knobs):
     """bf16 output goes through the LDS transpose of the epilogue, whose chunk swizzle depends on the wave tile's width
     (64, 96 and 128 columns here); ragged last tile row and column."""
     knobs(variant=variant)
     _gemm_case(fp4, oracle, MX, 272, 528, 1280, seed=80 + variant, out_f32=False, layout_gemm=True)
+
+
+@pytest.mark.parametrize("K", [128, 512, 896, 1024, 1152, 2048, 2176, 4224])
+def test_gemm_mxfp4_eight_stage_ring_with_two_scale_buffers(fp4, oracle, K, knobs):
+    """The 128x128 tile with an eight-stage operand ring (for launches with fewer tiles than compute units): the scale
+    batches alternate between two buffers and are requested eight steps ahead.  K / 128 = 1, 4, 7 (shorter than the ring),
+    8, 9 (one batch and the first step of the second), 16, 17, 33; scales that differ per row-block and K-step."""
+    import torch
+    knobs(variant=17)
+    M, N = 272, 400
+    rng = np.random.default_rng(8000 + K)
+
+    def operand(rows):
+        v = rng.standard_normal((rows, K))
+        v *= 2.0 ** ((np.arange(rows)[:, None] // 16 * 5) % 11 - 5)
+        v *= 2.0 ** ((np.arange(K)[None, :] // 128 * 3) % 7 - 3)
+        return v.astype(np.float32)
+
+    ya, yw = operand(M), operand(N)
+    ac, asc, _ = oracle.quantize(ya, MX)
+    wc, wsc, _ = oracle.quantize(yw, MX)
+    Y, S = oracle.matmul(oracle.dequantize(ac, asc, MX), oracle.dequantize(wc, wsc, MX))
+    say(f"gemm eight-stage ring K={K}")
+    qa = fp4.fp4_rotate_quantize(to_dev(ya), 1, MX, flags=fp4.LAYOUT_GEMM | fp4.INPUT_F32)
+    qw = fp4.fp4_quantize_weights(to_dev(yw), 1, MX, flags=fp4.LAYOUT_GEMM | fp4.INPUT_F32)
+    for fl in (fp4.OUT_F32, 0):
+        out = fp4.fp4_gemm(qa[0], qa[1], None, qw[0], qw[1], None, M, N, K, MX, flags=fl | fp4.A_LAYOUT_GEMM | fp4.W_LAYOUT_GEMM)
+        torch.cuda.synchronize()
+        err = np.abs(np_(out.float()).astype(np.float64) - Y)
+        tol = 1e-3 * S + (0 if fl else np.abs(Y) * 2.0 ** -8)
+        assert np.all(err <= tol), float((err / (1e-3 * S + 1e-300)).max())
 
 
 @pytest.mark.parametrize("grid", [1, 2, 4])
@@ -289,7 +320,7 @@ def test_gemm_mxfp4_persistent_variants_across_ragged_tiles(fp4, oracle, grid, o
     _gemm_case(fp4, oracle, MX, 528, 784, 3072, seed=90 + grid + variant, out_f32=out_f32, layout_gemm=True)
 
 
-@pytest.mark.parametrize("variant", [10, 11, 13, 3, 15])
+@pytest.mark.parametrize("variant", [10, 11, 13, 3, 15, 17])
 @pytest.mark.parametrize("K", [640, 1152, 2176])
 def test_gemm_mxfp4_scales_that_differ_per_row_block_and_k_block(fp4, oracle, variant, K, knobs):
     """The tile kernels fetch scale bytes in batches (eight K-steps of two row-blocks per copy with four stages, four
