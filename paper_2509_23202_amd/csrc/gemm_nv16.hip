@@ -326,24 +326,38 @@ __global__ __launch_bounds__(256) void nv16_reduce_kernel(const float* __restric
 
 // Split-K plan (see the MXFP4 kernels' plan: few tiles and a long K leave the launch bound by the latency of a handful of
 // compute units' loads; here M = 128, N = 8192, K = 28672 is 32 tiles and 411 us, slower than a bf16 GEMM).  128 x 256
-// tiles, two workgroups per compute unit, K-steps of 64 at about 0.93 us each, at least 32 per part, at most eight parts.
-// The number of parts minimises the estimate (microseconds)
-//     10 + K-steps per part x 0.93 + (split only) 3 + splits x M x N x 8 bytes of partials at 4 TB/s
-// and the product is split only for an estimated gain of at least 10 %.
+// tiles, two workgroups per compute unit, at least 32 K-steps of 64 per part, at most eight parts.  A K-step takes about
+// 0.93 us in a workgroup that has its compute unit to itself and half as much again when two share one; a 128 x 128 tile's
+// takes 0.58 us.  The number of parts minimises the estimate (microseconds)
+//     10 + K-steps per part x step time + (split only) 3 + splits x M x N x 8 bytes of partials at 8 TB/s
+// (the partials are written and read back within microseconds: most of them never leave the last-level cache)
+// and the product is split only for an estimated gain of at least 10 % over the unsplit launch (which uses the narrow
+// tiles when the wide ones are at most a round and a quarter: see launch_gemm_nv16).
+bool nv16_narrow_tiles(int64_t tiles_w, int cus)
+{
+    return 4 * tiles_w <= 5 * (int64_t)cus;
+}
+
 void plan_split_k_nv16(int64_t M, int64_t N, int64_t K, int cus, int* splits, int* steps)
 {
     *splits = 1;
     *steps = 0;
-    const int64_t tiles = ((M + 127) / 128) * ((N + 255) / 256);
+    const int64_t tiles_m = (M + 127) / 128;
+    const int64_t tiles = tiles_m * ((N + 255) / 256);
     const int64_t slots = 2 * (int64_t)cus;
     const int kh = (int)(K >> 6);
     const int64_t s_max = std::min<int64_t>(std::min<int64_t>(slots / tiles, kh / 32), 8);
-    double best = 0.9 * (10.0 + kh * 0.93);
+    // every part is as slow as the slowest compute unit's, and that one runs two workgroups as soon as there are more
+    // workgroups than compute units
+    auto shared = [&](int64_t wgs) { return wgs <= cus ? 1.0 : 1.47; };
+    double unsplit = 10.0 + kh * 0.93 * shared(tiles);
+    if (nv16_narrow_tiles(tiles, cus)) unsplit = 10.0 + kh * 0.58 * shared(tiles_m * ((N + 127) / 128));
+    double best = 0.9 * unsplit;
     for (int64_t s = 2; s <= s_max; ++s) {
         const int st = (int)(((kh + s - 1) / s + 7) / 8 * 8);
         const int64_t n = (kh + st - 1) / st;
         if (n < 2) continue;
-        const double t = 10.0 + st * 0.93 + 3.0 + (double)n * (double)M * (double)N * 8.0 / 4.0e6;
+        const double t = 10.0 + st * 0.93 * shared(n * tiles) + 3.0 + (double)n * (double)M * (double)N * 8.0 / 8.0e6;
         if (t < best) {
             best = t;
             *splits = (int)n;
@@ -468,6 +482,10 @@ hipError_t launch_gemm_nv16(const void* a_codes, const void* a_scales, const flo
     }
     g.n_first = 0;
     g.n_cols = (int)N;
+    // less than a round and a quarter of wide tiles (one per compute unit and a few doubled up, or compute units left
+    // idle): 128 x 128 tiles spread the same work twice as finely (N = 10240, K = 8192 at M = 512: 136 -> 119 us;
+    // N = 8192, K = 28672 at M = 512 without the split-K workspace: 412 -> 280 us)
+    if (nv16_narrow_tiles(tiles_w, cus)) return launch_tiles<128>(g, out_f32, st);
     return launch_tiles<256>(g, out_f32, st);
 }
 

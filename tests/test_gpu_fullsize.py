@@ -227,3 +227,12 @@ def test_nvfp4_two_launch_split_of_the_tile_grid(fp4, oracle, M, N):
     that can be the seam between the two launches are sampled on purpose."""
     seams = [c * 256 + d for c in range(1, (N + 255) // 256) for d in (-1, 0)]
     check_layer(fp4, oracle, inputs.RECIPES[4], M, 512, N, NV, 16, n_m=48, n_n=96, salt=M, extra_n=seams)
+
+
+@pytest.mark.parametrize("M,N", [(1024, 10240), (1000, 10200), (512, 8192)])
+def test_nvfp4_narrow_tiles_when_wide_ones_are_about_one_round(fp4, oracle, M, N):
+    """Between one 128 x 256 tile per compute unit and a round and a quarter of them the whole product runs as
+    128 x 128 tiles (640, 640 with ragged edges, and 256 of them here); columns either side of every multiple of 128
+    near the middle and the end of N are sampled on purpose."""
+    seams = [c * 128 + d for c in (1, 2, N // 256, N // 128 - 1, (N - 1) // 128) for d in (-1, 0) if 0 <= c * 128 + d < N]
+    check_layer(fp4, oracle, inputs.RECIPES[4], M, 512, N, NV, 16, n_m=48, n_n=96, salt=M + 5, extra_n=seams)
