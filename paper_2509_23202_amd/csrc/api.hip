@@ -235,11 +235,12 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
     const bool wide_mx = fmt == FP4MR_MXFP4 && M > 16 && N >= 16384 && K > 4096;
     // Optional split-K room behind what the call needs (FP4MR_OP_GEMM_SPLIT_K): used when the caller passed that much
     void* partial = nullptr;
-    if (M > 64 && variant == 0) {
+    const bool few = variant == 0 && !wide_mx && gemm_skinny_takes(M, N, K, (int)fmt);
+    if (M > 64 && variant == 0 && !few) {
         const size_t extra = fmt == FP4MR_MXFP4 ? gemm_mx_split_k_bytes(M, N, K) : nv16_split_k_bytes(M, N, K);
         if (extra && workspace && aligned16(workspace) && workspace_bytes >= align256(need) + extra) partial = static_cast<char*>(workspace) + align256(need);
     }
-    if (M <= 64 && variant == 0 && !wide_mx)
+    if (few)
         e = launch_gemm_skinny(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, M, N, K, (int)fmt, out, out_f32, alpha, st);
     else if (fmt == FP4MR_MXFP4)
         e = launch_gemm_mxfp4(a_codes, a_scales, w_codes, w_scales, M, N, K, out, out_f32, variant, alpha, partial, st);
@@ -340,7 +341,7 @@ size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t 
         // NVFP4 with more than 64 tokens: the activations are dequantized once to fp16 (2 bytes per element)
         if (fmt == FP4MR_NVFP4 && M > 64) n += align256(nv16_workspace_bytes(M, K));
         // what fp4_gemm needs, plus -- optional -- the fp32 partials of a split-K run where the shape has one
-        if (op == FP4MR_OP_GEMM_SPLIT_K && M > 64) {
+        if (op == FP4MR_OP_GEMM_SPLIT_K && M > 64 && !gemm_skinny_takes(M, N, K, (int)fmt)) {
             const size_t extra = fmt == FP4MR_MXFP4 ? gemm_mx_split_k_bytes(M, N, K) : nv16_split_k_bytes(M, N, K);
             if (extra) n = align256(n) + extra;
         }

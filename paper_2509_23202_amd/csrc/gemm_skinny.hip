@@ -1,4 +1,4 @@
-// W4A4 GEMM for few tokens (M <= 64): the weight-streaming regime (arXiv 2509.23202, appendix on inference regimes:
+// W4A4 GEMM for few tokens (M <= 64, and up to 128 on narrow MXFP4 layers): the weight-streaming regime (arXiv 2509.23202, appendix on inference regimes:
 // at small batch the layer is memory-bound).  out[m,n] = sum_k Ahat[m,k] * What[n,k], both formats.
 //
 // The weights are read exactly once, straight from global memory into registers: a workgroup owns one 16-column
@@ -36,6 +36,7 @@ struct SkinnyArgs {
     void* out;
     int M, N, K;
     float alpha;  // MXFP4: factor on the result (powers of 4/3 for operands whose scales carry the tensor-level 4/3), else 1
+    int parts;    // persistent kernel: 2 = the token blocks are shared out between two sets of workgroups (65 to 128 tokens), else 1
 };
 
 template <int FMT, int MT, bool OUT_F32>
@@ -296,7 +297,15 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
     const int k_begin = min(wave * per, KC), k_end = min(k_begin + per, KC);
     const int nb = (k_end - k_begin + U - 1) / U;       // batches per row-block for this wave (0 for a wave without a K share)
     const int n_rb = (g.N + 15) >> 4;
-    const int G = (int)gridDim.x;
+    // Two parts: workgroups 16 j .. 16 j + 7 are walkers 8 j .. 8 j + 7 of the first MT token blocks and the next eight the same
+    // walkers of the second MT token blocks, so the two workgroups that stream the same row-block of W start on the same XCD
+    // (workgroups go to the eight XCDs in turn) one dispatch apart: the second finds the fragments in that XCD's L2.
+    int walker = (int)blockIdx.x, G = (int)gridDim.x, tb0 = 0;
+    if (g.parts == 2) {
+        walker = (int)(((blockIdx.x >> 4) << 3) | (blockIdx.x & 7));
+        G = (int)(gridDim.x >> 1);
+        tb0 = (int)((blockIdx.x >> 3) & 1) * MT;
+    }
 
     // Buffer resources: the only per-lane addresses are 16 / 4 / 2 times the lane id, every fragment's position is a scalar
     // offset (64-bit per-load addresses in vector registers would cost the occupancy this kernel lives on).
@@ -341,7 +350,7 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
         if (nb > 0) {
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
-                const int mrb = min(t, a_rbs - 1);  // (a token block past the end re-reads the last one and is not stored)
+                const int mrb = min(tb0 + t, a_rbs - 1);  // (a token block past the end re-reads the last one and is not stored)
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int kc = min(k_begin + u, k_end - 1);
@@ -402,7 +411,7 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
     int prev_stores = 0;  // output stores this wave issued for the row-block before the current one (uniform)
     Batch buf0, buf1;
     int first = 0;
-    int rb = (int)blockIdx.x;
+    int rb = walker;
     if (nb > 0 && rb < n_rb) load_batch(buf0, rb, k_begin);
     for (int it = 0; rb < n_rb; ++it, rb += G) {
         v4f acc[MT];
@@ -449,7 +458,7 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
         const int r = wave * 32 + (lane & 31);
         const int l = r >> 2, v = r & 3;
         const int n = rb * 16 + (l >> 4) * 4 + v;
-        // The wave's 32 outputs of a token block are rows t * 16 + 8 (wave % 2) .. + 7 and columns rb * 16 + 4 (wave / 2) .. + 3:
+        // The wave's 32 outputs of token block tb0 + t are rows 16 (tb0 + t) + 8 (wave % 2) .. + 7 and columns rb * 16 + 4 (wave / 2) .. + 3:
         // one store instruction per token block that has any of them inside the matrix (uniform), none otherwise.
         const bool cols_in = rb * 16 + (wave >> 1) * 4 < g.N;
         prev_stores = 0;
@@ -459,8 +468,8 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
 #pragma unroll
             for (int w = 0; w < kSkinnyWaves; ++w) sum += partial[it & 1][w][t][r];
             sum *= ts;
-            const int m = t * 16 + (l & 15);
-            if (cols_in && t * 16 + (wave & 1) * 8 < g.M) {  // (uniform)
+            const int m = (tb0 + t) * 16 + (l & 15);
+            if (cols_in && (tb0 + t) * 16 + (wave & 1) * 8 < g.M) {  // (uniform)
                 ++prev_stores;
                 if (lane < 32 && m < g.M && n < g.N) {
                     if constexpr (OUT_F32) static_cast<float*>(g.out)[(int64_t)m * g.N + n] = sum;
@@ -514,6 +523,26 @@ bool try_stream(const SkinnyArgs& g, bool out_f32, int per, hipStream_t st, hipE
     else hipLaunchKernelGGL((gemm_stream_kernel<FMT, false, U, XRES, MT>), grid, block, 0, st, g);
     *err = hipGetLastError();
     return true;
+}
+
+// 65 to 128 tokens, MXFP4, K <= 4096: two sets of persistent workgroups, each with half of the token blocks resident in
+// registers.  W passes through every XCD's L2 once and is read from there twice; nothing of X is read again.  The walkers of a
+// part share the row-blocks evenly (as many rounds as the resident workgroups need, then the fewest walkers that do it in
+// that many rounds).
+template <int MT>
+hipError_t launch_stream_two_parts(SkinnyArgs g, bool out_f32, hipStream_t st)
+{
+    const int n_rb = (g.N + 15) / 16;
+    int cap = stream_cus() * stream_resident<0, 4, true, MT>(out_f32);
+    if (options().gemm_grid > 0 && options().gemm_grid < cap) cap = options().gemm_grid;
+    const int per_part = std::max(cap / 2, 8);
+    const int rounds = (n_rb + per_part - 1) / per_part;
+    const int walkers = ((n_rb + rounds - 1) / rounds + 7) / 8 * 8;
+    g.parts = 2;
+    const dim3 grid((unsigned)(2 * walkers)), block(kSkinnyWaves * 64);
+    if (out_f32) hipLaunchKernelGGL((gemm_stream_kernel<0, true, 4, true, MT>), grid, block, 0, st, g);
+    else hipLaunchKernelGGL((gemm_stream_kernel<0, false, 4, true, MT>), grid, block, 0, st, g);
+    return hipGetLastError();
 }
 
 template <int FMT, int MT>
@@ -574,11 +603,34 @@ hipError_t launch_fmt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
         case 2: return launch_tokens<FMT, 2>(g, out_f32, st);
         case 3: return launch_tokens<FMT, 3>(g, out_f32, st);
         case 4: return launch_tokens<FMT, 4>(g, out_f32, st);
+        case 5:
+        case 6:
+            if constexpr (FMT == 0) return launch_stream_two_parts<3>(g, out_f32, st);
+            return hipErrorInvalidValue;
+        case 7:
+        case 8:
+            if constexpr (FMT == 0) return launch_stream_two_parts<4>(g, out_f32, st);
+            return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }
 }
 
 }  // namespace
+
+// 65 to 128 tokens: MXFP4 with a wave's share of K resident in registers (K <= 4096), on layers narrow enough that the
+// tile kernels' fixed cost per launch (12-14 us at K = 4096, 8-10 at K = 2048) exceeds what the persistent kernel spends
+// per row-block (about 3.4 us + 0.7 us per 1024 output columns).  Measured, cold weights, M = 96, tiles -> two parts:
+// K = 4096: N = 4096 12.6 -> 6.4 us, 6144 12.9 -> 7.8, 8192 12.9 -> 9.5, 14336 14.5 -> 13.8, 28672 17.7 -> 25.0;
+// K = 2048: N = 4096 8.1 -> 6.0, 6144 9.3 -> 7.3, 8192 9.4 -> 8.7, 14336 10.1 -> 12.6; K = 1024: level or slower.
+bool gemm_skinny_takes(int64_t M, int64_t N, int64_t K, int fmt)
+{
+    if (M <= 64) return true;
+    if (fmt != 0 || M > 128) return false;
+    const int64_t per = ((K >> 7) + kSkinnyWaves - 1) / kSkinnyWaves;  // fragments of K per wave
+    if (per == 4) return N <= 12288;
+    if (per == 2 || per == 3) return N <= 6144;
+    return false;
+}
 
 hipError_t launch_gemm_skinny(const void* a_codes, const void* a_scales, const float* a_ts, const void* w_codes,
                               const void* w_scales, const float* w_ts, int64_t M, int64_t N, int64_t K, int fmt, void* out,

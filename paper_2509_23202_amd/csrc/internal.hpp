@@ -69,7 +69,9 @@ hipError_t launch_gemm_nv16(const void* a_codes, const void* a_scales, const flo
 // fp32 partials of a split-K run of that product (`partial`, may be null: then it is never split); 0 = not split
 size_t nv16_split_k_bytes(int64_t M, int64_t N, int64_t K);
 
-// few-token (M <= 64) weight-streaming GEMM, both formats, operands in GEMM layout
+// few-token weight-streaming GEMM, both formats, operands in GEMM layout: every shape up to 64 tokens, and the shapes
+// gemm_skinny_takes() accepts above that
+bool gemm_skinny_takes(int64_t M, int64_t N, int64_t K, int fmt);
 hipError_t launch_gemm_skinny(const void* a_codes, const void* a_scales, const float* a_ts, const void* w_codes,
                               const void* w_scales, const float* w_ts, int64_t M, int64_t N, int64_t K, int fmt, void* out,
                               bool out_f32, float alpha, hipStream_t st);

@@ -368,6 +368,18 @@ def test_gemm_mxfp4_persistent_weight_streaming_kernel(fp4, oracle, grid, M, N, 
     _gemm_case(fp4, oracle, MX, M, N, K, seed=300 + grid + K, out_f32=out_f32, layout_gemm=True)
 
 
+@pytest.mark.parametrize("grid,M,N,K,out_f32", [(0, 65, 400, 4096, False), (0, 128, 1000, 4096, True), (16, 96, 2056, 2048, False),
+                                                (16, 100, 1160, 1152, True), (1, 81, 520, 3072, False), (0, 113, 6144, 4096, False),
+                                                (16, 128, 4104, 1536, True), (0, 72, 12288, 3200, False)])
+def test_gemm_mxfp4_65_to_128_tokens_on_two_sets_of_persistent_workgroups(fp4, oracle, grid, M, N, K, out_f32, knobs):
+    """65 to 128 tokens on a narrow MXFP4 layer with 1024 < K <= 4096: the persistent weight-streaming kernel runs as two sets
+    of workgroups, each with three or four 16-token blocks of X in registers (five to eight blocks in all: the second set's
+    last block can lie past the end of M and is then neither loaded nor stored); a grid cap makes 8 walkers per set take many
+    row-blocks each; ragged N, waves without a K share (K / 128 = 9, 12), fp32 and bf16 output."""
+    knobs(grid=grid)
+    _gemm_case(fp4, oracle, MX, M, N, K, seed=500 + M + K, out_f32=out_f32, layout_gemm=True)
+
+
 @pytest.mark.parametrize("M,N,K,out_f32", [(1, 5000, 512, True), (16, 4944, 1152, False), (9, 5136, 128, False), (16, 8200, 640, True),
                                            (17, 5000, 512, False), (32, 4944, 1152, True), (40, 5136, 384, False), (64, 5000, 640, False),
                                            (50, 8200, 128, True)])
