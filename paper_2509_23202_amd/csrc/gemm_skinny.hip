@@ -328,35 +328,39 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
         v4i wf[U], xf[XRES ? 1 : U];
         uint32_t sw[U], sx[XRES ? 1 : U];
     };
-    // loads per batch and wave: a compile-time constant (the vmcnt bookkeeping below counts on it)
-    constexpr int LPB = (XRES ? 2 : 4) * U;
-    auto load_batch = [&](Batch& b, int rb, int kc0) {
-        const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(g.w_codes + (int64_t)rb * KC * 1024, (int64_t)KC * 1024);
-        const __amdgpu_buffer_rsrc_t rs_ws = make_rsrc(g.w_scales + (int64_t)rb * sc_per_rb * SCB, (int64_t)sc_per_rb * SCB);
+    // Every batch is requested UNCONDITIONALLY: a batch that does not exist (past the last row-block, or of a wave without a
+    // share of K) is requested through buffer resources of zero size, whose loads return zeros without touching memory.
+    // The compiler waits for loaded registers by counting the memory operations issued behind them, and at a merge of
+    // control flow it assumes the fewest: a prefetch issued under a condition counts as not issued, and the wait in front of
+    // the current batch's first product then also waits for the batch just requested -- the prefetch would overlap nothing.
+    const __amdgpu_buffer_rsrc_t rs_none = make_rsrc(g.a_codes, 0);
+    auto load_batch = [&](Batch& b, int rb, int kc0, bool valid) {
+        const int rbv = valid ? rb : 0;
+        const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(g.w_codes + (int64_t)rbv * KC * 1024, valid ? (int64_t)KC * 1024 : 0);
+        const __amdgpu_buffer_rsrc_t rs_ws = make_rsrc(g.w_scales + (int64_t)rbv * sc_per_rb * SCB, valid ? (int64_t)sc_per_rb * SCB : 0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int kc = min(kc0 + u, k_end - 1);  // the tail repeats the last fragment; its product is skipped
+            const int kc = max(min(kc0 + u, k_end - 1), 0);  // the tail repeats the last fragment; its product is skipped
             b.wf[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rs_w, lane16, kc * 1024, 2));  // streamed once
             b.sw[u] = load_scale(rs_ws, kc);
             if constexpr (!XRES) {
-                b.xf[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rs_x, lane16, kc * 1024, 0));
-                b.sx[u] = load_scale(rs_xs, kc);
+                b.xf[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(valid ? rs_x : rs_none, lane16, kc * 1024, 0));
+                b.sx[u] = load_scale(valid ? rs_xs : rs_none, kc);
             }
         }
     };
     v4i xres[MT][XRES ? U : 1];
     uint32_t sxres[MT][XRES ? U : 1];
+    const bool mine = nb > 0;  // this wave has a share of K
     if constexpr (XRES) {
-        if (nb > 0) {
 #pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                const int mrb = min(tb0 + t, a_rbs - 1);  // (a token block past the end re-reads the last one and is not stored)
+        for (int t = 0; t < MT; ++t) {
+            const int mrb = min(tb0 + t, a_rbs - 1);  // (a token block past the end re-reads the last one and is not stored)
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int kc = min(k_begin + u, k_end - 1);
-                    xres[t][u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rs_x, lane16, mrb * KC * 1024 + kc * 1024, 0));
-                    sxres[t][u] = load_scale(rs_xs, kc, mrb * sc_per_rb * SCB);
-                }
+            for (int u = 0; u < U; ++u) {
+                const int kc = max(min(k_begin + u, k_end - 1), 0);
+                xres[t][u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(mine ? rs_x : rs_none, lane16, mrb * KC * 1024 + kc * 1024, 0));
+                sxres[t][u] = load_scale(mine ? rs_xs : rs_none, kc, mrb * sc_per_rb * SCB);
             }
         }
     }
@@ -391,62 +395,9 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
     float ts = g.alpha;
     if constexpr (FMT == 1) ts = (*g.a_ts) * (*g.w_ts);
 
-    // The two batch buffers are addressed with compile-time indices only (a run-time index would put them in scratch
-    // memory): a row-block's batches alternate between them, two per trip of the loop, and a row-block with an odd number
-    // of batches hands the next one the other buffer first (`first`, uniform).
-    // vmcnt(LPB + stores): the batch just requested, and the output stores issued in front of it, may stay in flight.  The
-    // count has to be exact -- a store that no lane of the wave takes part in (token rows or columns past the end) is not
-    // in flight, and counting it would let the wait return with a load of the current batch still outstanding.
-    auto wait_allowing = [&](int stores) {
-        static_assert(LPB + MT < 64, "vmcnt is a 6-bit counter");
-        switch (stores) {
-            case 0: __builtin_amdgcn_s_waitcnt((LPB & 15) | ((LPB >> 4) << 14) | 0x0f70); break;
-            case 1: __builtin_amdgcn_s_waitcnt(((LPB + 1) & 15) | (((LPB + 1) >> 4) << 14) | 0x0f70); break;
-            case 2: __builtin_amdgcn_s_waitcnt(((LPB + (MT >= 2 ? 2 : 0)) & 15) | (((LPB + (MT >= 2 ? 2 : 0)) >> 4) << 14) | 0x0f70); break;
-            case 3: __builtin_amdgcn_s_waitcnt(((LPB + (MT >= 3 ? 3 : 0)) & 15) | (((LPB + (MT >= 3 ? 3 : 0)) >> 4) << 14) | 0x0f70); break;
-            default: __builtin_amdgcn_s_waitcnt(((LPB + (MT >= 4 ? 4 : 0)) & 15) | (((LPB + (MT >= 4 ? 4 : 0)) >> 4) << 14) | 0x0f70); break;
-        }
-    };
-    static_assert(MT <= 4, "wait_allowing counts up to four stores");
-    int prev_stores = 0;  // output stores this wave issued for the row-block before the current one (uniform)
-    Batch buf0, buf1;
-    int first = 0;
-    int rb = walker;
-    if (nb > 0 && rb < n_rb) load_batch(buf0, rb, k_begin);
-    for (int it = 0; rb < n_rb; ++it, rb += G) {
-        v4f acc[MT];
-#pragma unroll
-        for (int t = 0; t < MT; ++t) acc[t] = v4f{0.f, 0.f, 0.f, 0.f};
-        // one batch: request the one after it into `nxt`, wait for `cur`, multiply
-        auto step = [&](Batch& cur, Batch& nxt, int b) {
-            const bool more_here = b + 1 < nb, more_rb = rb + G < n_rb;
-            if (more_here) load_batch(nxt, rb, k_begin + (b + 1) * U);
-            else if (more_rb) load_batch(nxt, rb + G, k_begin);
-            // memory operations retire in issue order: everything but the batch just requested may be waited for (nothing
-            // else was issued behind the current batch except, before a row-block's first batch, the previous row-block's
-            // MT output stores)
-            if (more_here || more_rb) {
-                if (b == 0) wait_allowing(prev_stores);
-                else wait_allowing(0);
-            } else {
-                __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
-            }
-            consume(cur, k_begin + b * U, acc);
-        };
-        if (first == 0) {
-            for (int b = 0; b < nb; b += 2) {
-                step(buf0, buf1, b);
-                if (b + 1 < nb) step(buf1, buf0, b + 1);
-            }
-        } else {
-            for (int b = 0; b < nb; b += 2) {
-                step(buf1, buf0, b);
-                if (b + 1 < nb) step(buf0, buf1, b + 1);
-            }
-        }
-        first ^= nb & 1;
-        // partial sums meet in LDS (two buffers, alternating: a buffer is written again two row-blocks later, behind the
-        // next row-block's barrier, when every wave has long finished reading it)
+    // partial sums meet in LDS (two buffers, alternating: a buffer is written again two row-blocks later, behind the next
+    // row-block's barrier, when every wave has long finished reading it)
+    auto reduce_store = [&](const v4f (&acc)[MT], int rb, int it) {
 #pragma unroll
         for (int t = 0; t < MT; ++t) *reinterpret_cast<v4f*>(&partial[it & 1][wave][t][lane * 4]) = acc[t];
         __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the LDS writes have landed
@@ -458,10 +409,6 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
         const int r = wave * 32 + (lane & 31);
         const int l = r >> 2, v = r & 3;
         const int n = rb * 16 + (l >> 4) * 4 + v;
-        // The wave's 32 outputs of token block tb0 + t are rows 16 (tb0 + t) + 8 (wave % 2) .. + 7 and columns rb * 16 + 4 (wave / 2) .. + 3:
-        // one store instruction per token block that has any of them inside the matrix (uniform), none otherwise.
-        const bool cols_in = rb * 16 + (wave >> 1) * 4 < g.N;
-        prev_stores = 0;
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
             float sum = 0.0f;
@@ -469,13 +416,77 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
             for (int w = 0; w < kSkinnyWaves; ++w) sum += partial[it & 1][w][t][r];
             sum *= ts;
             const int m = (tb0 + t) * 16 + (l & 15);
-            if (cols_in && (tb0 + t) * 16 + (wave & 1) * 8 < g.M) {  // (uniform)
-                ++prev_stores;
-                if (lane < 32 && m < g.M && n < g.N) {
-                    if constexpr (OUT_F32) static_cast<float*>(g.out)[(int64_t)m * g.N + n] = sum;
-                    else static_cast<__bf16*>(g.out)[(int64_t)m * g.N + n] = (__bf16)sum;
+            if (lane < 32 && m < g.M && n < g.N) {
+                if constexpr (OUT_F32) static_cast<float*>(g.out)[(int64_t)m * g.N + n] = sum;
+                else static_cast<__bf16*>(g.out)[(int64_t)m * g.N + n] = (__bf16)sum;
+            }
+        }
+    };
+
+    // The batch buffers are addressed with compile-time indices only (a run-time index would put them in scratch memory).
+    // No explicit vmcnt waits: the compiler's own, in front of the first use of each loaded register, are exact here
+    // because every load of the loop is unconditional (output stores sit under conditions and count as not issued, which
+    // makes a wait a few operations stricter than necessary).
+    if constexpr (XRES) {
+        // A row-block is one batch per wave.  One token block: two buffers (121 registers, two workgroups per compute
+        // unit).  Several resident token blocks take 150-170 registers, one workgroup per compute unit, so there THREE
+        // buffers: the loads of two row-blocks ahead are in flight while one is multiplied and reduced.
+        constexpr int NBUF = MT >= 2 ? 3 : 2;
+        Batch b0, b1, b2;
+        int rb = walker, it = 0;
+        load_batch(b0, rb, k_begin, mine && rb < n_rb);
+        if constexpr (NBUF == 3) load_batch(b1, rb + G, k_begin, mine && rb + G < n_rb);
+        auto step = [&](Batch& cur, Batch& free) {
+            const int ahead = rb + (NBUF - 1) * G;
+            load_batch(free, ahead, k_begin, mine && ahead < n_rb);
+            v4f acc[MT];
+#pragma unroll
+            for (int t = 0; t < MT; ++t) acc[t] = v4f{0.f, 0.f, 0.f, 0.f};
+            consume(cur, k_begin, acc);
+            reduce_store(acc, rb, it);
+            ++it;
+            rb += G;
+        };
+        while (rb < n_rb) {
+            if constexpr (NBUF == 3) {
+                step(b0, b2);
+                if (rb < n_rb) step(b1, b0);
+                if (rb < n_rb) step(b2, b1);
+            } else {
+                step(b0, b1);
+                if (rb < n_rb) step(b1, b0);
+            }
+        }
+    } else {
+        // Several batches per row-block: they alternate between two buffers, two per trip of the inner loop, and a
+        // row-block with an odd number of batches hands the next one the other buffer first (`first`, uniform).
+        Batch buf0, buf1;
+        int first = 0;
+        int rb = walker;
+        load_batch(buf0, rb, k_begin, mine && rb < n_rb);
+        for (int it = 0; rb < n_rb; ++it, rb += G) {
+            v4f acc[MT];
+#pragma unroll
+            for (int t = 0; t < MT; ++t) acc[t] = v4f{0.f, 0.f, 0.f, 0.f};
+            // one batch: request the one after it (of this row-block, else the first of the next) into `nxt`, multiply `cur`
+            auto step = [&](Batch& cur, Batch& nxt, int b) {
+                const bool more_here = b + 1 < nb;
+                load_batch(nxt, more_here ? rb : rb + G, more_here ? k_begin + (b + 1) * U : k_begin, mine && (more_here || rb + G < n_rb));
+                consume(cur, k_begin + b * U, acc);
+            };
+            if (first == 0) {
+                for (int b = 0; b < nb; b += 2) {
+                    step(buf0, buf1, b);
+                    if (b + 1 < nb) step(buf1, buf0, b + 1);
+                }
+            } else {
+                for (int b = 0; b < nb; b += 2) {
+                    step(buf1, buf0, b);
+                    if (b + 1 < nb) step(buf0, buf1, b + 1);
                 }
             }
+            first ^= nb & 1;
+            reduce_store(acc, rb, it);
         }
     }
 }
@@ -488,36 +499,24 @@ int stream_cus()
     return cus;
 }
 
-// workgroups of the persistent kernel that are resident at once on one compute unit: asked of the runtime once per kernel
-template <int FMT, int U, bool XRES, int MT>
-int stream_resident(bool out_f32)
-{
-    static int resident[2] = {0, 0};
-    int& per_cu = resident[out_f32 ? 1 : 0];
-    if (per_cu == 0) {
-        int n = 0;
-        const hipError_t e = out_f32 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, gemm_stream_kernel<FMT, true, U, XRES, MT>, kSkinnyWaves * 64, 0)
-                                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, gemm_stream_kernel<FMT, false, U, XRES, MT>, kSkinnyWaves * 64, 0);
-        per_cu = (e == hipSuccess && n > 0) ? n : 1;
-    }
-    return per_cu;
-}
-
 // MXFP4, up to 16 tokens (MT = 1) or, with the X fragments resident, up to 64.  Returns false (nothing launched) where a
-// one-shot kernel is the better choice: the persistent kernel wins by keeping loads in flight across batches and row-blocks
-// (N = 28672, K = 4096: 10.9 us against 13.7; N = 4096, K = 14336: 7.8 against 8.4), which needs either several batches
-// per row-block or more row-blocks than resident workgroups; a layer that fits the chip in one go (N <= 8192 at K = 4096)
-// is launch-bound and 0.1-0.4 us faster with the one-shot kernel's higher occupancy.  NVFP4 stays with the one-shot
-// kernels: its in-register dequantization needs the registers that the second batch buffer takes (one workgroup per
-// compute unit: 68 us against 54 on N = 57344, K = 8192).
+// one-shot kernel is the better choice: the persistent kernel wins by keeping loads in flight across batches and row-blocks,
+// which needs either several batches per row-block or more row-blocks than workgroups; with one token block, a layer of at
+// most one row-block per compute unit (N <= 4096) is launch-bound and 0.1-0.4 us faster with the one-shot kernel's higher
+// occupancy.  With several token blocks the persistent kernel is taken always: the one-shot kernels re-read X from L2 per
+// W fragment.  NVFP4 stays with the one-shot kernels: its in-register dequantization needs the registers that the second
+// batch buffer takes (one workgroup per compute unit: 68 us against 54 on N = 57344, K = 8192).
 template <int FMT, int U, bool XRES, int MT = 1>
 bool try_stream(const SkinnyArgs& g, bool out_f32, int per, hipStream_t st, hipError_t* err)
 {
     const int n_rb = (g.N + 15) / 16;
-    int cap = stream_cus() * stream_resident<FMT, U, XRES, MT>(out_f32);
+    // One workgroup per compute unit, also where the registers would let two or three be resident: fewer, longer walks
+    // measured faster at every shape (K = 4096, cold weights, 256 against 512 workgroups: M = 16, N = 6144 4.9 us against 5.5,
+    // N = 14336 7.7 against 8.5, N = 28672 12.1 against 12.7; M = 32, N = 6144 6.1 against 7.1).
+    int cap = stream_cus();
     // (the grid-cap option, a testing aid: a small grid makes every workgroup walk many row-blocks)
     if (options().gemm_grid > 0 && options().gemm_grid < cap) cap = options().gemm_grid;
-    if (per <= U && n_rb <= cap) return false;
+    if (MT == 1 && per <= U && n_rb <= cap) return false;
     const dim3 grid((unsigned)std::min(n_rb, cap)), block(kSkinnyWaves * 64);
     if (out_f32) hipLaunchKernelGGL((gemm_stream_kernel<FMT, true, U, XRES, MT>), grid, block, 0, st, g);
     else hipLaunchKernelGGL((gemm_stream_kernel<FMT, false, U, XRES, MT>), grid, block, 0, st, g);
@@ -533,7 +532,7 @@ template <int MT>
 hipError_t launch_stream_two_parts(SkinnyArgs g, bool out_f32, hipStream_t st)
 {
     const int n_rb = (g.N + 15) / 16;
-    int cap = stream_cus() * stream_resident<0, 4, true, MT>(out_f32);
+    int cap = stream_cus();
     if (options().gemm_grid > 0 && options().gemm_grid < cap) cap = options().gemm_grid;
     const int per_part = std::max(cap / 2, 8);
     const int rounds = (n_rb + per_part - 1) / per_part;
