@@ -228,11 +228,11 @@ fp4mr_status_t fp4_gemm(const void* a_codes, const void* a_scales, const float* 
     }
     const bool out_f32 = (flags & FP4MR_OUT_F32) != 0;
     const float alpha = scale43_factor(flags);
-    // Few tokens: the weight-streaming kernels, except MXFP4 with more than one 16-token block, a very wide layer and
-    // K > 4096, where the one-shot kernels' per-token-block re-reads of the activations from L2 cost more than the 64 x 256
-    // tile kernel does (N = 28672, K = 8192, M = 64: 38.6 us against 34.5).  Up to K = 4096 the persistent kernel keeps all
-    // token blocks of X in registers and wins (N = 28672, K = 4096, M = 32 / 64: 15.2 / 17.6 us against 18.4 / 18.7).
-    const bool wide_mx = fmt == FP4MR_MXFP4 && M > 16 && N >= 16384 && K > 4096;
+    // Few tokens: the weight-streaming kernels, except MXFP4 with more than two 16-token blocks on a very wide layer with
+    // K > 4096, where the 64 x 256 tile kernel's time hardly grows with the token count and the streaming kernels' does
+    // (N = 57344, K = 14336, M = 48: 87 us against 113; K = 6144, M = 64: 39 against 45; below N = 40960 the streaming
+    // kernels win at every token count: N = 28672, K = 8192, M = 64: 27.7 us against 38.4).
+    const bool wide_mx = fmt == FP4MR_MXFP4 && M > 32 && N >= 40960 && K > 4096;
     // Optional split-K room behind what the call needs (FP4MR_OP_GEMM_SPLIT_K): used when the caller passed that much
     void* partial = nullptr;
     const bool few = variant == 0 && !wide_mx && gemm_skinny_takes(M, N, K, (int)fmt);

@@ -20,6 +20,7 @@
 #include "nv_dequant.hpp"
 
 #include <algorithm>
+#include <type_traits>
 
 namespace fp4mr {
 namespace {
@@ -36,7 +37,7 @@ struct SkinnyArgs {
     void* out;
     int M, N, K;
     float alpha;  // MXFP4: factor on the result (powers of 4/3 for operands whose scales carry the tensor-level 4/3), else 1
-    int parts;    // persistent kernel: 2 = the token blocks are shared out between two sets of workgroups (65 to 128 tokens), else 1
+    int parts;    // persistent kernel: > 1 = the token blocks are shared out between that many sets of workgroups, else 0 or 1
 };
 
 template <int FMT, int MT, bool OUT_F32>
@@ -284,10 +285,11 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nt_kernel(Skinn
 // row-block its X fragments are loaded once and stay in registers: a batch is then W only.
 // MT > 1 (XRES only): up to MT 16-token blocks of X stay in registers, a W fragment meets all of them, and nothing of X is
 // read again for the rest of the launch -- the one-shot kernels fetch MT X fragments from L2 per W fragment.
-template <int FMT, bool OUT_F32, int U, bool XRES, int MT = 1>
+template <int FMT, bool OUT_F32, int U, bool XRES, int MT = 1, int NB = 1>
 __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyArgs g)
 {
     static_assert(MT == 1 || XRES, "several token blocks only with the X fragments resident");
+    static_assert(NB == 1 || XRES, "a static number of batches per row-block only with the X fragments resident");
     __shared__ float partial[2][kSkinnyWaves][MT][256];
 
     const int lane = threadIdx.x & 63;
@@ -297,14 +299,16 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
     const int k_begin = min(wave * per, KC), k_end = min(k_begin + per, KC);
     const int nb = (k_end - k_begin + U - 1) / U;       // batches per row-block for this wave (0 for a wave without a K share)
     const int n_rb = (g.N + 15) >> 4;
-    // Two parts: workgroups 16 j .. 16 j + 7 are walkers 8 j .. 8 j + 7 of the first MT token blocks and the next eight the same
-    // walkers of the second MT token blocks, so the two workgroups that stream the same row-block of W start on the same XCD
-    // (workgroups go to the eight XCDs in turn) one dispatch apart: the second finds the fragments in that XCD's L2.
+    // Several sets of workgroups (g.parts = P > 1), each with its own MT token blocks: workgroups 8 P j .. 8 P j + 7 are
+    // walkers 8 j .. 8 j + 7 of the first set, the next eight the same walkers of the second set, and so on, so the
+    // workgroups that stream the same row-block of W start on the same XCD (workgroups go to the eight XCDs in turn) a
+    // dispatch apart: all but the first find the fragments in that XCD's L2.
     int walker = (int)blockIdx.x, G = (int)gridDim.x, tb0 = 0;
-    if (g.parts == 2) {
-        walker = (int)(((blockIdx.x >> 4) << 3) | (blockIdx.x & 7));
-        G = (int)(gridDim.x >> 1);
-        tb0 = (int)((blockIdx.x >> 3) & 1) * MT;
+    if (g.parts > 1) {
+        const int group = (int)(blockIdx.x >> 3);
+        walker = (group / g.parts) * 8 + (int)(blockIdx.x & 7);
+        G = (int)gridDim.x / g.parts;
+        tb0 = (group % g.parts) * MT;
     }
 
     // Buffer resources: the only per-lane addresses are 16 / 4 / 2 times the lane id, every fragment's position is a scalar
@@ -349,22 +353,26 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
             }
         }
     };
-    v4i xres[MT][XRES ? U : 1];
-    uint32_t sxres[MT][XRES ? U : 1];
+    constexpr int XF = XRES ? NB * U : 1;  // resident X fragments per token block: the wave's whole share of K
+    v4i xres[MT][XF];
+    uint32_t sxres[MT][XF];
     const bool mine = nb > 0;  // this wave has a share of K
     if constexpr (XRES) {
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
             const int mrb = min(tb0 + t, a_rbs - 1);  // (a token block past the end re-reads the last one and is not stored)
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int kc = max(min(k_begin + u, k_end - 1), 0);
-                xres[t][u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(mine ? rs_x : rs_none, lane16, mrb * KC * 1024 + kc * 1024, 0));
-                sxres[t][u] = load_scale(mine ? rs_xs : rs_none, kc, mrb * sc_per_rb * SCB);
+            for (int j = 0; j < XF; ++j) {
+                const bool has = k_begin + j < k_end;  // (fragments past the wave's share: zero-size loads, never multiplied)
+                const int kc = has ? k_begin + j : 0;
+                xres[t][j] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(has ? rs_x : rs_none, lane16, mrb * KC * 1024 + kc * 1024, 0));
+                sxres[t][j] = load_scale(has ? rs_xs : rs_none, kc, mrb * sc_per_rb * SCB);
             }
         }
     }
-    auto consume = [&](const Batch& b, int kc0, v4f (&acc)[MT]) {
+    // x0: index of the batch's first fragment among the resident ones (a compile-time constant at every call)
+    auto consume = [&](const Batch& b, int kc0, v4f (&acc)[MT], auto x0) {
+        constexpr int X0 = XRES ? decltype(x0)::value : 0;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (kc0 + u < k_end) {
@@ -373,8 +381,8 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
                     const v8i a8 = {b.wf[u][0], b.wf[u][1], b.wf[u][2], b.wf[u][3], 0, 0, 0, 0};
 #pragma unroll
                     for (int t = 0; t < MT; ++t) {
-                        const v4i xf = XRES ? xres[t][u] : b.xf[XRES ? 0 : u];
-                        const uint32_t sx = XRES ? sxres[t][u] : b.sx[XRES ? 0 : u];
+                        const v4i xf = XRES ? xres[t][XRES ? X0 + u : 0] : b.xf[XRES ? 0 : u];
+                        const uint32_t sx = XRES ? sxres[t][XRES ? X0 + u : 0] : b.sx[XRES ? 0 : u];
                         const v8i b8 = {xf[0], xf[1], xf[2], xf[3], 0, 0, 0, 0};
                         acc[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, acc[t], 4, 4, 0, (int)(b.sw[u] >> (8 * (kc & 3))), 0,
                                                                                 (int)(sx >> (8 * (kc & 3))));
@@ -383,7 +391,7 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
                     const NvFrag16 w16 = nv_dequant_frag(b.wf[u], b.sw[u]);
 #pragma unroll
                     for (int t = 0; t < MT; ++t) {
-                        const NvFrag16 x16 = nv_dequant_frag(XRES ? xres[t][u] : b.xf[XRES ? 0 : u], XRES ? sxres[t][u] : b.sx[XRES ? 0 : u]);
+                        const NvFrag16 x16 = nv_dequant_frag(XRES ? xres[t][XRES ? X0 + u : 0] : b.xf[XRES ? 0 : u], XRES ? sxres[t][XRES ? X0 + u : 0] : b.sx[XRES ? 0 : u]);
 #pragma unroll
                         for (int s = 0; s < 4; ++s) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w16.s[s], x16.s[s], acc[t], 0, 0, 0);
                     }
@@ -428,35 +436,46 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
     // because every load of the loop is unconditional (output stores sit under conditions and count as not issued, which
     // makes a wait a few operations stricter than necessary).
     if constexpr (XRES) {
-        // A row-block is one batch per wave.  One token block: two buffers (121 registers, two workgroups per compute
-        // unit).  Several resident token blocks take 150-170 registers, one workgroup per compute unit, so there THREE
-        // buffers: the loads of two row-blocks ahead are in flight while one is multiplied and reduced.
-        constexpr int NBUF = MT >= 2 ? 3 : 2;
-        Batch b0, b1, b2;
+        // A row-block is NB batches per wave (a compile-time count: the resident X fragments are addressed statically; a
+        // wave whose share of K is shorter requests its missing batches with zero size).  The batches of all the walker's
+        // row-blocks form one sequence, NBUF - 1 of them in flight ahead of the one being multiplied, through NBUF
+        // buffers in rotation; the loop body is NB * NBUF steps with every index a constant, left by `break` so that no
+        // control flow merges back into it.
+        constexpr int NBUF = MT * NB >= 7 ? 2 : 3;
+        constexpr int P = NB * NBUF;
+        static_assert(P <= 12, "the loop body below spells out twelve steps");
+        Batch buf[NBUF];
         int rb = walker, it = 0;
-        load_batch(b0, rb, k_begin, mine && rb < n_rb);
-        if constexpr (NBUF == 3) load_batch(b1, rb + G, k_begin, mine && rb + G < n_rb);
-        auto step = [&](Batch& cur, Batch& free) {
-            const int ahead = rb + (NBUF - 1) * G;
-            load_batch(free, ahead, k_begin, mine && ahead < n_rb);
-            v4f acc[MT];
+        auto request = [&](Batch& b, int rbq, int batch) { load_batch(b, rbq, k_begin + batch * U, mine && rbq < n_rb && batch < nb); };
+        request(buf[0], rb, 0);
+        if constexpr (NBUF == 3) request(buf[1], rb + (1 / NB) * G, 1 % NB);
+        v4f acc[MT];
 #pragma unroll
-            for (int t = 0; t < MT; ++t) acc[t] = v4f{0.f, 0.f, 0.f, 0.f};
-            consume(cur, k_begin, acc);
-            reduce_store(acc, rb, it);
-            ++it;
-            rb += G;
+        for (int t = 0; t < MT; ++t) acc[t] = v4f{0.f, 0.f, 0.f, 0.f};
+        // step q of the body: request the batch NBUF - 1 ahead into the buffer multiplied last, multiply batch q % NB of the
+        // current row-block, and behind a row-block's last batch reduce and store; true = that was the last row-block
+        auto step = [&](auto qc) -> bool {
+            constexpr int q = decltype(qc)::value, batch = q % NB, ahead = batch + NBUF - 1;
+            request(buf[(q + NBUF - 1) % NBUF], rb + (ahead / NB) * G, ahead % NB);
+            consume(buf[q % NBUF], k_begin + batch * U, acc, std::integral_constant<int, batch * U>{});
+            if constexpr (batch == NB - 1) {
+                reduce_store(acc, rb, it);
+#pragma unroll
+                for (int t = 0; t < MT; ++t) acc[t] = v4f{0.f, 0.f, 0.f, 0.f};
+                ++it;
+                rb += G;
+                return rb >= n_rb;
+            }
+            return false;
         };
-        while (rb < n_rb) {
-            if constexpr (NBUF == 3) {
-                step(b0, b2);
-                if (rb < n_rb) step(b1, b0);
-                if (rb < n_rb) step(b2, b1);
-            } else {
-                step(b0, b1);
-                if (rb < n_rb) step(b1, b0);
+#define FP4MR_STEP(q) if constexpr (P > q) { if (step(std::integral_constant<int, q>{})) break; }
+        if (rb < n_rb) {
+            for (;;) {
+                FP4MR_STEP(0) FP4MR_STEP(1) FP4MR_STEP(2) FP4MR_STEP(3) FP4MR_STEP(4) FP4MR_STEP(5)
+                FP4MR_STEP(6) FP4MR_STEP(7) FP4MR_STEP(8) FP4MR_STEP(9) FP4MR_STEP(10) FP4MR_STEP(11)
             }
         }
+#undef FP4MR_STEP
     } else {
         // Several batches per row-block: they alternate between two buffers, two per trip of the inner loop, and a
         // row-block with an odd number of batches hands the next one the other buffer first (`first`, uniform).
@@ -472,7 +491,7 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
             auto step = [&](Batch& cur, Batch& nxt, int b) {
                 const bool more_here = b + 1 < nb;
                 load_batch(nxt, more_here ? rb : rb + G, more_here ? k_begin + (b + 1) * U : k_begin, mine && (more_here || rb + G < n_rb));
-                consume(cur, k_begin + b * U, acc);
+                consume(cur, k_begin + b * U, acc, std::integral_constant<int, 0>{});
             };
             if (first == 0) {
                 for (int b = 0; b < nb; b += 2) {
@@ -499,48 +518,75 @@ int stream_cus()
     return cus;
 }
 
-// MXFP4, up to 16 tokens (MT = 1) or, with the X fragments resident, up to 64.  Returns false (nothing launched) where a
-// one-shot kernel is the better choice: the persistent kernel wins by keeping loads in flight across batches and row-blocks,
-// which needs either several batches per row-block or more row-blocks than workgroups; with one token block, a layer of at
-// most one row-block per compute unit (N <= 4096) is launch-bound and 0.1-0.4 us faster with the one-shot kernel's higher
-// occupancy.  With several token blocks the persistent kernel is taken always: the one-shot kernels re-read X from L2 per
-// W fragment.  NVFP4 stays with the one-shot kernels: its in-register dequantization needs the registers that the second
-// batch buffer takes (one workgroup per compute unit: 68 us against 54 on N = 57344, K = 8192).
-template <int FMT, int U, bool XRES, int MT = 1>
-bool try_stream(const SkinnyArgs& g, bool out_f32, int per, hipStream_t st, hipError_t* err)
+// Grid of the persistent kernels: one workgroup per compute unit, also where the registers would let two or three be
+// resident -- fewer, longer walks measured faster at every shape (K = 4096, cold weights, 256 against 512 workgroups:
+// M = 16, N = 6144 4.9 us against 5.5, N = 14336 7.7 against 8.5, N = 28672 12.1 against 12.7; M = 32, N = 6144 6.1 against 7.1).
+int stream_walkers()
 {
-    const int n_rb = (g.N + 15) / 16;
-    // One workgroup per compute unit, also where the registers would let two or three be resident: fewer, longer walks
-    // measured faster at every shape (K = 4096, cold weights, 256 against 512 workgroups: M = 16, N = 6144 4.9 us against 5.5,
-    // N = 14336 7.7 against 8.5, N = 28672 12.1 against 12.7; M = 32, N = 6144 6.1 against 7.1).
     int cap = stream_cus();
     // (the grid-cap option, a testing aid: a small grid makes every workgroup walk many row-blocks)
     if (options().gemm_grid > 0 && options().gemm_grid < cap) cap = options().gemm_grid;
-    if (MT == 1 && per <= U && n_rb <= cap) return false;
-    const dim3 grid((unsigned)std::min(n_rb, cap)), block(kSkinnyWaves * 64);
-    if (out_f32) hipLaunchKernelGGL((gemm_stream_kernel<FMT, true, U, XRES, MT>), grid, block, 0, st, g);
-    else hipLaunchKernelGGL((gemm_stream_kernel<FMT, false, U, XRES, MT>), grid, block, 0, st, g);
-    *err = hipGetLastError();
+    return cap;
+}
+
+// MXFP4 with the activations resident in registers: MT 16-token blocks, a wave's share of K in NB batches of four fragments
+// (K <= 4096 NB).  parts > 1: that many sets of workgroups, each with its own MT token blocks; W passes through every
+// XCD's L2 once and is read from there once per set.  The walkers of a set share the row-blocks evenly (as many rounds as
+// the resident workgroups need, then the fewest walkers that do it in that many rounds).
+template <int MT, int NB>
+hipError_t launch_stream_resident(SkinnyArgs g, bool out_f32, int parts, hipStream_t st)
+{
+    const int n_rb = (g.N + 15) / 16, cap = stream_walkers();
+    unsigned blocks = (unsigned)std::min(n_rb, cap);
+    if (parts > 1) {
+        const int per_part = std::max(cap / parts, 8);
+        const int rounds = (n_rb + per_part - 1) / per_part;
+        const int walkers = ((n_rb + rounds - 1) / rounds + 7) / 8 * 8;
+        blocks = (unsigned)(parts * walkers);
+        g.parts = parts;
+    }
+    const dim3 grid(blocks), block(kSkinnyWaves * 64);
+    if (out_f32) hipLaunchKernelGGL((gemm_stream_kernel<0, true, 4, true, MT, NB>), grid, block, 0, st, g);
+    else hipLaunchKernelGGL((gemm_stream_kernel<0, false, 4, true, MT, NB>), grid, block, 0, st, g);
+    return hipGetLastError();
+}
+
+// largest number of batches per row-block for which MT token blocks of X fit the registers (MT * NB * 20 for X: up to
+// 235 in all, no spills; three blocks with three batches would spill)
+constexpr int stream_max_batches(int mt)
+{
+    return mt <= 2 ? 4 : 2;
+}
+
+// false (nothing launched): the wave's share of K (`per` fragments) does not fit
+template <int MT>
+bool try_stream_resident(const SkinnyArgs& g, bool out_f32, int per, int parts, hipStream_t st, hipError_t* err)
+{
+    const int nbk = (per + 3) / 4;
+    if (nbk > stream_max_batches(MT)) return false;
+    switch (nbk) {
+        case 1: *err = launch_stream_resident<MT, 1>(g, out_f32, parts, st); break;
+        case 2:
+            if constexpr (stream_max_batches(MT) >= 2) *err = launch_stream_resident<MT, 2>(g, out_f32, parts, st);
+            break;
+        case 3:
+            if constexpr (stream_max_batches(MT) >= 3) *err = launch_stream_resident<MT, 3>(g, out_f32, parts, st);
+            break;
+        default:
+            if constexpr (stream_max_batches(MT) >= 4) *err = launch_stream_resident<MT, 4>(g, out_f32, parts, st);
+            break;
+    }
     return true;
 }
 
-// 65 to 128 tokens, MXFP4, K <= 4096: two sets of persistent workgroups, each with half of the token blocks resident in
-// registers.  W passes through every XCD's L2 once and is read from there twice; nothing of X is read again.  The walkers of a
-// part share the row-blocks evenly (as many rounds as the resident workgroups need, then the fewest walkers that do it in
-// that many rounds).
-template <int MT>
-hipError_t launch_stream_two_parts(SkinnyArgs g, bool out_f32, hipStream_t st)
+// MXFP4, up to 16 tokens, a share of K too long to keep X resident (K > 16384): the X fragments travel with W, two buffers.
+template <int FMT, int U>
+hipError_t launch_stream_travelling(const SkinnyArgs& g, bool out_f32, hipStream_t st)
 {
     const int n_rb = (g.N + 15) / 16;
-    int cap = stream_cus();
-    if (options().gemm_grid > 0 && options().gemm_grid < cap) cap = options().gemm_grid;
-    const int per_part = std::max(cap / 2, 8);
-    const int rounds = (n_rb + per_part - 1) / per_part;
-    const int walkers = ((n_rb + rounds - 1) / rounds + 7) / 8 * 8;
-    g.parts = 2;
-    const dim3 grid((unsigned)(2 * walkers)), block(kSkinnyWaves * 64);
-    if (out_f32) hipLaunchKernelGGL((gemm_stream_kernel<0, true, 4, true, MT>), grid, block, 0, st, g);
-    else hipLaunchKernelGGL((gemm_stream_kernel<0, false, 4, true, MT>), grid, block, 0, st, g);
+    const dim3 grid((unsigned)std::min(n_rb, stream_walkers())), block(kSkinnyWaves * 64);
+    if (out_f32) hipLaunchKernelGGL((gemm_stream_kernel<FMT, true, U, false>), grid, block, 0, st, g);
+    else hipLaunchKernelGGL((gemm_stream_kernel<FMT, false, U, false>), grid, block, 0, st, g);
     return hipGetLastError();
 }
 
@@ -573,10 +619,11 @@ template <int FMT, int MT>
 hipError_t launch_tokens(const SkinnyArgs& g, bool out_f32, hipStream_t st)
 {
     if constexpr (FMT == 0 && MT >= 2) {
-        // K <= 4096: the wave's share of K is one batch, so all MT token blocks of X stay in registers of the persistent kernel
+        // the persistent kernel with all MT token blocks of X in registers, where the wave's share of K fits: nothing of X is
+        // read again after the first microsecond (the one-shot kernels fetch MT X fragments from L2 per W fragment)
         const int per = ((g.K >> 7) + kSkinnyWaves - 1) / kSkinnyWaves;
         hipError_t e = hipSuccess;
-        if (per <= 4 && try_stream<0, 4, true, MT>(g, out_f32, per, st, &e)) return e;
+        if (try_stream_resident<MT>(g, out_f32, per, 1, st, &e)) return e;
     }
     // (MXFP4 with two token blocks measured level with the one-row-block kernel, with three and four 5-11 % faster:
     // N = 6144, K = 4096, M = 64: 8.5 us against 9.6; N = K = 8192: 14.4 against 16.1)
@@ -587,47 +634,73 @@ hipError_t launch_tokens(const SkinnyArgs& g, bool out_f32, hipStream_t st)
     return launch_mt<FMT, MT>(g, out_f32, st);
 }
 
+// MXFP4, more token blocks than one set of workgroups can keep resident for this K: the fewest sets, then the fewest token
+// blocks per set, that cover them (K <= 8192: up to four blocks per set, K <= 16384: two).  false: K too long.
+bool try_stream_sets(const SkinnyArgs& g, bool out_f32, int mt, int per, hipStream_t st, hipError_t* err)
+{
+    const int nbk = (per + 3) / 4;
+    const int mt_max = nbk <= stream_max_batches(4) ? 4 : nbk <= stream_max_batches(2) ? 2 : 0;
+    if (mt_max == 0) return false;
+    const int parts = (mt + mt_max - 1) / mt_max;
+    switch ((mt + parts - 1) / parts) {
+        case 1: return try_stream_resident<1>(g, out_f32, per, parts, st, err);
+        case 2: return try_stream_resident<2>(g, out_f32, per, parts, st, err);
+        case 3: return try_stream_resident<3>(g, out_f32, per, parts, st, err);
+        default: return try_stream_resident<4>(g, out_f32, per, parts, st, err);
+    }
+}
+
 template <int FMT>
 hipError_t launch_fmt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
 {
     const int mt = (g.M + 15) / 16;
+    const int per = ((g.K >> 7) + kSkinnyWaves - 1) / kSkinnyWaves;  // fragments of K per wave
+    if constexpr (FMT == 0) {
+        // more token blocks than fit one set of resident registers at this K
+        const int nbk = (per + 3) / 4;
+        const bool one_set = mt <= 4 && nbk <= stream_max_batches(mt);
+        hipError_t e = hipSuccess;
+        if (mt >= 2 && !one_set && try_stream_sets(g, out_f32, mt, per, st, &e)) return e;
+    }
     switch (mt) {
         case 1:
             if constexpr (FMT == 0) {
-                const int per = ((g.K >> 7) + kSkinnyWaves - 1) / kSkinnyWaves;  // fragments of K per wave
+                // The persistent kernels win by keeping loads in flight across batches and row-blocks, which needs several
+                // batches per row-block or more row-blocks than workgroups: a layer of at most one row-block per compute unit
+                // and one batch (N <= 4096, K <= 4096) is launch-bound and 0.1-0.4 us faster with the one-shot kernel's
+                // occupancy.  (NVFP4 stays with the one-shot kernels: its in-register dequantization needs the registers of
+                // the second batch buffer -- 68 us against 54 on N = 57344, K = 8192.)
+                const bool one_shot = per <= 4 && (g.N + 15) / 16 <= stream_walkers();
                 hipError_t e = hipSuccess;
-                if (per <= 4 ? try_stream<0, 4, true>(g, out_f32, per, st, &e) : try_stream<0, 4, false>(g, out_f32, per, st, &e)) return e;
+                if (!one_shot) {
+                    if (try_stream_resident<1>(g, out_f32, per, 1, st, &e)) return e;
+                    return launch_stream_travelling<0, 4>(g, out_f32, st);
+                }
             }
             return launch_tokens<FMT, 1>(g, out_f32, st);
         case 2: return launch_tokens<FMT, 2>(g, out_f32, st);
         case 3: return launch_tokens<FMT, 3>(g, out_f32, st);
         case 4: return launch_tokens<FMT, 4>(g, out_f32, st);
-        case 5:
-        case 6:
-            if constexpr (FMT == 0) return launch_stream_two_parts<3>(g, out_f32, st);
-            return hipErrorInvalidValue;
-        case 7:
-        case 8:
-            if constexpr (FMT == 0) return launch_stream_two_parts<4>(g, out_f32, st);
-            return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }
 }
 
 }  // namespace
 
-// 65 to 128 tokens: MXFP4 with a wave's share of K resident in registers (K <= 4096), on layers narrow enough that the
-// tile kernels' fixed cost per launch (12-14 us at K = 4096, 8-10 at K = 2048) exceeds what the persistent kernel spends
-// per row-block (about 3.4 us + 0.7 us per 1024 output columns).  Measured, cold weights, M = 96, tiles -> two parts:
-// K = 4096: N = 4096 12.6 -> 6.4 us, 6144 12.9 -> 7.8, 8192 12.9 -> 9.5, 14336 14.5 -> 13.8, 28672 17.7 -> 25.0;
-// K = 2048: N = 4096 8.1 -> 6.0, 6144 9.3 -> 7.3, 8192 9.4 -> 8.7, 14336 10.1 -> 12.6; K = 1024: level or slower.
+// 65 to 128 tokens: MXFP4 with K <= 8192 (two sets of workgroups with three or four token blocks resident each), on layers
+// narrow enough that the tile kernels' cost per launch (12-14 us at K = 4096, 15-25 at K = 8192, whatever the token count)
+// exceeds what the persistent kernel spends per row-block.  Measured, cold weights, M = 96, tiles -> two sets:
+// K = 4096: N = 4096 12.6 -> 6.4 us, 8192 12.9 -> 8.6, 14336 14.3 -> 12.2, 28672 17.9 -> 20.4 (not taken);
+// K = 8192: N = 4096 16.0 -> 9.3, 8192 17.8 -> 12.6, 14336 25.1 -> 18.9; K = 2048: N = 4096 8.1 -> 6.0, 8192 9.4 -> 8.7,
+// 14336 10.1 -> 12.6 (not taken); K = 1024: level or slower (not taken).  K = 14336 (four sets of two blocks): level with
+// the split-K tiles at N = 4096, slower beyond (not taken).
 bool gemm_skinny_takes(int64_t M, int64_t N, int64_t K, int fmt)
 {
     if (M <= 64) return true;
     if (fmt != 0 || M > 128) return false;
     const int64_t per = ((K >> 7) + kSkinnyWaves - 1) / kSkinnyWaves;  // fragments of K per wave
-    if (per == 4) return N <= 12288;
-    if (per == 2 || per == 3) return N <= 6144;
+    if (per >= 4 && per <= 8) return N <= 16384;
+    if (per == 2 || per == 3) return N <= 8192;
     return false;
 }
 

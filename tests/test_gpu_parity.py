@@ -368,11 +368,31 @@ def test_gemm_mxfp4_persistent_weight_streaming_kernel(fp4, oracle, grid, M, N, 
     _gemm_case(fp4, oracle, MX, M, N, K, seed=300 + grid + K, out_f32=out_f32, layout_gemm=True)
 
 
+@pytest.mark.parametrize("grid", [0, 2])
+@pytest.mark.parametrize("M,N,K,out_f32", [(16, 336, 5120, False), (7, 200, 8192, True), (16, 176, 4736, False), (12, 208, 9344, False),
+                                           (16, 240, 14336, True), (1, 160, 16384, False), (16, 144, 16512, False), (20, 336, 5120, True),
+                                           (32, 176, 8192, False), (25, 208, 12288, False), (32, 144, 12416, True), (40, 336, 6272, False),
+                                           (48, 176, 8192, True), (33, 144, 8320, False), (64, 208, 4224, False), (32, 144, 16384, False),
+                                           (17, 160, 16512, False), (64, 208, 8192, True), (50, 176, 8320, False), (31, 192, 14336, False),
+                                           (48, 176, 14336, False), (64, 144, 12288, True), (60, 160, 16384, False)])
+def test_gemm_mxfp4_persistent_kernel_with_several_batches_of_resident_activations(fp4, oracle, grid, M, N, K, out_f32, knobs):
+    """K above 4096: a wave's share of K is two to four batches of four fragments, and the activations of up to 32 / 64
+    tokens stay in registers for K up to 16384 / 8192 (every batch index static: the loop body is batches x buffers
+    steps).  K / 128 = 33, 37, 40, 49, 64, 73, 96, 97, 112, 128: shares that end inside a batch, waves with fewer batches than
+    the others or none; one step past each limit: K = 8320 with three and four token blocks, and K = 8192 < K <= 16384 with
+    33 to 64 tokens, run as two sets of workgroups with two token blocks each; K = 16512 takes the kernels that do not
+    keep X resident.  Grid cap 2: every workgroup walks many row-blocks, so batches of the next row-block are
+    requested while the current one is multiplied and reduced."""
+    knobs(grid=grid)
+    _gemm_case(fp4, oracle, MX, M, N, K, seed=700 + M + K, out_f32=out_f32, layout_gemm=True)
+
+
 @pytest.mark.parametrize("grid,M,N,K,out_f32", [(0, 65, 400, 4096, False), (0, 128, 1000, 4096, True), (16, 96, 2056, 2048, False),
                                                 (16, 100, 1160, 1152, True), (1, 81, 520, 3072, False), (0, 113, 6144, 4096, False),
-                                                (16, 128, 4104, 1536, True), (0, 72, 12288, 3200, False)])
+                                                (16, 128, 4104, 1536, True), (0, 72, 12288, 3200, False), (0, 96, 272, 8192, False),
+                                                (16, 128, 400, 6144, True), (0, 70, 144, 5120, False), (16, 81, 528, 8192, True)])
 def test_gemm_mxfp4_65_to_128_tokens_on_two_sets_of_persistent_workgroups(fp4, oracle, grid, M, N, K, out_f32, knobs):
-    """65 to 128 tokens on a narrow MXFP4 layer with 1024 < K <= 4096: the persistent weight-streaming kernel runs as two sets
+    """65 to 128 tokens on a narrow MXFP4 layer with 1024 < K <= 8192: the persistent weight-streaming kernel runs as two sets
     of workgroups, each with three or four 16-token blocks of X in registers (five to eight blocks in all: the second set's
     last block can lie past the end of M and is then neither loaded nor stored); a grid cap makes 8 walkers per set take many
     row-blocks each; ragged N, waves without a K share (K / 128 = 9, 12), fp32 and bf16 output."""
@@ -399,7 +419,7 @@ def test_gemm_mxfp4_three_and_four_token_blocks_two_row_blocks_per_workgroup(fp4
     _gemm_case(fp4, oracle, MX, M, N, K, seed=5100 + N + K, out_f32=out_f32, layout_gemm=True)
 
 
-@pytest.mark.parametrize("M,N,K,out_f32", [(65, 400, 8192, True), (128, 1024, 14336, False), (200, 1000, 12416, False), (300, 272, 16512, True),
+@pytest.mark.parametrize("M,N,K,out_f32", [(129, 400, 8192, True), (128, 1024, 14336, False), (200, 1000, 12416, False), (300, 272, 16512, True),
                                            (512, 520, 9088, False)])
 def test_gemm_mxfp4_split_k(fp4, oracle, M, N, K, out_f32):
     """More than 64 tokens against a narrow layer with a long K: with the optional workspace the tiles' K ranges are
