@@ -9,11 +9,12 @@
 // No split-K workspace, no atomics, one launch.
 //
 // Three kernels share that scheme.  gemm_skinny_kernel launches one workgroup per row-block; its loads drain before the
-// reduction, so each workgroup pays one memory latency with nothing in flight.  gemm_stream_kernel (MXFP4, M <= 16,
-// layers with more row-blocks than the chip holds workgroups) keeps a fixed grid resident, walks the row-blocks with a
-// stride and holds two register batches per wave, so the loads of the next row-block are in flight while the partial
-// sums of the current one meet in LDS.  gemm_skinny_nt_kernel (NVFP4; MXFP4 above 16 tokens) gives a workgroup two row-blocks so that
-// each dequantized X fragment serves two W fragments.  All add the eight partials in wave order: bit-identical results.
+// reduction, so each workgroup pays one memory latency with nothing in flight.  gemm_stream_kernel (MXFP4) keeps one
+// workgroup per compute unit resident, walks the row-blocks with a stride, holds the activations in registers for the
+// whole launch and two or three register batches of W per wave in rotation, so the loads of the next batches are in flight
+// while the current one is multiplied and its row-block's partial sums meet in LDS.  gemm_skinny_nt_kernel (NVFP4; MXFP4
+// where the activations do not fit the registers) gives a workgroup two row-blocks so that each X fragment serves two W
+// fragments.  All add the eight partials in wave order: bit-identical results.
 #include "device_util.hpp"
 #include "internal.hpp"
 #include "layout.hpp"
@@ -272,19 +273,18 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nt_kernel(Skinn
 }
 
 // ------------------------------------------------------------------------------------------------------
-// Up to 16 tokens (one X row-block): the same decomposition as above -- a workgroup per 16-column block of the output,
-// its 8 waves splitting K, partial sums added through LDS in a fixed order -- but the workgroups are PERSISTENT: the grid
-// is what fits on the chip at once and a workgroup walks the row-blocks of W with a stride of the grid.  A one-shot
-// workgroup streams 32 KB (K = 4096) and spends most of its life on its own start-up, its load latency and its
-// reduction, none of which overlap; here the loads of the next batch of fragments (of this row-block or the next) are in
-// flight while the current batch is multiplied and while the row-block's partial sums are reduced and stored, so HBM
-// sees a continuous stream.  Two register buffers of U fragments each (W codes and scales, X codes and scales); the
+// The same decomposition as above -- a workgroup per 16-column block of the output, its 8 waves splitting K, partial sums
+// added through LDS in a fixed order -- but the workgroups are PERSISTENT: one per compute unit, each walking the row-blocks
+// of W with a stride of the grid.  A one-shot workgroup streams 32 KB (K = 4096) and spends most of its life on its own
+// start-up, its load latency and its reduction, none of which overlap; here the loads of the next batches of fragments (of
+// this row-block or the next) are in flight while the current batch is multiplied and while the row-block's partial sums
+// are reduced and stored, so HBM sees a continuous stream.  Register buffers of U fragments each (W codes and scales); the
 // barrier per row-block is a bare s_barrier (no vmcnt drain) and the partial sums are double-buffered in LDS, so one
 // barrier per row-block suffices.  Bit-identical to the one-shot kernel (same K split, same order of additions).
-// XRES: the wave's share of K is at most U fragments (one batch per row-block), and since that share is the same for every
-// row-block its X fragments are loaded once and stay in registers: a batch is then W only.
-// MT > 1 (XRES only): up to MT 16-token blocks of X stay in registers, a W fragment meets all of them, and nothing of X is
-// read again for the rest of the launch -- the one-shot kernels fetch MT X fragments from L2 per W fragment.
+// XRES: the wave's share of K is at most NB batches of U fragments, and since that share is the same for every row-block
+// its X fragments -- of MT 16-token blocks -- are loaded once and stay in registers: a batch is W only, a W fragment meets
+// all MT blocks, and nothing of X is read again for the rest of the launch (the one-shot kernels fetch MT X fragments from
+// L2 per W fragment).  !XRES (MT = 1, any K): the X fragments travel with W in the batches, two buffers.
 template <int FMT, bool OUT_F32, int U, bool XRES, int MT = 1, int NB = 1>
 __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyArgs g)
 {
