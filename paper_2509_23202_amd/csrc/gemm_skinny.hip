@@ -290,6 +290,7 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
 {
     static_assert(MT == 1 || XRES, "several token blocks only with the X fragments resident");
     static_assert(NB == 1 || XRES, "a static number of batches per row-block only with the X fragments resident");
+    static_assert(FMT == 0 || !XRES || MT == 1, "NVFP4 keeps one token block resident (as fp16: 16 registers per fragment)");
     __shared__ float partial[2][kSkinnyWaves][MT][256];
 
     const int lane = threadIdx.x & 63;
@@ -354,8 +355,11 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
         }
     };
     constexpr int XF = XRES ? NB * U : 1;  // resident X fragments per token block: the wave's whole share of K
-    v4i xres[MT][XF];
-    uint32_t sxres[MT][XF];
+    // MXFP4: codes and scale dwords as loaded.  NVFP4: DEQUANTIZED once, as fp16 -- the per-fragment dequantization of X,
+    // half of the vector arithmetic that bounds the one-shot NVFP4 kernels, is then paid once per workgroup
+    v4i xres[FMT == 0 ? MT : 1][FMT == 0 ? XF : 1];
+    uint32_t sxres[FMT == 0 ? MT : 1][FMT == 0 ? XF : 1];
+    NvFrag16 xres16[FMT == 1 ? XF : 1];
     const bool mine = nb > 0;  // this wave has a share of K
     if constexpr (XRES) {
 #pragma unroll
@@ -365,8 +369,14 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
             for (int j = 0; j < XF; ++j) {
                 const bool has = k_begin + j < k_end;  // (fragments past the wave's share: zero-size loads, never multiplied)
                 const int kc = has ? k_begin + j : 0;
-                xres[t][j] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(has ? rs_x : rs_none, lane16, mrb * KC * 1024 + kc * 1024, 0));
-                sxres[t][j] = load_scale(has ? rs_xs : rs_none, kc, mrb * sc_per_rb * SCB);
+                const v4i xf = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(has ? rs_x : rs_none, lane16, mrb * KC * 1024 + kc * 1024, 0));
+                const uint32_t sx = load_scale(has ? rs_xs : rs_none, kc, mrb * sc_per_rb * SCB);
+                if constexpr (FMT == 0) {
+                    xres[t][j] = xf;
+                    sxres[t][j] = sx;
+                } else {
+                    xres16[j] = nv_dequant_frag(xf, sx);
+                }
             }
         }
     }
@@ -381,8 +391,8 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
                     const v8i a8 = {b.wf[u][0], b.wf[u][1], b.wf[u][2], b.wf[u][3], 0, 0, 0, 0};
 #pragma unroll
                     for (int t = 0; t < MT; ++t) {
-                        const v4i xf = XRES ? xres[t][XRES ? X0 + u : 0] : b.xf[XRES ? 0 : u];
-                        const uint32_t sx = XRES ? sxres[t][XRES ? X0 + u : 0] : b.sx[XRES ? 0 : u];
+                        const v4i xf = XRES ? xres[t][XRES && FMT == 0 ? X0 + u : 0] : b.xf[XRES ? 0 : u];
+                        const uint32_t sx = XRES ? sxres[t][XRES && FMT == 0 ? X0 + u : 0] : b.sx[XRES ? 0 : u];
                         const v8i b8 = {xf[0], xf[1], xf[2], xf[3], 0, 0, 0, 0};
                         acc[t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, acc[t], 4, 4, 0, (int)(b.sw[u] >> (8 * (kc & 3))), 0,
                                                                                 (int)(sx >> (8 * (kc & 3))));
@@ -391,7 +401,9 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
                     const NvFrag16 w16 = nv_dequant_frag(b.wf[u], b.sw[u]);
 #pragma unroll
                     for (int t = 0; t < MT; ++t) {
-                        const NvFrag16 x16 = nv_dequant_frag(XRES ? xres[t][XRES ? X0 + u : 0] : b.xf[XRES ? 0 : u], XRES ? sxres[t][XRES ? X0 + u : 0] : b.sx[XRES ? 0 : u]);
+                        NvFrag16 x16;
+                        if constexpr (XRES) x16 = xres16[XRES && FMT == 1 ? X0 + u : 0];
+                        else x16 = nv_dequant_frag(b.xf[XRES ? 0 : u], b.sx[XRES ? 0 : u]);
 #pragma unroll
                         for (int s = 0; s < 4; ++s) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w16.s[s], x16.s[s], acc[t], 0, 0, 0);
                     }
@@ -551,6 +563,17 @@ hipError_t launch_stream_resident(SkinnyArgs g, bool out_f32, int parts, hipStre
     return hipGetLastError();
 }
 
+// NVFP4, up to 16 tokens, K <= 8192: the activations resident as fp16 (a wave's share of K in NB batches of two fragments)
+template <int NB>
+hipError_t launch_stream_resident_nv(const SkinnyArgs& g, bool out_f32, hipStream_t st)
+{
+    const int n_rb = (g.N + 15) / 16;
+    const dim3 grid((unsigned)std::min(n_rb, stream_walkers())), block(kSkinnyWaves * 64);
+    if (out_f32) hipLaunchKernelGGL((gemm_stream_kernel<1, true, 2, true, 1, NB>), grid, block, 0, st, g);
+    else hipLaunchKernelGGL((gemm_stream_kernel<1, false, 2, true, 1, NB>), grid, block, 0, st, g);
+    return hipGetLastError();
+}
+
 // largest number of batches per row-block for which MT token blocks of X fit the registers (MT * NB * 20 for X: up to
 // 235 in all, no spills; three blocks with three batches would spill)
 constexpr int stream_max_batches(int mt)
@@ -675,6 +698,18 @@ hipError_t launch_fmt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
                 if (!one_shot) {
                     if (try_stream_resident<1>(g, out_f32, per, 1, st, &e)) return e;
                     return launch_stream_travelling<0, 4>(g, out_f32, st);
+                }
+            }
+            if constexpr (FMT == 1) {
+                // K <= 8192: the persistent kernel with the activations resident as fp16 (70B qkv, M = 16, cold weights: 15.3 ->
+                // 11.3 us; gate_up 49 -> 43.5 us = 6.2 TB/s; N = 28672, K = 4096: 16.6 -> 13.0), bit-identical to the kernels below
+                if (per <= 8) {
+                    switch ((per + 1) / 2) {
+                        case 1: return launch_stream_resident_nv<1>(g, out_f32, st);
+                        case 2: return launch_stream_resident_nv<2>(g, out_f32, st);
+                        case 3: return launch_stream_resident_nv<3>(g, out_f32, st);
+                        default: return launch_stream_resident_nv<4>(g, out_f32, st);
+                    }
                 }
             }
             return launch_tokens<FMT, 1>(g, out_f32, st);
