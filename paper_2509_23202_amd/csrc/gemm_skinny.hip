@@ -551,9 +551,9 @@ hipError_t launch_stream_resident(SkinnyArgs g, bool out_f32, int parts, hipStre
     const int n_rb = (g.N + 15) / 16, cap = stream_walkers();
     unsigned blocks = (unsigned)std::min(n_rb, cap);
     if (parts > 1) {
-        const int per_part = std::max(cap / parts, 8);
+        const int per_part = std::max(cap / parts / 8 * 8, 8);  // (whole groups of eight, all sets resident at once)
         const int rounds = (n_rb + per_part - 1) / per_part;
-        const int walkers = ((n_rb + rounds - 1) / rounds + 7) / 8 * 8;
+        const int walkers = std::min(per_part, ((n_rb + rounds - 1) / rounds + 7) / 8 * 8);
         blocks = (unsigned)(parts * walkers);
         g.parts = parts;
     }
@@ -565,13 +565,31 @@ hipError_t launch_stream_resident(SkinnyArgs g, bool out_f32, int parts, hipStre
 
 // NVFP4, up to 16 tokens, K <= 8192: the activations resident as fp16 (a wave's share of K in NB batches of two fragments)
 template <int NB>
-hipError_t launch_stream_resident_nv(const SkinnyArgs& g, bool out_f32, hipStream_t st)
+hipError_t launch_stream_resident_nv(SkinnyArgs g, bool out_f32, int parts, hipStream_t st)
 {
-    const int n_rb = (g.N + 15) / 16;
-    const dim3 grid((unsigned)std::min(n_rb, stream_walkers())), block(kSkinnyWaves * 64);
+    const int n_rb = (g.N + 15) / 16, cap = stream_walkers();
+    unsigned blocks = (unsigned)std::min(n_rb, cap);
+    if (parts > 1) {
+        const int per_part = std::max(cap / parts / 8 * 8, 8);  // (whole groups of eight, all sets resident at once)
+        const int rounds = (n_rb + per_part - 1) / per_part;
+        const int walkers = std::min(per_part, ((n_rb + rounds - 1) / rounds + 7) / 8 * 8);
+        blocks = (unsigned)(parts * walkers);
+        g.parts = parts;
+    }
+    const dim3 grid(blocks), block(kSkinnyWaves * 64);
     if (out_f32) hipLaunchKernelGGL((gemm_stream_kernel<1, true, 2, true, 1, NB>), grid, block, 0, st, g);
     else hipLaunchKernelGGL((gemm_stream_kernel<1, false, 2, true, 1, NB>), grid, block, 0, st, g);
     return hipGetLastError();
+}
+
+hipError_t launch_stream_nv(const SkinnyArgs& g, bool out_f32, int per, int parts, hipStream_t st)
+{
+    switch ((per + 1) / 2) {
+        case 1: return launch_stream_resident_nv<1>(g, out_f32, parts, st);
+        case 2: return launch_stream_resident_nv<2>(g, out_f32, parts, st);
+        case 3: return launch_stream_resident_nv<3>(g, out_f32, parts, st);
+        default: return launch_stream_resident_nv<4>(g, out_f32, parts, st);
+    }
 }
 
 // largest number of batches per row-block for which MT token blocks of X fit the registers (MT * NB * 20 for X: up to
@@ -703,19 +721,19 @@ hipError_t launch_fmt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
             if constexpr (FMT == 1) {
                 // K <= 8192: the persistent kernel with the activations resident as fp16 (70B qkv, M = 16, cold weights: 15.3 ->
                 // 11.3 us; gate_up 49 -> 43.5 us = 6.2 TB/s; N = 28672, K = 4096: 16.6 -> 13.0), bit-identical to the kernels below
-                if (per <= 8) {
-                    switch ((per + 1) / 2) {
-                        case 1: return launch_stream_resident_nv<1>(g, out_f32, st);
-                        case 2: return launch_stream_resident_nv<2>(g, out_f32, st);
-                        case 3: return launch_stream_resident_nv<3>(g, out_f32, st);
-                        default: return launch_stream_resident_nv<4>(g, out_f32, st);
-                    }
-                }
+                if (per <= 8) return launch_stream_nv(g, out_f32, per, 1, st);
             }
             return launch_tokens<FMT, 1>(g, out_f32, st);
-        case 2: return launch_tokens<FMT, 2>(g, out_f32, st);
-        case 3: return launch_tokens<FMT, 3>(g, out_f32, st);
-        case 4: return launch_tokens<FMT, 4>(g, out_f32, st);
+        case 2:
+        case 3:
+        case 4:
+            if constexpr (FMT == 1) {
+                // 17 to 64 tokens on a narrow layer: one set of such workgroups per token block (every set dequantizes W again,
+                // which the two-row-block kernels below share between token blocks: N = 10240, K = 8192, M = 32 / 64: 18.7 /
+                // 29.5 -> 15.5 / 24.5 us; N = 16384: level; N = 57344: 59 / 100 -> 67 / 113, not taken)
+                if (per <= 8 && g.N <= 12288) return launch_stream_nv(g, out_f32, per, mt, st);
+            }
+            return mt == 2 ? launch_tokens<FMT, 2>(g, out_f32, st) : mt == 3 ? launch_tokens<FMT, 3>(g, out_f32, st) : launch_tokens<FMT, 4>(g, out_f32, st);
         default: return hipErrorInvalidValue;
     }
 }

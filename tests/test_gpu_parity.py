@@ -403,13 +403,15 @@ def test_gemm_mxfp4_65_to_128_tokens_on_two_sets_of_persistent_workgroups(fp4, o
 @pytest.mark.parametrize("grid", [0, 1, 3])
 @pytest.mark.parametrize("M,N,K,out_f32", [(1, 400, 128, True), (16, 784, 384, False), (9, 1040, 1024, False), (16, 272, 1152, True),
                                            (3, 200, 2176, False), (16, 336, 4224, False), (12, 528, 8192, True), (16, 144, 8320, False),
-                                           (16, 4112, 2048, False)])
+                                           (16, 4112, 2048, False), (20, 1040, 1152, False), (40, 528, 8192, True), (64, 400, 4224, False),
+                                           (33, 4112, 512, True)])
 def test_gemm_nvfp4_persistent_kernel_with_fp16_resident_activations(fp4, oracle, grid, M, N, K, out_f32, knobs):
     """Up to 16 tokens on NVFP4 with K <= 8192: one workgroup per compute unit walks the row-blocks of W, its waves' shares
     of the activations dequantized once to fp16 and kept in registers, W in batches of two fragments with two batches in
     flight.  K / 128 = 1, 3, 8, 9, 17, 33, 64: one to four batches per row-block, shares that end inside a batch, waves
     without a share; K = 8320 is one step past the limit (the one-shot kernels); a grid of 1 or 3 workgroups makes each
-    walk many row-blocks; ragged N, fp32 and bf16 output."""
+    walk many row-blocks; ragged N, fp32 and bf16 output.  17 to 64 tokens on a narrow layer (N <= 12288): one set of such
+    workgroups per 16-token block (two to four sets, the last block ragged)."""
     knobs(grid=grid)
     _gemm_case(fp4, oracle, NV, M, N, K, seed=900 + grid + K, out_f32=out_f32, layout_gemm=True)
 
