@@ -144,7 +144,7 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_kernel(SkinnyAr
 // row-blocks (the arithmetic per KB of W is 48 (1 + MT / NT) instructions instead of 48 (1 + MT)).
 // FMT 0 (MXFP4, two to four token blocks): no dequantization there, but the X fragments come from L2 once per W fragment in
 // the kernel above and once per NT of them here.
-template <int FMT, int NT, int MT, bool OUT_F32>
+template <int FMT, int NT, int MT, bool OUT_F32, bool PF = false>
 __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nt_kernel(SkinnyArgs g)
 {
     constexpr int U = MT == 1 ? 4 : 2;  // K positions in flight per wave (NT W fragments and MT X fragments each)
@@ -190,9 +190,16 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nt_kernel(Skinn
 #pragma unroll
         for (int t = 0; t < MT; ++t) acc[r][t] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    for (int kc0 = k_begin; kc0 < k_end; kc0 += U) {
+    struct Fetch {
         v4i wf[U][NT], xf[U][MT];
         uint32_t swv[U][NT], sxv[U][MT];
+    };
+    // (a position past the wave's share repeats the last fragment -- valid memory, from L2 -- and its products are skipped)
+    auto fetch = [&](Fetch& f, int kc0) {
+        auto& wf = f.wf;
+        auto& xf = f.xf;
+        auto& swv = f.swv;
+        auto& sxv = f.sxv;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int kc = min(kc0 + u, k_end - 1);  // the tail repeats the last fragment; its products are skipped below
@@ -207,6 +214,12 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nt_kernel(Skinn
                 sxv[u][t] = load_scale(xsc[t], kc);
             }
         }
+    };
+    auto multiply = [&](const Fetch& f, int kc0) {
+        const auto& wf = f.wf;
+        const auto& xf = f.xf;
+        const auto& swv = f.swv;
+        const auto& sxv = f.sxv;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (kc0 + u < k_end) {
@@ -245,6 +258,29 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_nt_kernel(Skinn
                     }
                 }
             }
+        }
+    };
+    if constexpr (PF) {
+        // Two register sets: the loads of the next U positions are issued -- unconditionally, so that the compiler's wait
+        // in front of the current products leaves them in flight -- before the current ones are multiplied.  For launches
+        // with at most one workgroup per compute unit, where no other workgroup's loads hide this one's latency.
+        Fetch a, b;
+        if (k_begin < k_end) {
+            fetch(a, k_begin);
+            for (int kc0 = k_begin;; kc0 += 2 * U) {
+                fetch(b, kc0 + U);
+                multiply(a, kc0);
+                if (kc0 + U >= k_end) break;
+                fetch(a, kc0 + 2 * U);
+                multiply(b, kc0 + U);
+                if (kc0 + 2 * U >= k_end) break;
+            }
+        }
+    } else {
+        for (int kc0 = k_begin; kc0 < k_end; kc0 += U) {
+            Fetch f;
+            fetch(f, kc0);
+            multiply(f, kc0);
         }
     }
 
@@ -634,7 +670,17 @@ hipError_t launch_stream_travelling(const SkinnyArgs& g, bool out_f32, hipStream
 template <int FMT, int MT>
 hipError_t launch_mt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
 {
-    const dim3 grid((unsigned)((g.N + 15) / 16)), block(kSkinnyWaves * 64);
+    const int n_rb = (g.N + 15) / 16;
+    const dim3 grid((unsigned)n_rb), block(kSkinnyWaves * 64);
+    // At most one workgroup per compute unit and several batches of K per wave: no other workgroup's loads hide this one's
+    // latency, so the instantiation that requests the next batch before it multiplies the current one (NVFP4, N = 4096,
+    // K = 14336 ...).  Same K split, same order of additions.
+    const int per = ((g.K >> 7) + kSkinnyWaves - 1) / kSkinnyWaves;
+    if (n_rb <= stream_cus() && per > (MT == 1 ? 4 : 2)) {
+        if (out_f32) hipLaunchKernelGGL((gemm_skinny_nt_kernel<FMT, 1, MT, true, true>), grid, block, 0, st, g);
+        else hipLaunchKernelGGL((gemm_skinny_nt_kernel<FMT, 1, MT, false, true>), grid, block, 0, st, g);
+        return hipGetLastError();
+    }
     if (out_f32) hipLaunchKernelGGL((gemm_skinny_kernel<FMT, MT, true>), grid, block, 0, st, g);
     else hipLaunchKernelGGL((gemm_skinny_kernel<FMT, MT, false>), grid, block, 0, st, g);
     return hipGetLastError();
@@ -650,6 +696,14 @@ bool try_two_row_blocks(const SkinnyArgs& g, bool out_f32, hipStream_t st, hipEr
     const int n_rb = (g.N + 15) / 16, wgs = (n_rb + 1) / 2;
     if (5 * wgs < 3 * stream_cus()) return false;
     const dim3 grid((unsigned)wgs), block(kSkinnyWaves * 64);
+    // at most one workgroup per compute unit and several batches of K per wave: the instantiation that prefetches
+    const int per = ((g.K >> 7) + kSkinnyWaves - 1) / kSkinnyWaves;
+    if (FMT == 1 && wgs <= stream_cus() && per > (MT == 1 ? 4 : 2)) {
+        if (out_f32) hipLaunchKernelGGL((gemm_skinny_nt_kernel<FMT, 2, MT, true, true>), grid, block, 0, st, g);
+        else hipLaunchKernelGGL((gemm_skinny_nt_kernel<FMT, 2, MT, false, true>), grid, block, 0, st, g);
+        *err = hipGetLastError();
+        return true;
+    }
     if (out_f32) hipLaunchKernelGGL((gemm_skinny_nt_kernel<FMT, 2, MT, true>), grid, block, 0, st, g);
     else hipLaunchKernelGGL((gemm_skinny_nt_kernel<FMT, 2, MT, false>), grid, block, 0, st, g);
     *err = hipGetLastError();

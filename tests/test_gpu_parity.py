@@ -418,12 +418,15 @@ def test_gemm_nvfp4_persistent_kernel_with_fp16_resident_activations(fp4, oracle
 
 @pytest.mark.parametrize("M,N,K,out_f32", [(1, 5000, 512, True), (16, 4944, 1152, False), (9, 5136, 128, False), (16, 8200, 640, True),
                                            (17, 5000, 512, False), (32, 4944, 1152, True), (40, 5136, 384, False), (64, 5000, 640, False),
-                                           (50, 8200, 128, True)])
+                                           (50, 8200, 128, True), (16, 5000, 8320, False), (40, 5136, 8320, False), (17, 6160, 9216, True),
+                                           (64, 400, 8448, False)])
 def test_gemm_nvfp4_few_tokens_two_row_blocks_per_workgroup(fp4, oracle, M, N, K, out_f32):
     """Up to 64 tokens on NVFP4 with at least 0.6 workgroups per compute unit go to the kernel whose workgroups own two
     16-column blocks of the output (one dequantized X fragment per two W fragments): odd block counts (the last workgroup
     re-reads the last block and stores it once), ragged N, K / 128 = 1, 3, 4, 5, 9 (waves without a K share, ragged tails of
-    the load batches), one to four 16-token blocks with ragged M (a token block past the end re-reads the last one)."""
+    the load batches), one to four 16-token blocks with ragged M (a token block past the end re-reads the last one).
+    K / 128 = 65, 66, 72 with at most one workgroup per compute unit: the instantiations that request the next batch of
+    fragments before they multiply the current one (two row-blocks per workgroup for N = 5000 ... 6160, one for N = 400)."""
     _gemm_case(fp4, oracle, NV, M, N, K, seed=4100 + N + K, out_f32=out_f32, layout_gemm=True)
 
 
