@@ -577,23 +577,27 @@ int stream_walkers()
     return cap;
 }
 
+// Workgroups of a persistent launch: one per compute unit, or, with several sets (parts > 1), as many walkers per set as
+// share the row-blocks evenly -- as many rounds as the resident workgroups need, then the fewest walkers (whole groups of
+// eight, all sets resident at once) that do it in that many rounds.
+unsigned stream_grid(int N, int parts)
+{
+    const int n_rb = (N + 15) / 16, cap = stream_walkers();
+    if (parts <= 1) return (unsigned)std::min(n_rb, cap);
+    const int per_part = std::max(cap / parts / 8 * 8, 8);
+    const int rounds = (n_rb + per_part - 1) / per_part;
+    const int walkers = std::min(per_part, ((n_rb + rounds - 1) / rounds + 7) / 8 * 8);
+    return (unsigned)(parts * walkers);
+}
+
 // MXFP4 with the activations resident in registers: MT 16-token blocks, a wave's share of K in NB batches of four fragments
 // (K <= 4096 NB).  parts > 1: that many sets of workgroups, each with its own MT token blocks; W passes through every
-// XCD's L2 once and is read from there once per set.  The walkers of a set share the row-blocks evenly (as many rounds as
-// the resident workgroups need, then the fewest walkers that do it in that many rounds).
+// XCD's L2 once and is read from there once per set.
 template <int MT, int NB>
 hipError_t launch_stream_resident(SkinnyArgs g, bool out_f32, int parts, hipStream_t st)
 {
-    const int n_rb = (g.N + 15) / 16, cap = stream_walkers();
-    unsigned blocks = (unsigned)std::min(n_rb, cap);
-    if (parts > 1) {
-        const int per_part = std::max(cap / parts / 8 * 8, 8);  // (whole groups of eight, all sets resident at once)
-        const int rounds = (n_rb + per_part - 1) / per_part;
-        const int walkers = std::min(per_part, ((n_rb + rounds - 1) / rounds + 7) / 8 * 8);
-        blocks = (unsigned)(parts * walkers);
-        g.parts = parts;
-    }
-    const dim3 grid(blocks), block(kSkinnyWaves * 64);
+    g.parts = parts;
+    const dim3 grid(stream_grid(g.N, parts)), block(kSkinnyWaves * 64);
     if (out_f32) hipLaunchKernelGGL((gemm_stream_kernel<0, true, 4, true, MT, NB>), grid, block, 0, st, g);
     else hipLaunchKernelGGL((gemm_stream_kernel<0, false, 4, true, MT, NB>), grid, block, 0, st, g);
     return hipGetLastError();
@@ -603,16 +607,8 @@ hipError_t launch_stream_resident(SkinnyArgs g, bool out_f32, int parts, hipStre
 template <int NB>
 hipError_t launch_stream_resident_nv(SkinnyArgs g, bool out_f32, int parts, hipStream_t st)
 {
-    const int n_rb = (g.N + 15) / 16, cap = stream_walkers();
-    unsigned blocks = (unsigned)std::min(n_rb, cap);
-    if (parts > 1) {
-        const int per_part = std::max(cap / parts / 8 * 8, 8);  // (whole groups of eight, all sets resident at once)
-        const int rounds = (n_rb + per_part - 1) / per_part;
-        const int walkers = std::min(per_part, ((n_rb + rounds - 1) / rounds + 7) / 8 * 8);
-        blocks = (unsigned)(parts * walkers);
-        g.parts = parts;
-    }
-    const dim3 grid(blocks), block(kSkinnyWaves * 64);
+    g.parts = parts;
+    const dim3 grid(stream_grid(g.N, parts)), block(kSkinnyWaves * 64);
     if (out_f32) hipLaunchKernelGGL((gemm_stream_kernel<1, true, 2, true, 1, NB>), grid, block, 0, st, g);
     else hipLaunchKernelGGL((gemm_stream_kernel<1, false, 2, true, 1, NB>), grid, block, 0, st, g);
     return hipGetLastError();
