@@ -310,7 +310,7 @@ fp4mr_status_t fp4_dequantize(const void* codes, const void* scales, const float
 /*
  * Process-wide switches for tuning sweeps and cross-checks (none is needed for normal use; not thread-safe: set them
  * before calls are issued concurrently).  Returns FP4MR_ERR_FMT for an unknown option or a value out of range.
- *   FP4MR_OPT_GEMM_VARIANT  0 (default): fp4_gemm picks the tile shape from M, N, K; 1..17 (MXFP4) / 1..3 (NVFP4): force
+ *   FP4MR_OPT_GEMM_VARIANT  0 (default): fp4_gemm picks the tile shape from M, N, K; 1..18 (MXFP4) / 1..3 (NVFP4): force
  *                           one tile configuration (fp4_gemm returns FP4MR_ERR_FMT if the value is not valid for its format)
  *   FP4MR_OPT_GEMM_GRID     0 (default): one persistent workgroup per compute unit; n > 0: at most n workgroups
  *   FP4MR_OPT_SW_CODEC      1: the quantizers encode E2M1 / E4M3 with integer arithmetic instead of the converting

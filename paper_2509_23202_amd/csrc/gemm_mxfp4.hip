@@ -606,8 +606,9 @@ int pick_variant_mx(int64_t M, int64_t N, int64_t K)
         if ((variant == 10 || variant == 11) && K >= 768 && K <= 1280) variant = tiles(128, 256) > 2.0 * cus ? 16 : 15;
         // 128x128 tiles that leave compute units without a tile: one workgroup per unit at most, bound by what a single
         // unit can pull in -- the eight-stage ring keeps twice the bytes in flight (N = 4096, M = 128: K = 4096 14.3 ->
-        // 12.5 us, K = 14336 43 -> 35 us)
-        if (variant == 2 && n2 <= cus) variant = 17;
+        // 12.5 us, K = 14336 43 -> 35 us), and eight waves of 32 x 64 (two per SIMD, one's LDS reads under the other's
+        // MFMAs) are another 3-6 % faster than four of 64 x 64 (variant 17) when the unit has nothing else to run
+        if (variant == 2 && n2 <= cus) variant = 18;
     }
     return variant;
 }
@@ -628,7 +629,7 @@ void plan_split_k_mx(int64_t M, int64_t N, int64_t K, int variant, int* splits, 
     *steps = 0;
     int bm, bn, per_cu;
     double fixed, step_alone, step_shared;  // step time with at most one workgroup per compute unit / with more
-    if (variant == 2 || variant == 17) { bm = 128; bn = 128; per_cu = 2; fixed = 8.0; step_alone = variant == 17 ? 0.25 : 0.30; step_shared = 0.40; }
+    if (variant == 2 || variant == 17 || variant == 18) { bm = 128; bn = 128; per_cu = 2; fixed = 8.0; step_alone = variant == 2 ? 0.30 : 0.25; step_shared = 0.40; }
     else if (variant == 5) { bm = 256; bn = 128; per_cu = 1; fixed = 9.0; step_alone = step_shared = 0.45; }
     else if (variant == 10) { bm = 256; bn = 256; per_cu = 1; fixed = 9.5; step_alone = step_shared = 0.74; }
     else return;
@@ -683,7 +684,7 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
     if (variant == 0) {
         variant = pick_variant_mx(M, N, K);
         if (partial && M > 64) plan_split_k_mx(M, N, K, variant, &splits, &split_steps);
-        if (variant == 17 && splits > 1) variant = 2;  // the parts run as four-stage workgroups, two per compute unit where needed
+        if ((variant == 17 || variant == 18) && splits > 1) variant = 2;  // the parts run as four-stage workgroups, two per compute unit where needed
     }
     float* const pp = static_cast<float*>(partial);
     switch (variant) {
@@ -704,6 +705,7 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
         case 15: return launch_variant<128, 256, 64, 128, 3, 3>(g, out_f32, st);
         case 16: return launch_variant<128, 256, 64, 128, 3, 3, true>(g, out_f32, st);
         case 17: return launch_variant<128, 128, 64, 64, 8>(g, out_f32, st);
+        case 18: return launch_variant<128, 128, 32, 64, 8>(g, out_f32, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -34,7 +34,7 @@ struct LdsAttrOnce {
 };
 
 // largest valid forced tile configuration per format (fp4_gemm rejects anything else before it launches)
-constexpr int kMaxGemmVariantMx = 17;
+constexpr int kMaxGemmVariantMx = 18;
 constexpr int kMaxGemmVariantNv = 3;
 
 // policy: group scales by 0 abs-max, 1 squared-error search, 2 rounded exponent with the 4/3 factor (MXFP4 only).

@@ -143,7 +143,7 @@ def test_argument_validation_happens_before_any_launch(lib):
     fl = lambda fn, M: fn(fake, M, 128, 32, fake, fake, 16, 0, fake, b.W_LAYOUT_GEMM, None)
     assert fl(L.fp4_fused_linear, 5) == 2 and fl(L.fp4_fused_linear, 0) == 2 and fl(L.fp4_w4a16_linear, 17) == 2
     # options: unknown option / value out of range; a forced tile configuration that the format does not have
-    assert L.fp4_set_option(99, 1) == 4 and L.fp4_set_option(b.OPT_GEMM_VARIANT, 18) == 4 and L.fp4_set_option(b.OPT_GEMM_GRID, -1) == 4
+    assert L.fp4_set_option(99, 1) == 4 and L.fp4_set_option(b.OPT_GEMM_VARIANT, 19) == 4 and L.fp4_set_option(b.OPT_GEMM_GRID, -1) == 4
     assert L.fp4_set_option(b.OPT_GEMM_VARIANT, 9) == 0
     try:
         assert L.fp4_gemm(fake, fake, fake, fake, fake, fake, 16, 16, 128, 1, fake, None, 0, b.A_LAYOUT_GEMM | b.W_LAYOUT_GEMM, None) == 4

@@ -233,7 +233,7 @@ def test_gemm_gemm_layout_operands_bf16_out(fp4, oracle, fmt):
     _gemm_case(fp4, oracle, fmt, 200, 520, 1024 + 384, seed=5, out_f32=False, layout_gemm=True)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18])
 def test_gemm_mxfp4_every_tile_variant(fp4, oracle, variant, knobs):
     knobs(variant=variant)
     _gemm_case(fp4, oracle, MX, 272, 528, 1280, seed=variant, out_f32=True, layout_gemm=True)
@@ -248,7 +248,7 @@ def test_gemm_nvfp4_every_tile_variant(fp4, oracle, variant, out_f32, knobs):
     _gemm_case(fp4, oracle, NV, 272, 528, 1280, seed=30 + variant, out_f32=out_f32, layout_gemm=True)
 
 
-@pytest.mark.parametrize("variant", [2, 5, 10, 13, 15, 17])
+@pytest.mark.parametrize("variant", [2, 5, 10, 13, 15, 17, 18])
 def test_gemm_mxfp4_tile_variants_bf16_output_through_the_staged_epilogue(fp4, oracle, variant, knobs):
     """bf16 output goes through the LDS transpose of the epilogue, whose chunk swizzle depends on the wave tile's width
     (64, 96 and 128 columns here); ragged last tile row and column."""
@@ -256,13 +256,15 @@ def test_gemm_mxfp4_tile_variants_bf16_output_through_the_staged_epilogue(fp4, o
     _gemm_case(fp4, oracle, MX, 272, 528, 1280, seed=80 + variant, out_f32=False, layout_gemm=True)
 
 
+@pytest.mark.parametrize("variant", [17, 18])
 @pytest.mark.parametrize("K", [128, 512, 896, 1024, 1152, 2048, 2176, 4224])
-def test_gemm_mxfp4_eight_stage_ring_with_two_scale_buffers(fp4, oracle, K, knobs):
+def test_gemm_mxfp4_eight_stage_ring_with_two_scale_buffers(fp4, oracle, K, variant, knobs):
     """The 128x128 tile with an eight-stage operand ring (for launches with fewer tiles than compute units): the scale
     batches alternate between two buffers and are requested eight steps ahead.  K / 128 = 1, 4, 7 (shorter than the ring),
-    8, 9 (one batch and the first step of the second), 16, 17, 33; scales that differ per row-block and K-step."""
+    8, 9 (one batch and the first step of the second), 16, 17, 33; scales that differ per row-block and K-step.  Variant 17:
+    four waves of 64 x 64; variant 18: eight waves of 32 x 64."""
     import torch
-    knobs(variant=17)
+    knobs(variant=variant)
     M, N = 272, 400
     rng = np.random.default_rng(8000 + K)
 
@@ -320,7 +322,7 @@ def test_gemm_mxfp4_persistent_variants_across_ragged_tiles(fp4, oracle, grid, o
     _gemm_case(fp4, oracle, MX, 528, 784, 3072, seed=90 + grid + variant, out_f32=out_f32, layout_gemm=True)
 
 
-@pytest.mark.parametrize("variant", [10, 11, 13, 3, 15, 17])
+@pytest.mark.parametrize("variant", [10, 11, 13, 3, 15, 17, 18])
 @pytest.mark.parametrize("K", [640, 1152, 2176])
 def test_gemm_mxfp4_scales_that_differ_per_row_block_and_k_block(fp4, oracle, variant, K, knobs):
     """The tile kernels fetch scale bytes in batches (eight K-steps of two row-blocks per copy with four stages, four
