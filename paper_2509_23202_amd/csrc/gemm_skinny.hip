@@ -790,20 +790,22 @@ hipError_t launch_fmt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
 
 }  // namespace
 
-// 65 to 128 tokens: MXFP4 with K <= 8192 (two sets of workgroups with three or four token blocks resident each), on layers
-// narrow enough that the tile kernels' cost per launch (12-14 us at K = 4096, 15-25 at K = 8192, whatever the token count)
-// exceeds what the persistent kernel spends per row-block.  Measured, cold weights, M = 96, tiles -> two sets:
-// K = 4096: N = 4096 12.6 -> 6.4 us, 8192 12.9 -> 8.6, 14336 14.3 -> 12.2, 28672 17.9 -> 20.4 (not taken);
+// More than 64 tokens: MXFP4 with K <= 8192 as several sets of persistent workgroups (up to four resident token blocks
+// each), on layers narrow enough that the tile kernels' cost per launch (12-14 us at K = 4096, 15-25 at K = 8192, whatever
+// the token count) exceeds what the persistent kernel spends per row-block and set.  Measured, cold weights, tiles -> sets:
+// M = 96 (two sets), K = 4096: N = 4096 12.6 -> 6.4 us, 8192 12.9 -> 8.6, 14336 14.3 -> 12.2, 28672 17.9 -> 20.4 (not taken);
 // K = 8192: N = 4096 16.0 -> 9.3, 8192 17.8 -> 12.6, 14336 25.1 -> 18.9; K = 2048: N = 4096 8.1 -> 6.0, 8192 9.4 -> 8.7,
-// 14336 10.1 -> 12.6 (not taken); K = 1024: level or slower (not taken).  K = 14336 (four sets of two blocks): level with
-// the split-K tiles at N = 4096, slower beyond (not taken).
+// 14336 10.1 -> 12.6 (not taken); K = 1024: level or slower (not taken).  M = 256 (four sets), K = 4096: N = 4096 13.6 -> 9.3,
+// 6144 14.2 -> 11.2, 8192 14.5 -> 13.3, 14336 16.8 -> 20.9 (not taken); K = 8192: N = 4096 23.8 -> 12.7, 8192 24.5 -> 19.7.
+// M = 512 (eight sets): N = 4096 13.8 -> 12.8 (K = 4096), 24.0 -> 18.5 (K = 8192); N = 6144 15.1 -> 17.4 (not taken).
+// So: sets x N up to 32768.  K = 14336 (sets of two blocks): level with the split-K tiles at N = 4096, slower beyond (not taken).
 bool gemm_skinny_takes(int64_t M, int64_t N, int64_t K, int fmt)
 {
     if (M <= 64) return true;
-    if (fmt != 0 || M > 128) return false;
+    if (fmt != 0 || M > 512) return false;
     const int64_t per = ((K >> 7) + kSkinnyWaves - 1) / kSkinnyWaves;  // fragments of K per wave
-    if (per >= 4 && per <= 8) return N <= 16384;
-    if (per == 2 || per == 3) return N <= 8192;
+    if (per >= 4 && per <= 8) return (M + 63) / 64 * N <= 32768;
+    if (per == 2 || per == 3) return M <= 128 && N <= 8192;
     return false;
 }
 

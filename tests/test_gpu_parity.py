@@ -392,12 +392,14 @@ def test_gemm_mxfp4_persistent_kernel_with_several_batches_of_resident_activatio
 @pytest.mark.parametrize("grid,M,N,K,out_f32", [(0, 65, 400, 4096, False), (0, 128, 1000, 4096, True), (16, 96, 2056, 2048, False),
                                                 (16, 100, 1160, 1152, True), (1, 81, 520, 3072, False), (0, 113, 6144, 4096, False),
                                                 (16, 128, 4104, 1536, True), (0, 72, 12288, 3200, False), (0, 96, 272, 8192, False),
-                                                (16, 128, 400, 6144, True), (0, 70, 144, 5120, False), (16, 81, 528, 8192, True)])
-def test_gemm_mxfp4_65_to_128_tokens_on_two_sets_of_persistent_workgroups(fp4, oracle, grid, M, N, K, out_f32, knobs):
-    """65 to 128 tokens on a narrow MXFP4 layer with 1024 < K <= 8192: the persistent weight-streaming kernel runs as two sets
-    of workgroups, each with three or four 16-token blocks of X in registers (five to eight blocks in all: the second set's
-    last block can lie past the end of M and is then neither loaded nor stored); a grid cap makes 8 walkers per set take many
-    row-blocks each; ragged N, waves without a K share (K / 128 = 9, 12), fp32 and bf16 output."""
+                                                (16, 128, 400, 6144, True), (0, 70, 144, 5120, False), (16, 81, 528, 8192, True),
+                                                (0, 200, 1000, 4096, False), (24, 256, 528, 8192, True), (0, 300, 272, 5120, False),
+                                                (32, 512, 400, 4096, False), (0, 130, 8192, 4096, False)])
+def test_gemm_mxfp4_65_to_512_tokens_on_sets_of_persistent_workgroups(fp4, oracle, grid, M, N, K, out_f32, knobs):
+    """65 to 512 tokens on a narrow MXFP4 layer with 1024 < K <= 8192 (sets x N <= 32768): the persistent weight-streaming
+    kernel runs as two to eight sets of workgroups, each with three or four 16-token blocks of X in registers (the last
+    set's last blocks can lie past the end of M and are then neither loaded nor stored); a grid cap makes 8 walkers per
+    set take many row-blocks each; ragged N, waves without a K share (K / 128 = 9, 12), fp32 and bf16 output."""
     knobs(grid=grid)
     _gemm_case(fp4, oracle, MX, M, N, K, seed=500 + M + K, out_f32=out_f32, layout_gemm=True)
 
@@ -440,11 +442,11 @@ def test_gemm_mxfp4_three_and_four_token_blocks_two_row_blocks_per_workgroup(fp4
     _gemm_case(fp4, oracle, MX, M, N, K, seed=5100 + N + K, out_f32=out_f32, layout_gemm=True)
 
 
-@pytest.mark.parametrize("M,N,K,out_f32", [(129, 400, 8192, True), (128, 1024, 14336, False), (200, 1000, 12416, False), (300, 272, 16512, True),
+@pytest.mark.parametrize("M,N,K,out_f32", [(129, 400, 8320, True), (128, 1024, 14336, False), (200, 1000, 12416, False), (300, 272, 16512, True),
                                            (512, 520, 9088, False)])
 def test_gemm_mxfp4_split_k(fp4, oracle, M, N, K, out_f32):
     """More than 64 tokens against a narrow layer with a long K: with the optional workspace the tiles' K ranges are
-    shared by several workgroups (fp32 partials, added in split order).  Ragged M and N, K / 128 = 64, 71, 97, 112, 129
+    shared by several workgroups (fp32 partials, added in split order).  Ragged M and N, K / 128 = 65, 71, 97, 112, 129
     (a last split of one K-step; splits that end inside a scale batch of eight steps), both output types; the same call
     with the minimum workspace runs unsplit and must meet the same bound."""
     import torch
