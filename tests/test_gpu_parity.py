@@ -608,3 +608,29 @@ def test_results_are_deterministic(fp4):
                                  flags=fp4.A_LAYOUT_GEMM | fp4.W_LAYOUT_GEMM).clone())
     torch.cuda.synchronize()
     assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
+
+
+def _few_token_cases():
+    rng = np.random.default_rng(20251128)
+    out = []
+    for i in range(48):
+        fmt = MX if i % 3 else NV
+        M = int(rng.choice([1, 5, 16, 17, 31, 32, 33, 47, 48, 50, 64, 65, 80, 97, 128, 129, 200, 256, 300, 400, 512]))
+        N = int(rng.choice([16, 40, 136, 264, 520, 1032, 2056, 4104]))
+        K = 128 * int(rng.choice([1, 2, 3, 4, 7, 8, 9, 16, 24, 31, 32, 33, 40, 56, 63, 64, 65, 72, 96, 112, 128, 130]))
+        if M * N * K > 6.0e9:
+            N = 264
+        out.append((i, fmt, M, N, K, bool(rng.integers(0, 2)), int(rng.choice([0, 0, 1, 5, 24]))))
+    return out
+
+
+@pytest.mark.parametrize("case", _few_token_cases(), ids=lambda c: f"{c[0]}-fmt{c[1]}-M{c[2]}-N{c[3]}-K{c[4]}-{'f32' if c[5] else 'bf16'}-grid{c[6]}")
+def test_gemm_few_token_dispatch_on_seeded_random_shapes(fp4, oracle, case, knobs):
+    """Seeded random shapes across the few-token dispatch: one to 512 tokens, K / 128 from 1 to 130, both formats, ragged N,
+    with and without a cap on the persistent grid -- one-shot kernels (with and without the prefetching register set), the
+    persistent kernels with one to four resident token blocks and one to four batches per row-block, two to eight sets of
+    them, the NVFP4 kernels with fp16-resident activations, the kernel whose X fragments travel with W, and the tile kernels
+    where none of them takes the shape."""
+    i, fmt, M, N, K, out_f32, grid = case
+    knobs(grid=grid)
+    _gemm_case(fp4, oracle, fmt, M, N, K, seed=6000 + i, out_f32=out_f32, layout_gemm=True)
