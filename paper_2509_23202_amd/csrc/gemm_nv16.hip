@@ -326,7 +326,7 @@ __global__ __launch_bounds__(256) void nv16_reduce_kernel(const float* __restric
 
 // Split-K plan (see the MXFP4 kernels' plan: few tiles and a long K leave the launch bound by the latency of a handful of
 // compute units' loads; here M = 128, N = 8192, K = 28672 is 32 tiles and 411 us, slower than a bf16 GEMM).  128 x 256
-// tiles, two workgroups per compute unit, at least 32 K-steps of 64 per part, at most eight parts.  A K-step takes about
+// (or 128 x 128) tiles, two workgroups per compute unit, at least 8 K-steps of 64 per part, at most sixteen parts.  A K-step takes about
 // 0.93 us in a workgroup that has its compute unit to itself and half as much again when two share one; a 128 x 128 tile's
 // takes 0.58 us.  The number of parts minimises the estimate (microseconds)
 //     10 + K-steps per part x step time + (split only) 3 + splits x M x N x 8 bytes of partials at 8 TB/s
@@ -338,30 +338,38 @@ bool nv16_narrow_tiles(int64_t tiles_w, int cus)
     return 4 * tiles_w <= 5 * (int64_t)cus;
 }
 
-void plan_split_k_nv16(int64_t M, int64_t N, int64_t K, int cus, int* splits, int* steps)
+void plan_split_k_nv16(int64_t M, int64_t N, int64_t K, int cus, int* splits, int* steps, bool* narrow)
 {
     *splits = 1;
     *steps = 0;
+    *narrow = false;
     const int64_t tiles_m = (M + 127) / 128;
-    const int64_t tiles = tiles_m * ((N + 255) / 256);
+    const int64_t tiles_w = tiles_m * ((N + 255) / 256), tiles_n = tiles_m * ((N + 127) / 128);
     const int64_t slots = 2 * (int64_t)cus;
     const int kh = (int)(K >> 6);
-    const int64_t s_max = std::min<int64_t>(std::min<int64_t>(slots / tiles, kh / 32), 8);
     // every part is as slow as the slowest compute unit's, and that one runs two workgroups as soon as there are more
     // workgroups than compute units
     auto shared = [&](int64_t wgs) { return wgs <= cus ? 1.0 : 1.47; };
-    double unsplit = 10.0 + kh * 0.93 * shared(tiles);
-    if (nv16_narrow_tiles(tiles, cus)) unsplit = 10.0 + kh * 0.58 * shared(tiles_m * ((N + 127) / 128));
+    double unsplit = 10.0 + kh * 0.93 * shared(tiles_w);
+    if (nv16_narrow_tiles(tiles_w, cus)) unsplit = 10.0 + kh * 0.58 * shared(tiles_n);
     double best = 0.9 * unsplit;
-    for (int64_t s = 2; s <= s_max; ++s) {
-        const int st = (int)(((kh + s - 1) / s + 7) / 8 * 8);
-        const int64_t n = (kh + st - 1) / st;
-        if (n < 2) continue;
-        const double t = 10.0 + st * 0.93 * shared(n * tiles) + 3.0 + (double)n * (double)M * (double)N * 8.0 / 8.0e6;
-        if (t < best) {
-            best = t;
-            *splits = (int)n;
-            *steps = st;
+    // parts of at least eight K-steps (whole multiples of eight), up to sixteen of them, of wide or of narrow tiles, on at most
+    // two workgroups per compute unit
+    for (int nar = 0; nar < 2; ++nar) {
+        const int64_t tiles = nar ? tiles_n : tiles_w;
+        const double step = nar ? 0.58 : 0.93;
+        const int64_t s_max = std::min<int64_t>(std::min<int64_t>(slots / tiles, kh / 8), 16);
+        for (int64_t s = 2; s <= s_max; ++s) {
+            const int st = (int)(((kh + s - 1) / s + 7) / 8 * 8);
+            const int64_t n = (kh + st - 1) / st;
+            if (n < 2) continue;
+            const double t = 10.0 + st * step * shared(n * tiles) + 3.0 + (double)n * (double)M * (double)N * 8.0 / 8.0e6;
+            if (t < best) {
+                best = t;
+                *splits = (int)n;
+                *steps = st;
+                *narrow = nar != 0;
+            }
         }
     }
 }
@@ -373,10 +381,9 @@ int device_cus()
     return cus;
 }
 
-template <int BN, int STAGES = 3>
-hipError_t launch_tiles(const Nv16Args& g, bool out_f32, hipStream_t st, int splits = 1)
+template <int BN, int STAGES>
+hipError_t launch_tiles_ring(const Nv16Args& g, bool out_f32, hipStream_t st, int splits)
 {
-    if (g.n_cols <= 0) return hipSuccess;
     constexpr size_t lds = STAGES * (size_t)(8 * 2048 + (BN / 16) * 512 + 4 * 256);
     const int tiles_n = (g.n_cols + BN - 1) / BN;
     if (splits > 1) {
@@ -402,6 +409,16 @@ hipError_t launch_tiles(const Nv16Args& g, bool out_f32, hipStream_t st, int spl
     return hipGetLastError();
 }
 
+// Three stages (75 KB of LDS with 256 columns, two workgroups per compute unit).  (A ring of six or seven stages for launches
+// with at most one workgroup per compute unit measured the same: N = K = 4096, M = 80: 43.1 against 43.5 us -- a K-step of
+// such a launch is bound by the tile's own 64 MFMAs per wave, not by its loads.)
+template <int BN>
+hipError_t launch_tiles(const Nv16Args& g, bool out_f32, hipStream_t st, int splits = 1)
+{
+    if (g.n_cols <= 0) return hipSuccess;
+    return launch_tiles_ring<BN, 3>(g, out_f32, st, splits);
+}
+
 }  // namespace
 
 size_t nv16_workspace_bytes(int64_t M, int64_t K)
@@ -413,7 +430,8 @@ size_t nv16_workspace_bytes(int64_t M, int64_t K)
 size_t nv16_split_k_bytes(int64_t M, int64_t N, int64_t K)
 {
     int splits, steps;
-    plan_split_k_nv16(M, N, K, device_cus(), &splits, &steps);
+    bool narrow;
+    plan_split_k_nv16(M, N, K, device_cus(), &splits, &steps, &narrow);
     return splits > 1 ? (size_t)splits * (size_t)M * (size_t)N * 4 : 0;
 }
 
@@ -447,13 +465,14 @@ hipError_t launch_gemm_nv16(const void* a_codes, const void* a_scales, const flo
     if (partial) {
         // few tiles, long K: every tile's K range shared by several workgroups, partial results added by a second kernel
         int splits, steps;
-        plan_split_k_nv16(M, N, K, cus, &splits, &steps);
+        bool narrow;
+        plan_split_k_nv16(M, N, K, cus, &splits, &steps, &narrow);
         if (splits > 1) {
             g.out = partial;
             g.n_first = 0;
             g.n_cols = (int)N;
             g.split_steps = steps;
-            if ((e = launch_tiles<256>(g, true, st, splits)) != hipSuccess) return e;
+            if ((e = narrow ? launch_tiles<128>(g, true, st, splits) : launch_tiles<256>(g, true, st, splits)) != hipSuccess) return e;
             const int64_t mn = M * N;
             const unsigned rblocks = (unsigned)std::min<int64_t>((mn + 255) / 256, 256 * 16);
             if (out_f32) hipLaunchKernelGGL(nv16_reduce_kernel<true>, dim3(rblocks), dim3(256), 0, st, static_cast<const float*>(partial), splits, mn, a_ts, w_ts, out);

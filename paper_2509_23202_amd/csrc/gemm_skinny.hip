@@ -761,7 +761,8 @@ hipError_t launch_fmt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
                 // and one batch (N <= 4096, K <= 4096) is launch-bound and 0.1-0.4 us faster with the one-shot kernel's
                 // occupancy.  (NVFP4 stays with the one-shot kernels: its in-register dequantization needs the registers of
                 // the second batch buffer -- 68 us against 54 on N = 57344, K = 8192.)
-                const bool one_shot = per <= 4 && (g.N + 15) / 16 <= stream_walkers();
+                // ... and so is any layer with K <= 1024 (one fragment per wave: N = 8192, K = 1024, 3.7 us against 4.6)
+                const bool one_shot = per <= 1 || (per <= 4 && (g.N + 15) / 16 <= stream_walkers());
                 hipError_t e = hipSuccess;
                 if (!one_shot) {
                     if (try_stream_resident<1>(g, out_f32, per, 1, st, &e)) return e;
@@ -781,7 +782,8 @@ hipError_t launch_fmt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
                 // 17 to 64 tokens on a narrow layer: one set of such workgroups per token block (every set dequantizes W again,
                 // which the two-row-block kernels below share between token blocks: N = 10240, K = 8192, M = 32 / 64: 18.7 /
                 // 29.5 -> 15.5 / 24.5 us; N = 16384: level; N = 57344: 59 / 100 -> 67 / 113, not taken)
-                if (per <= 8 && g.N <= 12288) return launch_stream_nv(g, out_f32, per, mt, st);
+                // (not with a single fragment per wave: N = 8192, K = 1024, M = 64: 5.4 us against 7.2)
+                if (per >= 2 && per <= 8 && g.N <= 12288) return launch_stream_nv(g, out_f32, per, mt, st);
             }
             return mt == 2 ? launch_tokens<FMT, 2>(g, out_f32, st) : mt == 3 ? launch_tokens<FMT, 3>(g, out_f32, st) : launch_tokens<FMT, 4>(g, out_f32, st);
         default: return hipErrorInvalidValue;
@@ -798,13 +800,16 @@ hipError_t launch_fmt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
 // 14336 10.1 -> 12.6 (not taken); K = 1024: level or slower (not taken).  M = 256 (four sets), K = 4096: N = 4096 13.6 -> 9.3,
 // 6144 14.2 -> 11.2, 8192 14.5 -> 13.3, 14336 16.8 -> 20.9 (not taken); K = 8192: N = 4096 23.8 -> 12.7, 8192 24.5 -> 19.7.
 // M = 512 (eight sets): N = 4096 13.8 -> 12.8 (K = 4096), 24.0 -> 18.5 (K = 8192); N = 6144 15.1 -> 17.4 (not taken).
-// So: sets x N up to 32768.  K = 14336 (sets of two blocks): level with the split-K tiles at N = 4096, slower beyond (not taken).
+// So: sets x N up to 28672 (N = 16384, K = 6144, M = 128: 17.9 -> 21.3, not taken).  K = 14336 (sets of two blocks): level with the split-K tiles at N = 4096, slower beyond (not taken).
 bool gemm_skinny_takes(int64_t M, int64_t N, int64_t K, int fmt)
 {
     if (M <= 64) return true;
     if (fmt != 0 || M > 512) return false;
     const int64_t per = ((K >> 7) + kSkinnyWaves - 1) / kSkinnyWaves;  // fragments of K per wave
-    if (per >= 4 && per <= 8) return (M + 63) / 64 * N <= 32768;
+    // (up to four sets at K <= 4096: N = 4096, M = 384 / 512 measured 11.5 / 11.7 us on tiles against 12.3 / 13.5; with a longer
+    // K the tiles cost more and up to eight sets pay: N = 4096, K = 8192, M = 512: 24.0 -> 18.5)
+    const int64_t sets = (M + 63) / 64;
+    if (per >= 4 && per <= 8) return sets * N <= 28672 && (per > 4 || sets <= 4);
     if (per == 2 || per == 3) return M <= 128 && N <= 8192;
     return false;
 }
