@@ -194,9 +194,10 @@ fp4mr_status_t fp4_quantize_weights(const void* w, int64_t N, int64_t K, int had
  *   out          [M,N] row-major
  *   flags        layouts, FP4MR_OUT_F32, and for MXFP4 FP4MR_A_SCALE43 / FP4MR_W_SCALE43 (FP4MR_ERR_FMT with NVFP4)
  *   workspace    fp4_workspace_bytes(FP4MR_OP_GEMM, M, N, K, fmt, flags) bytes: room for operands handed over in
- *                row-major layout (they are re-tiled first), and, for NVFP4 with M > 64, 2 bytes per element of the
- *                activation operand (its exact fp16 values code * s_G are written once, so that the product kernel
- *                converts only W).  May be NULL when that size is 0 (MXFP4 with both operands in GEMM layout).
+ *                row-major layout (they are re-tiled first), and, for NVFP4 with M > 64 on the shapes that the
+ *                many-token kernel takes, 2 bytes per element of the activation operand (its exact fp16 values
+ *                code * s_G are written once, so that the product kernel converts only W).  May be NULL when that size
+ *                is 0 (MXFP4 with both operands in GEMM layout).
  *                Optional: with at least fp4_workspace_bytes(FP4MR_OP_GEMM_SPLIT_K, ...) bytes (the same plus room for
  *                fp32 partial results; equal to the former where the shape has nothing to gain) a product with few
  *                output tiles and a long K -- 65 to a few hundred tokens against a narrow layer -- is split along K

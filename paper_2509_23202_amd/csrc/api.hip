@@ -339,7 +339,7 @@ size_t fp4_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, fp4mr_fmt_t 
         if (!(flags & FP4MR_A_LAYOUT_GEMM)) n += repack_bytes(M, K, fmt);
         if (!(flags & FP4MR_W_LAYOUT_GEMM)) n += repack_bytes(N, K, fmt);
         // NVFP4 with more than 64 tokens: the activations are dequantized once to fp16 (2 bytes per element)
-        if (fmt == FP4MR_NVFP4 && M > 64) n += align256(nv16_workspace_bytes(M, K));
+        if (fmt == FP4MR_NVFP4 && M > 64 && !gemm_skinny_takes(M, N, K, (int)fmt)) n += align256(nv16_workspace_bytes(M, K));
         // what fp4_gemm needs, plus -- optional -- the fp32 partials of a split-K run where the shape has one
         if (op == FP4MR_OP_GEMM_SPLIT_K && M > 64 && !gemm_skinny_takes(M, N, K, (int)fmt)) {
             const size_t extra = fmt == FP4MR_MXFP4 ? gemm_mx_split_k_bytes(M, N, K) : nv16_split_k_bytes(M, N, K);
