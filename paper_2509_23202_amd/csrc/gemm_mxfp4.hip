@@ -608,7 +608,9 @@ int pick_variant_mx(int64_t M, int64_t N, int64_t K)
         // unit can pull in -- the eight-stage ring keeps twice the bytes in flight (N = 4096, M = 128: K = 4096 14.3 ->
         // 12.5 us, K = 14336 43 -> 35 us), and eight waves of 32 x 64 (two per SIMD, one's LDS reads under the other's
         // MFMAs) are another 3-6 % faster than four of 64 x 64 (variant 17) when the unit has nothing else to run
-        if (variant == 2 && n2 <= cus) variant = 18;
+        // (up to three quarters of the compute units busy; with more, four waves measured level or faster: N = 28672, M = 96,
+        // 224 tiles: 17.4 us against 20.3)
+        if (variant == 2 && n2 <= cus) variant = 4 * n2 <= 3 * cus ? 18 : 17;
     }
     return variant;
 }
