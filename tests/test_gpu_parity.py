@@ -409,15 +409,15 @@ def test_gemm_mxfp4_65_to_512_tokens_on_sets_of_persistent_workgroups(fp4, oracl
                                            (3, 200, 2176, False), (16, 336, 4224, False), (12, 528, 8192, True), (16, 144, 8320, False),
                                            (16, 4112, 2048, False), (20, 1040, 1152, False), (40, 528, 8192, True), (64, 400, 4224, False),
                                            (33, 4112, 512, True), (100, 528, 4096, False), (128, 400, 1152, True), (200, 272, 2048, False),
-                                           (256, 144, 8192, False), (65, 1040, 512, True)])
+                                           (256, 144, 8192, False), (65, 1040, 512, True), (400, 272, 2048, False), (512, 144, 1152, True)])
 def test_gemm_nvfp4_persistent_kernel_with_fp16_resident_activations(fp4, oracle, grid, M, N, K, out_f32, knobs):
     """Up to 16 tokens on NVFP4 with K <= 8192: one workgroup per compute unit walks the row-blocks of W, its waves' shares
     of the activations dequantized once to fp16 and kept in registers, W in batches of two fragments with two batches in
     flight.  K / 128 = 1, 3, 8, 9, 17, 33, 64: one to four batches per row-block, shares that end inside a batch, waves
     without a share; K = 8320 is one step past the limit (the one-shot kernels); a grid of 1 or 3 workgroups makes each
     walk many row-blocks; ragged N, fp32 and bf16 output.  17 to 64 tokens on a narrow layer (N <= 12288): one set of such
-    workgroups per 16-token block (two to four sets, the last block ragged); 65 to 256 tokens on a small layer: five to
-    sixteen sets."""
+    workgroups per 16-token block (two to four sets, the last block ragged); 65 to 512 tokens on a small layer: five to
+    thirty-two sets."""
     knobs(grid=grid)
     _gemm_case(fp4, oracle, NV, M, N, K, seed=900 + grid + K, out_f32=out_f32, layout_gemm=True)
 
@@ -473,7 +473,7 @@ def test_gemm_mxfp4_split_k(fp4, oracle, M, N, K, out_f32):
 
 
 @pytest.mark.parametrize("M,N,K,out_f32", [(65, 400, 8320, True), (128, 1024, 14336, False), (200, 1000, 10368, False), (300, 528, 16512, True),
-                                           (280, 1040, 4096, False), (300, 520, 2048, True)])
+                                           (520, 1040, 4096, False), (600, 520, 2048, True)])
 def test_gemm_nvfp4_split_k(fp4, oracle, M, N, K, out_f32):
     """The NVFP4 many-token kernel with its K range shared by several workgroups (optional workspace): ragged M and N,
     K / 64 = 32, 64, 130, 162, 224, 258 (a last split of two K-steps of 64, i.e. one fragment; ragged last splits; short K in
