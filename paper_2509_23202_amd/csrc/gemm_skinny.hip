@@ -788,7 +788,7 @@ hipError_t launch_fmt(const SkinnyArgs& g, bool out_f32, hipStream_t st)
             return mt == 2 ? launch_tokens<FMT, 2>(g, out_f32, st) : mt == 3 ? launch_tokens<FMT, 3>(g, out_f32, st) : launch_tokens<FMT, 4>(g, out_f32, st);
         default:
             if constexpr (FMT == 1) {
-                if (mt <= 32 && per >= 2 && per <= 8) return launch_stream_nv(g, out_f32, per, mt, st);
+                if (mt <= 32 && per <= 8) return launch_stream_nv(g, out_f32, per, mt, st);
             }
             return hipErrorInvalidValue;
     }
@@ -815,7 +815,14 @@ bool gemm_skinny_takes(int64_t M, int64_t N, int64_t K, int fmt)
     // 20.7 / 26.1 / 25.3 -> 10.3 / 12.5 / 21.6 us; N = K = 2048: 13.8 / 15.4 / 18.8 -> 4.8 / 5.7 / 8.5; N = 12288, K = 4096,
     // M = 80 / 128: 28.4 / 32.3 -> 21.2 / 30.3; N = 10240, K = 8192, M = 96 / 128: 38.2 / 41.6 -> 36.8 / 44.7 (128: not taken).
     // (257 to 512 tokens -- up to 32 sets -- on the smallest layers only: N = K = 2048, M = 512: 25 -> 15 us)
-    if (fmt == 1) return M <= 512 && per >= 2 && per <= 8 && N <= 12288 && (M + 15) / 16 * N * K <= (int64_t)1 << (M <= 256 ? 29 : 28);
+    if (fmt == 1) {
+        if (per > 8 || N > 12288) return false;
+        const int64_t work = (M + 15) / 16 * N * K;
+        // (one fragment per wave, K <= 1024: a set's row-block is mostly its barrier and reduction -- N = 8192, K = 1024:
+        // M = 80 / 128: 16 -> 9.0 / 11.9 us, M = 192: 17 -> 19.9, not taken)
+        if (per == 1) return M <= 256 && work <= (int64_t)1 << 26;
+        return M <= 512 && work <= (int64_t)1 << (M <= 256 ? 29 : 28);
+    }
     if (fmt != 0 || M > 512) return false;
     // (up to four sets at K <= 4096: N = 4096, M = 384 / 512 measured 11.5 / 11.7 us on tiles against 12.3 / 13.5; with a longer
     // K the tiles cost more and up to eight sets pay: N = 4096, K = 8192, M = 512: 24.0 -> 18.5)
