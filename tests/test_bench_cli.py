@@ -38,3 +38,13 @@ def test_summarize_db_prints_the_group_by_tables(tmp_path):
     assert r.returncode == 0, r.stderr
     line = [l for l in r.stdout.splitlines() if l.startswith("k_a")][0].split()
     assert line[1:4] == ["FETCH_SIZE", "1024", "2"] and float(line[4]) == 20.0
+
+
+def test_sweep_tool_parses_its_arguments_without_a_gpu():
+    """`python -m paper_2509_23202_amd.sweep --help` loads the binding (the built library) and prints its usage: nothing
+    touches the GPU before the arguments are read."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, "-m", "paper_2509_23202_amd.sweep", "--help"], capture_output=True, text=True, timeout=120,
+                       cwd=str(__import__("pathlib").Path(__file__).resolve().parents[1]))
+    assert r.returncode == 0 and "--tokens" in r.stdout and "bf16" in r.stdout
