@@ -614,9 +614,10 @@ def test_results_are_deterministic(fp4):
 
 
 def _few_token_cases():
-    rng = np.random.default_rng(20251128)
+    # (FP4MR_FUZZ_SEED / FP4MR_FUZZ_CASES: other seeds and more cases for a longer run by hand)
+    rng = np.random.default_rng(int(os.environ.get("FP4MR_FUZZ_SEED", "20251128")))
     out = []
-    for i in range(48):
+    for i in range(int(os.environ.get("FP4MR_FUZZ_CASES", "48"))):
         fmt = MX if i % 3 else NV
         M = int(rng.choice([1, 5, 16, 17, 31, 32, 33, 47, 48, 50, 64, 65, 80, 97, 128, 129, 200, 256, 300, 400, 512]))
         N = int(rng.choice([16, 40, 136, 264, 520, 1032, 2056, 4104]))
