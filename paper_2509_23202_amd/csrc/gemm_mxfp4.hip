@@ -600,7 +600,12 @@ int pick_variant_mx(int64_t M, int64_t N, int64_t K)
         if (t13 < best * 0.97) { variant = 13; best = t13; }
         // more 256x256 tiles than compute units: persistent workgroups, which prefetch the next tile's first stages
         // and let the output stores drain under its first K-steps (1.5-6% on such shapes, never slower)
-        if (variant == 10 && tiles(256, 256) > cus) variant = 11;
+        // -- where the tiles fill whole rounds or many of them; a ragged few rounds (N = 28672, M = 1024 / 2048: 1.75 / 3.5
+        // rounds) measured 5-6 % faster with one workgroup per tile, which the hardware hands to whichever unit is free
+        if (variant == 10 && tiles(256, 256) > cus) {
+            const int64_t t = (int64_t)tiles(256, 256);
+            if (t % cus == 0 || t >= 5 * (int64_t)cus) variant = 11;
+        }
         // K around 1024: a tile is 8 K-steps, about as long as its own start-up and stores.  128x256 tiles with two
         // workgroups per compute unit overlap one workgroup's epilogue with the other's main loop: 10-13 % faster
         // there, level at K = 1536-2048, slower beyond (three stages, one and a half times the operand traffic) and
