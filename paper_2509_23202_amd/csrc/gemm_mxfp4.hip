@@ -480,19 +480,6 @@ void gemm_mx_kernel(GemmArgs g)
     }
 }
 
-// compute units of the current device (the persistent variants launch one workgroup per unit)
-int compute_units()
-{
-    static int cached[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
-    }
-    return cached[dev];
-}
 
 // out[i] = alpha * (partial[0][i] + partial[1][i] + ...), the splits added in their order (deterministic), as bf16 or fp32
 template <bool OUT_F32>
@@ -717,6 +704,20 @@ hipError_t launch_gemm_mxfp4(const void* a_codes, const void* a_scales, const vo
         case 18: return launch_variant<128, 128, 32, 64, 8>(g, out_f32, st);
         default: return hipErrorInvalidValue;
     }
+}
+
+// compute units of the current device (asked of the runtime once per device)
+int compute_units()
+{
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
 }
 
 }  // namespace fp4mr

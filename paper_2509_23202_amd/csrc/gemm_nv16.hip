@@ -376,9 +376,7 @@ void plan_split_k_nv16(int64_t M, int64_t N, int64_t K, int cus, int* splits, in
 
 int device_cus()
 {
-    int cus = 256, dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-    return cus;
+    return compute_units();
 }
 
 template <int BN, int STAGES>

@@ -561,9 +561,7 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_stream_kernel(SkinnyAr
 // compute units of the current device
 int stream_cus()
 {
-    int cus = 256, dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-    return cus;
+    return compute_units();
 }
 
 // Grid of the persistent kernels: one workgroup per compute unit, also where the registers would let two or three be

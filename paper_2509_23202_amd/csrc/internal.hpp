@@ -33,6 +33,9 @@ struct LdsAttrOnce {
     }
 };
 
+// compute units of the current device (cached per device)
+int compute_units();
+
 // largest valid forced tile configuration per format (fp4_gemm rejects anything else before it launches)
 constexpr int kMaxGemmVariantMx = 18;
 constexpr int kMaxGemmVariantNv = 3;
