@@ -74,6 +74,12 @@ def test_sizes(lib):
         assert extra > 0 and extra % (128 * 4096 * 4) <= 255 and 2 <= extra // (128 * 4096 * 4) <= 16
         assert b.workspace_bytes(b.OP_GEMM_SPLIT_K, 4096, 4096, 4096, fmt, lay) == b.workspace_bytes(b.OP_GEMM, 4096, 4096, 4096, fmt, lay)
         assert b.workspace_bytes(b.OP_GEMM_SPLIT_K, 16, 4096, 14336, fmt, lay) == b.workspace_bytes(b.OP_GEMM, 16, 4096, 14336, fmt, lay)
+    # shapes that the few-token kernels take beyond 64 tokens need neither the split-K room nor (NVFP4) the fp16 copy of X
+    for M, N, K in ((96, 4096, 4096), (256, 4096, 8192), (512, 2048, 4096)):
+        assert b.workspace_bytes(b.OP_GEMM_SPLIT_K, M, N, K, b.MXFP4, lay) == 0
+    for M, N, K in ((96, 4096, 4096), (256, 2048, 2048), (128, 8192, 1024)):
+        assert b.workspace_bytes(b.OP_GEMM_SPLIT_K, M, N, K, b.NVFP4, lay) == 0
+    assert b.workspace_bytes(b.OP_GEMM, 128, 16384, 4096, b.NVFP4, lay) >= 128 * 4096 * 2      # the many-token kernel's fp16 X
 
 
 def test_argument_validation_happens_before_any_launch(lib):
